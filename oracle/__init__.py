@@ -1,0 +1,130 @@
+"""CPU float64 oracle for fused_linear_epilogue -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this package.  It imports nothing from the GPU package and shares no
+code with it.  The arithmetic lives in ``fle_oracle.c`` (plain C, float64);
+this module only compiles it with gcc, loads it with ctypes and marshals
+numpy arrays.
+
+The operator is the unfused "gold" composition of the paper's evaluator
+(Appendix A, Correctness): matmul, then each listed op with PyTorch-eager
+semantics, evaluated in float64 on exactly the input values the GPU receives.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fle_oracle.c")
+_LIB = os.path.join(_HERE, "libfle_oracle.so")
+
+# op kinds, in the numbering of fle_oracle.c
+BIAS, SCALE, RELU, GELU_ERF, GELU_TANH, RESIDUAL, LAYERNORM, SOFTMAX, LOGSUMEXP = range(9)
+_KINDS = {
+    "bias": BIAS, "scale": SCALE, "relu": RELU, "gelu_erf": GELU_ERF, "gelu_tanh": GELU_TANH,
+    "residual": RESIDUAL, "layernorm": LAYERNORM, "softmax": SOFTMAX, "logsumexp": LOGSUMEXP,
+}
+
+
+class _Op(ctypes.Structure):
+    _fields_ = [
+        ("kind", ctypes.c_int32),
+        ("alpha", ctypes.c_double),
+        ("p0", ctypes.c_void_p),
+        ("p1", ctypes.c_void_p),
+        ("ld", ctypes.c_int64),
+    ]
+
+
+def build(force: bool = False) -> str:
+    """Compile fle_oracle.c into libfle_oracle.so (baseline x86-64, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-std=gnu11", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.fle_oracle_run.restype = ctypes.c_int
+        lib.fle_oracle_run.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+            ctypes.POINTER(_Op), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
+        lib.fle_oracle_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Threads the oracle's row loop uses by default."""
+    return int(_load().fle_oracle_threads())
+
+
+def _f64(a):
+    if a is None:
+        return None
+    a = np.asarray(a)
+    if a.dtype != np.float64:
+        raise TypeError("the oracle takes float64 arrays only (upcast the rounded inputs exactly)")
+    return np.ascontiguousarray(a)
+
+
+def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
+    """float64 gold result of ``epilogue(x @ w.T)``.
+
+    x [M,K], w [N,K], b [N] or None: float64 numpy arrays (already holding the
+    fp32- or bf16-rounded values the GPU gets; the upcast is exact).
+    epilogue: ordered list of tuples
+        ("bias",) ("scale", alpha) ("relu",) ("gelu_erf",) ("gelu_tanh",)
+        ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps)
+        ("softmax",) ("logsumexp",)       -- logsumexp only as the last entry.
+    alpha and eps cross the GPU boundary as fp32, so they are rounded to fp32
+    here too (Appendix A compares like with like).
+    Returns [M,N] float64, or [M] when the list ends in logsumexp.
+    """
+    x, w, b = _f64(x), _f64(w), _f64(b)
+    if x.ndim != 2 or w.ndim != 2 or x.shape[1] != w.shape[1]:
+        raise ValueError("x must be [M,K] and w [N,K]")
+    M, K = x.shape
+    N = w.shape[0]
+    keep = [x, w, b]
+    ops = (_Op * max(1, len(epilogue)))()
+    for i, e in enumerate(epilogue):
+        kind = _KINDS[e[0]]
+        ops[i].kind = kind
+        if kind == SCALE:
+            ops[i].alpha = float(np.float32(e[1]))
+        elif kind == RESIDUAL:
+            r = _f64(e[1])
+            if r.shape != (M, N):
+                raise ValueError("residual must be [M,N]")
+            keep.append(r)
+            ops[i].p0 = r.ctypes.data
+            ops[i].ld = N
+        elif kind == LAYERNORM:
+            g, be = _f64(e[1]), _f64(e[2])
+            keep += [g, be]
+            ops[i].p0 = g.ctypes.data if g is not None else None
+            ops[i].p1 = be.ctypes.data if be is not None else None
+            ops[i].alpha = float(np.float32(e[3]))
+    lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
+    out = np.empty((M,) if lse else (M, N), dtype=np.float64)
+    rc = _load().fle_oracle_run(
+        M, N, K, x.ctypes.data, K, w.ctypes.data, K, b.ctypes.data if b is not None else None,
+        ops, len(epilogue), out.ctypes.data, N, int(n_threads))
+    if rc != 0:
+        raise ValueError("fle_oracle_run rejected the arguments (code %d)" % rc)
+    return out

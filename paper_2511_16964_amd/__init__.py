@@ -1,0 +1,15 @@
+"""fle: fused linear + epilogue for AMD MI355X (gfx950).
+
+``fused_linear_epilogue(x, w, b, epilogue)`` runs entirely in the hand-written
+HIP kernels of ``libfle.so`` (C ABI declared in ``include/fle.h``); this package
+is argument marshalling only.  Nothing here falls back to a CPU or PyTorch
+implementation: if the library is missing, calls raise.
+"""
+__all__ = ["fused_linear_epilogue", "inputs"]
+
+
+def __getattr__(name):
+    if name in ("fused_linear_epilogue", "binding"):
+        from . import binding
+        return binding if name == "binding" else binding.fused_linear_epilogue
+    raise AttributeError(name)

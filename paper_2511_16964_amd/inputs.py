@@ -1,0 +1,180 @@
+"""Seeded synthetic inputs for the benchmark configurations.
+
+This module holds no arithmetic of the operator itself: it only draws random
+tensors of the stated shapes and distributions and rounds them to the storage
+dtype.  Both the GPU tests and the CPU oracle consume exactly these values
+(the oracle after an exact upcast to float64).
+
+Generator: ``numpy.random.default_rng(seed)``; draw order per problem is
+x, W, b, r, gamma, beta (for the two-call MLP block: x, W1, b1, W2, b2, gamma,
+beta).  N(0,1) is ``standard_normal``; U(+-a) is ``uniform(-a, a)``;
+N(mu, s) has standard deviation s.  bf16 storage is round-to-nearest-even of
+the fp32 draw.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+
+@dataclass
+class Problem:
+    """One call of fused_linear_epilogue: CPU tensors in the storage dtype."""
+    name: str
+    dtype: torch.dtype
+    x: torch.Tensor                 # [M, K]
+    w: torch.Tensor                 # [N, K]
+    b: torch.Tensor | None          # [N]
+    epilogue: list = field(default_factory=list)  # tuples; tensors inside are CPU tensors
+
+    @property
+    def M(self): return self.x.shape[0]
+
+    @property
+    def N(self): return self.w.shape[0]
+
+    @property
+    def K(self): return self.x.shape[1]
+
+    @property
+    def flops(self): return 2 * self.M * self.N * self.K
+
+
+def _normal(rng, shape, mean=0.0, std=1.0):
+    a = rng.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    if mean != 0.0:
+        a += np.float32(mean)
+    return a
+
+
+def _uniform(rng, shape, a):
+    return rng.uniform(-a, a, size=shape).astype(np.float32)
+
+
+def _store(a: np.ndarray, dtype: torch.dtype) -> torch.Tensor:
+    return torch.from_numpy(a).to(dtype)
+
+
+# name -> (dtype, M, N, K)
+SHAPES = {
+    "c1": (torch.float32, 64, 256, 256),
+    "c2": (torch.bfloat16, 4096, 4096, 4096),
+    "c3": (torch.bfloat16, 8192, 4096, 4096),
+    "c4": (torch.bfloat16, 32, 32768, 8192),
+    "c5a": (torch.bfloat16, 16384, 16384, 4096),
+    "c5b": (torch.bfloat16, 16384, 4096, 16384),
+}
+
+
+def make(name: str, seed: int = 0, M: int | None = None, N: int | None = None,
+         K: int | None = None) -> Problem:
+    """Build configuration ``name`` ("c1".."c4"); M, N, K override the shape
+    (same distributions, for reduced-size parity cases)."""
+    dtype, M0, N0, K0 = SHAPES[name]
+    M, N, K = M or M0, N or N0, K or K0
+    rng = np.random.default_rng(seed)
+    if name == "c1":    # Linear + bias + GELU-erf, fp32
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 16); b = _uniform(rng, (N,), 1 / 16)
+        return Problem(name, dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype),
+                       [("bias",), ("gelu_erf",)])
+    if name == "c2":    # Linear + bias + ReLU + scale(0.5) + residual, bf16
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
+        r = _normal(rng, (M, N))
+        return Problem(name, dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype),
+                       [("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, dtype))])
+    if name == "c3":    # Linear + bias + GELU-tanh + LayerNorm, bf16
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
+        g = _normal(rng, (N,), 1.0, 0.02); be = _normal(rng, (N,), 0.0, 0.02)
+        return Problem(name, dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype),
+                       [("bias",), ("gelu_tanh",),
+                        ("layernorm", _store(g, dtype), _store(be, dtype), 1e-5)])
+    if name == "c4":    # skinny Linear + row softmax, bf16, no bias
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / math.sqrt(K))
+        return Problem(name, dtype, _store(x, dtype), _store(w, dtype), None, [("softmax",)])
+    raise KeyError(name)
+
+
+@dataclass
+class MlpBlock:
+    """Transformer MLP block as two calls: h = gelu_erf(x W1^T + b1);
+    out = layernorm(h W2^T + b2 + x)."""
+    x: torch.Tensor      # [T, D]
+    w1: torch.Tensor     # [F, D]
+    b1: torch.Tensor     # [F]
+    w2: torch.Tensor     # [D, F]
+    b2: torch.Tensor     # [D]
+    gamma: torch.Tensor  # [D]
+    beta: torch.Tensor   # [D]
+    eps: float = 1e-5
+
+    def call1(self, x=None) -> Problem:
+        x = self.x if x is None else x
+        return Problem("c5a", x.dtype, x, self.w1, self.b1, [("bias",), ("gelu_erf",)])
+
+    def call2(self, h, x=None) -> Problem:
+        x = self.x if x is None else x
+        return Problem("c5b", h.dtype, h, self.w2, self.b2,
+                       [("bias",), ("residual", x), ("layernorm", self.gamma, self.beta, self.eps)])
+
+
+def make_mlp(seed: int = 0, T: int = 16384, D: int = 4096, F: int = 16384,
+             dtype: torch.dtype = torch.bfloat16) -> MlpBlock:
+    rng = np.random.default_rng(seed)
+    x = _normal(rng, (T, D))
+    w1 = _uniform(rng, (F, D), 1 / math.sqrt(D)); b1 = _uniform(rng, (F,), 1 / math.sqrt(D))
+    w2 = _uniform(rng, (D, F), 1 / math.sqrt(F)); b2 = _uniform(rng, (D,), 1 / math.sqrt(F))
+    g = _normal(rng, (D,), 1.0, 0.02); be = _normal(rng, (D,), 0.0, 0.02)
+    s = lambda a: _store(a, dtype)
+    return MlpBlock(s(x), s(w1), s(b1), s(w2), s(b2), s(g), s(be))
+
+
+def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds: list[str],
+                   integer: bool = False) -> Problem:
+    """A problem with an arbitrary epilogue list, for parity sweeps.  With
+    ``integer`` every tensor holds small integers (exactly representable in
+    bf16), which makes the elementwise chain bias/relu/scale(0.5)/residual exact."""
+    rng = np.random.default_rng(seed)
+    if integer:
+        ri = lambda shape, a: rng.integers(-a, a + 1, size=shape).astype(np.float32)
+        x, w, b = ri((M, K), 2), ri((N, K), 2), ri((N,), 8)
+    else:
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / math.sqrt(max(K, 1)))
+        b = _uniform(rng, (N,), 0.5)
+    ep = []
+    for kd in kinds:
+        if kd == "scale":
+            ep.append(("scale", 0.5 if integer else float(np.float32(rng.uniform(0.25, 2.0)))))
+        elif kd == "residual":
+            r = ri((M, N), 8) if integer else _normal(rng, (M, N))
+            ep.append(("residual", _store(r, dtype)))
+        elif kd == "layernorm":
+            g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
+            ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+        else:
+            ep.append((kd,))
+    return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), ep)
+
+
+def to_f64(t):
+    """Exact upcast of a stored tensor to a float64 numpy array (None passes through)."""
+    return None if t is None else t.detach().cpu().to(torch.float64).numpy()
+
+
+def epilogue_f64(epilogue, rows=None):
+    """The epilogue list with its tensors upcast exactly to float64 numpy arrays.
+    ``rows`` selects rows of [M,N] operands (every op is row-local)."""
+    out = []
+    for e in epilogue:
+        if e[0] == "residual":
+            r = e[1] if rows is None else e[1][rows]
+            out.append(("residual", to_f64(r)))
+        elif e[0] == "layernorm":
+            out.append(("layernorm", to_f64(e[1]), to_f64(e[2]), e[3]))
+        else:
+            out.append(tuple(e))
+    return out

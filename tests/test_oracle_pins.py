@@ -1,0 +1,272 @@
+"""Pins for the CPU oracle: it is checked against what the mathematics fixes
+(closed forms, tabulated values, invariants, brute force with exact rational
+arithmetic) and against independent library routines (numpy, scipy, torch
+CPU float64) -- never against itself and never against the GPU path.
+
+The gold side of the paper's comparison is the original eager composition
+(Appendix A, Correctness); the last group of tests pins exactly that.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+import torch
+import torch.nn.functional as F
+
+import oracle
+
+RNG = np.random.default_rng(1234)
+
+
+def run(x, w, b=None, ep=()):
+    return oracle.fused_linear_epilogue(np.asarray(x, np.float64), np.asarray(w, np.float64),
+                                        None if b is None else np.asarray(b, np.float64), list(ep))
+
+
+def elementwise(kind, v, *args):
+    """Apply one op to a vector through the oracle: x = v as a column, W = [[1]]... i.e. K = 1."""
+    v = np.asarray(v, np.float64).reshape(-1, 1)
+    return run(v, np.ones((1, 1)), None, [(kind, *args)]).reshape(-1)
+
+
+def rowop(ep, z):
+    """Apply a chain to given rows z[M,N] through the oracle: W = identity."""
+    z = np.asarray(z, np.float64)
+    return run(z, np.eye(z.shape[1]), None, ep)
+
+
+# ---------------------------------------------------------------- contraction
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (2, 3, 5), (3, 2, 8), (5, 17, 3), (8, 5, 17), (17, 8, 2)])
+def test_contraction_brute_force_exact_rationals(M, N, K):
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((N, K))
+    got = run(x, w)
+    for m in range(M):
+        for n in range(N):
+            exact = sum(Fraction(float(x[m, k])) * Fraction(float(w[n, k])) for k in range(K))
+            scale = sum(abs(float(x[m, k]) * float(w[n, k])) for k in range(K))
+            assert abs(Fraction(float(got[m, n])) - exact) <= Fraction(1e-15) * Fraction(scale) * K
+
+
+def test_contraction_is_x_times_w_transposed_not_w():
+    # a non-square, asymmetric case with a known answer: catches a transposed operand
+    x = np.array([[1.0, 2.0, 3.0]])
+    w = np.array([[1.0, 0.0, 0.0], [0.0, 1.0, 0.0], [1.0, 1.0, 1.0], [0.0, 0.0, -2.0]])
+    assert run(x, w).tolist() == [[1.0, 2.0, 6.0, -6.0]]
+
+
+def test_contraction_special_operands():
+    x = RNG.standard_normal((6, 9))
+    assert np.array_equal(run(x, np.eye(9)), x)                      # W = I
+    w = RNG.standard_normal((4, 9))
+    e = np.zeros((1, 9)); e[0, 5] = 1.0
+    assert np.array_equal(run(e, w)[0], w[:, 5])                     # one-hot row selects a column of W^T
+    assert np.array_equal(run(np.ones((3, 40)), np.ones((2, 40))), np.full((3, 2), 40.0))
+
+
+def test_contraction_small_integers_exact():
+    x = RNG.integers(-2, 3, (13, 31)).astype(np.float64)
+    w = RNG.integers(-2, 3, (7, 31)).astype(np.float64)
+    want = (x.astype(np.int64) @ w.astype(np.int64).T).astype(np.float64)
+    assert np.array_equal(run(x, w), want)
+
+
+def test_contraction_vs_numpy_and_torch():
+    x = RNG.standard_normal((33, 257)); w = RNG.standard_normal((65, 257))
+    got = run(x, w)
+    np.testing.assert_allclose(got, x @ w.T, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(got, F.linear(torch.from_numpy(x), torch.from_numpy(w)).numpy(), rtol=0, atol=1e-11)
+
+
+def test_empty_and_degenerate_shapes():
+    assert run(np.zeros((0, 4)), np.ones((3, 4))).shape == (0, 3)
+    assert np.array_equal(run(np.zeros((2, 0)), np.zeros((3, 0)), np.array([1.0, 2.0, 3.0]), [("bias",)]),
+                          np.array([[1.0, 2.0, 3.0]] * 2))           # K = 0: empty sum is 0
+
+
+# ---------------------------------------------------------------- elementwise ops
+def test_bias_scale_relu_residual_definitions():
+    x = np.array([[1.0, -2.0], [0.5, 4.0]]); w = np.eye(2)
+    assert run(x, w, [10.0, 20.0], [("bias",)]).tolist() == [[11.0, 18.0], [10.5, 24.0]]
+    assert run(x, w, None, [("scale", -3.0)]).tolist() == [[-3.0, 6.0], [-1.5, -12.0]]
+    assert run(x, w, None, [("relu",)]).tolist() == [[1.0, 0.0], [0.5, 4.0]]
+    r = np.array([[100.0, 200.0], [300.0, 400.0]])
+    assert run(x, w, None, [("residual", r)]).tolist() == [[101.0, 198.0], [300.5, 404.0]]
+    out = elementwise("relu", [np.nan, -np.inf, np.inf, -0.0])
+    assert np.isnan(out[0]) and out[1] == 0.0 and out[2] == np.inf and out[3] == 0.0
+
+
+# Standard normal CDF table values (Phi), 16 digits: GELU-erf is x * Phi(x).
+PHI = {0.5: 0.6914624612740131, 1.0: 0.8413447460685429, 2.0: 0.9772498680518208, 3.0: 0.9986501019683699}
+
+
+def test_gelu_erf_fixed_points():
+    xs = np.array([0.0, 0.5, -0.5, 1.0, -1.0, 2.0, 3.0, -3.0])
+    want = np.array([0.0, 0.5 * PHI[0.5], -0.5 * (1 - PHI[0.5]), PHI[1.0], -(1 - PHI[1.0]),
+                     2 * PHI[2.0], 3 * PHI[3.0], -3 * (1 - PHI[3.0])])
+    np.testing.assert_allclose(elementwise("gelu_erf", xs), want, rtol=0, atol=2e-15)
+
+
+def test_gelu_erf_vs_scipy_cdf_and_oddness():
+    xs = np.linspace(-8, 8, 4001)
+    g = elementwise("gelu_erf", xs)
+    np.testing.assert_allclose(g, xs * scipy.stats.norm.cdf(xs), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(g - elementwise("gelu_erf", -xs), xs, rtol=0, atol=1e-14)   # g(x) - g(-x) = x
+
+
+def test_gelu_tanh_fixed_points_and_library():
+    # values of 0.5 x (1 + tanh(sqrt(2/pi)(x + 0.044715 x^3))) worked out with mpmath-grade arithmetic
+    xs = np.array([0.5, 1.0, -1.0, 2.0, 3.0])
+    want = np.array([0.34571400982514394, 0.8411919906082768, -0.15880800939172324,
+                     1.954597694087775, 2.996362607918227])
+    np.testing.assert_allclose(elementwise("gelu_tanh", xs), want, rtol=0, atol=2e-15)
+    grid = np.linspace(-6, 6, 2401)
+    g = elementwise("gelu_tanh", grid)
+    np.testing.assert_allclose(g, F.gelu(torch.from_numpy(grid), approximate="tanh").numpy(), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(g - elementwise("gelu_tanh", -grid), grid, rtol=0, atol=1e-14)
+    # the two GELU variants differ, by at most 4.73e-4 (near |x| = 2.7): a swapped variant is detectable
+    d = np.abs(g - elementwise("gelu_erf", grid))
+    assert 4.6e-4 < d.max() < 4.8e-4 and 2.5 < abs(grid[d.argmax()]) < 2.9
+
+
+# ---------------------------------------------------------------- row ops
+def test_layernorm_closed_forms():
+    z = RNG.standard_normal((5, 64)) * 3 + 7
+    eps = 1e-5
+    y = rowop([("layernorm", None, None, eps)], z)
+    np.testing.assert_allclose(y.mean(axis=1), 0, atol=1e-13)
+    var = z.var(axis=1)                                # biased
+    epsf = float(np.float32(eps))
+    np.testing.assert_allclose(y.var(axis=1), var / (var + epsf), rtol=1e-12)   # not 1: eps sits inside the sqrt
+    # constant row -> beta; N = 1 -> beta
+    beta = RNG.standard_normal(64); gamma = RNG.standard_normal(64)
+    yc = rowop([("layernorm", gamma, beta, eps)], np.full((2, 64), 3.25))
+    np.testing.assert_allclose(yc, np.tile(beta, (2, 1)), atol=1e-15)
+    assert rowop([("layernorm", np.array([2.0]), np.array([-7.0]), eps)], [[5.0]]).tolist() == [[-7.0]]
+    # affine invariance at eps = 0, and the affine step comes after normalisation
+    y0 = rowop([("layernorm", None, None, 0.0)], z)
+    np.testing.assert_allclose(rowop([("layernorm", None, None, 0.0)], 2.5 * z - 4), y0, atol=1e-12)
+    np.testing.assert_allclose(rowop([("layernorm", gamma, beta, 0.0)], z), y0 * gamma + beta, atol=1e-13)
+
+
+def test_layernorm_hand_example_and_torch():
+    # row (1,2,3,4): mean 2.5, biased variance 1.25
+    y = rowop([("layernorm", None, None, 0.0)], [[1.0, 2.0, 3.0, 4.0]])
+    np.testing.assert_allclose(y[0], np.array([-1.5, -0.5, 0.5, 1.5]) / math.sqrt(1.25), atol=1e-15)
+    z = RNG.standard_normal((7, 96)); g = RNG.standard_normal(96); be = RNG.standard_normal(96)
+    eps = float(np.float32(1e-5))
+    want = F.layer_norm(torch.from_numpy(z), (96,), torch.from_numpy(g), torch.from_numpy(be), eps).numpy()
+    np.testing.assert_allclose(rowop([("layernorm", g, be, 1e-5)], z), want, atol=1e-12)
+
+
+def test_softmax_closed_forms():
+    z = RNG.standard_normal((6, 50)) * 4
+    s = rowop([("softmax",)], z)
+    np.testing.assert_allclose(s.sum(axis=1), 1, atol=1e-14)
+    assert (s > 0).all() and (s <= 1).all()
+    np.testing.assert_allclose(rowop([("softmax",)], z + 123.0), s, atol=1e-13)       # shift invariance
+    np.testing.assert_allclose(s, scipy.special.softmax(z, axis=1), atol=1e-15)
+    two = rowop([("softmax",)], [[0.3, -1.1]])
+    assert abs(two[0, 0] - 1 / (1 + math.exp(-1.4))) < 1e-15                          # N = 2 is the logistic
+    np.testing.assert_allclose(rowop([("softmax",)], np.full((1, 8), -3.0)), 0.125, atol=1e-16)
+    big = rowop([("softmax",)], [[1000.0, 1000.0, -1000.0]])                          # no overflow
+    np.testing.assert_allclose(big, [[0.5, 0.5, 0.0]], atol=1e-300)
+
+
+def test_logsumexp_closed_forms():
+    z = RNG.standard_normal((6, 50)) * 4
+    l = rowop([("logsumexp",)], z)
+    assert l.shape == (6,)
+    np.testing.assert_allclose(l, np.log(np.exp(z).sum(axis=1)), atol=1e-13)          # the definition, |z| small
+    np.testing.assert_allclose(rowop([("logsumexp",)], z + 77.0), l + 77.0, atol=1e-12)
+    np.testing.assert_allclose(rowop([("logsumexp",)], np.full((1, 32), 2.0)), 2.0 + math.log(32), atol=1e-15)
+    np.testing.assert_allclose(l, scipy.special.logsumexp(z, axis=1), atol=1e-13)
+    np.testing.assert_allclose(np.exp(z - l[:, None]), rowop([("softmax",)], z), atol=1e-14)  # ties both ops
+    assert rowop([("logsumexp",)], [[1000.0, 1000.0]])[0] == pytest.approx(1000.0 + math.log(2), abs=1e-12)
+
+
+# ---------------------------------------------------------------- composition and order
+def test_order_matters():
+    x = np.array([[2.0, -3.0]]); w = np.eye(2)
+    assert run(x, w, None, [("scale", -1.0), ("relu",)]).tolist() == [[0.0, 3.0]]
+    assert run(x, w, None, [("relu",), ("scale", -1.0)]).tolist() == [[-2.0, 0.0]]
+    b = [-2.5, 4.0]
+    assert run(x, w, b, [("bias",), ("relu",)]).tolist() == [[0.0, 1.0]]
+    assert run(x, w, b, [("relu",), ("bias",)]).tolist() == [[-0.5, 4.0]]
+    # a row op in the middle of the list, then an elementwise op
+    got = run(x, w, None, [("softmax",), ("scale", 2.0)])
+    np.testing.assert_allclose(got, 2 * scipy.special.softmax(x, axis=1), atol=1e-15)
+
+
+def torch_eager(x, w, b, ep):
+    """The unfused PyTorch-eager composition in float64 on the CPU."""
+    t = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    z = F.linear(t(x), t(w))
+    for e in ep:
+        k = e[0]
+        if k == "bias": z = z + t(b)
+        elif k == "scale": z = z * float(np.float32(e[1]))
+        elif k == "relu": z = F.relu(z)
+        elif k == "gelu_erf": z = F.gelu(z)
+        elif k == "gelu_tanh": z = F.gelu(z, approximate="tanh")
+        elif k == "residual": z = z + t(e[1])
+        elif k == "layernorm":
+            z = F.layer_norm(z, (z.shape[1],), None if e[1] is None else t(e[1]),
+                             None if e[2] is None else t(e[2]), float(np.float32(e[3])))
+        elif k == "softmax": z = torch.softmax(z, -1)
+        elif k == "logsumexp": z = torch.logsumexp(z, -1)
+    return z.numpy()
+
+
+CHAINS = [
+    ["bias", "gelu_erf"],
+    ["bias", "relu", "scale", "residual"],
+    ["bias", "gelu_tanh", "layernorm"],
+    ["softmax"],
+    ["bias", "residual", "layernorm"],
+    ["scale", "logsumexp"],
+    ["bias", "layernorm", "gelu_erf", "residual"],
+    ["relu", "softmax", "scale"],
+    ["layernorm", "softmax"],
+    ["bias", "gelu_tanh", "scale", "relu", "residual", "logsumexp"],
+]
+
+
+@pytest.mark.parametrize("kinds", CHAINS)
+def test_composition_matches_torch_cpu_float64(kinds):
+    M, N, K = 9, 40, 23
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((N, K)) / 4; b = RNG.standard_normal(N)
+    ep = []
+    for k in kinds:
+        if k == "scale": ep.append(("scale", 0.7))
+        elif k == "residual": ep.append(("residual", RNG.standard_normal((M, N))))
+        elif k == "layernorm": ep.append(("layernorm", RNG.standard_normal(N), RNG.standard_normal(N), 1e-5))
+        else: ep.append((k,))
+    np.testing.assert_allclose(run(x, w, b, ep), torch_eager(x, w, b, ep), rtol=1e-11, atol=1e-11)
+
+
+def test_structural_invariants():
+    M, N, K = 12, 24, 16
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((N, K)) / 4; b = RNG.standard_normal(N)
+    r = RNG.standard_normal((M, N)); g = RNG.standard_normal(N); be = RNG.standard_normal(N)
+    ep = lambda r_, g_, be_: [("bias",), ("gelu_tanh",), ("residual", r_), ("layernorm", g_, be_, 1e-5)]
+    base = run(x, w, b, ep(r, g, be))
+    pm = RNG.permutation(M); pn = RNG.permutation(N)
+    np.testing.assert_allclose(run(x[pm], w, b, ep(r[pm], g, be)), base[pm], atol=1e-13)          # rows
+    np.testing.assert_allclose(run(x, w[pn], b[pn], ep(r[:, pn], g[pn], be[pn])), base[:, pn], atol=1e-12)  # columns
+    xz = np.hstack([x, np.zeros((M, 32))]); wz = np.hstack([w, RNG.standard_normal((N, 32))])
+    np.testing.assert_allclose(run(xz, wz, b, ep(r, g, be)), base, atol=1e-13)                    # zero K padding
+    top = run(x[:5], w, b, ep(r[:5], g, be)); bot = run(x[5:], w, b, ep(r[5:], g, be))
+    assert np.array_equal(np.vstack([top, bot]), base)                                            # split M
+
+
+def test_rejects_bad_arguments():
+    x = np.zeros((2, 3)); w = np.zeros((4, 3))
+    with pytest.raises(ValueError):
+        run(x, w, None, [("bias",)])                      # bias op without b
+    with pytest.raises(ValueError):
+        run(x, w, None, [("logsumexp",), ("relu",)])      # logsumexp must be last
+    with pytest.raises(TypeError):
+        oracle.fused_linear_epilogue(x.astype(np.float32), w, None, [])
