@@ -1,0 +1,145 @@
+/*
+ * fle.h -- C ABI of libfle: fused linear + epilogue for AMD MI355X (gfx950).
+ *
+ *     out = epilogue( x[M,K] * W[N,K]^T )
+ *
+ * The operator is the fusion pattern that arXiv 2511.16964 reports as a
+ * recurring source of speedup over PyTorch eager (Section 5.3: fusing a
+ * matmul with the elementwise and reduction ops that follow it into one
+ * kernel removes the intermediate tensors' memory traffic and the extra
+ * launches).  The epilogue is an ordered list drawn from
+ * {bias, scale, ReLU, GELU-erf, GELU-tanh, residual add, LayerNorm over N,
+ * row softmax, row logsumexp}; each op has PyTorch-eager semantics, and the
+ * result equals the unfused composition up to floating-point rounding (the
+ * comparison the paper's evaluator makes, Appendix A).
+ *
+ * Conventions
+ *   - All tensors are row-major.  W is [N,K] (the nn.Linear weight layout).
+ *   - One dtype per problem for x, W, b, residual, gamma, beta and out:
+ *     FLE_F32 or FLE_BF16.  Products are accumulated in fp32, the whole
+ *     epilogue runs in fp32, and the result is rounded once
+ *     (round-to-nearest-even) to the output dtype.
+ *   - Pointers inside fle_problem and fle_op are DEVICE pointers unless
+ *     stated otherwise; the structs themselves and the ops array live on the
+ *     HOST and are only read during the call.
+ *   - The caller owns every buffer; the library allocates, frees and keeps
+ *     nothing on the device.  Buffers must stay valid until the work
+ *     enqueued on `stream` has completed.
+ *   - No function throws or aborts; errors come back as fle_status and a
+ *     thread-local message (fle_last_error).  On any error nothing has been
+ *     enqueued.
+ *   - Results are bitwise reproducible for a given problem: no floating-point
+ *     atomics, fixed reduction order.
+ */
+#ifndef FLE_H
+#define FLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FLE_OK = 0,
+    FLE_ERR_NULL = 1,        /* a required pointer is NULL                               */
+    FLE_ERR_SHAPE = 2,       /* negative size, leading dimension too small, size overflow */
+    FLE_ERR_ALIGN = 3,       /* a pointer or leading dimension breaks the alignment rule */
+    FLE_ERR_OP = 4,          /* unknown op kind, bad op argument, too many ops           */
+    FLE_ERR_UNSUPPORTED = 5, /* valid math, but outside the accepted epilogue grammar    */
+    FLE_ERR_WORKSPACE = 6,   /* workspace missing or smaller than fle_workspace_size     */
+    FLE_ERR_HIP = 7          /* the HIP runtime refused a launch                         */
+} fle_status;
+
+typedef enum { FLE_F32 = 0, FLE_BF16 = 1 } fle_dtype;
+
+typedef enum {
+    FLE_BIAS = 0,      /* v += b[n]                                  (needs problem.b)     */
+    FLE_SCALE = 1,     /* v *= alpha                                                        */
+    FLE_RELU = 2,      /* v = max(v, 0); NaN stays NaN                                      */
+    FLE_GELU_ERF = 3,  /* v = 0.5 v (1 + erf(v / sqrt 2))            (approximate='none')  */
+    FLE_GELU_TANH = 4, /* v = 0.5 v (1 + tanh(sqrt(2/pi) (v + 0.044715 v^3)))               */
+    FLE_RESIDUAL = 5,  /* v += r[m,n]                                (p0 = r, ld)          */
+    FLE_LAYERNORM = 6, /* over n: (v - mean) / sqrt(biased var + alpha) * gamma[n] + beta[n];
+                          p0 = gamma or NULL (1), p1 = beta or NULL (0), alpha = eps        */
+    FLE_SOFTMAX = 7,   /* over n: exp(v - max) / sum exp(v - max)                           */
+    FLE_LOGSUMEXP = 8  /* over n: max + log sum exp(v - max); out becomes [M]; last op only */
+} fle_op_kind;
+
+#define FLE_MAX_OPS 8
+
+typedef struct {
+    int32_t kind;   /* fle_op_kind */
+    float alpha;    /* SCALE: factor.  LAYERNORM: eps.  Otherwise ignored.                 */
+    const void *p0; /* RESIDUAL: r[M,N] (device).  LAYERNORM: gamma[N] (device) or NULL.   */
+    const void *p1; /* LAYERNORM: beta[N] (device) or NULL.                                */
+    int64_t ld;     /* RESIDUAL: row stride of r in elements (>= N).                       */
+} fle_op;
+
+typedef struct {
+    int64_t M, N, K;        /* M >= 0, N >= 1, K >= 0.  M == 0 is a valid no-op.           */
+    int32_t dtype;          /* fle_dtype                                                    */
+    const void *x;          /* device [M,K], row stride ldx >= K elements                   */
+    int64_t ldx;
+    const void *w;          /* device [N,K], row stride ldw >= K elements                   */
+    int64_t ldw;
+    const void *b;          /* device [N], or NULL when no FLE_BIAS op is listed            */
+    void *out;              /* device [M,N] with row stride ldo >= N, or [M] contiguous
+                               (ldo ignored) when the list ends in FLE_LOGSUMEXP            */
+    int64_t ldo;
+    const fle_op *ops;      /* host array of n_ops entries, applied in order                */
+    int32_t n_ops;          /* 0 .. FLE_MAX_OPS                                             */
+    void *workspace;        /* device scratch of at least fle_workspace_size() bytes,
+                               256-byte aligned; may be NULL when that size is 0.  Its
+                               contents are undefined afterwards; it needs no clearing.     */
+    size_t workspace_bytes;
+    void *stream;           /* hipStream_t (NULL = the default stream)                      */
+} fle_problem;
+
+/*
+ * Accepted epilogue grammar:   elementwise*  [ LAYERNORM | SOFTMAX | LOGSUMEXP ]  elementwise*
+ * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL, at most one row
+ * op, and nothing after LOGSUMEXP.  A second row op gives FLE_ERR_UNSUPPORTED.
+ *
+ * Alignment rule: no alignment is required for correctness.  The MFMA fast paths are taken
+ * when x, W, out and residual pointers are 16-byte aligned, their row strides are multiples
+ * of 16 bytes and (bf16) K % 8 == 0; other problems run on a slower general kernel.
+ * `out` may alias a residual operand only exactly (same pointer and stride); it must not
+ * overlap x, W, b, gamma, beta or the workspace.
+ */
+
+/* Host only (no HIP call).  Checks everything fle_run checks except the workspace size. */
+fle_status fle_validate(const fle_problem *p);
+
+/* Host only.  Bytes of device scratch fle_run needs for this problem (0 for purely
+ * elementwise epilogues on the tiled kernels). */
+fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out);
+
+/* Validates, then enqueues one to three kernels on p->stream and returns without
+ * synchronising.  Never allocates or frees device memory. */
+fle_status fle_run(const fle_problem *p);
+
+/* Static description of a status code. */
+const char *fle_status_string(fle_status s);
+
+/* Detail text of the calling thread's most recent failing call ("" if none). */
+const char *fle_last_error(void);
+
+/* Human-readable plan (kernel variant, tile, grid) of the calling thread's most recent
+ * successful fle_run or fle_workspace_size, copied into buf (NUL-terminated, truncated to n). */
+fle_status fle_last_plan(char *buf, size_t n);
+
+/* Force a kernel variant for the calling thread's next calls, for tests and tuning:
+ * 0 = automatic, 1 = general kernel, 2 = tiled bf16 MFMA kernel (automatic tile), 3 = skinny
+ * kernel, 4 = tiled with the 256x256 tile, 5 = tiled with the 128x128 tile.
+ * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run. */
+void fle_force_variant(int variant);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int fle_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLE_H */

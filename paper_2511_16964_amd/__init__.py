@@ -5,11 +5,12 @@ HIP kernels of ``libfle.so`` (C ABI declared in ``include/fle.h``); this package
 is argument marshalling only.  Nothing here falls back to a CPU or PyTorch
 implementation: if the library is missing, calls raise.
 """
-__all__ = ["fused_linear_epilogue", "inputs"]
+import importlib
+
+__all__ = ["fused_linear_epilogue"]
 
 
 def __getattr__(name):
-    if name in ("fused_linear_epilogue", "binding"):
-        from . import binding
-        return binding if name == "binding" else binding.fused_linear_epilogue
+    if name == "fused_linear_epilogue":
+        return importlib.import_module(__name__ + ".binding").fused_linear_epilogue
     raise AttributeError(name)

@@ -1,0 +1,187 @@
+"""ctypes binding of libfle (see include/fle.h).  Argument marshalling only: every
+step of fused_linear_epilogue runs in the library's HIP kernels.  PyTorch provides
+device memory and the stream, nothing else.  There is no fallback path: if the
+library is missing or refuses a problem, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfle.so")
+
+F32, BF16 = 0, 1
+OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
+            "layernorm": 6, "softmax": 7, "logsumexp": 8}
+MAX_OPS = 8
+VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5}
+EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
+           "fle_last_plan", "fle_force_variant", "fle_version"]
+
+
+class FleOp(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("alpha", ctypes.c_float), ("p0", ctypes.c_void_p),
+                ("p1", ctypes.c_void_p), ("ld", ctypes.c_int64)]
+
+
+class FleProblem(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("dtype", ctypes.c_int32),
+                ("x", ctypes.c_void_p), ("ldx", ctypes.c_int64),
+                ("w", ctypes.c_void_p), ("ldw", ctypes.c_int64),
+                ("b", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("ldo", ctypes.c_int64),
+                ("ops", ctypes.POINTER(FleOp)), ("n_ops", ctypes.c_int32),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("stream", ctypes.c_void_p)]
+
+
+class FleError(RuntimeError):
+    def __init__(self, status: int, name: str, detail: str):
+        super().__init__("libfle: %s (status %d): %s" % (name, status, detail))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Load libfle.so (built in-tree by ``__graft_entry__.build()``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                LIB_PATH + " is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        for name in ("fle_validate", "fle_run"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.POINTER(FleProblem)]
+        L.fle_workspace_size.restype = ctypes.c_int
+        L.fle_workspace_size.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(ctypes.c_size_t)]
+        L.fle_status_string.restype = ctypes.c_char_p
+        L.fle_status_string.argtypes = [ctypes.c_int]
+        L.fle_last_error.restype = ctypes.c_char_p
+        L.fle_last_plan.restype = ctypes.c_int
+        L.fle_last_plan.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+        L.fle_force_variant.restype = None
+        L.fle_force_variant.argtypes = [ctypes.c_int]
+        L.fle_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        L = lib()
+        raise FleError(status, L.fle_status_string(status).decode(), L.fle_last_error().decode())
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return F32
+    if dt == torch.bfloat16:
+        return BF16
+    raise TypeError("fused_linear_epilogue supports float32 and bfloat16, got %s" % dt)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+class Call:
+    """A marshalled fle_problem bound to its tensors: ``run()`` enqueues it on the
+    current stream.  Keeps every tensor alive; reusable (the benchmark times ``run``)."""
+
+    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto"):
+        if x.dim() != 2 or w.dim() != 2 or x.shape[1] != w.shape[1]:
+            raise ValueError("x must be [M,K] and w [N,K]")
+        if x.stride(1) != 1 and x.shape[1] > 1 or w.stride(1) != 1 and w.shape[1] > 1:
+            raise ValueError("x and w must be row-major (unit stride along K)")
+        self.variant = VARIANTS[variant]
+        M, K = x.shape
+        N = w.shape[0]
+        dt = x.dtype
+        tensors = [x, w, b]
+        if len(epilogue) > MAX_OPS:
+            raise ValueError("at most %d epilogue ops" % MAX_OPS)
+        ops = (FleOp * max(1, len(epilogue)))()
+        for i, e in enumerate(epilogue):
+            kind = OP_KINDS[e[0]]
+            ops[i].kind = kind
+            if e[0] == "scale":
+                ops[i].alpha = float(e[1])
+            elif e[0] == "residual":
+                r = e[1]
+                if r.shape != (M, N) or (r.stride(1) != 1 and N > 1):
+                    raise ValueError("residual must be [M,N] with unit column stride")
+                tensors.append(r)
+                ops[i].p0 = r.data_ptr()
+                ops[i].ld = r.stride(0) if M > 1 else max(N, r.stride(0))
+            elif e[0] == "layernorm":
+                g, be, eps = e[1], e[2], e[3]
+                tensors += [g, be]
+                ops[i].p0 = None if g is None else g.data_ptr()
+                ops[i].p1 = None if be is None else be.data_ptr()
+                ops[i].alpha = float(eps)
+        for t in tensors:
+            if t is not None and (t.dtype != dt or t.device != x.device):
+                raise TypeError("all operands must share x's dtype and device")
+        lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
+        if out is None:
+            out = torch.empty((M,) if lse else (M, N), dtype=dt, device=x.device)
+        self.out = out
+        p = FleProblem()
+        p.M, p.N, p.K, p.dtype = M, N, K, _dtype_code(dt)
+        p.x, p.ldx = x.data_ptr(), (x.stride(0) if M > 1 else max(K, x.stride(0)))
+        p.w, p.ldw = w.data_ptr(), (w.stride(0) if N > 1 else max(K, w.stride(0)))
+        p.b = None if b is None else b.data_ptr()
+        p.out = out.data_ptr()
+        p.ldo = 0 if lse else (out.stride(0) if M > 1 else max(N, out.stride(0)))
+        p.ops, p.n_ops = ops, len(epilogue)
+        self._p, self._ops, self._tensors = p, ops, tensors
+        L = lib()
+        L.fle_force_variant(self.variant)
+        try:
+            need = ctypes.c_size_t(0)
+            _check(L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)))
+        finally:
+            L.fle_force_variant(0)
+        if workspace is None and need.value:
+            workspace = torch.empty(need.value, dtype=torch.uint8, device=x.device)
+        self.workspace = workspace
+        if workspace is not None:
+            p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        self.workspace_needed = need.value
+
+    def run(self, stream=None):
+        """Enqueue on ``stream`` (default: torch's current stream) and return ``out`` without synchronising."""
+        L = lib()
+        s = torch.cuda.current_stream() if stream is None else stream
+        self._p.stream = s.cuda_stream  # the HIP stream handle
+        L.fle_force_variant(self.variant)
+        try:
+            _check(L.fle_run(ctypes.byref(self._p)))
+        finally:
+            L.fle_force_variant(0)
+        return self.out
+
+    def plan(self) -> str:
+        buf = ctypes.create_string_buffer(256)
+        lib().fle_last_plan(buf, 256)
+        return buf.value.decode()
+
+
+def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto"):
+    """out = epilogue(x @ w.T) in one fused library call.
+
+    x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32 or bfloat16).
+    epilogue: ordered list of ("bias",) ("scale", a) ("relu",) ("gelu_erf",) ("gelu_tanh",)
+    ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",).
+    Returns a tensor of x's dtype: [M,N], or [M] when the list ends in logsumexp.
+    """
+    if not x.is_cuda:
+        raise RuntimeError("fused_linear_epilogue runs on the GPU only; there is no CPU path")
+    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant).run()

@@ -1,0 +1,222 @@
+// Host side of libfle: argument validation, epilogue grammar, kernel planning and the C ABI.
+// This translation unit makes no HIP call, so everything it decides is testable without a GPU.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "fle_plan.h"
+
+namespace fle {
+
+static thread_local char g_error[512] = "";
+static thread_local char g_plan[200] = "";
+static thread_local int g_forced = V_AUTO;
+
+fle_status fail(fle_status s, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+static inline bool is_row_op(int k) { return k == FLE_LAYERNORM || k == FLE_SOFTMAX || k == FLE_LOGSUMEXP; }
+static inline size_t esize(int dtype) { return dtype == FLE_BF16 ? 2 : 4; }
+static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Half-open byte ranges [a, a+na) and [b, b+nb) intersect.
+static bool overlaps(const void *a, size_t na, const void *b, size_t nb) {
+    if (!a || !b || na == 0 || nb == 0) return false;
+    uintptr_t pa = reinterpret_cast<uintptr_t>(a), pb = reinterpret_cast<uintptr_t>(b);
+    return pa < pb + nb && pb < pa + na;
+}
+
+static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return (static_cast<size_t>(rows - 1) * static_cast<size_t>(ld) + static_cast<size_t>(cols)) * es;
+}
+
+fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
+    if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
+    std::memset(plan, 0, sizeof *plan);
+    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32 or FLE_BF16", p->dtype);
+    const int64_t M = p->M, N = p->N, K = p->K;
+    const int64_t kLimit = int64_t(1) << 40;
+    if (M < 0 || N < 1 || K < 0) return fail(FLE_ERR_SHAPE, "need M >= 0, N >= 1, K >= 0 (got %lld, %lld, %lld)", (long long)M, (long long)N, (long long)K);
+    if (M > kLimit || N > (int64_t(1) << 30) || K > (int64_t(1) << 30)) return fail(FLE_ERR_SHAPE, "size too large");
+    if (p->n_ops < 0 || p->n_ops > FLE_MAX_OPS) return fail(FLE_ERR_OP, "n_ops %d outside 0..%d", p->n_ops, FLE_MAX_OPS);
+    if (p->n_ops > 0 && !p->ops) return fail(FLE_ERR_NULL, "ops is NULL with n_ops %d", p->n_ops);
+
+    DevEpilogue &e = plan->epi;
+    e.row_kind = -1;
+    e.dtype = p->dtype;
+    e.bias = p->b;
+    const size_t es = esize(p->dtype);
+    for (int i = 0; i < p->n_ops; ++i) {
+        const fle_op &op = p->ops[i];
+        if (op.kind < FLE_BIAS || op.kind > FLE_LOGSUMEXP) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (e.row_kind == FLE_LOGSUMEXP) return fail(FLE_ERR_UNSUPPORTED, "op %d follows logsumexp, which must be last", i);
+        DevOp d{op.kind, op.alpha, op.p0, op.p1, op.ld};
+        if (is_row_op(op.kind)) {
+            if (e.row_kind >= 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: a second row reduction in one list is not supported", i);
+            if (op.kind == FLE_LAYERNORM && !(op.alpha >= 0.0f && std::isfinite(op.alpha))) return fail(FLE_ERR_OP, "op %d: layernorm eps must be finite and >= 0", i);
+            e.row_kind = op.kind;
+            e.row = d;
+            continue;
+        }
+        if (op.kind == FLE_BIAS && !p->b && M > 0) return fail(FLE_ERR_NULL, "op %d: bias listed but b is NULL", i);
+        if (op.kind == FLE_SCALE && !std::isfinite(op.alpha)) return fail(FLE_ERR_OP, "op %d: scale factor is not finite", i);
+        if (op.kind == FLE_RESIDUAL) {
+            if (!op.p0 && M > 0) return fail(FLE_ERR_NULL, "op %d: residual pointer is NULL", i);
+            if (op.ld < N) return fail(FLE_ERR_SHAPE, "op %d: residual ld %lld < N %lld", i, (long long)op.ld, (long long)N);
+            if (op.ld > kLimit) return fail(FLE_ERR_SHAPE, "op %d: residual ld too large", i);
+        }
+        if (e.row_kind < 0) e.pre[e.n_pre++] = d; else e.post[e.n_post++] = d;
+    }
+    const bool lse = e.row_kind == FLE_LOGSUMEXP;
+    if (p->ldx < K || p->ldw < K) return fail(FLE_ERR_SHAPE, "ldx %lld / ldw %lld smaller than K %lld", (long long)p->ldx, (long long)p->ldw, (long long)K);
+    if (!lse && p->ldo < N) return fail(FLE_ERR_SHAPE, "ldo %lld < N %lld", (long long)p->ldo, (long long)N);
+    if (p->ldx > kLimit || p->ldw > kLimit || p->ldo > kLimit) return fail(FLE_ERR_SHAPE, "leading dimension too large");
+    if (M > 0) {
+        if (!p->out) return fail(FLE_ERR_NULL, "out is NULL");
+        if (K > 0 && (!p->x || !p->w)) return fail(FLE_ERR_NULL, "x or w is NULL");
+        // element alignment is the only hard requirement
+        if (!aligned(p->x, es) || !aligned(p->w, es) || !aligned(p->out, es) || !aligned(p->b, es)) return fail(FLE_ERR_ALIGN, "a pointer is not aligned to its element size");
+        const size_t out_bytes = lse ? size_t(M) * es : span_bytes(M, N, p->ldo, es);
+        if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, es)) || overlaps(p->out, out_bytes, p->w, span_bytes(N, K, p->ldw, es)) ||
+            overlaps(p->out, out_bytes, p->b, size_t(N) * es))
+            return fail(FLE_ERR_UNSUPPORTED, "out overlaps x, w or b");
+        for (int i = 0; i < p->n_ops; ++i) {
+            const fle_op &op = p->ops[i];
+            if (op.kind == FLE_RESIDUAL) {
+                if (!aligned(op.p0, es)) return fail(FLE_ERR_ALIGN, "op %d: residual pointer not aligned to its element size", i);
+                const bool same = op.p0 == p->out && op.ld == p->ldo && !lse;
+                if (!same && overlaps(p->out, out_bytes, op.p0, span_bytes(M, N, op.ld, es))) return fail(FLE_ERR_UNSUPPORTED, "op %d: out overlaps the residual without being identical to it", i);
+            } else if (op.kind == FLE_LAYERNORM) {
+                if (!aligned(op.p0, es) || !aligned(op.p1, es)) return fail(FLE_ERR_ALIGN, "op %d: gamma/beta not aligned to the element size", i);
+                if (overlaps(p->out, out_bytes, op.p0, size_t(N) * es) || overlaps(p->out, out_bytes, op.p1, size_t(N) * es)) return fail(FLE_ERR_UNSUPPORTED, "op %d: out overlaps gamma or beta", i);
+            }
+        }
+        if (p->workspace && overlaps(p->out, out_bytes, p->workspace, p->workspace_bytes)) return fail(FLE_ERR_UNSUPPORTED, "out overlaps the workspace");
+    }
+
+    // ---- kernel variant
+    bool res_ok = true, post_res_alias_out = false;
+    for (int i = 0; i < e.n_pre; ++i)
+        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, 8) && e.pre[i].ld % 4 == 0)) res_ok = false;
+    for (int i = 0; i < e.n_post; ++i)
+        if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
+    const bool tiled_ok = p->dtype == FLE_BF16 && K >= 64 && K % 64 == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
+                          p->ldx % 8 == 0 && p->ldw % 8 == 0 && aligned(p->out, 8) && (lse || p->ldo % 4 == 0) && aligned(p->b, 8) && res_ok &&
+                          p->ldx < (int64_t(1) << 21) && p->ldw < (int64_t(1) << 21);
+    int variant = forced, forced_tile = 0;
+    if (variant == V_TILED_256 || variant == V_TILED_128) {
+        forced_tile = variant == V_TILED_256 ? 256 : 128;
+        variant = V_TILED;
+    }
+    if (variant == V_AUTO) variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
+    if (variant == V_SKINNY) return fail(FLE_ERR_UNSUPPORTED, "the skinny variant is not available for this problem");
+    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 64 == 0, N %% 4 == 0 and 16-byte aligned operands");
+    if (variant != V_TILED && variant != V_GENERAL) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
+    plan->variant = variant;
+    if (variant == V_TILED) {
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+        const bool big = M > 128 && N > 128 && t256 >= 128;
+        plan->bm = plan->bn = forced_tile ? forced_tile : big ? 256 : 128;
+        plan->part_cols = plan->bn / 2;  // one partial per wave column
+    } else {
+        plan->bm = plan->bn = 32;
+        plan->part_cols = 16;
+    }
+    plan->tiles_m = (M + plan->bm - 1) / plan->bm;
+    plan->tiles_n = (N + plan->bn - 1) / plan->bn;
+    if (plan->tiles_m * plan->tiles_n > (int64_t(1) << 31) - 1) return fail(FLE_ERR_SHAPE, "too many tiles for one launch");
+
+    // ---- staging and workspace
+    size_t off = 0;
+    plan->staging = ST_NONE;
+    if (e.row_kind >= 0) {
+        plan->np = int32_t((N + plan->part_cols - 1) / plan->part_cols);
+        plan->ws_part_off = off;
+        off = round_up(off + size_t(M) * size_t(plan->np) * 2 * sizeof(float), 256);
+        if (!lse) {
+            const bool in_out = !post_res_alias_out && (e.row_kind == FLE_LAYERNORM || p->dtype == FLE_F32);
+            plan->staging = in_out ? ST_OUT : ST_WS;
+            if (!in_out) {
+                plan->ws_y_off = off;
+                off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);
+            }
+        }
+    }
+    plan->ws_total = M > 0 ? off : 0;
+    snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld row_op=%d np=%d staging=%s workspace=%zu",
+             variant == V_TILED ? "tiled_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, variant == V_TILED ? 64 : 16, (long long)plan->tiles_m,
+             (long long)plan->tiles_n, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
+    return FLE_OK;
+}
+
+}  // namespace fle
+
+using namespace fle;
+
+extern "C" {
+
+fle_status fle_validate(const fle_problem *p) {
+    Plan plan;
+    return make_plan(p, g_forced, &plan);
+}
+
+fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out) {
+    if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
+    Plan plan;
+    fle_status s = make_plan(p, g_forced, &plan);
+    if (s != FLE_OK) return s;
+    *bytes_out = plan.ws_total;
+    std::memcpy(g_plan, plan.text, sizeof g_plan);
+    return FLE_OK;
+}
+
+fle_status fle_run(const fle_problem *p) {
+    Plan plan;
+    fle_status s = make_plan(p, g_forced, &plan);
+    if (s != FLE_OK) return s;
+    if (p->M == 0) return FLE_OK;
+    if (plan.ws_total > 0) {
+        if (!p->workspace) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", plan.ws_total);
+        if (p->workspace_bytes < plan.ws_total) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_total);
+        if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
+    }
+    s = launch(p, plan);
+    if (s == FLE_OK) std::memcpy(g_plan, plan.text, sizeof g_plan);
+    return s;
+}
+
+const char *fle_status_string(fle_status s) {
+    switch (s) {
+    case FLE_OK: return "ok";
+    case FLE_ERR_NULL: return "required pointer is NULL";
+    case FLE_ERR_SHAPE: return "invalid shape or leading dimension";
+    case FLE_ERR_ALIGN: return "misaligned pointer or leading dimension";
+    case FLE_ERR_OP: return "invalid epilogue op";
+    case FLE_ERR_UNSUPPORTED: return "unsupported combination";
+    case FLE_ERR_WORKSPACE: return "workspace missing or too small";
+    case FLE_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *fle_last_error(void) { return g_error; }
+
+fle_status fle_last_plan(char *buf, size_t n) {
+    if (!buf || n == 0) return fail(FLE_ERR_NULL, "buf is NULL or empty");
+    snprintf(buf, n, "%s", g_plan);
+    return FLE_OK;
+}
+
+void fle_force_variant(int variant) { g_forced = variant; }
+
+int fle_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal: the plan the host derives from an fle_problem and hands to the kernels.
+// Shared by the HIP-free host translation unit and the kernel translation unit.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fle.h"
+
+namespace fle {
+
+// One epilogue op as the kernels see it (pointers are device pointers).
+struct DevOp {
+    int32_t kind;
+    float alpha;
+    const void *p0;
+    const void *p1;
+    int64_t ld;
+};
+
+// The op list split at its (single, optional) row reduction.
+struct DevEpilogue {
+    int32_t n_pre;     // elementwise ops applied in the GEMM kernel's registers
+    int32_t n_post;    // elementwise ops applied by the finalize pass, after the row op
+    int32_t row_kind;  // FLE_LAYERNORM / FLE_SOFTMAX / FLE_LOGSUMEXP, or -1
+    int32_t dtype;     // fle_dtype of every operand
+    const void *bias;  // b[N] or nullptr
+    DevOp row;         // valid when row_kind >= 0
+    DevOp pre[FLE_MAX_OPS];
+    DevOp post[FLE_MAX_OPS];
+};
+
+enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5 };
+
+// Where the GEMM pass writes its (pre-row-op) values.
+enum Staging {
+    ST_NONE = 0,  // no row op: final values go straight to out; or logsumexp: nothing staged
+    ST_OUT = 1,   // staged in out itself (storage dtype), finalize rewrites it in place
+    ST_WS = 2     // staged as fp32 [M,N] in the workspace
+};
+
+struct Plan {
+    int32_t variant;
+    int32_t bm, bn;          // block tile: rows of x, rows of W
+    int32_t part_cols;       // columns covered by one row-reduction partial
+    int32_t np;              // partials per row = ceil(N / part_cols)
+    int32_t staging;
+    int64_t tiles_m, tiles_n;
+    size_t ws_part_off, ws_y_off, ws_total;
+    DevEpilogue epi;
+    char text[200];
+};
+
+// Validates p (everything except workspace size) and fills plan.  Host only, no HIP calls.
+fle_status make_plan(const fle_problem *p, int forced_variant, Plan *plan);
+
+// Records the calling thread's error detail; returns s.
+fle_status fail(fle_status s, const char *fmt, ...);
+
+// Implemented in the kernel translation unit: enqueue the planned kernels.
+fle_status launch(const fle_problem *p, const Plan &plan);
+
+}  // namespace fle

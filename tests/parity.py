@@ -1,0 +1,72 @@
+"""Shared helpers of the GPU parity tests: run a Problem through the C-ABI library,
+run the same values through the CPU oracle, and compare element by element.
+
+Pass criterion (the allclose form of the paper's Appendix A, with the trusted side on the
+right and the absolute part scaled to the output's magnitude):
+    |gpu - ref| <= tol * (s + |ref|),   s = min(1, RMS(ref)),
+with tol = 1e-4 for fp32 problems and 2e-2 for bf16 problems.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2511_16964_amd import binding, inputs
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+
+def to_dev(t, dev="cuda:0"):
+    return None if t is None else t.to(dev)
+
+
+def dev_epilogue(ep, dev="cuda:0"):
+    return [tuple(to_dev(a, dev) if isinstance(a, torch.Tensor) else a for a in e) for e in ep]
+
+
+def make_call(prob: inputs.Problem, variant="auto", **kw) -> binding.Call:
+    return binding.Call(to_dev(prob.x), to_dev(prob.w), to_dev(prob.b), dev_epilogue(prob.epilogue),
+                        variant=variant, **kw)
+
+
+def run_gpu(prob: inputs.Problem, variant="auto"):
+    call = make_call(prob, variant)
+    out = call.run()
+    torch.cuda.synchronize()
+    return out.cpu(), call
+
+
+def oracle_rows(prob: inputs.Problem, rows=None) -> np.ndarray:
+    """Oracle result for all rows, or for the listed rows only (every op is row-local)."""
+    x = prob.x if rows is None else prob.x[rows]
+    return oracle.fused_linear_epilogue(inputs.to_f64(x), inputs.to_f64(prob.w), inputs.to_f64(prob.b),
+                                        inputs.epilogue_f64(prob.epilogue, rows))
+
+
+def excess(got: np.ndarray, ref: np.ndarray, tol: float):
+    """(worst violation of the criterion (<= 0 passes), max abs error, RMS-scale s)."""
+    s = min(1.0, float(np.sqrt(np.mean(ref * ref)))) if ref.size else 1.0
+    err = np.abs(got - ref)
+    if ref.size == 0:
+        return 0.0, 0.0, s
+    return float(np.max(err - tol * (s + np.abs(ref)))), float(err.max()), s
+
+
+def assert_close(got_t: torch.Tensor, ref: np.ndarray, dtype, what=""):
+    got = got_t.to(torch.float64).numpy()
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all(), "non-finite GPU output " + what
+    worst, maxerr, s = excess(got, ref, TOL[dtype])
+    assert worst <= 0, "%s: criterion exceeded by %.3e (max |err| %.3e, s %.3e)" % (what, worst, maxerr, s)
+    return maxerr
+
+
+def sample_rows(M: int, count: int, tile: int = 256, seed: int = 7):
+    """Row sample that always holds the first and last row of the matrix and of some tiles."""
+    rng = np.random.default_rng(seed)
+    rows = {0, M - 1, min(M - 1, tile - 1), min(M - 1, tile), min(M - 1, 31), min(M - 1, 32),
+            max(0, M - tile), max(0, M - tile - 1)}
+    while len(rows) < min(count, M):
+        rows.add(int(rng.integers(0, M)))
+    return sorted(rows)

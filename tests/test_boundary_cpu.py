@@ -1,0 +1,181 @@
+"""Host-side tests of the C-ABI library that need no GPU: the library loads, exports
+every function include/fle.h declares, and rejects invalid problems before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_16964_amd import binding
+from paper_2511_16964_amd.binding import FleOp, FleProblem
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_SHAPE, E_ALIGN, E_OP, E_UNSUP, E_WS, E_HIP = range(8)
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fle.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fle_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(L):
+    names = declared_functions()
+    assert sorted(names) == sorted(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings(L):
+    assert L.fle_version() >= 100
+    seen = {L.fle_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and all(s for s in seen)
+
+
+G = 1 << 32   # fake buffers sit 4 GiB apart so that large shapes never overlap
+
+
+def problem(M=64, N=64, K=64, dtype=binding.BF16, ops=(), b=5 * G, base=G):
+    """A problem with fake (never dereferenced) device addresses; validation is host-only."""
+    p = FleProblem()
+    p.M, p.N, p.K, p.dtype = M, N, K, dtype
+    p.x, p.ldx = base, K
+    p.w, p.ldw = base + G, K
+    p.b = b
+    p.out, p.ldo = base + 2 * G, N
+    arr = (FleOp * max(1, len(ops)))()
+    for i, (kind, alpha, p0, p1, ld) in enumerate(ops):
+        arr[i].kind, arr[i].alpha, arr[i].p0, arr[i].p1, arr[i].ld = kind, alpha, p0, p1, ld
+    p.ops, p.n_ops = arr, len(ops)
+    p._keep = arr
+    return p
+
+
+def op(kind, alpha=0.0, p0=None, p1=None, ld=0):
+    return (binding.OP_KINDS[kind], alpha, p0, p1, ld)
+
+
+def validate(L, p):
+    return L.fle_validate(ctypes.byref(p))
+
+
+def test_accepts_all_benchmark_chains(L):
+    res = 6 * G
+    chains = [
+        [op("bias"), op("gelu_erf")],
+        [op("bias"), op("relu"), op("scale", 0.5), op("residual", p0=res, ld=64)],
+        [op("bias"), op("gelu_tanh"), op("layernorm", 1e-5, 7 * G, 8 * G)],
+        [op("softmax")],
+        [op("bias"), op("residual", p0=res, ld=64), op("layernorm", 1e-5, 7 * G, 8 * G)],
+        [op("scale", 2.0), op("logsumexp")],
+        [op("layernorm", 1e-5), op("gelu_erf"), op("residual", p0=res, ld=64)],
+        [],
+    ]
+    for ch in chains:
+        for dt in (binding.F32, binding.BF16):
+            assert validate(L, problem(ops=ch, dtype=dt)) == OK, L.fle_last_error()
+
+
+def test_null_pointers(L):
+    assert L.fle_validate(None) == E_NULL
+    p = problem(); p.x = None
+    assert validate(L, p) == E_NULL
+    p = problem(); p.out = None
+    assert validate(L, p) == E_NULL
+    assert validate(L, problem(ops=[op("bias")], b=None)) == E_NULL
+    assert b"bias" in L.fle_last_error()
+    assert validate(L, problem(ops=[op("residual", p0=None, ld=64)])) == E_NULL
+    p = problem(); p.n_ops = 2; p.ops = None
+    assert validate(L, p) == E_NULL
+    assert L.fle_workspace_size(ctypes.byref(problem()), None) == E_NULL
+
+
+def test_shapes(L):
+    assert validate(L, problem(M=-1)) == E_SHAPE
+    assert validate(L, problem(N=0)) == E_SHAPE
+    assert validate(L, problem(K=-3)) == E_SHAPE
+    p = problem(); p.ldx = 63
+    assert validate(L, p) == E_SHAPE
+    p = problem(); p.ldw = 8
+    assert validate(L, p) == E_SHAPE
+    p = problem(); p.ldo = 63
+    assert validate(L, p) == E_SHAPE
+    assert validate(L, problem(ops=[op("residual", p0=6 * G, ld=63)])) == E_SHAPE
+    # M == 0 is a valid no-op, even with NULL buffers
+    p = problem(M=0); p.x = None; p.out = None
+    assert validate(L, p) == OK
+    assert L.fle_run(ctypes.byref(p)) == OK          # returns before any HIP call
+
+
+def test_ops_and_grammar(L):
+    assert validate(L, problem(ops=[(42, 0.0, None, None, 0)])) == E_OP
+    assert validate(L, problem(ops=[op("scale", float("nan"))])) == E_OP
+    assert validate(L, problem(ops=[op("layernorm", -1.0)])) == E_OP
+    p = problem(); p.n_ops = 9
+    assert validate(L, p) == E_OP
+    p = problem(); p.dtype = 7
+    assert validate(L, p) == E_OP
+    assert validate(L, problem(ops=[op("softmax"), op("layernorm", 1e-5)])) == E_UNSUP
+    assert validate(L, problem(ops=[op("logsumexp"), op("relu")])) == E_UNSUP
+    assert b"logsumexp" in L.fle_last_error()
+
+
+def test_alignment_and_aliasing(L):
+    p = problem(); p.x = G + 1
+    assert validate(L, p) == E_ALIGN                  # not even element-aligned
+    p = problem(); p.out = p.x
+    assert validate(L, p) == E_UNSUP                  # out overlaps x
+    out = problem().out
+    assert validate(L, problem(ops=[op("residual", p0=out, ld=64)])) == OK        # exact alias allowed
+    assert validate(L, problem(ops=[op("residual", p0=out + 2, ld=64)])) == E_UNSUP  # partial overlap
+
+
+def test_workspace_sizes_and_plan_text(L):
+    need = ctypes.c_size_t(99)
+    assert L.fle_workspace_size(ctypes.byref(problem(ops=[op("bias"), op("relu")])), ctypes.byref(need)) == OK
+    assert need.value == 0
+    # LayerNorm, bf16, staged in out: only partials [M][np][2] floats
+    p = problem(M=512, N=1024, K=256, ops=[op("layernorm", 1e-5)])
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    buf = ctypes.create_string_buffer(256)
+    L.fle_last_plan(buf, 256)
+    text = buf.value.decode()
+    assert "tiled_bf16_mfma" in text and "staging=out" in text
+    np_ = int(re.search(r"np=(\d+)", text).group(1))
+    assert need.value == 512 * np_ * 8
+    # bf16 softmax stages fp32 in the workspace
+    p = problem(M=512, N=1024, K=256, ops=[op("softmax")])
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    assert need.value >= 512 * 1024 * 4
+    # run without workspace fails before any HIP call
+    assert L.fle_run(ctypes.byref(p)) == E_WS
+    p.workspace, p.workspace_bytes = 9 * G, 16
+    assert L.fle_run(ctypes.byref(p)) == E_WS
+
+
+def test_variant_selection(L):
+    def plan_of(p):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return buf.value.decode()
+    assert "tile=256x256" in plan_of(problem(M=4096, N=4096, K=4096))
+    assert "tile=128x128" in plan_of(problem(M=512, N=512, K=512))
+    assert "general" in plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))
+    assert "general" in plan_of(problem(M=512, N=512, K=500))      # K not a multiple of 64
+    p = problem(M=512, N=512, K=512); p.x = p.x + 2                # misaligned x
+    assert "general" in plan_of(p)
+    L.fle_force_variant(2)
+    try:
+        assert validate(L, problem(M=64, N=256, K=256, dtype=binding.F32)) == E_UNSUP
+    finally:
+        L.fle_force_variant(0)

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU float64 oracle, element by
+element, on the same seeded inputs.  Tolerances: 1e-4 (fp32), 2e-2 (bf16); integer-valued
+problems must match bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_16964_amd import binding, inputs
+
+from parity import TOL, assert_close, make_call, oracle_rows, run_gpu, sample_rows, to_dev, dev_epilogue
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = torch.float32, torch.bfloat16
+
+
+def announce(*a):
+    print("[case]", *a, flush=True)
+
+
+# ------------------------------------------------------------------ small, complete comparisons
+def test_c1_fp32_bias_gelu_erf_full():
+    prob = inputs.make("c1")
+    announce("c1 full", prob.M, prob.N, prob.K)
+    got, call = run_gpu(prob)
+    assert "general" in call.plan()
+    err = assert_close(got, oracle_rows(prob), F32, "c1")
+    print("c1 max|err| %.3e" % err)
+
+
+@pytest.mark.parametrize("variant,M,N,K", [
+    ("tiled", 256, 256, 64), ("tiled", 300, 520, 192), ("tiled", 128, 128, 128), ("tiled", 77, 132, 64),
+    ("tiled", 513, 772, 128), ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
+])
+def test_integer_inputs_are_bit_exact(variant, M, N, K):
+    """Small-integer operands: every product and partial sum is exact in fp32 and the chain
+    bias/relu/scale(0.5)/residual stays exactly representable in bf16, so any difference at
+    all is an indexing error (tile mapping, MFMA operand layout, LDS swizzle, masking)."""
+    prob = inputs.random_problem(11, M, N, K, BF16, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("integer exact", variant, M, N, K)
+    got, call = run_gpu(prob, variant)
+    ref = oracle_rows(prob)
+    assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
+
+
+def test_integer_exact_on_the_256_tile():
+    prob = inputs.random_problem(12, 2304, 2000, 128, BF16, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("integer exact 256-tile", prob.M, prob.N, prob.K)
+    got, call = run_gpu(prob, "tiled256")
+    assert "tile=256x256" in call.plan()
+    rows = sample_rows(prob.M, 96)
+    assert np.array_equal(got[rows].to(torch.float64).numpy(), oracle_rows(prob, rows))
+
+
+CHAINS = [
+    [], ["bias"], ["bias", "gelu_erf"], ["bias", "gelu_tanh"], ["bias", "relu", "scale", "residual"],
+    ["bias", "gelu_tanh", "layernorm"], ["softmax"], ["bias", "residual", "layernorm"], ["scale", "logsumexp"],
+    ["bias", "layernorm", "gelu_erf", "residual"], ["relu", "softmax", "scale", "bias"], ["bias", "logsumexp"],
+]
+SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kernels and dtypes
+    ("tiled", BF16, 200, 392, 128), ("tiled", BF16, 129, 260, 64), ("general", BF16, 70, 97, 83),
+    ("general", F32, 70, 97, 83), ("general", F32, 64, 256, 256), ("general", BF16, 37, 264, 96),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "%s-%s-%dx%dx%d" % (s[0], str(s[1])[6:], s[2], s[3], s[4]))
+@pytest.mark.parametrize("kinds", CHAINS, ids=lambda k: "+".join(k) or "plain")
+def test_chains_small_shapes(shape, kinds):
+    variant, dtype, M, N, K = shape
+    prob = inputs.random_problem(3, M, N, K, dtype, kinds)
+    announce("chain", variant, dtype, M, N, K, kinds)
+    got, call = run_gpu(prob, variant)
+    assert_close(got, oracle_rows(prob), dtype, "%s %s" % (kinds, call.plan()))
+
+
+def test_both_gelu_variants_are_distinguished_in_fp32():
+    """The two GELUs differ by up to 4.7e-4, above the fp32 tolerance: a swapped variant fails."""
+    prob = inputs.random_problem(5, 64, 128, 64, F32, ["scale", "gelu_tanh"])
+    prob.epilogue[0] = ("scale", 3.0)
+    got, _ = run_gpu(prob)
+    assert_close(got, oracle_rows(prob), F32, "gelu_tanh fp32")
+    swapped = inputs.Problem("x", F32, prob.x, prob.w, prob.b, [("scale", 3.0), ("gelu_erf",)])
+    worst = np.abs(got.to(torch.float64).numpy() - oracle_rows(swapped)).max()
+    assert worst > 2e-4
+
+
+def test_256_tile_row_ops_and_ragged_edges():
+    for kinds in (["bias", "gelu_tanh", "layernorm"], ["softmax"], ["bias", "logsumexp"]):
+        prob = inputs.random_problem(8, 2100, 2312, 128, BF16, kinds)
+        announce("256-tile", kinds)
+        got, call = run_gpu(prob, "tiled256")
+        assert "tile=256x256" in call.plan()
+        rows = sample_rows(prob.M, 64)
+        assert_close(got[rows], oracle_rows(prob, rows), BF16, str(kinds))
+
+
+# ------------------------------------------------------------------ edge cases
+def test_empty_and_tiny():
+    dev = "cuda:0"
+    x = torch.zeros((0, 64), dtype=BF16, device=dev); w = torch.ones((128, 64), dtype=BF16, device=dev)
+    out = binding.fused_linear_epilogue(x, w, None, [("relu",)])
+    assert out.shape == (0, 128)
+    # K = 0: the contraction is an empty sum
+    x = torch.zeros((5, 0), dtype=F32, device=dev); w = torch.zeros((7, 0), dtype=F32, device=dev)
+    b = torch.arange(7, dtype=F32, device=dev)
+    out = binding.fused_linear_epilogue(x, w, b, [("bias",)])
+    torch.cuda.synchronize()
+    assert torch.equal(out.cpu(), torch.arange(7, dtype=F32).repeat(5, 1))
+    # one row, one column
+    prob = inputs.random_problem(2, 1, 1, 7, F32, ["bias", "gelu_erf"])
+    got, _ = run_gpu(prob)
+    assert_close(got, oracle_rows(prob), F32, "1x1")
+    # N = 1 row ops: layernorm -> beta, softmax -> 1, logsumexp -> the value itself
+    prob = inputs.random_problem(2, 9, 1, 16, F32, ["layernorm"])
+    got, _ = run_gpu(prob)
+    assert_close(got, oracle_rows(prob), F32, "ln N=1")
+    prob = inputs.random_problem(2, 9, 1, 16, F32, ["softmax"])
+    got, _ = run_gpu(prob)
+    assert torch.equal(got, torch.ones(9, 1))
+
+
+def test_strided_operands_and_in_place_residual():
+    """Leading dimensions larger than the row length, and out aliasing the residual exactly."""
+    dev = "cuda:0"
+    prob = inputs.random_problem(21, 150, 264, 128, BF16, ["bias", "residual"])
+    pad = lambda t, extra: torch.cat([t, torch.full((t.shape[0], extra), 7.0, dtype=t.dtype)], 1)
+    xs = to_dev(pad(prob.x, 64))[:, :128]
+    ws = to_dev(pad(prob.w, 8))[:, :128]
+    r = prob.epilogue[1][1]
+    rs = to_dev(pad(r, 24))[:, :264]
+    ref = oracle_rows(prob)
+    for variant in ("tiled", "general"):
+        store = torch.empty((150, 264 + 24), dtype=BF16, device=dev)
+        store[:, :264] = rs
+        out_view = store[:, :264]
+        got = binding.fused_linear_epilogue(xs, ws, to_dev(prob.b), [("bias",), ("residual", out_view)],
+                                            out=out_view, variant=variant)
+        torch.cuda.synchronize()
+        assert got.data_ptr() == store.data_ptr()
+        assert_close(got.cpu(), ref, BF16, "strided in-place " + variant)
+
+
+def test_padding_columns_of_out_are_not_written():
+    dev = "cuda:0"
+    prob = inputs.random_problem(22, 140, 136, 64, BF16, ["bias", "gelu_tanh", "layernorm"])
+    for variant in ("tiled", "general"):
+        store = torch.full((140, 136 + 40), -77.0, dtype=BF16, device=dev)
+        out_view = store[:, :136]
+        binding.fused_linear_epilogue(to_dev(prob.x), to_dev(prob.w), to_dev(prob.b), dev_epilogue(prob.epilogue),
+                                      out=out_view, variant=variant)
+        torch.cuda.synchronize()
+        assert torch.all(store[:, 136:] == -77.0)
+        assert_close(out_view.cpu(), oracle_rows(prob), BF16, "padded out " + variant)
+
+
+def test_results_are_bitwise_reproducible():
+    prob = inputs.random_problem(9, 520, 776, 256, BF16, ["bias", "gelu_erf", "layernorm"])
+    call = make_call(prob)
+    first = call.run().clone()
+    for _ in range(5):
+        again = call.run()
+        torch.cuda.synchronize()
+        assert torch.equal(first, again)
+
+
+def test_workspace_too_small_is_refused():
+    prob = inputs.random_problem(9, 128, 256, 64, BF16, ["softmax"])
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    call = make_call(prob, workspace=small)
+    with pytest.raises(binding.FleError) as e:
+        call.run()
+    assert e.value.status == 6
+
+
+def test_structural_invariants_on_gpu():
+    """Row permutation and M-splitting commute with the op (tile mapping cannot leak between rows)."""
+    prob = inputs.random_problem(31, 300, 264, 128, BF16, ["bias", "gelu_tanh", "residual", "layernorm"])
+    base, _ = run_gpu(prob)
+    perm = torch.randperm(300, generator=torch.Generator().manual_seed(1))
+    ep = list(prob.epilogue); ep[2] = ("residual", prob.epilogue[2][1][perm])
+    p2 = inputs.Problem("perm", BF16, prob.x[perm], prob.w, prob.b, ep)
+    got, _ = run_gpu(p2)
+    assert torch.equal(got, base[perm])
+    ep = list(prob.epilogue); ep[2] = ("residual", prob.epilogue[2][1][:100].contiguous())
+    top, _ = run_gpu(inputs.Problem("top", BF16, prob.x[:100].contiguous(), prob.w, prob.b, ep))
+    assert torch.equal(top, base[:100])
