@@ -105,7 +105,7 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
     // ---- kernel variant
     bool res_ok = true, post_res_alias_out = false;
     for (int i = 0; i < e.n_pre; ++i)
-        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, 8) && e.pre[i].ld % 4 == 0)) res_ok = false;
+        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, 8) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < (int64_t(1) << 21))) res_ok = false;
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
     const bool tiled_ok = p->dtype == FLE_BF16 && K >= 64 && K % 64 == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&

@@ -12,6 +12,8 @@
 // 8-byte vectors, and a row reduction is in-register work plus one cross-lane exchange.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fle_plan.h"
 
 namespace fle {
@@ -76,7 +78,19 @@ __device__ __forceinline__ f32x4 ld4_bf16(const void *p) {  // p is 8-byte align
 
 __device__ __forceinline__ float relu_f(float v) { return v < 0.0f ? 0.0f : v; }  // NaN stays NaN
 
-__device__ __forceinline__ float gelu_erf_f(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// GELU with the exact-erf definition.  erfc(|x|) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2),
+// t = 1 / (1 + p |x|)  (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7), and
+// 1 + erf(x) = erfc(|x|) for x < 0, 2 - erfc(|x|) otherwise: no cancellation in the left tail.
+__device__ __forceinline__ float gelu_erf_f(float v) {
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float c = p * t * __expf(-x * x);
+    return 0.5f * v * (v < 0.0f ? c : 2.0f - c);
+}
 
 // 0.5 v (1 + tanh u) == v / (1 + exp(-2u)),  u = sqrt(2/pi) (v + 0.044715 v^3)
 __device__ __forceinline__ float gelu_tanh_f(float v) {
@@ -157,12 +171,24 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
 // ------------------------------------------------------------------ tiled bf16 MFMA GEMM
 // Block tile BM x BN (rows of x, rows of W), K step 64, 4 waves as 2 x 2, each wave owning
 // (BM/2) x (BN/2) outputs as 32x32 accumulator tiles of v_mfma_f32_32x32x16_bf16.
-// Operand tiles are copied HBM -> LDS by buffer loads that write LDS directly (no registers),
-// two stages deep; a stage's row is 64 bf16 = 8 chunks of 16 bytes, stored at chunk position
-// c ^ g(row) with g(row) = (row & 7) ^ ((row >> 3) & 1), which spreads the 16-byte reads of an
-// MFMA fragment (32 consecutive rows, same logical chunk) over all LDS banks.
+//
+// Main loop.  Operand tiles go HBM -> LDS by buffer loads that write LDS directly (no
+// registers), two stages deep.  A stage row is 64 bf16 = 8 chunks of 16 bytes, stored at chunk
+// position c ^ g(row), g(row) = (row & 7) ^ ((row >> 3) & 1): the 16-byte reads of an MFMA
+// fragment (32 consecutive rows, one logical chunk) then hit every LDS bank once.  Within a
+// K step the copy instructions for the next stage and the fragment reads for the next
+// 16-wide k slice are issued one at a time between pairs of MFMAs (pinned with
+// sched_barrier): a wave issues in order, so a burst of memory instructions would otherwise
+// leave the matrix pipe idle while the LDS and texture paths accept them.
+//
+// Epilogue.  One 32-row block of the wave's accumulators at a time is staged through LDS as
+// fp32 and read back row-contiguous: a lane then owns 4 (or 2 x 4) consecutive columns of one
+// row, 16 lanes cover a whole 64-column run, so bias / residual / output accesses are full
+// cache lines and a row reduction is a 16-lane DPP reduction.  The residual tile is copied
+// into LDS by the same direct loads, the first block before the main loop starts.
 template <int ROWS>
 struct TileLoader {
+    static constexpr int NI = ROWS / 32;  // copy instructions per wave per stage (8 rows each)
     __amdgpu_buffer_rsrc_t rsrc;
     uint32_t off_even, off_odd;  // this lane's byte offset in the tile for even / odd 8-row groups
     uint32_t row_step;           // bytes between 8-row groups
@@ -179,23 +205,47 @@ struct TileLoader {
         off_odd = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ 1) << 4);
         row_step = 8 * ldb;
     }
-    // Copy this wave's quarter of the [ROWS x 64] tile at column k0 into stage memory `lds`.
+    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at column k0.
+    __device__ __forceinline__ void issue_one(char *lds, uint32_t k0, int j) const {
+        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+    }
     __device__ __forceinline__ void issue(char *lds, uint32_t k0) const {
 #pragma unroll
-        for (int j = 0; j < ROWS / 32; ++j) {
-            const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
-        }
+        for (int j = 0; j < NI; ++j) issue_one(lds, k0, j);
     }
 };
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N), other counters untouched
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// Sum / max over the 16 lanes of a DPP row by rotations; every lane ends with the result.
+template <bool MAX>
+__device__ __forceinline__ float row16_allreduce(float v) {
+#define FLE_ROR(n)                                                                                              \
+    {                                                                                                           \
+        const float o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + (n), 0xF, 0xF, false)); \
+        v = MAX ? fmaxf(v, o) : v + o;                                                                          \
+    }
+    FLE_ROR(8) FLE_ROR(4) FLE_ROR(2) FLE_ROR(1)
+#undef FLE_ROR
+    return v;
+}
+
 template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_bf16_tiled(const GemmArgs a) {
+__device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-    __shared__ __attribute__((aligned(1024))) char sW0[BN * 128];
-    __shared__ __attribute__((aligned(1024))) char sW1[BN * 128];
-    __shared__ __attribute__((aligned(1024))) char sX0[BM * 128];
-    __shared__ __attribute__((aligned(1024))) char sX1[BM * 128];
+    constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
+    constexpr int NH = WN / 64;                                    // 64-column runs per wave tile
+    constexpr int EP_STRIDE = WN * 4 + 16;                         // staged fp32 row + 16 bytes of bank skew
+    constexpr int EP_WAVE = 32 * EP_STRIDE;
+    constexpr int RES_WAVE = 32 * WN * 2;                          // one 32-row residual block per wave
+    constexpr int RES1_OFF = 4 * EP_WAVE, RES0_OFF = 2 * STAGE;
+    static_assert(RES1_OFF + 4 * RES_WAVE <= 2 * STAGE, "epilogue buffers must fit in the stage area");
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE + 4 * RES_WAVE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -217,18 +267,53 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled(const GemmArgs a) {
     }
     const int64_t m0 = int64_t(tile_m) * BM, n0 = int64_t(tile_n) * BN;
     const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m_wave = m0 + wm * WM, n_wave = n0 + wn * WN;  // origin of this wave's outputs
+
+    // ---- residual operand of the first RESIDUAL op whose rows are 16-byte aligned: copied to LDS
+    // block by block (other residual operands are read straight from memory in the epilogue)
+    int res_idx = -1;
+    bool has_bias = false;
+    for (int o = a.epi.n_pre - 1; o >= 0; --o) {
+        const DevOp &op = a.epi.pre[o];
+        if (op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
+        if (op.kind == FLE_BIAS) has_bias = true;
+    }
+    const bool wave_live = m_wave < M && n_wave < N;  // this wave owns at least one output
+    __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, 0x00020000);
+    uint32_t res_lane_off = 0, res_block_step = 0;
+    if (res_idx >= 0 && wave_live) {
+        const int64_t ld = a.epi.pre[res_idx].ld;
+        const int64_t rows = (M - m_wave) < WM ? (M - m_wave) : WM;
+        const char *base = reinterpret_cast<const char *>(a.epi.pre[res_idx].p0) + (m_wave * ld + n_wave) * 2;
+        res_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, uint32_t(((rows - 1) * ld + (N - n_wave)) * 2), 0x00020000);
+        // copy instruction t of a block covers rows 4t .. 4t+3 when WN = 128 (16 lanes x 16 bytes per row),
+        // rows 8t .. 8t+7 when WN = 64
+        constexpr int LPR = WN / 8;  // lanes per row
+        res_lane_off = uint32_t(lane / LPR) * uint32_t(ld) * 2 + uint32_t(lane % LPR) * 16;
+        res_block_step = uint32_t(64 / LPR) * uint32_t(ld) * 2;
+    }
+    auto issue_residual = [&](int block, int buf) {
+        constexpr int NI = RES_WAVE / 1024;
+        char *dst = smem + (buf ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
+        const uint32_t base = uint32_t(block) * 32 * uint32_t(a.epi.pre[res_idx].ld) * 2 + res_lane_off;
+#pragma unroll
+        for (int t = 0; t < NI; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_rsrc, (lds_void *)(dst + t * 1024), 16, base + uint32_t(t) * res_block_step, 0, 0, 0);
+    };
+    if (res_idx >= 0 && wave_live) issue_residual(0, 0);
 
     TileLoader<BM> ldx_;
     TileLoader<BN> ldw_;
     ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * 2, a.ldx, M - m0, a.K, wave, lane);
     ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2, a.ldw, N - n0, a.K, wave, lane);
+    constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
 
     // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
     uint32_t rd_off[4];
     {
-        const int g = (lane & 7) ^ ((lane >> 3) & 1), h = lane >> 5;
+        const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + h) ^ g) << 4));
+        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
     }
 
     f32x16 acc[TM][TN];
@@ -239,206 +324,236 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled(const GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    auto compute = [&](const char *sW, const char *sX) {
+    bf16x8 fw[2][TN], fx[2][TM];
+    // One K step on stage `stage`; ISSUE: also copy K step kt+1 into the other stage.
+    auto k_step = [&](int kt, auto issue_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
+        char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
+        const uint32_t ik0 = uint32_t(kt + 1) * 64;
+        wait_vmcnt<0>();                  // this wave's copies into the current stage have landed
+        __builtin_amdgcn_s_barrier();     // everyone's have, and everyone is done reading the other stage
+#pragma unroll
+        for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
+#pragma unroll
+        for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 fw[TN], fx[TM];
+            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 4, MPD = NMF / NDS;
+            const int cur = kk & 1;
 #pragma unroll
-            for (int t = 0; t < TN; ++t) fw[t] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + t * 32) * 128 + rd_off[kk]);
+            for (int g = 0; g < NDS; ++g) {
+                if (kk + 1 < 4) {  // one fragment of the next 16-wide k slice
+                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
+                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
+                }
+                if (ISSUE && g < NVM) {  // one copy instruction of the next stage
+                    const int idx = kk * NVM + g;
+                    if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                    else ldx_.issue_one(iX, ik0, idx - NIW);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < TM; ++t) fx[t] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + t * 32) * 128 + rd_off[kk]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[j], fx[i], acc[i][j], 0, 0, 0);
+                for (int q = g * MPD; q < (g + 1 == NDS ? NMF : (g + 1) * MPD); ++q)
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
 
     const int KT = int(a.K / 64);
-    ldw_.issue(sW0, 0);
-    ldx_.issue(sX0, 0);
-    for (int kt = 0; kt < KT; kt += 2) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies into stage 0 have landed
-        __syncthreads();                     // everyone's have, and everyone is done reading stage 1
-        if (kt + 1 < KT) {
-            ldw_.issue(sW1, uint32_t(kt + 1) * 64);
-            ldx_.issue(sX1, uint32_t(kt + 1) * 64);
-        }
-        compute(sW0, sX0);
-        if (kt + 1 < KT) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-            if (kt + 2 < KT) {
-                ldw_.issue(sW0, uint32_t(kt + 2) * 64);
-                ldx_.issue(sX0, uint32_t(kt + 2) * 64);
-            }
-            compute(sW1, sX1);
-        }
+    ldw_.issue(smem, 0);
+    ldx_.issue(smem + SW, 0);
+    {
+        int kt = 0;
+        for (; kt < KT - 1; ++kt) k_step(kt, std::true_type{});
+        k_step(kt, std::false_type{});
     }
+    __syncthreads();  // the stage area becomes epilogue scratch
+    if (!wave_live) return;
 
-    // ---- epilogue, all in registers.  acc[i][j][4q+e] is out[m_i][n_(j,q) + e].
-    const int h = lane >> 5;
-    const int64_t m_lane = m0 + wm * WM + (lane & 31);     // + 32 i
-    const int64_t n_lane = n0 + wn * WN + 4 * h;           // + 32 j + 8 q + e
-    const uint16_t *bias = reinterpret_cast<const uint16_t *>(a.epi.bias);
+    // ---- epilogue
+    const int rsub = lane >> 4;  // row within a group of 4 rows
+    const int cl = lane & 15;
+    char *ep = smem + wave * EP_WAVE;
+    // columns of this lane in the read-back layout: run hc covers n_wave + 64 hc + 4 cl .. + 3
+    int64_t n_col[NH];
+    bool n_ok[NH];
+    f32x4 bias_v[NH];
+#pragma unroll
+    for (int hc = 0; hc < NH; ++hc) {
+        n_col[hc] = n_wave + 64 * hc + 4 * cl;
+        n_ok[hc] = n_col[hc] < N;
+        bias_v[hc] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (has_bias) bias_v[hc] = ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + (n_ok[hc] ? n_col[hc] : N - 4));
+    }
+    const int p_idx = int(n_wave / WN);
+    const int64_t cols_left = N - n_wave;
+    const float cnt = float(cols_left < WN ? cols_left : WN);
+    constexpr int NIT = 8;  // 4 rows per iteration
 
-    for (int o = 0; o < a.epi.n_pre; ++o) {
-        const DevOp op = a.epi.pre[o];
-        switch (op.kind) {
-        case FLE_BIAS:
+#pragma unroll 1
+    for (int i = 0; i < TM; ++i) {
+        const int64_t m_blk = m_wave + 32 * i;
+        if (m_blk >= M) break;
+        if (res_idx >= 0) {
+            wait_vmcnt<0>();  // residual block i is in LDS (and this wave's earlier stores are done)
+            if (i + 1 < TM && m_blk + 32 < M) issue_residual(i + 1, (i + 1) & 1);
+        }
+        // accumulators of row block i -> LDS, row (lane & 31), columns 32 j + 8 q + 4 h .. + 3
+        {
+            char *wr = ep + (lane & 31) * EP_STRIDE + (lane >> 5) * 16;
+            auto put = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                if constexpr (I < TM) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                    for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t n = n_lane + 32 * j + 8 * q;
-                    f32x4 bv = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (n < N) bv = ld4_bf16(bias + n);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += bv[e];
+                        for (int q = 0; q < 4; ++q)
+                            *reinterpret_cast<f32x4 *>(wr + (32 * j + 8 * q) * 4) = f32x4{acc[I][j][4 * q], acc[I][j][4 * q + 1], acc[I][j][4 * q + 2], acc[I][j][4 * q + 3]};
                 }
-            break;
-        case FLE_SCALE:
+            };
+            switch (i) {
+            case 0: put(std::integral_constant<int, 0>{}); break;
+            case 1: put(std::integral_constant<int, 1>{}); break;
+            case 2: put(std::integral_constant<int, 2>{}); break;
+            default: put(std::integral_constant<int, 3>{}); break;
+            }
+        }
+        // read back row-contiguous: v[it][hc] = row 4 it + rsub, columns of run hc
+        f32x4 v[NIT][NH];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] *= op.alpha;
-            break;
-        case FLE_RELU:
+            for (int hc = 0; hc < NH; ++hc) v[it][hc] = *reinterpret_cast<const f32x4 *>(ep + (4 * it + rsub) * EP_STRIDE + hc * 256 + cl * 16);
+
+        for (int o = 0; o < a.epi.n_pre; ++o) {
+            const DevOp op = a.epi.pre[o];
+            switch (op.kind) {
+            case FLE_BIAS:
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] += bias_v[hc];
+                break;
+            case FLE_SCALE:
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = relu_f(acc[i][j][r]);
-            break;
-        case FLE_GELU_ERF:
+                for (int it = 0; it < NIT; ++it)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] *= op.alpha;
+                break;
+            case FLE_RELU:
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_erf_f(acc[i][j][r]);
-            break;
-        case FLE_GELU_TANH:
+                    for (int hc = 0; hc < NH; ++hc)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = relu_f(v[it][hc][e]);
+                break;
+            case FLE_GELU_ERF:
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = gelu_tanh_f(acc[i][j][r]);
-            break;
-        case FLE_RESIDUAL: {
-            const uint16_t *res = reinterpret_cast<const uint16_t *>(op.p0);
+                    for (int hc = 0; hc < NH; ++hc)
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int64_t m = m_lane + 32 * i;
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_erf_f(v[it][hc][e]);
+                break;
+            case FLE_GELU_TANH:
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int64_t n = n_lane + 32 * j + 8 * q;
-                        if (m < M && n < N) {
-                            const f32x4 rv = ld4_bf16(res + m * op.ld + n);
+                    for (int hc = 0; hc < NH; ++hc)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += rv[e];
-                        }
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_tanh_f(v[it][hc][e]);
+                break;
+            case FLE_RESIDUAL:
+                if (o == res_idx) {  // staged in LDS: [32 rows][WN] bf16
+                    const char *rb = smem + ((i & 1) ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4_bf16(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8);
+                } else {  // a further residual operand: straight from memory, clamped to stay in bounds
+                    const uint16_t *res = reinterpret_cast<const uint16_t *>(op.p0);
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int64_t m = m_blk + 4 * it + rsub;
+                        const int64_t mc = m < M ? m : M - 1;
+#pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4_bf16(res + mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
                     }
+                }
+                break;
+            default: break;
             }
-            break;
         }
-        default: break;
-        }
-    }
 
-    // ---- row-reduction partials over this wave's WN columns, from the unrounded fp32 values
-    if (a.epi.row_kind >= 0) {
-        const int p = int((n0 + wn * WN) / WN);
-        const bool ln = a.epi.row_kind == FLE_LAYERNORM;
-        const int64_t cols_left = N - (n0 + wn * WN);
-        const float cnt = float(cols_left < WN ? (cols_left > 0 ? cols_left : 0) : WN);
+        // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
+        if (a.epi.row_kind >= 0) {
+            const bool ln = a.epi.row_kind == FLE_LAYERNORM;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t m = m_lane + 32 * i;
-            float s0, s1;
-            if (ln) {
-                float sum = 0.0f;
+            for (int it = 0; it < NIT; ++it) {
+                const int64_t m = m_blk + 4 * it + rsub;
+                float s0, s1;
+                if (ln) {
+                    float sum = 0.0f;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc]) sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                    sum = row16_allreduce<false>(sum);
+                    const float mean = sum / cnt;
+                    float m2 = 0.0f;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (n_lane + 32 * j + 8 * q < N)
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc])
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) sum += acc[i][j][4 * q + e];
-                sum += __shfl_xor(sum, 32);
-                const float mean = cnt > 0.0f ? sum / cnt : 0.0f;
-                float m2 = 0.0f;
+                            for (int e = 0; e < 4; ++e) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
+                    m2 = row16_allreduce<false>(m2);
+                    s0 = mean;
+                    s1 = m2;
+                } else {
+                    float mx = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc]) mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
+                    mx = row16_allreduce<true>(mx);
+                    float se = 0.0f;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (n_lane + 32 * j + 8 * q < N)
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc])
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float d = acc[i][j][4 * q + e] - mean;
-                                m2 += d * d;
-                            }
-                m2 += __shfl_xor(m2, 32);
-                s0 = mean;
-                s1 = m2;
-            } else {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (n_lane + 32 * j + 8 * q < N)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[i][j][4 * q + e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                float se = 0.0f;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        if (n_lane + 32 * j + 8 * q < N)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) se += __expf(acc[i][j][4 * q + e] - mx);
-                se += __shfl_xor(se, 32);
-                s0 = mx;
-                s1 = se;
-            }
-            if (h == 0 && m < M && cols_left > 0) {
-                float2 *dstp = reinterpret_cast<float2 *>(a.partials + (m * a.np + p) * 2);
-                *dstp = make_float2(s0, s1);
+                            for (int e = 0; e < 4; ++e) se += __expf(v[it][hc][e] - mx);
+                    se = row16_allreduce<false>(se);
+                    s0 = mx;
+                    s1 = se;
+                }
+                if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
             }
         }
-    }
 
-    // ---- store: final values (no row op) or staged values for the finalize pass
-    if (a.dst) {
+        // store: final values (no row op) or staged values for the finalize pass
+        if (a.dst) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t m = m_lane + 32 * i;
+            for (int it = 0; it < NIT; ++it) {
+                const int64_t m = m_blk + 4 * it + rsub;
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t n = n_lane + 32 * j + 8 * q;
-                    if (m < M && n < N) {
-                        f32x4 v;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+                for (int hc = 0; hc < NH; ++hc)
+                    if (m < M && n_ok[hc]) {
                         if (a.dst_f32)
-                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + m * a.ldd + n) = v;
+                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + m * a.ldd + n_col[hc]) = v[it][hc];
                         else
-                            *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + m * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+                            *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + m * a.ldd + n_col[hc]) = __builtin_convertvector(v[it][hc], bf16x4);
                     }
-                }
+            }
         }
     }
 }
+
+// 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).
+__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_bf16_tiled_body<256, 256>(a); }
+// 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_bf16_tiled_body<128, 128>(a); }
 
 // ------------------------------------------------------------------ general GEMM (fp32 MFMA)
 // Block tile 32 x 32 outputs; the 4 waves split K (wave w takes 16-wide k blocks w, w+4, ...),
@@ -680,8 +795,8 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
 
     const uint32_t grid = uint32_t(plan.tiles_m * plan.tiles_n);
     if (plan.variant == V_TILED) {
-        if (plan.bm == 256) hipLaunchKernelGGL((gemm_bf16_tiled<256, 256>), dim3(grid), dim3(256), 0, stream, g);
-        else hipLaunchKernelGGL((gemm_bf16_tiled<128, 128>), dim3(grid), dim3(256), 0, stream, g);
+        if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, dim3(grid), dim3(256), 0, stream, g);
+        else hipLaunchKernelGGL(gemm_bf16_tiled_128, dim3(grid), dim3(256), 0, stream, g);
     } else {
         // vector loads need 4-element groups that never straddle K and rows that keep the alignment
         const size_t va = bf16 ? 8 : 16;
