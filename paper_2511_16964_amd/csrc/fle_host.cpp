@@ -116,12 +116,20 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
         forced_tile = variant == V_TILED_256 ? 256 : 128;
         variant = V_TILED;
     }
-    if (variant == V_AUTO) variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
-    if (variant == V_SKINNY) return fail(FLE_ERR_UNSUPPORTED, "the skinny variant is not available for this problem");
+    const bool skinny_ok = tiled_ok && M <= 64;
+    if (variant == V_AUTO) {
+        if (skinny_ok && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
+        else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
+    }
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs M <= 64 and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 64 == 0, N %% 4 == 0 and 16-byte aligned operands");
-    if (variant != V_TILED && variant != V_GENERAL) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
+    if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
-    if (variant == V_TILED) {
+    if (variant == V_SKINNY) {
+        plan->bm = M <= 32 ? 32 : 64;
+        plan->bn = 128;
+        plan->part_cols = 32;  // one partial per wave tile
+    } else if (variant == V_TILED) {
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
         const bool big = M > 128 && N > 128 && t256 >= 128;
         plan->bm = plan->bn = forced_tile ? forced_tile : big ? 256 : 128;
@@ -152,7 +160,7 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
     }
     plan->ws_total = M > 0 ? off : 0;
     snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld row_op=%d np=%d staging=%s workspace=%zu",
-             variant == V_TILED ? "tiled_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, variant == V_TILED ? 64 : 16, (long long)plan->tiles_m,
+             variant == V_TILED ? "tiled_bf16_mfma" : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, variant == V_GENERAL ? 16 : 64, (long long)plan->tiles_m,
              (long long)plan->tiles_n, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
     return FLE_OK;
 }

@@ -190,7 +190,7 @@ template <int ROWS>
 struct TileLoader {
     static constexpr int NI = ROWS / 32;  // copy instructions per wave per stage (8 rows each)
     __amdgpu_buffer_rsrc_t rsrc;
-    uint32_t off_even, off_odd;  // this lane's byte offset in the tile for even / odd 8-row groups
+    uint32_t off_even, off_odd;  // this lane's byte offset in the tile for its even / odd 8-row groups
     uint32_t row_step;           // bytes between 8-row groups
     int wave;
 
@@ -201,8 +201,9 @@ struct TileLoader {
         const int lr = lane >> 3, lp = lane & 7;
         const uint32_t ldb = uint32_t(ld) * 2;
         wave = wave_;
-        off_even = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr) << 4);
-        off_odd = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ 1) << 4);
+        const int p0 = (wave_ * (ROWS / 4) / 8) & 1;  // parity of this wave's first 8-row group
+        off_even = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0) << 4);
+        off_odd = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0 ^ 1) << 4);
         row_step = 8 * ldb;
     }
     // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at column k0.
@@ -555,6 +556,202 @@ __global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { g
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_bf16_tiled_body<128, 128>(a); }
 
+
+// ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
+// HBM-bound: W streams through once and the matrix pipe is nearly idle, so the design goal is
+// bytes in flight.  One workgroup owns 128 rows of W (columns of out) and all of K; each of its
+// 4 waves copies and consumes its own 32 W rows, the small x tile is shared.  The LDS ring is
+// NST stages of (128 + 32 TMB) x 64 bf16, NST-1 of them in flight (about 100 KB of W per CU,
+// what 8 TB/s x ~2 us of latency / 256 CUs asks for).  Same swizzle and orientation as the
+// tiled kernel; the wave tile is 32 TMB x 32, so the epilogue stays in the MFMA register layout.
+template <int TMB>
+__device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
+    constexpr int BM = 32 * TMB, BN = 128;
+    constexpr int NST = TMB == 1 ? 7 : 6;
+    constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;
+    __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t M = a.M, N = a.N;
+    const int64_t n0 = int64_t(blockIdx.x) * BN;
+
+    TileLoader<BM> ldx_;
+    TileLoader<BN> ldw_;
+    ldx_.init(a.x, a.ldx, M, a.K, wave, lane);
+    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2, a.ldw, N - n0, a.K, wave, lane);
+    constexpr int LPS = TileLoader<BN>::NI + TileLoader<BM>::NI;  // copy instructions per wave per stage
+
+    uint32_t rd_off[4];
+    {
+        const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
+    }
+    f32x16 acc[TMB];
+#pragma unroll
+    for (int t = 0; t < TMB; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    const int KT = int(a.K / 64);
+    auto issue = [&](int kt) {
+        char *base = smem + (kt % NST) * STAGE;
+        ldw_.issue(base, uint32_t(kt) * 64);
+        ldx_.issue(base + SW, uint32_t(kt) * 64);
+    };
+    auto compute = [&](int kt) {
+        const char *sW = smem + (kt % NST) * STAGE + wave * 32 * 128, *sX = smem + (kt % NST) * STAGE + SW;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 fw = *reinterpret_cast<const bf16x8 *>(sW + rd_off[kk]);
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) {
+                const bf16x8 fx = *reinterpret_cast<const bf16x8 *>(sX + t * 32 * 128 + rd_off[kk]);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
+            }
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < KT) issue(s);
+    int kt = 0;
+    for (; kt + NST - 1 < KT; ++kt) {
+        wait_vmcnt<(NST - 2) * LPS>();  // the newest NST-2 stages may still be in flight
+        __builtin_amdgcn_s_barrier();    // stage kt is complete; stage kt-1 is no longer read
+        issue(kt + NST - 1);
+        compute(kt);
+    }
+    for (; kt < KT; ++kt) {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        compute(kt);
+    }
+
+    // ---- epilogue in the MFMA layout: acc[t][4q+e] = out[32 t + (lane & 31)][n_lane + 8 q + e]
+    const int h = lane >> 5;
+    const int64_t n_lane = n0 + wave * 32 + 4 * h;
+    if (n0 + wave * 32 >= N) return;
+    int64_t n_c[4];  // clamped column of each group of four (loads stay in bounds; stores are masked)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) n_c[q] = n_lane + 8 * q < N ? n_lane + 8 * q : N - 4;
+    for (int o = 0; o < a.epi.n_pre; ++o) {
+        const DevOp op = a.epi.pre[o];
+        switch (op.kind) {
+        case FLE_BIAS:
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bv = ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + n_c[q]);
+#pragma unroll
+                for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[t][4 * q + e] += bv[e];
+            }
+            break;
+        case FLE_SCALE:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) acc[t] *= op.alpha;
+            break;
+        case FLE_RELU:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = relu_f(acc[t][r]);
+            break;
+        case FLE_GELU_ERF:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = gelu_erf_f(acc[t][r]);
+            break;
+        case FLE_GELU_TANH:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = gelu_tanh_f(acc[t][r]);
+            break;
+        case FLE_RESIDUAL:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) {
+                const int64_t m = 32 * t + (lane & 31), mc = m < M ? m : M - 1;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 rv = ld4_bf16(reinterpret_cast<const uint16_t *>(op.p0) + mc * op.ld + n_c[q]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[t][4 * q + e] += rv[e];
+                }
+            }
+            break;
+        default: break;
+        }
+    }
+    if (a.epi.row_kind >= 0) {  // one partial per (row, 32-column wave tile)
+        const int64_t left = N - (n0 + wave * 32);
+        const float cnt = float(left < 32 ? left : 32);
+        const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+#pragma unroll
+        for (int t = 0; t < TMB; ++t) {
+            const int64_t m = 32 * t + (lane & 31);
+            float s0, s1;
+            if (ln) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) sum += acc[t][4 * q + e];
+                sum += __shfl_xor(sum, 32);
+                const float mean = sum / cnt;
+                float m2 = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) m2 += (acc[t][4 * q + e] - mean) * (acc[t][4 * q + e] - mean);
+                m2 += __shfl_xor(m2, 32);
+                s0 = mean;
+                s1 = m2;
+            } else {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[t][4 * q + e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                float se = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) se += __expf(acc[t][4 * q + e] - mx);
+                se += __shfl_xor(se, 32);
+                s0 = mx;
+                s1 = se;
+            }
+            if (h == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + (n0 + wave * 32) / 32) * 2) = make_float2(s0, s1);
+        }
+    }
+    if (a.dst) {
+#pragma unroll
+        for (int t = 0; t < TMB; ++t) {
+            const int64_t m = 32 * t + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t n = n_lane + 8 * q;
+                if (m < M && n < N) {
+                    const f32x4 v = f32x4{acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+                    if (a.dst_f32)
+                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + m * a.ldd + n) = v;
+                    else
+                        *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + m * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+                }
+            }
+        }
+    }
+}
+__global__ __launch_bounds__(256) void gemm_bf16_skinny_32(const GemmArgs a) { gemm_bf16_skinny_body<1>(a); }
+__global__ __launch_bounds__(256) void gemm_bf16_skinny_64(const GemmArgs a) { gemm_bf16_skinny_body<2>(a); }
+
 // ------------------------------------------------------------------ general GEMM (fp32 MFMA)
 // Block tile 32 x 32 outputs; the 4 waves split K (wave w takes 16-wide k blocks w, w+4, ...),
 // each computing the whole tile with v_mfma_f32_16x16x4_f32 (bf16 inputs are widened exactly),
@@ -794,7 +991,10 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     else { g.dst = nullptr; g.ldd = 0; g.dst_f32 = 0; }
 
     const uint32_t grid = uint32_t(plan.tiles_m * plan.tiles_n);
-    if (plan.variant == V_TILED) {
+    if (plan.variant == V_SKINNY) {
+        if (plan.bm == 32) hipLaunchKernelGGL(gemm_bf16_skinny_32, dim3(grid), dim3(256), 0, stream, g);
+        else hipLaunchKernelGGL(gemm_bf16_skinny_64, dim3(grid), dim3(256), 0, stream, g);
+    } else if (plan.variant == V_TILED) {
         if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, dim3(grid), dim3(256), 0, stream, g);
         else hipLaunchKernelGGL(gemm_bf16_tiled_128, dim3(grid), dim3(256), 0, stream, g);
     } else {
