@@ -880,19 +880,45 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 }
 
 // ------------------------------------------------------------------ finalize passes
-// One workgroup per (row, 4096-column chunk).  Every wave combines the row's partials itself
-// (a handful of values, identical result in every lane), then the chunk is streamed once:
-// read staged y, normalise, apply the trailing elementwise ops, round, write.
+// One wave per (row, 2048-column chunk).  The wave combines the row's partials itself (one
+// per lane, then a fixed butterfly: identical result in every lane), issues all of its
+// 16-byte loads of staged y at once, normalises, applies the trailing elementwise ops, rounds
+// and writes 16-byte vectors.
+__device__ __forceinline__ void ld8(const void *p, int64_t i, bool f32, float (&v)[8]) {  // 8 elements at index i
+    if (f32) {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+        const f32x4 u0 = src[0], u1 = src[1];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[e] = u0[e]; v[4 + e] = u1[e]; }
+    } else {
+        const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(p) + i);
+        const uint32_t wv[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(wv[e] << 16); v[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u); }
+    }
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
+    constexpr int CH = 2048, IT = CH / 512;
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int dtype = a.epi.dtype;
+    const bool f32 = dtype == FLE_F32;
     const bool ln = a.epi.row_kind == FLE_LAYERNORM;
     const int64_t N = a.N;
-    constexpr int CHUNK = 4096;
-    const int64_t c0 = int64_t(blockIdx.x) * CHUNK;
-    const int64_t c1 = c0 + CHUNK < N ? c0 + CHUNK : N;
-    for (int64_t row = blockIdx.y; row < a.M; row += gridDim.y) {
+    const int64_t chunks = (N + CH - 1) / CH, items = a.M * chunks;
+    for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
+        const int64_t row = item / chunks, c0 = (item % chunks) * CH;
+        const int64_t c1 = c0 + CH < N ? c0 + CH : N;
+        float y[IT][8];
+        if (VEC) {  // issue the loads before the partials are combined
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int64_t n = c0 + it * 512 + lane * 8;
+                if (n < c1) ld8(a.y, row * a.ldy + n, a.y_f32 || f32, y[it]);
+            }
+        }
         float sub, mul;  // out = (y - sub) * mul  (LayerNorm),  exp(y - sub) * mul  (softmax)
         if (ln) {
             const Stat s = reduce_partials<true>(a.partials, row, a.np, a.part_cols, N, lane);
@@ -903,54 +929,56 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
             sub = s.a;
             mul = 1.0f / s.b;
         }
-        auto finish = [&](float y, int64_t n) -> float {
-            float v;
-            if (ln) {
-                v = (y - sub) * mul;
-                if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
-                if (a.epi.row.p1) v += ld_elem(a.epi.row.p1, n, dtype);
-            } else {
-                v = __expf(y - sub) * mul;
-            }
+        auto post = [&](float v, int64_t n) -> float {
             for (int o = 0; o < a.epi.n_post; ++o) v = apply_op(a.epi.post[o], v, row, n, a.epi.bias, dtype);
             return v;
         };
         if (VEC) {
-            for (int64_t n = c0 + int64_t(threadIdx.x) * 8; n < c1; n += 256 * 8) {
-                float y[8];
-                if (a.y_f32) {
-                    const f32x4 *src = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(a.y) + row * a.ldy + n);
-                    const f32x4 u0 = src[0], u1 = src[1];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { y[e] = u0[e]; y[4 + e] = u1[e]; }
-                } else if (dtype == FLE_BF16) {
-                    const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(a.y) + row * a.ldy + n);
-                    const uint32_t wv[4] = {u.x, u.y, u.z, u.w};
+            for (int it = 0; it < IT; ++it) {
+                const int64_t n = c0 + it * 512 + lane * 8;
+                if (n < c1) {
+                    float *v = y[it];
+                    if (ln) {
+                        float g[8], be[8];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { y[2 * e] = __uint_as_float(wv[e] << 16); y[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u); }
-                } else {
-                    const f32x4 *src = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(a.y) + row * a.ldy + n);
-                    const f32x4 u0 = src[0], u1 = src[1];
+                        for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; }
+                        if (a.epi.row.p0) ld8(a.epi.row.p0, n, f32, g);
+                        if (a.epi.row.p1) ld8(a.epi.row.p1, n, f32, be);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { y[e] = u0[e]; y[4 + e] = u1[e]; }
-                }
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] - sub) * mul * g[e] + be[e];
+                    } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = finish(y[e], n + e);
-                if (dtype == FLE_BF16) {
-                    bf16x8 o;
+                        for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - sub) * mul;
+                    }
+                    if (a.epi.n_post > 0) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(y[e]);
-                    *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.out) + row * a.ldo + n) = o;
-                } else {
-                    f32x4 *dstp = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + row * a.ldo + n);
-                    dstp[0] = f32x4{y[0], y[1], y[2], y[3]};
-                    dstp[1] = f32x4{y[4], y[5], y[6], y[7]};
+                        for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
+                    }
+                    if (f32) {
+                        f32x4 *dstp = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + row * a.ldo + n);
+                        dstp[0] = f32x4{v[0], v[1], v[2], v[3]};
+                        dstp[1] = f32x4{v[4], v[5], v[6], v[7]};
+                    } else {
+                        bf16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.out) + row * a.ldo + n) = o;
+                    }
                 }
             }
         } else {
-            for (int64_t n = c0 + threadIdx.x; n < c1; n += 256) {
-                const float y = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
-                st_elem(a.out, row * a.ldo + n, dtype, finish(y, n));
+            for (int64_t n = c0 + lane; n < c1; n += 64) {
+                const float yv = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
+                float v;
+                if (ln) {
+                    v = (yv - sub) * mul;
+                    if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
+                    if (a.epi.row.p1) v += ld_elem(a.epi.row.p1, n, dtype);
+                } else {
+                    v = __expf(yv - sub) * mul;
+                }
+                st_elem(a.out, row * a.ldo + n, dtype, post(v, n));
             }
         }
     }
@@ -1027,8 +1055,12 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     const size_t ysz = f.y_f32 ? 4 : es;
     const bool vec = p->N % 8 == 0 && f.ldy % 8 == 0 && p->ldo % 8 == 0 && reinterpret_cast<uintptr_t>(f.y) % (8 * ysz) == 0 &&
                      reinterpret_cast<uintptr_t>(p->out) % (8 * es) == 0;
-    const dim3 fgrid(uint32_t((p->N + 4095) / 4096), uint32_t(p->M < 65535 ? p->M : 65535));
-    if (vec) hipLaunchKernelGGL(finalize_rows<true>, fgrid, dim3(256), 0, stream, f);
+    // vector path also needs 16-byte aligned gamma / beta
+    const bool gb_ok = reinterpret_cast<uintptr_t>(e.row.p0) % (8 * es) == 0 && reinterpret_cast<uintptr_t>(e.row.p1) % (8 * es) == 0;
+    const int64_t items = p->M * ((p->N + 2047) / 2048);
+    const int64_t want = (items + 3) / 4;
+    const dim3 fgrid(uint32_t(want < (int64_t(1) << 20) ? want : (int64_t(1) << 20)));
+    if (vec && gb_ok) hipLaunchKernelGGL(finalize_rows<true>, fgrid, dim3(256), 0, stream, f);
     else hipLaunchKernelGGL(finalize_rows<false>, fgrid, dim3(256), 0, stream, f);
     return check_launch("row finalize launch");
 }
