@@ -132,7 +132,8 @@ fle_status fle_last_plan(char *buf, size_t n);
 
 /* Force a kernel variant for the calling thread's next calls, for tests and tuning:
  * 0 = automatic, 1 = general kernel, 2 = tiled bf16 MFMA kernel (automatic tile), 3 = skinny
- * kernel, 4 = tiled with the 256x256 tile, 5 = tiled with the 128x128 tile.
+ * kernel, 4 = tiled with the 256x256 tile, 5 = tiled with the 128x128 tile, 6 / 7 = skinny
+ * kernel with a K step of 128 / 256 instead of 64.
  * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run. */
 void fle_force_variant(int variant);
 

@@ -564,53 +564,70 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) 
 // NST stages of (128 + 32 TMB) x 64 bf16, NST-1 of them in flight (about 100 KB of W per CU,
 // what 8 TB/s x ~2 us of latency / 256 CUs asks for).  Same swizzle and orientation as the
 // tiled kernel; the wave tile is 32 TMB x 32, so the epilogue stays in the MFMA register layout.
-template <int TMB>
+template <int TMB, int BK>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     constexpr int BM = 32 * TMB, BN = 128;
-    constexpr int NST = TMB == 1 ? 7 : 6;
-    constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;
+    constexpr int RB = BK * 2;                 // bytes per staged row
+    constexpr int CPR = BK / 8, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
+    constexpr int KPS = BK / 16;               // 16-wide k slices per stage
+    constexpr int SW = BN * RB, SX = BM * RB, STAGE = SW + SX;
+    constexpr int NST = (160 * 1024) / STAGE < 8 ? (160 * 1024) / STAGE : 8;
+    constexpr int NIW = 32 / RPI, NIX = (8 * TMB) / RPI, LPS = NIW + NIX;  // copy instructions per wave per stage
+    static_assert(NST >= 2 && NIX >= 1 && (NST - 2) * LPS < 64, "ring does not fit the counters");
     __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t M = a.M, N = a.N;
     const int64_t n0 = int64_t(blockIdx.x) * BN;
 
-    TileLoader<BM> ldx_;
-    TileLoader<BN> ldw_;
-    ldx_.init(a.x, a.ldx, M, a.K, wave, lane);
-    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2, a.ldw, N - n0, a.K, wave, lane);
-    constexpr int LPS = TileLoader<BN>::NI + TileLoader<BM>::NI;  // copy instructions per wave per stage
-
-    uint32_t rd_off[4];
+    // Chunk c of a row is stored at position c ^ sw(row): every 16-lane group of a fragment read
+    // (16 consecutive rows, one logical chunk) then covers 16 different 16-byte bank groups.
+    auto sw = [](int row) { return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); };
+    const int lr = lane / CPR, lp = lane % CPR;
+    __amdgpu_buffer_rsrc_t rw, rx;
     {
-        const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
+        const int64_t wrows = (N - n0) < BN ? (N - n0) : BN, xrows = M < BM ? M : BM;
+        rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2), 0,
+                                               uint32_t(((wrows - 1) * a.ldw + a.K) * 2), 0x00020000);
+        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, uint32_t(((xrows - 1) * a.ldx + a.K) * 2), 0x00020000);
     }
+    const uint32_t ldwb = uint32_t(a.ldw) * 2, ldxb = uint32_t(a.ldx) * 2;
+    auto issue = [&](int kt) {
+        char *base = smem + (kt % NST) * STAGE;
+        const uint32_t kb = uint32_t(kt) * RB;
+#pragma unroll
+        for (int j = 0; j < NIW; ++j) {  // this wave's own 32 rows of W
+            const int row = j * RPI + lr;
+            const uint32_t voff = uint32_t(wave * 32 + row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NIX; ++j) {  // a quarter of the shared x tile
+            const int row = wave * (8 * TMB) + j * RPI + lr;
+            const uint32_t voff = uint32_t(row) * ldxb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(base + SW + (wave * (8 * TMB) + j * RPI) * RB), 16, voff, 0, 0, 0);
+        }
+    };
+    const int fr = lane & 31, fh = lane >> 5, fs = sw(fr);
     f32x16 acc[TMB];
 #pragma unroll
     for (int t = 0; t < TMB; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-
-    const int KT = int(a.K / 64);
-    auto issue = [&](int kt) {
-        char *base = smem + (kt % NST) * STAGE;
-        ldw_.issue(base, uint32_t(kt) * 64);
-        ldx_.issue(base + SW, uint32_t(kt) * 64);
-    };
     auto compute = [&](int kt) {
-        const char *sW = smem + (kt % NST) * STAGE + wave * 32 * 128, *sX = smem + (kt % NST) * STAGE + SW;
+        const char *sW = smem + (kt % NST) * STAGE + wave * 32 * RB + fr * RB, *sX = smem + (kt % NST) * STAGE + SW + fr * RB;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 fw = *reinterpret_cast<const bf16x8 *>(sW + rd_off[kk]);
+        for (int kk = 0; kk < KPS; ++kk) {
+            const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
+            const bf16x8 fw = *reinterpret_cast<const bf16x8 *>(sW + off);
 #pragma unroll
             for (int t = 0; t < TMB; ++t) {
-                const bf16x8 fx = *reinterpret_cast<const bf16x8 *>(sX + t * 32 * 128 + rd_off[kk]);
+                const bf16x8 fx = *reinterpret_cast<const bf16x8 *>(sX + t * 32 * RB + off);
                 acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
             }
         }
     };
+    const int KT = int(a.K / BK);
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < KT) issue(s);
@@ -749,8 +766,8 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         }
     }
 }
-__global__ __launch_bounds__(256) void gemm_bf16_skinny_32(const GemmArgs a) { gemm_bf16_skinny_body<1>(a); }
-__global__ __launch_bounds__(256) void gemm_bf16_skinny_64(const GemmArgs a) { gemm_bf16_skinny_body<2>(a); }
+template <int TMB, int BK>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK>(a); }
 
 // ------------------------------------------------------------------ general GEMM (fp32 MFMA)
 // Block tile 32 x 32 outputs; the 4 waves split K (wave w takes 16-wide k blocks w, w+4, ...),
@@ -1020,8 +1037,14 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
 
     const uint32_t grid = uint32_t(plan.tiles_m * plan.tiles_n);
     if (plan.variant == V_SKINNY) {
-        if (plan.bm == 32) hipLaunchKernelGGL(gemm_bf16_skinny_32, dim3(grid), dim3(256), 0, stream, g);
-        else hipLaunchKernelGGL(gemm_bf16_skinny_64, dim3(grid), dim3(256), 0, stream, g);
+        if (plan.bm == 32) {
+            if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), dim3(grid), dim3(256), 0, stream, g);
+            else if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<1, 128>), dim3(grid), dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_bf16_skinny<1, 64>), dim3(grid), dim3(256), 0, stream, g);
+        } else {
+            if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), dim3(grid), dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), dim3(grid), dim3(256), 0, stream, g);
+        }
     } else if (plan.variant == V_TILED) {
         if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, dim3(grid), dim3(256), 0, stream, g);
         else hipLaunchKernelGGL(gemm_bf16_tiled_128, dim3(grid), dim3(256), 0, stream, g);

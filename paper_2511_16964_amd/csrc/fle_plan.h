@@ -29,7 +29,7 @@ struct DevEpilogue {
     DevOp post[FLE_MAX_OPS];
 };
 
-enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5 };
+enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5, V_SKINNY_128 = 6, V_SKINNY_256 = 7 };
 
 // Where the GEMM pass writes its (pre-row-op) values.
 enum Staging {
@@ -40,7 +40,7 @@ enum Staging {
 
 struct Plan {
     int32_t variant;
-    int32_t bm, bn;          // block tile: rows of x, rows of W
+    int32_t bm, bn, bk;      // block tile: rows of x, rows of W, K step
     int32_t part_cols;       // columns covered by one row-reduction partial
     int32_t np;              // partials per row = ceil(N / part_cols)
     int32_t staging;
