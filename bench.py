@@ -23,6 +23,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/CU/clk
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+# Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
+# measured for the kernel as it stands.
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.4e6 + 69.2e6, "c4": 541.2e6 + 4.5e6, "c1": None, "c5": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -98,6 +102,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy a few times (known traffic, to scale FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding): use --gpus 1")
@@ -185,11 +191,11 @@ def main():
     hbm_bound = args.workload == "c4"
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": None}
+        out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES[args.workload]}
     else:
         peak = PEAK_BF16_TFLOPS if prob0.dtype == torch.bfloat16 else PEAK_F32_TFLOPS
         a = flops / (ev_ms * 1e-3) / 1e12
-        out["roofline"] = {"bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak, "traffic": None}
+        out["roofline"] = {"bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak, "traffic": TRAFFIC_BYTES[args.workload]}
     out["roofline"]["kernel"] = "all kernels of one step (event time over the timed region / steps)"
     out["algorithmic_bytes"] = alg_bytes
 
@@ -200,6 +206,13 @@ def main():
                         "bare_matmul_first_call_tflops": probs[0].flops / (mm_wall * 1e-3) / 1e12}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
+    if args.calibrate_copy:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration"] = "3 device copies of 536870912 bytes (read 512 MiB, write 512 MiB each)"
     out["paper_context"] = "PIKE-B geomean 2.88x vs PyTorch eager, 1.85x vs torch.compile, KernelBench L3-pike on one H100 (other hardware, other workload)"
     print(json.dumps(out))
 

@@ -177,9 +177,10 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
 // position c ^ g(row), g(row) = (row & 7) ^ ((row >> 3) & 1): the 16-byte reads of an MFMA
 // fragment (32 consecutive rows, one logical chunk) then hit every LDS bank once.  Within a
 // K step the copy instructions for the next stage and the fragment reads for the next
-// 16-wide k slice are issued one at a time between pairs of MFMAs (pinned with
+// 16-wide k slice are issued one at a time in the gaps between MFMAs (pinned with
 // sched_barrier): a wave issues in order, so a burst of memory instructions would otherwise
-// leave the matrix pipe idle while the LDS and texture paths accept them.
+// leave the matrix pipe idle while the LDS and texture paths accept them.  The copies all go
+// out in the first half of the K step, which gives them most of a K step to land.
 //
 // Epilogue.  One 32-row block of the wave's accumulators at a time is staged through LDS as
 // fp32 and read back row-contiguous: a lane then owns 4 (or 2 x 4) consecutive columns of one
@@ -341,23 +342,25 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 4, MPD = NMF / NDS;
+            // 16-wide k slice kk: NMF MFMAs; in the issue slot before MFMA q goes at most one
+            // fragment read of slice kk+1 and (first two slices only) one copy instruction.
+            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
+            constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
             const int cur = kk & 1;
 #pragma unroll
-            for (int g = 0; g < NDS; ++g) {
-                if (kk + 1 < 4) {  // one fragment of the next 16-wide k slice
+            for (int q = 0; q < NMF; ++q) {
+                if (kk + 1 < 4 && q % QD == 0) {
+                    const int g = q / QD;
                     if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
                     else fx[cur ^ 1][g - TN] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
                 }
-                if (ISSUE && g < NVM) {  // one copy instruction of the next stage
-                    const int idx = kk * NVM + g;
+                if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
+                    const int idx = kk * NVM + q / QV;
                     if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
                     else ldx_.issue_one(iX, ik0, idx - NIW);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int q = g * MPD; q < (g + 1 == NDS ? NMF : (g + 1) * MPD); ++q)
-                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
