@@ -104,7 +104,7 @@ typedef struct {
  *
  * Alignment rule: no alignment is required for correctness.  The MFMA fast paths are taken
  * when x, W, out and residual pointers are 16-byte aligned, their row strides are multiples
- * of 16 bytes and (bf16) K % 8 == 0; other problems run on a slower general kernel.
+ * of 16 bytes, N % 4 == 0 and (bf16) K % 8 == 0; other problems run on a slower general kernel.
  * `out` may alias a residual operand only exactly (same pointer and stride); it must not
  * overlap x, W, b, gamma, beta or the workspace.
  */

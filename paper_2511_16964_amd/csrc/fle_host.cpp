@@ -108,7 +108,7 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
         if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, 8) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < (int64_t(1) << 21))) res_ok = false;
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
-    const bool tiled_ok = p->dtype == FLE_BF16 && K >= 64 && K % 64 == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
+    const bool tiled_ok = p->dtype == FLE_BF16 && K >= 8 && K % 8 == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
                           p->ldx % 8 == 0 && p->ldw % 8 == 0 && aligned(p->out, 8) && (lse || p->ldo % 4 == 0) && aligned(p->b, 8) && res_ok &&
                           p->ldx < (int64_t(1) << 21) && p->ldw < (int64_t(1) << 21);
     int variant = forced, forced_tile = 0;
@@ -121,13 +121,13 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
         forced_bk = variant == V_SKINNY_128 ? 128 : 256;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && M <= 64;
+    const bool skinny_ok = tiled_ok && M <= 64 && K % 64 == 0;
     if (variant == V_AUTO) {
         if (skinny_ok && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
         else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
     }
-    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs M <= 64 and everything the tiled kernel needs");
-    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 64 == 0, N %% 4 == 0 and 16-byte aligned operands");
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs M <= 64, K %% 64 == 0 and everything the tiled kernel needs");
+    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 8 == 0, N %% 4 == 0 and 16-byte aligned operands");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
     if (variant == V_SKINNY) {

@@ -194,6 +194,7 @@ struct TileLoader {
     uint32_t off_even, off_odd;  // this lane's byte offset in the tile for its even / odd 8-row groups
     uint32_t row_step;           // bytes between 8-row groups
     int wave;
+    int chunk_even;              // logical 16-byte chunk (0..7) this lane copies in its even groups (odd: ^ 1)
 
     __device__ __forceinline__ void init(const void *base, int64_t ld, int64_t rows_valid, int64_t K, int wave_, int lane) {
         const int64_t rv = rows_valid < ROWS ? rows_valid : ROWS;
@@ -205,6 +206,7 @@ struct TileLoader {
         const int p0 = (wave_ * (ROWS / 4) / 8) & 1;  // parity of this wave's first 8-row group
         off_even = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0) << 4);
         off_odd = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0 ^ 1) << 4);
+        chunk_even = lp ^ lr ^ p0;
         row_step = 8 * ldb;
     }
     // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at column k0.
@@ -212,9 +214,19 @@ struct TileLoader {
         const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
     }
-    __device__ __forceinline__ void issue(char *lds, uint32_t k0) const {
+    // Same for the last, partial K step: chunks at or beyond `valid` (= remaining K / 8) get an
+    // out-of-range offset, for which the buffer load delivers zeros.
+    __device__ __forceinline__ void issue_one_tail(char *lds, uint32_t k0, int j, int valid) const {
+        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
+        if ((chunk_even ^ (j & 1)) >= valid) voff = 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+    }
+    __device__ __forceinline__ void issue(char *lds, uint32_t k0, int valid) const {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) issue_one(lds, k0, j);
+        for (int j = 0; j < NI; ++j) {
+            if (valid >= 8) issue_one(lds, k0, j);
+            else issue_one_tail(lds, k0, j, valid);
+        }
     }
 };
 
@@ -327,9 +339,13 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
     bf16x8 fw[2][TN], fx[2][TM];
-    // One K step on stage `stage`; ISSUE: also copy K step kt+1 into the other stage.
+    const int KT = int((a.K + 63) / 64);
+    const int tail_valid = int((a.K - int64_t(KT - 1) * 64) / 8);  // 16-byte chunks of the last K step (8 = full)
+    // One K step on stage kt & 1; ISSUE 1: also copy K step kt+1 into the other stage, 2: kt+1 is the
+    // partial last step.
     auto k_step = [&](int kt, auto issue_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
+        constexpr int IMODE = decltype(issue_c)::value;
+        constexpr bool ISSUE = IMODE != 0;
         const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
         char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
         const uint32_t ik0 = uint32_t(kt + 1) * 64;
@@ -356,8 +372,13 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
                 }
                 if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
                     const int idx = kk * NVM + q / QV;
-                    if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
-                    else ldx_.issue_one(iX, ik0, idx - NIW);
+                    if (IMODE == 2) {
+                        if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, tail_valid);
+                        else ldx_.issue_one_tail(iX, ik0, idx - NIW, tail_valid);
+                    } else {
+                        if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                        else ldx_.issue_one(iX, ik0, idx - NIW);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
@@ -366,13 +387,20 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
         }
     };
 
-    const int KT = int(a.K / 64);
-    ldw_.issue(smem, 0);
-    ldx_.issue(smem + SW, 0);
+    ldw_.issue(smem, 0, KT == 1 ? tail_valid : 8);
+    ldx_.issue(smem + SW, 0, KT == 1 ? tail_valid : 8);
     {
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
         int kt = 0;
-        for (; kt < KT - 1; ++kt) k_step(kt, std::true_type{});
-        k_step(kt, std::false_type{});
+        for (; kt < KT - 2; ++kt) k_step(kt, I1{});
+        if (kt < KT - 1) {
+            if (tail_valid < 8) k_step(kt, I2{});
+            else k_step(kt, I1{});
+            ++kt;
+        }
+        k_step(kt, I0{});
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;

@@ -30,7 +30,8 @@ def test_c1_fp32_bias_gelu_erf_full():
 
 @pytest.mark.parametrize("variant,M,N,K", [
     ("tiled", 256, 256, 64), ("tiled", 300, 520, 192), ("tiled", 128, 128, 128), ("tiled", 77, 132, 64),
-    ("tiled", 513, 772, 128), ("skinny", 32, 256, 64), ("skinny", 61, 132, 128), ("skinny", 7, 2052, 1024), ("skinny128", 32, 256, 256), ("skinny256", 19, 388, 512), ("skinny128", 64, 132, 384),
+    ("tiled", 513, 772, 128), ("tiled", 200, 264, 72), ("tiled", 130, 132, 200), ("tiled256", 300, 520, 8), ("tiled128", 64, 128, 24),
+    ("skinny", 32, 256, 64), ("skinny", 61, 132, 128), ("skinny", 7, 2052, 1024), ("skinny128", 32, 256, 256), ("skinny256", 19, 388, 512), ("skinny128", 64, 132, 384),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
@@ -59,7 +60,7 @@ CHAINS = [
     ["bias", "layernorm", "gelu_erf", "residual"], ["relu", "softmax", "scale", "bias"], ["bias", "logsumexp"],
 ]
 SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kernels and dtypes
-    ("tiled", BF16, 200, 392, 128), ("tiled", BF16, 129, 260, 64), ("skinny", BF16, 32, 2304, 256),
+    ("tiled", BF16, 200, 392, 128), ("tiled", BF16, 129, 260, 64), ("tiled", BF16, 150, 260, 136), ("skinny", BF16, 32, 2304, 256),
     ("skinny", BF16, 17, 392, 576), ("skinny", BF16, 50, 260, 192), ("skinny128", BF16, 40, 520, 640),
     ("skinny256", BF16, 32, 2304, 1024), ("general", BF16, 70, 97, 83),
     ("general", F32, 70, 97, 83), ("general", F32, 64, 256, 256), ("general", BF16, 37, 264, 96),
