@@ -341,11 +341,11 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
     bf16x8 fw[2][TN], fx[2][TM];
     const int KT = int((a.K + 63) / 64);
     const int tail_valid = int((a.K - int64_t(KT - 1) * 64) / 8);  // 16-byte chunks of the last K step (8 = full)
-    // One K step on stage kt & 1; ISSUE 1: also copy K step kt+1 into the other stage, 2: kt+1 is the
-    // partial last step.
+    // One K step on stage kt & 1; ISSUE: also copy K step kt+1 into the other stage (masked to the
+    // valid chunks when that is the partial last step).
     auto k_step = [&](int kt, auto issue_c) {
-        constexpr int IMODE = decltype(issue_c)::value;
-        constexpr bool ISSUE = IMODE != 0;
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        const int valid = kt + 2 == KT ? tail_valid : 8;
         const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
         char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
         const uint32_t ik0 = uint32_t(kt + 1) * 64;
@@ -372,13 +372,8 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
                 }
                 if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
                     const int idx = kk * NVM + q / QV;
-                    if (IMODE == 2) {
-                        if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, tail_valid);
-                        else ldx_.issue_one_tail(iX, ik0, idx - NIW, tail_valid);
-                    } else {
-                        if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
-                        else ldx_.issue_one(iX, ik0, idx - NIW);
-                    }
+                    if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                    else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
@@ -390,17 +385,9 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
     ldw_.issue(smem, 0, KT == 1 ? tail_valid : 8);
     ldx_.issue(smem + SW, 0, KT == 1 ? tail_valid : 8);
     {
-        using I0 = std::integral_constant<int, 0>;
-        using I1 = std::integral_constant<int, 1>;
-        using I2 = std::integral_constant<int, 2>;
         int kt = 0;
-        for (; kt < KT - 2; ++kt) k_step(kt, I1{});
-        if (kt < KT - 1) {
-            if (tail_valid < 8) k_step(kt, I2{});
-            else k_step(kt, I1{});
-            ++kt;
-        }
-        k_step(kt, I0{});
+        for (; kt < KT - 1; ++kt) k_step(kt, std::true_type{});
+        k_step(kt, std::false_type{});
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;

@@ -1,0 +1,56 @@
+"""Compile-time properties of the hot kernels, checked without a GPU: the gfx950 code object
+must keep the tiled and skinny GEMM kernels free of scratch spills (a spill in the K loop costs
+~30 % on the box) and inside the LDS and register budgets their launch configuration assumes."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+
+
+@pytest.fixture(scope="module")
+def asm(tmp_path_factory):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    out = tmp_path_factory.mktemp("asm") / "fle_kernels.s"
+    subprocess.check_call([HIPCC, "-O3", "--offload-arch=gfx950", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only",
+                           "-o", str(out), os.path.join(ROOT, "paper_2511_16964_amd", "csrc", "fle_kernels.hip")],
+                          stderr=subprocess.DEVNULL)
+    return out.read_text()
+
+
+def kernel_props(asm):
+    props = {}
+    for m in re.finditer(r"\.amdhsa_kernel (\S+)(.*?)\.end_amdhsa_kernel", asm, flags=re.S):
+        body = m.group(2)
+        get = lambda key: int(re.search(r"\.amdhsa_%s (\d+)" % key, body).group(1))
+        props[m.group(1)] = dict(lds=get("group_segment_fixed_size"), scratch=get("private_segment_fixed_size"),
+                                 vgpr=get("next_free_vgpr"))
+    return props
+
+
+def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
+    props = kernel_props(asm)
+    names = {k: v for k, v in props.items() if "gemm_bf16" in k}
+    assert len(names) >= 7, sorted(props)
+    for name, p in names.items():
+        assert p["scratch"] == 0, "%s spills %d bytes of scratch" % (name, p["scratch"])
+        assert p["lds"] <= 160 * 1024, name
+        assert p["vgpr"] <= 512, name
+    t128 = [v for k, v in names.items() if "tiled_128" in k][0]
+    assert t128["lds"] <= 80 * 1024 and t128["vgpr"] <= 256      # two workgroups per CU
+    t256 = [v for k, v in names.items() if "tiled_256" in k][0]
+    assert t256["lds"] == 160 * 1024
+
+
+def test_main_loop_uses_the_intended_instructions(asm):
+    body = asm[asm.index("gemm_bf16_tiled_256"):]
+    assert "v_mfma_f32_32x32x16_bf16" in body
+    assert re.search(r"buffer_load_dwordx4 .* lds", body)          # direct-to-LDS copies
+    assert "v_mfma_f32_16x16x4_f32" in asm                         # fp32 path stays on fp32 MFMA
+    assert "v_pk_fma_f32" not in asm and "v_pk_mul_f32" not in asm and "v_pk_add_f32" not in asm
