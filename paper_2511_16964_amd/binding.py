@@ -155,17 +155,23 @@ class Call:
         if workspace is not None:
             p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
         self.workspace_needed = need.value
+        self._pref = ctypes.byref(p)
 
     def run(self, stream=None):
         """Enqueue on ``stream`` (default: torch's current stream) and return ``out`` without synchronising."""
         L = lib()
         s = torch.cuda.current_stream() if stream is None else stream
         self._p.stream = s.cuda_stream  # the HIP stream handle
-        L.fle_force_variant(self.variant)
-        try:
-            _check(L.fle_run(ctypes.byref(self._p)))
-        finally:
-            L.fle_force_variant(0)
+        if self.variant == 0:
+            status = L.fle_run(self._pref)
+        else:
+            L.fle_force_variant(self.variant)
+            try:
+                status = L.fle_run(self._pref)
+            finally:
+                L.fle_force_variant(0)
+        if status != 0:
+            _check(status)
         return self.out
 
     def plan(self) -> str:

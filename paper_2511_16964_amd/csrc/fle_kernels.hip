@@ -829,21 +829,29 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
+    // This wave's k blocks are wave, wave+4, ...; four of them are loaded at once (16 independent
+    // vector loads in flight) before their MFMAs run, so small problems pay one memory latency, not four.
     const int64_t KB = (K + 15) / 16;
-    for (int64_t kb = wave; kb < KB; kb += 4) {
-        const int64_t k = kb * 16 + 4 * q4;
-        f32x4 fw[2], fx[2];
+    constexpr int U = 4;
+    for (int64_t kb0 = wave; kb0 < KB; kb0 += 4 * U) {
+        f32x4 fw[U][2], fx[U][2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            fw[t] = load_k4<BF16, VEC>(a.w, a.ldw, n0 + 16 * t + r16, N, k, K);
-            fx[t] = load_k4<BF16, VEC>(a.x, a.ldx, m0 + 16 * t + r16, M, k, K);
+        for (int u = 0; u < U; ++u) {
+            const int64_t k = (kb0 + 4 * u) * 16 + 4 * q4;  // blocks past KB have k >= K and load zeros
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fw[u][t] = load_k4<BF16, VEC>(a.w, a.ldw, n0 + 16 * t + r16, N, k, K);
+                fx[u][t] = load_k4<BF16, VEC>(a.x, a.ldx, m0 + 16 * t + r16, M, k, K);
+            }
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[j][e], fx[i][e], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[u][j][e], fx[u][i][e], acc[i][j], 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
