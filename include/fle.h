@@ -137,6 +137,13 @@ fle_status fle_last_plan(char *buf, size_t n);
  * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run. */
 void fle_force_variant(int variant);
 
+/* Force the split of K for the calling thread's next calls on the tiled and skinny kernels, for
+ * tests and tuning: 0 = automatic, 1 = no split, S > 1 = S workgroups per output tile, each
+ * over its own K range, summed in a fixed order by a reduction pass (capped at the number of
+ * K steps and at 64).  A split needs S * M * N * 4 more workspace bytes; fle_workspace_size
+ * reports them. */
+void fle_force_split(int split);
+
 /* Library version: major * 10000 + minor * 100 + patch. */
 int fle_version(void);
 

@@ -19,7 +19,7 @@ OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "re
 MAX_OPS = 8
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7}
 EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
-           "fle_last_plan", "fle_force_variant", "fle_version"]
+           "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version"]
 
 
 class FleOp(ctypes.Structure):
@@ -68,6 +68,8 @@ def lib():
         L.fle_last_plan.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
         L.fle_force_variant.restype = None
         L.fle_force_variant.argtypes = [ctypes.c_int]
+        L.fle_force_split.restype = None
+        L.fle_force_split.argtypes = [ctypes.c_int]
         L.fle_version.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -95,12 +97,13 @@ class Call:
     """A marshalled fle_problem bound to its tensors: ``run()`` enqueues it on the
     current stream.  Keeps every tensor alive; reusable (the benchmark times ``run``)."""
 
-    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto"):
+    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):
         if x.dim() != 2 or w.dim() != 2 or x.shape[1] != w.shape[1]:
             raise ValueError("x must be [M,K] and w [N,K]")
         if x.stride(1) != 1 and x.shape[1] > 1 or w.stride(1) != 1 and w.shape[1] > 1:
             raise ValueError("x and w must be row-major (unit stride along K)")
         self.variant = VARIANTS[variant]
+        self.split = int(split)  # 0: automatic split of K; S >= 1 forces S workgroups per tile
         M, K = x.shape
         N = w.shape[0]
         dt = x.dtype
@@ -144,11 +147,13 @@ class Call:
         self._p, self._ops, self._tensors = p, ops, tensors
         L = lib()
         L.fle_force_variant(self.variant)
+        L.fle_force_split(self.split)
         try:
             need = ctypes.c_size_t(0)
             _check(L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)))
         finally:
             L.fle_force_variant(0)
+            L.fle_force_split(0)
         if workspace is None and need.value:
             workspace = torch.empty(need.value, dtype=torch.uint8, device=x.device)
         self.workspace = workspace
@@ -162,14 +167,16 @@ class Call:
         L = lib()
         s = torch.cuda.current_stream() if stream is None else stream
         self._p.stream = s.cuda_stream  # the HIP stream handle
-        if self.variant == 0:
+        if self.variant == 0 and self.split == 0:
             status = L.fle_run(self._pref)
         else:
             L.fle_force_variant(self.variant)
+            L.fle_force_split(self.split)
             try:
                 status = L.fle_run(self._pref)
             finally:
                 L.fle_force_variant(0)
+                L.fle_force_split(0)
         if status != 0:
             _check(status)
         return self.out
@@ -180,7 +187,7 @@ class Call:
         return buf.value.decode()
 
 
-def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto"):
+def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):
     """out = epilogue(x @ w.T) in one fused library call.
 
     x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32 or bfloat16).
@@ -190,4 +197,4 @@ def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="
     """
     if not x.is_cuda:
         raise RuntimeError("fused_linear_epilogue runs on the GPU only; there is no CPU path")
-    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant).run()
+    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, split=split).run()

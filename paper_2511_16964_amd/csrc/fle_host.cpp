@@ -12,6 +12,7 @@ namespace fle {
 static thread_local char g_error[512] = "";
 static thread_local char g_plan[200] = "";
 static thread_local int g_forced = V_AUTO;
+static thread_local int g_split = 0;
 
 fle_status fail(fle_status s, const char *fmt, ...) {
     va_list ap;
@@ -38,7 +39,7 @@ static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
     return (static_cast<size_t>(rows - 1) * static_cast<size_t>(ld) + static_cast<size_t>(cols)) * es;
 }
 
-fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
+fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
     if (p->dtype != FLE_F32 && p->dtype != FLE_BF16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32 or FLE_BF16", p->dtype);
@@ -130,6 +131,7 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 8 == 0, N %% 4 == 0 and 16-byte aligned operands");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
+    int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
     if (variant == V_SKINNY) {
         plan->bm = M <= 32 ? 32 : 64;
         plan->bn = 128;
@@ -142,11 +144,35 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile
     } else if (variant == V_TILED) {
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        const bool big = M > 128 && N > 128 && t256 >= 128;
-        plan->bm = plan->bn = forced_tile ? forced_tile : big ? 256 : 128;
+        // Tile and split of K together, by a coarse time model (microseconds) fitted to measured runs:
+        // a K step costs a 256 tile 1.45, a 128 tile 0.85 with two workgroups per CU and 0.6 alone;
+        // filling the pipeline and the epilogue cost about 8 (10) more steps; workgroups beyond the
+        // 256 (512) that are resident at once wait for a second round; a split adds a launch and
+        // 8 S M N bytes of slab traffic at about 6 TB/s (the slabs mostly stay in the last-level cache).
+        const int64_t steps = (K + 63) / 64;
+        auto cost = [&](int tile, int64_t sp) -> double {
+            const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
+            const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
+            const double per_step = tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6;
+            double t = double(rounds) * (double((steps + sp - 1) / sp) + (tile == 256 ? 8.0 : 10.0)) * per_step;
+            if (sp > 1) t += 4.0 + 8.0 * double(sp) * double(M) * double(N) / 6.0e6;
+            return t;
+        };
+        static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+        int best_tile = 0, best_split = 1;
+        double best = 0.0;
+        for (int tile = 128; tile <= 256; tile += 128) {
+            if (forced_tile ? tile != forced_tile : (tile == 256 && !(M > 128 && N > 128))) continue;
+            for (int sp : kSplits) {
+                if (forced_split > 0 ? sp != 1 : (sp > 1 && (sp * 4 > steps || int64_t(sp) * M * N * 4 > (int64_t(128) << 20)))) continue;
+                const double t = cost(tile, sp);
+                if (!best_tile || t < best) { best = t; best_tile = tile; best_split = sp; }
+            }
+        }
+        plan->bm = plan->bn = best_tile;
         plan->bk = 64;
         plan->part_cols = plan->bn / 2;  // one partial per wave column
+        auto_split = best_split;
     } else {
         plan->bm = plan->bn = 32;
         plan->bk = 16;
@@ -155,6 +181,31 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
     plan->tiles_m = (M + plan->bm - 1) / plan->bm;
     plan->tiles_n = (N + plan->bn - 1) / plan->bn;
     if (plan->tiles_m * plan->tiles_n > (int64_t(1) << 31) - 1) return fail(FLE_ERR_SHAPE, "too many tiles for one launch");
+
+    // ---- split K: few tiles and a long K leave most of the chip idle, so several workgroups share
+    // a tile, each over its own K range, writing fp32 slabs that a reduction pass sums in slab order
+    // (deterministic).
+    plan->split_k = 1;
+    if (variant != V_GENERAL && M > 0) {
+        const int64_t steps = variant == V_TILED ? (K + 63) / 64 : K / plan->bk;
+        int64_t s = 1;
+        if (forced_split > 0) s = forced_split;
+        else if (auto_split > 0) s = auto_split;
+        else {  // skinny kernel: fill the chip as long as every workgroup keeps at least 512 of K
+            const int64_t tiles = plan->tiles_m * plan->tiles_n;
+            const int64_t min_steps = 512 / plan->bk > 2 ? 512 / plan->bk : 2;
+            if (tiles * 2 <= 256) {
+                s = 256 / tiles;
+                if (s > steps / min_steps) s = steps / min_steps;
+                if (s > 16) s = 16;
+            }
+        }
+        if (s > steps) s = steps;
+        if (s > 64) s = 64;
+        if (s < 1) s = 1;
+        plan->split_k = int32_t(s);
+        if (s > 1) plan->part_cols = 256;  // the reduction pass owns the partials
+    }
 
     // ---- staging and workspace
     size_t off = 0;
@@ -172,10 +223,14 @@ fle_status make_plan(const fle_problem *p, int forced, Plan *plan) {
             }
         }
     }
+    if (plan->split_k > 1) {
+        plan->ws_slab_off = off;
+        off = round_up(off + size_t(plan->split_k) * size_t(M) * size_t(N) * sizeof(float), 256);
+    }
     plan->ws_total = M > 0 ? off : 0;
-    snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld row_op=%d np=%d staging=%s workspace=%zu",
+    snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
              variant == V_TILED ? "tiled_bf16_mfma" : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
-             (long long)plan->tiles_n, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
+             (long long)plan->tiles_n, plan->split_k, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
     return FLE_OK;
 }
 
@@ -187,13 +242,13 @@ extern "C" {
 
 fle_status fle_validate(const fle_problem *p) {
     Plan plan;
-    return make_plan(p, g_forced, &plan);
+    return make_plan(p, g_forced, g_split, &plan);
 }
 
 fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out) {
     if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
     Plan plan;
-    fle_status s = make_plan(p, g_forced, &plan);
+    fle_status s = make_plan(p, g_forced, g_split, &plan);
     if (s != FLE_OK) return s;
     *bytes_out = plan.ws_total;
     std::memcpy(g_plan, plan.text, sizeof g_plan);
@@ -202,7 +257,7 @@ fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out) {
 
 fle_status fle_run(const fle_problem *p) {
     Plan plan;
-    fle_status s = make_plan(p, g_forced, &plan);
+    fle_status s = make_plan(p, g_forced, g_split, &plan);
     if (s != FLE_OK) return s;
     if (p->M == 0) return FLE_OK;
     if (plan.ws_total > 0) {
@@ -238,6 +293,8 @@ fle_status fle_last_plan(char *buf, size_t n) {
 }
 
 void fle_force_variant(int variant) { g_forced = variant; }
+
+void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
 int fle_version(void) { return 100; }
 

@@ -36,6 +36,21 @@ struct GemmArgs {
     int32_t np;       // row-reduction partials per row
     float *partials;  // [M][np][2], or nullptr without a row op
     int32_t tiles_m, tiles_n;
+    int64_t split_stride;  // split K (gridDim.y > 1): workgroup row y owns a K range and writes dst + y * split_stride bytes
+    DevEpilogue epi;
+};
+
+// Sum of the split-K slabs followed by the ops before the row op (reduce_slabs).
+struct RedArgs {
+    int64_t M, N;
+    const float *slabs;  // [S][M][N] fp32
+    int64_t stride;      // elements between slabs
+    int32_t S;
+    int32_t dst_f32;
+    void *dst;           // as GemmArgs::dst
+    int64_t ldd;
+    int32_t np;
+    float *partials;     // one partial per (row, 256 columns)
     DevEpilogue epi;
 };
 
@@ -382,15 +397,18 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
         }
     };
 
-    ldw_.issue(smem, 0, KT == 1 ? tail_valid : 8);
-    ldx_.issue(smem + SW, 0, KT == 1 ? tail_valid : 8);
+    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y)
+    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
+    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 64, kb + 1 == KT ? tail_valid : 8);
+    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 64, kb + 1 == KT ? tail_valid : 8);
     {
-        int kt = 0;
-        for (; kt < KT - 1; ++kt) k_step(kt, std::true_type{});
+        int kt = kb;
+        for (; kt < ke - 1; ++kt) k_step(kt, std::true_type{});
         k_step(kt, std::false_type{});
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;
+    char *const dst = a.dst ? reinterpret_cast<char *>(a.dst) + int64_t(blockIdx.y) * a.split_stride : nullptr;
 
     // ---- epilogue
     const int rsub = lane >> 4;  // row within a group of 4 rows
@@ -560,9 +578,9 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
                 for (int hc = 0; hc < NH; ++hc)
                     if (m < M && n_ok[hc]) {
                         if (a.dst_f32)
-                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + m * a.ldd + n_col[hc]) = v[it][hc];
+                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]) = v[it][hc];
                         else
-                            *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + m * a.ldd + n_col[hc]) = __builtin_convertvector(v[it][hc], bf16x4);
+                            *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n_col[hc]) = __builtin_convertvector(v[it][hc], bf16x4);
                     }
             }
         }
@@ -645,11 +663,13 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
             }
         }
     };
-    const int KT = int(a.K / BK);
+    // K stages kt .. KT-1 of this workgroup (all of them unless K is split over gridDim.y)
+    const int KA = int(a.K / BK);
+    int kt = int(int64_t(blockIdx.y) * KA / gridDim.y);
+    const int KT = int(int64_t(blockIdx.y + 1) * KA / gridDim.y);
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
-        if (s < KT) issue(s);
-    int kt = 0;
+        if (kt + s < KT) issue(kt + s);
     for (; kt + NST - 1 < KT; ++kt) {
         wait_vmcnt<(NST - 2) * LPS>();  // the newest NST-2 stages may still be in flight
         __builtin_amdgcn_s_barrier();    // stage kt is complete; stage kt-1 is no longer read
@@ -663,6 +683,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     }
 
     // ---- epilogue in the MFMA layout: acc[t][4q+e] = out[32 t + (lane & 31)][n_lane + 8 q + e]
+    char *const dst = a.dst ? reinterpret_cast<char *>(a.dst) + int64_t(blockIdx.y) * a.split_stride : nullptr;
     const int h = lane >> 5;
     const int64_t n_lane = n0 + wave * 32 + 4 * h;
     if (n0 + wave * 32 >= N) return;
@@ -776,9 +797,9 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 if (m < M && n < N) {
                     const f32x4 v = f32x4{acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
                     if (a.dst_f32)
-                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + m * a.ldd + n) = v;
+                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n) = v;
                     else
-                        *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + m * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+                        *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n) = __builtin_convertvector(v, bf16x4);
                 }
             }
         }
@@ -1036,6 +1057,94 @@ __global__ __launch_bounds__(256) void finalize_lse(const FinArgs a) {
     if (lane == 0) st_elem(a.out, row, a.epi.dtype, s.a + __logf(s.b));
 }
 
+// ------------------------------------------------------------------ split-K reduction
+// One wave per (row, 256-column chunk), a lane per 4 consecutive columns: sums the S fp32 slabs
+// in slab order, applies the ops that precede the row op, writes the value (final, or staged
+// for the finalize pass) and, with a row op, the chunk's partial.  bf16 problems only.
+template <bool MAX>
+__device__ __forceinline__ float wave_allreduce(float v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_xor(v, d);
+        v = MAX ? fmaxf(v, o) : v + o;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t N = a.N;
+    const int64_t chunks = (N + 255) / 256, items = a.M * chunks;
+    for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
+        const int64_t row = item / chunks, c0 = (item % chunks) * 256;
+        const int64_t n = c0 + lane * 4;
+        const bool ok = n < N;  // N % 4 == 0: a lane's four columns are all inside or all outside
+        f32x4 v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (ok) {
+            const float *src = a.slabs + row * N + n;
+            int s = 0;
+            for (; s + 4 <= a.S; s += 4) {
+                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(src + (s + 0) * a.stride);
+                const f32x4 u1 = *reinterpret_cast<const f32x4 *>(src + (s + 1) * a.stride);
+                const f32x4 u2 = *reinterpret_cast<const f32x4 *>(src + (s + 2) * a.stride);
+                const f32x4 u3 = *reinterpret_cast<const f32x4 *>(src + (s + 3) * a.stride);
+                v = (((v + u0) + u1) + u2) + u3;
+            }
+            for (; s < a.S; ++s) v += *reinterpret_cast<const f32x4 *>(src + s * a.stride);
+            for (int o = 0; o < a.epi.n_pre; ++o) {
+                const DevOp op = a.epi.pre[o];
+                switch (op.kind) {
+                case FLE_BIAS: v += ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + n); break;
+                case FLE_SCALE: v *= op.alpha; break;
+                case FLE_RELU:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = relu_f(v[e]);
+                    break;
+                case FLE_GELU_ERF:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_erf_f(v[e]);
+                    break;
+                case FLE_GELU_TANH:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
+                    break;
+                case FLE_RESIDUAL: v += ld4_bf16(reinterpret_cast<const uint16_t *>(op.p0) + row * op.ld + n); break;
+                default: break;
+                }
+            }
+        }
+        if (a.epi.row_kind >= 0) {
+            float s0, s1;
+            if (a.epi.row_kind == FLE_LAYERNORM) {
+                const float cnt = float(N - c0 < 256 ? N - c0 : 256);
+                const float mean = wave_allreduce<false>(ok ? (v[0] + v[1]) + (v[2] + v[3]) : 0.0f) / cnt;
+                float m2 = 0.0f;
+                if (ok)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) m2 += (v[e] - mean) * (v[e] - mean);
+                s0 = mean;
+                s1 = wave_allreduce<false>(m2);
+            } else {
+                const float mx = wave_allreduce<true>(ok ? fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])) : -INFINITY);
+                float se = 0.0f;
+                if (ok)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) se += __expf(v[e] - mx);
+                s0 = mx;
+                s1 = wave_allreduce<false>(se);
+            }
+            if (lane == 0) *reinterpret_cast<float2 *>(a.partials + (row * a.np + c0 / 256) * 2) = make_float2(s0, s1);
+        }
+        if (a.dst && ok) {
+            if (a.dst_f32)
+                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * a.ldd + n) = v;
+            else
+                *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + row * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+        }
+    }
+}
+
 // ------------------------------------------------------------------ launcher
 static fle_status check_launch(const char *what) {
     const hipError_t err = hipGetLastError();
@@ -1061,46 +1170,68 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     else if (plan.staging == ST_WS) { g.dst = ws + plan.ws_y_off; g.ldd = p->N; g.dst_f32 = 1; }
     else { g.dst = nullptr; g.ldd = 0; g.dst_f32 = 0; }
 
-    const uint32_t grid = uint32_t(plan.tiles_m * plan.tiles_n);
+    // Split K: the GEMM writes bare fp32 slabs; reduce_slabs takes over dst, the pre-ops and the partials.
+    RedArgs r{};
+    const bool split = plan.split_k > 1;
+    if (split) {
+        r.M = p->M; r.N = p->N;
+        r.slabs = reinterpret_cast<const float *>(ws + plan.ws_slab_off);
+        r.stride = p->M * p->N;
+        r.S = plan.split_k;
+        r.dst = g.dst; r.ldd = g.ldd; r.dst_f32 = g.dst_f32;
+        r.np = plan.np; r.partials = g.partials;
+        r.epi = e;
+        g.dst = ws + plan.ws_slab_off; g.ldd = p->N; g.dst_f32 = 1;
+        g.split_stride = r.stride * int64_t(sizeof(float));
+        g.partials = nullptr;
+        g.epi.n_pre = 0; g.epi.n_post = 0; g.epi.row_kind = -1;
+    }
+    const dim3 grid(uint32_t(plan.tiles_m * plan.tiles_n), uint32_t(plan.split_k));
     if (plan.variant == V_SKINNY) {
         if (plan.bm == 32) {
-            if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), dim3(grid), dim3(256), 0, stream, g);
-            else if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<1, 128>), dim3(grid), dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_bf16_skinny<1, 64>), dim3(grid), dim3(256), 0, stream, g);
+            if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), grid, dim3(256), 0, stream, g);
+            else if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<1, 128>), grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_bf16_skinny<1, 64>), grid, dim3(256), 0, stream, g);
         } else {
-            if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), dim3(grid), dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), dim3(grid), dim3(256), 0, stream, g);
+            if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), grid, dim3(256), 0, stream, g);
         }
     } else if (plan.variant == V_TILED) {
-        if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, dim3(grid), dim3(256), 0, stream, g);
-        else hipLaunchKernelGGL(gemm_bf16_tiled_128, dim3(grid), dim3(256), 0, stream, g);
+        if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, grid, dim3(256), 0, stream, g);
+        else hipLaunchKernelGGL(gemm_bf16_tiled_128, grid, dim3(256), 0, stream, g);
     } else {
         // vector loads need 4-element groups that never straddle K and rows that keep the alignment
         const size_t va = bf16 ? 8 : 16;
         const bool vec = p->K % 4 == 0 && reinterpret_cast<uintptr_t>(p->x) % va == 0 && reinterpret_cast<uintptr_t>(p->w) % va == 0 &&
                          p->ldx % 4 == 0 && p->ldw % 4 == 0;
         if (bf16) {
-            if (vec) hipLaunchKernelGGL((gemm_general<true, true>), dim3(grid), dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_general<true, false>), dim3(grid), dim3(256), 0, stream, g);
+            if (vec) hipLaunchKernelGGL((gemm_general<true, true>), grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_general<true, false>), grid, dim3(256), 0, stream, g);
         } else {
-            if (vec) hipLaunchKernelGGL((gemm_general<false, true>), dim3(grid), dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_general<false, false>), dim3(grid), dim3(256), 0, stream, g);
+            if (vec) hipLaunchKernelGGL((gemm_general<false, true>), grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL((gemm_general<false, false>), grid, dim3(256), 0, stream, g);
         }
     }
     fle_status s = check_launch("GEMM kernel launch");
+    if (s == FLE_OK && split) {
+        const int64_t want = (p->M * ((p->N + 255) / 256) + 3) / 4;
+        hipLaunchKernelGGL(reduce_slabs, dim3(uint32_t(want < (int64_t(1) << 20) ? want : (int64_t(1) << 20))), dim3(256), 0, stream, r);
+        s = check_launch("split-K reduction launch");
+    }
     if (s != FLE_OK || e.row_kind < 0) return s;
 
     FinArgs f{};
     f.M = p->M; f.N = p->N;
     f.np = plan.np; f.part_cols = plan.part_cols;
-    f.partials = g.partials;
+    f.partials = split ? r.partials : g.partials;
     f.out = p->out; f.ldo = p->ldo;
     f.epi = e;
     if (e.row_kind == FLE_LOGSUMEXP) {
         hipLaunchKernelGGL(finalize_lse, dim3(uint32_t((p->M + 3) / 4)), dim3(256), 0, stream, f);
         return check_launch("logsumexp finalize launch");
     }
-    f.y = g.dst; f.ldy = g.ldd; f.y_f32 = g.dst_f32;
+    if (split) { f.y = r.dst; f.ldy = r.ldd; f.y_f32 = r.dst_f32; }
+    else { f.y = g.dst; f.ldy = g.ldd; f.y_f32 = g.dst_f32; }
     const size_t ysz = f.y_f32 ? 4 : es;
     const bool vec = p->N % 8 == 0 && f.ldy % 8 == 0 && p->ldo % 8 == 0 && reinterpret_cast<uintptr_t>(f.y) % (8 * ysz) == 0 &&
                      reinterpret_cast<uintptr_t>(p->out) % (8 * es) == 0;

@@ -44,14 +44,15 @@ struct Plan {
     int32_t part_cols;       // columns covered by one row-reduction partial
     int32_t np;              // partials per row = ceil(N / part_cols)
     int32_t staging;
+    int32_t split_k;         // workgroups along K per tile (1: none); > 1 adds fp32 slabs and a reduction pass
     int64_t tiles_m, tiles_n;
-    size_t ws_part_off, ws_y_off, ws_total;
+    size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
     DevEpilogue epi;
     char text[200];
 };
 
 // Validates p (everything except workspace size) and fills plan.  Host only, no HIP calls.
-fle_status make_plan(const fle_problem *p, int forced_variant, Plan *plan);
+fle_status make_plan(const fle_problem *p, int forced_variant, int forced_split, Plan *plan);
 
 // Records the calling thread's error detail; returns s.
 fle_status fail(fle_status s, const char *fmt, ...);

@@ -30,8 +30,8 @@ def make_call(prob: inputs.Problem, variant="auto", **kw) -> binding.Call:
                         variant=variant, **kw)
 
 
-def run_gpu(prob: inputs.Problem, variant="auto"):
-    call = make_call(prob, variant)
+def run_gpu(prob: inputs.Problem, variant="auto", **kw):
+    call = make_call(prob, variant, **kw)
     out = call.run()
     torch.cuda.synchronize()
     return out.cpu(), call

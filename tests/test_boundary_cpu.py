@@ -179,3 +179,42 @@ def test_variant_selection(L):
         assert validate(L, problem(M=64, N=256, K=256, dtype=binding.F32)) == E_UNSUP
     finally:
         L.fle_force_variant(0)
+
+
+def test_split_k_planning(L):
+    def plan_of(p):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return buf.value.decode(), need.value
+    split = lambda text: int(re.search(r"split_k=(\d+)", text).group(1))
+    # the large benchmark shapes fill the chip by themselves: 256 tile, no split, no workspace
+    for M, N, K in ((4096, 4096, 4096), (8192, 4096, 4096), (16384, 16384, 4096), (16384, 4096, 16384)):
+        text, need = plan_of(problem(M=M, N=N, K=K))
+        assert "tile=256x256" in text and split(text) == 1 and need == 0, text
+    # one tile row and a long K: split, and the slabs are counted in the workspace
+    text, need = plan_of(problem(M=128, N=4096, K=4096))
+    s = split(text)
+    assert "tiled" in text and s > 1 and need == s * 128 * 4096 * 4, text
+    text, need = plan_of(problem(M=16, N=4096, K=4096))
+    assert "skinny" in text and split(text) > 1 and need == split(text) * 16 * 4096 * 4, text
+    # many small tiles and a short K: the 128 tile without a split
+    text, need = plan_of(problem(M=512, N=16384, K=1024))
+    assert "tile=128x128" in text and split(text) == 1 and need == 0, text
+    # the slabs come after the row-op partials and the staged fp32 values
+    text, need = plan_of(problem(M=128, N=4096, K=4096, ops=[op("softmax")]))
+    s, np_ = split(text), int(re.search(r"np=(\d+)", text).group(1))
+    assert s > 1 and np_ == 4096 // 256 and need == 128 * np_ * 8 + 128 * 4096 * 4 + s * 128 * 4096 * 4, text
+    L.fle_force_split(3)
+    try:
+        text, need = plan_of(problem(M=300, N=520, K=576))
+        assert split(text) == 3 and need == -(-3 * 300 * 520 * 4 // 256) * 256, text
+        text, need = plan_of(problem(M=300, N=520, K=72))        # two K steps only
+        assert split(text) == 2, text
+        text, need = plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))
+        assert "general" in text and split(text) == 1 and need == 0, text
+    finally:
+        L.fle_force_split(0)
+    text, _ = plan_of(problem(M=300, N=520, K=576))
+    assert split(text) == 1, text

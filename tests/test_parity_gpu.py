@@ -42,6 +42,7 @@ def test_integer_inputs_are_bit_exact(variant, M, N, K):
     announce("integer exact", variant, M, N, K)
     got, call = run_gpu(prob, variant)
     ref = oracle_rows(prob)
+    assert np.array_equal(ref, torch.from_numpy(ref).to(BF16).to(torch.float64).numpy()), "test premise: the exact result fits bf16"
     assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
 
 
@@ -52,6 +53,48 @@ def test_integer_exact_on_the_256_tile():
     assert "tile=256x256" in call.plan()
     rows = sample_rows(prob.M, 96)
     assert np.array_equal(got[rows].to(torch.float64).numpy(), oracle_rows(prob, rows))
+
+
+@pytest.mark.parametrize("variant,split,M,N,K", [
+    ("tiled128", 3, 200, 264, 200), ("tiled256", 5, 300, 520, 576), ("tiled", 2, 130, 132, 72), ("tiled128", 64, 77, 132, 320),
+    ("tiled256", 16, 513, 772, 512), ("skinny", 4, 61, 132, 512), ("skinny256", 3, 19, 388, 768), ("skinny128", 3, 64, 132, 384),
+    ("skinny128", 4, 32, 2052, 512), ("skinny", 7, 32, 260, 448),
+])
+def test_split_k_integer_inputs_are_bit_exact(variant, split, M, N, K):
+    """K split over several workgroups per tile (uneven ranges, a ragged last K step, more splits
+    asked for than there are K steps): the slabs and their ordered sum are exact on integer data."""
+    prob = inputs.random_problem(13, M, N, K, BF16, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("split-K integer exact", variant, split, M, N, K)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "split_k=1 " not in call.plan(), call.plan()
+    ref = oracle_rows(prob)
+    assert np.array_equal(ref, torch.from_numpy(ref).to(BF16).to(torch.float64).numpy()), "test premise: the exact result fits bf16"
+    assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
+
+
+SPLIT_SHAPES = [("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024)]
+
+
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "%s-s%d-%dx%dx%d" % s)
+@pytest.mark.parametrize("kinds", [[], ["bias", "gelu_erf"], ["bias", "residual", "layernorm"], ["relu", "softmax", "scale", "bias"],
+                                   ["bias", "logsumexp"], ["bias", "layernorm", "gelu_tanh", "residual"]], ids=lambda k: "+".join(k) or "plain")
+def test_split_k_chains(shape, kinds):
+    variant, split, M, N, K = shape
+    prob = inputs.random_problem(4, M, N, K, BF16, kinds)
+    announce("split-K chain", variant, split, M, N, K, kinds)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "split_k=%d " % split in call.plan(), call.plan()
+    assert_close(got, oracle_rows(prob), BF16, "%s %s" % (kinds, call.plan()))
+
+
+def test_split_k_is_chosen_for_few_tiles_and_long_k():
+    """Automatic plan: a problem with few output tiles and a long K is split, and agrees with the oracle."""
+    for M, N, K in ((128, 1024, 4096), (48, 2048, 4096)):
+        prob = inputs.random_problem(6, M, N, K, BF16, ["bias", "gelu_tanh", "layernorm"])
+        announce("auto split", M, N, K)
+        got, call = run_gpu(prob)
+        assert "split_k=1 " not in call.plan(), call.plan()
+        assert_close(got, oracle_rows(prob), BF16, call.plan())
 
 
 CHAINS = [
