@@ -104,14 +104,19 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
 
     // ---- kernel variant
+    const bool f32 = p->dtype == FLE_F32;
+    // The tiled kernels copy 16-byte chunks and read / write groups of 4 consecutive columns.
+    const int64_t chunk = 16 / int64_t(es);                  // elements per 16-byte chunk: 8 bf16, 4 fp32
+    const size_t vec4 = 4 * es;                              // alignment of a 4-column group
+    const int64_t ld_max = int64_t(1) << (f32 ? 20 : 21);    // 32-bit byte offsets inside a 256-row tile
     bool res_ok = true, post_res_alias_out = false;
     for (int i = 0; i < e.n_pre; ++i)
-        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, 8) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < (int64_t(1) << 21))) res_ok = false;
+        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, vec4) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < ld_max)) res_ok = false;
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
-    const bool tiled_ok = p->dtype == FLE_BF16 && K >= 8 && K % 8 == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
-                          p->ldx % 8 == 0 && p->ldw % 8 == 0 && aligned(p->out, 8) && (lse || p->ldo % 4 == 0) && aligned(p->b, 8) && res_ok &&
-                          p->ldx < (int64_t(1) << 21) && p->ldw < (int64_t(1) << 21);
+    const bool tiled_ok = K >= chunk && K % chunk == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
+                          p->ldx % chunk == 0 && p->ldw % chunk == 0 && aligned(p->out, vec4) && (lse || p->ldo % 4 == 0) && aligned(p->b, vec4) && res_ok &&
+                          p->ldx < ld_max && p->ldw < ld_max;
     int variant = forced, forced_tile = 0;
     if (variant == V_TILED_256 || variant == V_TILED_128) {
         forced_tile = variant == V_TILED_256 ? 256 : 128;
@@ -122,13 +127,49 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         forced_bk = variant == V_SKINNY_128 ? 128 : 256;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && M <= 64 && K % 64 == 0;
+    const bool skinny_ok = tiled_ok && !f32 && M <= 64 && K % 64 == 0;
+
+    // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
+    // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
+    // with two workgroups per CU and 0.6 alone.  fp32: the matrix pipe bounds a K step at 7.8 / 3.9 /
+    // 1.95.  Filling the pipeline and the epilogue cost about 12 us (256 tile) or 6 to 8 us;
+    // workgroups beyond the 256 (512) that are resident at once wait for a second round; a split adds
+    // a launch and 8 S M N bytes of slab traffic at about 6 TB/s (the slabs mostly stay in the
+    // last-level cache).
+    const int64_t tiled_steps = (K * int64_t(es) + 127) / 128;
+    auto tiled_cost = [&](int tile, int64_t sp) -> double {
+        const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
+        const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
+        const double per_step = f32 ? (tile == 256 ? 7.8 : wgs > 256 ? 3.9 : 1.95) : (tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6);
+        const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 8.0 : 10.0);  // in K steps
+        double t = double(rounds) * (double((tiled_steps + sp - 1) / sp) + fixed) * per_step;
+        if (sp > 1) t += 4.0 + 8.0 * double(sp) * double(M) * double(N) / 6.0e6;
+        return t;
+    };
+    int best_tile = 0, best_split = 1;
+    double best = 0.0;
+    if (tiled_ok && M > 0) {
+        static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+        for (int tile = 128; tile <= 256; tile += 128) {
+            if (forced_tile ? tile != forced_tile : (tile == 256 && !(M > 128 && N > 128))) continue;
+            for (int sp : kSplits) {
+                if (forced_split > 0 ? sp != 1 : (sp > 1 && (sp * 4 > tiled_steps || int64_t(sp) * M * N * 4 > (int64_t(128) << 20)))) continue;
+                const double t = tiled_cost(tile, sp);
+                if (!best_tile || t < best) { best = t; best_tile = tile; best_split = sp; }
+            }
+        }
+    }
+    if (!best_tile) best_tile = forced_tile ? forced_tile : 128;
     if (variant == V_AUTO) {
         if (skinny_ok && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
-        else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
+        else if (f32) {
+            // the general kernel runs fp32 at about 55 TFLOP/s behind some 7 us of launch and latency
+            const double general = 7.0 + 2.0 * double(M) * double(N) * double(K) / 55.0e6;
+            variant = (tiled_ok && M > 0 && best < general) ? V_TILED : V_GENERAL;
+        } else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
     }
-    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs M <= 64, K %% 64 == 0 and everything the tiled kernel needs");
-    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled bf16 MFMA kernel needs bf16, K %% 8 == 0, N %% 4 == 0 and 16-byte aligned operands");
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 64, K %% 64 == 0 and everything the tiled kernel needs");
+    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs K a multiple of 16 bytes, N %% 4 == 0 and 16-byte aligned operands");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
@@ -144,33 +185,8 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile
     } else if (variant == V_TILED) {
-        // Tile and split of K together, by a coarse time model (microseconds) fitted to measured runs:
-        // a K step costs a 256 tile 1.45, a 128 tile 0.85 with two workgroups per CU and 0.6 alone;
-        // filling the pipeline and the epilogue cost about 8 (10) more steps; workgroups beyond the
-        // 256 (512) that are resident at once wait for a second round; a split adds a launch and
-        // 8 S M N bytes of slab traffic at about 6 TB/s (the slabs mostly stay in the last-level cache).
-        const int64_t steps = (K + 63) / 64;
-        auto cost = [&](int tile, int64_t sp) -> double {
-            const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
-            const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
-            const double per_step = tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6;
-            double t = double(rounds) * (double((steps + sp - 1) / sp) + (tile == 256 ? 8.0 : 10.0)) * per_step;
-            if (sp > 1) t += 4.0 + 8.0 * double(sp) * double(M) * double(N) / 6.0e6;
-            return t;
-        };
-        static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16};
-        int best_tile = 0, best_split = 1;
-        double best = 0.0;
-        for (int tile = 128; tile <= 256; tile += 128) {
-            if (forced_tile ? tile != forced_tile : (tile == 256 && !(M > 128 && N > 128))) continue;
-            for (int sp : kSplits) {
-                if (forced_split > 0 ? sp != 1 : (sp > 1 && (sp * 4 > steps || int64_t(sp) * M * N * 4 > (int64_t(128) << 20)))) continue;
-                const double t = cost(tile, sp);
-                if (!best_tile || t < best) { best = t; best_tile = tile; best_split = sp; }
-            }
-        }
         plan->bm = plan->bn = best_tile;
-        plan->bk = 64;
+        plan->bk = f32 ? 32 : 64;
         plan->part_cols = plan->bn / 2;  // one partial per wave column
         auto_split = best_split;
     } else {
@@ -187,7 +203,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // (deterministic).
     plan->split_k = 1;
     if (variant != V_GENERAL && M > 0) {
-        const int64_t steps = variant == V_TILED ? (K + 63) / 64 : K / plan->bk;
+        const int64_t steps = variant == V_TILED ? tiled_steps : K / plan->bk;
         int64_t s = 1;
         if (forced_split > 0) s = forced_split;
         else if (auto_split > 0) s = auto_split;
@@ -229,7 +245,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     plan->ws_total = M > 0 ? off : 0;
     snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             variant == V_TILED ? "tiled_bf16_mfma" : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
+             variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
              (long long)plan->tiles_n, plan->split_k, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
     return FLE_OK;
 }

@@ -91,6 +91,13 @@ __device__ __forceinline__ f32x4 ld4_bf16(const void *p) {  // p is 8-byte align
     return r;
 }
 
+// 4 consecutive elements at element index i of p as fp32 (p + i aligned to 4 elements).
+template <bool F32>
+__device__ __forceinline__ f32x4 ld4(const void *p, int64_t i) {
+    if constexpr (F32) return *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+    else return ld4_bf16(reinterpret_cast<const uint16_t *>(p) + i);
+}
+
 __device__ __forceinline__ float relu_f(float v) { return v < 0.0f ? 0.0f : v; }  // NaN stays NaN
 
 // GELU with the exact-erf definition.  erfc(|x|) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2),
@@ -211,12 +218,13 @@ struct TileLoader {
     int wave;
     int chunk_even;              // logical 16-byte chunk (0..7) this lane copies in its even groups (odd: ^ 1)
 
-    __device__ __forceinline__ void init(const void *base, int64_t ld, int64_t rows_valid, int64_t K, int wave_, int lane) {
+    // ld_bytes: distance between rows; k_bytes: length of a row (K elements), both in bytes
+    __device__ __forceinline__ void init(const void *base, int64_t ld_bytes, int64_t rows_valid, int64_t k_bytes, int wave_, int lane) {
         const int64_t rv = rows_valid < ROWS ? rows_valid : ROWS;
-        const uint32_t nrec = uint32_t(((rv - 1) * ld + K) * 2);
+        const uint32_t nrec = uint32_t((rv - 1) * ld_bytes + k_bytes);
         rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, nrec, 0x00020000);
         const int lr = lane >> 3, lp = lane & 7;
-        const uint32_t ldb = uint32_t(ld) * 2;
+        const uint32_t ldb = uint32_t(ld_bytes);
         wave = wave_;
         const int p0 = (wave_ * (ROWS / 4) / 8) & 1;  // parity of this wave's first 8-row group
         off_even = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0) << 4);
@@ -224,15 +232,15 @@ struct TileLoader {
         chunk_even = lp ^ lr ^ p0;
         row_step = 8 * ldb;
     }
-    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at column k0.
+    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at byte column k0.
     __device__ __forceinline__ void issue_one(char *lds, uint32_t k0, int j) const {
-        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
+        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
     }
-    // Same for the last, partial K step: chunks at or beyond `valid` (= remaining K / 8) get an
-    // out-of-range offset, for which the buffer load delivers zeros.
+    // Same for the last, partial K step: chunks at or beyond `valid` (= remaining row bytes / 16) get
+    // an out-of-range offset, for which the buffer load delivers zeros.
     __device__ __forceinline__ void issue_one_tail(char *lds, uint32_t k0, int j, int valid) const {
-        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0 * 2;
+        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
         if ((chunk_even ^ (j & 1)) >= valid) voff = 0x80000000u;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
     }
@@ -264,8 +272,9 @@ __device__ __forceinline__ float row16_allreduce(float v) {
     return v;
 }
 
-template <int BM, int BN>
-__device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
+template <int BM, int BN, bool F32>
+__device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
+    constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
     constexpr int NH = WN / 64;                                    // 64-column runs per wave tile
@@ -304,7 +313,7 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
     bool has_bias = false;
     for (int o = a.epi.n_pre - 1; o >= 0; --o) {
         const DevOp &op = a.epi.pre[o];
-        if (op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
+        if (!F32 && op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
         if (op.kind == FLE_BIAS) has_bias = true;
     }
     const bool wave_live = m_wave < M && n_wave < N;  // this wave owns at least one output
@@ -333,8 +342,8 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 
     TileLoader<BM> ldx_;
     TileLoader<BN> ldw_;
-    ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * 2, a.ldx, M - m0, a.K, wave, lane);
-    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2, a.ldw, N - n0, a.K, wave, lane);
+    ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * ES, a.ldx * ES, M - m0, a.K * ES, wave, lane);
+    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
     constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
 
     // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
@@ -353,9 +362,10 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    bf16x8 fw[2][TN], fx[2][TM];
-    const int KT = int((a.K + 63) / 64);
-    const int tail_valid = int((a.K - int64_t(KT - 1) * 64) / 8);  // 16-byte chunks of the last K step (8 = full)
+    using frag_t = typename std::conditional<F32, f32x4, bf16x8>::type;  // 16 bytes of one row: 4 fp32 or 8 bf16 along K
+    frag_t fw[2][TN], fx[2][TM];
+    const int KT = int((a.K * ES + 127) / 128);
+    const int tail_valid = int((a.K * ES - int64_t(KT - 1) * 128) / 16);  // 16-byte chunks of the last K step (8 = full)
     // One K step on stage kt & 1; ISSUE: also copy K step kt+1 into the other stage (masked to the
     // valid chunks when that is the partial last step).
     auto k_step = [&](int kt, auto issue_c) {
@@ -363,13 +373,13 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
         const int valid = kt + 2 == KT ? tail_valid : 8;
         const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
         char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
-        const uint32_t ik0 = uint32_t(kt + 1) * 64;
+        const uint32_t ik0 = uint32_t(kt + 1) * 128;  // byte column of the K step being copied
         wait_vmcnt<0>();                  // this wave's copies into the current stage have landed
         __builtin_amdgcn_s_barrier();     // everyone's have, and everyone is done reading the other stage
 #pragma unroll
-        for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
+        for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
 #pragma unroll
-        for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
+        for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -382,8 +392,8 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
             for (int q = 0; q < NMF; ++q) {
                 if (kk + 1 < 4 && q % QD == 0) {
                     const int g = q / QD;
-                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const bf16x8 *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
-                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const bf16x8 *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
+                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
+                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
                 }
                 if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
                     const int idx = kk * NVM + q / QV;
@@ -391,7 +401,15 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
                     else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                if constexpr (F32) {
+                    // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
+                    // same K permutation for both operands
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
+                } else {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -399,8 +417,8 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 
     // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y)
     const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
-    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 64, kb + 1 == KT ? tail_valid : 8);
-    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 64, kb + 1 == KT ? tail_valid : 8);
+    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
+    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
     {
         int kt = kb;
         for (; kt < ke - 1; ++kt) k_step(kt, std::true_type{});
@@ -423,7 +441,7 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
         n_col[hc] = n_wave + 64 * hc + 4 * cl;
         n_ok[hc] = n_col[hc] < N;
         bias_v[hc] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (has_bias) bias_v[hc] = ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + (n_ok[hc] ? n_col[hc] : N - 4));
+        if (has_bias) bias_v[hc] = ld4<F32>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
     }
     const int p_idx = int(n_wave / WN);
     const int64_t cols_left = N - n_wave;
@@ -512,13 +530,12 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 #pragma unroll
                         for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4_bf16(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8);
                 } else {  // a further residual operand: straight from memory, clamped to stay in bounds
-                    const uint16_t *res = reinterpret_cast<const uint16_t *>(op.p0);
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
                         const int64_t m = m_blk + 4 * it + rsub;
                         const int64_t mc = m < M ? m : M - 1;
 #pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4_bf16(res + mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<F32>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
                     }
                 }
                 break;
@@ -577,7 +594,7 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 #pragma unroll
                 for (int hc = 0; hc < NH; ++hc)
                     if (m < M && n_ok[hc]) {
-                        if (a.dst_f32)
+                        if (F32 || a.dst_f32)
                             *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]) = v[it][hc];
                         else
                             *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n_col[hc]) = __builtin_convertvector(v[it][hc], bf16x4);
@@ -588,9 +605,13 @@ __device__ __forceinline__ void gemm_bf16_tiled_body(const GemmArgs &a) {
 }
 
 // 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_bf16_tiled_body<256, 256>(a); }
+__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, false>(a); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_bf16_tiled_body<128, 128>(a); }
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, false>(a); }
+// fp32 operands on the same tiles: a K step is 32 elements and each fragment pair feeds four
+// v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
+__global__ __launch_bounds__(256) void gemm_f32_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, true>(a); }
+__global__ __launch_bounds__(256, 2) void gemm_f32_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, true>(a); }
 
 
 // ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
@@ -1060,7 +1081,7 @@ __global__ __launch_bounds__(256) void finalize_lse(const FinArgs a) {
 // ------------------------------------------------------------------ split-K reduction
 // One wave per (row, 256-column chunk), a lane per 4 consecutive columns: sums the S fp32 slabs
 // in slab order, applies the ops that precede the row op, writes the value (final, or staged
-// for the finalize pass) and, with a row op, the chunk's partial.  bf16 problems only.
+// for the finalize pass) and, with a row op, the chunk's partial.
 template <bool MAX>
 __device__ __forceinline__ float wave_allreduce(float v) {
 #pragma unroll
@@ -1075,6 +1096,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t N = a.N;
+    const bool f32 = a.epi.dtype == FLE_F32;
     const int64_t chunks = (N + 255) / 256, items = a.M * chunks;
     for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
         const int64_t row = item / chunks, c0 = (item % chunks) * 256;
@@ -1095,7 +1117,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
             for (int o = 0; o < a.epi.n_pre; ++o) {
                 const DevOp op = a.epi.pre[o];
                 switch (op.kind) {
-                case FLE_BIAS: v += ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + n); break;
+                case FLE_BIAS: v += f32 ? ld4<true>(a.epi.bias, n) : ld4<false>(a.epi.bias, n); break;
                 case FLE_SCALE: v *= op.alpha; break;
                 case FLE_RELU:
 #pragma unroll
@@ -1109,7 +1131,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
                     break;
-                case FLE_RESIDUAL: v += ld4_bf16(reinterpret_cast<const uint16_t *>(op.p0) + row * op.ld + n); break;
+                case FLE_RESIDUAL: v += f32 ? ld4<true>(op.p0, row * op.ld + n) : ld4<false>(op.p0, row * op.ld + n); break;
                 default: break;
                 }
             }
@@ -1137,7 +1159,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
             if (lane == 0) *reinterpret_cast<float2 *>(a.partials + (row * a.np + c0 / 256) * 2) = make_float2(s0, s1);
         }
         if (a.dst && ok) {
-            if (a.dst_f32)
+            if (a.dst_f32 || f32)
                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * a.ldd + n) = v;
             else
                 *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + row * a.ldd + n) = __builtin_convertvector(v, bf16x4);
@@ -1197,8 +1219,13 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
             else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), grid, dim3(256), 0, stream, g);
         }
     } else if (plan.variant == V_TILED) {
-        if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, grid, dim3(256), 0, stream, g);
-        else hipLaunchKernelGGL(gemm_bf16_tiled_128, grid, dim3(256), 0, stream, g);
+        if (bf16) {
+            if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL(gemm_bf16_tiled_128, grid, dim3(256), 0, stream, g);
+        } else {
+            if (plan.bm == 256) hipLaunchKernelGGL(gemm_f32_tiled_256, grid, dim3(256), 0, stream, g);
+            else hipLaunchKernelGGL(gemm_f32_tiled_128, grid, dim3(256), 0, stream, g);
+        }
     } else {
         // vector loads need 4-element groups that never straddle K and rows that keep the alignment
         const size_t va = bf16 ? 8 : 16;

@@ -170,13 +170,17 @@ def test_variant_selection(L):
         return buf.value.decode()
     assert "tile=256x256" in plan_of(problem(M=4096, N=4096, K=4096))
     assert "tile=128x128" in plan_of(problem(M=512, N=512, K=512))
-    assert "general" in plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))
+    assert "general" in plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))   # tiny: launch-bound, many small tiles win
+    assert "tiled_f32_mfma tile=128x128x32" in plan_of(problem(M=2048, N=2048, K=2048, dtype=binding.F32))
+    assert "tiled_f32_mfma" in plan_of(problem(M=4096, N=4096, K=4096, dtype=binding.F32))
+    assert "general" in plan_of(problem(M=2048, N=2048, K=2046, dtype=binding.F32))
     assert "general" in plan_of(problem(M=512, N=512, K=500))      # K not a multiple of 64
     p = problem(M=512, N=512, K=512); p.x = p.x + 2                # misaligned x
     assert "general" in plan_of(p)
     L.fle_force_variant(2)
     try:
-        assert validate(L, problem(M=64, N=256, K=256, dtype=binding.F32)) == E_UNSUP
+        assert validate(L, problem(M=64, N=256, K=254, dtype=binding.F32)) == E_UNSUP   # rows are not whole 16-byte chunks
+        assert validate(L, problem(M=64, N=256, K=256, dtype=binding.F32)) == OK
     finally:
         L.fle_force_variant(0)
 

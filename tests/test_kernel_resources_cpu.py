@@ -36,16 +36,16 @@ def kernel_props(asm):
 
 def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
     props = kernel_props(asm)
-    names = {k: v for k, v in props.items() if "gemm_bf16" in k}
-    assert len(names) >= 7, sorted(props)
+    names = {k: v for k, v in props.items() if "gemm_bf16" in k or "gemm_f32_tiled" in k}
+    assert len(names) >= 9, sorted(props)
     for name, p in names.items():
         assert p["scratch"] == 0, "%s spills %d bytes of scratch" % (name, p["scratch"])
         assert p["lds"] <= 160 * 1024, name
         assert p["vgpr"] <= 512, name
-    t128 = [v for k, v in names.items() if "tiled_128" in k][0]
-    assert t128["lds"] <= 80 * 1024 and t128["vgpr"] <= 256      # two workgroups per CU
-    t256 = [v for k, v in names.items() if "tiled_256" in k][0]
-    assert t256["lds"] == 160 * 1024
+    for t128 in [v for k, v in names.items() if "tiled_128" in k]:
+        assert t128["lds"] <= 80 * 1024 and t128["vgpr"] <= 256  # two workgroups per CU
+    for t256 in [v for k, v in names.items() if "tiled_256" in k]:
+        assert t256["lds"] == 160 * 1024
 
 
 def test_main_loop_uses_the_intended_instructions(asm):
@@ -53,4 +53,6 @@ def test_main_loop_uses_the_intended_instructions(asm):
     assert "v_mfma_f32_32x32x16_bf16" in body
     assert re.search(r"buffer_load_dwordx4 .* lds", body)          # direct-to-LDS copies
     assert "v_mfma_f32_16x16x4_f32" in asm                         # fp32 path stays on fp32 MFMA
+    f32_body = asm[asm.index("gemm_f32_tiled_256"):]
+    assert "v_mfma_f32_32x32x2_f32" in f32_body and "_bf16" not in f32_body[:f32_body.index("s_endpgm")]
     assert "v_pk_fma_f32" not in asm and "v_pk_mul_f32" not in asm and "v_pk_add_f32" not in asm

@@ -46,6 +46,29 @@ def test_integer_inputs_are_bit_exact(variant, M, N, K):
     assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
 
 
+@pytest.mark.parametrize("variant,split,M,N,K", [
+    ("tiled128", 0, 200, 264, 100), ("tiled256", 0, 300, 520, 36), ("tiled", 0, 130, 132, 68), ("tiled128", 3, 200, 264, 200),
+    ("tiled256", 2, 513, 772, 160), ("tiled256", 0, 2304, 1000, 64),
+])
+def test_fp32_tiled_integer_inputs_are_bit_exact(variant, split, M, N, K):
+    """The fp32 tiled kernel on small-integer operands (sums far below 2^24): bit-exact, ragged K included."""
+    prob = inputs.random_problem(14, M, N, K, F32, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("fp32 tiled integer exact", variant, split, M, N, K)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "tiled_f32_mfma" in call.plan(), call.plan()
+    rows = sample_rows(M, 128)
+    assert np.array_equal(got[rows].to(torch.float64).numpy(), oracle_rows(prob, rows)), call.plan()
+
+
+def test_fp32_large_shape_takes_the_tiled_kernel():
+    prob = inputs.random_problem(15, 1536, 2048, 1024, F32, ["bias", "gelu_erf", "layernorm"])
+    announce("fp32 tiled auto", prob.M, prob.N, prob.K)
+    got, call = run_gpu(prob)
+    assert "tiled_f32_mfma" in call.plan(), call.plan()
+    rows = sample_rows(prob.M, 48)
+    assert_close(got[rows], oracle_rows(prob, rows), F32, call.plan())
+
+
 def test_integer_exact_on_the_256_tile():
     prob = inputs.random_problem(12, 2304, 2000, 128, BF16, ["bias", "relu", "scale", "residual"], integer=True)
     announce("integer exact 256-tile", prob.M, prob.N, prob.K)
@@ -72,19 +95,21 @@ def test_split_k_integer_inputs_are_bit_exact(variant, split, M, N, K):
     assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
 
 
-SPLIT_SHAPES = [("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024)]
+SPLIT_SHAPES = [("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024),
+                ("tiled128", 3, 200, 392, 160, F32)]
 
 
-@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "%s-s%d-%dx%dx%d" % s)
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "%s-s%d-%dx%dx%d" % s[:5] + ("-f32" if len(s) > 5 else ""))
 @pytest.mark.parametrize("kinds", [[], ["bias", "gelu_erf"], ["bias", "residual", "layernorm"], ["relu", "softmax", "scale", "bias"],
                                    ["bias", "logsumexp"], ["bias", "layernorm", "gelu_tanh", "residual"]], ids=lambda k: "+".join(k) or "plain")
 def test_split_k_chains(shape, kinds):
-    variant, split, M, N, K = shape
-    prob = inputs.random_problem(4, M, N, K, BF16, kinds)
-    announce("split-K chain", variant, split, M, N, K, kinds)
+    variant, split, M, N, K = shape[:5]
+    dtype = shape[5] if len(shape) > 5 else BF16
+    prob = inputs.random_problem(4, M, N, K, dtype, kinds)
+    announce("split-K chain", variant, split, M, N, K, dtype, kinds)
     got, call = run_gpu(prob, variant, split=split)
     assert "split_k=%d " % split in call.plan(), call.plan()
-    assert_close(got, oracle_rows(prob), BF16, "%s %s" % (kinds, call.plan()))
+    assert_close(got, oracle_rows(prob), dtype, "%s %s" % (kinds, call.plan()))
 
 
 def test_split_k_is_chosen_for_few_tiles_and_long_k():
@@ -107,6 +132,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("skinny", BF16, 17, 392, 576), ("skinny", BF16, 50, 260, 192), ("skinny128", BF16, 40, 520, 640),
     ("skinny256", BF16, 32, 2304, 1024), ("general", BF16, 70, 97, 83),
     ("general", F32, 70, 97, 83), ("general", F32, 64, 256, 256), ("general", BF16, 37, 264, 96),
+    ("tiled", F32, 200, 392, 128), ("tiled256", F32, 150, 260, 100),
 ]
 
 
