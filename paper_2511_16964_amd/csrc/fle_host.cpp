@@ -114,9 +114,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, vec4) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < ld_max)) res_ok = false;
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
-    const bool tiled_ok = K >= chunk && K % chunk == 0 && N % 4 == 0 && aligned(p->x, 16) && aligned(p->w, 16) &&
-                          p->ldx % chunk == 0 && p->ldw % chunk == 0 && aligned(p->out, vec4) && (lse || p->ldo % 4 == 0) && aligned(p->b, vec4) && res_ok &&
+    // x and W rows must be whole, aligned 16-byte chunks; everything the epilogue touches may be ragged
+    // (the kernel then has an element-wise epilogue)
+    const bool tiled_ok = K >= chunk && K % chunk == 0 && aligned(p->x, 16) && aligned(p->w, 16) && p->ldx % chunk == 0 && p->ldw % chunk == 0 &&
                           p->ldx < ld_max && p->ldw < ld_max;
+    const bool vec_epi = N % 4 == 0 && (lse || (aligned(p->out, vec4) && p->ldo % 4 == 0)) && aligned(p->b, vec4) && res_ok;
     int variant = forced, forced_tile = 0;
     if (variant == V_TILED_256 || variant == V_TILED_128) {
         forced_tile = variant == V_TILED_256 ? 256 : 128;
@@ -127,7 +129,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         forced_bk = variant == V_SKINNY_128 ? 128 : 256;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && !f32 && M <= 64 && K % 64 == 0;
+    const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 64 && K % 64 == 0;
 
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
     // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
@@ -153,7 +155,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         for (int tile = 128; tile <= 256; tile += 128) {
             if (forced_tile ? tile != forced_tile : (tile == 256 && !(M > 128 && N > 128))) continue;
             for (int sp : kSplits) {
-                if (forced_split > 0 ? sp != 1 : (sp > 1 && (sp * 4 > tiled_steps || int64_t(sp) * M * N * 4 > (int64_t(128) << 20)))) continue;
+                if (forced_split > 0 ? sp != 1 : (sp > 1 && (sp * 4 > tiled_steps || int64_t(sp) * M * (N + 3) * 4 > (int64_t(128) << 20)))) continue;
                 const double t = tiled_cost(tile, sp);
                 if (!best_tile || t < best) { best = t; best_tile = tile; best_split = sp; }
             }
@@ -169,9 +171,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         } else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
     }
     if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 64, K %% 64 == 0 and everything the tiled kernel needs");
-    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs K a multiple of 16 bytes, N %% 4 == 0 and 16-byte aligned operands");
+    if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
+    plan->edge = 0;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
     if (variant == V_SKINNY) {
         plan->bm = M <= 32 ? 32 : 64;
@@ -188,6 +191,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->bm = plan->bn = best_tile;
         plan->bk = f32 ? 32 : 64;
         plan->part_cols = plan->bn / 2;  // one partial per wave column
+        plan->edge = vec_epi ? 0 : 1;
         auto_split = best_split;
     } else {
         plan->bm = plan->bn = 32;
@@ -241,11 +245,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     if (plan->split_k > 1) {
         plan->ws_slab_off = off;
-        off = round_up(off + size_t(plan->split_k) * size_t(M) * size_t(N) * sizeof(float), 256);
+        off = round_up(off + size_t(plan->split_k) * size_t(M) * size_t((N + 3) / 4 * 4) * sizeof(float), 256);
     }
     plan->ws_total = M > 0 ? off : 0;
-    snprintf(plan->text, sizeof plan->text, "variant=%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
+    snprintf(plan->text, sizeof plan->text, "variant=%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+             variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->edge ? "+edge" : "", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
              (long long)plan->tiles_n, plan->split_k, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
     return FLE_OK;
 }

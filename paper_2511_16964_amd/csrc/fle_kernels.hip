@@ -45,7 +45,9 @@ struct RedArgs {
     int64_t M, N;
     const float *slabs;  // [S][M][N] fp32
     int64_t stride;      // elements between slabs
+    int64_t ld_slab;     // elements between slab rows (N rounded up to a multiple of 4)
     int32_t S;
+    int32_t vec;         // b, residual and dst allow 4-column vector accesses
     int32_t dst_f32;
     void *dst;           // as GemmArgs::dst
     int64_t ldd;
@@ -272,7 +274,9 @@ __device__ __forceinline__ float row16_allreduce(float v) {
     return v;
 }
 
-template <int BM, int BN, bool F32>
+// EDGE: N, the leading dimensions or the addresses of b / residual / out do not allow 4-column vector
+// accesses; the epilogue then touches memory one element at a time, masked per column.
+template <int BM, int BN, bool F32, bool EDGE>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
     constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -313,7 +317,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
     bool has_bias = false;
     for (int o = a.epi.n_pre - 1; o >= 0; --o) {
         const DevOp &op = a.epi.pre[o];
-        if (!F32 && op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
+        if (!F32 && !EDGE && op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
         if (op.kind == FLE_BIAS) has_bias = true;
     }
     const bool wave_live = m_wave < M && n_wave < N;  // this wave owns at least one output
@@ -441,7 +445,15 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
         n_col[hc] = n_wave + 64 * hc + 4 * cl;
         n_ok[hc] = n_col[hc] < N;
         bias_v[hc] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (has_bias) bias_v[hc] = ld4<F32>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
+        if (has_bias) {
+            if constexpr (EDGE) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(a.epi.bias, n_col[hc] + e, F32 ? FLE_F32 : FLE_BF16);
+            } else {
+                bias_v[hc] = ld4<F32>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
+            }
+        }
     }
     const int p_idx = int(n_wave / WN);
     const int64_t cols_left = N - n_wave;
@@ -535,7 +547,15 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                         const int64_t m = m_blk + 4 * it + rsub;
                         const int64_t mc = m < M ? m : M - 1;
 #pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<F32>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                        for (int hc = 0; hc < NH; ++hc) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, F32 ? FLE_F32 : FLE_BF16);
+                            } else {
+                                v[it][hc] += ld4<F32>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                            }
+                        }
                     }
                 }
                 break;
@@ -554,7 +574,15 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                     float sum = 0.0f;
 #pragma unroll
                     for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc]) sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                        if (n_ok[hc]) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) sum += v[it][hc][e];
+                            } else {
+                                sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                            }
+                        }
                     sum = row16_allreduce<false>(sum);
                     const float mean = sum / cnt;
                     float m2 = 0.0f;
@@ -562,7 +590,8 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                     for (int hc = 0; hc < NH; ++hc)
                         if (n_ok[hc])
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
+                            for (int e = 0; e < 4; ++e)
+                                if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
                     m2 = row16_allreduce<false>(m2);
                     s0 = mean;
                     s1 = m2;
@@ -570,14 +599,23 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                     float mx = -INFINITY;
 #pragma unroll
                     for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc]) mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
+                        if (n_ok[hc]) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) mx = fmaxf(mx, v[it][hc][e]);
+                            } else {
+                                mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
+                            }
+                        }
                     mx = row16_allreduce<true>(mx);
                     float se = 0.0f;
 #pragma unroll
                     for (int hc = 0; hc < NH; ++hc)
                         if (n_ok[hc])
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) se += __expf(v[it][hc][e] - mx);
+                            for (int e = 0; e < 4; ++e)
+                                if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - mx);
                     se = row16_allreduce<false>(se);
                     s0 = mx;
                     s1 = se;
@@ -594,7 +632,11 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 #pragma unroll
                 for (int hc = 0; hc < NH; ++hc)
                     if (m < M && n_ok[hc]) {
-                        if (F32 || a.dst_f32)
+                        if constexpr (EDGE) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, (F32 || a.dst_f32) ? FLE_F32 : FLE_BF16, v[it][hc][e]);
+                        } else if (F32 || a.dst_f32)
                             *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]) = v[it][hc];
                         else
                             *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n_col[hc]) = __builtin_convertvector(v[it][hc], bf16x4);
@@ -605,13 +647,17 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 }
 
 // 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, false>(a); }
+template <bool EDGE>
+__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, false, EDGE>(a); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, false>(a); }
+template <bool EDGE>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, false, EDGE>(a); }
 // fp32 operands on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
-__global__ __launch_bounds__(256) void gemm_f32_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, true>(a); }
-__global__ __launch_bounds__(256, 2) void gemm_f32_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, true>(a); }
+template <bool EDGE>
+__global__ __launch_bounds__(256) void gemm_f32_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, true, EDGE>(a); }
+template <bool EDGE>
+__global__ __launch_bounds__(256, 2) void gemm_f32_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, true, EDGE>(a); }
 
 
 // ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
@@ -1096,15 +1142,20 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t N = a.N;
-    const bool f32 = a.epi.dtype == FLE_F32;
+    const int dtype = a.epi.dtype;
+    const bool f32 = dtype == FLE_F32;
+    const bool vec = a.vec != 0;  // 4-column vector accesses to b, residual and dst are possible
     const int64_t chunks = (N + 255) / 256, items = a.M * chunks;
     for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
         const int64_t row = item / chunks, c0 = (item % chunks) * 256;
         const int64_t n = c0 + lane * 4;
-        const bool ok = n < N;  // N % 4 == 0: a lane's four columns are all inside or all outside
+        const bool ok = n < N;  // at least the first of this lane's four columns exists
+        bool okc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) okc[e] = n + e < N;
         f32x4 v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (ok) {
-            const float *src = a.slabs + row * N + n;
+            const float *src = a.slabs + row * a.ld_slab + n;  // slab rows are padded to whole groups of four
             int s = 0;
             for (; s + 4 <= a.S; s += 4) {
                 const f32x4 u0 = *reinterpret_cast<const f32x4 *>(src + (s + 0) * a.stride);
@@ -1114,10 +1165,19 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
                 v = (((v + u0) + u1) + u2) + u3;
             }
             for (; s < a.S; ++s) v += *reinterpret_cast<const f32x4 *>(src + s * a.stride);
+            auto add4 = [&](const void *ptr, int64_t idx) {
+                if (vec) {
+                    v += f32 ? ld4<true>(ptr, idx) : ld4<false>(ptr, idx);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (okc[e]) v[e] += ld_elem(ptr, idx + e, dtype);
+                }
+            };
             for (int o = 0; o < a.epi.n_pre; ++o) {
                 const DevOp op = a.epi.pre[o];
                 switch (op.kind) {
-                case FLE_BIAS: v += f32 ? ld4<true>(a.epi.bias, n) : ld4<false>(a.epi.bias, n); break;
+                case FLE_BIAS: add4(a.epi.bias, n); break;
                 case FLE_SCALE: v *= op.alpha; break;
                 case FLE_RELU:
 #pragma unroll
@@ -1131,7 +1191,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
                     break;
-                case FLE_RESIDUAL: v += f32 ? ld4<true>(op.p0, row * op.ld + n) : ld4<false>(op.p0, row * op.ld + n); break;
+                case FLE_RESIDUAL: add4(op.p0, row * op.ld + n); break;
                 default: break;
                 }
             }
@@ -1140,29 +1200,43 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
             float s0, s1;
             if (a.epi.row_kind == FLE_LAYERNORM) {
                 const float cnt = float(N - c0 < 256 ? N - c0 : 256);
-                const float mean = wave_allreduce<false>(ok ? (v[0] + v[1]) + (v[2] + v[3]) : 0.0f) / cnt;
-                float m2 = 0.0f;
-                if (ok)
+                float sum = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) m2 += (v[e] - mean) * (v[e] - mean);
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) sum += v[e];
+                const float mean = wave_allreduce<false>(sum) / cnt;
+                float m2 = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) m2 += (v[e] - mean) * (v[e] - mean);
                 s0 = mean;
                 s1 = wave_allreduce<false>(m2);
             } else {
-                const float mx = wave_allreduce<true>(ok ? fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])) : -INFINITY);
-                float se = 0.0f;
-                if (ok)
+                float mx = -INFINITY;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) se += __expf(v[e] - mx);
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) mx = fmaxf(mx, v[e]);
+                mx = wave_allreduce<true>(mx);
+                float se = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) se += __expf(v[e] - mx);
                 s0 = mx;
                 s1 = wave_allreduce<false>(se);
             }
             if (lane == 0) *reinterpret_cast<float2 *>(a.partials + (row * a.np + c0 / 256) * 2) = make_float2(s0, s1);
         }
         if (a.dst && ok) {
-            if (a.dst_f32 || f32)
+            const bool d32 = a.dst_f32 || f32;
+            if (!vec) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) st_elem(a.dst, row * a.ldd + n + e, d32 ? FLE_F32 : FLE_BF16, v[e]);
+            } else if (d32) {
                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * a.ldd + n) = v;
-            else
+            } else {
                 *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + row * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+            }
         }
     }
 }
@@ -1198,12 +1272,14 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     if (split) {
         r.M = p->M; r.N = p->N;
         r.slabs = reinterpret_cast<const float *>(ws + plan.ws_slab_off);
-        r.stride = p->M * p->N;
+        r.ld_slab = (p->N + 3) / 4 * 4;
+        r.stride = p->M * r.ld_slab;
+        r.vec = plan.edge ? 0 : 1;
         r.S = plan.split_k;
         r.dst = g.dst; r.ldd = g.ldd; r.dst_f32 = g.dst_f32;
         r.np = plan.np; r.partials = g.partials;
         r.epi = e;
-        g.dst = ws + plan.ws_slab_off; g.ldd = p->N; g.dst_f32 = 1;
+        g.dst = ws + plan.ws_slab_off; g.ldd = r.ld_slab; g.dst_f32 = 1;
         g.split_stride = r.stride * int64_t(sizeof(float));
         g.partials = nullptr;
         g.epi.n_pre = 0; g.epi.n_post = 0; g.epi.row_kind = -1;
@@ -1219,13 +1295,12 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
             else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), grid, dim3(256), 0, stream, g);
         }
     } else if (plan.variant == V_TILED) {
-        if (bf16) {
-            if (plan.bm == 256) hipLaunchKernelGGL(gemm_bf16_tiled_256, grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL(gemm_bf16_tiled_128, grid, dim3(256), 0, stream, g);
-        } else {
-            if (plan.bm == 256) hipLaunchKernelGGL(gemm_f32_tiled_256, grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL(gemm_f32_tiled_128, grid, dim3(256), 0, stream, g);
-        }
+        // split K writes fp32 slabs with a padded leading dimension: vector stores whatever out looks like
+        const bool edge = plan.edge && !split;
+        void (*kern)(GemmArgs);
+        if (bf16) kern = plan.bm == 256 ? (edge ? gemm_bf16_tiled_256<true> : gemm_bf16_tiled_256<false>) : (edge ? gemm_bf16_tiled_128<true> : gemm_bf16_tiled_128<false>);
+        else kern = plan.bm == 256 ? (edge ? gemm_f32_tiled_256<true> : gemm_f32_tiled_256<false>) : (edge ? gemm_f32_tiled_128<true> : gemm_f32_tiled_128<false>);
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else {
         // vector loads need 4-element groups that never straddle K and rows that keep the alignment
         const size_t va = bf16 ? 8 : 16;

@@ -69,6 +69,40 @@ def test_fp32_large_shape_takes_the_tiled_kernel():
     assert_close(got[rows], oracle_rows(prob, rows), F32, call.plan())
 
 
+@pytest.mark.parametrize("variant,split,dtype,M,N,K", [
+    ("tiled", 0, BF16, 200, 263, 128), ("tiled256", 0, BF16, 300, 521, 72), ("tiled128", 3, BF16, 130, 133, 200), ("tiled256", 2, BF16, 513, 770, 256),
+    ("tiled", 0, F32, 150, 262, 100), ("tiled256", 0, F32, 290, 515, 36), ("tiled128", 2, F32, 77, 129, 160), ("tiled", 0, BF16, 64, 1, 64),
+])
+def test_ragged_n_integer_inputs_are_bit_exact(variant, split, dtype, M, N, K):
+    """N not a multiple of 4 (so rows of b, r and out are not vector-aligned either): the tiled kernels
+    switch to their element-wise epilogue; exact on integer data, with and without a split of K."""
+    prob = inputs.random_problem(16, M, N, K, dtype, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("ragged N integer exact", variant, split, dtype, M, N, K)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "+edge" in call.plan(), call.plan()
+    ref = oracle_rows(prob)
+    assert np.array_equal(ref, torch.from_numpy(ref).to(dtype).to(torch.float64).numpy()), "test premise: the exact result fits the dtype"
+    assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
+
+
+def test_misaligned_out_and_residual_take_the_edge_epilogue():
+    """N is a multiple of 4 but out and the residual start 2 bytes off a vector boundary."""
+    dev = "cuda:0"
+    prob = inputs.random_problem(23, 150, 264, 128, BF16, ["bias", "residual", "layernorm"])
+    ref = oracle_rows(prob)
+    r = prob.epilogue[1][1]
+    rstore = torch.zeros((150, 264 + 8), dtype=BF16, device=dev); rstore[:, 1:265] = to_dev(r)
+    ostore = torch.full((150, 264 + 8), -77.0, dtype=BF16, device=dev)
+    ep = dev_epilogue(prob.epilogue); ep[1] = ("residual", rstore[:, 1:265])
+    for split in (1, 2):
+        ostore.fill_(-77.0)
+        call = binding.Call(to_dev(prob.x), to_dev(prob.w), to_dev(prob.b), ep, out=ostore[:, 1:265], variant="tiled", split=split)
+        call.run(); torch.cuda.synchronize()
+        assert "+edge" in call.plan(), call.plan()
+        assert torch.all(ostore[:, 0] == -77.0) and torch.all(ostore[:, 265:] == -77.0)
+        assert_close(ostore[:, 1:265].cpu(), ref, BF16, call.plan())
+
+
 def test_integer_exact_on_the_256_tile():
     prob = inputs.random_problem(12, 2304, 2000, 128, BF16, ["bias", "relu", "scale", "residual"], integer=True)
     announce("integer exact 256-tile", prob.M, prob.N, prob.K)
@@ -133,6 +167,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("skinny256", BF16, 32, 2304, 1024), ("general", BF16, 70, 97, 83),
     ("general", F32, 70, 97, 83), ("general", F32, 64, 256, 256), ("general", BF16, 37, 264, 96),
     ("tiled", F32, 200, 392, 128), ("tiled256", F32, 150, 260, 100),
+    ("tiled", BF16, 129, 259, 64), ("tiled256", BF16, 150, 262, 136), ("tiled", F32, 100, 261, 96),
 ]
 
 
