@@ -102,9 +102,13 @@ typedef struct {
  * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL, at most one row
  * op, and nothing after LOGSUMEXP.  A second row op gives FLE_ERR_UNSUPPORTED.
  *
- * Alignment rule: no alignment is required for correctness.  The MFMA fast paths are taken
- * when x, W, out and residual pointers are 16-byte aligned, their row strides are multiples
- * of 16 bytes, N % 4 == 0 and (bf16) K % 8 == 0; other problems run on a slower general kernel.
+ * Alignment rule: no alignment is required for correctness.  The tiled MFMA kernels (bf16
+ * and fp32) are taken when x and W are 16-byte aligned and K and their row strides are
+ * multiples of 16 bytes (8 bf16 / 4 fp32 elements); N, out, b and the residual may then be
+ * ragged or misaligned (the kernel switches to an element-wise epilogue).  Other problems
+ * run on a slower general kernel.  Problems with few output tiles and a long K are split
+ * along K over several workgroups; the partial sums go through the workspace and are added
+ * in a fixed order, so the result stays reproducible.
  * `out` may alias a residual operand only exactly (same pointer and stride); it must not
  * overlap x, W, b, gamma, beta or the workspace.
  */
@@ -113,7 +117,7 @@ typedef struct {
 fle_status fle_validate(const fle_problem *p);
 
 /* Host only.  Bytes of device scratch fle_run needs for this problem (0 for purely
- * elementwise epilogues on the tiled kernels). */
+ * elementwise epilogues unless K is split). */
 fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out);
 
 /* Validates, then enqueues one to three kernels on p->stream and returns without

@@ -292,3 +292,42 @@ def test_structural_invariants_on_gpu():
     ep = list(prob.epilogue); ep[2] = ("residual", prob.epilogue[2][1][:100].contiguous())
     top, _ = run_gpu(inputs.Problem("top", BF16, prob.x[:100].contiguous(), prob.w, prob.b, ep))
     assert torch.equal(top, base[:100])
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
+    """fle_run only launches kernels (no allocation, no synchronisation, no memset), so a sequence
+    of calls can be captured once and replayed: every replay must reproduce the eager results bit
+    for bit, also after the inputs have changed and with eager work between the replays."""
+    dev = "cuda:0"
+    probs = [inputs.random_problem(41, 64, 256, 256, F32, ["bias", "gelu_erf"]),                         # general kernel
+             inputs.random_problem(42, 300, 520, 256, BF16, ["bias", "gelu_tanh", "layernorm"]),         # tiled + finalize
+             inputs.random_problem(43, 48, 2048, 2048, BF16, ["softmax"]),                               # skinny, split K, staged fp32
+             inputs.random_problem(44, 130, 263, 512, BF16, ["bias", "relu", "scale", "residual"])]      # edge epilogue
+    calls = [make_call(p) for p in probs]
+    plans = []
+    for c in calls:
+        c.run(); plans.append(c.plan())
+    torch.cuda.synchronize()
+    assert "general" in plans[0] and "tiled" in plans[1] and "skinny" in plans[2] and "split_k=1 " not in plans[2] and "+edge" in plans[3], plans
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        for c in calls:
+            c.run()
+    gen = torch.Generator().manual_seed(5)
+    for rep in range(3):
+        for c in calls:  # new x values in place: the graph reads the same buffers
+            x = c._tensors[0]
+            x.copy_(torch.randn(x.shape, generator=gen).to(x.dtype))
+        eager = [c.run().clone() for c in calls]
+        torch.cuda.synchronize()
+        for c in calls:
+            c.out.fill_(-5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        for c, ref, plan in zip(calls, eager, plans):
+            assert torch.equal(c.out, ref), "replay %d differs: %s" % (rep, plan)
+    # the last replay also agrees with the oracle on the current inputs
+    for c, p in zip(calls, probs):
+        cur = inputs.Problem("cur", p.dtype, c._tensors[0].cpu(), p.w, p.b, p.epilogue)
+        assert_close(c.out.cpu(), oracle_rows(cur), p.dtype, "graph replay vs oracle")
