@@ -164,6 +164,9 @@ __device__ __forceinline__ Stat combine_sm(const Stat &p, const Stat &q) {
 }
 
 // All lanes of a wave end up with the combination of every partial of `row`, in a fixed order.
+// LayerNorm: Chan's update, lane-serial then a butterfly.  Softmax / logsumexp: the row maximum first
+// (exact in any order), then every partial sum rescaled to it once and added lane-serially and by
+// butterfly: one exp per partial instead of two per pairwise combine.
 template <bool LN>
 __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t row, int np, int part_cols, int64_t N, int lane) {
     Stat s;
@@ -171,24 +174,77 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
     s.a = LN ? 0.0f : -INFINITY;
     s.b = 0.0f;
     const float *pr = partials + row * np * 2;
+    // a lane takes partials lane, lane + 64, ...; the loads go out in batches of 16 so that their
+    // latencies overlap (a row of a 32768-column softmax has 1024 partials, 16 per lane)
+    constexpr int B = 16;
+    if (LN) {
+        for (int p0 = 0; p0 < np; p0 += 64 * B) {
+            float2 buf[B];
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const int p = p0 + j * 64 + lane;
+                buf[j] = p < np ? *reinterpret_cast<const float2 *>(pr + 2 * p) : make_float2(0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int j = 0; j < B; ++j) {
+                const int p = p0 + j * 64 + lane;
+                if (p < np) {
+                    Stat q;
+                    const int64_t left = N - int64_t(p) * part_cols;
+                    q.n = float(left < part_cols ? left : part_cols);
+                    q.a = buf[j].x;
+                    q.b = buf[j].y;
+                    s = combine_ln(s, q);
+                }
+            }
+        }
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            Stat o;
+            o.n = __shfl_xor(s.n, d);
+            o.a = __shfl_xor(s.a, d);
+            o.b = __shfl_xor(s.b, d);
+            const bool upper = (lane & d) != 0;  // both partners combine (lower lane, upper lane): identical results
+            const Stat lo = upper ? o : s, hi = upper ? s : o;
+            s = combine_ln(lo, hi);
+        }
+        return s;
+    }
+    if (np <= 64 * B) {  // one batch: keep the partials in registers between the two sweeps
+        float2 buf[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int p = j * 64 + lane;
+            buf[j] = p < np ? *reinterpret_cast<const float2 *>(pr + 2 * p) : make_float2(-INFINITY, 0.0f);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < B; ++j) mx = fmaxf(mx, buf[j].x);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+        float sum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (buf[j].y != 0.0f) sum += buf[j].y * __expf(buf[j].x - mx);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) sum += __shfl_xor(sum, d);  // partners add the same two numbers: identical in every lane
+        s.a = mx;
+        s.b = sum;
+        return s;
+    }
+    float mx = -INFINITY;
+    for (int p = lane; p < np; p += 64) mx = fmaxf(mx, pr[2 * p]);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+    float sum = 0.0f;
     for (int p = lane; p < np; p += 64) {
-        Stat q;
-        const int64_t left = N - int64_t(p) * part_cols;
-        q.n = LN ? float(left < part_cols ? left : part_cols) : 0.0f;
-        q.a = pr[2 * p];
-        q.b = pr[2 * p + 1];
-        s = LN ? combine_ln(s, q) : combine_sm(s, q);
+        const float2 q = *reinterpret_cast<const float2 *>(pr + 2 * p);
+        if (q.y != 0.0f) sum += q.y * __expf(q.x - mx);
     }
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        Stat o;
-        o.n = __shfl_xor(s.n, d);
-        o.a = __shfl_xor(s.a, d);
-        o.b = __shfl_xor(s.b, d);
-        const bool upper = (lane & d) != 0;  // both partners combine (lower lane, upper lane): identical results
-        const Stat lo = upper ? o : s, hi = upper ? s : o;
-        s = LN ? combine_ln(lo, hi) : combine_sm(lo, hi);
-    }
+    for (int d = 1; d < 64; d <<= 1) sum += __shfl_xor(sum, d);
+    s.a = mx;
+    s.b = sum;
     return s;
 }
 
