@@ -759,7 +759,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         for (int j = 0; j < NIW; ++j) {  // this wave's own 32 rows of W
             const int row = j * RPI + lr;
             const uint32_t voff = uint32_t(wave * 32 + row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 2);
         }
 #pragma unroll
         for (int j = 0; j < NIX; ++j) {  // a quarter of the shared x tile
