@@ -174,6 +174,7 @@ def main():
 
     # ---- timing
     wall_ms, ev_ms = time_loop(torch, step, args.steps, args.warmup)
+    repeats = [ev_ms] + [time_loop(torch, step, args.steps, 0)[1] for _ in range(2)]  # spread only; `value` uses the first
     flush = torch.empty(768 << 20, dtype=torch.uint8, device=dev)
     cold_mean, cold_med, cold_min = time_cold(torch, step, 50, flush)
     tflops = flops / (wall_ms * 1e-3) / 1e12
@@ -185,6 +186,7 @@ def main():
         "config": {"workload": desc, "plan": plans, "accumulate": "fp32"},
         "pct_of_bf16_mfma_peak": 100 * tflops / PEAK_BF16_TFLOPS,
         "event_ms_per_step": ev_ms,
+        "event_ms_per_step_repeats": repeats,
         "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
                           "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }

@@ -976,6 +976,18 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
     const int64_t tile_n = blockIdx.x % a.tiles_n, tile_m = blockIdx.x / a.tiles_n;
     const int64_t m0 = tile_m * 32, n0 = tile_n * 32;
     const int dtype = BF16 ? FLE_BF16 : FLE_F32;
+    // epilogue coordinates of this lane (wave t finishes sub-tile t = 2 i + j: row m, columns n .. n+3);
+    // the bias is fetched now so that its latency hides behind the K loop (tiny problems are all latency)
+    const int ti = wave >> 1, tj = wave & 1;
+    const int64_t m = m0 + 16 * ti + r16;
+    const int64_t nb = n0 + 16 * tj;        // first column of this wave's 16-column segment
+    const int64_t n = nb + 4 * q4;
+    f32x4 bias_v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    if (a.epi.bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (n + e < N) bias_v[e] = ld_elem(a.epi.bias, n + e, dtype);
+    }
 
     f32x4 acc[2][2];
 #pragma unroll
@@ -1012,17 +1024,16 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) *reinterpret_cast<f32x4 *>(&red[wave][i * 2 + j][lane][0]) = acc[i][j];
     __syncthreads();
-    // wave t finishes sub-tile t = 2 i + j: lane owns row m, columns n .. n+3
-    const int ti = wave >> 1, tj = wave & 1;
     f32x4 v = *reinterpret_cast<const f32x4 *>(&red[0][wave][lane][0]);
 #pragma unroll
     for (int ww = 1; ww < 4; ++ww) v += *reinterpret_cast<const f32x4 *>(&red[ww][wave][lane][0]);
 
-    const int64_t m = m0 + 16 * ti + r16;
-    const int64_t nb = n0 + 16 * tj;        // first column of this wave's 16-column segment
-    const int64_t n = nb + 4 * q4;
     for (int o = 0; o < a.epi.n_pre; ++o) {
         const DevOp op = a.epi.pre[o];
+        if (op.kind == FLE_BIAS) {
+            v += bias_v;
+            continue;
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (m < M && n + e < N) v[e] = apply_op(op, v[e], m, n + e, a.epi.bias, dtype);
