@@ -129,7 +129,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         forced_bk = variant == V_SKINNY_128 ? 128 : 256;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 64 && K % 64 == 0;
+    const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 256 && K % 64 == 0;
 
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
     // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
@@ -163,27 +163,28 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     if (!best_tile) best_tile = forced_tile ? forced_tile : 128;
     if (variant == V_AUTO) {
-        if (skinny_ok && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
+        if (skinny_ok && M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
         else if (f32) {
             // the general kernel runs fp32 at about 55 TFLOP/s behind some 7 us of launch and latency
             const double general = 7.0 + 2.0 * double(M) * double(N) * double(K) / 55.0e6;
             variant = (tiled_ok && M > 0 && best < general) ? V_TILED : V_GENERAL;
         } else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
     }
-    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 64, K %% 64 == 0 and everything the tiled kernel needs");
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
     plan->edge = 0;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
     if (variant == V_SKINNY) {
-        plan->bm = M <= 32 ? 32 : 64;
+        // Row blocks of 32 with the 256-wide K step, or (forced K step 128, M > 32) blocks of 64
+        plan->bm = (M <= 32 || forced_bk != 128) ? 32 : 64;
         plan->bn = 128;
         // The widest K step that fits two stages wins on the box: 512-byte runs per W row stream at
         // 4.8 TB/s where 128-byte runs reach 3.9 TB/s.  forced 64 keeps the narrow ring for comparison.
         int bk = forced_bk ? forced_bk : 256;
         if (forced == V_SKINNY) bk = 64;
-        if (bk == 256 && M > 32) bk = 128;  // two x blocks leave room for one 256-wide stage only
+        if (bk == 256 && plan->bm > 32) bk = 128;  // two x blocks leave room for one 256-wide stage only
         while (bk > 64 && K % bk != 0) bk /= 2;
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile

@@ -747,7 +747,17 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t M = a.M, N = a.N;
-    const int64_t n0 = int64_t(blockIdx.x) * BN;
+    // Workgroup -> (W tile, block of BM rows of x).  The row blocks of one W tile get ids that differ
+    // by multiples of 8, next to each other in dispatch order: they land on the same XCD at about the
+    // same time, so W comes from HBM once and from that XCD's L2 for the other row blocks.
+    int64_t n0, m0;
+    {
+        const uint32_t bid = blockIdx.x, xcd = bid % 8, rest = bid / 8, tm = uint32_t(a.tiles_m);
+        const uint32_t tile_n = (rest / tm) * 8 + xcd;
+        if (tile_n >= uint32_t(a.tiles_n)) return;  // grid rounded up to a multiple of 8 tiles; the whole workgroup leaves
+        n0 = int64_t(tile_n) * BN;
+        m0 = int64_t(rest % tm) * BM;
+    }
 
     // Chunk c of a row is stored at position c ^ sw(row): every 16-lane group of a fragment read
     // (16 consecutive rows, one logical chunk) then covers 16 different 16-byte bank groups.
@@ -755,10 +765,11 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     const int lr = lane / CPR, lp = lane % CPR;
     __amdgpu_buffer_rsrc_t rw, rx;
     {
-        const int64_t wrows = (N - n0) < BN ? (N - n0) : BN, xrows = M < BM ? M : BM;
+        const int64_t wrows = (N - n0) < BN ? (N - n0) : BN, xrows = (M - m0) < BM ? (M - m0) : BM;
         rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2), 0,
                                                uint32_t(((wrows - 1) * a.ldw + a.K) * 2), 0x00020000);
-        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, uint32_t(((xrows - 1) * a.ldx + a.K) * 2), 0x00020000);
+        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * 2), 0,
+                                               uint32_t(((xrows - 1) * a.ldx + a.K) * 2), 0x00020000);
     }
     const uint32_t ldwb = uint32_t(a.ldw) * 2, ldxb = uint32_t(a.ldx) * 2;
     auto issue = [&](int kt) {
@@ -861,7 +872,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         case FLE_RESIDUAL:
 #pragma unroll
             for (int t = 0; t < TMB; ++t) {
-                const int64_t m = 32 * t + (lane & 31), mc = m < M ? m : M - 1;
+                const int64_t m = m0 + 32 * t + (lane & 31), mc = m < M ? m : M - 1;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const f32x4 rv = ld4_bf16(reinterpret_cast<const uint16_t *>(op.p0) + mc * op.ld + n_c[q]);
@@ -879,7 +890,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         const bool ln = a.epi.row_kind == FLE_LAYERNORM;
 #pragma unroll
         for (int t = 0; t < TMB; ++t) {
-            const int64_t m = 32 * t + (lane & 31);
+            const int64_t m = m0 + 32 * t + (lane & 31);
             float s0, s1;
             if (ln) {
                 float sum = 0.0f;
@@ -923,7 +934,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     if (a.dst) {
 #pragma unroll
         for (int t = 0; t < TMB; ++t) {
-            const int64_t m = 32 * t + (lane & 31);
+            const int64_t m = m0 + 32 * t + (lane & 31);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int64_t n = n_lane + 8 * q;
@@ -1361,7 +1372,9 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         g.partials = nullptr;
         g.epi.n_pre = 0; g.epi.n_post = 0; g.epi.row_kind = -1;
     }
-    const dim3 grid(uint32_t(plan.tiles_m * plan.tiles_n), uint32_t(plan.split_k));
+    // skinny kernel: W tiles in groups of 8 (one per XCD), each with all its row blocks
+    const int64_t wgs = plan.variant == V_SKINNY ? (plan.tiles_n + 7) / 8 * 8 * plan.tiles_m : plan.tiles_m * plan.tiles_n;
+    const dim3 grid{uint32_t(wgs), uint32_t(plan.split_k)};
     if (plan.variant == V_SKINNY) {
         if (plan.bm == 32) {
             if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), grid, dim3(256), 0, stream, g);
