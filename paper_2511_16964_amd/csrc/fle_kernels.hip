@@ -174,29 +174,14 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
     s.a = LN ? 0.0f : -INFINITY;
     s.b = 0.0f;
     const float *pr = partials + row * np * 2;
-    // a lane takes partials lane, lane + 64, ...; the loads go out in batches of 16 so that their
-    // latencies overlap (a row of a 32768-column softmax has 1024 partials, 16 per lane)
-    constexpr int B = 16;
-    if (LN) {
-        for (int p0 = 0; p0 < np; p0 += 64 * B) {
-            float2 buf[B];
-#pragma unroll
-            for (int j = 0; j < B; ++j) {
-                const int p = p0 + j * 64 + lane;
-                buf[j] = p < np ? *reinterpret_cast<const float2 *>(pr + 2 * p) : make_float2(0.0f, 0.0f);
-            }
-#pragma unroll
-            for (int j = 0; j < B; ++j) {
-                const int p = p0 + j * 64 + lane;
-                if (p < np) {
-                    Stat q;
-                    const int64_t left = N - int64_t(p) * part_cols;
-                    q.n = float(left < part_cols ? left : part_cols);
-                    q.a = buf[j].x;
-                    q.b = buf[j].y;
-                    s = combine_ln(s, q);
-                }
-            }
+    if (LN) {  // few partials per row (N / 64 or fewer): one load per lane and round
+        for (int p = lane; p < np; p += 64) {
+            Stat q;
+            const int64_t left = N - int64_t(p) * part_cols;
+            q.n = float(left < part_cols ? left : part_cols);
+            q.a = pr[2 * p];
+            q.b = pr[2 * p + 1];
+            s = combine_ln(s, q);
         }
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -210,12 +195,16 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
         }
         return s;
     }
+    // softmax / logsumexp: a lane takes partials lane, lane + 64, ...; up to 16 loads go out together so
+    // that their latencies overlap (a row of a 32768-column softmax has 1024 partials, 16 per lane)
+    constexpr int B = 16;
     if (np <= 64 * B) {  // one batch: keep the partials in registers between the two sweeps
         float2 buf[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) {
             const int p = j * 64 + lane;
-            buf[j] = p < np ? *reinterpret_cast<const float2 *>(pr + 2 * p) : make_float2(-INFINITY, 0.0f);
+            buf[j] = make_float2(-INFINITY, 0.0f);
+            if (j * 64 < np && p < np) buf[j] = *reinterpret_cast<const float2 *>(pr + 2 * p);  // outer test is wave-uniform
         }
         float mx = -INFINITY;
 #pragma unroll
@@ -225,7 +214,7 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
         float sum = 0.0f;
 #pragma unroll
         for (int j = 0; j < B; ++j)
-            if (buf[j].y != 0.0f) sum += buf[j].y * __expf(buf[j].x - mx);
+            if (j * 64 < np && buf[j].y != 0.0f) sum += buf[j].y * __expf(buf[j].x - mx);
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) sum += __shfl_xor(sum, d);  // partners add the same two numbers: identical in every lane
         s.a = mx;
@@ -1117,14 +1106,15 @@ __device__ __forceinline__ void ld8(const void *p, int64_t i, bool f32, float (&
     }
 }
 
-template <bool VEC>
+// LNK: LayerNorm (true) or softmax (false); separate kernels so that each gets its own register budget.
+template <bool VEC, bool LNK>
 __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
     constexpr int CH = 2048, IT = CH / 512;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int dtype = a.epi.dtype;
     const bool f32 = dtype == FLE_F32;
-    const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+    constexpr bool ln = LNK;
     const int64_t N = a.N;
     const int64_t chunks = (N + CH - 1) / CH, items = a.M * chunks;
     for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
@@ -1432,8 +1422,10 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     const int64_t items = p->M * ((p->N + 2047) / 2048);
     const int64_t want = (items + 3) / 4;
     const dim3 fgrid(uint32_t(want < (int64_t(1) << 20) ? want : (int64_t(1) << 20)));
-    if (vec && gb_ok) hipLaunchKernelGGL(finalize_rows<true>, fgrid, dim3(256), 0, stream, f);
-    else hipLaunchKernelGGL(finalize_rows<false>, fgrid, dim3(256), 0, stream, f);
+    void (*fin)(FinArgs);
+    if (e.row_kind == FLE_LAYERNORM) fin = (vec && gb_ok) ? finalize_rows<true, true> : finalize_rows<false, true>;
+    else fin = (vec && gb_ok) ? finalize_rows<true, false> : finalize_rows<false, false>;
+    hipLaunchKernelGGL(fin, fgrid, dim3(256), 0, stream, f);
     return check_launch("row finalize launch");
 }
 

@@ -48,6 +48,14 @@ def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
         assert t256["lds"] == 160 * 1024
 
 
+def test_streaming_finalize_keeps_its_occupancy(asm):
+    """The LayerNorm finalize pass is a bandwidth-bound streaming kernel: it needs many waves per SIMD, so
+    its register count must stay low (a shared code path once pushed it to 149 and cost 40 % of its speed)."""
+    props = kernel_props(asm)
+    ln = [v for k, v in props.items() if "finalize_rowsILb1ELb1" in k]
+    assert len(ln) == 1 and ln[0]["vgpr"] <= 96 and ln[0]["scratch"] == 0, ln
+
+
 def test_main_loop_uses_the_intended_instructions(asm):
     body = asm[asm.index("gemm_bf16_tiled_256"):]
     assert "v_mfma_f32_32x32x16_bf16" in body
