@@ -134,7 +134,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
     // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
     // with two workgroups per CU and 0.6 alone.  fp32: the matrix pipe bounds a K step at 7.8 / 3.9 /
-    // 1.95.  Filling the pipeline and the epilogue cost about 12 us (256 tile) or 6 to 8 us;
+    // 1.95.  Filling the pipeline and the epilogue cost about 15 us (256 tile) or 6 us;
     // workgroups beyond the 256 (512) that are resident at once wait for a second round; a split adds
     // a launch and 8 S M N bytes of slab traffic at about 6 TB/s (the slabs mostly stay in the
     // last-level cache).
@@ -143,7 +143,8 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
         const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
         const double per_step = f32 ? (tile == 256 ? 7.8 : wgs > 256 ? 3.9 : 1.95) : (tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6);
-        const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 8.0 : 10.0);  // in K steps
+        // in K steps; two co-resident 128 tiles hide part of each other's epilogue
+        const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 10.5 : wgs > 256 ? 7.0 : 10.0);
         double t = double(rounds) * (double((tiled_steps + sp - 1) / sp) + fixed) * per_step;
         if (sp > 1) t += 4.0 + 8.0 * double(sp) * double(M) * double(N) / 6.0e6;
         return t;
@@ -231,13 +232,19 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // ---- staging and workspace
     size_t off = 0;
     plan->staging = ST_NONE;
+    plan->stage_rel = 0;
     if (e.row_kind >= 0) {
         plan->np = int32_t((N + plan->part_cols - 1) / plan->part_cols);
         plan->ws_part_off = off;
         off = round_up(off + size_t(M) * size_t(plan->np) * 2 * sizeof(float), 256);
         if (!lse) {
-            const bool in_out = !post_res_alias_out && (e.row_kind == FLE_LAYERNORM || p->dtype == FLE_F32);
+            // Staged in out itself unless a trailing residual aliases out.  LayerNorm values survive one bf16
+            // rounding (the normalised result is O(1)); bf16 softmax stages v minus the maximum of v's partial,
+            // which is <= 0, so the rounding error of exp() stays below |d| 2^-9 with d the distance to that
+            // maximum: negligible where the probability is not.
+            const bool in_out = !post_res_alias_out;
             plan->staging = in_out ? ST_OUT : ST_WS;
+            plan->stage_rel = (in_out && e.row_kind == FLE_SOFTMAX && p->dtype == FLE_BF16) ? 1 : 0;
             if (!in_out) {
                 plan->ws_y_off = off;
                 off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);

@@ -33,6 +33,7 @@ struct GemmArgs {
     void *dst;  // where the values after the pre-ops go (nullptr: nowhere, logsumexp)
     int64_t ldd;
     int32_t dst_f32;  // dst holds fp32 regardless of the storage dtype (workspace staging)
+    int32_t dst_rel;  // softmax staged in bf16: store v - (maximum of v's partial), which is <= 0 and keeps exp() accurate
     int32_t np;       // row-reduction partials per row
     float *partials;  // [M][np][2], or nullptr without a row op
     int32_t tiles_m, tiles_n;
@@ -49,6 +50,7 @@ struct RedArgs {
     int32_t S;
     int32_t vec;         // b, residual and dst allow 4-column vector accesses
     int32_t dst_f32;
+    int32_t dst_rel;     // as GemmArgs::dst_rel
     void *dst;           // as GemmArgs::dst
     int64_t ldd;
     int32_t np;
@@ -61,6 +63,7 @@ struct FinArgs {
     const void *y;  // staged values: storage dtype (may alias out) or fp32
     int64_t ldy;
     int32_t y_f32;
+    int32_t y_rel;  // staged values are relative to the maximum of their partial (bf16 softmax)
     int32_t np, part_cols;
     const float *partials;
     void *out;
@@ -614,6 +617,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
         }
 
         // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
+        float part_max[NIT];  // softmax: the partial's maximum per row of this block
         if (a.epi.row_kind >= 0) {
             const bool ln = a.epi.row_kind == FLE_LAYERNORM;
 #pragma unroll
@@ -670,7 +674,14 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                     s0 = mx;
                     s1 = se;
                 }
+                part_max[it] = s0;
                 if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
+            }
+            if (a.dst_rel) {
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] -= part_max[it];
             }
         }
 
@@ -918,6 +929,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 s1 = se;
             }
             if (h == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + (n0 + wave * 32) / 32) * 2) = make_float2(s0, s1);
+            if (a.dst_rel) acc[t] -= s0;
         }
     }
     if (a.dst) {
@@ -1079,6 +1091,7 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
             dstp[0] = s0;
             dstp[1] = s1;
         }
+        if (a.dst_rel) v -= s0;
     }
     if (a.dst && m < M) {
 #pragma unroll
@@ -1157,8 +1170,10 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = (v[e] - sub) * mul * g[e] + be[e];
                     } else {
+                        // staged relative to the maximum of the partial the 8 columns lie in (part_cols is a multiple of 8)
+                        const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - sub) * mul;
+                        for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - shift) * mul;
                     }
                     if (a.epi.n_post > 0) {
 #pragma unroll
@@ -1177,7 +1192,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                 }
             }
         } else {
-            for (int64_t n = c0 + lane; n < c1; n += 64) {
+            auto one = [&](int64_t n) {  // one element
                 const float yv = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
                 float v;
                 if (ln) {
@@ -1185,9 +1200,56 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                     if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
                     if (a.epi.row.p1) v += ld_elem(a.epi.row.p1, n, dtype);
                 } else {
-                    v = __expf(yv - sub) * mul;
+                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
+                    v = __expf(yv - shift) * mul;
                 }
                 st_elem(a.out, row * a.ldo + n, dtype, post(v, n));
+            };
+            // bf16 rows whose staged values and outputs share their offset within a 16-byte line (always so
+            // when staged in out itself): skip h elements to the next line boundary, then whole lines as
+            // 16-byte vectors.  Chunk k takes elements h + 2048 k ... of the row, chunk 0 also the first h.
+            const uintptr_t ya = reinterpret_cast<uintptr_t>(a.y) + uintptr_t(row * a.ldy) * 2;
+            const uintptr_t oa = reinterpret_cast<uintptr_t>(a.out) + uintptr_t(row * a.ldo) * 2;
+            if (!f32 && !a.y_f32 && ((ya ^ oa) & 15) == 0 && (ya & 1) == 0) {
+                const int h = int(((16 - (ya & 15)) & 15) >> 1);
+                if (c0 == 0 && lane < h && lane < N) one(lane);
+#pragma unroll
+                for (int it = 0; it < IT; ++it) {
+                    const int64_t n = h + c0 + (it * 64 + lane) * 8;
+                    if (n + 8 <= N) {
+                        float v[8];
+                        ld8(a.y, row * a.ldy + n, false, v);
+                        if (ln) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                v[e] = (v[e] - sub) * mul;
+                                if (a.epi.row.p0) v[e] *= ld_elem(a.epi.row.p0, n + e, dtype);
+                                if (a.epi.row.p1) v[e] += ld_elem(a.epi.row.p1, n + e, dtype);
+                            }
+                        } else {
+                            float s0 = sub, s1 = sub;
+                            const int64_t p0 = n / a.part_cols, p1 = (n + 7) / a.part_cols;  // the 8 columns may straddle two partials
+                            if (a.y_rel) {
+                                s0 = sub - a.partials[(row * a.np + p0) * 2];
+                                s1 = sub - a.partials[(row * a.np + p1) * 2];
+                            }
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
+                        }
+                        if (a.epi.n_post > 0) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
+                        }
+                        bf16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
+                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.out) + row * a.ldo + n) = o;
+                    } else {
+                        for (int64_t nn = n; nn < N; ++nn) one(nn);  // the row's last, partial line (one lane at most)
+                    }
+                }
+            } else {
+                for (int64_t n = c0 + lane; n < c1; n += 64) one(n);
             }
         }
     }
@@ -1303,6 +1365,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
                 s1 = wave_allreduce<false>(se);
             }
             if (lane == 0) *reinterpret_cast<float2 *>(a.partials + (row * a.np + c0 / 256) * 2) = make_float2(s0, s1);
+            if (a.dst_rel) v -= s0;
         }
         if (a.dst && ok) {
             const bool d32 = a.dst_f32 || f32;
@@ -1340,7 +1403,7 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     g.partials = e.row_kind >= 0 ? reinterpret_cast<float *>(ws + plan.ws_part_off) : nullptr;
     g.tiles_m = int32_t(plan.tiles_m); g.tiles_n = int32_t(plan.tiles_n);
     g.epi = e;
-    if (e.row_kind < 0 || plan.staging == ST_OUT) { g.dst = p->out; g.ldd = p->ldo; g.dst_f32 = 0; }
+    if (e.row_kind < 0 || plan.staging == ST_OUT) { g.dst = p->out; g.ldd = p->ldo; g.dst_f32 = 0; g.dst_rel = plan.stage_rel; }
     else if (plan.staging == ST_WS) { g.dst = ws + plan.ws_y_off; g.ldd = p->N; g.dst_f32 = 1; }
     else { g.dst = nullptr; g.ldd = 0; g.dst_f32 = 0; }
 
@@ -1354,10 +1417,10 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         r.stride = p->M * r.ld_slab;
         r.vec = plan.edge ? 0 : 1;
         r.S = plan.split_k;
-        r.dst = g.dst; r.ldd = g.ldd; r.dst_f32 = g.dst_f32;
+        r.dst = g.dst; r.ldd = g.ldd; r.dst_f32 = g.dst_f32; r.dst_rel = g.dst_rel;
         r.np = plan.np; r.partials = g.partials;
         r.epi = e;
-        g.dst = ws + plan.ws_slab_off; g.ldd = r.ld_slab; g.dst_f32 = 1;
+        g.dst = ws + plan.ws_slab_off; g.ldd = r.ld_slab; g.dst_f32 = 1; g.dst_rel = 0;
         g.split_stride = r.stride * int64_t(sizeof(float));
         g.partials = nullptr;
         g.epi.n_pre = 0; g.epi.n_post = 0; g.epi.row_kind = -1;
@@ -1414,6 +1477,7 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     }
     if (split) { f.y = r.dst; f.ldy = r.ldd; f.y_f32 = r.dst_f32; }
     else { f.y = g.dst; f.ldy = g.ldd; f.y_f32 = g.dst_f32; }
+    f.y_rel = plan.stage_rel;
     const size_t ysz = f.y_f32 ? 4 : es;
     const bool vec = p->N % 8 == 0 && f.ldy % 8 == 0 && p->ldo % 8 == 0 && reinterpret_cast<uintptr_t>(f.y) % (8 * ysz) == 0 &&
                      reinterpret_cast<uintptr_t>(p->out) % (8 * es) == 0;

@@ -192,6 +192,34 @@ def test_both_gelu_variants_are_distinguished_in_fp32():
     assert worst > 2e-4
 
 
+@pytest.mark.parametrize("variant,split,M,N,K", [("tiled", 0, 200, 520, 128), ("tiled256", 2, 300, 776, 256), ("skinny", 0, 32, 2304, 256),
+                                                 ("general", 0, 70, 97, 83), ("tiled", 0, 150, 263, 64)])
+def test_bf16_softmax_with_wide_logits(variant, split, M, N, K):
+    """bf16 softmax is staged in out as the distance to the partial's maximum: logits with a spread of
+    several tens (scale 16 on unit-variance sums) must still come out within the bf16 tolerance."""
+    prob = inputs.random_problem(17, M, N, K, BF16, ["bias", "scale", "softmax"])
+    prob.epilogue[1] = ("scale", 16.0)
+    announce("wide softmax", variant, split, M, N, K)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "staging=out" in call.plan(), call.plan()
+    ref = oracle_rows(prob)
+    assert ref.max() > 0.5          # peaked rows: the spread is real
+    assert_close(got, ref, BF16, call.plan())
+    assert np.abs(got.to(torch.float64).numpy().sum(1) - 1.0).max() < 1e-2
+
+
+def test_softmax_followed_by_a_residual_that_aliases_out():
+    dev = "cuda:0"
+    prob = inputs.random_problem(18, 150, 264, 128, BF16, ["bias", "softmax", "residual"])
+    ref = oracle_rows(prob)
+    out = to_dev(prob.epilogue[2][1]).clone()
+    ep = dev_epilogue(prob.epilogue); ep[2] = ("residual", out)
+    call = binding.Call(to_dev(prob.x), to_dev(prob.w), to_dev(prob.b), ep, out=out)
+    call.run(); torch.cuda.synchronize()
+    assert "staging=workspace_f32" in call.plan(), call.plan()
+    assert_close(out.cpu(), ref, BF16, call.plan())
+
+
 def test_256_tile_row_ops_and_ragged_edges():
     for kinds in (["bias", "gelu_tanh", "layernorm"], ["softmax"], ["bias", "logsumexp"]):
         prob = inputs.random_problem(8, 2100, 2312, 128, BF16, kinds)
