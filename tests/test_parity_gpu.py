@@ -359,3 +359,17 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
     for c, p in zip(calls, probs):
         cur = inputs.Problem("cur", p.dtype, c._tensors[0].cpu(), p.w, p.b, p.epilogue)
         assert_close(c.out.cpu(), oracle_rows(cur), p.dtype, "graph replay vs oracle")
+
+
+@pytest.mark.parametrize("variant,M,N,K,kinds", [
+    ("skinny", 8, 33024, 64, ["softmax"]), ("skinny", 8, 33024, 64, ["bias", "logsumexp"]),     # 1032 partials per row
+    ("tiled128", 40, 4352, 64, ["bias", "gelu_tanh", "layernorm"]),                              # 68 LayerNorm partials per row
+    ("general", 5, 1100, 32, ["layernorm"]), ("general", 5, 17000, 16, ["softmax"]),            # 69 and 1063 partials
+])
+def test_rows_with_many_partials(variant, M, N, K, kinds):
+    """Rows whose partial statistics do not fit one lane each (LayerNorm: more than 64; softmax: more
+    than 1024, which leaves the register-resident batch)."""
+    prob = inputs.random_problem(19, M, N, K, BF16, kinds)
+    announce("many partials", variant, M, N, K, kinds)
+    got, call = run_gpu(prob, variant)
+    assert_close(got, oracle_rows(prob), BF16, call.plan())
