@@ -178,15 +178,14 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     plan->edge = 0;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
     if (variant == V_SKINNY) {
-        // Row blocks of 32 with the 256-wide K step, or (forced K step 128, M > 32) blocks of 64
-        plan->bm = (M <= 32 || forced_bk != 128) ? 32 : 64;
-        plan->bn = 128;
         // The widest K step that fits two stages wins on the box: 512-byte runs per W row stream at
-        // 4.8 TB/s where 128-byte runs reach 3.9 TB/s.  forced 64 keeps the narrow ring for comparison.
+        // 6.0 TB/s where 128- and 256-byte runs reach 4.5 TB/s.  forced 64 keeps the narrow ring for comparison.
         int bk = forced_bk ? forced_bk : 256;
         if (forced == V_SKINNY) bk = 64;
-        if (bk == 256 && plan->bm > 32) bk = 128;  // two x blocks leave room for one 256-wide stage only
         while (bk > 64 && K % bk != 0) bk /= 2;
+        // Row blocks of 32; blocks of 64 (two x blocks, which leave room for the 128-wide K step only) on request
+        plan->bm = (M > 32 && forced_bk == 128 && bk == 128) ? 64 : 32;
+        plan->bn = 128;
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile
     } else if (variant == V_TILED) {

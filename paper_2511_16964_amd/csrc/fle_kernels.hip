@@ -1433,9 +1433,8 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
             if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), grid, dim3(256), 0, stream, g);
             else if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<1, 128>), grid, dim3(256), 0, stream, g);
             else hipLaunchKernelGGL((gemm_bf16_skinny<1, 64>), grid, dim3(256), 0, stream, g);
-        } else {
-            if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_bf16_skinny<2, 64>), grid, dim3(256), 0, stream, g);
+        } else {  // row blocks of 64: only with the 128-wide K step (the planner never asks for another)
+            hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), grid, dim3(256), 0, stream, g);
         }
     } else if (plan.variant == V_TILED) {
         // split K writes fp32 slabs with a padded leading dimension: vector stores whatever out looks like

@@ -32,6 +32,7 @@ def test_c1_fp32_bias_gelu_erf_full():
     ("tiled", 256, 256, 64), ("tiled", 300, 520, 192), ("tiled", 128, 128, 128), ("tiled", 77, 132, 64),
     ("tiled", 513, 772, 128), ("tiled", 200, 264, 72), ("tiled", 130, 132, 200), ("tiled256", 300, 520, 8), ("tiled128", 64, 128, 24),
     ("skinny", 32, 256, 64), ("skinny", 61, 132, 128), ("skinny", 7, 2052, 1024), ("skinny128", 32, 256, 256), ("skinny256", 19, 388, 512), ("skinny128", 64, 132, 384),
+    ("skinny128", 64, 132, 320), ("skinny256", 40, 260, 192), ("skinny", 200, 388, 128),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
