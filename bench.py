@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 4.5e6, "c1": None, "c5": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
