@@ -64,6 +64,54 @@ def time_loop(torch, fn, steps, warmup):
     return wall, e0.elapsed_time(e1) / steps
 
 
+class ClockSampler:
+    """Samples the GPU's graphics clock and socket power (amdsmi) from a host thread while the timed loop
+    runs: under a sustained matrix load the chip does not hold its nominal 2.4 GHz, and the number that the
+    roofline is priced against should be read with the clock it was measured at.  Best effort: any failure
+    (library missing, no permission) just leaves the fields out."""
+
+    def __init__(self):
+        self.samples, self._stop, self._thread, self._h = [], False, None, None
+        try:
+            import amdsmi
+            amdsmi.amdsmi_init()
+            self._smi, self._h = amdsmi, amdsmi.amdsmi_get_processor_handles()[0]
+        except Exception:
+            self._h = None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                m = self._smi.amdsmi_get_gpu_metrics_info(self._h)
+                self.samples.append((m.get("current_gfxclk"), m.get("current_socket_power")))
+            except Exception:
+                return
+            time.sleep(0.02)
+
+    def __enter__(self):
+        if self._h is not None:
+            import threading
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread is not None:
+            self._thread.join(timeout=2.0)
+
+    def summary(self):
+        busy = [(c, p) for c, p in self.samples if isinstance(c, (int, float)) and c > 500]
+        if not busy:
+            return None
+        clk = [c for c, _ in busy]
+        pw = [p for _, p in busy if isinstance(p, (int, float))]
+        out = {"samples": len(busy), "gfx_clock_mhz": {"min": min(clk), "max": max(clk), "last": clk[-1]}, "nominal_mhz": 2400}
+        if pw:
+            out["socket_power_w"] = {"max": max(pw), "last": pw[-1]}
+        return out
+
+
 def time_cold(torch, fn, iters, flush):
     """Mean per-call event time with L2 and the Infinity Cache evicted before every call."""
     ts = []
@@ -173,8 +221,9 @@ def main():
         sys.exit("bench.py: GPU result fails parity against the oracle; no timing reported")
 
     # ---- timing
-    wall_ms, ev_ms = time_loop(torch, step, args.steps, args.warmup)
-    repeats = [ev_ms] + [time_loop(torch, step, args.steps, 0)[1] for _ in range(2)]  # spread only; `value` uses the first
+    with ClockSampler() as clocks:
+        wall_ms, ev_ms = time_loop(torch, step, args.steps, args.warmup)
+        repeats = [ev_ms] + [time_loop(torch, step, args.steps, 0)[1] for _ in range(2)]  # spread only; `value` uses the first
     flush = torch.empty(768 << 20, dtype=torch.uint8, device=dev)
     cold_mean, cold_med, cold_min = time_cold(torch, step, 50, flush)
     tflops = flops / (wall_ms * 1e-3) / 1e12
@@ -187,6 +236,7 @@ def main():
         "pct_of_bf16_mfma_peak": 100 * tflops / PEAK_BF16_TFLOPS,
         "event_ms_per_step": ev_ms,
         "event_ms_per_step_repeats": repeats,
+        "clocks_during_timed_loops": clocks.summary(),
         "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
                           "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
