@@ -374,3 +374,20 @@ def test_rows_with_many_partials(variant, M, N, K, kinds):
     announce("many partials", variant, M, N, K, kinds)
     got, call = run_gpu(prob, variant)
     assert_close(got, oracle_rows(prob), BF16, call.plan())
+
+
+def test_calls_on_side_streams_run_concurrently_and_independently():
+    """Two calls with their own workspaces, enqueued on two side streams (default priority), interleaved
+    several times: each must equal its result on the default stream, bit for bit."""
+    pa = inputs.random_problem(51, 300, 1032, 512, BF16, ["bias", "gelu_tanh", "layernorm"])
+    pb = inputs.random_problem(52, 48, 2048, 2048, BF16, ["softmax"])
+    ca, cb = make_call(pa), make_call(pb)
+    ra, rb = ca.run().clone(), cb.run().clone()
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(5):
+        ca.out.fill_(0); cb.out.fill_(0)
+        torch.cuda.synchronize()
+        ca.run(stream=sa); cb.run(stream=sb); ca.run(stream=sa); cb.run(stream=sb)
+        sa.synchronize(); sb.synchronize()
+        assert torch.equal(ca.out, ra) and torch.equal(cb.out, rb)
