@@ -195,7 +195,9 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->edge = vec_epi ? 0 : 1;
         auto_split = best_split;
     } else {
-        plan->bm = plan->bn = 32;
+        // 32 x 32 tiles; 16 x 16 when those would give fewer than 128 workgroups (tiny, latency-bound problems)
+        const int64_t t32 = ((M + 31) / 32) * ((N + 31) / 32);
+        plan->bm = plan->bn = t32 < 128 ? 16 : 32;
         plan->bk = 16;
         plan->part_cols = 16;
     }

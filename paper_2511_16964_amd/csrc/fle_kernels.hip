@@ -978,19 +978,22 @@ __device__ __forceinline__ f32x4 load_k4(const void *base, int64_t ld, int64_t r
     return v;
 }
 
-template <bool BF16, bool VEC>
+// T: 16 x 16 sub-tiles per side of the block tile (2: 32 x 32 outputs; 1: 16 x 16, for problems so small
+// that 32 x 32 tiles would leave most CUs without a workgroup).
+template <bool BF16, bool VEC, int T>
 __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
-    __shared__ float red[4][4][64][4];
+    constexpr int TS = 16 * T;
+    __shared__ float red[4][T * T][64][4];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q4 = lane >> 4;
     const int64_t M = a.M, N = a.N, K = a.K;
     const int64_t tile_n = blockIdx.x % a.tiles_n, tile_m = blockIdx.x / a.tiles_n;
-    const int64_t m0 = tile_m * 32, n0 = tile_n * 32;
+    const int64_t m0 = tile_m * TS, n0 = tile_n * TS;
     const int dtype = BF16 ? FLE_BF16 : FLE_F32;
     // epilogue coordinates of this lane (wave t finishes sub-tile t = 2 i + j: row m, columns n .. n+3);
     // the bias is fetched now so that its latency hides behind the K loop (tiny problems are all latency)
-    const int ti = wave >> 1, tj = wave & 1;
+    const int ti = T == 2 ? wave >> 1 : 0, tj = T == 2 ? wave & 1 : 0;  // waves beyond T * T leave after the sum
     const int64_t m = m0 + 16 * ti + r16;
     const int64_t nb = n0 + 16 * tj;        // first column of this wave's 16-column segment
     const int64_t n = nb + 4 * q4;
@@ -1001,23 +1004,23 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
             if (n + e < N) bias_v[e] = ld_elem(a.epi.bias, n + e, dtype);
     }
 
-    f32x4 acc[2][2];
+    f32x4 acc[T][T];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < T; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int j = 0; j < T; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     // This wave's k blocks are wave, wave+4, ...; four of them are loaded at once (16 independent
     // vector loads in flight) before their MFMAs run, so small problems pay one memory latency, not four.
     const int64_t KB = (K + 15) / 16;
     constexpr int U = 4;
     for (int64_t kb0 = wave; kb0 < KB; kb0 += 4 * U) {
-        f32x4 fw[U][2], fx[U][2];
+        f32x4 fw[U][T], fx[U][T];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t k = (kb0 + 4 * u) * 16 + 4 * q4;  // blocks past KB have k >= K and load zeros
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < T; ++t) {
                 fw[u][t] = load_k4<BF16, VEC>(a.w, a.ldw, n0 + 16 * t + r16, N, k, K);
                 fx[u][t] = load_k4<BF16, VEC>(a.x, a.ldx, m0 + 16 * t + r16, M, k, K);
             }
@@ -1027,15 +1030,16 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < T; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[u][j][e], fx[u][i][e], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < T; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[u][j][e], fx[u][i][e], acc[i][j], 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < T; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) *reinterpret_cast<f32x4 *>(&red[wave][i * 2 + j][lane][0]) = acc[i][j];
+        for (int j = 0; j < T; ++j) *reinterpret_cast<f32x4 *>(&red[wave][i * T + j][lane][0]) = acc[i][j];
     __syncthreads();
+    if (wave >= T * T) return;
     f32x4 v = *reinterpret_cast<const f32x4 *>(&red[0][wave][lane][0]);
 #pragma unroll
     for (int ww = 1; ww < 4; ++ww) v += *reinterpret_cast<const f32x4 *>(&red[ww][wave][lane][0]);
@@ -1448,13 +1452,15 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         const size_t va = bf16 ? 8 : 16;
         const bool vec = p->K % 4 == 0 && reinterpret_cast<uintptr_t>(p->x) % va == 0 && reinterpret_cast<uintptr_t>(p->w) % va == 0 &&
                          p->ldx % 4 == 0 && p->ldw % 4 == 0;
-        if (bf16) {
-            if (vec) hipLaunchKernelGGL((gemm_general<true, true>), grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_general<true, false>), grid, dim3(256), 0, stream, g);
+        void (*kern)(GemmArgs);
+        if (plan.bm == 32) {
+            if (bf16) kern = vec ? gemm_general<true, true, 2> : gemm_general<true, false, 2>;
+            else kern = vec ? gemm_general<false, true, 2> : gemm_general<false, false, 2>;
         } else {
-            if (vec) hipLaunchKernelGGL((gemm_general<false, true>), grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_general<false, false>), grid, dim3(256), 0, stream, g);
+            if (bf16) kern = vec ? gemm_general<true, true, 1> : gemm_general<true, false, 1>;
+            else kern = vec ? gemm_general<false, true, 1> : gemm_general<false, false, 1>;
         }
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     }
     fle_status s = check_launch("GEMM kernel launch");
     if (s == FLE_OK && split) {
