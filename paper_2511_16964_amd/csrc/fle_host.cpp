@@ -10,7 +10,9 @@
 namespace fle {
 
 static thread_local char g_error[512] = "";
-static thread_local char g_plan[200] = "";
+// The calling thread's most recent plan; its text is only formatted when fle_last_plan asks for it.
+static thread_local Plan g_plan;
+static thread_local bool g_have_plan = false;
 static thread_local int g_forced = V_AUTO;
 static thread_local int g_split = 0;
 
@@ -257,15 +259,20 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         off = round_up(off + size_t(plan->split_k) * size_t(M) * size_t((N + 3) / 4 * 4) * sizeof(float), 256);
     }
     plan->ws_total = M > 0 ? off : 0;
-    snprintf(plan->text, sizeof plan->text, "variant=%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma", plan->edge ? "+edge" : "", plan->bm, plan->bn, plan->bk, (long long)plan->tiles_m,
-             (long long)plan->tiles_n, plan->split_k, e.row_kind, plan->np, plan->staging == ST_OUT ? "out" : plan->staging == ST_WS ? "workspace_f32" : "none", plan->ws_total);
     return FLE_OK;
 }
 
 }  // namespace fle
 
 using namespace fle;
+
+static void format_plan(const Plan &plan, char *buf, size_t n) {
+    const bool f32 = plan.epi.dtype == FLE_F32;
+    snprintf(buf, n, "variant=%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+             plan.variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : plan.variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma",
+             plan.edge ? "+edge" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
+             plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
+}
 
 extern "C" {
 
@@ -280,7 +287,8 @@ fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out) {
     fle_status s = make_plan(p, g_forced, g_split, &plan);
     if (s != FLE_OK) return s;
     *bytes_out = plan.ws_total;
-    std::memcpy(g_plan, plan.text, sizeof g_plan);
+    g_plan = plan;
+    g_have_plan = true;
     return FLE_OK;
 }
 
@@ -295,7 +303,10 @@ fle_status fle_run(const fle_problem *p) {
         if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
     }
     s = launch(p, plan);
-    if (s == FLE_OK) std::memcpy(g_plan, plan.text, sizeof g_plan);
+    if (s == FLE_OK) {
+        g_plan = plan;
+        g_have_plan = true;
+    }
     return s;
 }
 
@@ -317,7 +328,8 @@ const char *fle_last_error(void) { return g_error; }
 
 fle_status fle_last_plan(char *buf, size_t n) {
     if (!buf || n == 0) return fail(FLE_ERR_NULL, "buf is NULL or empty");
-    snprintf(buf, n, "%s", g_plan);
+    if (g_have_plan) format_plan(g_plan, buf, n);
+    else buf[0] = 0;
     return FLE_OK;
 }
 

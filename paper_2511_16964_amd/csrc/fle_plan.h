@@ -50,7 +50,6 @@ struct Plan {
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
     DevEpilogue epi;
-    char text[200];
 };
 
 // Validates p (everything except workspace size) and fills plan.  Host only, no HIP calls.
