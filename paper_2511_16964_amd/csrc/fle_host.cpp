@@ -146,7 +146,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
         const double per_step = f32 ? (tile == 256 ? 7.8 : wgs > 256 ? 3.9 : 1.95) : (tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6);
         // in K steps; two co-resident 128 tiles hide part of each other's epilogue
-        const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 10.5 : wgs > 256 ? 7.0 : 10.0);
+        const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 10.5 : wgs > 256 ? 7.0 : 8.0);
         double t = double(rounds) * (double((tiled_steps + sp - 1) / sp) + fixed) * per_step;
         if (sp > 1) t += 4.0 + 8.0 * double(sp) * double(M) * double(N) / 6.0e6;
         return t;
@@ -167,11 +167,18 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     if (!best_tile) best_tile = forced_tile ? forced_tile : 128;
     if (variant == V_AUTO) {
         if (skinny_ok && M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
-        else if (f32) {
-            // the general kernel runs fp32 at about 55 TFLOP/s behind some 7 us of launch and latency
-            const double general = 7.0 + 2.0 * double(M) * double(N) * double(K) / 55.0e6;
-            variant = (tiled_ok && M > 0 && best < general) ? V_TILED : V_GENERAL;
-        } else variant = (tiled_ok && M * N >= 64 * 64) ? V_TILED : V_GENERAL;
+        else {
+            // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on
+            // fp32 operands, 45 on bf16) or, for few workgroups and a long K, the serial chain of one
+            // workgroup (1.25 us per 256 of K; up to 4 workgroups per CU are resident).
+            const int64_t gt = ((M + 31) / 32) * ((N + 31) / 32) < 128 ? 16 : 32;
+            const int64_t gw = ((M + gt - 1) / gt) * ((N + gt - 1) / gt);
+            const double chain = double((gw + 1023) / 1024) * double((K + 255) / 256) * 1.25;
+            const double rate = 2.0 * double(M) * double(N) * double(K) / (f32 ? 55.0e6 : 45.0e6);
+            const double general = 4.0 + (chain > rate ? chain : rate);
+            // a forced split only exists on the tiled and skinny kernels
+            variant = (tiled_ok && M > 0 && (best < general || forced_split > 1)) ? V_TILED : V_GENERAL;
+        }
     }
     if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");

@@ -175,7 +175,9 @@ def test_variant_selection(L):
         L.fle_last_plan(buf, 256)
         return buf.value.decode()
     assert "tile=256x256" in plan_of(problem(M=4096, N=4096, K=4096))
-    assert "tile=128x128" in plan_of(problem(M=512, N=512, K=512))
+    assert "tile=128x128" in plan_of(problem(M=1024, N=1024, K=512))
+    assert "general" in plan_of(problem(M=256, N=256, K=256)) and "tile=16x16" in plan_of(problem(M=256, N=256, K=256))   # tiny: many small tiles
+    assert "tiled" in plan_of(problem(M=128, N=256, K=4096))                                                              # few tiles, long K: split K
     assert "general" in plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))   # tiny: launch-bound, many small tiles win
     assert "tiled_f32_mfma tile=128x128x32" in plan_of(problem(M=2048, N=2048, K=2048, dtype=binding.F32))
     assert "tiled_f32_mfma" in plan_of(problem(M=4096, N=4096, K=4096, dtype=binding.F32))
@@ -222,7 +224,7 @@ def test_split_k_planning(L):
         assert split(text) == 3 and need == -(-3 * 300 * 520 * 4 // 256) * 256, text
         text, need = plan_of(problem(M=300, N=520, K=72))        # two K steps only
         assert split(text) == 2, text
-        text, need = plan_of(problem(M=64, N=256, K=256, dtype=binding.F32))
+        text, need = plan_of(problem(M=64, N=256, K=254, dtype=binding.F32))   # rows are not whole chunks: general kernel, no split
         assert "general" in text and split(text) == 1 and need == 0, text
     finally:
         L.fle_force_split(0)

@@ -332,7 +332,7 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed():
              inputs.random_problem(42, 300, 520, 256, BF16, ["bias", "gelu_tanh", "layernorm"]),         # tiled + finalize
              inputs.random_problem(43, 48, 2048, 2048, BF16, ["softmax"]),                               # skinny, split K, staged fp32
              inputs.random_problem(44, 130, 263, 512, BF16, ["bias", "relu", "scale", "residual"])]      # edge epilogue
-    calls = [make_call(p) for p in probs]
+    calls = [make_call(p, v) for p, v in zip(probs, ("auto", "tiled", "auto", "tiled"))]
     plans = []
     for c in calls:
         c.run(); plans.append(c.plan())
