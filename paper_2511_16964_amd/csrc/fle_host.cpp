@@ -169,12 +169,12 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         if (skinny_ok && M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
         else {
             // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on
-            // fp32 operands, 45 on bf16) or, for few workgroups and a long K, the serial chain of one
+            // fp32 operands, 70 on bf16) or, for few workgroups and a long K, the serial chain of one
             // workgroup (1.25 us per 256 of K; up to 4 workgroups per CU are resident).
             const int64_t gt = ((M + 31) / 32) * ((N + 31) / 32) < 128 ? 16 : 32;
             const int64_t gw = ((M + gt - 1) / gt) * ((N + gt - 1) / gt);
             const double chain = double((gw + 1023) / 1024) * double((K + 255) / 256) * 1.25;
-            const double rate = 2.0 * double(M) * double(N) * double(K) / (f32 ? 55.0e6 : 45.0e6);
+            const double rate = 2.0 * double(M) * double(N) * double(K) / (f32 ? 55.0e6 : 70.0e6);
             const double general = 4.0 + (chain > rate ? chain : rate);
             // a forced split only exists on the tiled and skinny kernels
             variant = (tiled_ok && M > 0 && (best < general || forced_split > 1)) ? V_TILED : V_GENERAL;
@@ -276,7 +276,7 @@ using namespace fle;
 static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
     snprintf(buf, n, "variant=%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             plan.variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : plan.variant == V_SKINNY ? "skinny_bf16_mfma" : "general_f32_mfma",
+             plan.variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : plan.variant == V_SKINNY ? "skinny_bf16_mfma" : (f32 ? "general_f32_mfma" : "general_bf16_mfma"),
              plan.edge ? "+edge" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
 }

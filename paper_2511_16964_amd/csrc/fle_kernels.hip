@@ -953,29 +953,44 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
 template <int TMB, int BK>
 __global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK>(a); }
 
-// ------------------------------------------------------------------ general GEMM (fp32 MFMA)
-// Block tile 32 x 32 outputs; the 4 waves split K (wave w takes 16-wide k blocks w, w+4, ...),
-// each computing the whole tile with v_mfma_f32_16x16x4_f32 (bf16 inputs are widened exactly),
-// then the partial tiles are summed through LDS in a fixed order.  A lane loads 4 consecutive k
-// of its row; MFMA number e consumes element e of every lane's vector, i.e. the k order inside
-// a block is permuted identically for both operands, which leaves the sum unchanged.
+// ------------------------------------------------------------------ general GEMM
+// Block tile 32 x 32 (or 16 x 16) outputs; the 4 waves split K (wave w takes 16-wide k blocks w,
+// w+4, ...), each computing the whole tile, then the partial tiles are summed through LDS in a
+// fixed order.  A lane loads 4 consecutive k of its row.  fp32: four v_mfma_f32_16x16x4_f32 per k
+// block, MFMA number e consuming element e of every lane's vector, i.e. the k order inside a block
+// is permuted identically for both operands, which leaves the sum unchanged.  bf16: one
+// v_mfma_f32_16x16x16_bf16 per k block on the raw values (its operand layout is exactly 4
+// consecutive k per lane).
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// 4 consecutive k of one row: fp32 values, or the raw bf16 bit patterns (zeros outside the matrix).
 template <bool BF16, bool VEC>
-__device__ __forceinline__ f32x4 load_k4(const void *base, int64_t ld, int64_t row, int64_t rows, int64_t k, int64_t K) {
-    f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (row >= rows) return v;
-    if (VEC) {
-        if (k < K) {
-            if (BF16)
-                v = ld4_bf16(reinterpret_cast<const uint16_t *>(base) + row * ld + k);
-            else
-                v = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(base) + row * ld + k);
-        }
-    } else {
+__device__ __forceinline__ auto load_k4(const void *base, int64_t ld, int64_t row, int64_t rows, int64_t k, int64_t K) {
+    if constexpr (BF16) {
+        s16x4 v = {0, 0, 0, 0};
+        if (row >= rows) return v;
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(base) + row * ld + k;
+        if (VEC) {
+            if (k < K) v = *reinterpret_cast<const s16x4 *>(src);
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (k + e < K) v[e] = ld_elem(base, row * ld + k + e, BF16 ? FLE_BF16 : FLE_F32);
+            for (int e = 0; e < 4; ++e)
+                if (k + e < K) v[e] = short(src[e]);
+        }
+        return v;
+    } else {
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row >= rows) return v;
+        const float *src = reinterpret_cast<const float *>(base) + row * ld + k;
+        if (VEC) {
+            if (k < K) v = *reinterpret_cast<const f32x4 *>(src);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (k + e < K) v[e] = src[e];
+        }
+        return v;
     }
-    return v;
 }
 
 // T: 16 x 16 sub-tiles per side of the block tile (2: 32 x 32 outputs; 1: 16 x 16, for problems so small
@@ -1015,7 +1030,8 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
     const int64_t KB = (K + 15) / 16;
     constexpr int U = 4;
     for (int64_t kb0 = wave; kb0 < KB; kb0 += 4 * U) {
-        f32x4 fw[U][T], fx[U][T];
+        using frag_t = typename std::conditional<BF16, s16x4, f32x4>::type;
+        frag_t fw[U][T], fx[U][T];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t k = (kb0 + 4 * u) * 16 + 4 * q4;  // blocks past KB have k >= K and load zeros
@@ -1026,13 +1042,21 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
             }
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
+        for (int u = 0; u < U; ++u) {
+            if constexpr (BF16) {  // one 16x16x16 bf16 step per k block: products of bf16 values are exact in fp32
 #pragma unroll
                 for (int i = 0; i < T; ++i)
 #pragma unroll
-                    for (int j = 0; j < T; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[u][j][e], fx[u][i][e], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < T; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(fw[u][j], fx[u][i], acc[i][j], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < T; ++i)
+#pragma unroll
+                        for (int j = 0; j < T; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fw[u][j][e], fx[u][i][e], acc[i][j], 0, 0, 0);
+            }
+        }
     }
 #pragma unroll
     for (int i = 0; i < T; ++i)
