@@ -16,7 +16,7 @@
  * Conventions
  *   - All tensors are row-major.  W is [N,K] (the nn.Linear weight layout).
  *   - One dtype per problem for x, W, b, residual, gamma, beta and out:
- *     FLE_F32 or FLE_BF16.  Products are accumulated in fp32, the whole
+ *     FLE_F32, FLE_BF16 or FLE_F16.  Products are accumulated in fp32, the whole
  *     epilogue runs in fp32, and the result is rounded once
  *     (round-to-nearest-even) to the output dtype.
  *   - Pointers inside fle_problem and fle_op are DEVICE pointers unless
@@ -52,7 +52,7 @@ typedef enum {
     FLE_ERR_HIP = 7          /* the HIP runtime refused a launch                         */
 } fle_status;
 
-typedef enum { FLE_F32 = 0, FLE_BF16 = 1 } fle_dtype;
+typedef enum { FLE_F32 = 0, FLE_BF16 = 1, FLE_F16 = 2 } fle_dtype;
 
 typedef enum {
     FLE_BIAS = 0,      /* v += b[n]                                  (needs problem.b)     */

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
             "layernorm": 6, "softmax": 7, "logsumexp": 8}
 MAX_OPS = 8
@@ -86,7 +86,9 @@ def _dtype_code(dt: torch.dtype) -> int:
         return F32
     if dt == torch.bfloat16:
         return BF16
-    raise TypeError("fused_linear_epilogue supports float32 and bfloat16, got %s" % dt)
+    if dt == torch.float16:
+        return F16
+    raise TypeError("fused_linear_epilogue supports float32, bfloat16 and float16, got %s" % dt)
 
 
 def _ptr(t):
@@ -198,7 +200,7 @@ class Call:
 def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):
     """out = epilogue(x @ w.T) in one fused library call.
 
-    x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32 or bfloat16).
+    x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32, bfloat16 or float16).
     epilogue: ordered list of ("bias",) ("scale", a) ("relu",) ("gelu_erf",) ("gelu_tanh",)
     ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",).
     Returns a tensor of x's dtype: [M,N], or [M] when the list ends in logsumexp.

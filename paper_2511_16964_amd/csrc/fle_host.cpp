@@ -25,7 +25,7 @@ fle_status fail(fle_status s, const char *fmt, ...) {
 }
 
 static inline bool is_row_op(int k) { return k == FLE_LAYERNORM || k == FLE_SOFTMAX || k == FLE_LOGSUMEXP; }
-static inline size_t esize(int dtype) { return dtype == FLE_BF16 ? 2 : 4; }
+static inline size_t esize(int dtype) { return dtype == FLE_F32 ? 4 : 2; }
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -44,7 +44,7 @@ static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
 fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
-    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32 or FLE_BF16", p->dtype);
+    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
     const int64_t M = p->M, N = p->N, K = p->K;
     const int64_t kLimit = int64_t(1) << 40;
     if (M < 0 || N < 1 || K < 0) return fail(FLE_ERR_SHAPE, "need M >= 0, N >= 1, K >= 0 (got %lld, %lld, %lld)", (long long)M, (long long)N, (long long)K);
@@ -180,7 +180,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
             variant = (tiled_ok && M > 0 && (best < general || forced_split > 1)) ? V_TILED : V_GENERAL;
         }
     }
-    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs bf16, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs 2-byte operands, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");
     if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
@@ -254,7 +254,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
             // maximum: negligible where the probability is not.
             const bool in_out = !post_res_alias_out;
             plan->staging = in_out ? ST_OUT : ST_WS;
-            plan->stage_rel = (in_out && e.row_kind == FLE_SOFTMAX && p->dtype == FLE_BF16) ? 1 : 0;
+            plan->stage_rel = (in_out && e.row_kind == FLE_SOFTMAX && p->dtype != FLE_F32) ? 1 : 0;
             if (!in_out) {
                 plan->ws_y_off = off;
                 off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);
@@ -275,8 +275,9 @@ using namespace fle;
 
 static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
-    snprintf(buf, n, "variant=%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             plan.variant == V_TILED ? (f32 ? "tiled_f32_mfma" : "tiled_bf16_mfma") : plan.variant == V_SKINNY ? "skinny_bf16_mfma" : (f32 ? "general_f32_mfma" : "general_bf16_mfma"),
+    const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
+    snprintf(buf, n, "variant=%s_%s_mfma%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+             plan.variant == V_TILED ? "tiled" : plan.variant == V_SKINNY ? "skinny" : "general", dt,
              plan.edge ? "+edge" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
 }

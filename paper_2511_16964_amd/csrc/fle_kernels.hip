@@ -20,6 +20,10 @@ namespace fle {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -76,12 +80,15 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as
 
 __device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype) {
     if (dtype == FLE_BF16) return bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(p)[i]);
+    if (dtype == FLE_F16) return float(reinterpret_cast<const _Float16 *>(p)[i]);
     return reinterpret_cast<const float *>(p)[i];
 }
 
 __device__ __forceinline__ void st_elem(void *p, int64_t i, int dtype, float v) {
     if (dtype == FLE_BF16)
         reinterpret_cast<__bf16 *>(p)[i] = static_cast<__bf16>(v);
+    else if (dtype == FLE_F16)
+        reinterpret_cast<_Float16 *>(p)[i] = static_cast<_Float16>(v);
     else
         reinterpret_cast<float *>(p)[i] = v;
 }
@@ -96,12 +103,27 @@ __device__ __forceinline__ f32x4 ld4_bf16(const void *p) {  // p is 8-byte align
     return r;
 }
 
-// 4 consecutive elements at element index i of p as fp32 (p + i aligned to 4 elements).
-template <bool F32>
+// 4 consecutive elements at element index i of p as fp32 (p + i aligned to 4 elements).  DT: fle_dtype.
+template <int DT>
 __device__ __forceinline__ f32x4 ld4(const void *p, int64_t i) {
-    if constexpr (F32) return *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+    if constexpr (DT == FLE_F32) return *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+    else if constexpr (DT == FLE_F16) return __builtin_convertvector(*reinterpret_cast<const f16x4 *>(reinterpret_cast<const _Float16 *>(p) + i), f32x4);
     else return ld4_bf16(reinterpret_cast<const uint16_t *>(p) + i);
 }
+__device__ __forceinline__ f32x4 ld4_rt(const void *p, int64_t i, int dtype) {  // dtype known at run time only
+    if (dtype == FLE_F32) return ld4<FLE_F32>(p, i);
+    if (dtype == FLE_F16) return ld4<FLE_F16>(p, i);
+    return ld4<FLE_BF16>(p, i);
+}
+
+// 4 fp32 values rounded (to nearest even) to a 2-byte dtype and packed into 8 bytes.
+template <int DT>
+__device__ __forceinline__ u32x2 pack4(f32x4 v) {
+    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte dtypes only");
+    if constexpr (DT == FLE_F16) return __builtin_bit_cast(u32x2, __builtin_convertvector(v, f16x4));
+    else return __builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4));
+}
+__device__ __forceinline__ u32x2 pack4_rt(f32x4 v, int dtype) { return dtype == FLE_F16 ? pack4<FLE_F16>(v) : pack4<FLE_BF16>(v); }
 
 __device__ __forceinline__ float relu_f(float v) { return v < 0.0f ? 0.0f : v; }  // NaN stays NaN
 
@@ -325,8 +347,9 @@ __device__ __forceinline__ float row16_allreduce(float v) {
 
 // EDGE: N, the leading dimensions or the addresses of b / residual / out do not allow 4-column vector
 // accesses; the epilogue then touches memory one element at a time, masked per column.
-template <int BM, int BN, bool F32, bool EDGE>
+template <int BM, int BN, int DT, bool EDGE>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
+    constexpr bool F32 = DT == FLE_F32;
     constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
@@ -415,7 +438,8 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    using frag_t = typename std::conditional<F32, f32x4, bf16x8>::type;  // 16 bytes of one row: 4 fp32 or 8 bf16 along K
+    // 16 bytes of one row: 4 fp32, 8 bf16 or 8 fp16 along K
+    using frag_t = typename std::conditional<F32, f32x4, typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type>::type;
     frag_t fw[2][TN], fx[2][TM];
     const int KT = int((a.K * ES + 127) / 128);
     const int tail_valid = int((a.K * ES - int64_t(KT - 1) * 128) / 16);  // 16-byte chunks of the last K step (8 = full)
@@ -460,6 +484,8 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
+                } else if constexpr (DT == FLE_F16) {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
                 } else {
                     acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
                 }
@@ -502,9 +528,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
             if constexpr (EDGE) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(a.epi.bias, n_col[hc] + e, F32 ? FLE_F32 : FLE_BF16);
+                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(a.epi.bias, n_col[hc] + e, DT);
             } else {
-                bias_v[hc] = ld4<F32>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
+                bias_v[hc] = ld4<DT>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
             }
         }
     }
@@ -593,7 +619,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 #pragma unroll
                     for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4_bf16(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8);
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<DT>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8, 0);
                 } else {  // a further residual operand: straight from memory, clamped to stay in bounds
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
@@ -604,9 +630,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                             if constexpr (EDGE) {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, F32 ? FLE_F32 : FLE_BF16);
+                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DT);
                             } else {
-                                v[it][hc] += ld4<F32>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                                v[it][hc] += ld4<DT>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
                             }
                         }
                     }
@@ -696,15 +722,16 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
                         if constexpr (EDGE) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, (F32 || a.dst_f32) ? FLE_F32 : FLE_BF16, v[it][hc][e]);
+                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DT, v[it][hc][e]);
                         } else if (F32 || a.dst_f32) {
                             f32x4 *q = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]);
                             if (stream_out) __builtin_nontemporal_store(v[it][hc], q);
                             else *q = v[it][hc];
                         } else {
-                            bf16x4 *q = reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n_col[hc]);
-                            if (stream_out) __builtin_nontemporal_store(__builtin_convertvector(v[it][hc], bf16x4), q);
-                            else *q = __builtin_convertvector(v[it][hc], bf16x4);
+                            u32x2 *q = reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n_col[hc]);
+                            constexpr int DT2 = F32 ? FLE_BF16 : DT;  // (this branch is never taken for fp32 problems)
+                            if (stream_out) __builtin_nontemporal_store(pack4<DT2>(v[it][hc]), q);
+                            else *q = pack4<DT2>(v[it][hc]);
                         }
                     }
             }
@@ -712,18 +739,14 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
     }
 }
 
-// 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).
-template <bool EDGE>
-__global__ __launch_bounds__(256) void gemm_bf16_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, false, EDGE>(a); }
-// 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-template <bool EDGE>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, false, EDGE>(a); }
-// fp32 operands on the same tiles: a K step is 32 elements and each fragment pair feeds four
+// 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).  DT: fle_dtype of the operands.
+// fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
-template <bool EDGE>
-__global__ __launch_bounds__(256) void gemm_f32_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, true, EDGE>(a); }
-template <bool EDGE>
-__global__ __launch_bounds__(256, 2) void gemm_f32_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, true, EDGE>(a); }
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE>(a); }
+// 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE>(a); }
 
 
 // ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
@@ -733,8 +756,10 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_tiled_128(const GemmArgs a) {
 // NST stages of (128 + 32 TMB) x 64 bf16, NST-1 of them in flight (about 100 KB of W per CU,
 // what 8 TB/s x ~2 us of latency / 256 CUs asks for).  Same swizzle and orientation as the
 // tiled kernel; the wave tile is 32 TMB x 32, so the epilogue stays in the MFMA register layout.
-template <int TMB, int BK>
+template <int TMB, int BK, int DT>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
+    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");
+    using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
     constexpr int BM = 32 * TMB, BN = 128;
     constexpr int RB = BK * 2;                 // bytes per staged row
     constexpr int CPR = BK / 8, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
@@ -799,11 +824,12 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
 #pragma unroll
         for (int kk = 0; kk < KPS; ++kk) {
             const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
-            const bf16x8 fw = *reinterpret_cast<const bf16x8 *>(sW + off);
+            const frag_t fw = *reinterpret_cast<const frag_t *>(sW + off);
 #pragma unroll
             for (int t = 0; t < TMB; ++t) {
-                const bf16x8 fx = *reinterpret_cast<const bf16x8 *>(sX + t * 32 * RB + off);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
+                const frag_t fx = *reinterpret_cast<const frag_t *>(sX + t * 32 * RB + off);
+                if constexpr (DT == FLE_F16) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[t], 0, 0, 0);
+                else acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
             }
         }
     };
@@ -840,7 +866,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         case FLE_BIAS:
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const f32x4 bv = ld4_bf16(reinterpret_cast<const uint16_t *>(a.epi.bias) + n_c[q]);
+                const f32x4 bv = ld4<DT>(a.epi.bias, n_c[q]);
 #pragma unroll
                 for (int t = 0; t < TMB; ++t)
 #pragma unroll
@@ -875,7 +901,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 const int64_t m = m0 + 32 * t + (lane & 31), mc = m < M ? m : M - 1;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const f32x4 rv = ld4_bf16(reinterpret_cast<const uint16_t *>(op.p0) + mc * op.ld + n_c[q]);
+                    const f32x4 rv = ld4<DT>(op.p0, mc * op.ld + n_c[q]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) acc[t][4 * q + e] += rv[e];
                 }
@@ -944,14 +970,14 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                     if (a.dst_f32)
                         *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n) = v;
                     else
-                        *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(dst) + m * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n) = pack4<DT>(v);
                 }
             }
         }
     }
 }
-template <int TMB, int BK>
-__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK>(a); }
+template <int TMB, int BK, int DT>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK, DT>(a); }
 
 // ------------------------------------------------------------------ general GEMM
 // Block tile 32 x 32 (or 16 x 16) outputs; the 4 waves split K (wave w takes 16-wide k blocks w,
@@ -963,7 +989,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm
 // consecutive k per lane).
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-// 4 consecutive k of one row: fp32 values, or the raw bf16 bit patterns (zeros outside the matrix).
+// 4 consecutive k of one row: fp32 values, or the raw bit patterns of a 2-byte dtype (zeros outside the matrix).
 template <bool BF16, bool VEC>
 __device__ __forceinline__ auto load_k4(const void *base, int64_t ld, int64_t row, int64_t rows, int64_t k, int64_t K) {
     if constexpr (BF16) {
@@ -995,8 +1021,9 @@ __device__ __forceinline__ auto load_k4(const void *base, int64_t ld, int64_t ro
 
 // T: 16 x 16 sub-tiles per side of the block tile (2: 32 x 32 outputs; 1: 16 x 16, for problems so small
 // that 32 x 32 tiles would leave most CUs without a workgroup).
-template <bool BF16, bool VEC, int T>
+template <int DT, bool VEC, int T>
 __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
+    constexpr bool BF16 = DT != FLE_F32;  // 2-byte operands (bf16 or fp16): raw fragments, one 16x16x16 MFMA per k block
     constexpr int TS = 16 * T;
     __shared__ float red[4][T * T][64][4];
     const int lane = threadIdx.x & 63;
@@ -1005,7 +1032,7 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
     const int64_t M = a.M, N = a.N, K = a.K;
     const int64_t tile_n = blockIdx.x % a.tiles_n, tile_m = blockIdx.x / a.tiles_n;
     const int64_t m0 = tile_m * TS, n0 = tile_n * TS;
-    const int dtype = BF16 ? FLE_BF16 : FLE_F32;
+    const int dtype = DT;
     // epilogue coordinates of this lane (wave t finishes sub-tile t = 2 i + j: row m, columns n .. n+3);
     // the bias is fetched now so that its latency hides behind the K loop (tiny problems are all latency)
     const int ti = T == 2 ? wave >> 1 : 0, tj = T == 2 ? wave & 1 : 0;  // waves beyond T * T leave after the sum
@@ -1047,7 +1074,12 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 #pragma unroll
                 for (int i = 0; i < T; ++i)
 #pragma unroll
-                    for (int j = 0; j < T; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(fw[u][j], fx[u][i], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < T; ++j) {
+                        if constexpr (DT == FLE_F16)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, fw[u][j]), __builtin_bit_cast(f16x4, fx[u][i]), acc[i][j], 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(fw[u][j], fx[u][i], acc[i][j], 0, 0, 0);
+                    }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
@@ -1133,18 +1165,38 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 // per lane, then a fixed butterfly: identical result in every lane), issues all of its
 // 16-byte loads of staged y at once, normalises, applies the trailing elementwise ops, rounds
 // and writes 16-byte vectors.
-__device__ __forceinline__ void ld8(const void *p, int64_t i, bool f32, float (&v)[8]) {  // 8 elements at index i
-    if (f32) {
+__device__ __forceinline__ void ld8(const void *p, int64_t i, int dtype, float (&v)[8]) {  // 8 elements at index i
+    if (dtype == FLE_F32) {
         const f32x4 *src = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
         const f32x4 u0 = src[0], u1 = src[1];
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[e] = u0[e]; v[4 + e] = u1[e]; }
+    } else if (dtype == FLE_F16) {
+        const f16x8 u = *reinterpret_cast<const f16x8 *>(reinterpret_cast<const _Float16 *>(p) + i);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = float(u[e]);
     } else {
         const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(p) + i);
         const uint32_t wv[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(wv[e] << 16); v[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u); }
     }
+}
+// 8 fp32 values rounded to a 2-byte dtype, stored as one 16-byte vector at element index i.
+__device__ __forceinline__ void st8_2byte(void *p, int64_t i, int dtype, const float (&v)[8]) {
+    u32x4 o;
+    if (dtype == FLE_F16) {
+        f16x8 h;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = static_cast<_Float16>(v[e]);
+        o = __builtin_bit_cast(u32x4, h);
+    } else {
+        bf16x8 h;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = static_cast<__bf16>(v[e]);
+        o = __builtin_bit_cast(u32x4, h);
+    }
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p) + i) = o;
 }
 
 // LNK: LayerNorm (true) or softmax (false); separate kernels so that each gets its own register budget.
@@ -1166,7 +1218,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
 #pragma unroll
             for (int it = 0; it < IT; ++it) {
                 const int64_t n = c0 + it * 512 + lane * 8;
-                if (n < c1) ld8(a.y, row * a.ldy + n, a.y_f32 || f32, y[it]);
+                if (n < c1) ld8(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype, y[it]);
             }
         }
         float sub, mul;  // out = (y - sub) * mul  (LayerNorm),  exp(y - sub) * mul  (softmax)
@@ -1193,8 +1245,8 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                         float g[8], be[8];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; }
-                        if (a.epi.row.p0) ld8(a.epi.row.p0, n, f32, g);
-                        if (a.epi.row.p1) ld8(a.epi.row.p1, n, f32, be);
+                        if (a.epi.row.p0) ld8(a.epi.row.p0, n, dtype, g);
+                        if (a.epi.row.p1) ld8(a.epi.row.p1, n, dtype, be);
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = (v[e] - sub) * mul * g[e] + be[e];
                     } else {
@@ -1212,10 +1264,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                         dstp[0] = f32x4{v[0], v[1], v[2], v[3]};
                         dstp[1] = f32x4{v[4], v[5], v[6], v[7]};
                     } else {
-                        bf16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
-                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.out) + row * a.ldo + n) = o;
+                        st8_2byte(a.out, row * a.ldo + n, dtype, y[it]);
                     }
                 }
             }
@@ -1246,7 +1295,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                     const int64_t n = h + c0 + (it * 64 + lane) * 8;
                     if (n + 8 <= N) {
                         float v[8];
-                        ld8(a.y, row * a.ldy + n, false, v);
+                        ld8(a.y, row * a.ldy + n, dtype, v);
                         if (ln) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) {
@@ -1268,10 +1317,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
                         }
-                        bf16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = static_cast<__bf16>(v[e]);
-                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.out) + row * a.ldo + n) = o;
+                        st8_2byte(a.out, row * a.ldo + n, dtype, v);
                     } else {
                         for (int64_t nn = n; nn < N; ++nn) one(nn);  // the row's last, partial line (one lane at most)
                     }
@@ -1335,7 +1381,7 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
             for (; s < a.S; ++s) v += *reinterpret_cast<const f32x4 *>(src + s * a.stride);
             auto add4 = [&](const void *ptr, int64_t idx) {
                 if (vec) {
-                    v += f32 ? ld4<true>(ptr, idx) : ld4<false>(ptr, idx);
+                    v += ld4_rt(ptr, idx, dtype);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
@@ -1400,11 +1446,11 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
             if (!vec) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (okc[e]) st_elem(a.dst, row * a.ldd + n + e, d32 ? FLE_F32 : FLE_BF16, v[e]);
+                    if (okc[e]) st_elem(a.dst, row * a.ldd + n + e, d32 ? FLE_F32 : dtype, v[e]);
             } else if (d32) {
                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * a.ldd + n) = v;
             } else {
-                *reinterpret_cast<bf16x4 *>(reinterpret_cast<__bf16 *>(a.dst) + row * a.ldd + n) = __builtin_convertvector(v, bf16x4);
+                *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(a.dst) + row * a.ldd + n) = pack4_rt(v, dtype);
             }
         }
     }
@@ -1421,7 +1467,7 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     hipStream_t stream = reinterpret_cast<hipStream_t>(p->stream);
     const DevEpilogue &e = plan.epi;
     char *ws = reinterpret_cast<char *>(p->workspace);
-    const bool bf16 = p->dtype == FLE_BF16;
+    const bool bf16 = p->dtype != FLE_F32;  // 2-byte operands (bf16 or fp16)
     const size_t es = bf16 ? 2 : 4;
 
     GemmArgs g{};
@@ -1457,33 +1503,38 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
     const int64_t wgs = plan.variant == V_SKINNY ? (plan.tiles_n + 7) / 8 * 8 * plan.tiles_m : plan.tiles_m * plan.tiles_n;
     const dim3 grid{uint32_t(wgs), uint32_t(plan.split_k)};
     if (plan.variant == V_SKINNY) {
-        if (plan.bm == 32) {
-            if (plan.bk == 256) hipLaunchKernelGGL((gemm_bf16_skinny<1, 256>), grid, dim3(256), 0, stream, g);
-            else if (plan.bk == 128) hipLaunchKernelGGL((gemm_bf16_skinny<1, 128>), grid, dim3(256), 0, stream, g);
-            else hipLaunchKernelGGL((gemm_bf16_skinny<1, 64>), grid, dim3(256), 0, stream, g);
-        } else {  // row blocks of 64: only with the 128-wide K step (the planner never asks for another)
-            hipLaunchKernelGGL((gemm_bf16_skinny<2, 128>), grid, dim3(256), 0, stream, g);
-        }
+        auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
+            constexpr int DT = decltype(dt_c)::value;
+            if (plan.bm == 32) return plan.bk == 256 ? gemm_bf16_skinny<1, 256, DT> : plan.bk == 128 ? gemm_bf16_skinny<1, 128, DT> : gemm_bf16_skinny<1, 64, DT>;
+            return gemm_bf16_skinny<2, 128, DT>;  // row blocks of 64: only with the 128-wide K step (the planner never asks for another)
+        };
+        void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else if (plan.variant == V_TILED) {
         // split K writes fp32 slabs with a padded leading dimension: vector stores whatever out looks like
         const bool edge = plan.edge && !split;
         void (*kern)(GemmArgs);
-        if (bf16) kern = plan.bm == 256 ? (edge ? gemm_bf16_tiled_256<true> : gemm_bf16_tiled_256<false>) : (edge ? gemm_bf16_tiled_128<true> : gemm_bf16_tiled_128<false>);
-        else kern = plan.bm == 256 ? (edge ? gemm_f32_tiled_256<true> : gemm_f32_tiled_256<false>) : (edge ? gemm_f32_tiled_128<true> : gemm_f32_tiled_128<false>);
+        auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
+            constexpr int DT = decltype(dt_c)::value;
+            if (plan.bm == 256) return edge ? gemm_tiled_256<DT, true> : gemm_tiled_256<DT, false>;
+            return edge ? gemm_tiled_128<DT, true> : gemm_tiled_128<DT, false>;
+        };
+        if (p->dtype == FLE_F32) kern = pick(std::integral_constant<int, FLE_F32>{});
+        else if (p->dtype == FLE_F16) kern = pick(std::integral_constant<int, FLE_F16>{});
+        else kern = pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else {
         // vector loads need 4-element groups that never straddle K and rows that keep the alignment
         const size_t va = bf16 ? 8 : 16;
         const bool vec = p->K % 4 == 0 && reinterpret_cast<uintptr_t>(p->x) % va == 0 && reinterpret_cast<uintptr_t>(p->w) % va == 0 &&
                          p->ldx % 4 == 0 && p->ldw % 4 == 0;
-        void (*kern)(GemmArgs);
-        if (plan.bm == 32) {
-            if (bf16) kern = vec ? gemm_general<true, true, 2> : gemm_general<true, false, 2>;
-            else kern = vec ? gemm_general<false, true, 2> : gemm_general<false, false, 2>;
-        } else {
-            if (bf16) kern = vec ? gemm_general<true, true, 1> : gemm_general<true, false, 1>;
-            else kern = vec ? gemm_general<false, true, 1> : gemm_general<false, false, 1>;
-        }
+        auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
+            constexpr int DT = decltype(dt_c)::value;
+            if (plan.bm == 32) return vec ? gemm_general<DT, true, 2> : gemm_general<DT, false, 2>;
+            return vec ? gemm_general<DT, true, 1> : gemm_general<DT, false, 1>;
+        };
+        void (*kern)(GemmArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
+                                 : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     }
     fle_status s = check_launch("GEMM kernel launch");

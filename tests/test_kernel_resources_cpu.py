@@ -36,8 +36,8 @@ def kernel_props(asm):
 
 def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
     props = kernel_props(asm)
-    names = {k: v for k, v in props.items() if "gemm_bf16" in k or "gemm_f32_tiled" in k}
-    assert len(names) >= 9, sorted(props)
+    names = {k: v for k, v in props.items() if "gemm_bf16_skinny" in k or "gemm_tiled_" in k}
+    assert len(names) == 8 + 12, sorted(props)   # skinny: 4 shapes x 2 dtypes; tiled: 2 tiles x 3 dtypes x 2 epilogues
     for name, p in names.items():
         assert p["scratch"] == 0, "%s spills %d bytes of scratch" % (name, p["scratch"])
         assert p["lds"] <= 160 * 1024, name
@@ -57,10 +57,11 @@ def test_streaming_finalize_keeps_its_occupancy(asm):
 
 
 def test_main_loop_uses_the_intended_instructions(asm):
-    body = asm[asm.index("gemm_bf16_tiled_256"):]
-    assert "v_mfma_f32_32x32x16_bf16" in body
+    body = asm
+    assert "v_mfma_f32_32x32x16_bf16" in body and "v_mfma_f32_32x32x16_f16" in body
     assert re.search(r"buffer_load_dwordx4 .* lds", body)          # direct-to-LDS copies
     assert "v_mfma_f32_16x16x4_f32" in asm                         # fp32 path stays on fp32 MFMA
-    f32_body = asm[asm.index("gemm_f32_tiled_256"):]
-    assert "v_mfma_f32_32x32x2_f32" in f32_body and "_bf16" not in f32_body[:f32_body.index("s_endpgm")]
+    m = re.search(r"^_ZN3fle14gemm_tiled_256ILi0ELb0EEEvNS_8GemmArgsE:(.*?)s_endpgm", asm, flags=re.S | re.M)   # fp32 operands
+    assert m and "v_mfma_f32_32x32x2_f32" in m.group(1) and "_bf16" not in m.group(1) and "x16_f16" not in m.group(1)
+    assert "v_mfma_f32_16x16x16_bf16" in asm and "v_mfma_f32_16x16x16_f16" in asm   # general kernel on 2-byte operands
     assert "v_pk_fma_f32" not in asm and "v_pk_mul_f32" not in asm and "v_pk_add_f32" not in asm

@@ -11,7 +11,7 @@ from parity import TOL, assert_close, make_call, oracle_rows, run_gpu, sample_ro
 
 pytestmark = pytest.mark.gpu
 
-F32, BF16 = torch.float32, torch.bfloat16
+F32, BF16, F16 = torch.float32, torch.bfloat16, torch.float16
 
 
 def announce(*a):
@@ -104,6 +104,21 @@ def test_misaligned_out_and_residual_take_the_edge_epilogue():
         assert_close(ostore[:, 1:265].cpu(), ref, BF16, call.plan())
 
 
+@pytest.mark.parametrize("variant,split,M,N,K", [
+    ("tiled128", 0, 200, 264, 200), ("tiled256", 0, 300, 520, 72), ("tiled256", 3, 513, 772, 320), ("tiled", 0, 130, 133, 64),
+    ("skinny", 0, 61, 132, 128), ("skinny256", 2, 19, 388, 512), ("skinny128", 0, 64, 132, 384), ("general", 0, 77, 45, 50), ("general", 0, 300, 264, 64),
+])
+def test_fp16_integer_inputs_are_bit_exact(variant, split, M, N, K):
+    """fp16 operands (v_mfma_f32_32x32x16_f16 / 16x16x16_f16): exact on small integers through every kernel."""
+    prob = inputs.random_problem(20, M, N, K, F16, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("fp16 integer exact", variant, split, M, N, K)
+    got, call = run_gpu(prob, variant, split=split)
+    assert "_f16_" in call.plan(), call.plan()
+    ref = oracle_rows(prob)
+    assert np.array_equal(ref, torch.from_numpy(ref).to(F16).to(torch.float64).numpy()), "test premise: the exact result fits fp16"
+    assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
+
+
 def test_integer_exact_on_the_256_tile():
     prob = inputs.random_problem(12, 2304, 2000, 128, BF16, ["bias", "relu", "scale", "residual"], integer=True)
     announce("integer exact 256-tile", prob.M, prob.N, prob.K)
@@ -131,10 +146,10 @@ def test_split_k_integer_inputs_are_bit_exact(variant, split, M, N, K):
 
 
 SPLIT_SHAPES = [("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024),
-                ("tiled128", 3, 200, 392, 160, F32)]
+                ("tiled128", 3, 200, 392, 160, F32), ("tiled128", 2, 200, 392, 256, F16), ("skinny", 2, 32, 2304, 256, F16)]
 
 
-@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "%s-s%d-%dx%dx%d" % s[:5] + ("-f32" if len(s) > 5 else ""))
+@pytest.mark.parametrize("shape", SPLIT_SHAPES, ids=lambda s: "%s-s%d-%dx%dx%d" % s[:5] + ("-" + str(s[5])[6:] if len(s) > 5 else ""))
 @pytest.mark.parametrize("kinds", [[], ["bias", "gelu_erf"], ["bias", "residual", "layernorm"], ["relu", "softmax", "scale", "bias"],
                                    ["bias", "logsumexp"], ["bias", "layernorm", "gelu_tanh", "residual"]], ids=lambda k: "+".join(k) or "plain")
 def test_split_k_chains(shape, kinds):
@@ -169,6 +184,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("general", F32, 70, 97, 83), ("general", F32, 64, 256, 256), ("general", BF16, 37, 264, 96),
     ("tiled", F32, 200, 392, 128), ("tiled256", F32, 150, 260, 100),
     ("tiled", BF16, 129, 259, 64), ("tiled256", BF16, 150, 262, 136), ("tiled", F32, 100, 261, 96),
+    ("tiled", F16, 200, 392, 128), ("tiled256", F16, 150, 262, 136), ("skinny", F16, 32, 2304, 256), ("general", F16, 70, 97, 83),
 ]
 
 
