@@ -1,0 +1,264 @@
+// Device-side types and helpers shared by every libfle kernel: vector types, kernel argument structs,
+// dtype-aware loads and stores, the elementwise ops, and the row-reduction partials.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "fle_plan.h"
+
+namespace fle {
+
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) void lds_void;
+
+struct GemmArgs {
+    int64_t M, N, K;
+    const void *x;
+    int64_t ldx;
+    const void *w;
+    int64_t ldw;
+    void *dst;  // where the values after the pre-ops go (nullptr: nowhere, logsumexp)
+    int64_t ldd;
+    int32_t dst_f32;  // dst holds fp32 regardless of the storage dtype (workspace staging)
+    int32_t dst_rel;  // softmax staged in bf16: store v - (maximum of v's partial), which is <= 0 and keeps exp() accurate
+    int32_t np;       // row-reduction partials per row
+    float *partials;  // [M][np][2], or nullptr without a row op
+    int32_t tiles_m, tiles_n;
+    int64_t split_stride;  // split K (gridDim.y > 1): workgroup row y owns a K range and writes dst + y * split_stride bytes
+    DevEpilogue epi;
+};
+
+// Sum of the split-K slabs followed by the ops before the row op (reduce_slabs).
+struct RedArgs {
+    int64_t M, N;
+    const float *slabs;  // [S][M][N] fp32
+    int64_t stride;      // elements between slabs
+    int64_t ld_slab;     // elements between slab rows (N rounded up to a multiple of 4)
+    int32_t S;
+    int32_t vec;         // b, residual and dst allow 4-column vector accesses
+    int32_t dst_f32;
+    int32_t dst_rel;     // as GemmArgs::dst_rel
+    void *dst;           // as GemmArgs::dst
+    int64_t ldd;
+    int32_t np;
+    float *partials;     // one partial per (row, 256 columns)
+    DevEpilogue epi;
+};
+
+struct FinArgs {
+    int64_t M, N;
+    const void *y;  // staged values: storage dtype (may alias out) or fp32
+    int64_t ldy;
+    int32_t y_f32;
+    int32_t y_rel;  // staged values are relative to the maximum of their partial (bf16 softmax)
+    int32_t np, part_cols;
+    const float *partials;
+    void *out;
+    int64_t ldo;
+    DevEpilogue epi;
+};
+
+// ------------------------------------------------------------------ scalar helpers
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ float ld_elem(const void *p, int64_t i, int dtype) {
+    if (dtype == FLE_BF16) return bf16_bits_to_f32(reinterpret_cast<const uint16_t *>(p)[i]);
+    if (dtype == FLE_F16) return float(reinterpret_cast<const _Float16 *>(p)[i]);
+    return reinterpret_cast<const float *>(p)[i];
+}
+
+__device__ __forceinline__ void st_elem(void *p, int64_t i, int dtype, float v) {
+    if (dtype == FLE_BF16)
+        reinterpret_cast<__bf16 *>(p)[i] = static_cast<__bf16>(v);
+    else if (dtype == FLE_F16)
+        reinterpret_cast<_Float16 *>(p)[i] = static_cast<_Float16>(v);
+    else
+        reinterpret_cast<float *>(p)[i] = v;
+}
+
+__device__ __forceinline__ f32x4 ld4_bf16(const void *p) {  // p is 8-byte aligned
+    const uint2 u = *reinterpret_cast<const uint2 *>(p);
+    f32x4 r;
+    r[0] = __uint_as_float(u.x << 16);
+    r[1] = __uint_as_float(u.x & 0xffff0000u);
+    r[2] = __uint_as_float(u.y << 16);
+    r[3] = __uint_as_float(u.y & 0xffff0000u);
+    return r;
+}
+
+// 4 consecutive elements at element index i of p as fp32 (p + i aligned to 4 elements).  DT: fle_dtype.
+template <int DT>
+__device__ __forceinline__ f32x4 ld4(const void *p, int64_t i) {
+    if constexpr (DT == FLE_F32) return *reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+    else if constexpr (DT == FLE_F16) return __builtin_convertvector(*reinterpret_cast<const f16x4 *>(reinterpret_cast<const _Float16 *>(p) + i), f32x4);
+    else return ld4_bf16(reinterpret_cast<const uint16_t *>(p) + i);
+}
+__device__ __forceinline__ f32x4 ld4_rt(const void *p, int64_t i, int dtype) {  // dtype known at run time only
+    if (dtype == FLE_F32) return ld4<FLE_F32>(p, i);
+    if (dtype == FLE_F16) return ld4<FLE_F16>(p, i);
+    return ld4<FLE_BF16>(p, i);
+}
+
+// 4 fp32 values rounded (to nearest even) to a 2-byte dtype and packed into 8 bytes.
+template <int DT>
+__device__ __forceinline__ u32x2 pack4(f32x4 v) {
+    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte dtypes only");
+    if constexpr (DT == FLE_F16) return __builtin_bit_cast(u32x2, __builtin_convertvector(v, f16x4));
+    else return __builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4));
+}
+__device__ __forceinline__ u32x2 pack4_rt(f32x4 v, int dtype) { return dtype == FLE_F16 ? pack4<FLE_F16>(v) : pack4<FLE_BF16>(v); }
+
+__device__ __forceinline__ float relu_f(float v) { return v < 0.0f ? 0.0f : v; }  // NaN stays NaN
+
+// GELU with the exact-erf definition.  erfc(|x|) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2),
+// t = 1 / (1 + p |x|)  (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7), and
+// 1 + erf(x) = erfc(|x|) for x < 0, 2 - erfc(|x|) otherwise: no cancellation in the left tail.
+__device__ __forceinline__ float gelu_erf_f(float v) {
+    const float x = fabsf(v) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    const float c = p * t * __expf(-x * x);
+    return 0.5f * v * (v < 0.0f ? c : 2.0f - c);
+}
+
+// 0.5 v (1 + tanh u) == v / (1 + exp(-2u)),  u = sqrt(2/pi) (v + 0.044715 v^3)
+__device__ __forceinline__ float gelu_tanh_f(float v) {
+    const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
+    return v * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+}
+
+// One elementwise op on one value at (m, n).
+__device__ __forceinline__ float apply_op(const DevOp &op, float v, int64_t m, int64_t n, const void *bias, int dtype) {
+    switch (op.kind) {
+    case FLE_BIAS: return v + ld_elem(bias, n, dtype);
+    case FLE_SCALE: return v * op.alpha;
+    case FLE_RELU: return relu_f(v);
+    case FLE_GELU_ERF: return gelu_erf_f(v);
+    case FLE_GELU_TANH: return gelu_tanh_f(v);
+    case FLE_RESIDUAL: return v + ld_elem(op.p0, m * op.ld + n, dtype);
+    default: return v;
+    }
+}
+
+// ------------------------------------------------------------------ row-reduction partials
+// LayerNorm partial over c values: (mean, M2 = sum (v - mean)^2); the count is implied by the
+// partial's position.  Softmax / logsumexp partial: (max, sum exp(v - max)).
+struct Stat {
+    float n, a, b;  // n = count (LayerNorm only); (a, b) = (mean, M2) or (max, sum)
+};
+
+__device__ __forceinline__ Stat combine_ln(const Stat &p, const Stat &q) {
+    if (q.n == 0.0f) return p;
+    if (p.n == 0.0f) return q;
+    Stat r;
+    r.n = p.n + q.n;
+    const float d = q.a - p.a;
+    r.a = p.a + d * (q.n / r.n);
+    r.b = p.b + q.b + d * d * (p.n * q.n / r.n);
+    return r;
+}
+
+__device__ __forceinline__ Stat combine_sm(const Stat &p, const Stat &q) {
+    Stat r;
+    r.n = 0.0f;
+    r.a = fmaxf(p.a, q.a);
+    const float sp = p.b == 0.0f ? 0.0f : p.b * __expf(p.a - r.a);
+    const float sq = q.b == 0.0f ? 0.0f : q.b * __expf(q.a - r.a);
+    r.b = sp + sq;
+    return r;
+}
+
+// All lanes of a wave end up with the combination of every partial of `row`, in a fixed order.
+// LayerNorm: Chan's update, lane-serial then a butterfly.  Softmax / logsumexp: the row maximum first
+// (exact in any order), then every partial sum rescaled to it once and added lane-serially and by
+// butterfly: one exp per partial instead of two per pairwise combine.
+template <bool LN>
+__device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t row, int np, int part_cols, int64_t N, int lane) {
+    Stat s;
+    s.n = 0.0f;
+    s.a = LN ? 0.0f : -INFINITY;
+    s.b = 0.0f;
+    const float *pr = partials + row * np * 2;
+    if (LN) {  // few partials per row (N / 64 or fewer): one load per lane and round
+        for (int p = lane; p < np; p += 64) {
+            Stat q;
+            const int64_t left = N - int64_t(p) * part_cols;
+            q.n = float(left < part_cols ? left : part_cols);
+            q.a = pr[2 * p];
+            q.b = pr[2 * p + 1];
+            s = combine_ln(s, q);
+        }
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            Stat o;
+            o.n = __shfl_xor(s.n, d);
+            o.a = __shfl_xor(s.a, d);
+            o.b = __shfl_xor(s.b, d);
+            const bool upper = (lane & d) != 0;  // both partners combine (lower lane, upper lane): identical results
+            const Stat lo = upper ? o : s, hi = upper ? s : o;
+            s = combine_ln(lo, hi);
+        }
+        return s;
+    }
+    // softmax / logsumexp: a lane takes partials lane, lane + 64, ...; up to 16 loads go out together so
+    // that their latencies overlap (a row of a 32768-column softmax has 1024 partials, 16 per lane)
+    constexpr int B = 16;
+    if (np <= 64 * B) {  // one batch: keep the partials in registers between the two sweeps
+        float2 buf[B];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int p = j * 64 + lane;
+            buf[j] = make_float2(-INFINITY, 0.0f);
+            if (j * 64 < np && p < np) buf[j] = *reinterpret_cast<const float2 *>(pr + 2 * p);  // outer test is wave-uniform
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < B; ++j) mx = fmaxf(mx, buf[j].x);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+        float sum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            if (j * 64 < np && buf[j].y != 0.0f) sum += buf[j].y * __expf(buf[j].x - mx);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) sum += __shfl_xor(sum, d);  // partners add the same two numbers: identical in every lane
+        s.a = mx;
+        s.b = sum;
+        return s;
+    }
+    float mx = -INFINITY;
+    for (int p = lane; p < np; p += 64) mx = fmaxf(mx, pr[2 * p]);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+    float sum = 0.0f;
+    for (int p = lane; p < np; p += 64) {
+        const float2 q = *reinterpret_cast<const float2 *>(pr + 2 * p);
+        if (q.y != 0.0f) sum += q.y * __expf(q.x - mx);
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) sum += __shfl_xor(sum, d);
+    s.a = mx;
+    s.b = sum;
+    return s;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // s_waitcnt vmcnt(N), other counters untouched
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+
+}  // namespace fle

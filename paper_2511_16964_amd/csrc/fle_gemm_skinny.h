@@ -1,0 +1,237 @@
+// The HBM-bound skinny GEMM (M <= 64 per row block, 2-byte operands).
+#pragma once
+#include "fle_device_common.h"
+
+namespace fle {
+
+// ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
+// HBM-bound: W streams through once and the matrix pipe is nearly idle, so the design goal is
+// bytes in flight.  One workgroup owns 128 rows of W (columns of out) and all of K; each of its
+// 4 waves copies and consumes its own 32 W rows, the small x tile is shared.  The LDS ring is
+// NST stages of (128 + 32 TMB) x 64 bf16, NST-1 of them in flight (about 100 KB of W per CU,
+// what 8 TB/s x ~2 us of latency / 256 CUs asks for).  Same swizzle and orientation as the
+// tiled kernel; the wave tile is 32 TMB x 32, so the epilogue stays in the MFMA register layout.
+template <int TMB, int BK, int DT>
+__device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
+    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");
+    using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
+    constexpr int BM = 32 * TMB, BN = 128;
+    constexpr int RB = BK * 2;                 // bytes per staged row
+    constexpr int CPR = BK / 8, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
+    constexpr int KPS = BK / 16;               // 16-wide k slices per stage
+    constexpr int SW = BN * RB, SX = BM * RB, STAGE = SW + SX;
+    constexpr int NST = (160 * 1024) / STAGE < 8 ? (160 * 1024) / STAGE : 8;
+    constexpr int NIW = 32 / RPI, NIX = (8 * TMB) / RPI, LPS = NIW + NIX;  // copy instructions per wave per stage
+    static_assert(NST >= 2 && NIX >= 1 && (NST - 2) * LPS < 64, "ring does not fit the counters");
+    __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t M = a.M, N = a.N;
+    // Workgroup -> (W tile, block of BM rows of x).  The row blocks of one W tile get ids that differ
+    // by multiples of 8, next to each other in dispatch order: they land on the same XCD at about the
+    // same time, so W comes from HBM once and from that XCD's L2 for the other row blocks.
+    int64_t n0, m0;
+    {
+        const uint32_t bid = blockIdx.x, xcd = bid % 8, rest = bid / 8, tm = uint32_t(a.tiles_m);
+        const uint32_t tile_n = (rest / tm) * 8 + xcd;
+        if (tile_n >= uint32_t(a.tiles_n)) return;  // grid rounded up to a multiple of 8 tiles; the whole workgroup leaves
+        n0 = int64_t(tile_n) * BN;
+        m0 = int64_t(rest % tm) * BM;
+    }
+
+    // Chunk c of a row is stored at position c ^ sw(row): every 16-lane group of a fragment read
+    // (16 consecutive rows, one logical chunk) then covers 16 different 16-byte bank groups.
+    auto sw = [](int row) { return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); };
+    const int lr = lane / CPR, lp = lane % CPR;
+    __amdgpu_buffer_rsrc_t rw, rx;
+    {
+        const int64_t wrows = (N - n0) < BN ? (N - n0) : BN, xrows = (M - m0) < BM ? (M - m0) : BM;
+        rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2), 0,
+                                               uint32_t(((wrows - 1) * a.ldw + a.K) * 2), 0x00020000);
+        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * 2), 0,
+                                               uint32_t(((xrows - 1) * a.ldx + a.K) * 2), 0x00020000);
+    }
+    const uint32_t ldwb = uint32_t(a.ldw) * 2, ldxb = uint32_t(a.ldx) * 2;
+    auto issue = [&](int kt) {
+        char *base = smem + (kt % NST) * STAGE;
+        const uint32_t kb = uint32_t(kt) * RB;
+#pragma unroll
+        for (int j = 0; j < NIW; ++j) {  // this wave's own 32 rows of W
+            const int row = j * RPI + lr;
+            const uint32_t voff = uint32_t(wave * 32 + row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 2);
+        }
+#pragma unroll
+        for (int j = 0; j < NIX; ++j) {  // a quarter of the shared x tile
+            const int row = wave * (8 * TMB) + j * RPI + lr;
+            const uint32_t voff = uint32_t(row) * ldxb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(base + SW + (wave * (8 * TMB) + j * RPI) * RB), 16, voff, 0, 0, 0);
+        }
+    };
+    const int fr = lane & 31, fh = lane >> 5, fs = sw(fr);
+    f32x16 acc[TMB];
+#pragma unroll
+    for (int t = 0; t < TMB; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+    auto compute = [&](int kt) {
+        const char *sW = smem + (kt % NST) * STAGE + wave * 32 * RB + fr * RB, *sX = smem + (kt % NST) * STAGE + SW + fr * RB;
+#pragma unroll
+        for (int kk = 0; kk < KPS; ++kk) {
+            const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
+            const frag_t fw = *reinterpret_cast<const frag_t *>(sW + off);
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) {
+                const frag_t fx = *reinterpret_cast<const frag_t *>(sX + t * 32 * RB + off);
+                if constexpr (DT == FLE_F16) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[t], 0, 0, 0);
+                else acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
+            }
+        }
+    };
+    // K stages kt .. KT-1 of this workgroup (all of them unless K is split over gridDim.y)
+    const int KA = int(a.K / BK);
+    int kt = int(int64_t(blockIdx.y) * KA / gridDim.y);
+    const int KT = int(int64_t(blockIdx.y + 1) * KA / gridDim.y);
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (kt + s < KT) issue(kt + s);
+    for (; kt + NST - 1 < KT; ++kt) {
+        wait_vmcnt<(NST - 2) * LPS>();  // the newest NST-2 stages may still be in flight
+        __builtin_amdgcn_s_barrier();    // stage kt is complete; stage kt-1 is no longer read
+        issue(kt + NST - 1);
+        compute(kt);
+    }
+    for (; kt < KT; ++kt) {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        compute(kt);
+    }
+
+    // ---- epilogue in the MFMA layout: acc[t][4q+e] = out[32 t + (lane & 31)][n_lane + 8 q + e]
+    char *const dst = a.dst ? reinterpret_cast<char *>(a.dst) + int64_t(blockIdx.y) * a.split_stride : nullptr;
+    const int h = lane >> 5;
+    const int64_t n_lane = n0 + wave * 32 + 4 * h;
+    if (n0 + wave * 32 >= N) return;
+    int64_t n_c[4];  // clamped column of each group of four (loads stay in bounds; stores are masked)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) n_c[q] = n_lane + 8 * q < N ? n_lane + 8 * q : N - 4;
+    for (int o = 0; o < a.epi.n_pre; ++o) {
+        const DevOp op = a.epi.pre[o];
+        switch (op.kind) {
+        case FLE_BIAS:
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bv = ld4<DT>(a.epi.bias, n_c[q]);
+#pragma unroll
+                for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[t][4 * q + e] += bv[e];
+            }
+            break;
+        case FLE_SCALE:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) acc[t] *= op.alpha;
+            break;
+        case FLE_RELU:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = relu_f(acc[t][r]);
+            break;
+        case FLE_GELU_ERF:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = gelu_erf_f(acc[t][r]);
+            break;
+        case FLE_GELU_TANH:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = gelu_tanh_f(acc[t][r]);
+            break;
+        case FLE_RESIDUAL:
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) {
+                const int64_t m = m0 + 32 * t + (lane & 31), mc = m < M ? m : M - 1;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 rv = ld4<DT>(op.p0, mc * op.ld + n_c[q]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[t][4 * q + e] += rv[e];
+                }
+            }
+            break;
+        default: break;
+        }
+    }
+    if (a.epi.row_kind >= 0) {  // one partial per (row, 32-column wave tile)
+        const int64_t left = N - (n0 + wave * 32);
+        const float cnt = float(left < 32 ? left : 32);
+        const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+#pragma unroll
+        for (int t = 0; t < TMB; ++t) {
+            const int64_t m = m0 + 32 * t + (lane & 31);
+            float s0, s1;
+            if (ln) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) sum += acc[t][4 * q + e];
+                sum += __shfl_xor(sum, 32);
+                const float mean = sum / cnt;
+                float m2 = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) m2 += (acc[t][4 * q + e] - mean) * (acc[t][4 * q + e] - mean);
+                m2 += __shfl_xor(m2, 32);
+                s0 = mean;
+                s1 = m2;
+            } else {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[t][4 * q + e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                float se = 0.0f;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (n_lane + 8 * q < N)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) se += __expf(acc[t][4 * q + e] - mx);
+                se += __shfl_xor(se, 32);
+                s0 = mx;
+                s1 = se;
+            }
+            if (h == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + (n0 + wave * 32) / 32) * 2) = make_float2(s0, s1);
+            if (a.dst_rel) acc[t] -= s0;
+        }
+    }
+    if (a.dst) {
+#pragma unroll
+        for (int t = 0; t < TMB; ++t) {
+            const int64_t m = m0 + 32 * t + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t n = n_lane + 8 * q;
+                if (m < M && n < N) {
+                    const f32x4 v = f32x4{acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+                    if (a.dst_f32)
+                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n) = v;
+                    else
+                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n) = pack4<DT>(v);
+                }
+            }
+        }
+    }
+}
+template <int TMB, int BK, int DT>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK, DT>(a); }
+
+}  // namespace fle

@@ -1,0 +1,487 @@
+// The tiled MFMA GEMM (bf16, fp16 and fp32 operands) with the fused epilogue.
+#pragma once
+#include "fle_device_common.h"
+
+namespace fle {
+
+// ------------------------------------------------------------------ tiled MFMA GEMM (bf16 and fp32)
+// Block tile BM x BN (rows of x, rows of W), K step 128 bytes (64 bf16 or 32 fp32), 4 waves as
+// 2 x 2, each wave owning (BM/2) x (BN/2) outputs as 32x32 accumulator tiles of
+// v_mfma_f32_32x32x16_bf16 (fp32 operands: four v_mfma_f32_32x32x2_f32 per fragment pair).
+//
+// Main loop.  Operand tiles go HBM -> LDS by buffer loads that write LDS directly (no
+// registers), two stages deep.  A stage row is 128 bytes = 8 chunks of 16 bytes, stored at chunk
+// position c ^ g(row), g(row) = (row & 7) ^ ((row >> 3) & 1): the 16-byte reads of an MFMA
+// fragment (32 consecutive rows, one logical chunk) then hit every LDS bank once.  Within a
+// K step the copy instructions for the next stage and the fragment reads for the next
+// 16-wide k slice are issued one at a time in the gaps between MFMAs (pinned with
+// sched_barrier): a wave issues in order, so a burst of memory instructions would otherwise
+// leave the matrix pipe idle while the LDS and texture paths accept them.  The copies all go
+// out in the first half of the K step, which gives them most of a K step to land.
+//
+// Epilogue.  One 32-row block of the wave's accumulators at a time is staged through LDS as
+// fp32 and read back row-contiguous: a lane then owns 4 (or 2 x 4) consecutive columns of one
+// row, 16 lanes cover a whole 64-column run, so bias / residual / output accesses are full
+// cache lines and a row reduction is a 16-lane DPP reduction.  The residual tile is copied
+// into LDS by the same direct loads, the first block before the main loop starts.
+template <int ROWS>
+struct TileLoader {
+    static constexpr int NI = ROWS / 32;  // copy instructions per wave per stage (8 rows each)
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t off_even, off_odd;  // this lane's byte offset in the tile for its even / odd 8-row groups
+    uint32_t row_step;           // bytes between 8-row groups
+    int wave;
+    int chunk_even;              // logical 16-byte chunk (0..7) this lane copies in its even groups (odd: ^ 1)
+
+    // ld_bytes: distance between rows; k_bytes: length of a row (K elements), both in bytes
+    __device__ __forceinline__ void init(const void *base, int64_t ld_bytes, int64_t rows_valid, int64_t k_bytes, int wave_, int lane) {
+        const int64_t rv = rows_valid < ROWS ? rows_valid : ROWS;
+        const uint32_t nrec = uint32_t((rv - 1) * ld_bytes + k_bytes);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, nrec, 0x00020000);
+        const int lr = lane >> 3, lp = lane & 7;
+        const uint32_t ldb = uint32_t(ld_bytes);
+        wave = wave_;
+        const int p0 = (wave_ * (ROWS / 4) / 8) & 1;  // parity of this wave's first 8-row group
+        off_even = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0) << 4);
+        off_odd = uint32_t(wave_ * (ROWS / 4) + lr) * ldb + uint32_t((lp ^ lr ^ p0 ^ 1) << 4);
+        chunk_even = lp ^ lr ^ p0;
+        row_step = 8 * ldb;
+    }
+    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at byte column k0.
+    __device__ __forceinline__ void issue_one(char *lds, uint32_t k0, int j) const {
+        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+    }
+    // Same for the last, partial K step: chunks at or beyond `valid` (= remaining row bytes / 16) get
+    // an out-of-range offset, for which the buffer load delivers zeros.
+    __device__ __forceinline__ void issue_one_tail(char *lds, uint32_t k0, int j, int valid) const {
+        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
+        if ((chunk_even ^ (j & 1)) >= valid) voff = 0x80000000u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+    }
+    __device__ __forceinline__ void issue(char *lds, uint32_t k0, int valid) const {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            if (valid >= 8) issue_one(lds, k0, j);
+            else issue_one_tail(lds, k0, j, valid);
+        }
+    }
+};
+
+// Sum / max over the 16 lanes of a DPP row by rotations; every lane ends with the result.
+template <bool MAX>
+__device__ __forceinline__ float row16_allreduce(float v) {
+#define FLE_ROR(n)                                                                                              \
+    {                                                                                                           \
+        const float o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + (n), 0xF, 0xF, false)); \
+        v = MAX ? fmaxf(v, o) : v + o;                                                                          \
+    }
+    FLE_ROR(8) FLE_ROR(4) FLE_ROR(2) FLE_ROR(1)
+#undef FLE_ROR
+    return v;
+}
+
+// EDGE: N, the leading dimensions or the addresses of b / residual / out do not allow 4-column vector
+// accesses; the epilogue then touches memory one element at a time, masked per column.
+template <int BM, int BN, int DT, bool EDGE>
+__device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
+    constexpr bool F32 = DT == FLE_F32;
+    constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
+    constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+    constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
+    constexpr int NH = WN / 64;                                    // 64-column runs per wave tile
+    constexpr int EP_STRIDE = WN * 4 + 16;                         // staged fp32 row + 16 bytes of bank skew
+    constexpr int EP_WAVE = 32 * EP_STRIDE;
+    constexpr int RES_WAVE = 32 * WN * 2;                          // one 32-row residual block per wave
+    constexpr int RES1_OFF = 4 * EP_WAVE, RES0_OFF = 2 * STAGE;
+    static_assert(RES1_OFF + 4 * RES_WAVE <= 2 * STAGE, "epilogue buffers must fit in the stage area");
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE + 4 * RES_WAVE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t M = a.M, N = a.N;
+
+    // Workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs, so give each
+    // XCD a contiguous range of tile ids, then walk tiles in groups of 4 tile rows: the tiles
+    // an XCD works on at any time share x and W panels in its own L2.
+    int tile_m, tile_n;
+    {
+        const uint32_t G = uint32_t(a.tiles_m) * uint32_t(a.tiles_n), bid = blockIdx.x;
+        const uint32_t per = G / 8, rem = G % 8, xcd = bid % 8, loc = bid / 8;
+        const uint32_t id = loc + xcd * per + (xcd < rem ? xcd : rem);
+        const uint32_t width = 4 * uint32_t(a.tiles_n);
+        const uint32_t first_m = (id / width) * 4;
+        const uint32_t gsz = (uint32_t(a.tiles_m) - first_m) < 4 ? (uint32_t(a.tiles_m) - first_m) : 4;
+        tile_m = int(first_m + (id % width) % gsz);
+        tile_n = int((id % width) / gsz);
+    }
+    const int64_t m0 = int64_t(tile_m) * BM, n0 = int64_t(tile_n) * BN;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m_wave = m0 + wm * WM, n_wave = n0 + wn * WN;  // origin of this wave's outputs
+
+    // ---- residual operand of the first RESIDUAL op whose rows are 16-byte aligned: copied to LDS
+    // block by block (other residual operands are read straight from memory in the epilogue)
+    int res_idx = -1;
+    bool has_bias = false;
+    for (int o = a.epi.n_pre - 1; o >= 0; --o) {
+        const DevOp &op = a.epi.pre[o];
+        if (!F32 && !EDGE && op.kind == FLE_RESIDUAL && op.ld % 8 == 0 && reinterpret_cast<uintptr_t>(op.p0) % 16 == 0) res_idx = o;
+        if (op.kind == FLE_BIAS) has_bias = true;
+    }
+    const bool wave_live = m_wave < M && n_wave < N;  // this wave owns at least one output
+    __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, 0x00020000);
+    uint32_t res_lane_off = 0, res_block_step = 0;
+    if (res_idx >= 0 && wave_live) {
+        const int64_t ld = a.epi.pre[res_idx].ld;
+        const int64_t rows = (M - m_wave) < WM ? (M - m_wave) : WM;
+        const char *base = reinterpret_cast<const char *>(a.epi.pre[res_idx].p0) + (m_wave * ld + n_wave) * 2;
+        res_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, uint32_t(((rows - 1) * ld + (N - n_wave)) * 2), 0x00020000);
+        // copy instruction t of a block covers rows 4t .. 4t+3 when WN = 128 (16 lanes x 16 bytes per row),
+        // rows 8t .. 8t+7 when WN = 64
+        constexpr int LPR = WN / 8;  // lanes per row
+        res_lane_off = uint32_t(lane / LPR) * uint32_t(ld) * 2 + uint32_t(lane % LPR) * 16;
+        res_block_step = uint32_t(64 / LPR) * uint32_t(ld) * 2;
+    }
+    auto issue_residual = [&](int block, int buf) {
+        constexpr int NI = RES_WAVE / 1024;
+        char *dst = smem + (buf ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
+        const uint32_t base = uint32_t(block) * 32 * uint32_t(a.epi.pre[res_idx].ld) * 2 + res_lane_off;
+#pragma unroll
+        for (int t = 0; t < NI; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_rsrc, (lds_void *)(dst + t * 1024), 16, base + uint32_t(t) * res_block_step, 0, 0, 2);  // read once: non-temporal
+    };
+    if (res_idx >= 0 && wave_live) issue_residual(0, 0);
+
+    TileLoader<BM> ldx_;
+    TileLoader<BN> ldw_;
+    ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * ES, a.ldx * ES, M - m0, a.K * ES, wave, lane);
+    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
+    constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
+
+    // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
+    uint32_t rd_off[4];
+    {
+        const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // 16 bytes of one row: 4 fp32, 8 bf16 or 8 fp16 along K
+    using frag_t = typename std::conditional<F32, f32x4, typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type>::type;
+    frag_t fw[2][TN], fx[2][TM];
+    const int KT = int((a.K * ES + 127) / 128);
+    const int tail_valid = int((a.K * ES - int64_t(KT - 1) * 128) / 16);  // 16-byte chunks of the last K step (8 = full)
+    // One K step on stage kt & 1; ISSUE: also copy K step kt+1 into the other stage (masked to the
+    // valid chunks when that is the partial last step).
+    auto k_step = [&](int kt, auto issue_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        const int valid = kt + 2 == KT ? tail_valid : 8;
+        const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
+        char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
+        const uint32_t ik0 = uint32_t(kt + 1) * 128;  // byte column of the K step being copied
+        wait_vmcnt<0>();                  // this wave's copies into the current stage have landed
+        __builtin_amdgcn_s_barrier();     // everyone's have, and everyone is done reading the other stage
+#pragma unroll
+        for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
+#pragma unroll
+        for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            // 16-wide k slice kk: NMF MFMAs; in the issue slot before MFMA q goes at most one
+            // fragment read of slice kk+1 and (first two slices only) one copy instruction.
+            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
+            constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
+            const int cur = kk & 1;
+#pragma unroll
+            for (int q = 0; q < NMF; ++q) {
+                if (kk + 1 < 4 && q % QD == 0) {
+                    const int g = q / QD;
+                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
+                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
+                }
+                if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
+                    const int idx = kk * NVM + q / QV;
+                    if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                    else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (F32) {
+                    // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
+                    // same K permutation for both operands
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
+                } else if constexpr (DT == FLE_F16) {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                } else {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y)
+    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
+    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
+    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
+    {
+        int kt = kb;
+        for (; kt < ke - 1; ++kt) k_step(kt, std::true_type{});
+        k_step(kt, std::false_type{});
+    }
+    __syncthreads();  // the stage area becomes epilogue scratch
+    if (!wave_live) return;
+    char *const dst = a.dst ? reinterpret_cast<char *>(a.dst) + int64_t(blockIdx.y) * a.split_stride : nullptr;
+
+    // ---- epilogue
+    // Final values are written once and not read again by this call: non-temporal stores keep them from
+    // displacing operand panels in L2 (measured -2.4 % on the MLP block).  Values staged for the finalize
+    // pass or the split-K reduction are re-read soon and stay cacheable (non-temporal costs +3 % there).
+    const bool stream_out = a.epi.row_kind < 0 && gridDim.y == 1;
+    const int rsub = lane >> 4;  // row within a group of 4 rows
+    const int cl = lane & 15;
+    char *ep = smem + wave * EP_WAVE;
+    // columns of this lane in the read-back layout: run hc covers n_wave + 64 hc + 4 cl .. + 3
+    int64_t n_col[NH];
+    bool n_ok[NH];
+    f32x4 bias_v[NH];
+#pragma unroll
+    for (int hc = 0; hc < NH; ++hc) {
+        n_col[hc] = n_wave + 64 * hc + 4 * cl;
+        n_ok[hc] = n_col[hc] < N;
+        bias_v[hc] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (has_bias) {
+            if constexpr (EDGE) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(a.epi.bias, n_col[hc] + e, DT);
+            } else {
+                bias_v[hc] = ld4<DT>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
+            }
+        }
+    }
+    const int p_idx = int(n_wave / WN);
+    const int64_t cols_left = N - n_wave;
+    const float cnt = float(cols_left < WN ? cols_left : WN);
+    constexpr int NIT = 8;  // 4 rows per iteration
+
+#pragma unroll 1
+    for (int i = 0; i < TM; ++i) {
+        const int64_t m_blk = m_wave + 32 * i;
+        if (m_blk >= M) break;
+        if (res_idx >= 0) {
+            wait_vmcnt<0>();  // residual block i is in LDS (and this wave's earlier stores are done)
+            if (i + 1 < TM && m_blk + 32 < M) issue_residual(i + 1, (i + 1) & 1);
+        }
+        // accumulators of row block i -> LDS, row (lane & 31), columns 32 j + 8 q + 4 h .. + 3
+        {
+            char *wr = ep + (lane & 31) * EP_STRIDE + (lane >> 5) * 16;
+            auto put = [&](auto ic) {
+                constexpr int I = decltype(ic)::value;
+                if constexpr (I < TM) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            *reinterpret_cast<f32x4 *>(wr + (32 * j + 8 * q) * 4) = f32x4{acc[I][j][4 * q], acc[I][j][4 * q + 1], acc[I][j][4 * q + 2], acc[I][j][4 * q + 3]};
+                }
+            };
+            switch (i) {
+            case 0: put(std::integral_constant<int, 0>{}); break;
+            case 1: put(std::integral_constant<int, 1>{}); break;
+            case 2: put(std::integral_constant<int, 2>{}); break;
+            default: put(std::integral_constant<int, 3>{}); break;
+            }
+        }
+        // read back row-contiguous: v[it][hc] = row 4 it + rsub, columns of run hc
+        f32x4 v[NIT][NH];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int hc = 0; hc < NH; ++hc) v[it][hc] = *reinterpret_cast<const f32x4 *>(ep + (4 * it + rsub) * EP_STRIDE + hc * 256 + cl * 16);
+
+        for (int o = 0; o < a.epi.n_pre; ++o) {
+            const DevOp op = a.epi.pre[o];
+            switch (op.kind) {
+            case FLE_BIAS:
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] += bias_v[hc];
+                break;
+            case FLE_SCALE:
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] *= op.alpha;
+                break;
+            case FLE_RELU:
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = relu_f(v[it][hc][e]);
+                break;
+            case FLE_GELU_ERF:
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_erf_f(v[it][hc][e]);
+                break;
+            case FLE_GELU_TANH:
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_tanh_f(v[it][hc][e]);
+                break;
+            case FLE_RESIDUAL:
+                if (o == res_idx) {  // staged in LDS: [32 rows][WN] bf16
+                    const char *rb = smem + ((i & 1) ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<DT>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8, 0);
+                } else {  // a further residual operand: straight from memory, clamped to stay in bounds
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const int64_t m = m_blk + 4 * it + rsub;
+                        const int64_t mc = m < M ? m : M - 1;
+#pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DT);
+                            } else {
+                                v[it][hc] += ld4<DT>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                            }
+                        }
+                    }
+                }
+                break;
+            default: break;
+            }
+        }
+
+        // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
+        float part_max[NIT];  // softmax: the partial's maximum per row of this block
+        if (a.epi.row_kind >= 0) {
+            const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int64_t m = m_blk + 4 * it + rsub;
+                float s0, s1;
+                if (ln) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc]) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) sum += v[it][hc][e];
+                            } else {
+                                sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                            }
+                        }
+                    sum = row16_allreduce<false>(sum);
+                    const float mean = sum / cnt;
+                    float m2 = 0.0f;
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc])
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
+                    m2 = row16_allreduce<false>(m2);
+                    s0 = mean;
+                    s1 = m2;
+                } else {
+                    float mx = -INFINITY;
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc]) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) mx = fmaxf(mx, v[it][hc][e]);
+                            } else {
+                                mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
+                            }
+                        }
+                    mx = row16_allreduce<true>(mx);
+                    float se = 0.0f;
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (n_ok[hc])
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - mx);
+                    se = row16_allreduce<false>(se);
+                    s0 = mx;
+                    s1 = se;
+                }
+                part_max[it] = s0;
+                if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
+            }
+            if (a.dst_rel) {
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc) v[it][hc] -= part_max[it];
+            }
+        }
+
+        // store: final values (no row op) or staged values for the finalize pass
+        if (a.dst) {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int64_t m = m_blk + 4 * it + rsub;
+#pragma unroll
+                for (int hc = 0; hc < NH; ++hc)
+                    if (m < M && n_ok[hc]) {
+                        if constexpr (EDGE) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DT, v[it][hc][e]);
+                        } else if (F32 || a.dst_f32) {
+                            f32x4 *q = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]);
+                            if (stream_out) __builtin_nontemporal_store(v[it][hc], q);
+                            else *q = v[it][hc];
+                        } else {
+                            u32x2 *q = reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n_col[hc]);
+                            constexpr int DT2 = F32 ? FLE_BF16 : DT;  // (this branch is never taken for fp32 problems)
+                            if (stream_out) __builtin_nontemporal_store(pack4<DT2>(v[it][hc]), q);
+                            else *q = pack4<DT2>(v[it][hc]);
+                        }
+                    }
+            }
+        }
+    }
+}
+
+// 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).  DT: fle_dtype of the operands.
+// fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
+// v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE>(a); }
+// 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE>(a); }
+
+}  // namespace fle

@@ -1,0 +1,303 @@
+// Second passes: finalize of LayerNorm / softmax / logsumexp, and the split-K reduction.
+#pragma once
+#include "fle_device_common.h"
+
+namespace fle {
+
+// ------------------------------------------------------------------ finalize passes
+// One wave per (row, 2048-column chunk).  The wave combines the row's partials itself (one
+// per lane, then a fixed butterfly: identical result in every lane), issues all of its
+// 16-byte loads of staged y at once, normalises, applies the trailing elementwise ops, rounds
+// and writes 16-byte vectors.
+__device__ __forceinline__ void ld8(const void *p, int64_t i, int dtype, float (&v)[8]) {  // 8 elements at index i
+    if (dtype == FLE_F32) {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(p) + i);
+        const f32x4 u0 = src[0], u1 = src[1];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[e] = u0[e]; v[4 + e] = u1[e]; }
+    } else if (dtype == FLE_F16) {
+        const f16x8 u = *reinterpret_cast<const f16x8 *>(reinterpret_cast<const _Float16 *>(p) + i);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = float(u[e]);
+    } else {
+        const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(p) + i);
+        const uint32_t wv[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(wv[e] << 16); v[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u); }
+    }
+}
+// 8 fp32 values rounded to a 2-byte dtype, stored as one 16-byte vector at element index i.
+__device__ __forceinline__ void st8_2byte(void *p, int64_t i, int dtype, const float (&v)[8]) {
+    u32x4 o;
+    if (dtype == FLE_F16) {
+        f16x8 h;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = static_cast<_Float16>(v[e]);
+        o = __builtin_bit_cast(u32x4, h);
+    } else {
+        bf16x8 h;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = static_cast<__bf16>(v[e]);
+        o = __builtin_bit_cast(u32x4, h);
+    }
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p) + i) = o;
+}
+
+// LNK: LayerNorm (true) or softmax (false); separate kernels so that each gets its own register budget.
+template <bool VEC, bool LNK>
+__global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
+    constexpr int CH = 2048, IT = CH / 512;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int dtype = a.epi.dtype;
+    const bool f32 = dtype == FLE_F32;
+    constexpr bool ln = LNK;
+    const int64_t N = a.N;
+    const int64_t chunks = (N + CH - 1) / CH, items = a.M * chunks;
+    for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
+        const int64_t row = item / chunks, c0 = (item % chunks) * CH;
+        const int64_t c1 = c0 + CH < N ? c0 + CH : N;
+        float y[IT][8];
+        if (VEC) {  // issue the loads before the partials are combined
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int64_t n = c0 + it * 512 + lane * 8;
+                if (n < c1) ld8(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype, y[it]);
+            }
+        }
+        float sub, mul;  // out = (y - sub) * mul  (LayerNorm),  exp(y - sub) * mul  (softmax)
+        if (ln) {
+            const Stat s = reduce_partials<true>(a.partials, row, a.np, a.part_cols, N, lane);
+            sub = s.a;
+            mul = rsqrtf(s.b / float(N) + a.epi.row.alpha);
+        } else {
+            const Stat s = reduce_partials<false>(a.partials, row, a.np, a.part_cols, N, lane);
+            sub = s.a;
+            mul = 1.0f / s.b;
+        }
+        auto post = [&](float v, int64_t n) -> float {
+            for (int o = 0; o < a.epi.n_post; ++o) v = apply_op(a.epi.post[o], v, row, n, a.epi.bias, dtype);
+            return v;
+        };
+        if (VEC) {
+#pragma unroll
+            for (int it = 0; it < IT; ++it) {
+                const int64_t n = c0 + it * 512 + lane * 8;
+                if (n < c1) {
+                    float *v = y[it];
+                    if (ln) {
+                        float g[8], be[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; }
+                        if (a.epi.row.p0) ld8(a.epi.row.p0, n, dtype, g);
+                        if (a.epi.row.p1) ld8(a.epi.row.p1, n, dtype, be);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] - sub) * mul * g[e] + be[e];
+                    } else {
+                        // staged relative to the maximum of the partial the 8 columns lie in (part_cols is a multiple of 8)
+                        const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - shift) * mul;
+                    }
+                    if (a.epi.n_post > 0) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
+                    }
+                    if (f32) {
+                        f32x4 *dstp = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + row * a.ldo + n);
+                        dstp[0] = f32x4{v[0], v[1], v[2], v[3]};
+                        dstp[1] = f32x4{v[4], v[5], v[6], v[7]};
+                    } else {
+                        st8_2byte(a.out, row * a.ldo + n, dtype, y[it]);
+                    }
+                }
+            }
+        } else {
+            auto one = [&](int64_t n) {  // one element
+                const float yv = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
+                float v;
+                if (ln) {
+                    v = (yv - sub) * mul;
+                    if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
+                    if (a.epi.row.p1) v += ld_elem(a.epi.row.p1, n, dtype);
+                } else {
+                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
+                    v = __expf(yv - shift) * mul;
+                }
+                st_elem(a.out, row * a.ldo + n, dtype, post(v, n));
+            };
+            // bf16 rows whose staged values and outputs share their offset within a 16-byte line (always so
+            // when staged in out itself): skip h elements to the next line boundary, then whole lines as
+            // 16-byte vectors.  Chunk k takes elements h + 2048 k ... of the row, chunk 0 also the first h.
+            const uintptr_t ya = reinterpret_cast<uintptr_t>(a.y) + uintptr_t(row * a.ldy) * 2;
+            const uintptr_t oa = reinterpret_cast<uintptr_t>(a.out) + uintptr_t(row * a.ldo) * 2;
+            if (!f32 && !a.y_f32 && ((ya ^ oa) & 15) == 0 && (ya & 1) == 0) {
+                const int h = int(((16 - (ya & 15)) & 15) >> 1);
+                if (c0 == 0 && lane < h && lane < N) one(lane);
+#pragma unroll
+                for (int it = 0; it < IT; ++it) {
+                    const int64_t n = h + c0 + (it * 64 + lane) * 8;
+                    if (n + 8 <= N) {
+                        float v[8];
+                        ld8(a.y, row * a.ldy + n, dtype, v);
+                        if (ln) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                v[e] = (v[e] - sub) * mul;
+                                if (a.epi.row.p0) v[e] *= ld_elem(a.epi.row.p0, n + e, dtype);
+                                if (a.epi.row.p1) v[e] += ld_elem(a.epi.row.p1, n + e, dtype);
+                            }
+                        } else {
+                            float s0 = sub, s1 = sub;
+                            const int64_t p0 = n / a.part_cols, p1 = (n + 7) / a.part_cols;  // the 8 columns may straddle two partials
+                            if (a.y_rel) {
+                                s0 = sub - a.partials[(row * a.np + p0) * 2];
+                                s1 = sub - a.partials[(row * a.np + p1) * 2];
+                            }
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
+                        }
+                        if (a.epi.n_post > 0) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
+                        }
+                        st8_2byte(a.out, row * a.ldo + n, dtype, v);
+                    } else {
+                        for (int64_t nn = n; nn < N; ++nn) one(nn);  // the row's last, partial line (one lane at most)
+                    }
+                }
+            } else {
+                for (int64_t n = c0 + lane; n < c1; n += 64) one(n);
+            }
+        }
+    }
+}
+
+// logsumexp: one wave per row, out[row] = max + log(sum).
+__global__ __launch_bounds__(256) void finalize_lse(const FinArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= a.M) return;
+    const Stat s = reduce_partials<false>(a.partials, row, a.np, a.part_cols, a.N, lane);
+    if (lane == 0) st_elem(a.out, row, a.epi.dtype, s.a + __logf(s.b));
+}
+
+// ------------------------------------------------------------------ split-K reduction
+// One wave per (row, 256-column chunk), a lane per 4 consecutive columns: sums the S fp32 slabs
+// in slab order, applies the ops that precede the row op, writes the value (final, or staged
+// for the finalize pass) and, with a row op, the chunk's partial.
+template <bool MAX>
+__device__ __forceinline__ float wave_allreduce(float v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_xor(v, d);
+        v = MAX ? fmaxf(v, o) : v + o;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t N = a.N;
+    const int dtype = a.epi.dtype;
+    const bool f32 = dtype == FLE_F32;
+    const bool vec = a.vec != 0;  // 4-column vector accesses to b, residual and dst are possible
+    const int64_t chunks = (N + 255) / 256, items = a.M * chunks;
+    for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
+        const int64_t row = item / chunks, c0 = (item % chunks) * 256;
+        const int64_t n = c0 + lane * 4;
+        const bool ok = n < N;  // at least the first of this lane's four columns exists
+        bool okc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) okc[e] = n + e < N;
+        f32x4 v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (ok) {
+            const float *src = a.slabs + row * a.ld_slab + n;  // slab rows are padded to whole groups of four
+            int s = 0;
+            for (; s + 4 <= a.S; s += 4) {
+                const f32x4 u0 = *reinterpret_cast<const f32x4 *>(src + (s + 0) * a.stride);
+                const f32x4 u1 = *reinterpret_cast<const f32x4 *>(src + (s + 1) * a.stride);
+                const f32x4 u2 = *reinterpret_cast<const f32x4 *>(src + (s + 2) * a.stride);
+                const f32x4 u3 = *reinterpret_cast<const f32x4 *>(src + (s + 3) * a.stride);
+                v = (((v + u0) + u1) + u2) + u3;
+            }
+            for (; s < a.S; ++s) v += *reinterpret_cast<const f32x4 *>(src + s * a.stride);
+            auto add4 = [&](const void *ptr, int64_t idx) {
+                if (vec) {
+                    v += ld4_rt(ptr, idx, dtype);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (okc[e]) v[e] += ld_elem(ptr, idx + e, dtype);
+                }
+            };
+            for (int o = 0; o < a.epi.n_pre; ++o) {
+                const DevOp op = a.epi.pre[o];
+                switch (op.kind) {
+                case FLE_BIAS: add4(a.epi.bias, n); break;
+                case FLE_SCALE: v *= op.alpha; break;
+                case FLE_RELU:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = relu_f(v[e]);
+                    break;
+                case FLE_GELU_ERF:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_erf_f(v[e]);
+                    break;
+                case FLE_GELU_TANH:
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
+                    break;
+                case FLE_RESIDUAL: add4(op.p0, row * op.ld + n); break;
+                default: break;
+                }
+            }
+        }
+        if (a.epi.row_kind >= 0) {
+            float s0, s1;
+            if (a.epi.row_kind == FLE_LAYERNORM) {
+                const float cnt = float(N - c0 < 256 ? N - c0 : 256);
+                float sum = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) sum += v[e];
+                const float mean = wave_allreduce<false>(sum) / cnt;
+                float m2 = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) m2 += (v[e] - mean) * (v[e] - mean);
+                s0 = mean;
+                s1 = wave_allreduce<false>(m2);
+            } else {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) mx = fmaxf(mx, v[e]);
+                mx = wave_allreduce<true>(mx);
+                float se = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) se += __expf(v[e] - mx);
+                s0 = mx;
+                s1 = wave_allreduce<false>(se);
+            }
+            if (lane == 0) *reinterpret_cast<float2 *>(a.partials + (row * a.np + c0 / 256) * 2) = make_float2(s0, s1);
+            if (a.dst_rel) v -= s0;
+        }
+        if (a.dst && ok) {
+            const bool d32 = a.dst_f32 || f32;
+            if (!vec) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (okc[e]) st_elem(a.dst, row * a.ldd + n + e, d32 ? FLE_F32 : dtype, v[e]);
+            } else if (d32) {
+                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * a.ldd + n) = v;
+            } else {
+                *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(a.dst) + row * a.ldd + n) = pack4_rt(v, dtype);
+            }
+        }
+    }
+}
+
+}  // namespace fle
