@@ -4,13 +4,15 @@
 
 namespace fle {
 
-// ------------------------------------------------------------------ skinny bf16 GEMM (M <= 64)
+// ------------------------------------------------------------------ skinny GEMM (bf16 / fp16, row blocks of up to 64 rows)
 // HBM-bound: W streams through once and the matrix pipe is nearly idle, so the design goal is
 // bytes in flight.  One workgroup owns 128 rows of W (columns of out) and all of K; each of its
 // 4 waves copies and consumes its own 32 W rows, the small x tile is shared.  The LDS ring is
-// NST stages of (128 + 32 TMB) x 64 bf16, NST-1 of them in flight (about 100 KB of W per CU,
-// what 8 TB/s x ~2 us of latency / 256 CUs asks for).  Same swizzle and orientation as the
-// tiled kernel; the wave tile is 32 TMB x 32, so the epilogue stays in the MFMA register layout.
+// NST stages of (128 + 32 TMB) x BK elements, NST-1 of them in flight; measured, the length of
+// the contiguous run per W row (2 BK bytes) matters more than the ring depth, and the W loads
+// carry the non-temporal hint (W is read once and must not displace anything in L2 or the
+// Infinity Cache).  Same swizzle and orientation as the tiled kernel; the wave tile is
+// 32 TMB x 32, so the epilogue stays in the MFMA register layout.
 template <int TMB, int BK, int DT>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");

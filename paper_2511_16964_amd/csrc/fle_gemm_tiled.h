@@ -4,10 +4,10 @@
 
 namespace fle {
 
-// ------------------------------------------------------------------ tiled MFMA GEMM (bf16 and fp32)
-// Block tile BM x BN (rows of x, rows of W), K step 128 bytes (64 bf16 or 32 fp32), 4 waves as
-// 2 x 2, each wave owning (BM/2) x (BN/2) outputs as 32x32 accumulator tiles of
-// v_mfma_f32_32x32x16_bf16 (fp32 operands: four v_mfma_f32_32x32x2_f32 per fragment pair).
+// ------------------------------------------------------------------ tiled MFMA GEMM
+// Block tile BM x BN (rows of x, rows of W), K step 128 bytes (64 bf16 / fp16 or 32 fp32), 4 waves
+// as 2 x 2, each wave owning (BM/2) x (BN/2) outputs as 32x32 accumulator tiles of
+// v_mfma_f32_32x32x16_bf16 / _f16 (fp32 operands: four v_mfma_f32_32x32x2_f32 per fragment pair).
 //
 // Main loop.  Operand tiles go HBM -> LDS by buffer loads that write LDS directly (no
 // registers), two stages deep.  A stage row is 128 bytes = 8 chunks of 16 bytes, stored at chunk
