@@ -102,9 +102,9 @@ typedef struct {
  * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL, at most one row
  * op, and nothing after LOGSUMEXP.  A second row op gives FLE_ERR_UNSUPPORTED.
  *
- * Alignment rule: no alignment is required for correctness.  The tiled MFMA kernels (bf16
- * and fp32) are taken when x and W are 16-byte aligned and K and their row strides are
- * multiples of 16 bytes (8 bf16 / 4 fp32 elements); N, out, b and the residual may then be
+ * Alignment rule: no alignment is required for correctness.  The tiled MFMA kernels (every
+ * dtype) are taken when x and W are 16-byte aligned and K and their row strides are
+ * multiples of 16 bytes (8 bf16 or fp16 / 4 fp32 elements); N, out, b and the residual may then be
  * ragged or misaligned (the kernel switches to an element-wise epilogue).  Other problems
  * run on a slower general kernel.  Problems with few output tiles and a long K are split
  * along K over several workgroups; the partial sums go through the workspace and are added
@@ -135,9 +135,9 @@ const char *fle_last_error(void);
 fle_status fle_last_plan(char *buf, size_t n);
 
 /* Force a kernel variant for the calling thread's next calls, for tests and tuning:
- * 0 = automatic, 1 = general kernel, 2 = tiled bf16 MFMA kernel (automatic tile), 3 = skinny
- * kernel, 4 = tiled with the 256x256 tile, 5 = tiled with the 128x128 tile, 6 / 7 = skinny
- * kernel with a K step of 128 / 256 instead of 64.
+ * 0 = automatic, 1 = general kernel, 2 = tiled MFMA kernel (automatic tile), 3 = skinny kernel
+ * (bf16 / fp16, M <= 256) with a K step of 64, 4 = tiled with the 256x256 tile, 5 = tiled with
+ * the 128x128 tile, 6 / 7 = skinny kernel with a K step of 128 / 256.
  * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run. */
 void fle_force_variant(int variant);
 

@@ -345,6 +345,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 100; }
+int fle_version(void) { return 200; }  // 0.2.0: fp16 operands, split K, fle_force_split
 
 }  // extern "C"
