@@ -13,8 +13,16 @@ namespace fle {
 // carry the non-temporal hint (W is read once and must not displace anything in L2 or the
 // Infinity Cache).  Same swizzle and orientation as the tiled kernel; the wave tile is
 // 32 TMB x 32, so the epilogue stays in the MFMA register layout.
-template <int TMB, int BK, int DT>
+//
+// SEQ (two row blocks, K step 256): a stage of W with both x blocks does not fit LDS twice, so the two
+// blocks of 32 rows take turns on the same W stage, each with its own 16 KB x buffer: two W stages
+// of 64 KB and two x buffers are exactly the 160 KB.  While block 0 is multiplied, x block 1 of the
+// same K step and the next W stage are on their way; while block 1 is multiplied, x block 0 of the
+// next K step is.  The copies return in order, so the wait before block 1 allows exactly the
+// younger W stage to be outstanding.
+template <int TMB, int BK, int DT, bool SEQ = false>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
+    static_assert(!SEQ || (TMB == 2 && BK == 256), "the sequential variant is two row blocks on a 256-wide K step");
     static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");
     using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
     constexpr int BM = 32 * TMB, BN = 128;
@@ -22,10 +30,11 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     constexpr int CPR = BK / 8, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
     constexpr int KPS = BK / 16;               // 16-wide k slices per stage
     constexpr int SW = BN * RB, SX = BM * RB, STAGE = SW + SX;
-    constexpr int NST = (160 * 1024) / STAGE < 8 ? (160 * 1024) / STAGE : 8;
+    constexpr int NST = SEQ ? 2 : (160 * 1024) / STAGE < 8 ? (160 * 1024) / STAGE : 8;
     constexpr int NIW = 32 / RPI, NIX = (8 * TMB) / RPI, LPS = NIW + NIX;  // copy instructions per wave per stage
-    static_assert(NST >= 2 && NIX >= 1 && (NST - 2) * LPS < 64, "ring does not fit the counters");
-    __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE];
+    static_assert(SEQ || (NST >= 2 && NIX >= 1 && (NST - 2) * LPS < 64), "ring does not fit the counters");
+    constexpr int SXB = 32 * RB;  // one x block of 32 rows (SEQ)
+    __shared__ __attribute__((aligned(1024))) char smem[SEQ ? 2 * SW + 2 * SXB : NST * STAGE];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t M = a.M, N = a.N;
@@ -94,19 +103,71 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     const int KA = int(a.K / BK);
     int kt = int(int64_t(blockIdx.y) * KA / gridDim.y);
     const int KT = int(int64_t(blockIdx.y + 1) * KA / gridDim.y);
+    if constexpr (SEQ) {
+        auto issue_w = [&](int k) {  // this wave's own 32 rows of W stage k
+            char *base = smem + (k & 1) * SW;
+            const uint32_t kb = uint32_t(k) * RB;
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s)
-        if (kt + s < KT) issue(kt + s);
-    for (; kt + NST - 1 < KT; ++kt) {
-        wait_vmcnt<(NST - 2) * LPS>();  // the newest NST-2 stages may still be in flight
-        __builtin_amdgcn_s_barrier();    // stage kt is complete; stage kt-1 is no longer read
-        issue(kt + NST - 1);
-        compute(kt);
-    }
-    for (; kt < KT; ++kt) {
-        wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        compute(kt);
+            for (int j = 0; j < NIW; ++j) {
+                const int row = j * RPI + lr;
+                const uint32_t voff = uint32_t(wave * 32 + row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 2);
+            }
+        };
+        auto issue_x = [&](int k, int blk) {  // this wave's 8 rows of x block blk at K step k
+            char *base = smem + 2 * SW + blk * SXB;
+            const uint32_t kb = uint32_t(k) * RB;
+#pragma unroll
+            for (int j = 0; j < 8 / RPI; ++j) {
+                const int row = wave * 8 + j * RPI + lr;  // row within the block; rows beyond M read zeros (out of range)
+                const uint32_t voff = uint32_t(blk * 32 + row) * ldxb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(base + (wave * 8 + j * RPI) * RB), 16, voff, 0, 0, 0);
+            }
+        };
+        auto compute_blk = [&](int k, auto blk_c) {
+            constexpr int BLK = decltype(blk_c)::value;
+            const char *sW = smem + (k & 1) * SW + wave * 32 * RB + fr * RB, *sX = smem + 2 * SW + BLK * SXB + fr * RB;
+#pragma unroll
+            for (int kk = 0; kk < KPS; ++kk) {
+                const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
+                const frag_t fw = *reinterpret_cast<const frag_t *>(sW + off);
+                const frag_t fx = *reinterpret_cast<const frag_t *>(sX + off);
+                if constexpr (DT == FLE_F16) acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[BLK], 0, 0, 0);
+                else acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[BLK], 0, 0, 0);
+            }
+        };
+        if (kt < KT) {
+            issue_w(kt);
+            issue_x(kt, 0);
+        }
+        for (; kt < KT; ++kt) {
+            const bool more = kt + 1 < KT;
+            wait_vmcnt<0>();                 // W stage kt and x block 0 of it have landed (this wave's part)
+            __builtin_amdgcn_s_barrier();    // everyone's have; nobody reads x buffer 1 or the other W stage any more
+            issue_x(kt, 1);
+            if (more) issue_w(kt + 1);
+            compute_blk(kt, std::integral_constant<int, 0>{});
+            if (more) wait_vmcnt<NIW>();     // x block 1 has landed; the younger W stage may still be in flight
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();    // everyone's has; nobody reads x buffer 0 any more
+            if (more) issue_x(kt + 1, 0);
+            compute_blk(kt, std::integral_constant<int, 1>{});
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < NST - 1; ++s)
+            if (kt + s < KT) issue(kt + s);
+        for (; kt + NST - 1 < KT; ++kt) {
+            wait_vmcnt<(NST - 2) * LPS>();  // the newest NST-2 stages may still be in flight
+            __builtin_amdgcn_s_barrier();    // stage kt is complete; stage kt-1 is no longer read
+            issue(kt + NST - 1);
+            compute(kt);
+        }
+        for (; kt < KT; ++kt) {
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            compute(kt);
+        }
     }
 
     // ---- epilogue in the MFMA layout: acc[t][4q+e] = out[32 t + (lane & 31)][n_lane + 8 q + e]
@@ -233,7 +294,7 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
         }
     }
 }
-template <int TMB, int BK, int DT>
-__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK, DT>(a); }
+template <int TMB, int BK, int DT, bool SEQ = false>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny(const GemmArgs a) { gemm_bf16_skinny_body<TMB, BK, DT, SEQ>(a); }
 
 }  // namespace fle

@@ -192,8 +192,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         int bk = forced_bk ? forced_bk : 256;
         if (forced == V_SKINNY) bk = 64;
         while (bk > 64 && K % bk != 0) bk /= 2;
-        // Row blocks of 32; blocks of 64 (two x blocks, which leave room for the 128-wide K step only) on request
-        plan->bm = (M > 32 && forced_bk == 128 && bk == 128) ? 64 : 32;
+        // Row blocks of 32.  More than 32 rows: blocks of 64 whose two halves take turns on a 256-wide W
+        // stage (automatic choice), or, on request, both halves at once on a 128-wide K step; a forced
+        // 256-wide K step keeps blocks of 32 (one workgroup each) for comparison.
+        // (with fewer than 64 W tiles the chip is not full and twice as many smaller workgroups do better)
+        plan->bm = (M > 32 && ((forced_bk == 128 && bk == 128) || (forced == V_AUTO && bk == 256 && N >= 8192))) ? 64 : 32;
         plan->bn = 128;
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile

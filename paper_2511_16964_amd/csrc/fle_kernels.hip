@@ -70,7 +70,8 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm == 32) return plan.bk == 256 ? gemm_bf16_skinny<1, 256, DT> : plan.bk == 128 ? gemm_bf16_skinny<1, 128, DT> : gemm_bf16_skinny<1, 64, DT>;
-            return gemm_bf16_skinny<2, 128, DT>;  // row blocks of 64: only with the 128-wide K step (the planner never asks for another)
+            // row blocks of 64: the two blocks in turn on a 256-wide K step, or both at once on a 128-wide one
+            return plan.bk == 256 ? gemm_bf16_skinny<2, 256, DT, true> : gemm_bf16_skinny<2, 128, DT>;
         };
         void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);

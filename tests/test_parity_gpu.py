@@ -33,6 +33,7 @@ def test_c1_fp32_bias_gelu_erf_full():
     ("tiled", 513, 772, 128), ("tiled", 200, 264, 72), ("tiled", 130, 132, 200), ("tiled256", 300, 520, 8), ("tiled128", 64, 128, 24),
     ("skinny", 32, 256, 64), ("skinny", 61, 132, 128), ("skinny", 7, 2052, 1024), ("skinny128", 32, 256, 256), ("skinny256", 19, 388, 512), ("skinny128", 64, 132, 384),
     ("skinny128", 64, 132, 320), ("skinny256", 40, 260, 192), ("skinny", 200, 388, 128),
+    ("auto_skinny_seq", 64, 8192, 512), ("auto_skinny_seq", 33, 8196, 512), ("auto_skinny_seq", 50, 16384, 256),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
@@ -41,7 +42,10 @@ def test_integer_inputs_are_bit_exact(variant, M, N, K):
     all is an indexing error (tile mapping, MFMA operand layout, LDS swizzle, masking)."""
     prob = inputs.random_problem(11, M, N, K, BF16, ["bias", "relu", "scale", "residual"], integer=True)
     announce("integer exact", variant, M, N, K)
-    got, call = run_gpu(prob, variant)
+    seq = variant == "auto_skinny_seq"   # automatic plan: row block of 64 whose halves take turns on a 256-wide W stage
+    got, call = run_gpu(prob, "auto" if seq else variant)
+    if seq:
+        assert "skinny" in call.plan() and "tile=64x128x256" in call.plan(), call.plan()
     ref = oracle_rows(prob)
     assert np.array_equal(ref, torch.from_numpy(ref).to(BF16).to(torch.float64).numpy()), "test premise: the exact result fits bf16"
     assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
@@ -185,6 +189,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("tiled", F32, 200, 392, 128), ("tiled256", F32, 150, 260, 100),
     ("tiled", BF16, 129, 259, 64), ("tiled256", BF16, 150, 262, 136), ("tiled", F32, 100, 261, 96),
     ("tiled", F16, 200, 392, 128), ("tiled256", F16, 150, 262, 136), ("skinny", F16, 32, 2304, 256), ("general", F16, 70, 97, 83),
+    ("auto", BF16, 48, 8192, 512), ("auto", F16, 64, 8192, 512),   # skinny kernel, one row block of 64 in two halves
 ]
 
 
