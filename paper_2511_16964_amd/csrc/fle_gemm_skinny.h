@@ -14,15 +14,17 @@ namespace fle {
 // Infinity Cache).  Same swizzle and orientation as the tiled kernel; the wave tile is
 // 32 TMB x 32, so the epilogue stays in the MFMA register layout.
 //
-// SEQ (two row blocks, K step 256): a stage of W with both x blocks does not fit LDS twice, so the two
-// blocks of 32 rows take turns on the same W stage, each with its own 16 KB x buffer: two W stages
-// of 64 KB and two x buffers are exactly the 160 KB.  While block 0 is multiplied, x block 1 of the
-// same K step and the next W stage are on their way; while block 1 is multiplied, x block 0 of the
-// next K step is.  The copies return in order, so the wait before block 1 allows exactly the
-// younger W stage to be outstanding.
+// SEQ (TMB = 2, 4 or 8 row blocks of 32, K step 256): a stage of W with all its x blocks does not fit
+// LDS twice, so the blocks take turns on the same W stage, each through one of two 16 KB x buffers:
+// two W stages of 64 KB and the two x buffers are exactly the 160 KB.  While block j is multiplied,
+// x block j+1 (of the next K step after the last block) is on its way, and the next W stage all
+// through the current one.  The copies of a wave return in order, so a wave that waited for a
+// young x block would also wait for the W stage issued before it; therefore the copy duties are
+// split by wave: waves 0 and 1 copy W (and wait once per stage), waves 2 and 3 copy x (and wait
+// every block); all four multiply.
 template <int TMB, int BK, int DT, bool SEQ = false>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
-    static_assert(!SEQ || (TMB == 2 && BK == 256), "the sequential variant is two row blocks on a 256-wide K step");
+    static_assert(!SEQ || ((TMB == 2 || TMB == 4 || TMB == 8) && BK == 256), "the sequential variant is 2, 4 or 8 row blocks on a 256-wide K step");
     static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");
     using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
     constexpr int BM = 32 * TMB, BN = 128;
@@ -104,29 +106,30 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
     int kt = int(int64_t(blockIdx.y) * KA / gridDim.y);
     const int KT = int(int64_t(blockIdx.y + 1) * KA / gridDim.y);
     if constexpr (SEQ) {
-        auto issue_w = [&](int k) {  // this wave's own 32 rows of W stage k
+        const bool w_wave = wave < 2;  // copy duty of this wave: W (waves 0, 1) or x (waves 2, 3)
+        auto issue_w = [&](int k) {    // 64 rows of W stage k
             char *base = smem + (k & 1) * SW;
             const uint32_t kb = uint32_t(k) * RB;
 #pragma unroll
-            for (int j = 0; j < NIW; ++j) {
-                const int row = j * RPI + lr;
-                const uint32_t voff = uint32_t(wave * 32 + row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 32 + j * RPI) * RB), 16, voff, 0, 0, 2);
+            for (int j = 0; j < 64 / RPI; ++j) {
+                const int row = wave * 64 + j * RPI + lr;
+                const uint32_t voff = uint32_t(row) * ldwb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void *)(base + (wave * 64 + j * RPI) * RB), 16, voff, 0, 0, 2);
             }
         };
-        auto issue_x = [&](int k, int blk) {  // this wave's 8 rows of x block blk at K step k
-            char *base = smem + 2 * SW + blk * SXB;
+        auto issue_x = [&](int k, int blk) {  // 16 rows of x block blk at K step k, into x buffer blk & 1
+            char *base = smem + 2 * SW + (blk & 1) * SXB;
             const uint32_t kb = uint32_t(k) * RB;
 #pragma unroll
-            for (int j = 0; j < 8 / RPI; ++j) {
-                const int row = wave * 8 + j * RPI + lr;  // row within the block; rows beyond M read zeros (out of range)
+            for (int j = 0; j < 16 / RPI; ++j) {
+                const int row = (wave - 2) * 16 + j * RPI + lr;  // row within the block; rows beyond M read zeros (out of range)
                 const uint32_t voff = uint32_t(blk * 32 + row) * ldxb + uint32_t((lp ^ sw(row)) & (CPR - 1)) * 16 + kb;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(base + (wave * 8 + j * RPI) * RB), 16, voff, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void *)(base + ((wave - 2) * 16 + j * RPI) * RB), 16, voff, 0, 0, 0);
             }
         };
         auto compute_blk = [&](int k, auto blk_c) {
             constexpr int BLK = decltype(blk_c)::value;
-            const char *sW = smem + (k & 1) * SW + wave * 32 * RB + fr * RB, *sX = smem + 2 * SW + BLK * SXB + fr * RB;
+            const char *sW = smem + (k & 1) * SW + wave * 32 * RB + fr * RB, *sX = smem + 2 * SW + (BLK & 1) * SXB + fr * RB;
 #pragma unroll
             for (int kk = 0; kk < KPS; ++kk) {
                 const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
@@ -136,22 +139,37 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 else acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[BLK], 0, 0, 0);
             }
         };
+        // one block step: wait for what this wave copied for it, let everyone catch up, send the next copies, multiply
+        auto block_step = [&](int k, auto blk_c, bool more) {
+            constexpr int BLK = decltype(blk_c)::value;
+            if (!w_wave || BLK == 0) wait_vmcnt<0>();   // x wave: x block BLK has landed; W wave, block 0: W stage k has
+            __builtin_amdgcn_s_barrier();                // everyone's have; the buffers of the previous block step are free
+            if (w_wave) {
+                if (BLK == 0 && more) issue_w(k + 1);
+            } else {
+                if (BLK + 1 < TMB) issue_x(k, BLK + 1);
+                else if (more) issue_x(k + 1, 0);
+            }
+            compute_blk(k, blk_c);
+        };
         if (kt < KT) {
-            issue_w(kt);
-            issue_x(kt, 0);
+            if (w_wave) issue_w(kt);
+            else issue_x(kt, 0);
         }
         for (; kt < KT; ++kt) {
             const bool more = kt + 1 < KT;
-            wait_vmcnt<0>();                 // W stage kt and x block 0 of it have landed (this wave's part)
-            __builtin_amdgcn_s_barrier();    // everyone's have; nobody reads x buffer 1 or the other W stage any more
-            issue_x(kt, 1);
-            if (more) issue_w(kt + 1);
-            compute_blk(kt, std::integral_constant<int, 0>{});
-            if (more) wait_vmcnt<NIW>();     // x block 1 has landed; the younger W stage may still be in flight
-            else wait_vmcnt<0>();
-            __builtin_amdgcn_s_barrier();    // everyone's has; nobody reads x buffer 0 any more
-            if (more) issue_x(kt + 1, 0);
-            compute_blk(kt, std::integral_constant<int, 1>{});
+            block_step(kt, std::integral_constant<int, 0>{}, more);
+            block_step(kt, std::integral_constant<int, 1>{}, more);
+            if constexpr (TMB >= 4) {
+                block_step(kt, std::integral_constant<int, 2>{}, more);
+                block_step(kt, std::integral_constant<int, 3>{}, more);
+            }
+            if constexpr (TMB >= 8) {
+                block_step(kt, std::integral_constant<int, 4>{}, more);
+                block_step(kt, std::integral_constant<int, 5>{}, more);
+                block_step(kt, std::integral_constant<int, 6>{}, more);
+                block_step(kt, std::integral_constant<int, 7>{}, more);
+            }
         }
     } else {
 #pragma unroll

@@ -127,8 +127,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         variant = V_TILED;
     }
     int forced_bk = 0;
-    if (variant == V_SKINNY_128 || variant == V_SKINNY_256) {
+    bool forced_seq = false;
+    if (variant == V_SKINNY_128 || variant == V_SKINNY_256 || variant == V_SKINNY_SEQ) {
         forced_bk = variant == V_SKINNY_128 ? 128 : 256;
+        forced_seq = variant == V_SKINNY_SEQ;
         variant = V_SKINNY;
     }
     const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 256 && K % 64 == 0;
@@ -166,7 +168,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     if (!best_tile) best_tile = forced_tile ? forced_tile : 128;
     if (variant == V_AUTO) {
-        if (skinny_ok && M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) variant = V_SKINNY;  // W is worth streaming
+        // W is worth streaming: always for a small M; up to 128 rows when W (256 MB or more) cannot stay in the
+        // Infinity Cache anyway (measured: 128 x 32768 x 8192 124 us against 156 us tiled; at 134 MB the tiled
+        // kernel wins warm and cold; 8 sub-blocks are slower than the tiled kernel everywhere)
+        if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) || (M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
         else {
             // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on
             // fp32 operands, 70 on bf16) or, for few workgroups and a long K, the serial chain of one
@@ -192,11 +197,13 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         int bk = forced_bk ? forced_bk : 256;
         if (forced == V_SKINNY) bk = 64;
         while (bk > 64 && K % bk != 0) bk /= 2;
-        // Row blocks of 32.  More than 32 rows: blocks of 64 whose two halves take turns on a 256-wide W
-        // stage (automatic choice), or, on request, both halves at once on a 128-wide K step; a forced
+        // Row blocks of 32.  More than 32 rows: one block of 64, 128 or 256 rows whose 32-row sub-blocks take
+        // turns on a 256-wide W stage (automatic choice; with fewer than 64 W tiles the chip is not full and
+        // more, smaller workgroups do better), or, on request, 64 rows at once on a 128-wide K step; a forced
         // 256-wide K step keeps blocks of 32 (one workgroup each) for comparison.
-        // (with fewer than 64 W tiles the chip is not full and twice as many smaller workgroups do better)
-        plan->bm = (M > 32 && ((forced_bk == 128 && bk == 128) || (forced == V_AUTO && bk == 256 && N >= 8192))) ? 64 : 32;
+        plan->bm = 32;
+        if (M > 32 && forced_bk == 128 && bk == 128) plan->bm = 64;
+        else if (M > 32 && bk == 256 && (forced_seq || (forced == V_AUTO && N >= 8192))) plan->bm = M <= 64 ? 64 : M <= 128 ? 128 : 256;
         plan->bn = 128;
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile

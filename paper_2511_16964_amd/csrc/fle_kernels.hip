@@ -70,8 +70,9 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm == 32) return plan.bk == 256 ? gemm_bf16_skinny<1, 256, DT> : plan.bk == 128 ? gemm_bf16_skinny<1, 128, DT> : gemm_bf16_skinny<1, 64, DT>;
-            // row blocks of 64: the two blocks in turn on a 256-wide K step, or both at once on a 128-wide one
-            return plan.bk == 256 ? gemm_bf16_skinny<2, 256, DT, true> : gemm_bf16_skinny<2, 128, DT>;
+            // larger row blocks: 32-row sub-blocks in turn on a 256-wide K step, or (64 rows) both at once on a 128-wide one
+            if (plan.bk == 128) return gemm_bf16_skinny<2, 128, DT>;
+            return plan.bm == 64 ? gemm_bf16_skinny<2, 256, DT, true> : plan.bm == 128 ? gemm_bf16_skinny<4, 256, DT, true> : gemm_bf16_skinny<8, 256, DT, true>;
         };
         void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);

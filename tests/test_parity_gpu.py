@@ -34,6 +34,7 @@ def test_c1_fp32_bias_gelu_erf_full():
     ("skinny", 32, 256, 64), ("skinny", 61, 132, 128), ("skinny", 7, 2052, 1024), ("skinny128", 32, 256, 256), ("skinny256", 19, 388, 512), ("skinny128", 64, 132, 384),
     ("skinny128", 64, 132, 320), ("skinny256", 40, 260, 192), ("skinny", 200, 388, 128),
     ("auto_skinny_seq", 64, 8192, 512), ("auto_skinny_seq", 33, 8196, 512), ("auto_skinny_seq", 50, 16384, 256),
+    ("skinnyseq", 100, 388, 512), ("skinnyseq", 200, 260, 512), ("skinnyseq", 256, 132, 256), ("skinnyseq", 33, 132, 512), ("skinnyseq", 129, 2052, 256),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
@@ -135,7 +136,7 @@ def test_integer_exact_on_the_256_tile():
 @pytest.mark.parametrize("variant,split,M,N,K", [
     ("tiled128", 3, 200, 264, 200), ("tiled256", 5, 300, 520, 576), ("tiled", 2, 130, 132, 72), ("tiled128", 64, 77, 132, 320),
     ("tiled256", 16, 513, 772, 512), ("skinny", 4, 61, 132, 512), ("skinny256", 3, 19, 388, 768), ("skinny128", 3, 64, 132, 384),
-    ("skinny128", 4, 32, 2052, 512), ("skinny", 7, 32, 260, 448),
+    ("skinny128", 4, 32, 2052, 512), ("skinny", 7, 32, 260, 448), ("skinnyseq", 2, 100, 388, 512), ("skinnyseq", 3, 200, 132, 768),
 ])
 def test_split_k_integer_inputs_are_bit_exact(variant, split, M, N, K):
     """K split over several workgroups per tile (uneven ranges, a ragged last K step, more splits
@@ -190,6 +191,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("tiled", BF16, 129, 259, 64), ("tiled256", BF16, 150, 262, 136), ("tiled", F32, 100, 261, 96),
     ("tiled", F16, 200, 392, 128), ("tiled256", F16, 150, 262, 136), ("skinny", F16, 32, 2304, 256), ("general", F16, 70, 97, 83),
     ("auto", BF16, 48, 8192, 512), ("auto", F16, 64, 8192, 512),   # skinny kernel, one row block of 64 in two halves
+    ("skinnyseq", BF16, 100, 2304, 512), ("skinnyseq", F16, 250, 520, 256),   # four and eight sub-blocks in turn
 ]
 
 
