@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused linear + epilogue hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|g1|g2]
 
 A step is one pass of the whole path (every kernel the call enqueues) over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s
@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -142,12 +142,35 @@ def cpu_baseline(prob, inputs, flops_per_row, budget_s=12.0):
             "sample": "first %d of %d rows, all %d columns, %.1f s" % (n, prob.M, prob.N, t)}
 
 
+def cpu_baseline_grouped(gp, inputs, budget_s=12.0):
+    """The oracle's loop over groups on a bounded sample: the first rows of every group, all columns."""
+    import oracle
+    G = len(gp.offsets) - 1
+    def run(per_group):
+        rows, counts = [], []
+        for lo, hi in zip(gp.offsets, gp.offsets[1:]):
+            n = min(per_group, hi - lo)
+            rows += list(range(lo, lo + n)); counts.append(n)
+        off = [0]
+        for c in counts:
+            off.append(off[-1] + c)
+        x, w, b = inputs.to_f64(gp.x[rows]), inputs.to_f64(gp.w), inputs.to_f64(gp.b)
+        t0 = time.perf_counter()
+        oracle.grouped_fused_linear_epilogue(x, w, b, off, inputs.epilogue_f64(gp.epilogue, rows))
+        return time.perf_counter() - t0, len(rows)
+    t, n = run(1)
+    per = int(max(1, min(gp.M, budget_s / max(t / max(n, 1), 1e-9)) // G))
+    t, n = run(per)
+    return {"value": 2.0 * gp.N * gp.K * n / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "first %d rows of each of %d groups (%d of %d rows), all %d columns, %.1f s" % (per, G, n, gp.M, gp.N, t)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -171,7 +194,34 @@ def main():
     dev_ep = lambda ep: [tuple(to(a) if isinstance(a, torch.Tensor) else a for a in e) for e in ep]
 
     # ---- workload
-    if args.workload == "c5":
+    grouped = args.workload in inputs.GROUPED_SHAPES
+    gp = None
+    if grouped:
+        # grouped form: rows routed to G groups, one weight matrix per group, one launch
+        gp = inputs.make_grouped(args.workload)
+        ep = dev_ep(gp.epilogue)
+        xg, wg, bg = to(gp.x), to(gp.w), to(gp.b)
+        off = torch.tensor(gp.offsets, dtype=torch.int64, device=dev)
+        calls = [binding.Call(xg, wg, bg, ep, offsets=off)]
+        probs = [gp]
+        flops = gp.flops
+        G = len(gp.offsets) - 1
+        live = [g for g in range(G) if gp.offsets[g + 1] > gp.offsets[g]]
+        desc = "%s: grouped %s, bf16, %d rows routed to %d groups (largest %d, empty %d), N=%d K=%d" % (
+            args.workload, "+".join(["linear"] + [e[0] for e in gp.epilogue]), gp.M, G,
+            max(b - a for a, b in zip(gp.offsets, gp.offsets[1:])), G - len(live), gp.N, gp.K)
+        spans = [(g, gp.offsets[g], gp.offsets[g + 1]) for g in live]
+        eager_out = torch.empty(gp.M, gp.N, dtype=xg.dtype, device=dev)
+        def eager():  # the loop over groups in PyTorch eager (host-side offsets, so no synchronisation is charged to it)
+            for g, lo, hi in spans:
+                eager_out[lo:hi] = F.gelu(F.linear(xg[lo:hi], wg[g]) + bg[g], approximate="tanh")
+            return eager_out
+        # weights of the groups that own rows, x, bias, out
+        alg_bytes = 2 * (len(live) * gp.N * gp.K + gp.M * gp.K + len(live) * gp.N + gp.M * gp.N)
+        # the same loop over groups with one plain fused call per group
+        loop_out = torch.empty(gp.M, gp.N, dtype=xg.dtype, device=dev)
+        loop_calls = [binding.Call(xg[lo:hi], wg[g], bg[g], ep, out=loop_out[lo:hi]) for g, lo, hi in spans]
+    elif args.workload == "c5":
         blk = inputs.make_mlp()
         p1 = blk.call1()
         xg = to(blk.x)
@@ -211,9 +261,14 @@ def main():
     plans = [c.plan() for c in calls]
     import oracle
     prob0 = probs[0]
-    rows = sorted(set([0, prob0.M - 1] + list(np.random.default_rng(1).integers(0, prob0.M, 6))))
-    ref = oracle.fused_linear_epilogue(inputs.to_f64(prob0.x[rows]), inputs.to_f64(prob0.w), inputs.to_f64(prob0.b),
-                                       inputs.epilogue_f64(prob0.epilogue, rows))
+    rows = sorted(set([0, prob0.M - 1] + [int(r) for r in np.random.default_rng(1).integers(0, prob0.M, 6)]))
+    if grouped:
+        owner = np.searchsorted(np.asarray(gp.offsets[1:]), np.asarray(rows), side="right")
+        ref = np.concatenate([oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(gp.b[g]),
+                                                           inputs.epilogue_f64(gp.epilogue, [m])) for m, g in zip(rows, owner)])
+    else:
+        ref = oracle.fused_linear_epilogue(inputs.to_f64(prob0.x[rows]), inputs.to_f64(prob0.w), inputs.to_f64(prob0.b),
+                                           inputs.epilogue_f64(prob0.epilogue, rows))
     got = calls[0].out[rows].cpu().to(torch.float64).numpy()
     tol = 2e-2 if prob0.dtype == torch.bfloat16 else 1e-4
     s = min(1.0, float(np.sqrt(np.mean(ref * ref))))
@@ -240,7 +295,7 @@ def main():
         "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
                           "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
-    hbm_bound = args.workload == "c4"
+    hbm_bound = args.workload in ("c4", "g2")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES[args.workload]}
@@ -253,11 +308,18 @@ def main():
 
     if not args.no_eager:
         ewall, eev = time_loop(torch, eager, max(10, args.steps // 4), 5)
-        mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
-        out["eager"] = {"ms_per_step": ewall, "tflops": flops / (ewall * 1e-3) / 1e12, "speedup_fused_vs_eager": ewall / wall_ms,
-                        "bare_matmul_first_call_tflops": probs[0].flops / (mm_wall * 1e-3) / 1e12}
+        out["eager"] = {"ms_per_step": ewall, "tflops": flops / (ewall * 1e-3) / 1e12, "speedup_fused_vs_eager": ewall / wall_ms}
+        if grouped:
+            def loop_step():
+                for c in loop_calls:
+                    c.run()
+            lwall, _ = time_loop(torch, loop_step, max(10, args.steps // 4), 5)
+            out["loop_of_plain_fused_calls"] = {"ms_per_step": lwall, "calls": len(loop_calls), "speedup_grouped_vs_loop": lwall / wall_ms}
+        else:
+            mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
+            out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
+        out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs) if grouped else cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
     if args.calibrate_copy:
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)

@@ -124,6 +124,41 @@ fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out);
  * synchronising.  Never allocates or frees device memory. */
 fle_status fle_run(const fle_problem *p);
 
+/*
+ * Grouped form: the rows of x are cut into G consecutive groups and group g is multiplied by its
+ * own weight matrix W_g (and gets its own bias b_g), all in one launch.  This is the layout of a
+ * mixture-of-experts layer after the tokens have been sorted by expert; the paper's appendix on
+ * outlier tasks (Level 5, the mixture-of-experts task) reports that replacing the loop over experts
+ * by one grouped matrix multiplication over packed expert weights is what gave its ~10x there.
+ *
+ *     out[m, :] = epilogue( x[m, :] * W_g^T ),   row_offsets[g] <= m < row_offsets[g+1]
+ *
+ * The fle_problem describes the stacked operands: M is the total number of rows, x / out / every
+ * residual operand are [M, ...] as in the plain form, p->w points to W_0 and p->b to b_0.  The
+ * epilogue (any list the plain form accepts) is the same for every group; LayerNorm's gamma / beta
+ * are shared.
+ */
+typedef struct {
+    int32_t n_groups;           /* G, 1 .. 65536                                                  */
+    const int64_t *row_offsets; /* DEVICE array of G + 1 entries, non-decreasing, [0] = 0 and
+                                   [G] = M; group g owns rows [g] .. [g+1] - 1 (possibly none).
+                                   Read by the kernel only, so a routing kernel may still be
+                                   writing it on the same stream when the call is made.  Entries
+                                   are clamped to 0 .. M and to be non-decreasing before use, so a
+                                   malformed array never causes an out-of-bounds access; rows that
+                                   no group owns are left undefined in out.                       */
+    int64_t w_group_stride;     /* elements from W_g to W_g+1 (N * ldw for packed weights); a
+                                   multiple of 16 bytes                                           */
+    int64_t b_group_stride;     /* elements from b_g to b_g+1 (0: one bias for all groups)        */
+} fle_groups;
+
+/* As fle_validate / fle_workspace_size / fle_run, for a grouped problem.  Grouped problems run on the
+ * tiled MFMA kernels only: x and W must satisfy that path's 16-byte rule (see above), otherwise
+ * FLE_ERR_UNSUPPORTED; K is never split.  The structs are read during the call only. */
+fle_status fle_validate_grouped(const fle_problem *p, const fle_groups *g);
+fle_status fle_workspace_size_grouped(const fle_problem *p, const fle_groups *g, size_t *bytes_out);
+fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
+
 /* Static description of a status code. */
 const char *fle_status_string(fle_status s);
 
@@ -139,7 +174,8 @@ fle_status fle_last_plan(char *buf, size_t n);
  * (bf16 / fp16, M <= 256) with a K step of 64, 4 = tiled with the 256x256 tile, 5 = tiled with
  * the 128x128 tile, 6 / 7 = skinny kernel with a K step of 128 / 256, 8 = skinny kernel with one
  * row block of up to 256 rows whose 32-row sub-blocks take turns on a 256-wide K step.
- * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run. */
+ * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run.  Grouped
+ * problems accept 0, 2, 4 and 5. */
 void fle_force_variant(int variant);
 
 /* Force the split of K for the calling thread's next calls on the tiled and skinny kernels, for

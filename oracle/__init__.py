@@ -128,3 +128,36 @@ def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
     if rc != 0:
         raise ValueError("fle_oracle_run rejected the arguments (code %d)" % rc)
     return out
+
+
+def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0) -> np.ndarray:
+    """float64 gold result of the grouped form: the loop over groups written out.
+
+    Rows ``offsets[g] .. offsets[g+1]-1`` of x go through ``fused_linear_epilogue`` with
+    ``w[g]`` (and ``b[g]``), exactly the per-expert loop that the paper's appendix on outlier
+    tasks (Level 5, the mixture-of-experts task) says the optimised solutions replace by one
+    grouped matrix multiplication; the grouping never changes a row's result.
+
+    x [M,K]; w [G,N,K]; b [G,N], [N] (shared) or None; offsets: G+1 non-decreasing integers
+    from 0 to M; residual operands in the epilogue are [M,N].  Returns [M,N], or [M] when the
+    list ends in logsumexp.
+    """
+    x, w = _f64(x), _f64(w)
+    b = _f64(b)
+    if x.ndim != 2 or w.ndim != 3 or x.shape[1] != w.shape[2]:
+        raise ValueError("x must be [M,K] and w [G,N,K]")
+    offsets = [int(o) for o in offsets]
+    G, N = w.shape[0], w.shape[1]
+    M = x.shape[0]
+    if len(offsets) != G + 1 or offsets[0] != 0 or offsets[-1] != M or any(a > c for a, c in zip(offsets, offsets[1:])):
+        raise ValueError("offsets must be G+1 non-decreasing integers from 0 to M")
+    lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
+    out = np.empty((M,) if lse else (M, N), dtype=np.float64)
+    for g in range(G):
+        lo, hi = offsets[g], offsets[g + 1]
+        if hi == lo:
+            continue
+        ep = [("residual", np.asarray(e[1])[lo:hi]) if e[0] == "residual" else e for e in epilogue]
+        bg = None if b is None else (b[g] if b.ndim == 2 else b)
+        out[lo:hi] = fused_linear_epilogue(x[lo:hi], w[g], bg, ep, n_threads)
+    return out

@@ -7,10 +7,10 @@ implementation: if the library is missing, calls raise.
 """
 import importlib
 
-__all__ = ["fused_linear_epilogue"]
+__all__ = ["fused_linear_epilogue", "grouped_fused_linear_epilogue"]
 
 
 def __getattr__(name):
-    if name == "fused_linear_epilogue":
-        return importlib.import_module(__name__ + ".binding").fused_linear_epilogue
+    if name in __all__:
+        return getattr(importlib.import_module(__name__ + ".binding"), name)
     raise AttributeError(name)

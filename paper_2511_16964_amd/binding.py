@@ -19,7 +19,8 @@ OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "re
 MAX_OPS = 8
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8}
 EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
-           "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version"]
+           "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
+           "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped"]
 
 
 class FleOp(ctypes.Structure):
@@ -37,6 +38,11 @@ class FleProblem(ctypes.Structure):
                 ("ops", ctypes.POINTER(FleOp)), ("n_ops", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
+
+
+class FleGroups(ctypes.Structure):
+    _fields_ = [("n_groups", ctypes.c_int32), ("row_offsets", ctypes.c_void_p),
+                ("w_group_stride", ctypes.c_int64), ("b_group_stride", ctypes.c_int64)]
 
 
 class FleError(RuntimeError):
@@ -61,6 +67,11 @@ def lib():
             getattr(L, name).argtypes = [ctypes.POINTER(FleProblem)]
         L.fle_workspace_size.restype = ctypes.c_int
         L.fle_workspace_size.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(ctypes.c_size_t)]
+        for name in ("fle_validate_grouped", "fle_run_grouped"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FleGroups)]
+        L.fle_workspace_size_grouped.restype = ctypes.c_int
+        L.fle_workspace_size_grouped.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FleGroups), ctypes.POINTER(ctypes.c_size_t)]
         L.fle_status_string.restype = ctypes.c_char_p
         L.fle_status_string.argtypes = [ctypes.c_int]
         L.fle_last_error.restype = ctypes.c_char_p
@@ -106,17 +117,32 @@ class Call:
     """A marshalled fle_problem bound to its tensors: ``run()`` enqueues it on the
     current stream.  Keeps every tensor alive; reusable (the benchmark times ``run``)."""
 
-    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):
-        if x.dim() != 2 or w.dim() != 2 or x.shape[1] != w.shape[1]:
-            raise ValueError("x must be [M,K] and w [N,K]")
-        if x.stride(1) != 1 and x.shape[1] > 1 or w.stride(1) != 1 and w.shape[1] > 1:
+    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0, offsets=None):
+        grouped = offsets is not None
+        if x.dim() != 2 or w.dim() != (3 if grouped else 2) or x.shape[1] != w.shape[-1]:
+            raise ValueError("x must be [M,K] and w [N,K] (grouped: [G,N,K])")
+        if x.stride(1) != 1 and x.shape[1] > 1 or w.stride(-1) != 1 and w.shape[-1] > 1:
             raise ValueError("x and w must be row-major (unit stride along K)")
         self.variant = VARIANTS[variant]
         self.split = int(split)  # 0: automatic split of K; S >= 1 forces S workgroups per tile
         M, K = x.shape
-        N = w.shape[0]
+        N = w.shape[-2]
         dt = x.dtype
         tensors = [x, w, b]
+        self._groups = None
+        if grouped:
+            G = w.shape[0]
+            if offsets.dtype != torch.int64 or offsets.dim() != 1 or offsets.numel() != G + 1 or not offsets.is_contiguous() or offsets.device != x.device:
+                raise ValueError("offsets must be a contiguous int64 tensor of G + 1 entries on x's device")
+            if b is not None and b.dim() == 2 and (b.shape != (G, N) or (b.stride(1) != 1 and N > 1)):
+                raise ValueError("grouped b must be [G,N] (or [N], shared by all groups)")
+            g = FleGroups()
+            g.n_groups, g.row_offsets = G, offsets.data_ptr()
+            g.w_group_stride = w.stride(0) if G > 1 else 0
+            g.b_group_stride = b.stride(0) if (b is not None and b.dim() == 2 and G > 1) else 0
+            self._groups, self._gref = g, ctypes.byref(g)
+            tensors.append(offsets)
+            offsets = None
         if len(epilogue) > MAX_OPS:
             raise ValueError("at most %d epilogue ops" % MAX_OPS)
         ops = (FleOp * max(1, len(epilogue)))()
@@ -139,7 +165,7 @@ class Call:
                 ops[i].p1 = None if be is None else be.data_ptr()
                 ops[i].alpha = float(eps)
         for t in tensors:
-            if t is not None and (t.dtype != dt or t.device != x.device):
+            if t is not None and t.dtype != torch.int64 and (t.dtype != dt or t.device != x.device):
                 raise TypeError("all operands must share x's dtype and device")
         lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
         if out is None:
@@ -148,7 +174,7 @@ class Call:
         p = FleProblem()
         p.M, p.N, p.K, p.dtype = M, N, K, _dtype_code(dt)
         p.x, p.ldx = x.data_ptr(), (x.stride(0) if M > 1 else max(K, x.stride(0)))
-        p.w, p.ldw = w.data_ptr(), (w.stride(0) if N > 1 else max(K, w.stride(0)))
+        p.w, p.ldw = w.data_ptr(), (w.stride(-2) if N > 1 else max(K, w.stride(-2)))
         p.b = None if b is None else b.data_ptr()
         p.out = out.data_ptr()
         p.ldo = 0 if lse else (out.stride(0) if M > 1 else max(N, out.stride(0)))
@@ -160,7 +186,10 @@ class Call:
         L.fle_force_split(self.split)
         try:
             need = ctypes.c_size_t(0)
-            _check(L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)))
+            if self._groups is None:
+                _check(L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)))
+            else:
+                _check(L.fle_workspace_size_grouped(ctypes.byref(p), self._gref, ctypes.byref(need)))
         finally:
             L.fle_force_variant(0)
             L.fle_force_split(0)
@@ -178,12 +207,12 @@ class Call:
         # the HIP stream handle: torch's current stream on the operands' device unless one is given
         self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
         if self.variant == 0 and self.split == 0:
-            status = L.fle_run(self._pref)
+            status = L.fle_run(self._pref) if self._groups is None else L.fle_run_grouped(self._pref, self._gref)
         else:
             L.fle_force_variant(self.variant)
             L.fle_force_split(self.split)
             try:
-                status = L.fle_run(self._pref)
+                status = L.fle_run(self._pref) if self._groups is None else L.fle_run_grouped(self._pref, self._gref)
             finally:
                 L.fle_force_variant(0)
                 L.fle_force_split(0)
@@ -195,6 +224,18 @@ class Call:
         buf = ctypes.create_string_buffer(256)
         lib().fle_last_plan(buf, 256)
         return buf.value.decode()
+
+
+def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, out=None, workspace=None, variant="auto"):
+    """Grouped form: rows offsets[g] .. offsets[g+1]-1 of x go through w[g] (and b[g]), one launch.
+
+    x [M,K]; w [G,N,K]; b [G,N], [N] (shared) or None; offsets: int64 tensor [G+1] on the device,
+    non-decreasing from 0 to M (read by the kernel only, no host synchronisation); epilogue as in
+    ``fused_linear_epilogue`` with residual operands [M,N].  Returns [M,N] (or [M] for logsumexp).
+    """
+    if not x.is_cuda:
+        raise RuntimeError("grouped_fused_linear_epilogue runs on the GPU only; there is no CPU path")
+    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, offsets=offsets).run()
 
 
 def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):

@@ -81,10 +81,116 @@ __device__ __forceinline__ float row16_allreduce(float v) {
     return v;
 }
 
+// The output tile a workgroup computes: its origin, the first row past the rows it may touch (the
+// end of the matrix, or of the row group that owns the tile), and the W and bias of that owner.
+struct TileRef {
+    int64_t m0, n0, m_end;
+    const void *w, *bias;
+};
+
+// Workgroup id -> tile of a tiles_m x tiles_n grid.  Consecutive workgroup ids go round-robin over
+// the 8 XCDs, so give each XCD a contiguous range of tile ids, then walk tiles in groups of 4 tile
+// rows: the tiles an XCD works on at any time share x and W panels in its own L2.
+__device__ __forceinline__ void tile_of_workgroup(uint32_t bid, uint32_t tiles_m, uint32_t tiles_n, int &tile_m, int &tile_n) {
+    const uint32_t G = tiles_m * tiles_n;
+    const uint32_t per = G / 8, rem = G % 8, xcd = bid % 8, loc = bid / 8;
+    const uint32_t id = loc + xcd * per + (xcd < rem ? xcd : rem);
+    const uint32_t width = 4 * tiles_n;
+    const uint32_t first_m = (id / width) * 4;
+    const uint32_t gsz = (tiles_m - first_m) < 4 ? (tiles_m - first_m) : 4;
+    tile_m = int(first_m + (id % width) % gsz);
+    tile_n = int((id % width) / gsz);
+}
+
+template <int BM>
+__device__ __forceinline__ TileRef whole_matrix_tile(const GemmArgs &a) {
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, uint32_t(a.tiles_m), uint32_t(a.tiles_n), tile_m, tile_n);
+    return TileRef{int64_t(tile_m) * BM, int64_t(tile_n) * BM, a.M, a.w, a.epi.bias};
+}
+
+// Grouped problems: the rows of x / out / residual are cut into consecutive groups by a device array
+// of offsets, and group g multiplies by its own W (and adds its own bias).
+struct GroupArgs {
+    const int64_t *row_offsets;  // [n_groups + 1], device memory
+    int32_t n_groups;
+    int64_t w_stride_bytes;      // from one group's W (bias) to the next group's
+    int64_t b_stride_bytes;
+};
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = uint32_t(__shfl_up(int(v), d, 64));
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+__device__ __forceinline__ int64_t wave_pick_i64(int64_t v, int src) {
+    const uint32_t lo = uint32_t(__builtin_amdgcn_readfirstlane(__shfl(int(uint32_t(v)), src, 64)));
+    const uint32_t hi = uint32_t(__builtin_amdgcn_readfirstlane(__shfl(int(uint32_t(uint64_t(v) >> 32)), src, 64)));
+    return int64_t((uint64_t(hi) << 32) | lo);
+}
+
+// Workgroup id -> tile of a grouped problem.  Group g owns ceil(rows_g / BM) tile rows, which start at
+// the group's first row, so no tile straddles two groups.  The offsets live in device memory (a router
+// kernel usually writes them), so every workgroup derives the mapping itself: each lane takes one
+// group, a wave prefix sum over the groups' tile rows gives the total (for the XCD-aware id -> tile
+// mapping) and then the group holding this workgroup's tile row.  Offsets are clamped to [0, M] and
+// to be non-decreasing, so whatever the array holds, every access stays inside the operands.
+// Returns false for the surplus workgroups of the launch (the grid is sized for the worst case).
+template <int BM>
+__device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs &ga, TileRef &t) {
+    const int lane = threadIdx.x & 63;
+    const int64_t M = a.M;
+    const int G = ga.n_groups;
+    auto group_rows = [&](int g, int64_t &b, int64_t &e) -> uint32_t {  // tile rows of group g (0 beyond the last group)
+        b = e = 0;
+        if (g >= G) return 0u;
+        b = ga.row_offsets[g];
+        e = ga.row_offsets[g + 1];
+        b = b < 0 ? 0 : (b > M ? M : b);
+        e = e < b ? b : (e > M ? M : e);
+        return uint32_t((e - b + BM - 1) / BM);
+    };
+    uint32_t total = 0;
+    for (int c = 0; c < G; c += 64) {
+        int64_t b, e;
+        const uint32_t incl = wave_inclusive_scan(group_rows(c + lane, b, e), lane);
+        total += uint32_t(__builtin_amdgcn_readfirstlane(__shfl(int(incl), 63, 64)));
+    }
+    const uint32_t tiles_n = uint32_t(a.tiles_n);
+    if (blockIdx.x >= total * tiles_n) return false;
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, total, tiles_n, tile_m, tile_n);
+    uint32_t base = 0;
+    for (int c = 0; c < G; c += 64) {
+        int64_t b, e;
+        const uint32_t mine = group_rows(c + lane, b, e);
+        const uint32_t incl = wave_inclusive_scan(mine, lane);
+        const uint64_t hit = __ballot(base + incl > uint32_t(tile_m));
+        if (hit) {
+            const int src = __builtin_ctzll(hit);
+            const uint32_t first = base + uint32_t(__builtin_amdgcn_readfirstlane(__shfl(int(incl - mine), src, 64)));  // first tile row of the group
+            const int64_t gb = wave_pick_i64(b, src), ge = wave_pick_i64(e, src);
+            const int64_t g = c + src;
+            t.m0 = gb + int64_t(uint32_t(tile_m) - first) * BM;
+            t.m_end = ge;
+            t.n0 = int64_t(tile_n) * BM;
+            t.w = reinterpret_cast<const char *>(a.w) + g * ga.w_stride_bytes;
+            t.bias = a.epi.bias ? reinterpret_cast<const char *>(a.epi.bias) + g * ga.b_stride_bytes : nullptr;
+            return true;
+        }
+        base += uint32_t(__builtin_amdgcn_readfirstlane(__shfl(int(incl), 63, 64)));
+    }
+    return false;  // not reached: tile_m < total
+}
+
 // EDGE: N, the leading dimensions or the addresses of b / residual / out do not allow 4-column vector
 // accesses; the epilogue then touches memory one element at a time, masked per column.
 template <int BM, int BN, int DT, bool EDGE>
-__device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
+__device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef &t) {
     constexpr bool F32 = DT == FLE_F32;
     constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
@@ -99,23 +205,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t M = a.M, N = a.N;
+    const int64_t M = t.m_end, N = a.N;  // M: first row past the rows this tile may touch
 
-    // Workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs, so give each
-    // XCD a contiguous range of tile ids, then walk tiles in groups of 4 tile rows: the tiles
-    // an XCD works on at any time share x and W panels in its own L2.
-    int tile_m, tile_n;
-    {
-        const uint32_t G = uint32_t(a.tiles_m) * uint32_t(a.tiles_n), bid = blockIdx.x;
-        const uint32_t per = G / 8, rem = G % 8, xcd = bid % 8, loc = bid / 8;
-        const uint32_t id = loc + xcd * per + (xcd < rem ? xcd : rem);
-        const uint32_t width = 4 * uint32_t(a.tiles_n);
-        const uint32_t first_m = (id / width) * 4;
-        const uint32_t gsz = (uint32_t(a.tiles_m) - first_m) < 4 ? (uint32_t(a.tiles_m) - first_m) : 4;
-        tile_m = int(first_m + (id % width) % gsz);
-        tile_n = int((id % width) / gsz);
-    }
-    const int64_t m0 = int64_t(tile_m) * BM, n0 = int64_t(tile_n) * BN;
+    const int64_t m0 = t.m0, n0 = t.n0;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t m_wave = m0 + wm * WM, n_wave = n0 + wn * WN;  // origin of this wave's outputs
 
@@ -155,7 +247,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
     TileLoader<BM> ldx_;
     TileLoader<BN> ldw_;
     ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * ES, a.ldx * ES, M - m0, a.K * ES, wave, lane);
-    ldw_.init(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
+    ldw_.init(reinterpret_cast<const char *>(t.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
     constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
 
     // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
@@ -264,9 +356,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
             if constexpr (EDGE) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(a.epi.bias, n_col[hc] + e, DT);
+                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(t.bias, n_col[hc] + e, DT);
             } else {
-                bias_v[hc] = ld4<DT>(a.epi.bias, n_ok[hc] ? n_col[hc] : N - 4);
+                bias_v[hc] = ld4<DT>(t.bias, n_ok[hc] ? n_col[hc] : N - 4);
             }
         }
     }
@@ -479,9 +571,23 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a) {
 // fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
 template <int DT, bool EDGE>
-__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE>(a); }
+__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE>(a, whole_matrix_tile<256>(a)); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
 template <int DT, bool EDGE>
-__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE>(a); }
+__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE>(a, whole_matrix_tile<128>(a)); }
+
+// Grouped forms: the same tiles, with the tile -> rows mapping taken from the group offsets.
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256) void gemm_tiled_grouped_256(const GemmArgs a, const GroupArgs ga) {
+    TileRef t;
+    if (!grouped_tile<256>(a, ga, t)) return;
+    gemm_tiled_body<256, 256, DT, EDGE>(a, t);
+}
+template <int DT, bool EDGE>
+__global__ __launch_bounds__(256, 2) void gemm_tiled_grouped_128(const GemmArgs a, const GroupArgs ga) {
+    TileRef t;
+    if (!grouped_tile<128>(a, ga, t)) return;
+    gemm_tiled_body<128, 128, DT, EDGE>(a, t);
+}
 
 }  // namespace fle

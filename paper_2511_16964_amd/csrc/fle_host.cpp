@@ -41,7 +41,7 @@ static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
     return (static_cast<size_t>(rows - 1) * static_cast<size_t>(ld) + static_cast<size_t>(cols)) * es;
 }
 
-fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan) {
+fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
     if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
@@ -51,6 +51,15 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     if (M > kLimit || N > (int64_t(1) << 30) || K > (int64_t(1) << 30)) return fail(FLE_ERR_SHAPE, "size too large");
     if (p->n_ops < 0 || p->n_ops > FLE_MAX_OPS) return fail(FLE_ERR_OP, "n_ops %d outside 0..%d", p->n_ops, FLE_MAX_OPS);
     if (p->n_ops > 0 && !p->ops) return fail(FLE_ERR_NULL, "ops is NULL with n_ops %d", p->n_ops);
+
+    const int64_t G = grp ? grp->n_groups : 0;
+    if (grp) {
+        if (G < 1 || G > 65536) return fail(FLE_ERR_SHAPE, "n_groups %lld outside 1..65536", (long long)G);
+        if (grp->w_group_stride < 0 || grp->b_group_stride < 0 || grp->w_group_stride > kLimit || grp->b_group_stride > kLimit) return fail(FLE_ERR_SHAPE, "group strides must be >= 0");
+        if (M > 0 && !grp->row_offsets) return fail(FLE_ERR_NULL, "row_offsets is NULL");
+        if (!aligned(grp->row_offsets, 8)) return fail(FLE_ERR_ALIGN, "row_offsets is not aligned to 8 bytes");
+    }
+    plan->groups = int32_t(G);
 
     DevEpilogue &e = plan->epi;
     e.row_kind = -1;
@@ -88,9 +97,12 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         // element alignment is the only hard requirement
         if (!aligned(p->x, es) || !aligned(p->w, es) || !aligned(p->out, es) || !aligned(p->b, es)) return fail(FLE_ERR_ALIGN, "a pointer is not aligned to its element size");
         const size_t out_bytes = lse ? size_t(M) * es : span_bytes(M, N, p->ldo, es);
-        if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, es)) || overlaps(p->out, out_bytes, p->w, span_bytes(N, K, p->ldw, es)) ||
-            overlaps(p->out, out_bytes, p->b, size_t(N) * es))
+        const size_t w_bytes = span_bytes(N, K, p->ldw, es) + (grp ? size_t(G - 1) * size_t(grp->w_group_stride) * es : 0);
+        const size_t b_bytes = size_t(N) * es + (grp ? size_t(G - 1) * size_t(grp->b_group_stride) * es : 0);
+        if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, es)) || overlaps(p->out, out_bytes, p->w, w_bytes) || overlaps(p->out, out_bytes, p->b, b_bytes))
             return fail(FLE_ERR_UNSUPPORTED, "out overlaps x, w or b");
+        if (grp && (overlaps(p->out, out_bytes, grp->row_offsets, size_t(G + 1) * 8) || overlaps(p->workspace, p->workspace_bytes, grp->row_offsets, size_t(G + 1) * 8)))
+            return fail(FLE_ERR_UNSUPPORTED, "out or the workspace overlaps row_offsets");
         for (int i = 0; i < p->n_ops; ++i) {
             const fle_op &op = p->ops[i];
             if (op.kind == FLE_RESIDUAL) {
@@ -119,8 +131,27 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // x and W rows must be whole, aligned 16-byte chunks; everything the epilogue touches may be ragged
     // (the kernel then has an element-wise epilogue)
     const bool tiled_ok = K >= chunk && K % chunk == 0 && aligned(p->x, 16) && aligned(p->w, 16) && p->ldx % chunk == 0 && p->ldw % chunk == 0 &&
-                          p->ldx < ld_max && p->ldw < ld_max;
-    const bool vec_epi = N % 4 == 0 && (lse || (aligned(p->out, vec4) && p->ldo % 4 == 0)) && aligned(p->b, vec4) && res_ok;
+                          p->ldx < ld_max && p->ldw < ld_max && (!grp || grp->w_group_stride % chunk == 0);
+    const bool vec_epi = N % 4 == 0 && (lse || (aligned(p->out, vec4) && p->ldo % 4 == 0)) && aligned(p->b, vec4) && res_ok && (!grp || grp->b_group_stride % 4 == 0);
+    if (grp) {
+        // Grouped problems run on the tiled kernels only, one workgroup per tile over the whole K.  A group's
+        // tile rows start at its first row, so with rows spread over G groups about G / 2 tile rows are
+        // partly empty: the 256 tile (1.45 us per K step for 4 times the outputs of a 128 tile, which costs
+        // 0.85 / 2 with two workgroups per CU) only pays when groups hold several hundred rows.
+        if (forced != V_AUTO && forced != V_TILED && forced != V_TILED_256 && forced != V_TILED_128) return fail(FLE_ERR_UNSUPPORTED, "grouped problems run on the tiled kernels only");
+        if (forced_split > 1) return fail(FLE_ERR_UNSUPPORTED, "grouped problems are not split along K");
+        if (!tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "a grouped problem needs x and W rows made of whole, 16-byte aligned chunks (K, the leading dimensions and the W group stride multiples of 16 bytes)");
+        if (forced == V_AUTO || forced == V_TILED) {
+            auto cost = [&](int tile) -> double {
+                const double wgs = (double(M) / tile + 0.5 * double(G)) * double((N + tile - 1) / tile);
+                const double slots = tile == 128 ? 512.0 : 256.0;
+                const double per_step = p->dtype == FLE_F32 ? (tile == 256 ? 7.8 : 3.9) : (tile == 256 ? 1.45 : 0.85);
+                return (wgs > slots ? wgs / slots : 1.0) * per_step;
+            };
+            forced = (M > 128 && N > 128 && cost(256) < cost(128)) ? V_TILED_256 : V_TILED_128;
+        }
+        forced_split = 1;
+    }
     int variant = forced, forced_tile = 0;
     if (variant == V_TILED_256 || variant == V_TILED_128) {
         forced_tile = variant == V_TILED_256 ? 256 : 128;
@@ -221,6 +252,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->part_cols = 16;
     }
     plan->tiles_m = (M + plan->bm - 1) / plan->bm;
+    if (grp) {  // every group may end in a partly filled tile row; the kernel finds the actual count
+        plan->tiles_m = M / plan->bm + G;
+        if (plan->tiles_m > M) plan->tiles_m = M;
+    }
     plan->tiles_n = (N + plan->bn - 1) / plan->bn;
     if (plan->tiles_m * plan->tiles_n > (int64_t(1) << 31) - 1) return fail(FLE_ERR_SHAPE, "too many tiles for one launch");
 
@@ -287,9 +322,17 @@ static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
     const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
     snprintf(buf, n, "variant=%s_%s_mfma%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             plan.variant == V_TILED ? "tiled" : plan.variant == V_SKINNY ? "skinny" : "general", dt,
+             plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : "general", dt,
              plan.edge ? "+edge" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
+}
+
+static fle_status check_workspace(const fle_problem *p, const Plan &plan) {
+    if (plan.ws_total == 0) return FLE_OK;
+    if (!p->workspace) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", plan.ws_total);
+    if (p->workspace_bytes < plan.ws_total) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_total);
+    if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
+    return FLE_OK;
 }
 
 extern "C" {
@@ -315,12 +358,43 @@ fle_status fle_run(const fle_problem *p) {
     fle_status s = make_plan(p, g_forced, g_split, &plan);
     if (s != FLE_OK) return s;
     if (p->M == 0) return FLE_OK;
-    if (plan.ws_total > 0) {
-        if (!p->workspace) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", plan.ws_total);
-        if (p->workspace_bytes < plan.ws_total) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_total);
-        if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
+    s = check_workspace(p, plan);
+    if (s == FLE_OK) s = launch(p, plan);
+    if (s == FLE_OK) {
+        g_plan = plan;
+        g_have_plan = true;
     }
-    s = launch(p, plan);
+    return s;
+}
+
+static fle_status check_groups(const fle_groups *g) { return g ? FLE_OK : fail(FLE_ERR_NULL, "groups is NULL"); }
+
+fle_status fle_validate_grouped(const fle_problem *p, const fle_groups *g) {
+    Plan plan;
+    fle_status s = check_groups(g);
+    return s != FLE_OK ? s : make_plan(p, g_forced, g_split, &plan, g);
+}
+
+fle_status fle_workspace_size_grouped(const fle_problem *p, const fle_groups *g, size_t *bytes_out) {
+    if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
+    Plan plan;
+    fle_status s = check_groups(g);
+    if (s == FLE_OK) s = make_plan(p, g_forced, g_split, &plan, g);
+    if (s != FLE_OK) return s;
+    *bytes_out = plan.ws_total;
+    g_plan = plan;
+    g_have_plan = true;
+    return FLE_OK;
+}
+
+fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g) {
+    Plan plan;
+    fle_status s = check_groups(g);
+    if (s == FLE_OK) s = make_plan(p, g_forced, g_split, &plan, g);
+    if (s != FLE_OK) return s;
+    if (p->M == 0) return FLE_OK;
+    s = check_workspace(p, plan);
+    if (s == FLE_OK) s = launch(p, plan, g);
     if (s == FLE_OK) {
         g_plan = plan;
         g_have_plan = true;
@@ -355,6 +429,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 200; }  // 0.2.0: fp16 operands, split K, fle_force_split
+int fle_version(void) { return 300; }  // 0.3.0: grouped problems
 
 }  // extern "C"

@@ -1,6 +1,6 @@
 // Device side of libfle: hand-written gfx950 (CDNA4) kernels and their launcher.
 //
-//   fle_gemm_tiled.h     gemm_tiled_256 / _128: LDS-tiled MFMA GEMM (bf16, fp16, fp32) with the epilogue fused
+//   fle_gemm_tiled.h     gemm_tiled_256 / _128 (+ _grouped_): LDS-tiled MFMA GEMM (bf16, fp16, fp32) with the epilogue fused
 //   fle_gemm_skinny.h    gemm_bf16_skinny: HBM-bound GEMM for M <= 64 per row block (2-byte operands)
 //   fle_gemm_general.h   gemm_general: any shape / alignment / dtype, small tiles, in-block split of K
 //   fle_rowops.h         finalize_rows / finalize_lse (second pass of a row reduction + trailing ops),
@@ -27,7 +27,7 @@ static fle_status check_launch(const char *what) {
     return FLE_OK;
 }
 
-fle_status launch(const fle_problem *p, const Plan &plan) {
+fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp) {
     hipStream_t stream = reinterpret_cast<hipStream_t>(p->stream);
     const DevEpilogue &e = plan.epi;
     char *ws = reinterpret_cast<char *>(p->workspace);
@@ -76,6 +76,17 @@ fle_status launch(const fle_problem *p, const Plan &plan) {
         };
         void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
+    } else if (plan.variant == V_TILED && grp) {
+        const bool edge = plan.edge != 0;
+        GroupArgs ga{grp->row_offsets, grp->n_groups, grp->w_group_stride * int64_t(es), grp->b_group_stride * int64_t(es)};
+        auto pick = [&](auto dt_c) -> void (*)(GemmArgs, GroupArgs) {
+            constexpr int DT = decltype(dt_c)::value;
+            if (plan.bm == 256) return edge ? gemm_tiled_grouped_256<DT, true> : gemm_tiled_grouped_256<DT, false>;
+            return edge ? gemm_tiled_grouped_128<DT, true> : gemm_tiled_grouped_128<DT, false>;
+        };
+        void (*kern)(GemmArgs, GroupArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
+                                            : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g, ga);
     } else if (plan.variant == V_TILED) {
         // split K writes fp32 slabs with a padded leading dimension: vector stores whatever out looks like
         const bool edge = plan.edge && !split;

@@ -47,18 +47,20 @@ struct Plan {
     int32_t stage_rel;       // bf16 softmax staged in out as v - (maximum of v's partial)
     int32_t edge;            // tiled kernel: the epilogue must access b / residual / out one element at a time
     int32_t split_k;         // workgroups along K per tile (1: none); > 1 adds fp32 slabs and a reduction pass
+    int32_t groups;          // grouped problem: number of row groups (tiles_m is then an upper bound); 0 otherwise
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
     DevEpilogue epi;
 };
 
 // Validates p (everything except workspace size) and fills plan.  Host only, no HIP calls.
-fle_status make_plan(const fle_problem *p, int forced_variant, int forced_split, Plan *plan);
+// groups: nullptr for a plain problem, else the row groups of a grouped one.
+fle_status make_plan(const fle_problem *p, int forced_variant, int forced_split, Plan *plan, const fle_groups *groups = nullptr);
 
 // Records the calling thread's error detail; returns s.
 fle_status fail(fle_status s, const char *fmt, ...);
 
 // Implemented in the kernel translation unit: enqueue the planned kernels.
-fle_status launch(const fle_problem *p, const Plan &plan);
+fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *groups = nullptr);
 
 }  // namespace fle

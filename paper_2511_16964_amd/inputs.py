@@ -160,6 +160,89 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
     return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), ep)
 
 
+@dataclass
+class GroupedProblem:
+    """One grouped call: rows offsets[g] .. offsets[g+1]-1 of x belong to group g."""
+    dtype: torch.dtype
+    x: torch.Tensor                 # [M, K]
+    w: torch.Tensor                 # [G, N, K]
+    b: torch.Tensor | None          # [G, N]
+    offsets: list                   # G + 1 integers, 0 .. M
+    epilogue: list = field(default_factory=list)  # residual operands are [M, N]
+
+    @property
+    def M(self): return self.x.shape[0]
+
+    @property
+    def N(self): return self.w.shape[1]
+
+    @property
+    def K(self): return self.x.shape[1]
+
+    @property
+    def flops(self): return 2 * self.M * self.N * self.K
+
+
+def routed_counts(seed: int, M: int, G: int, skew: float = 1.0) -> list[int]:
+    """Rows per group for M rows routed to G groups: a multinomial draw whose probabilities come
+    from a Dirichlet(skew) draw, the load imbalance of a learned router (small skew: a few hot
+    groups and some empty ones; large skew: nearly even)."""
+    rng = np.random.default_rng(seed)
+    prob = rng.dirichlet(np.full(G, float(skew)))
+    return [int(c) for c in rng.multinomial(M, prob)]
+
+
+def offsets_of(counts) -> list[int]:
+    off = [0]
+    for c in counts:
+        off.append(off[-1] + int(c))
+    return off
+
+
+def random_grouped(seed: int, counts, N: int, K: int, dtype: torch.dtype, kinds: list[str],
+                   integer: bool = False, shared_bias: bool = False) -> GroupedProblem:
+    """A grouped problem with ``counts[g]`` rows in group g; same value recipes as
+    ``random_problem`` (draw order x, W, b, then the epilogue operands)."""
+    rng = np.random.default_rng(seed)
+    G, M = len(counts), int(sum(counts))
+    bshape = (N,) if shared_bias else (G, N)
+    if integer:
+        ri = lambda shape, a: rng.integers(-a, a + 1, size=shape).astype(np.float32)
+        x, w, b = ri((M, K), 2), ri((G, N, K), 2), ri(bshape, 8)
+    else:
+        x = _normal(rng, (M, K)); w = _uniform(rng, (G, N, K), 1 / math.sqrt(max(K, 1)))
+        b = _uniform(rng, bshape, 0.5)
+    ep = []
+    for kd in kinds:
+        if kd == "scale":
+            ep.append(("scale", 0.5 if integer else float(np.float32(rng.uniform(0.25, 2.0)))))
+        elif kd == "residual":
+            r = ri((M, N), 8) if integer else _normal(rng, (M, N))
+            ep.append(("residual", _store(r, dtype)))
+        elif kd == "layernorm":
+            g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
+            ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+        else:
+            ep.append((kd,))
+    return GroupedProblem(dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), offsets_of(counts), ep)
+
+
+# name -> (dtype, rows M, groups G, N, K, Dirichlet skew of the routing)
+GROUPED_SHAPES = {
+    "g1": (torch.bfloat16, 32768, 32, 4096, 4096, 1.0),   # a routed training / prefill batch: about 1024 rows per group
+    "g2": (torch.bfloat16, 512, 32, 4096, 4096, 1.0),     # a small decoding batch: about 16 rows per group, weight-bound
+}
+
+
+def make_grouped(name: str, seed: int = 0, M: int | None = None, G: int | None = None,
+                 N: int | None = None, K: int | None = None) -> GroupedProblem:
+    """Grouped benchmark configuration ``name``: Linear + bias + GELU-tanh per group, rows routed by
+    ``routed_counts``; M, G, N, K override the shape for reduced-size parity cases."""
+    dtype, M0, G0, N0, K0, skew = GROUPED_SHAPES[name]
+    M, G, N, K = M or M0, G or G0, N or N0, K or K0
+    return random_grouped(seed, routed_counts(seed + 1000, M, G, skew), N, K, dtype, ["bias", "gelu_tanh"])
+
+
 def to_f64(t):
     """Exact upcast of a stored tensor to a float64 numpy array (None passes through)."""
     return None if t is None else t.detach().cpu().to(torch.float64).numpy()

@@ -71,3 +71,29 @@ def sample_rows(M: int, count: int, tile: int = 256, seed: int = 7):
     while len(rows) < min(count, M):
         rows.add(int(rng.integers(0, M)))
     return sorted(rows)
+
+
+def run_grouped_gpu(gp: inputs.GroupedProblem, variant="auto", offsets=None, shared_out=None, dev="cuda:0"):
+    """Run a grouped problem through the C ABI.  ``offsets`` overrides the device array (the library
+    never sees the host list)."""
+    off = torch.tensor(gp.offsets if offsets is None else offsets, dtype=torch.int64, device=dev)
+    call = binding.Call(to_dev(gp.x, dev), to_dev(gp.w, dev), to_dev(gp.b, dev), dev_epilogue(gp.epilogue, dev),
+                        out=shared_out, variant=variant, offsets=off)
+    out = call.run()
+    torch.cuda.synchronize()
+    return out.cpu(), call
+
+
+def oracle_grouped(gp: inputs.GroupedProblem, rows=None) -> np.ndarray:
+    """Oracle result of a grouped problem: all rows, or only the listed rows (each row goes through its
+    own group's weights as a group of one row)."""
+    if rows is None:
+        return oracle.grouped_fused_linear_epilogue(inputs.to_f64(gp.x), inputs.to_f64(gp.w), inputs.to_f64(gp.b), gp.offsets,
+                                                    inputs.epilogue_f64(gp.epilogue))
+    owner = np.searchsorted(np.asarray(gp.offsets[1:]), np.asarray(rows), side="right")
+    outs = []
+    for m, g in zip(rows, owner):
+        b = None if gp.b is None else (gp.b[g] if gp.b.dim() == 2 else gp.b)
+        outs.append(oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(b),
+                                                 inputs.epilogue_f64(gp.epilogue, [m])))
+    return np.concatenate(outs, axis=0)

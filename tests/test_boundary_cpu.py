@@ -230,3 +230,82 @@ def test_split_k_planning(L):
         L.fle_force_split(0)
     text, _ = plan_of(problem(M=300, N=520, K=576))
     assert split(text) == 1, text
+
+
+# ---------------------------------------------------------------- grouped problems
+def groups(n=8, offs=9 * G, w_stride=None, b_stride=None, N=1024, K=512):
+    g = binding.FleGroups()
+    g.n_groups, g.row_offsets = n, offs
+    g.w_group_stride = N * K if w_stride is None else w_stride
+    g.b_group_stride = N if b_stride is None else b_stride
+    return g
+
+
+def test_grouped_validation_and_planning(L):
+    def plan_of(p, g):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size_grouped(ctypes.byref(p), ctypes.byref(g), ctypes.byref(need)) == OK, L.fle_last_error()
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return buf.value.decode(), need.value
+    tiles = lambda text: tuple(int(v) for v in re.search(r"tiles=(\d+)x(\d+)", text).groups())
+    p = problem(M=4096, N=1024, K=512, ops=[op("bias"), op("gelu_tanh")])
+    text, need = plan_of(problem(M=32768, N=1024, K=512, ops=[op("bias"), op("gelu_tanh")]), groups(8))
+    # 4096 rows per group and more tiles than the chip holds at once: the 256 tile; at most one partly filled tile row per group
+    assert "grouped_tiled_bf16_mfma tile=256x256" in text and tiles(text) == (32768 // 256 + 8, 4) and "split_k=1" in text and need == 0, text
+    text, _ = plan_of(p, groups(64))
+    assert "tile=128x128" in text and tiles(text) == (4096 // 128 + 64, 8), text       # 64 rows per group: the small tile
+    text, _ = plan_of(problem(M=40, N=1024, K=512), groups(64))
+    assert tiles(text)[0] == 40, text                                                     # never more tile rows than rows
+    # row ops work as in the plain form: partials per row, staged in out
+    text, need = plan_of(problem(M=4096, N=1024, K=512, ops=[op("bias"), op("layernorm", 1e-5, 7 * G, 8 * G)]), groups(8))
+    np_ = int(re.search(r"np=(\d+)", text).group(1))
+    assert "staging=out" in text and need == 4096 * np_ * 8, text
+    # ragged N or a bias stride that breaks 4-column groups: element-wise epilogue
+    text, _ = plan_of(problem(M=4096, N=1022, K=512), groups(8, N=1022))
+    assert "+edge" in text, text
+    text, _ = plan_of(p, groups(8, b_stride=1026))
+    assert "+edge" in text, text
+    text, _ = plan_of(p, groups(8, b_stride=0))
+    assert "+edge" not in text, text
+    # fp32 and fp16 operands
+    assert "grouped_tiled_f32_mfma" in plan_of(problem(M=4096, N=1024, K=512, dtype=binding.F32), groups(8))[0]
+    assert "grouped_tiled_f16_mfma" in plan_of(problem(M=4096, N=1024, K=512, dtype=binding.F16), groups(8))[0]
+    # forced tiles
+    for code, want in ((4, "tile=256x256"), (5, "tile=128x128")):
+        L.fle_force_variant(code)
+        try:
+            assert want in plan_of(p, groups(8))[0]
+        finally:
+            L.fle_force_variant(0)
+
+    bad = lambda p_, g_: L.fle_validate_grouped(ctypes.byref(p_), ctypes.byref(g_))
+    assert L.fle_validate_grouped(ctypes.byref(p), None) == E_NULL
+    assert bad(p, groups(0)) == E_SHAPE
+    assert bad(p, groups(1 << 20)) == E_SHAPE
+    assert bad(p, groups(8, offs=None)) == E_NULL
+    assert bad(p, groups(8, offs=9 * G + 4)) == E_ALIGN
+    assert bad(p, groups(8, w_stride=-1)) == E_SHAPE
+    assert bad(p, groups(8, w_stride=1024 * 512 + 4)) == E_UNSUP          # W_g would not be 16-byte aligned
+    assert bad(problem(M=4096, N=1024, K=500), groups(8, K=500)) == E_UNSUP   # no general-kernel path for groups
+    assert b"grouped" in L.fle_last_error()
+    assert bad(p, groups(8, offs=p.out + 64)) == E_UNSUP                  # out overlaps the offsets
+    g_big = groups(8, w_stride=G // 8)                                      # W_7 would reach into out
+    assert bad(p, g_big) == E_UNSUP
+    for code in (1, 3, 6, 7, 8):
+        L.fle_force_variant(code)
+        try:
+            assert bad(p, groups(8)) == E_UNSUP
+        finally:
+            L.fle_force_variant(0)
+    L.fle_force_split(2)
+    try:
+        assert bad(p, groups(8)) == E_UNSUP
+    finally:
+        L.fle_force_split(0)
+    # M == 0: nothing to do, no HIP call
+    p0 = problem(M=0, N=1024, K=512); p0.x = None; p0.out = None
+    assert L.fle_run_grouped(ctypes.byref(p0), ctypes.byref(groups(8, offs=None))) == OK
+    # a workspace that is needed but missing is reported before any launch
+    pl = problem(M=4096, N=1024, K=512, ops=[op("softmax")])
+    assert L.fle_run_grouped(ctypes.byref(pl), ctypes.byref(groups(8))) == E_WS

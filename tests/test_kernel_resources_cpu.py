@@ -37,14 +37,14 @@ def kernel_props(asm):
 def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
     props = kernel_props(asm)
     names = {k: v for k, v in props.items() if "gemm_bf16_skinny" in k or "gemm_tiled_" in k}
-    assert len(names) == 14 + 12, sorted(props)   # skinny: 7 shapes x 2 dtypes; tiled: 2 tiles x 3 dtypes x 2 epilogues
+    assert len(names) == 14 + 12 + 12, sorted(props)   # skinny: 7 shapes x 2 dtypes; tiled, and tiled grouped: 2 tiles x 3 dtypes x 2 epilogues
     for name, p in names.items():
         assert p["scratch"] == 0, "%s spills %d bytes of scratch" % (name, p["scratch"])
         assert p["lds"] <= 160 * 1024, name
         assert p["vgpr"] <= 512, name
-    for t128 in [v for k, v in names.items() if "tiled_128" in k]:
+    for t128 in [v for k, v in names.items() if "tiled_128" in k or "grouped_128" in k]:
         assert t128["lds"] <= 80 * 1024 and t128["vgpr"] <= 256  # two workgroups per CU
-    for t256 in [v for k, v in names.items() if "tiled_256" in k]:
+    for t256 in [v for k, v in names.items() if "tiled_256" in k or "grouped_256" in k]:
         assert t256["lds"] == 160 * 1024
 
 

@@ -276,3 +276,64 @@ def test_rejects_bad_arguments():
         run(x, w, None, [("logsumexp",), ("relu",)])      # logsumexp must be last
     with pytest.raises(TypeError):
         oracle.fused_linear_epilogue(x.astype(np.float32), w, None, [])
+
+
+# ---------------------------------------------------------------- grouped form
+def grouped(x, w, b, offsets, ep=()):
+    return oracle.grouped_fused_linear_epilogue(np.asarray(x, np.float64), np.asarray(w, np.float64),
+                                                None if b is None else np.asarray(b, np.float64), offsets, list(ep))
+
+
+def test_grouped_equals_one_hot_masked_sum():
+    """Independent formulation (numpy only): out[m] = sum_g [m in group g] (x[m] W_g^T + b_g)."""
+    counts = [3, 0, 5, 1, 0, 4]
+    G, N, K = len(counts), 7, 6
+    off = np.concatenate([[0], np.cumsum(counts)])
+    M = int(off[-1])
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((G, N, K)); b = RNG.standard_normal((G, N))
+    owner = np.repeat(np.arange(G), counts)
+    onehot = (owner[:, None] == np.arange(G)[None, :]).astype(np.float64)     # [M, G]
+    dense = np.einsum("mk,gnk->mgn", x, w) + b[None, :, :]                      # every row through every group
+    want = np.einsum("mg,mgn->mn", onehot, dense)
+    np.testing.assert_allclose(grouped(x, w, b, off, [("bias",)]), want, atol=1e-13)
+    # a group index shifted by one, a transposed W_g or a dropped bias would all differ
+    assert np.abs(want - (np.einsum("mg,mgn->mn", np.roll(onehot, 1, axis=1), dense))).max() > 0.1
+    # shared bias [N]
+    np.testing.assert_allclose(grouped(x, w, b[0], off, [("bias",)]), np.einsum("mg,mgn->mn", onehot, np.einsum("mk,gnk->mgn", x, w)) + b[0], atol=1e-13)
+
+
+def test_grouped_reductions_and_plain_form():
+    counts = [4, 2, 6]
+    off = [0, 4, 6, 12]
+    M, N, K = 12, 10, 5
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((3, N, K)); b = RNG.standard_normal((3, N))
+    r = RNG.standard_normal((M, N)); g = RNG.standard_normal(N); be = RNG.standard_normal(N)
+    ep = [("bias",), ("gelu_tanh",), ("residual", r), ("layernorm", g, be, 1e-5)]
+    got = grouped(x, w, b, off, ep)
+    # every row equals the plain operator applied to that row alone with its group's weights
+    for m in range(M):
+        gi = 0 if m < 4 else 1 if m < 6 else 2
+        one = run(x[m:m + 1], w[gi], b[gi], [("bias",), ("gelu_tanh",), ("residual", r[m:m + 1]), ("layernorm", g, be, 1e-5)])
+        assert np.array_equal(got[m], one[0])
+    # one group is the plain form; equal weights in every group are the plain form too
+    assert np.array_equal(grouped(x, w[:1], b[:1], [0, M], ep), run(x, w[0], b[0], ep))
+    same = np.stack([w[1]] * 3); sb = np.stack([b[1]] * 3)
+    assert np.array_equal(grouped(x, same, sb, off, ep), run(x, w[1], b[1], ep))
+    # logsumexp gives one value per row; empty groups change nothing
+    lse = grouped(x, w, b, off, [("bias",), ("logsumexp",)])
+    assert lse.shape == (M,)
+    np.testing.assert_allclose(lse[4:6], scipy.special.logsumexp(x[4:6] @ w[1].T + b[1], axis=1), atol=1e-12)
+    w5 = np.stack([w[0], w[2], w[1], w[0], w[2]]); b5 = np.stack([b[0], b[2], b[1], b[0], b[2]])
+    assert np.array_equal(grouped(x, w5, b5, [0, 4, 4, 6, 6, 12], ep), got)
+    # swapping two groups' row blocks together with their weights permutes the output blocks
+    perm = np.concatenate([np.arange(6, 12), np.arange(4, 6), np.arange(0, 4)])
+    sw = grouped(x[perm], w[[2, 1, 0]], b[[2, 1, 0]], [0, 6, 8, 12], [("bias",), ("gelu_tanh",), ("residual", r[perm]), ("layernorm", g, be, 1e-5)])
+    assert np.array_equal(sw, got[perm])
+
+
+def test_grouped_rejects_bad_offsets():
+    x = np.zeros((4, 3)); w = np.zeros((2, 5, 3))
+    for off in ([0, 2], [0, 3, 2], [1, 2, 4], [0, 2, 5], [0, 3, 2, 4]):
+        with pytest.raises(ValueError):
+            grouped(x, w, None, off)
+    assert grouped(x, w, None, [0, 0, 4]).shape == (4, 5)
