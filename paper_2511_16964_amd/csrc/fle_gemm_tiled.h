@@ -24,7 +24,8 @@ namespace fle {
 // row, 16 lanes cover a whole 64-column run, so bias / residual / output accesses are full
 // cache lines and a row reduction is a 16-lane DPP reduction.  The residual tile is copied
 // into LDS by the same direct loads, the first block before the main loop starts.
-template <int ROWS>
+// AUX: cache policy bits of the copy instructions (2 = non-temporal, for a panel that is read once).
+template <int ROWS, int AUX = 0>
 struct TileLoader {
     static constexpr int NI = ROWS / 32;  // copy instructions per wave per stage (8 rows each)
     __amdgpu_buffer_rsrc_t rsrc;
@@ -50,14 +51,14 @@ struct TileLoader {
     // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at byte column k0.
     __device__ __forceinline__ void issue_one(char *lds, uint32_t k0, int j) const {
         const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, AUX);
     }
     // Same for the last, partial K step: chunks at or beyond `valid` (= remaining row bytes / 16) get
     // an out-of-range offset, for which the buffer load delivers zeros.
     __device__ __forceinline__ void issue_one_tail(char *lds, uint32_t k0, int j, int valid) const {
         uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
         if ((chunk_even ^ (j & 1)) >= valid) voff = 0x80000000u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, AUX);
     }
     __device__ __forceinline__ void issue(char *lds, uint32_t k0, int valid) const {
 #pragma unroll
@@ -189,7 +190,9 @@ __device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs 
 
 // EDGE: N, the leading dimensions or the addresses of b / residual / out do not allow 4-column vector
 // accesses; the epilogue then touches memory one element at a time, masked per column.
-template <int BM, int BN, int DT, bool EDGE>
+// W_NT: the W panel is read by this workgroup only (grouped problems with about one tile row per group), so
+// its copies carry the non-temporal hint and do not displace other data from L2 and the Infinity Cache.
+template <int BM, int BN, int DT, bool EDGE, bool W_NT = false>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef &t) {
     constexpr bool F32 = DT == FLE_F32;
     constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
@@ -245,7 +248,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     if (res_idx >= 0 && wave_live) issue_residual(0, 0);
 
     TileLoader<BM> ldx_;
-    TileLoader<BN> ldw_;
+    TileLoader<BN, W_NT ? 2 : 0> ldw_;
     ldx_.init(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * ES, a.ldx * ES, M - m0, a.K * ES, wave, lane);
     ldw_.init(reinterpret_cast<const char *>(t.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
     constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
@@ -583,11 +586,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_grouped_256(const GemmArgs a, 
     if (!grouped_tile<256>(a, ga, t)) return;
     gemm_tiled_body<256, 256, DT, EDGE>(a, t);
 }
-template <int DT, bool EDGE>
+template <int DT, bool EDGE, bool W_NT>
 __global__ __launch_bounds__(256, 2) void gemm_tiled_grouped_128(const GemmArgs a, const GroupArgs ga) {
     TileRef t;
     if (!grouped_tile<128>(a, ga, t)) return;
-    gemm_tiled_body<128, 128, DT, EDGE>(a, t);
+    gemm_tiled_body<128, 128, DT, EDGE, W_NT>(a, t);
 }
 
 }  // namespace fle

@@ -41,6 +41,11 @@ static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
     return (static_cast<size_t>(rows - 1) * static_cast<size_t>(ld) + static_cast<size_t>(cols)) * es;
 }
 
+// Grouped problems with at most this many rows per group on average read nearly every W panel once: their W
+// copies carry the non-temporal hint (32 groups of 4096 x 4096, 512 rows in all: 187 -> 174 us back to back,
+// 249 -> 185 us from cold caches; at 128 rows per group the hint costs 3 % back to back, so the limit is 64).
+static const int64_t kGroupedStreamRows = 64;
+
 fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
@@ -255,6 +260,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     if (grp) {  // every group may end in a partly filled tile row; the kernel finds the actual count
         plan->tiles_m = M / plan->bm + G;
         if (plan->tiles_m > M) plan->tiles_m = M;
+        plan->w_stream = (plan->bm == 128 && M <= G * kGroupedStreamRows) ? 1 : 0;
     }
     plan->tiles_n = (N + plan->bn - 1) / plan->bn;
     if (plan->tiles_m * plan->tiles_n > (int64_t(1) << 31) - 1) return fail(FLE_ERR_SHAPE, "too many tiles for one launch");
@@ -321,9 +327,9 @@ using namespace fle;
 static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
     const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
-    snprintf(buf, n, "variant=%s_%s_mfma%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+    snprintf(buf, n, "variant=%s_%s_mfma%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
              plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : "general", dt,
-             plan.edge ? "+edge" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
+             plan.edge ? "+edge" : "", plan.w_stream ? "+wstream" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
 }
 

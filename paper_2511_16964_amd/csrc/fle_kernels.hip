@@ -82,7 +82,8 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs, GroupArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm == 256) return edge ? gemm_tiled_grouped_256<DT, true> : gemm_tiled_grouped_256<DT, false>;
-            return edge ? gemm_tiled_grouped_128<DT, true> : gemm_tiled_grouped_128<DT, false>;
+            if (plan.w_stream) return edge ? gemm_tiled_grouped_128<DT, true, true> : gemm_tiled_grouped_128<DT, false, true>;
+            return edge ? gemm_tiled_grouped_128<DT, true, false> : gemm_tiled_grouped_128<DT, false, false>;
         };
         void (*kern)(GemmArgs, GroupArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
                                             : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});

@@ -48,6 +48,7 @@ struct Plan {
     int32_t edge;            // tiled kernel: the epilogue must access b / residual / out one element at a time
     int32_t split_k;         // workgroups along K per tile (1: none); > 1 adds fp32 slabs and a reduction pass
     int32_t groups;          // grouped problem: number of row groups (tiles_m is then an upper bound); 0 otherwise
+    int32_t w_stream;        // grouped problem with about one tile row per group: W panels are read once (non-temporal copies)
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
     DevEpilogue epi;

@@ -255,6 +255,7 @@ def test_grouped_validation_and_planning(L):
     assert "grouped_tiled_bf16_mfma tile=256x256" in text and tiles(text) == (32768 // 256 + 8, 4) and "split_k=1" in text and need == 0, text
     text, _ = plan_of(p, groups(64))
     assert "tile=128x128" in text and tiles(text) == (4096 // 128 + 64, 8), text       # 64 rows per group: the small tile
+    assert "+wstream" in text and "+wstream" not in plan_of(problem(M=8192, N=1024, K=512), groups(64))[0]   # W panels read once: streamed
     text, _ = plan_of(problem(M=40, N=1024, K=512), groups(64))
     assert tiles(text)[0] == 40, text                                                     # never more tile rows than rows
     # row ops work as in the plain form: partials per row, staged in out
