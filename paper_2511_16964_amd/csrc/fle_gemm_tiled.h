@@ -178,6 +178,7 @@ __device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs 
             const int64_t g = c + src;
             t.m0 = gb + int64_t(uint32_t(tile_m) - first) * BM;
             t.m_end = ge;
+            if (t.m0 >= ge) return false;  // only if a malformed array made the 32-bit tile counts wrap
             t.n0 = int64_t(tile_n) * BM;
             t.w = reinterpret_cast<const char *>(a.w) + g * ga.w_stride_bytes;
             t.bias = a.epi.bias ? reinterpret_cast<const char *>(a.epi.bias) + g * ga.b_stride_bytes : nullptr;
