@@ -90,10 +90,15 @@ def oracle_grouped(gp: inputs.GroupedProblem, rows=None) -> np.ndarray:
     if rows is None:
         return oracle.grouped_fused_linear_epilogue(inputs.to_f64(gp.x), inputs.to_f64(gp.w), inputs.to_f64(gp.b), gp.offsets,
                                                     inputs.epilogue_f64(gp.epilogue))
+    rows = list(rows)
     owner = np.searchsorted(np.asarray(gp.offsets[1:]), np.asarray(rows), side="right")
-    outs = []
-    for m, g in zip(rows, owner):
+    out = [None] * len(rows)
+    for g in sorted(set(int(o) for o in owner)):      # one oracle call per group that owns sampled rows
+        idx = [i for i, o in enumerate(owner) if o == g]
+        sel = [rows[i] for i in idx]
         b = None if gp.b is None else (gp.b[g] if gp.b.dim() == 2 else gp.b)
-        outs.append(oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(b),
-                                                 inputs.epilogue_f64(gp.epilogue, [m])))
-    return np.concatenate(outs, axis=0)
+        res = oracle.fused_linear_epilogue(inputs.to_f64(gp.x[sel]), inputs.to_f64(gp.w[g]), inputs.to_f64(b),
+                                           inputs.epilogue_f64(gp.epilogue, sel))
+        for i, r in zip(idx, res):
+            out[i] = r
+    return np.stack(out, axis=0)

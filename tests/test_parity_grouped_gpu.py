@@ -158,3 +158,23 @@ def test_grouped_routed_batch_sampled_rows():
             rows.update((lo, hi - 1))
     rows = sorted(rows)
     assert_close(got[rows], oracle_grouped(gp, rows), BF16, call.plan())
+
+
+@pytest.mark.parametrize("name,tile", [("g1", "tile=256x256"), ("g2", "tile=128x128")])
+def test_grouped_benchmark_workloads_full_size_sampled_rows(name, tile):
+    """The grouped benchmark workloads at full size, in the launch configuration bench.py times:
+    sampled rows (every group's first and last row, tile boundaries, random rows) against the oracle,
+    and a poison check that every row of out was written."""
+    gp = inputs.make_grouped(name)
+    announce(name, gp.M, gp.N, gp.K, len(gp.offsets) - 1)
+    poison = torch.full((gp.M, gp.N), float("nan"), dtype=BF16, device="cuda:0")
+    got, call = run_grouped_gpu(gp, shared_out=poison)
+    assert tile in call.plan() and "grouped" in call.plan(), call.plan()
+    assert torch.isfinite(got.float()).all()
+    rows = set(sample_rows(gp.M, 24))
+    for lo, hi in zip(gp.offsets, gp.offsets[1:]):
+        if hi > lo:
+            rows.update((lo, hi - 1))
+    rows = sorted(rows)
+    err = assert_close(got[rows], oracle_grouped(gp, rows), BF16, call.plan())
+    print("%s max|err| %.3e over %d rows" % (name, err, len(rows)))
