@@ -173,7 +173,8 @@ fle_status fle_last_plan(char *buf, size_t n);
  * 0 = automatic, 1 = general kernel, 2 = tiled MFMA kernel (automatic tile), 3 = skinny kernel
  * (bf16 / fp16, M <= 256) with a K step of 64, 4 = tiled with the 256x256 tile, 5 = tiled with
  * the 128x128 tile, 6 / 7 = skinny kernel with a K step of 128 / 256, 8 = skinny kernel with one
- * row block of up to 256 rows whose 32-row sub-blocks take turns on a 256-wide K step.
+ * row block of up to 256 rows whose 32-row sub-blocks take turns on a 256-wide K step, 9 = thin kernel
+ * (M <= 32: 16-row W tiles streamed without LDS staging, every dtype).
  * A forced variant that cannot run the problem gives FLE_ERR_UNSUPPORTED from fle_run.  Grouped
  * problems accept 0, 2, 4 and 5. */
 void fle_force_variant(int variant);

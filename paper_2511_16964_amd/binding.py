@@ -17,7 +17,7 @@ F32, BF16, F16 = 0, 1, 2
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
             "layernorm": 6, "softmax": 7, "logsumexp": 8}
 MAX_OPS = 8
-VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8}
+VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
 EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
            "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
            "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped"]

@@ -44,6 +44,72 @@ __device__ __forceinline__ auto load_k4(const void *base, int64_t ld, int64_t ro
     }
 }
 
+// Finishes one 16 x 16 sub-tile held in the 16x16 MFMA result layout (a lane owns row m and columns
+// nb + 4 q4 .. + 3 of the 16-column segment that starts at nb): the elementwise ops, the segment's
+// row-reduction partial, the store.  Shared by the general and the thin kernel.
+__device__ __forceinline__ void finish_tile16(const GemmArgs &a, f32x4 v, f32x4 bias_v, int64_t m, int64_t nb, int q4, int dtype) {
+    const int64_t M = a.M, N = a.N;
+    const int64_t n = nb + 4 * q4;
+    for (int o = 0; o < a.epi.n_pre; ++o) {
+        const DevOp op = a.epi.pre[o];
+        if (op.kind == FLE_BIAS) {
+            v += bias_v;
+            continue;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (m < M && n + e < N) v[e] = apply_op(op, v[e], m, n + e, a.epi.bias, dtype);
+    }
+    if (a.epi.row_kind >= 0) {
+        const int64_t left = N - nb;
+        const float cnt = float(left < 16 ? (left > 0 ? left : 0) : 16);
+        float s0, s1;
+        if (a.epi.row_kind == FLE_LAYERNORM) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (n + e < N) sum += v[e];
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            const float mean = cnt > 0.0f ? sum / cnt : 0.0f;
+            float m2 = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (n + e < N) m2 += (v[e] - mean) * (v[e] - mean);
+            m2 += __shfl_xor(m2, 16);
+            m2 += __shfl_xor(m2, 32);
+            s0 = mean;
+            s1 = m2;
+        } else {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (n + e < N) mx = fmaxf(mx, v[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            float se = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (n + e < N) se += __expf(v[e] - mx);
+            se += __shfl_xor(se, 16);
+            se += __shfl_xor(se, 32);
+            s0 = mx;
+            s1 = se;
+        }
+        if (q4 == 0 && m < M && left > 0) {
+            float *dstp = a.partials + (m * a.np + nb / 16) * 2;
+            dstp[0] = s0;
+            dstp[1] = s1;
+        }
+        if (a.dst_rel) v -= s0;
+    }
+    if (a.dst && m < M) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (n + e < N) st_elem(a.dst, m * a.ldd + n + e, a.dst_f32 ? FLE_F32 : dtype, v[e]);
+    }
+}
+
 // T: 16 x 16 sub-tiles per side of the block tile (2: 32 x 32 outputs; 1: 16 x 16, for problems so small
 // that 32 x 32 tiles would leave most CUs without a workgroup).
 template <int DT, bool VEC, int T>
@@ -125,64 +191,7 @@ __global__ __launch_bounds__(256) void gemm_general(const GemmArgs a) {
 #pragma unroll
     for (int ww = 1; ww < 4; ++ww) v += *reinterpret_cast<const f32x4 *>(&red[ww][wave][lane][0]);
 
-    for (int o = 0; o < a.epi.n_pre; ++o) {
-        const DevOp op = a.epi.pre[o];
-        if (op.kind == FLE_BIAS) {
-            v += bias_v;
-            continue;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (m < M && n + e < N) v[e] = apply_op(op, v[e], m, n + e, a.epi.bias, dtype);
-    }
-    if (a.epi.row_kind >= 0) {
-        const int64_t left = N - nb;
-        const float cnt = float(left < 16 ? (left > 0 ? left : 0) : 16);
-        float s0, s1;
-        if (a.epi.row_kind == FLE_LAYERNORM) {
-            float sum = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n + e < N) sum += v[e];
-            sum += __shfl_xor(sum, 16);
-            sum += __shfl_xor(sum, 32);
-            const float mean = cnt > 0.0f ? sum / cnt : 0.0f;
-            float m2 = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n + e < N) m2 += (v[e] - mean) * (v[e] - mean);
-            m2 += __shfl_xor(m2, 16);
-            m2 += __shfl_xor(m2, 32);
-            s0 = mean;
-            s1 = m2;
-        } else {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n + e < N) mx = fmaxf(mx, v[e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float se = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n + e < N) se += __expf(v[e] - mx);
-            se += __shfl_xor(se, 16);
-            se += __shfl_xor(se, 32);
-            s0 = mx;
-            s1 = se;
-        }
-        if (q4 == 0 && m < M && left > 0) {
-            float *dstp = a.partials + (m * a.np + nb / 16) * 2;
-            dstp[0] = s0;
-            dstp[1] = s1;
-        }
-        if (a.dst_rel) v -= s0;
-    }
-    if (a.dst && m < M) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (n + e < N) st_elem(a.dst, m * a.ldd + n + e, a.dst_f32 ? FLE_F32 : dtype, v[e]);
-    }
+    finish_tile16(a, v, bias_v, m, nb, q4, dtype);
 }
 
 }  // namespace fle

@@ -170,6 +170,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         variant = V_SKINNY;
     }
     const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 256 && K % 64 == 0;
+    const bool thin_ok = tiled_ok && M >= 1 && M <= 32;  // element-wise epilogue: nothing else needs alignment
 
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
     // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
@@ -207,12 +208,23 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         // W is worth streaming: always for a small M; up to 128 rows when W (256 MB or more) cannot stay in the
         // Infinity Cache anyway (measured: 128 x 32768 x 8192 124 us against 156 us tiled; at 134 MB the tiled
         // kernel wins warm and cold; 8 sub-blocks are slower than the tiled kernel everywhere)
-        if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) || (M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
+        // A few rows against a whole weight matrix (a perceptron layer at batch 1 .. 32): the thin kernels, where
+        // they measured faster than what follows.  Dot-product form: fp32 up to 8 rows from 512 x 1024 weights on
+        // (4096^2 at one row: 16 us against 33 us general; 1024 x 32768: 46 against 110); 2-byte dtypes up to 4
+        // rows while the skinny kernel would need a split of K and a second launch (4096^2: 8.5-9.6 us against
+        // 12.5), i.e. up to 2^24 weights, with rows of 2048 or more beyond 2^22.  MFMA form: 2-byte dtypes, 5 .. 32 rows,
+        // 2^20 .. 2^23 weights (2048^2 at 16 rows: 7.9 us against 10.4).
+        const int64_t nk = N * K;
+        const bool gemv_auto = thin_ok && M <= (f32 ? 8 : 4) && nk >= (int64_t(1) << 19) &&
+                               (f32 || (nk <= (int64_t(1) << 24) && (nk <= (int64_t(1) << 22) || K >= 2048)));
+        const bool thin_auto = thin_ok && !f32 && M > 4 && nk >= (int64_t(1) << 20) && nk <= (int64_t(1) << 23);
+        if ((gemv_auto || thin_auto) && forced_split <= 1) variant = V_THIN;
+        else if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) || (M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
         else {
             // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on
             // fp32 operands, 70 on bf16) or, for few workgroups and a long K, the serial chain of one
             // workgroup (1.25 us per 256 of K; up to 4 workgroups per CU are resident).
-            const int64_t gt = ((M + 31) / 32) * ((N + 31) / 32) < 128 ? 16 : 32;
+            const int64_t gt = (M <= 16 || ((M + 31) / 32) * ((N + 31) / 32) < 128) ? 16 : 32;
             const int64_t gw = ((M + gt - 1) / gt) * ((N + gt - 1) / gt);
             const double chain = double((gw + 1023) / 1024) * double((K + 255) / 256) * 1.25;
             const double rate = 2.0 * double(M) * double(N) * double(K) / (f32 ? 55.0e6 : 70.0e6);
@@ -223,7 +235,9 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs 2-byte operands, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");
-    if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
+    if (variant == V_THIN && !thin_ok) return fail(FLE_ERR_UNSUPPORTED, "the thin kernel needs M <= 32 and everything the tiled kernel needs of x and W");
+    if (variant == V_THIN && forced_split > 1) return fail(FLE_ERR_UNSUPPORTED, "the thin kernel does not split K");
+    if (variant != V_TILED && variant != V_GENERAL && variant != V_SKINNY && variant != V_THIN) return fail(FLE_ERR_OP, "unknown forced variant %d", variant);
     plan->variant = variant;
     plan->edge = 0;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
@@ -243,6 +257,13 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->bn = 128;
         plan->bk = bk;
         plan->part_cols = 32;  // one partial per wave tile
+    } else if (variant == V_THIN) {
+        // few rows: dot products on row-contiguous loads (the vector ALU keeps up with HBM to 4 rows of a 2-byte
+        // dtype, 8 of fp32); else the 16x16 MFMA
+        plan->bm = M <= (f32 ? 8 : 4) ? 8 : M <= 16 ? 16 : 32;
+        plan->bn = 16;
+        plan->bk = int32_t(64 / es);  // one step: 64 bytes of every row
+        plan->part_cols = 16;
     } else if (variant == V_TILED) {
         plan->bm = plan->bn = best_tile;
         plan->bk = f32 ? 32 : 64;
@@ -252,7 +273,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     } else {
         // 32 x 32 tiles; 16 x 16 when those would give fewer than 128 workgroups (tiny, latency-bound problems)
         const int64_t t32 = ((M + 31) / 32) * ((N + 31) / 32);
-        plan->bm = plan->bn = t32 < 128 ? 16 : 32;
+        plan->bm = plan->bn = (M <= 16 || t32 < 128) ? 16 : 32;  // (up to 16 rows a 32-row tile would be half empty)
         plan->bk = 16;
         plan->part_cols = 16;
     }
@@ -269,7 +290,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // a tile, each over its own K range, writing fp32 slabs that a reduction pass sums in slab order
     // (deterministic).
     plan->split_k = 1;
-    if (variant != V_GENERAL && M > 0) {
+    if (variant != V_GENERAL && variant != V_THIN && M > 0) {
         const int64_t steps = variant == V_TILED ? tiled_steps : K / plan->bk;
         int64_t s = 1;
         if (forced_split > 0) s = forced_split;
@@ -328,7 +349,7 @@ static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
     const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
     snprintf(buf, n, "variant=%s_%s_mfma%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
-             plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : "general", dt,
+             plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : plan.variant == V_THIN ? "thin" : "general", dt,
              plan.edge ? "+edge" : "", plan.w_stream ? "+wstream" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
 }

@@ -2,6 +2,8 @@
 //
 //   fle_gemm_tiled.h     gemm_tiled_256 / _128 (+ _grouped_): LDS-tiled MFMA GEMM (bf16, fp16, fp32) with the epilogue fused
 //   fle_gemm_skinny.h    gemm_bf16_skinny: HBM-bound GEMM for M <= 64 per row block (2-byte operands)
+//   fle_gemm_thin.h      gemm_gemv (M <= 4 / 8, row-contiguous loads and dot products), gemm_thin (M <= 32, 16-row W tiles on
+//                        the 16x16 MFMA): streams over W without LDS staging, every dtype
 //   fle_gemm_general.h   gemm_general: any shape / alignment / dtype, small tiles, in-block split of K
 //   fle_rowops.h         finalize_rows / finalize_lse (second pass of a row reduction + trailing ops),
 //                        reduce_slabs (ordered sum of split-K slabs + the ops before the row op)
@@ -15,6 +17,7 @@
 #include "fle_device_common.h"
 #include "fle_gemm_general.h"
 #include "fle_gemm_skinny.h"
+#include "fle_gemm_thin.h"
 #include "fle_gemm_tiled.h"
 #include "fle_rowops.h"
 
@@ -76,6 +79,19 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         };
         void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
+    } else if (plan.variant == V_THIN) {
+        auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
+            constexpr int DT = decltype(dt_c)::value;
+            if (plan.bm <= 8) {  // (the planner gives 5 .. 8 rows to this form for fp32 only)
+                if constexpr (DT == FLE_F32)
+                    if (p->M > 4) return gemm_gemv<DT, 8>;
+                return p->M <= 1 ? gemm_gemv<DT, 1> : p->M <= 2 ? gemm_gemv<DT, 2> : gemm_gemv<DT, 4>;
+            }
+            return plan.bm == 16 ? gemm_thin<DT, 1> : gemm_thin<DT, 2>;
+        };
+        void (*kern)(GemmArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
+                                 : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
+        hipLaunchKernelGGL(kern, dim3(uint32_t(plan.tiles_n)), dim3(256), 0, stream, g);
     } else if (plan.variant == V_TILED && grp) {
         const bool edge = plan.edge != 0;
         GroupArgs ga{grp->row_offsets, grp->n_groups, grp->w_group_stride * int64_t(es), grp->b_group_stride * int64_t(es)};

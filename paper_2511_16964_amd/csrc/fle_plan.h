@@ -29,7 +29,7 @@ struct DevEpilogue {
     DevOp post[FLE_MAX_OPS];
 };
 
-enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5, V_SKINNY_128 = 6, V_SKINNY_256 = 7, V_SKINNY_SEQ = 8 };
+enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5, V_SKINNY_128 = 6, V_SKINNY_256 = 7, V_SKINNY_SEQ = 8, V_THIN = 9 };
 
 // Where the GEMM pass writes its (pre-row-op) values.
 enum Staging {

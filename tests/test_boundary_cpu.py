@@ -193,6 +193,46 @@ def test_variant_selection(L):
         L.fle_force_variant(0)
 
 
+def test_thin_kernel_selection(L):
+    def plan_of(p):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        text = buf.value.decode()
+        assert need.value == 0 or "thin" not in text   # the thin kernels never need a workspace without a row op
+        return text
+    F32, BF16, F16 = binding.F32, binding.BF16, binding.F16
+    # a perceptron layer at batch 1: the dot-product form (8-row plan), one launch, no split of K
+    for dt in (F32, BF16, F16):
+        text = plan_of(problem(M=1, N=4096, K=4096, dtype=dt))
+        assert "thin_" in text and "tile=8x16" in text and "split_k=1" in text, text
+    assert "thin_f32_mfma tile=8x16" in plan_of(problem(M=8, N=1024, K=32768, dtype=F32))     # fp32: up to 8 rows, any size
+    assert "thin_f32_mfma tile=8x16" in plan_of(problem(M=1, N=32768, K=8192, dtype=F32))
+    assert "thin" not in plan_of(problem(M=9, N=4096, K=4096, dtype=F32))                      # more rows in fp32: general / tiled
+    assert "thin" not in plan_of(problem(M=1, N=256, K=256, dtype=F32))                        # tiny: the general kernel
+    assert "thin_bf16_mfma tile=8x16" in plan_of(problem(M=4, N=2048, K=2048))
+    assert "skinny" in plan_of(problem(M=1, N=32768, K=8192))                                  # large weights in 2 bytes: the skinny kernel streams as well
+    assert "skinny" in plan_of(problem(M=4, N=32768, K=1024))                                  # short rows
+    # 5 .. 32 rows of a 2-byte dtype on mid-sized weights: the MFMA form, 16- or 32-row plan
+    assert "thin_bf16_mfma tile=16x16x32" in plan_of(problem(M=16, N=2048, K=2048))
+    assert "thin_f16_mfma tile=32x16x32" in plan_of(problem(M=32, N=1024, K=2048, dtype=F16))
+    assert "skinny" in plan_of(problem(M=16, N=4096, K=4096))
+    assert "thin" not in plan_of(problem(M=33, N=2048, K=2048))
+    # x or W rows that are not whole 16-byte chunks: not eligible
+    assert "general" in plan_of(problem(M=1, N=4096, K=4092, dtype=BF16))
+    L.fle_force_variant(9)
+    try:
+        assert validate(L, problem(M=32, N=64, K=64)) == OK
+        assert validate(L, problem(M=33, N=64, K=64)) == E_UNSUP
+        assert validate(L, problem(M=4, N=64, K=62)) == E_UNSUP
+        L.fle_force_split(2)
+        assert validate(L, problem(M=4, N=64, K=64)) == E_UNSUP
+    finally:
+        L.fle_force_variant(0)
+        L.fle_force_split(0)
+
+
 def test_split_k_planning(L):
     def plan_of(p):
         need = ctypes.c_size_t(0)

@@ -48,6 +48,14 @@ def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
         assert t256["lds"] == 160 * 1024
 
 
+def test_thin_kernels_do_not_spill(asm):
+    props = kernel_props(asm)
+    thin = {k: v for k, v in props.items() if "gemm_thin" in k or "gemm_gemv" in k}
+    assert len(thin) == 6 + 10, sorted(thin)   # MFMA form: 3 dtypes x 2 row counts; dot-product form: 1, 2, 4 rows x 3 dtypes and 8 rows in fp32
+    for name, p in thin.items():
+        assert p["scratch"] == 0 and p["vgpr"] <= 256, (name, p)   # at least two waves per SIMD
+
+
 def test_streaming_finalize_keeps_its_occupancy(asm):
     """The LayerNorm finalize pass is a bandwidth-bound streaming kernel: it needs many waves per SIMD, so
     its register count must stay low (a shared code path once pushed it to 149 and cost 40 % of its speed)."""

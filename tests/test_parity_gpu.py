@@ -36,6 +36,7 @@ def test_c1_fp32_bias_gelu_erf_full():
     ("auto_skinny_seq", 64, 8192, 512), ("auto_skinny_seq", 33, 8196, 512), ("auto_skinny_seq", 50, 16384, 256),
     ("skinnyseq", 100, 388, 512), ("skinnyseq", 200, 260, 512), ("skinnyseq", 256, 132, 256), ("skinnyseq", 33, 132, 512), ("skinnyseq", 129, 2052, 256),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
+    ("thin", 1, 16, 8), ("thin", 1, 1000, 512), ("thin", 16, 132, 264), ("thin", 17, 260, 576), ("thin", 32, 45, 520), ("thin", 5, 2052, 72), ("thin", 9, 31, 328),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
     """Small-integer operands: every product and partial sum is exact in fp32 and the chain
@@ -192,6 +193,8 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("tiled", F16, 200, 392, 128), ("tiled256", F16, 150, 262, 136), ("skinny", F16, 32, 2304, 256), ("general", F16, 70, 97, 83),
     ("auto", BF16, 48, 8192, 512), ("auto", F16, 64, 8192, 512),   # skinny kernel, one row block of 64 in two halves
     ("skinnyseq", BF16, 100, 2304, 512), ("skinnyseq", F16, 250, 520, 256),   # four and eight sub-blocks in turn
+    ("thin", BF16, 1, 2052, 1024), ("thin", BF16, 16, 263, 2056), ("thin", BF16, 29, 97, 520), ("thin", F16, 7, 392, 776),
+    ("thin", F32, 1, 1000, 1028), ("thin", F32, 16, 261, 516), ("thin", F32, 32, 130, 2052),
 ]
 
 
@@ -203,6 +206,21 @@ def test_chains_small_shapes(shape, kinds):
     announce("chain", variant, dtype, M, N, K, kinds)
     got, call = run_gpu(prob, variant)
     assert_close(got, oracle_rows(prob), dtype, "%s %s" % (kinds, call.plan()))
+
+
+@pytest.mark.parametrize("dtype,M,N,K,tile", [
+    (F32, 1, 4096, 4096, "tile=8x16"), (BF16, 1, 4096, 4096, "tile=8x16"), (F16, 3, 2048, 2048, "tile=8x16"), (F32, 8, 1000, 3000, "tile=8x16"),
+    (F32, 2, 32768, 1024, "tile=8x16"), (BF16, 4, 1024, 16384, "tile=8x16"), (BF16, 16, 2048, 2048, "tile=16x16"), (F16, 29, 1024, 4096, "tile=32x16"),
+])
+@pytest.mark.parametrize("kinds", [["bias", "relu"], ["bias", "gelu_erf", "layernorm"], ["scale", "softmax"], ["bias", "logsumexp"]], ids=lambda k: "+".join(k))
+def test_perceptron_layers_take_the_thin_kernels(dtype, M, N, K, tile, kinds):
+    """A few rows against a whole weight matrix (the automatic plan): the thin kernels, one launch plus
+    the finalize pass of a row op, whole result against the oracle."""
+    prob = inputs.random_problem(31, M, N, K, dtype, kinds)
+    announce("thin auto", dtype, M, N, K, kinds)
+    got, call = run_gpu(prob)
+    assert "thin_" in call.plan() and tile in call.plan() and "split_k=1 " in call.plan(), call.plan()
+    assert_close(got, oracle_rows(prob), dtype, call.plan())
 
 
 def test_both_gelu_variants_are_distinguished_in_fp32():
