@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused linear + epilogue hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|g1|g2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|g1|g2|m1]
 
 A step is one pass of the whole path (every kernel the call enqueues) over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s
@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -165,12 +165,34 @@ def cpu_baseline_grouped(gp, inputs, budget_s=12.0):
             "sample": "first %d rows of each of %d groups (%d of %d rows), all %d columns, %.1f s" % (per, G, n, gp.M, gp.N, t)}
 
 
+def cpu_baseline_chain(ch, inputs, budget_s=12.0):
+    """The oracle on the whole perceptron chain (every layer, the full batch), repeated to fill the budget."""
+    import oracle
+    import numpy as np
+    ws, bs = [inputs.to_f64(w) for w in ch.ws], [inputs.to_f64(b) for b in ch.bs]
+    x0 = inputs.to_f64(ch.x)
+    def once():
+        h = x0
+        for w, b in zip(ws, bs):
+            h = oracle.fused_linear_epilogue(h, w, b, [("bias",), ("relu",)])
+        return h
+    t0 = time.perf_counter(); once(); t1 = time.perf_counter() - t0
+    reps = int(max(1, min(1000, budget_s / max(t1, 1e-6))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        once()
+    t = time.perf_counter() - t0
+    flops = sum(2.0 * ch.x.shape[0] * w.shape[0] * w.shape[1] for w in ch.ws)
+    return {"value": flops * reps / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "the whole chain (%d layers, batch %d), %d passes, %.1f s" % (len(ch.ws), ch.x.shape[0], reps, t)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -221,6 +243,24 @@ def main():
         # the same loop over groups with one plain fused call per group
         loop_out = torch.empty(gp.M, gp.N, dtype=xg.dtype, device=dev)
         loop_calls = [binding.Call(xg[lo:hi], wg[g], bg[g], ep, out=loop_out[lo:hi]) for g, lo, hi in spans]
+    elif args.workload == "m1":
+        # a perceptron at batch 1 (the regime of the paper's MLP tasks): 8 dependent fused calls, fp32
+        ch = inputs.make_chain()
+        xg = to(ch.x)
+        wsg, bsg = [to(w) for w in ch.ws], [to(b) for b in ch.bs]
+        calls, cur = [], xg
+        for w, b in zip(wsg, bsg):
+            calls.append(binding.Call(cur, w, b, [("bias",), ("relu",)]))
+            cur = calls[-1].out
+        probs = [ch.layer(0, ch.x)]
+        flops = sum(2 * ch.x.shape[0] * w.shape[0] * w.shape[1] for w in ch.ws)
+        desc = "m1: perceptron, %d layers of linear+bias+relu, fp32, batch %d, width %d" % (len(ch.ws), ch.x.shape[0], ch.x.shape[1])
+        def eager():
+            h = xg
+            for w, b in zip(wsg, bsg):
+                h = F.relu(F.linear(h, w, b))
+            return h
+        alg_bytes = sum(4 * (w.numel() + b.numel()) for w, b in zip(ch.ws, ch.bs)) + 4 * 2 * len(ch.ws) * ch.x.numel()
     elif args.workload == "c5":
         blk = inputs.make_mlp()
         p1 = blk.call1()
@@ -295,7 +335,7 @@ def main():
         "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
                           "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
-    hbm_bound = args.workload in ("c4", "g2")
+    hbm_bound = args.workload in ("c4", "g2", "m1")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES[args.workload]}
@@ -319,7 +359,12 @@ def main():
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs) if grouped else cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
+        if grouped:
+            out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs)
+        elif args.workload == "m1":
+            out["cpu_baseline"] = cpu_baseline_chain(ch, inputs)
+        else:
+            out["cpu_baseline"] = cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
     if args.calibrate_copy:
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).fill_(3)
         dst = torch.empty_like(src)

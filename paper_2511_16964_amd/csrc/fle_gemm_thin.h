@@ -119,9 +119,9 @@ __global__ __launch_bounds__(256) void gemm_thin(const GemmArgs a) {
 // instruction of a wave covers 1024 contiguous bytes of one row (lane l takes bytes 16 l ..), and the lane
 // multiplies its 16 bytes with the same 16 bytes of each x row (converted to fp32, then plain FMAs: 8 + 8 M
 // vector instructions per 16 bytes of a 2-byte dtype, which keeps up with HBM to M = 4; fp32 operands need
-// 4 M and go to M = 8), accumulating per (W row, x row) in fp32.  A wave owns 4 W rows and all of K and keeps D blocks of
+// 4 M and go to M = 8), accumulating per (W row, x row) in fp32.  A wave owns R (4, 2 or 1) W rows and all of K and keeps D blocks of
 // 1 KB per row in flight in registers (two register batches, one multiplied while the next arrives); the x
-// block of a lane is loaded once per K block and reused by the 4 rows.  At the end each (W row, x row) sum
+// block of a lane is loaded once per K block and reused by the wave's rows.  At the end each (W row, x row) sum
 // is reduced over the 64 lanes by a butterfly (fixed order), the 16 x MR results of the workgroup meet in
 // LDS, and wave 0 finishes them as one 16 x 16 tile like the general kernel.
 // 16 bytes of a row as fp32 values (8 of a 2-byte dtype, else 4).
@@ -150,13 +150,15 @@ __device__ __forceinline__ Unpacked<DT> unpack16(u32x4 r) {
 }
 
 // MR: x rows held per lane (M <= MR).
-template <int DT, int MR>
-__global__ __launch_bounds__(256) void gemm_gemv(const GemmArgs a) {
+// R: W rows per wave; the workgroup always owns 16 rows, so it has 16 / R waves.  R = 4 and 4 waves is the
+// default; R = 1 and 16 waves (used for a single x row) keeps more loads in flight per CU.
+template <int DT, int MR, int R>
+__global__ __launch_bounds__(1024 / R) void gemm_gemv(const GemmArgs a) {
     constexpr int ES = DT == FLE_F32 ? 4 : 2;
-    constexpr int R = 4;                 // W rows per wave
+    constexpr int NW = 16 / R;           // waves per workgroup
     constexpr int D = 2;                 // K blocks (1 KB of every row) per register batch (deeper batches gain nothing and cost occupancy)
     __shared__ float red[16][16];        // [W row of the workgroup][x row]
-    __shared__ float part[4][R * MR][65];  // per wave: [value][lane] (+1: the readers of different values hit different banks)
+    __shared__ float part[NW][R * MR][65];  // per wave: [value][lane] (+1: the readers of different values hit different banks)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r16 = lane & 15, q4 = lane >> 4;

@@ -212,11 +212,12 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         // they measured faster than what follows.  Dot-product form: fp32 up to 8 rows from 512 x 1024 weights on
         // (4096^2 at one row: 16 us against 33 us general; 1024 x 32768: 46 against 110); 2-byte dtypes up to 4
         // rows while the skinny kernel would need a split of K and a second launch (4096^2: 8.5-9.6 us against
-        // 12.5), i.e. up to 2^24 weights, with rows of 2048 or more beyond 2^22.  MFMA form: 2-byte dtypes, 5 .. 32 rows,
+        // 12.5), i.e. up to 2^24 weights (any size for a single row: 32768 x 8192 85 us against 91), with rows of
+        // 2048 or more beyond 2^22.  MFMA form: 2-byte dtypes, 5 .. 32 rows,
         // 2^20 .. 2^23 weights (2048^2 at 16 rows: 7.9 us against 10.4).
         const int64_t nk = N * K;
         const bool gemv_auto = thin_ok && M <= (f32 ? 8 : 4) && nk >= (int64_t(1) << 19) &&
-                               (f32 || (nk <= (int64_t(1) << 24) && (nk <= (int64_t(1) << 22) || K >= 2048)));
+                               (f32 || ((M == 1 || nk <= (int64_t(1) << 24)) && (nk <= (int64_t(1) << 22) || K >= 2048)));
         const bool thin_auto = thin_ok && !f32 && M > 4 && nk >= (int64_t(1) << 20) && nk <= (int64_t(1) << 23);
         if ((gemv_auto || thin_auto) && forced_split <= 1) variant = V_THIN;
         else if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) || (M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
@@ -262,7 +263,13 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         // dtype, 8 of fp32); else the 16x16 MFMA
         plan->bm = M <= (f32 ? 8 : 4) ? 8 : M <= 16 ? 16 : 32;
         plan->bn = 16;
-        plan->bk = int32_t(64 / es);  // one step: 64 bytes of every row
+        plan->bk = int32_t(64 / es);  // MFMA form: one step is 64 bytes of every row
+        if (plan->bm == 8) {
+            // dot-product form: the field holds the W rows per wave instead.  One row of x against many long rows
+            // of W: one W row per wave and 16 waves per workgroup keep more loads in flight (fp32 8192^2: 53 ->
+            // 47 us; bf16 32768 x 8192: 91 -> 85 us); with more x rows or few W rows 4 per wave are faster.
+            plan->bk = (M == 1 && N >= 4096 && K >= 2048) ? 1 : 4;
+        }
         plan->part_cols = 16;
     } else if (variant == V_TILED) {
         plan->bm = plan->bn = best_tile;
@@ -348,8 +355,9 @@ using namespace fle;
 static void format_plan(const Plan &plan, char *buf, size_t n) {
     const bool f32 = plan.epi.dtype == FLE_F32;
     const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
-    snprintf(buf, n, "variant=%s_%s_mfma%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+    snprintf(buf, n, "variant=%s_%s_%s%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
              plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : plan.variant == V_THIN ? "thin" : "general", dt,
+             plan.variant == V_THIN && plan.bm == 8 ? "dot" : "mfma",
              plan.edge ? "+edge" : "", plan.w_stream ? "+wstream" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
              plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
 }

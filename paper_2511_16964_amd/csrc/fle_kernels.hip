@@ -80,18 +80,22 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else if (plan.variant == V_THIN) {
+        // dot-product form: 4 rows of W per wave, or (one row of x, many rows of W) one per wave and 16 waves
+        const bool wide = plan.bm <= 8 && plan.bk == 1;  // (the plan's K step field carries the rows per wave for this form)
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm <= 8) {  // (the planner gives 5 .. 8 rows to this form for fp32 only)
                 if constexpr (DT == FLE_F32)
-                    if (p->M > 4) return gemm_gemv<DT, 8>;
-                return p->M <= 1 ? gemm_gemv<DT, 1> : p->M <= 2 ? gemm_gemv<DT, 2> : gemm_gemv<DT, 4>;
+                    if (p->M > 4) return gemm_gemv<DT, 8, 4>;
+                if (wide) return gemm_gemv<DT, 1, 1>;
+                return p->M <= 1 ? gemm_gemv<DT, 1, 4> : p->M <= 2 ? gemm_gemv<DT, 2, 4> : gemm_gemv<DT, 4, 4>;
             }
             return plan.bm == 16 ? gemm_thin<DT, 1> : gemm_thin<DT, 2>;
         };
         void (*kern)(GemmArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
                                  : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
-        hipLaunchKernelGGL(kern, dim3(uint32_t(plan.tiles_n)), dim3(256), 0, stream, g);
+        const uint32_t threads = wide ? 1024u : 256u;
+        hipLaunchKernelGGL(kern, dim3(uint32_t(plan.tiles_n)), dim3(threads), 0, stream, g);
     } else if (plan.variant == V_TILED && grp) {
         const bool edge = plan.edge != 0;
         GroupArgs ga{grp->row_offsets, grp->n_groups, grp->w_group_stride * int64_t(es), grp->b_group_stride * int64_t(es)};

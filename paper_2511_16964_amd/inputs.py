@@ -243,6 +243,30 @@ def make_grouped(name: str, seed: int = 0, M: int | None = None, G: int | None =
     return random_grouped(seed, routed_counts(seed + 1000, M, G, skew), N, K, dtype, ["bias", "gelu_tanh"])
 
 
+@dataclass
+class MlpChain:
+    """A multi-layer perceptron at a tiny batch: layer i is h_i = relu(h_{i-1} W_i^T + b_i), h_0 = x."""
+    x: torch.Tensor        # [B, width]
+    ws: list               # L tensors [width, width]
+    bs: list               # L tensors [width]
+
+    def layer(self, i: int, h: torch.Tensor) -> Problem:
+        return Problem("m1.%d" % i, h.dtype, h, self.ws[i], self.bs[i], [("bias",), ("relu",)])
+
+
+def make_chain(seed: int = 0, batch: int = 1, width: int = 4096, layers: int = 8,
+               dtype: torch.dtype = torch.float32) -> MlpChain:
+    """Workload m1: x ~ N(0,1); W_i ~ U(+-sqrt(6/width)) (keeps the activations' scale through the
+    ReLUs), b_i ~ U(+-0.1); draw order x, then W_i, b_i layer by layer."""
+    rng = np.random.default_rng(seed)
+    x = _normal(rng, (batch, width))
+    ws, bs = [], []
+    for _ in range(layers):
+        ws.append(_store(_uniform(rng, (width, width), math.sqrt(6.0 / width)), dtype))
+        bs.append(_store(_uniform(rng, (width,), 0.1), dtype))
+    return MlpChain(_store(x, dtype), ws, bs)
+
+
 def to_f64(t):
     """Exact upcast of a stored tensor to a float64 numpy array (None passes through)."""
     return None if t is None else t.detach().cpu().to(torch.float64).numpy()

@@ -207,12 +207,14 @@ def test_thin_kernel_selection(L):
     for dt in (F32, BF16, F16):
         text = plan_of(problem(M=1, N=4096, K=4096, dtype=dt))
         assert "thin_" in text and "tile=8x16" in text and "split_k=1" in text, text
-    assert "thin_f32_mfma tile=8x16" in plan_of(problem(M=8, N=1024, K=32768, dtype=F32))     # fp32: up to 8 rows, any size
-    assert "thin_f32_mfma tile=8x16" in plan_of(problem(M=1, N=32768, K=8192, dtype=F32))
+    assert "thin_f32_dot tile=8x16" in plan_of(problem(M=8, N=1024, K=32768, dtype=F32))     # fp32: up to 8 rows, any size
+    assert "thin_f32_dot tile=8x16" in plan_of(problem(M=1, N=32768, K=8192, dtype=F32))
     assert "thin" not in plan_of(problem(M=9, N=4096, K=4096, dtype=F32))                      # more rows in fp32: general / tiled
     assert "thin" not in plan_of(problem(M=1, N=256, K=256, dtype=F32))                        # tiny: the general kernel
-    assert "thin_bf16_mfma tile=8x16" in plan_of(problem(M=4, N=2048, K=2048))
-    assert "skinny" in plan_of(problem(M=1, N=32768, K=8192))                                  # large weights in 2 bytes: the skinny kernel streams as well
+    assert "thin_bf16_dot tile=8x16" in plan_of(problem(M=4, N=2048, K=2048))
+    assert "thin_bf16_dot tile=8x16x1 " in plan_of(problem(M=1, N=32768, K=8192))              # one row, many long rows of W: one W row per wave
+    assert "thin_bf16_dot tile=8x16x4 " in plan_of(problem(M=1, N=2048, K=2048))
+    assert "skinny" in plan_of(problem(M=2, N=32768, K=8192))                                  # more rows on large weights in 2 bytes: the skinny kernel
     assert "skinny" in plan_of(problem(M=4, N=32768, K=1024))                                  # short rows
     # 5 .. 32 rows of a 2-byte dtype on mid-sized weights: the MFMA form, 16- or 32-row plan
     assert "thin_bf16_mfma tile=16x16x32" in plan_of(problem(M=16, N=2048, K=2048))
@@ -350,3 +352,32 @@ def test_grouped_validation_and_planning(L):
     # a workspace that is needed but missing is reported before any launch
     pl = problem(M=4096, N=1024, K=512, ops=[op("softmax")])
     assert L.fle_run_grouped(ctypes.byref(pl), ctypes.byref(groups(8))) == E_WS
+
+
+def test_every_variant_plans_every_kind_of_epilogue(L):
+    """Planning is pure host arithmetic: every kernel variant must produce a complete plan (partials per
+    row, staging, workspace) for every kind of epilogue, for each dtype it supports."""
+    chains = [[], [op("bias")], [op("softmax")], [op("scale", 2.0), op("logsumexp")],
+              [op("bias"), op("residual", p0=6 * G, ld=2048), op("layernorm", 1e-5, 7 * G, 8 * G)]]
+    shapes = {"general": (70, 2048, 83), "tiled": (200, 2048, 128), "tiled256": (300, 2048, 256), "tiled128": (64, 2048, 64),
+              "skinny": (32, 2048, 256), "skinny128": (40, 2048, 640), "skinny256": (32, 2048, 1024), "skinnyseq": (100, 2048, 512),
+              "thin": (1, 2048, 1024), "auto": (1, 2048, 2048)}
+    buf = ctypes.create_string_buffer(256)
+    for name, (M, N, K) in shapes.items():
+        for dt in (binding.F32, binding.BF16, binding.F16):
+            if name.startswith("skinny") and dt == binding.F32:
+                continue
+            for rows in ((M,) if name != "thin" else (1, 3, 8, 16, 32)):
+                for ch in chains:
+                    p = problem(M=rows, N=N, K=K, dtype=dt, ops=ch)
+                    need = ctypes.c_size_t(0)
+                    L.fle_force_variant(binding.VARIANTS[name])
+                    try:
+                        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK, (name, dt, rows, L.fle_last_error())
+                    finally:
+                        L.fle_force_variant(0)
+                    L.fle_last_plan(buf, 256)
+                    text = buf.value.decode()
+                    np_ = int(re.search(r"np=(\d+)", text).group(1))
+                    has_row = any(o[0] >= 6 for o in ch)
+                    assert (np_ > 0) == has_row and (need.value >= rows * np_ * 8) and ("row_op=-1" in text) == (not has_row), text

@@ -91,3 +91,23 @@ def test_c5b_per_call_on_oracle_rounded_h():
     got, call = run_gpu(p2)
     sub = list(range(0, 512, 8))
     assert_close(got[sub], oracle_rows(p2, sub), BF16, "c5b " + call.plan())
+
+
+def test_m1_perceptron_chain_every_layer():
+    """The batch-1 perceptron of bench.py's workload m1: every layer's GPU output against the oracle applied
+    to the same input (the GPU's own previous activation), and the chain end to end against the oracle's
+    float64 chain."""
+    ch = inputs.make_chain()
+    announce("m1", len(ch.ws), ch.x.shape)
+    F32 = torch.float32
+    h_gpu, h_ref = ch.x, inputs.to_f64(ch.x)
+    import oracle
+    for i in range(len(ch.ws)):
+        prob = ch.layer(i, h_gpu)
+        out, call = run_gpu(prob)
+        assert "thin_f32" in call.plan() and "tile=8x16" in call.plan(), call.plan()
+        assert_close(out, oracle_rows(prob), F32, "m1 layer %d" % i)
+        h_ref = oracle.fused_linear_epilogue(h_ref, inputs.to_f64(ch.ws[i]), inputs.to_f64(ch.bs[i]), [("bias",), ("relu",)])
+        h_gpu = out
+    err = assert_close(h_gpu, h_ref, F32, "m1 end to end")
+    print("m1 end-to-end max|err| %.3e" % err)

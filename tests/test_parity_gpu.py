@@ -210,7 +210,7 @@ def test_chains_small_shapes(shape, kinds):
 
 @pytest.mark.parametrize("dtype,M,N,K,tile", [
     (F32, 1, 4096, 4096, "tile=8x16"), (BF16, 1, 4096, 4096, "tile=8x16"), (F16, 3, 2048, 2048, "tile=8x16"), (F32, 8, 1000, 3000, "tile=8x16"),
-    (F32, 2, 32768, 1024, "tile=8x16"), (BF16, 4, 1024, 16384, "tile=8x16"), (BF16, 16, 2048, 2048, "tile=16x16"), (F16, 29, 1024, 4096, "tile=32x16"),
+    (F32, 2, 32768, 1024, "tile=8x16"), (BF16, 4, 1024, 16384, "tile=8x16"), (BF16, 1, 8192, 2048, "tile=8x16x1 "), (F32, 1, 4100, 2052, "tile=8x16x1 "), (BF16, 16, 2048, 2048, "tile=16x16"), (F16, 29, 1024, 4096, "tile=32x16"),
 ])
 @pytest.mark.parametrize("kinds", [["bias", "relu"], ["bias", "gelu_erf", "layernorm"], ["scale", "softmax"], ["bias", "logsumexp"]], ids=lambda k: "+".join(k))
 def test_perceptron_layers_take_the_thin_kernels(dtype, M, N, K, tile, kinds):
