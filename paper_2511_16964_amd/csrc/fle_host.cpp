@@ -464,6 +464,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 300; }  // 0.3.0: grouped problems
+int fle_version(void) { return 400; }  // 0.4.0: thin kernels (0.3.0: grouped problems)
 
 }  // extern "C"
