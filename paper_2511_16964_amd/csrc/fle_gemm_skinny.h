@@ -1,10 +1,10 @@
-// The HBM-bound skinny GEMM (M <= 64 per row block, 2-byte operands).
+// The HBM-bound skinny GEMM (row blocks of 32 rows; 2-byte operands also 64 .. 256).
 #pragma once
 #include "fle_device_common.h"
 
 namespace fle {
 
-// ------------------------------------------------------------------ skinny GEMM (bf16 / fp16, row blocks of up to 64 rows)
+// ------------------------------------------------------------------ skinny GEMM (row blocks of 32; bf16 / fp16 up to 256 rows)
 // HBM-bound: W streams through once and the matrix pipe is nearly idle, so the design goal is
 // bytes in flight.  One workgroup owns 128 rows of W (columns of out) and all of K; each of its
 // 4 waves copies and consumes its own 32 W rows, the small x tile is shared.  The LDS ring is
@@ -12,7 +12,9 @@ namespace fle {
 // the contiguous run per W row (2 BK bytes) matters more than the ring depth, and the W loads
 // carry the non-temporal hint (W is read once and must not displace anything in L2 or the
 // Infinity Cache).  Same swizzle and orientation as the tiled kernel; the wave tile is
-// 32 TMB x 32, so the epilogue stays in the MFMA register layout.
+// 32 TMB x 32, so the epilogue stays in the MFMA register layout.  BK is the K step in elements; a
+// staged row is BK x (2 or 4) bytes.  fp32 operands run four v_mfma_f32_32x32x2_f32 per 16-byte chunk
+// pair, which keeps the matrix pipe about as busy as the memory system, so they take row blocks of 32 only.
 //
 // SEQ (TMB = 2, 4 or 8 row blocks of 32, K step 256): a stage of W with all its x blocks does not fit
 // LDS twice, so the blocks take turns on the same W stage, each through one of two 16 KB x buffers:
@@ -24,13 +26,15 @@ namespace fle {
 // every block); all four multiply.
 template <int TMB, int BK, int DT, bool SEQ = false>
 __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
-    static_assert(!SEQ || ((TMB == 2 || TMB == 4 || TMB == 8) && BK == 256), "the sequential variant is 2, 4 or 8 row blocks on a 256-wide K step");
-    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte operands only");
-    using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
+    constexpr bool F32 = DT == FLE_F32;
+    constexpr int ES = F32 ? 4 : 2;            // bytes per operand element
+    static_assert(!SEQ || ((TMB == 2 || TMB == 4 || TMB == 8) && BK == 256 && !F32), "the sequential variant is 2, 4 or 8 row blocks on a 256-wide K step of a 2-byte dtype");
+    static_assert(!F32 || TMB == 1, "fp32 operands: row blocks of 32 only (the matrix pipe is as busy as the memory system already)");
+    using frag_t = typename std::conditional<F32, f32x4, typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type>::type;
     constexpr int BM = 32 * TMB, BN = 128;
-    constexpr int RB = BK * 2;                 // bytes per staged row
-    constexpr int CPR = BK / 8, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
-    constexpr int KPS = BK / 16;               // 16-wide k slices per stage
+    constexpr int RB = BK * ES;                // bytes per staged row
+    constexpr int CPR = RB / 16, RPI = 64 / CPR;  // 16-byte chunks per row, rows per copy instruction
+    constexpr int KPS = RB / 32;               // k slices (two 16-byte chunks of every row) per stage
     constexpr int SW = BN * RB, SX = BM * RB, STAGE = SW + SX;
     constexpr int NST = SEQ ? 2 : (160 * 1024) / STAGE < 8 ? (160 * 1024) / STAGE : 8;
     constexpr int NIW = 32 / RPI, NIX = (8 * TMB) / RPI, LPS = NIW + NIX;  // copy instructions per wave per stage
@@ -54,17 +58,17 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
 
     // Chunk c of a row is stored at position c ^ sw(row): every 16-lane group of a fragment read
     // (16 consecutive rows, one logical chunk) then covers 16 different 16-byte bank groups.
-    auto sw = [](int row) { return BK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); };
+    auto sw = [](int row) { return CPR == 8 ? ((row & 7) ^ ((row >> 3) & 1)) : (row & 15); };
     const int lr = lane / CPR, lp = lane % CPR;
     __amdgpu_buffer_rsrc_t rw, rx;
     {
         const int64_t wrows = (N - n0) < BN ? (N - n0) : BN, xrows = (M - m0) < BM ? (M - m0) : BM;
-        rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * 2), 0,
-                                               uint32_t(((wrows - 1) * a.ldw + a.K) * 2), 0x00020000);
-        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * 2), 0,
-                                               uint32_t(((xrows - 1) * a.ldx + a.K) * 2), 0x00020000);
+        rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w) + n0 * a.ldw * ES), 0,
+                                               uint32_t(((wrows - 1) * a.ldw + a.K) * ES), 0x00020000);
+        rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.x) + m0 * a.ldx * ES), 0,
+                                               uint32_t(((xrows - 1) * a.ldx + a.K) * ES), 0x00020000);
     }
-    const uint32_t ldwb = uint32_t(a.ldw) * 2, ldxb = uint32_t(a.ldx) * 2;
+    const uint32_t ldwb = uint32_t(a.ldw) * ES, ldxb = uint32_t(a.ldx) * ES;
     auto issue = [&](int kt) {
         char *base = smem + (kt % NST) * STAGE;
         const uint32_t kb = uint32_t(kt) * RB;
@@ -96,7 +100,12 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
 #pragma unroll
             for (int t = 0; t < TMB; ++t) {
                 const frag_t fx = *reinterpret_cast<const frag_t *>(sX + t * 32 * RB + off);
-                if constexpr (DT == FLE_F16) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[t], 0, 0, 0);
+                if constexpr (F32) {
+                    // four 32x32x2 steps: step e pairs element e of the two 16-byte chunks of every row (the same k
+                    // permutation for both operands)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[e], fx[e], acc[t], 0, 0, 0);
+                } else if constexpr (DT == FLE_F16) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[t], 0, 0, 0);
                 else acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[t], 0, 0, 0);
             }
         }
@@ -135,7 +144,8 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 const int off = (((2 * kk + fh) ^ fs) & (CPR - 1)) * 16;
                 const frag_t fw = *reinterpret_cast<const frag_t *>(sW + off);
                 const frag_t fx = *reinterpret_cast<const frag_t *>(sX + off);
-                if constexpr (DT == FLE_F16) acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[BLK], 0, 0, 0);
+                if constexpr (F32) {  // (never instantiated: the sequential variant is for 2-byte dtypes)
+                } else if constexpr (DT == FLE_F16) acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw, fx, acc[BLK], 0, 0, 0);
                 else acc[BLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, fx, acc[BLK], 0, 0, 0);
             }
         };
@@ -303,10 +313,12 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 const int64_t n = n_lane + 8 * q;
                 if (m < M && n < N) {
                     const f32x4 v = f32x4{acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
-                    if (a.dst_f32)
+                    if (F32 || a.dst_f32) {
                         *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n) = v;
-                    else
-                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n) = pack4<DT>(v);
+                    } else {
+                        constexpr int DT2 = F32 ? FLE_BF16 : DT;  // (this branch is never taken for fp32 problems)
+                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n) = pack4<DT2>(v);
+                    }
                 }
             }
         }

@@ -169,7 +169,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         forced_seq = variant == V_SKINNY_SEQ;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && vec_epi && !f32 && M <= 256 && K % 64 == 0;
+    const bool skinny_ok = tiled_ok && vec_epi && M <= 256 && K % (f32 ? 32 : 64) == 0;  // a K step is at least 128 bytes of every row
     const bool thin_ok = tiled_ok && M >= 1 && M <= 32;  // element-wise epilogue: nothing else needs alignment
 
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
@@ -220,7 +220,9 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
                                (f32 || ((M == 1 || nk <= (int64_t(1) << 24)) && (nk <= (int64_t(1) << 22) || K >= 2048)));
         const bool thin_auto = thin_ok && !f32 && M > 4 && nk >= (int64_t(1) << 20) && nk <= (int64_t(1) << 23);
         if ((gemv_auto || thin_auto) && forced_split <= 1) variant = V_THIN;
-        else if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << 22)) || (M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
+        // (fp32 operands keep the matrix pipe about as busy as the memory system: worth it from 2^24 weights on,
+        // 2^25 up to 16 rows where the general kernel's 16 x 16 tiles are as fast; 8192^2 at 16 rows 83 -> 60 us)
+        else if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << (f32 ? (M <= 16 ? 25 : 24) : 22))) || (!f32 && M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
         else {
             // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on
             // fp32 operands, 70 on bf16) or, for few workgroups and a long K, the serial chain of one
@@ -234,7 +236,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
             variant = (tiled_ok && M > 0 && (best < general || forced_split > 1)) ? V_TILED : V_GENERAL;
         }
     }
-    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs 2-byte operands, M <= 256, K %% 64 == 0 and everything the tiled kernel needs");
+    if (variant == V_SKINNY && !skinny_ok) return fail(FLE_ERR_UNSUPPORTED, "the skinny kernel needs M <= 256, K a multiple of 128 bytes and everything the tiled kernel needs");
     if (variant == V_TILED && !tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "the tiled MFMA kernel needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 bytes)");
     if (variant == V_THIN && !thin_ok) return fail(FLE_ERR_UNSUPPORTED, "the thin kernel needs M <= 32 and everything the tiled kernel needs of x and W");
     if (variant == V_THIN && forced_split > 1) return fail(FLE_ERR_UNSUPPORTED, "the thin kernel does not split K");
@@ -245,18 +247,20 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     if (variant == V_SKINNY) {
         // The widest K step that fits two stages wins on the box: 512-byte runs per W row stream at
         // 6.0 TB/s where 128- and 256-byte runs reach 4.5 TB/s.  forced 64 keeps the narrow ring for comparison.
-        int bk = forced_bk ? forced_bk : 256;
+        int bk = forced_bk ? forced_bk : 256;  // in 2-byte elements; fp32 operands take half as many for the same bytes
         if (forced == V_SKINNY) bk = 64;
-        while (bk > 64 && K % bk != 0) bk /= 2;
+        const int per = f32 ? 2 : 1;
+        while (bk > 64 && K % (bk / per) != 0) bk /= 2;
         // Row blocks of 32.  More than 32 rows: one block of 64, 128 or 256 rows whose 32-row sub-blocks take
         // turns on a 256-wide W stage (automatic choice; with fewer than 64 W tiles the chip is not full and
         // more, smaller workgroups do better), or, on request, 64 rows at once on a 128-wide K step; a forced
         // 256-wide K step keeps blocks of 32 (one workgroup each) for comparison.
         plan->bm = 32;
-        if (M > 32 && forced_bk == 128 && bk == 128) plan->bm = 64;
+        if (f32) { /* row blocks of 32 only */ }
+        else if (M > 32 && forced_bk == 128 && bk == 128) plan->bm = 64;
         else if (M > 32 && bk == 256 && (forced_seq || (forced == V_AUTO && N >= 8192))) plan->bm = M <= 64 ? 64 : M <= 128 ? 128 : 256;
         plan->bn = 128;
-        plan->bk = bk;
+        plan->bk = bk / per;
         plan->part_cols = 32;  // one partial per wave tile
     } else if (variant == V_THIN) {
         // few rows: dot products on row-contiguous loads (the vector ALU keeps up with HBM to 4 rows of a 2-byte

@@ -1,7 +1,8 @@
 // Device side of libfle: hand-written gfx950 (CDNA4) kernels and their launcher.
 //
 //   fle_gemm_tiled.h     gemm_tiled_256 / _128 (+ _grouped_): LDS-tiled MFMA GEMM (bf16, fp16, fp32) with the epilogue fused
-//   fle_gemm_skinny.h    gemm_bf16_skinny: HBM-bound GEMM for M <= 64 per row block (2-byte operands)
+//   fle_gemm_skinny.h    gemm_bf16_skinny: HBM-bound GEMM for few rows, W staged through LDS in long contiguous runs
+//                        (row blocks of 32; bf16 / fp16 also 64 .. 256)
 //   fle_gemm_thin.h      gemm_gemv (M <= 4 / 8, row-contiguous loads and dot products), gemm_thin (M <= 32, 16-row W tiles on
 //                        the 16x16 MFMA): streams over W without LDS staging, every dtype
 //   fle_gemm_general.h   gemm_general: any shape / alignment / dtype, small tiles, in-block split of K
@@ -77,7 +78,11 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
             if (plan.bk == 128) return gemm_bf16_skinny<2, 128, DT>;
             return plan.bm == 64 ? gemm_bf16_skinny<2, 256, DT, true> : plan.bm == 128 ? gemm_bf16_skinny<4, 256, DT, true> : gemm_bf16_skinny<8, 256, DT, true>;
         };
-        void (*kern)(GemmArgs) = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
+        void (*kern)(GemmArgs);
+        if (p->dtype == FLE_F32)  // row blocks of 32 only; the K step is half as many elements for the same bytes
+            kern = plan.bk == 128 ? gemm_bf16_skinny<1, 128, FLE_F32> : plan.bk == 64 ? gemm_bf16_skinny<1, 64, FLE_F32> : gemm_bf16_skinny<1, 32, FLE_F32>;
+        else
+            kern = p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else if (plan.variant == V_THIN) {
         // dot-product form: 4 rows of W per wave, or (one row of x, many rows of W) one per wave and 16 waves

@@ -235,6 +235,28 @@ def test_thin_kernel_selection(L):
         L.fle_force_split(0)
 
 
+def test_fp32_skinny_selection(L):
+    def plan_of(p):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return buf.value.decode()
+    F32 = binding.F32
+    assert "skinny_f32_mfma tile=32x128x128" in plan_of(problem(M=16, N=8192, K=8192, dtype=F32))   # 512 bytes of a row per K step
+    assert "skinny_f32_mfma tile=32x128x128" in plan_of(problem(M=48, N=4096, K=4096, dtype=F32))   # two row blocks of 32
+    assert "skinny_f32_mfma tile=32x128x64" in plan_of(problem(M=32, N=8192, K=8256, dtype=F32))    # K not a multiple of 128 elements
+    assert "skinny" not in plan_of(problem(M=16, N=4096, K=4096, dtype=F32))                          # the general kernel is as fast there
+    assert "skinny" not in plan_of(problem(M=65, N=8192, K=8192, dtype=F32))
+    assert "thin_f32_dot" in plan_of(problem(M=8, N=8192, K=8192, dtype=F32))                        # up to 8 rows: dot products
+    L.fle_force_variant(7)
+    try:
+        assert "skinny_f32_mfma tile=32x128x128" in plan_of(problem(M=100, N=260, K=128, dtype=F32))
+        assert validate(L, problem(M=32, N=256, K=48, dtype=F32)) == E_UNSUP                          # a K step is at least 128 bytes
+    finally:
+        L.fle_force_variant(0)
+
+
 def test_split_k_planning(L):
     def plan_of(p):
         need = ctypes.c_size_t(0)

@@ -36,14 +36,18 @@ def test_c1_fp32_bias_gelu_erf_full():
     ("auto_skinny_seq", 64, 8192, 512), ("auto_skinny_seq", 33, 8196, 512), ("auto_skinny_seq", 50, 16384, 256),
     ("skinnyseq", 100, 388, 512), ("skinnyseq", 200, 260, 512), ("skinnyseq", 256, 132, 256), ("skinnyseq", 33, 132, 512), ("skinnyseq", 129, 2052, 256),
     ("general", 77, 45, 50), ("general", 33, 64, 64), ("general", 1, 1, 1),
+    ("skinny_f32", 32, 256, 32), ("skinny_f32", 19, 388, 160), ("skinny128_f32", 7, 2052, 64), ("skinny256_f32", 32, 132, 384), ("skinny256_f32", 100, 260, 128),
     ("thin", 1, 16, 8), ("thin", 1, 1000, 512), ("thin", 16, 132, 264), ("thin", 17, 260, 576), ("thin", 32, 45, 520), ("thin", 5, 2052, 72), ("thin", 9, 31, 328),
 ])
 def test_integer_inputs_are_bit_exact(variant, M, N, K):
     """Small-integer operands: every product and partial sum is exact in fp32 and the chain
     bias/relu/scale(0.5)/residual stays exactly representable in bf16, so any difference at
     all is an indexing error (tile mapping, MFMA operand layout, LDS swizzle, masking)."""
-    prob = inputs.random_problem(11, M, N, K, BF16, ["bias", "relu", "scale", "residual"], integer=True)
-    announce("integer exact", variant, M, N, K)
+    dtype = BF16
+    if variant.endswith("_f32"):   # the skinny kernel on fp32 operands
+        variant, dtype = variant[:-4], F32
+    prob = inputs.random_problem(11, M, N, K, dtype, ["bias", "relu", "scale", "residual"], integer=True)
+    announce("integer exact", variant, dtype, M, N, K)
     seq = variant == "auto_skinny_seq"   # automatic plan: row block of 64 whose halves take turns on a 256-wide W stage
     got, call = run_gpu(prob, "auto" if seq else variant)
     if seq:
@@ -151,7 +155,7 @@ def test_split_k_integer_inputs_are_bit_exact(variant, split, M, N, K):
     assert np.array_equal(got.to(torch.float64).numpy(), ref), call.plan()
 
 
-SPLIT_SHAPES = [("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024),
+SPLIT_SHAPES = [("skinny256", 3, 32, 2304, 1024, F32), ("tiled128", 2, 200, 392, 256), ("tiled256", 3, 150, 520, 320), ("skinny", 2, 32, 2304, 256), ("skinny128", 4, 50, 260, 1024),
                 ("tiled128", 3, 200, 392, 160, F32), ("tiled128", 2, 200, 392, 256, F16), ("skinny", 2, 32, 2304, 256, F16)]
 
 
@@ -193,6 +197,7 @@ SHAPES = [  # (variant, dtype, M, N, K): several tiles, ragged tails, both kerne
     ("tiled", F16, 200, 392, 128), ("tiled256", F16, 150, 262, 136), ("skinny", F16, 32, 2304, 256), ("general", F16, 70, 97, 83),
     ("auto", BF16, 48, 8192, 512), ("auto", F16, 64, 8192, 512),   # skinny kernel, one row block of 64 in two halves
     ("skinnyseq", BF16, 100, 2304, 512), ("skinnyseq", F16, 250, 520, 256),   # four and eight sub-blocks in turn
+    ("skinny", F32, 32, 2304, 128), ("skinny256", F32, 17, 392, 640), ("skinny128", F32, 50, 260, 192),
     ("thin", BF16, 1, 2052, 1024), ("thin", BF16, 16, 263, 2056), ("thin", BF16, 29, 97, 520), ("thin", F16, 7, 392, 776),
     ("thin", F32, 1, 1000, 1028), ("thin", F32, 16, 261, 516), ("thin", F32, 32, 130, 2052),
 ]
