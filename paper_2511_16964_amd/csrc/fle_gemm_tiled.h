@@ -275,65 +275,107 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     frag_t fw[2][TN], fx[2][TM];
     const int KT = int((a.K * ES + 127) / 128);
     const int tail_valid = int((a.K * ES - int64_t(KT - 1) * 128) / 16);  // 16-byte chunks of the last K step (8 = full)
-    // One K step on stage kt & 1; ISSUE: also copy K step kt+1 into the other stage (masked to the
-    // valid chunks when that is the partial last step).
-    auto k_step = [&](int kt, auto issue_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
-        const int valid = kt + 2 == KT ? tail_valid : 8;
-        const char *sW = smem + (kt & 1) * STAGE, *sX = sW + SW;
-        char *iW = smem + ((kt + 1) & 1) * STAGE, *iX = iW + SW;
-        const uint32_t ik0 = uint32_t(kt + 1) * 128;  // byte column of the K step being copied
-        wait_vmcnt<0>();                  // this wave's copies into the current stage have landed
-        __builtin_amdgcn_s_barrier();     // everyone's have, and everyone is done reading the other stage
+    // One 16-wide k slice KK of the stage at (sW, sX): NMF MFMAs on the fragments in buffer KK & 1.  In the
+    // issue slots between them go, one at a time, (READ) the fragment reads of the slice that is multiplied
+    // next, slice (KK + 1) & 3 of the stage at (rW, rX), into the other buffer, and (HALF = 1 or 2) the first
+    // or second half of the copy instructions of one K step into the stage at (iW, iX) (masked to the valid
+    // chunks when that is the partial last step).
+    auto slice = [&](auto kk_c, auto read_c, auto half_c, const char *sW, const char *sX, const char *rW, const char *rX,
+                     char *iW, char *iX, uint32_t ik0, int valid) {
+        constexpr int KK = decltype(kk_c)::value, HALF = decltype(half_c)::value;
+        constexpr bool READ = decltype(read_c)::value;
+        constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
+        constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
+        constexpr int cur = KK & 1;
+        (void)sW; (void)sX;
+#pragma unroll
+        for (int q = 0; q < NMF; ++q) {
+            if (READ && q % QD == 0) {
+                const int g = q / QD;
+                if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(rW + (wn * WN + g * 32) * 128 + rd_off[(KK + 1) & 3]);
+                else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(rX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(KK + 1) & 3]);
+            }
+            if (HALF != 0 && q % QV == (QV > 1 ? 1 : 0)) {
+                const int idx = (HALF - 1) * NVM + q / QV;
+                if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (F32) {
+                // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
+                // same K permutation for both operands
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
+            } else if constexpr (DT == FLE_F16) {
+                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+            } else {
+                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
+    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y).
+    //
+    // The loop is rotated by one slice against the K steps.  The wait for the next stage and the workgroup
+    // barrier sit between slices 2 and 3 of a step, not at its end: by then every fragment of the current
+    // stage is in registers (so the stage may be overwritten) and the copies of the next stage have had two
+    // slices to land.  Slice 3 then runs on registers alone and covers the first fragment reads of the next
+    // stage and the first half of the copies of the step after it; the other half goes out during slice 0.
+    // No MFMA ever waits right behind the barrier for an LDS read.
+    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
+    auto valid_of = [&](int step) { return step + 1 == KT ? tail_valid : 8; };
+    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
+    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    {
+        const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
 #pragma unroll
         for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
 #pragma unroll
         for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        if (kb + 1 < ke) {  // first half of the copies of the second step (later steps: during slice 3 of the step before)
+            char *iW = smem + ((kb + 1) & 1) * STAGE, *iX = iW + SW;
+            constexpr int NVM = (NIW + NIX) / 2;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            // 16-wide k slice kk: NMF MFMAs; in the issue slot before MFMA q goes at most one
-            // fragment read of slice kk+1 and (first two slices only) one copy instruction.
-            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
-            constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
-            const int cur = kk & 1;
-#pragma unroll
-            for (int q = 0; q < NMF; ++q) {
-                if (kk + 1 < 4 && q % QD == 0) {
-                    const int g = q / QD;
-                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + g * 32) * 128 + rd_off[(kk + 1) & 3]);
-                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(kk + 1) & 3]);
-                }
-                if (ISSUE && kk < 2 && q % QV == (QV > 1 ? 1 : 0)) {
-                    const int idx = kk * NVM + q / QV;
-                    if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
-                    else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr (F32) {
-                    // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
-                    // same K permutation for both operands
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
-                } else if constexpr (DT == FLE_F16) {
-                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
-                } else {
-                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+            for (int idx = 0; idx < NVM; ++idx) {
+                if (idx < NIW) ldw_.issue_one_tail(iW, uint32_t(kb + 1) * 128, idx, valid_of(kb + 1));
+                else ldx_.issue_one_tail(iX, uint32_t(kb + 1) * 128, idx - NIW, valid_of(kb + 1));
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // One K step: MORE: a next step exists (second half of its copies in slice 0, wait and barrier before
+    // slice 3, its first fragments read in slice 3); MORE2: so does the one after it (first half of its copies
+    // in slice 3).  The flags are compile-time so that the loop body is one straight-line sequence.
+    auto k_step = [&](int kt, auto more_c, auto more2_c) {
+        constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+        char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;        // the stage being multiplied
+        char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;  // the stage of the next step
+        slice(I0{}, std::true_type{}, std::integral_constant<int, MORE ? 2 : 0>{}, cW, cX, cW, cX, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+        slice(I1{}, std::true_type{}, I0{}, cW, cX, cW, cX, nW, nX, 0u, 8);
+        slice(I2{}, std::true_type{}, I0{}, cW, cX, cW, cX, nW, nX, 0u, 8);
+        if constexpr (MORE) {
+            wait_vmcnt<0>();                          // this wave's copies of the next stage have landed ...
+            __builtin_amdgcn_s_waitcnt(0xC07F);       // ... and its last fragment reads of this stage have returned
+            __builtin_amdgcn_s_barrier();             // everyone's have: the next stage is complete, this one is free
+        }
+        slice(I3{}, std::integral_constant<bool, MORE>{}, std::integral_constant<int, MORE2 ? 1 : 0>{}, cW, cX, nW, nX, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
     };
-
-    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y)
-    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
-    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
-    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, kb + 1 == KT ? tail_valid : 8);
     {
         int kt = kb;
-        for (; kt < ke - 1; ++kt) k_step(kt, std::true_type{});
-        k_step(kt, std::false_type{});
+        for (; kt + 2 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{});
+        if (kt + 1 < ke) {
+            k_step(kt, std::true_type{}, std::false_type{});
+            ++kt;
+        }
+        k_step(kt, std::false_type{}, std::false_type{});
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;
