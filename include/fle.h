@@ -102,8 +102,9 @@ typedef struct {
  * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL, at most one row
  * op, and nothing after LOGSUMEXP.  A second row op gives FLE_ERR_UNSUPPORTED.
  *
- * Alignment rule: no alignment is required for correctness.  The tiled MFMA kernels (every
- * dtype) are taken when x and W are 16-byte aligned and K and their row strides are
+ * Alignment rule: no alignment is required for correctness.  The fast kernels (tiled MFMA
+ * kernels for every dtype; the skinny and thin kernels that stream W for up to 256, 32 or 8
+ * rows of x) are taken when x and W are 16-byte aligned and K and their row strides are
  * multiples of 16 bytes (8 bf16 or fp16 / 4 fp32 elements); N, out, b and the residual may then be
  * ragged or misaligned (the kernel switches to an element-wise epilogue).  Other problems
  * run on a slower general kernel.  Problems with few output tiles and a long K are split
@@ -166,7 +167,9 @@ const char *fle_status_string(fle_status s);
 const char *fle_last_error(void);
 
 /* Human-readable plan (kernel variant, tile, grid) of the calling thread's most recent
- * successful fle_run or fle_workspace_size, copied into buf (NUL-terminated, truncated to n). */
+ * successful fle_run or fle_workspace_size (or their grouped forms), copied into buf (NUL-terminated,
+ * truncated to n).  "tile=AxBxC" is rows of x, rows of W and the K step in elements; for the
+ * dot-product thin kernel ("thin_*_dot") C is the number of W rows per wave instead. */
 fle_status fle_last_plan(char *buf, size_t n);
 
 /* Force a kernel variant for the calling thread's next calls, for tests and tuning:
