@@ -64,6 +64,10 @@ struct FinArgs {
     const float *partials;
     void *out;
     int64_t ldo;
+    // grouped problems whose list has a bias op after the row op: the row's group selects the bias
+    const int64_t *row_offsets;  // [n_groups + 1] (device), or nullptr
+    int32_t n_groups;
+    int64_t b_stride_bytes;
     DevEpilogue epi;
 };
 

@@ -154,6 +154,14 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     f.partials = split ? r.partials : g.partials;
     f.out = p->out; f.ldo = p->ldo;
     f.epi = e;
+    if (grp && grp->b_group_stride != 0) {  // a bias op after the row op needs the row's group
+        for (int o = 0; o < e.n_post; ++o)
+            if (e.post[o].kind == FLE_BIAS) {
+                f.row_offsets = grp->row_offsets;
+                f.n_groups = grp->n_groups;
+                f.b_stride_bytes = grp->b_group_stride * int64_t(es);
+            }
+    }
     if (e.row_kind == FLE_LOGSUMEXP) {
         hipLaunchKernelGGL(finalize_lse, dim3(uint32_t((p->M + 3) / 4)), dim3(256), 0, stream, f);
         return check_launch("logsumexp finalize launch");

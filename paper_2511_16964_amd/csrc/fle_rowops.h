@@ -75,8 +75,20 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
             sub = s.a;
             mul = 1.0f / s.b;
         }
+        // the bias of this row: of its group for a grouped problem (the last group whose first row is <= row:
+        // empty groups share their offset with the next one), else the problem's
+        const void *bias = a.epi.bias;
+        if (a.row_offsets && bias) {
+            int lo = 0, hi = a.n_groups;  // invariant: offsets[lo] <= row (offsets[0] counts as 0), offsets[hi] > row or hi == n_groups
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) / 2;
+                if (a.row_offsets[mid] <= row) lo = mid;
+                else hi = mid;
+            }
+            bias = reinterpret_cast<const char *>(bias) + int64_t(lo) * a.b_stride_bytes;
+        }
         auto post = [&](float v, int64_t n) -> float {
-            for (int o = 0; o < a.epi.n_post; ++o) v = apply_op(a.epi.post[o], v, row, n, a.epi.bias, dtype);
+            for (int o = 0; o < a.epi.n_post; ++o) v = apply_op(a.epi.post[o], v, row, n, bias, dtype);
             return v;
         };
         if (VEC) {

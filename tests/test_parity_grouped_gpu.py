@@ -52,6 +52,8 @@ def test_grouped_other_dtypes_integer_exact(dtype, variant, counts, N, K):
 
 
 CHAINS = [
+    ["softmax", "bias"],                       # a bias after the row op: the finalize pass must pick the row's group
+    ["bias", "layernorm", "bias", "relu"],
     ["bias", "gelu_tanh"],
     ["bias", "gelu_erf", "scale", "residual"],
     ["bias", "relu", "layernorm", "residual"],
