@@ -29,7 +29,7 @@ struct GemmArgs {
     void *dst;  // where the values after the pre-ops go (nullptr: nowhere, logsumexp)
     int64_t ldd;
     int32_t dst_f32;  // dst holds fp32 regardless of the storage dtype (workspace staging)
-    int32_t dst_rel;  // softmax staged in bf16: store v - (maximum of v's partial), which is <= 0 and keeps exp() accurate
+    int32_t dst_rel;  // row op staged in a 2-byte dtype: store v - (mean / maximum of v's partial); the finalize pass adds it back in fp32
     int32_t np;       // row-reduction partials per row
     float *partials;  // [M][np][2], or nullptr without a row op
     int32_t tiles_m, tiles_n;
@@ -59,7 +59,7 @@ struct FinArgs {
     const void *y;  // staged values: storage dtype (may alias out) or fp32
     int64_t ldy;
     int32_t y_f32;
-    int32_t y_rel;  // staged values are relative to the maximum of their partial (bf16 softmax)
+    int32_t y_rel;  // staged values are relative to the mean / maximum of their partial (2-byte dtypes)
     int32_t np, part_cols;
     const float *partials;
     void *out;

@@ -331,13 +331,14 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->ws_part_off = off;
         off = round_up(off + size_t(M) * size_t(plan->np) * 2 * sizeof(float), 256);
         if (!lse) {
-            // Staged in out itself unless a trailing residual aliases out.  LayerNorm values survive one bf16
-            // rounding (the normalised result is O(1)); bf16 softmax stages v minus the maximum of v's partial,
-            // which is <= 0, so the rounding error of exp() stays below |d| 2^-9 with d the distance to that
-            // maximum: negligible where the probability is not.
+            // Staged in out itself unless a trailing residual aliases out.  A 2-byte dtype stages v minus the
+            // statistic of v's partial (its mean for LayerNorm, its maximum for softmax), which the finalize pass
+            // adds back in fp32: the rounding error of the staged value is then relative to the distance from that
+            // statistic, not to v itself (a row of mean 100 and deviation 0.01 keeps its deviations; exp() of a
+            // distance d <= 0 is off by at most |d| 2^-9, negligible where the probability is not).
             const bool in_out = !post_res_alias_out;
             plan->staging = in_out ? ST_OUT : ST_WS;
-            plan->stage_rel = (in_out && e.row_kind == FLE_SOFTMAX && p->dtype != FLE_F32) ? 1 : 0;
+            plan->stage_rel = (in_out && p->dtype != FLE_F32) ? 1 : 0;
             if (!in_out) {
                 plan->ws_y_off = off;
                 off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);

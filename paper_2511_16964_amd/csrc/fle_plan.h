@@ -44,7 +44,7 @@ struct Plan {
     int32_t part_cols;       // columns covered by one row-reduction partial
     int32_t np;              // partials per row = ceil(N / part_cols)
     int32_t staging;
-    int32_t stage_rel;       // bf16 softmax staged in out as v - (maximum of v's partial)
+    int32_t stage_rel;       // 2-byte row op staged in out as v - (mean / maximum of v's partial)
     int32_t edge;            // tiled kernel: the epilogue must access b / residual / out one element at a time
     int32_t split_k;         // workgroups along K per tile (1: none); > 1 adds fp32 slabs and a reduction pass
     int32_t groups;          // grouped problem: number of row groups (tiles_m is then an upper bound); 0 otherwise

@@ -97,6 +97,8 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                 const int64_t n = c0 + it * 512 + lane * 8;
                 if (n < c1) {
                     float *v = y[it];
+                    // staged relative to the statistic (mean / maximum) of the partial the 8 columns lie in (part_cols is a multiple of 8)
+                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
                     if (ln) {
                         float g[8], be[8];
 #pragma unroll
@@ -104,10 +106,8 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                         if (a.epi.row.p0) ld8(a.epi.row.p0, n, dtype, g);
                         if (a.epi.row.p1) ld8(a.epi.row.p1, n, dtype, be);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = (v[e] - sub) * mul * g[e] + be[e];
+                        for (int e = 0; e < 8; ++e) v[e] = (v[e] - shift) * mul * g[e] + be[e];
                     } else {
-                        // staged relative to the maximum of the partial the 8 columns lie in (part_cols is a multiple of 8)
-                        const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - shift) * mul;
                     }
@@ -128,12 +128,12 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
             auto one = [&](int64_t n) {  // one element
                 const float yv = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
                 float v;
+                const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
                 if (ln) {
-                    v = (yv - sub) * mul;
+                    v = (yv - shift) * mul;
                     if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
                     if (a.epi.row.p1) v += ld_elem(a.epi.row.p1, n, dtype);
                 } else {
-                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
                     v = __expf(yv - shift) * mul;
                 }
                 st_elem(a.out, row * a.ldo + n, dtype, post(v, n));
@@ -152,20 +152,20 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                     if (n + 8 <= N) {
                         float v[8];
                         ld8(a.y, row * a.ldy + n, dtype, v);
+                        float s0 = sub, s1 = sub;
+                        const int64_t p0 = n / a.part_cols, p1 = (n + 7) / a.part_cols;  // the 8 columns may straddle two partials
+                        if (a.y_rel) {
+                            s0 = sub - a.partials[(row * a.np + p0) * 2];
+                            s1 = sub - a.partials[(row * a.np + p1) * 2];
+                        }
                         if (ln) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) {
-                                v[e] = (v[e] - sub) * mul;
+                                v[e] = (v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
                                 if (a.epi.row.p0) v[e] *= ld_elem(a.epi.row.p0, n + e, dtype);
                                 if (a.epi.row.p1) v[e] += ld_elem(a.epi.row.p1, n + e, dtype);
                             }
                         } else {
-                            float s0 = sub, s1 = sub;
-                            const int64_t p0 = n / a.part_cols, p1 = (n + 7) / a.part_cols;  // the 8 columns may straddle two partials
-                            if (a.y_rel) {
-                                s0 = sub - a.partials[(row * a.np + p0) * 2];
-                                s1 = sub - a.partials[(row * a.np + p1) * 2];
-                            }
 #pragma unroll
                             for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
                         }

@@ -255,6 +255,22 @@ def test_bf16_softmax_with_wide_logits(variant, split, M, N, K):
     assert np.abs(got.to(torch.float64).numpy().sum(1) - 1.0).max() < 1e-2
 
 
+@pytest.mark.parametrize("variant,dtype,M,N,K", [("tiled", BF16, 200, 520, 128), ("tiled256", F16, 300, 776, 64), ("general", BF16, 70, 97, 83),
+                                                 ("skinny", BF16, 32, 2304, 256), ("thin", F16, 3, 392, 520), ("thin", BF16, 20, 263, 264),
+                                                 ("tiled128", BF16, 150, 392, 256), ("general", BF16, 35, 1, 54)])
+def test_layernorm_of_rows_with_a_large_common_offset(variant, dtype, M, N, K):
+    """A 2-byte dtype stages the values for the LayerNorm pass relative to their partial's mean: a row whose
+    mean is hundreds of times its deviation (bias 100 on unit-scale sums) must still normalise correctly,
+    which a plainly rounded staged value (error 0.2 .. 0.4 here) would not.  One column is the degenerate
+    case: the result is beta exactly."""
+    prob = inputs.random_problem(19, M, N, K, dtype, ["bias", "layernorm"])
+    prob.b = torch.full_like(prob.b, 100.0)
+    announce("layernorm with offset", variant, dtype, M, N, K)
+    got, call = run_gpu(prob, variant, split=2 if variant == "tiled128" else 0)
+    assert "staging=out" in call.plan(), call.plan()
+    assert_close(got, oracle_rows(prob), dtype, call.plan())
+
+
 def test_softmax_followed_by_a_residual_that_aliases_out():
     dev = "cuda:0"
     prob = inputs.random_problem(18, 150, 264, 128, BF16, ["bias", "softmax", "residual"])
