@@ -28,7 +28,7 @@ def random_chain(rng):
 
 
 def random_dims(rng):
-    kind = rng.integers(0, 6)
+    kind = rng.integers(0, 7)
     if kind == 0:      # tiny
         return int(rng.integers(1, 40)), int(rng.integers(1, 70)), int(rng.integers(1, 70))
     if kind == 1:      # a few rows against a wide matrix (thin / skinny kernels)
@@ -39,7 +39,9 @@ def random_dims(rng):
         return int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 300))
     if kind == 4:      # long K, few tiles (split K)
         return int(rng.integers(1, 200)), int(rng.integers(64, 400)), int(rng.integers(8, 40)) * 128
-    return int(rng.integers(1, 33)), int(rng.integers(8, 64)) * 128, int(rng.integers(4, 20)) * 256   # perceptron layers
+    if kind == 5:      # perceptron layers
+        return int(rng.integers(1, 33)), int(rng.integers(8, 64)) * 128, int(rng.integers(4, 20)) * 256
+    return int(rng.integers(200, 1000)), int(rng.integers(200, 2000)), int(rng.integers(8, 128)) * 8   # several large tiles
 
 
 @pytest.mark.parametrize("seed", range(160))
@@ -78,8 +80,10 @@ def test_random_problem_matches_oracle(seed):
         variants += ["tiled", "tiled128", "tiled256"]
         if M <= 32:
             variants.append("thin")
-        if M <= 256 and K % 64 == 0 and N % 4 == 0 and dtype != torch.float32:
+        if M <= 256 and K % 64 == 0 and N % 4 == 0:
             variants += ["skinny", "skinny256"]
+            if dtype != torch.float32 and K % 256 == 0:
+                variants.append("skinnyseq")
     variant = variants[rng.integers(0, len(variants))]
     print("[case] seed %d %s M=%d N=%d K=%d %s pad=%d shift=%d %s" % (seed, str(dtype)[6:], M, N, K, variant, pad, shift, chain), flush=True)
     try:
