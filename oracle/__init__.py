@@ -63,6 +63,11 @@ def _load():
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
             ctypes.POINTER(_Op), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
+        lib.fle_oracle_attention.restype = ctypes.c_int
+        lib.fle_oracle_attention.argtypes = [
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+            ctypes.c_int32, ctypes.c_double, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
         lib.fle_oracle_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -161,3 +166,53 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0
         bg = None if b is None else (b[g] if b.ndim == 2 else b)
         out[lo:hi] = fused_linear_epilogue(x[lo:hi], w[g], bg, ep, n_threads)
     return out
+
+
+def attention(q, k, v, causal: bool, scale=None, n_threads: int = 0) -> np.ndarray:
+    """float64 gold result of scaled dot-product attention, token-major.
+
+    q, k, v: [B, T, H, D] float64 (any strides whose last two axes are contiguous, so the three
+    thirds of a fused QKV projection's output can be passed as views); scale defaults to
+    1/sqrt(D) and is rounded to fp32 as it is when it crosses the GPU boundary.  causal: query t
+    sees keys 0..t only (the mask the paper's attention solutions apply on the fly, appendix on
+    Level 5 outliers).  Returns [B, T, H, D].
+    """
+    q, k, v = (np.asarray(a) for a in (q, k, v))
+    if q.ndim != 4 or q.shape != k.shape or q.shape != v.shape:
+        raise ValueError("q, k, v must be [B,T,H,D] of one shape")
+    for a in (q, k, v):
+        if a.dtype != np.float64:
+            raise TypeError("the oracle takes float64 arrays only")
+    B, T, H, D = q.shape
+    q2, k2, v2 = (np.ascontiguousarray(a).reshape(B * T, H * D) for a in (q, k, v))
+    sc = float(np.float32(1.0 / np.sqrt(D) if scale is None else scale))
+    out = np.empty((B * T, H * D), dtype=np.float64)
+    rc = _load().fle_oracle_attention(
+        B, H, T, D, q2.ctypes.data, H * D, k2.ctypes.data, H * D, v2.ctypes.data, H * D,
+        1 if causal else 0, sc, out.ctypes.data, H * D, int(n_threads))
+    if rc != 0:
+        raise ValueError("fle_oracle_attention rejected the arguments (code %d)" % rc)
+    return out.reshape(B, T, H, D)
+
+
+def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads: int, causal: bool, residual=None, n_threads: int = 0) -> np.ndarray:
+    """float64 gold result of a self-attention block: the unfused composition.
+
+    qkv = x w_qkv^T + b_qkv is cut into thirds q | k | v along its columns, each third into
+    `heads` heads of D = C / heads columns; attention runs per head; the heads' outputs, side by
+    side again, go through the output projection w_o (+ b_o, + residual).  This is the block whose
+    fusion (projections included) the paper's task-wise analysis reports as its largest recurring
+    speedup.  x [B,T,C]; w_qkv [3C,C]; b_qkv [3C] or None; w_o [C,C]; b_o [C] or None;
+    residual [B,T,C] or None.  Returns [B,T,C].
+    """
+    x = _f64(x)
+    B, T, C = x.shape
+    if C % heads:
+        raise ValueError("C must be a multiple of heads")
+    D = C // heads
+    qkv = fused_linear_epilogue(x.reshape(B * T, C), w_qkv, b_qkv, [("bias",)] if b_qkv is not None else [], n_threads)
+    qkv = qkv.reshape(B, T, 3, heads, D)
+    o = attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], causal, None, n_threads)
+    ep = ([("bias",)] if b_o is not None else []) + ([("residual", _f64(residual).reshape(B * T, C))] if residual is not None else [])
+    y = fused_linear_epilogue(o.reshape(B * T, C), w_o, b_o, ep, n_threads)
+    return y.reshape(B, T, C)

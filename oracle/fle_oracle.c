@@ -185,6 +185,71 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
     return failed ? -5 : 0;
 }
 
+/*
+ * Scaled dot-product attention over token-major operands, the definition written out (the
+ * attention block that the paper's task-wise analysis, and its appendix on Level 3-pike and
+ * Level 5 outliers, names as the largest recurring win once it is fused with its input and
+ * output projections and masks causally on the fly):
+ *
+ *     s[j]   = scale * sum_d q[b,t,h,d] * k[b,j,h,d]        for every key j the mask allows
+ *     p      = softmax over the allowed j
+ *     o[b,t,h,:] = sum_j p[j] * v[b,j,h,:]
+ *
+ * causal != 0 allows keys j <= t only.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d],
+ * likewise k, v and o.  Returns 0, or a negative code for bad arguments / -5 out of memory.
+ */
+int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const double *q, int64_t ldq,
+                         const double *k, int64_t ldk, const double *v, int64_t ldv, int32_t causal,
+                         double scale, double *o, int64_t ldo, int32_t threads) {
+    if (B < 0 || H < 1 || T < 1 || D < 1) return -1;
+    if (!q || !k || !v || !o) return -2;
+    if (ldq < H * D || ldk < H * D || ldv < H * D || ldo < H * D) return -3;
+    int failed = 0;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)T);
+        if (!s) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1) collapse(2)
+        for (int64_t b = 0; b < B; ++b)
+            for (int64_t t = 0; t < T; ++t) {
+                if (!s) continue;
+                const int64_t keys = causal ? t + 1 : T;
+                for (int64_t h = 0; h < H; ++h) {
+                    const double *qr = q + (b * T + t) * ldq + h * D;
+                    for (int64_t j = 0; j < keys; ++j) {
+                        const double *kr = k + (b * T + j) * ldk + h * D;
+                        double acc = 0.0;
+                        for (int64_t d = 0; d < D; ++d) acc += qr[d] * kr[d];
+                        s[j] = scale * acc;
+                    }
+                    const double mx = row_max(s, keys);
+                    double sum = 0.0;
+                    for (int64_t j = 0; j < keys; ++j) {
+                        s[j] = exp(s[j] - mx);
+                        sum += s[j];
+                    }
+                    double *orow = o + (b * T + t) * ldo + h * D;
+                    for (int64_t d = 0; d < D; ++d) orow[d] = 0.0;
+                    for (int64_t j = 0; j < keys; ++j) {
+                        const double p = s[j] / sum;
+                        const double *vr = v + (b * T + j) * ldv + h * D;
+                        for (int64_t d = 0; d < D; ++d) orow[d] += p * vr[d];
+                    }
+                }
+            }
+        free(s);
+    }
+    return failed ? -5 : 0;
+}
+
 /* Number of threads the parallel loop above will use (for the timing report). */
 int fle_oracle_threads(void) {
 #ifdef _OPENMP

@@ -337,3 +337,122 @@ def test_grouped_rejects_bad_offsets():
         with pytest.raises(ValueError):
             grouped(x, w, None, off)
     assert grouped(x, w, None, [0, 0, 4]).shape == (4, 5)
+
+
+# ------------------------------------------------------------------ attention (the block the paper's
+# task-wise analysis names as its largest recurring win; appendix on Level 3-pike / Level 5 outliers)
+def _qkv(B, T, H, D, rng=RNG):
+    return tuple(rng.standard_normal((B, T, H, D)) for _ in range(3))
+
+
+def test_attention_closed_forms():
+    B, T, H, D = 2, 9, 3, 4
+    q, k, v = _qkv(B, T, H, D)
+    # causal: the first query sees one key, so its output is that key's value row
+    o = oracle.attention(q, k, v, True)
+    np.testing.assert_allclose(o[:, 0], v[:, 0], rtol=0, atol=1e-15)
+    # equal scores (q = 0, or all keys equal): uniform weights -> (prefix) mean of v
+    o = oracle.attention(np.zeros_like(q), k, v, False)
+    np.testing.assert_allclose(o, np.broadcast_to(v.mean(axis=1, keepdims=True), v.shape), rtol=0, atol=1e-14)
+    same_k = np.broadcast_to(k[:, :1], k.shape).copy()
+    o = oracle.attention(q, same_k, v, True)
+    prefix_mean = np.cumsum(v, axis=1) / np.arange(1, T + 1).reshape(1, T, 1, 1)
+    np.testing.assert_allclose(o, prefix_mean, rtol=0, atol=1e-14)
+    # two keys, D = 4 (default scale 1/2): weights are the logistic function of the score difference
+    q2 = np.zeros((1, 2, 1, 4)); k2 = np.zeros((1, 2, 1, 4)); v2 = np.zeros((1, 2, 1, 4))
+    q2[0, :, 0, 0] = [2.0, -6.0]
+    k2[0, 0, 0, 0] = 1.0
+    v2[0, 0, 0] = [1, 0, 3, 0]; v2[0, 1, 0] = [0, 1, 0, -2]
+    o = oracle.attention(q2, k2, v2, False)
+    s1 = 0.7310585786300049  # 1 / (1 + e^-1): query 0 scores (1, 0)
+    np.testing.assert_allclose(o[0, 0, 0], s1 * v2[0, 0, 0] + (1 - s1) * v2[0, 1, 0], rtol=0, atol=1e-15)
+    s3 = 1.0 / (1.0 + math.exp(3.0))  # query 1 scores (-3, 0)
+    np.testing.assert_allclose(o[0, 1, 0], s3 * v2[0, 0, 0] + (1 - s3) * v2[0, 1, 0], rtol=0, atol=1e-15)
+    # an explicit scale: zero makes the weights uniform again
+    o = oracle.attention(q, k, v, False, scale=0.0)
+    np.testing.assert_allclose(o, np.broadcast_to(v.mean(axis=1, keepdims=True), v.shape), rtol=0, atol=1e-14)
+
+
+def test_attention_selects_the_matching_key():
+    # keys are far-apart one-hot rows and query t points at key perm[t]: the weights collapse onto it
+    T, D = 6, 8
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    k = np.zeros((1, T, 1, D)); q = np.zeros((1, T, 1, D))
+    for j in range(T):
+        k[0, j, 0, j] = 40.0
+        q[0, j, 0, perm[j]] = 40.0
+    v = RNG.standard_normal((1, T, 1, D))
+    o = oracle.attention(q, k, v, False)
+    np.testing.assert_allclose(o[0, :, 0], v[0, perm, 0], rtol=0, atol=1e-12)
+
+
+def test_attention_invariants():
+    B, T, H, D = 2, 11, 2, 8
+    q, k, v = _qkv(B, T, H, D)
+    base = oracle.attention(q, k, v, False)
+    # no mask: the order of the keys does not matter; permuting queries permutes outputs
+    perm = RNG.permutation(T)
+    np.testing.assert_allclose(oracle.attention(q, k[:, perm], v[:, perm], False), base, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(oracle.attention(q[:, perm], k, v, False), base[:, perm], rtol=0, atol=1e-14)
+    # a vector added to every key shifts all of a query's scores alike
+    c = RNG.standard_normal((1, 1, H, D))
+    np.testing.assert_allclose(oracle.attention(q, k + c, v, False), base, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(oracle.attention(q, k + c, v, True), oracle.attention(q, k, v, True), rtol=0, atol=1e-13)
+    # heads and batch entries are independent problems
+    alone = oracle.attention(q[1:, :, 1:], k[1:, :, 1:], v[1:, :, 1:], True)
+    np.testing.assert_allclose(oracle.attention(q, k, v, True)[1:, :, 1:], alone, rtol=0, atol=0)
+    # causal: outputs up to t do not depend on later tokens
+    cut = 5
+    np.testing.assert_allclose(oracle.attention(q, k, v, True)[:, :cut],
+                               oracle.attention(q[:, :cut], k[:, :cut], v[:, :cut], True), rtol=0, atol=0)
+    # linear in v; outputs are convex combinations of the value rows
+    np.testing.assert_allclose(oracle.attention(q, k, 2 * v + 1, False), 2 * base + 1, rtol=0, atol=1e-13)
+    assert (base <= v.max(axis=1, keepdims=True) + 1e-14).all() and (base >= v.min(axis=1, keepdims=True) - 1e-14).all()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_matches_torch_cpu_float64(causal):
+    B, T, H, D = 2, 13, 3, 16
+    q, k, v = _qkv(B, T, H, D)
+    tq, tk, tv = (torch.from_numpy(a).permute(0, 2, 1, 3) for a in (q, k, v))  # torch wants [B,H,T,D]
+    ref = F.scaled_dot_product_attention(tq, tk, tv, is_causal=causal, scale=float(np.float32(1 / math.sqrt(D))))
+    np.testing.assert_allclose(oracle.attention(q, k, v, causal), ref.permute(0, 2, 1, 3).numpy(), rtol=1e-12, atol=1e-13)
+    # views into one fused [B,T,3,H,D] buffer are accepted as they are
+    qkv = np.stack([q, k, v], axis=2)
+    np.testing.assert_allclose(oracle.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], causal),
+                               oracle.attention(q, k, v, causal), rtol=0, atol=0)
+
+
+def test_attention_block_layout_and_composition():
+    B, T, C, heads = 2, 6, 8, 2
+    D = C // heads
+    x = RNG.standard_normal((B, T, C))
+    # q and k thirds zero, v third and output projection the identity: causal prefix mean of x
+    w_qkv = np.zeros((3 * C, C)); w_qkv[2 * C:] = np.eye(C)
+    b_o = RNG.standard_normal(C); res = RNG.standard_normal((B, T, C))
+    y = oracle.attention_block(x, w_qkv, None, np.eye(C), b_o, heads, True, residual=res)
+    prefix_mean = np.cumsum(x, axis=1) / np.arange(1, T + 1).reshape(1, T, 1)
+    np.testing.assert_allclose(y, prefix_mean + b_o + res, rtol=0, atol=1e-14)
+    # column layout of the projection's output is [q | k | v], each cut into heads of D columns:
+    # against the same block composed from torch CPU float64 ops
+    w_qkv = RNG.standard_normal((3 * C, C)) * 0.5; b_qkv = RNG.standard_normal(3 * C)
+    w_o = RNG.standard_normal((C, C)) * 0.5
+    tx = torch.from_numpy(x)
+    qkv = F.linear(tx, torch.from_numpy(w_qkv), torch.from_numpy(b_qkv))
+    tq, tk, tv = (t.reshape(B, T, heads, D).transpose(1, 2) for t in qkv.split(C, dim=2))
+    att = F.scaled_dot_product_attention(tq, tk, tv, is_causal=False, scale=float(np.float32(1 / math.sqrt(D))))
+    ref = F.linear(att.transpose(1, 2).reshape(B, T, C), torch.from_numpy(w_o), torch.from_numpy(b_o))
+    y = oracle.attention_block(x, w_qkv, b_qkv, w_o, b_o, heads, False)
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-12, atol=1e-12)
+    # heads differ: with a single head over all C columns the result changes
+    assert np.abs(oracle.attention_block(x, w_qkv, b_qkv, w_o, b_o, 1, False) - y).max() > 1e-3
+
+
+def test_attention_rejects_bad_arguments():
+    q, k, v = _qkv(1, 3, 1, 4)
+    with pytest.raises(ValueError):
+        oracle.attention(q, k[:, :2], v, False)
+    with pytest.raises(TypeError):
+        oracle.attention(q.astype(np.float32), k, v, False)
+    with pytest.raises(ValueError):
+        oracle.attention_block(np.zeros((1, 2, 6)), np.zeros((18, 6)), None, np.eye(6), None, 4, False)
