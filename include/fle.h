@@ -160,6 +160,71 @@ fle_status fle_validate_grouped(const fle_problem *p, const fle_groups *g);
 fle_status fle_workspace_size_grouped(const fle_problem *p, const fle_groups *g, size_t *bytes_out);
 fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
 
+/*
+ * Scaled dot-product attention, forward, with the causal mask applied on the fly:
+ *
+ *     o[b,t,h,:] = sum_j softmax_j( scale * q[b,t,h,:] . k[b,j,h,:] ) * v[b,j,h,:]      (j <= t when causal)
+ *
+ * The paper's task-wise analysis (Section 5.3) and its appendix on Level 3-pike and Level 5 outliers
+ * name a flash-attention kernel, fused with the input and output projections and masking causally
+ * without a materialised mask, as the largest recurring speedup over eager PyTorch.  Operands are
+ * token-major, the layout a fused QKV projection writes: element (b,t,h,d) of q is at
+ * q[(b*T + t)*ldq + h*D + d], likewise k, v, o, so q, k and v may be the three column thirds of one
+ * [B*T, 3*H*D] matrix (ldq = ldk = ldv = 3*H*D) and o is ready to be the x of the output projection.
+ * The score matrix never reaches memory: one kernel walks the keys with a running maximum and sum
+ * (fp32 statistics and accumulation; the probabilities are rounded to the storage dtype for the
+ * second product, as the values are).
+ */
+typedef struct {
+    int32_t dtype;         /* FLE_BF16 or FLE_F16                                                  */
+    int32_t causal;        /* 0: every key; otherwise query t sees keys 0 .. t                      */
+    int64_t B, H, T, D;    /* batch, heads, tokens per sequence (>= 1), head dimension (64 or 128)  */
+    const void *q, *k, *v; /* DEVICE, 16-byte aligned                                               */
+    int64_t ldq, ldk, ldv; /* elements between consecutive tokens, >= H*D, multiples of 8           */
+    void *o;               /* DEVICE, 8-byte aligned; must not overlap q, k or v                    */
+    int64_t ldo;           /* >= H*D, a multiple of 4                                               */
+    float scale;           /* > 0, or 0 for 1/sqrt(D)                                               */
+    void *stream;          /* hipStream_t (NULL = the default stream)                               */
+} fle_attention;
+
+/* Host only (no HIP call): checks everything fle_attention_run checks. */
+fle_status fle_attention_validate(const fle_attention *p);
+
+/* Validates, then enqueues one kernel on p->stream and returns without synchronising.  Needs no
+ * workspace and never allocates.  B == 0 is a valid no-op. */
+fle_status fle_attention_run(const fle_attention *p);
+
+/*
+ * A whole self-attention block in three launches that share no host synchronisation:
+ *
+ *     qkv = x w_qkv^T + b_qkv          [B*T, 3C]   (fused linear, columns are q | k | v, each H heads of D = C/H)
+ *     a   = attention(q, k, v)         [B*T, C]    (fle_attention_run reading the thirds of qkv in place)
+ *     out = a w_o^T + b_o (+ residual) [B*T, C]    (fused linear with its epilogue)
+ *
+ * All operands are row-major and packed (row strides C, 3C as above); qkv and a live in the workspace.
+ */
+typedef struct {
+    int32_t dtype;        /* FLE_BF16 or FLE_F16                                          */
+    int32_t causal;
+    int64_t B, T, C, H;   /* C = H * D with D = 64 or 128                                 */
+    const void *x;        /* DEVICE [B*T, C]                                              */
+    const void *w_qkv;    /* DEVICE [3C, C]                                               */
+    const void *b_qkv;    /* DEVICE [3C] or NULL                                          */
+    const void *w_o;      /* DEVICE [C, C]                                                */
+    const void *b_o;      /* DEVICE [C] or NULL                                           */
+    const void *residual; /* DEVICE [B*T, C] or NULL; may be x                            */
+    void *out;            /* DEVICE [B*T, C]; may alias residual exactly, nothing else    */
+    void *workspace;      /* DEVICE, 256-byte aligned, fle_attention_block_workspace_size bytes */
+    size_t workspace_bytes;
+    void *stream;
+} fle_attention_block;
+
+fle_status fle_attention_block_validate(const fle_attention_block *p);
+fle_status fle_attention_block_workspace_size(const fle_attention_block *p, size_t *bytes_out);
+/* Enqueues the three stages on p->stream.  On an error from a later stage the earlier ones may
+ * already be enqueued (they only write the workspace). */
+fle_status fle_attention_block_run(const fle_attention_block *p);
+
 /* Static description of a status code. */
 const char *fle_status_string(fle_status s);
 

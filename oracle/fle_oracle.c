@@ -196,12 +196,14 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
  *     o[b,t,h,:] = sum_j p[j] * v[b,j,h,:]
  *
  * causal != 0 allows keys j <= t only.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d],
- * likewise k, v and o.  Returns 0, or a negative code for bad arguments / -5 out of memory.
+ * likewise k, v and o.  Only queries t >= t_first are evaluated (the other rows of o are left
+ * untouched), so that a few rows of a long sequence can be checked without computing all of them.
+ * Returns 0, or a negative code for bad arguments / -5 out of memory.
  */
 int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const double *q, int64_t ldq,
                          const double *k, int64_t ldk, const double *v, int64_t ldv, int32_t causal,
-                         double scale, double *o, int64_t ldo, int32_t threads) {
-    if (B < 0 || H < 1 || T < 1 || D < 1) return -1;
+                         double scale, double *o, int64_t ldo, int64_t t_first, int32_t threads) {
+    if (B < 0 || H < 1 || T < 1 || D < 1 || t_first < 0 || t_first > T) return -1;
     if (!q || !k || !v || !o) return -2;
     if (ldq < H * D || ldk < H * D || ldv < H * D || ldo < H * D) return -3;
     int failed = 0;
@@ -219,7 +221,7 @@ int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const doubl
         }
 #pragma omp for schedule(dynamic, 1) collapse(2)
         for (int64_t b = 0; b < B; ++b)
-            for (int64_t t = 0; t < T; ++t) {
+            for (int64_t t = t_first; t < T; ++t) {
                 if (!s) continue;
                 const int64_t keys = causal ? t + 1 : T;
                 for (int64_t h = 0; h < H; ++h) {

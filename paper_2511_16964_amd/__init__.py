@@ -7,7 +7,7 @@ implementation: if the library is missing, calls raise.
 """
 import importlib
 
-__all__ = ["fused_linear_epilogue", "grouped_fused_linear_epilogue"]
+__all__ = ["fused_linear_epilogue", "grouped_fused_linear_epilogue", "attention", "attention_block"]
 
 
 def __getattr__(name):

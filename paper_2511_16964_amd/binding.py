@@ -20,7 +20,9 @@ MAX_OPS = 8
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
 EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
            "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
-           "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped"]
+           "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped",
+           "fle_attention_validate", "fle_attention_run", "fle_attention_block_validate",
+           "fle_attention_block_workspace_size", "fle_attention_block_run"]
 
 
 class FleOp(ctypes.Structure):
@@ -43,6 +45,24 @@ class FleProblem(ctypes.Structure):
 class FleGroups(ctypes.Structure):
     _fields_ = [("n_groups", ctypes.c_int32), ("row_offsets", ctypes.c_void_p),
                 ("w_group_stride", ctypes.c_int64), ("b_group_stride", ctypes.c_int64)]
+
+
+class FleAttention(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("B", ctypes.c_int64), ("H", ctypes.c_int64), ("T", ctypes.c_int64), ("D", ctypes.c_int64),
+                ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("ldq", ctypes.c_int64), ("ldk", ctypes.c_int64), ("ldv", ctypes.c_int64),
+                ("o", ctypes.c_void_p), ("ldo", ctypes.c_int64), ("scale", ctypes.c_float),
+                ("stream", ctypes.c_void_p)]
+
+
+class FleAttentionBlock(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("B", ctypes.c_int64), ("T", ctypes.c_int64), ("C", ctypes.c_int64), ("H", ctypes.c_int64),
+                ("x", ctypes.c_void_p), ("w_qkv", ctypes.c_void_p), ("b_qkv", ctypes.c_void_p),
+                ("w_o", ctypes.c_void_p), ("b_o", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("stream", ctypes.c_void_p)]
 
 
 class FleError(RuntimeError):
@@ -72,6 +92,14 @@ def lib():
             getattr(L, name).argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FleGroups)]
         L.fle_workspace_size_grouped.restype = ctypes.c_int
         L.fle_workspace_size_grouped.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FleGroups), ctypes.POINTER(ctypes.c_size_t)]
+        for name in ("fle_attention_validate", "fle_attention_run"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.POINTER(FleAttention)]
+        for name in ("fle_attention_block_validate", "fle_attention_block_run"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.POINTER(FleAttentionBlock)]
+        L.fle_attention_block_workspace_size.restype = ctypes.c_int
+        L.fle_attention_block_workspace_size.argtypes = [ctypes.POINTER(FleAttentionBlock), ctypes.POINTER(ctypes.c_size_t)]
         L.fle_status_string.restype = ctypes.c_char_p
         L.fle_status_string.argtypes = [ctypes.c_int]
         L.fle_last_error.restype = ctypes.c_char_p
@@ -249,3 +277,102 @@ def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="
     if not x.is_cuda:
         raise RuntimeError("fused_linear_epilogue runs on the GPU only; there is no CPU path")
     return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, split=split).run()
+
+
+def _token_stride(t):
+    """[B,T,H,D] view whose (h, d) axes are packed and whose batch axis continues the token axis."""
+    B, T, H, D = t.shape
+    if t.stride(3) != 1 or t.stride(2) != D or (B > 1 and t.stride(0) != T * t.stride(1)):
+        raise ValueError("q, k, v, o must be token-major [B,T,H,D] views: unit stride along D, D along H, one stride per token")
+    return t.stride(1)
+
+
+class AttentionCall:
+    """A marshalled fle_attention bound to its tensors; ``run()`` enqueues it on the current stream."""
+
+    def __init__(self, q, k, v, causal, scale=None, out=None):
+        if q.dim() != 4 or q.shape != k.shape or q.shape != v.shape:
+            raise ValueError("q, k, v must be [B,T,H,D] of one shape")
+        if not (q.is_cuda and k.is_cuda and v.is_cuda):
+            raise RuntimeError("attention runs on the GPU only; there is no CPU path")
+        if k.dtype != q.dtype or v.dtype != q.dtype:
+            raise TypeError("q, k, v must share one dtype")
+        B, T, H, D = q.shape
+        if out is None:
+            out = torch.empty((B, T, H, D), device=q.device, dtype=q.dtype)
+        p = FleAttention()
+        p.dtype, p.causal = _dtype_code(q.dtype), 1 if causal else 0
+        p.B, p.H, p.T, p.D = B, H, T, D
+        p.q, p.k, p.v, p.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
+        p.ldq, p.ldk, p.ldv, p.ldo = (_token_stride(t) for t in (q, k, v, out))
+        p.scale = 0.0 if scale is None else float(scale)
+        self._keep = (q, k, v)
+        self.out, self._p, self._pref, self._dev = out, p, ctypes.byref(p), q.device.index
+        _check(lib().fle_attention_validate(self._pref))
+
+    def run(self, stream=None):
+        self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
+        status = lib().fle_attention_run(self._pref)
+        if status != 0:
+            _check(status)
+        return self.out
+
+
+def attention(q, k, v, causal, scale=None, out=None):
+    """Scaled dot-product attention over token-major [B,T,H,D] tensors (bf16 or fp16, D = 64 or 128).
+
+    q, k, v may be views into one fused projection output (``qkv.view(B,T,3,H,D)[:, :, i]``); nothing is
+    copied or transposed.  causal: query t sees keys 0..t.  scale defaults to 1/sqrt(D).
+    """
+    return AttentionCall(q, k, v, causal, scale, out).run()
+
+
+class AttentionBlockCall:
+    """A marshalled fle_attention_block (QKV projection, attention, output projection) bound to its tensors."""
+
+    def __init__(self, x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual=None, out=None, workspace=None):
+        if x.dim() != 3:
+            raise ValueError("x must be [B,T,C]")
+        if not x.is_cuda:
+            raise RuntimeError("attention_block runs on the GPU only; there is no CPU path")
+        B, T, C = x.shape
+        for name, t, shape in (("w_qkv", w_qkv, (3 * C, C)), ("b_qkv", b_qkv, (3 * C,)), ("w_o", w_o, (C, C)),
+                               ("b_o", b_o, (C,)), ("residual", residual, (B, T, C)), ("out", out, (B, T, C))):
+            if t is None:
+                continue
+            if tuple(t.shape) != shape or not t.is_contiguous() or t.dtype != x.dtype or t.device != x.device:
+                raise ValueError("%s must be a contiguous %s tensor of x's dtype and device" % (name, list(shape)))
+        if not x.is_contiguous():
+            raise ValueError("x must be contiguous")
+        if out is None:
+            out = torch.empty_like(x)
+        p = FleAttentionBlock()
+        p.dtype, p.causal = _dtype_code(x.dtype), 1 if causal else 0
+        p.B, p.T, p.C, p.H = B, T, C, int(heads)
+        p.x, p.w_qkv, p.w_o, p.out = x.data_ptr(), w_qkv.data_ptr(), w_o.data_ptr(), out.data_ptr()
+        p.b_qkv = None if b_qkv is None else b_qkv.data_ptr()
+        p.b_o = None if b_o is None else b_o.data_ptr()
+        p.residual = None if residual is None else residual.data_ptr()
+        need = ctypes.c_size_t(0)
+        _check(lib().fle_attention_block_workspace_size(ctypes.byref(p), ctypes.byref(need)))
+        if workspace is None:
+            workspace = torch.empty(max(need.value, 256), device=x.device, dtype=torch.uint8)
+        p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        self.workspace_needed = need.value
+        self._keep = (x, w_qkv, b_qkv, w_o, b_o, residual, workspace)
+        self.out, self._p, self._pref, self._dev = out, p, ctypes.byref(p), x.device.index
+
+    def run(self, stream=None):
+        self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
+        status = lib().fle_attention_block_run(self._pref)
+        if status != 0:
+            _check(status)
+        return self.out
+
+
+def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual=None, out=None, workspace=None):
+    """out = (attention over `heads` heads of (x w_qkv^T + b_qkv)) w_o^T + b_o (+ residual), three fused launches.
+
+    x [B,T,C]; w_qkv [3C,C] with output columns q | k | v; C / heads must be 64 or 128; bf16 or fp16.
+    """
+    return AttentionBlockCall(x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual, out, workspace).run()

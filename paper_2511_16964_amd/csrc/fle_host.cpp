@@ -375,6 +375,106 @@ static fle_status check_workspace(const fle_problem *p, const Plan &plan) {
     return FLE_OK;
 }
 
+// ------------------------------------------------------------------ attention
+static fle_status check_attention(const fle_attention *p) {
+    if (!p) return fail(FLE_ERR_NULL, "attention problem is NULL");
+    if (p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_UNSUPPORTED, "attention takes FLE_BF16 or FLE_F16 (got dtype %d)", p->dtype);
+    if (p->B < 0 || p->H < 1 || p->T < 1) return fail(FLE_ERR_SHAPE, "need B >= 0, H >= 1, T >= 1 (got %lld, %lld, %lld)", (long long)p->B, (long long)p->H, (long long)p->T);
+    if (p->D != 64 && p->D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 64 or 128", (long long)p->D);
+    if (p->B > 65535 || p->H > 65535) return fail(FLE_ERR_SHAPE, "B and H are limited to 65535");
+    if (p->T > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T is limited to 2^24");
+    const int64_t HD = p->H * p->D;
+    const int64_t kLimit = int64_t(1) << 40;
+    if (p->ldq < HD || p->ldk < HD || p->ldv < HD || p->ldo < HD) return fail(FLE_ERR_SHAPE, "a token stride is smaller than H*D = %lld", (long long)HD);
+    if (p->ldq > kLimit || p->ldk > kLimit || p->ldv > kLimit || p->ldo > kLimit) return fail(FLE_ERR_SHAPE, "token stride too large");
+    if (!(p->scale >= 0.0f) || std::isinf(p->scale)) return fail(FLE_ERR_OP, "scale must be finite and > 0 (or 0 for 1/sqrt(D))");
+    if (p->B == 0) return FLE_OK;
+    if (!p->q || !p->k || !p->v || !p->o) return fail(FLE_ERR_NULL, "q, k, v or o is NULL");
+    if (!aligned(p->q, 16) || !aligned(p->k, 16) || !aligned(p->v, 16)) return fail(FLE_ERR_ALIGN, "q, k and v must be 16-byte aligned");
+    if (p->ldq % 8 || p->ldk % 8 || p->ldv % 8) return fail(FLE_ERR_ALIGN, "ldq, ldk and ldv must be multiples of 8 elements");
+    if (!aligned(p->o, 8) || p->ldo % 4) return fail(FLE_ERR_ALIGN, "o must be 8-byte aligned and ldo a multiple of 4 elements");
+    const int64_t rows = p->B * p->T;
+    const size_t no = span_bytes(rows, HD, p->ldo, 2);
+    if (overlaps(p->o, no, p->q, span_bytes(rows, HD, p->ldq, 2)) || overlaps(p->o, no, p->k, span_bytes(rows, HD, p->ldk, 2)) ||
+        overlaps(p->o, no, p->v, span_bytes(rows, HD, p->ldv, 2)))
+        return fail(FLE_ERR_UNSUPPORTED, "o overlaps q, k or v");
+    return FLE_OK;
+}
+
+// The three stages of an attention block and where their intermediates sit in the workspace.
+struct BlockParts {
+    fle_problem proj, outp;
+    fle_attention att;
+    fle_op proj_ops[1], out_ops[2];
+    Plan proj_plan, out_plan;
+    size_t qkv_off, a_off, sub_off, total;
+};
+
+static fle_status plan_block(const fle_attention_block *p, BlockParts *bp) {
+    if (!p) return fail(FLE_ERR_NULL, "attention block is NULL");
+    if (p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_UNSUPPORTED, "attention takes FLE_BF16 or FLE_F16 (got dtype %d)", p->dtype);
+    if (p->B < 0 || p->T < 1 || p->C < 1 || p->H < 1) return fail(FLE_ERR_SHAPE, "need B >= 0, T >= 1, C >= 1, H >= 1");
+    if (p->B > 65535 || p->T > (int64_t(1) << 24) || p->C > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "size too large");
+    if (p->C % p->H) return fail(FLE_ERR_SHAPE, "C = %lld is not a multiple of H = %lld", (long long)p->C, (long long)p->H);
+    const int64_t D = p->C / p->H, rows = p->B * p->T, C = p->C;
+    std::memset(bp, 0, sizeof *bp);
+    bp->qkv_off = 0;
+    bp->a_off = round_up(size_t(rows) * size_t(3 * C) * 2, 256);
+    bp->sub_off = bp->a_off + round_up(size_t(rows) * size_t(C) * 2, 256);
+    char *ws = reinterpret_cast<char *>(p->workspace);
+    char *qkv = ws ? ws + bp->qkv_off : nullptr, *a = ws ? ws + bp->a_off : nullptr;
+
+    fle_problem &pj = bp->proj;
+    pj.M = rows; pj.N = 3 * C; pj.K = C; pj.dtype = p->dtype;
+    pj.x = p->x; pj.ldx = C; pj.w = p->w_qkv; pj.ldw = C; pj.b = p->b_qkv;
+    pj.out = qkv;
+    pj.ldo = 3 * C;
+    if (p->b_qkv) { bp->proj_ops[0].kind = FLE_BIAS; pj.n_ops = 1; }
+    pj.ops = bp->proj_ops;
+    pj.stream = p->stream;
+
+    fle_attention &at = bp->att;
+    at.dtype = p->dtype; at.causal = p->causal; at.B = p->B; at.H = p->H; at.T = p->T; at.D = D;
+    at.q = qkv; at.k = qkv ? qkv + C * 2 : nullptr; at.v = qkv ? qkv + 2 * C * 2 : nullptr;
+    at.ldq = at.ldk = at.ldv = 3 * C;
+    at.o = a; at.ldo = C; at.scale = 0.0f; at.stream = p->stream;
+
+    fle_problem &po = bp->outp;
+    po.M = rows; po.N = C; po.K = C; po.dtype = p->dtype;
+    po.x = a; po.ldx = C; po.w = p->w_o; po.ldw = C; po.b = p->b_o;
+    po.out = p->out; po.ldo = C;
+    int n = 0;
+    if (p->b_o) bp->out_ops[n++].kind = FLE_BIAS;
+    if (p->residual) { bp->out_ops[n].kind = FLE_RESIDUAL; bp->out_ops[n].p0 = p->residual; bp->out_ops[n].ld = C; ++n; }
+    po.ops = bp->out_ops; po.n_ops = n;
+    po.stream = p->stream;
+
+    if (D != 64 && D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension C / H = %lld is not 64 or 128", (long long)D);
+    if (rows > 0 && (!p->x || !p->w_qkv || !p->w_o || !p->out)) return fail(FLE_ERR_NULL, "x, w_qkv, w_o or out is NULL");
+    fle_status s;
+    if (ws) {
+        s = make_plan(&pj, V_AUTO, 0, &bp->proj_plan);
+        if (s == FLE_OK) s = check_attention(&at);
+        if (s == FLE_OK) s = make_plan(&po, V_AUTO, 0, &bp->out_plan);
+        if (s != FLE_OK) return s;
+        if (rows > 0 && overlaps(p->out, size_t(rows) * size_t(C) * 2, ws, p->workspace_bytes)) return fail(FLE_ERR_UNSUPPORTED, "out overlaps the workspace");
+    } else {
+        // No workspace yet (validation, sizing): the intermediates get a stand-in address that is never
+        // dereferenced; the plans of the two projections do not depend on where qkv and a will live.
+        fle_problem t1 = pj, t2 = po;
+        t1.out = reinterpret_cast<void *>(uintptr_t(256));
+        t2.x = reinterpret_cast<const void *>(uintptr_t(256));
+        s = make_plan(&t1, V_AUTO, 0, &bp->proj_plan);
+        if (s == FLE_OK) s = make_plan(&t2, V_AUTO, 0, &bp->out_plan);
+        if (s != FLE_OK) return s;
+    }
+    const size_t sub = bp->proj_plan.ws_total > bp->out_plan.ws_total ? bp->proj_plan.ws_total : bp->out_plan.ws_total;
+    bp->total = bp->sub_off + round_up(sub, 256);
+    pj.workspace = ws ? ws + bp->sub_off : nullptr; pj.workspace_bytes = round_up(sub, 256);
+    po.workspace = pj.workspace; po.workspace_bytes = pj.workspace_bytes;
+    return FLE_OK;
+}
+
 extern "C" {
 
 fle_status fle_validate(const fle_problem *p) {
@@ -442,6 +542,60 @@ fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g) {
     return s;
 }
 
+fle_status fle_attention_validate(const fle_attention *p) { return check_attention(p); }
+
+fle_status fle_attention_run(const fle_attention *p) {
+    fle_status s = check_attention(p);
+    if (s != FLE_OK || p->B == 0) return s;
+    return launch_attention(p);
+}
+
+fle_status fle_attention_block_validate(const fle_attention_block *p) {
+    BlockParts bp;
+    if (!p) return fail(FLE_ERR_NULL, "attention block is NULL");
+    fle_attention_block t = *p;
+    t.workspace = nullptr;  // validation does not look at the workspace
+    return plan_block(&t, &bp);
+}
+
+fle_status fle_attention_block_workspace_size(const fle_attention_block *p, size_t *bytes_out) {
+    if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
+    if (!p) return fail(FLE_ERR_NULL, "attention block is NULL");
+    BlockParts bp;
+    fle_attention_block t = *p;
+    t.workspace = nullptr;
+    fle_status s = plan_block(&t, &bp);
+    if (s == FLE_OK) *bytes_out = bp.total;
+    return s;
+}
+
+fle_status fle_attention_block_run(const fle_attention_block *p) {
+    BlockParts bp;
+    if (!p) return fail(FLE_ERR_NULL, "attention block is NULL");
+    {
+        fle_attention_block t = *p;
+        t.workspace = nullptr;
+        fle_status s = plan_block(&t, &bp);
+        if (s != FLE_OK) return s;
+    }
+    if (p->B == 0) return FLE_OK;
+    if (!p->workspace) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", bp.total);
+    if (p->workspace_bytes < bp.total) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, bp.total);
+    if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
+    fle_status s = plan_block(p, &bp);
+    if (s != FLE_OK) return s;
+    s = check_workspace(&bp.proj, bp.proj_plan);
+    if (s == FLE_OK) s = check_workspace(&bp.outp, bp.out_plan);
+    if (s == FLE_OK) s = launch(&bp.proj, bp.proj_plan);
+    if (s == FLE_OK) s = launch_attention(&bp.att);
+    if (s == FLE_OK) s = launch(&bp.outp, bp.out_plan);
+    if (s == FLE_OK) {
+        g_plan = bp.out_plan;
+        g_have_plan = true;
+    }
+    return s;
+}
+
 const char *fle_status_string(fle_status s) {
     switch (s) {
     case FLE_OK: return "ok";
@@ -469,6 +623,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 400; }  // 0.4.0: thin kernels (0.3.0: grouped problems)
+int fle_version(void) { return 500; }  // 0.5.0: attention (0.4.0: thin kernels; 0.3.0: grouped problems)
 
 }  // extern "C"

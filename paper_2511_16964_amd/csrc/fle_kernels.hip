@@ -19,6 +19,7 @@
 #include "fle_gemm_general.h"
 #include "fle_gemm_skinny.h"
 #include "fle_gemm_thin.h"
+#include "fle_attention.h"
 #include "fle_gemm_tiled.h"
 #include "fle_rowops.h"
 
@@ -182,6 +183,36 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     else fin = (vec && gb_ok) ? finalize_rows<true, false> : finalize_rows<false, false>;
     hipLaunchKernelGGL(fin, fgrid, dim3(256), 0, stream, f);
     return check_launch("row finalize launch");
+}
+
+template <int DT, int D>
+static void launch_attention_dt(const fle_attention *p, const AttnArgs &a, hipStream_t stream) {
+    // two query tiles per wave (256 queries per workgroup) once that still gives every CU several
+    // workgroups; short sequences and small batches take 128 queries per workgroup
+    const int64_t wg2 = (p->T + 255) / 256 * p->H * p->B;
+    if (p->T > 256 && wg2 >= 512) {
+        hipLaunchKernelGGL((flash_attention<DT, D, 2>), dim3(uint32_t((p->T + 255) / 256), uint32_t(p->H), uint32_t(p->B)), dim3(256), 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128), uint32_t(p->H), uint32_t(p->B)), dim3(256), 0, stream, a);
+    }
+}
+
+fle_status launch_attention(const fle_attention *p) {
+    hipStream_t stream = reinterpret_cast<hipStream_t>(p->stream);
+    AttnArgs a;
+    a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o;
+    a.ldq = p->ldq; a.ldk = p->ldk; a.ldv = p->ldv; a.ldo = p->ldo;
+    a.T = int32_t(p->T); a.H = int32_t(p->H); a.causal = p->causal != 0;
+    const float scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(float(p->D));
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    if (p->dtype == FLE_F16) {
+        if (p->D == 64) launch_attention_dt<FLE_F16, 64>(p, a, stream);
+        else launch_attention_dt<FLE_F16, 128>(p, a, stream);
+    } else {
+        if (p->D == 64) launch_attention_dt<FLE_BF16, 64>(p, a, stream);
+        else launch_attention_dt<FLE_BF16, 128>(p, a, stream);
+    }
+    return check_launch("flash_attention");
 }
 
 }  // namespace fle

@@ -64,4 +64,7 @@ fle_status fail(fle_status s, const char *fmt, ...);
 // Implemented in the kernel translation unit: enqueue the planned kernels.
 fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *groups = nullptr);
 
+// Implemented in the kernel translation unit: enqueue the attention kernel for an already validated problem.
+fle_status launch_attention(const fle_attention *p);
+
 }  // namespace fle

@@ -267,6 +267,62 @@ def make_chain(seed: int = 0, batch: int = 1, width: int = 4096, layers: int = 8
     return MlpChain(_store(x, dtype), ws, bs)
 
 
+@dataclass
+class AttentionProblem:
+    """One self-attention block: CPU tensors in the storage dtype."""
+    name: str
+    dtype: torch.dtype
+    heads: int
+    causal: bool
+    x: torch.Tensor                 # [B, T, C]
+    w_qkv: torch.Tensor             # [3C, C], output columns q | k | v
+    b_qkv: torch.Tensor | None      # [3C]
+    w_o: torch.Tensor               # [C, C]
+    b_o: torch.Tensor | None        # [C]
+    residual: torch.Tensor | None   # [B, T, C]
+
+    @property
+    def flops(self) -> float:
+        """Both projections, and the two products of the attention itself over the keys the mask allows."""
+        B, T, C = self.x.shape
+        pairs = T * (T + 1) / 2 if self.causal else T * T
+        return 2.0 * B * T * C * 3 * C + 4.0 * B * pairs * C + 2.0 * B * T * C * C
+
+
+# name: (dtype, B, T, C, heads, causal) -- a1: a GPT-style causal block, 16 sequences of 2048 tokens
+ATTENTION_SHAPES = {
+    "a1": (torch.bfloat16, 16, 2048, 2048, 16, True),
+}
+
+
+def make_attention(name: str = "a1", seed: int = 0, B: int | None = None, T: int | None = None, C: int | None = None,
+                   heads: int | None = None, causal: bool | None = None, dtype: torch.dtype | None = None,
+                   bias: bool = True, residual: bool = True) -> AttentionProblem:
+    """x ~ N(0,1); W_qkv ~ N(0, 1/sqrt(C)) so that q, k, v are ~N(0,1) and the scores ~N(0,1) after the
+    1/sqrt(D) scale; b_qkv ~ U(+-0.1); W_o ~ N(0, 1/sqrt(C)); b_o ~ U(+-0.1); the residual is x itself
+    (the block's input, as in a pre-norm transformer).  Draw order x, W_qkv, b_qkv, W_o, b_o."""
+    dt0, B0, T0, C0, H0, c0 = ATTENTION_SHAPES[name]
+    dtype = dt0 if dtype is None else dtype
+    B, T, C = (B0 if B is None else B), (T0 if T is None else T), (C0 if C is None else C)
+    heads = H0 if heads is None else heads
+    causal = c0 if causal is None else causal
+    rng = np.random.default_rng(seed)
+    x = _store(_normal(rng, (B, T, C)), dtype)
+    w_qkv = _store(_normal(rng, (3 * C, C), 0.0, 1.0 / math.sqrt(C)), dtype)
+    b_qkv = _store(_uniform(rng, (3 * C,), 0.1), dtype)
+    w_o = _store(_normal(rng, (C, C), 0.0, 1.0 / math.sqrt(C)), dtype)
+    b_o = _store(_uniform(rng, (C,), 0.1), dtype)
+    return AttentionProblem(name, dtype, heads, causal, x, w_qkv, b_qkv if bias else None, w_o, b_o if bias else None,
+                            x if residual else None)
+
+
+def make_qkv(seed: int, B: int, T: int, H: int, D: int, dtype: torch.dtype, spread: float = 1.0):
+    """q, k, v for the attention kernel alone: one [B, T, 3, H, D] tensor ~ N(0, spread) (the layout a
+    fused QKV projection writes); q, k, v are its views [:, :, i]."""
+    rng = np.random.default_rng(seed)
+    return _store(_normal(rng, (B, T, 3, H, D), 0.0, spread), dtype)
+
+
 def to_f64(t):
     """Exact upcast of a stored tensor to a float64 numpy array (None passes through)."""
     return None if t is None else t.detach().cpu().to(torch.float64).numpy()

@@ -405,6 +405,9 @@ def test_attention_invariants():
     cut = 5
     np.testing.assert_allclose(oracle.attention(q, k, v, True)[:, :cut],
                                oracle.attention(q[:, :cut], k[:, :cut], v[:, :cut], True), rtol=0, atol=0)
+    # evaluating only the last queries gives the same rows
+    for causal in (False, True):
+        np.testing.assert_allclose(oracle.attention(q, k, v, causal, first_query=7), oracle.attention(q, k, v, causal)[:, 7:], rtol=0, atol=0)
     # linear in v; outputs are convex combinations of the value rows
     np.testing.assert_allclose(oracle.attention(q, k, 2 * v + 1, False), 2 * base + 1, rtol=0, atol=1e-13)
     assert (base <= v.max(axis=1, keepdims=True) + 1e-14).all() and (base >= v.min(axis=1, keepdims=True) - 1e-14).all()

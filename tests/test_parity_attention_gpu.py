@@ -1,0 +1,120 @@
+"""GPU parity of the attention kernel and of the three-launch attention block against the CPU oracle
+(scaled dot-product attention written out in float64).  Floating point within 2e-2 (bf16) / 4e-3 (fp16)
+of the oracle, the same criterion as the fused linear operator."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_16964_amd import binding, inputs
+
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+
+BF16, F16 = torch.bfloat16, torch.float16
+DEV = "cuda:0"
+
+
+def announce(*a):
+    print("[case]", *a, flush=True)
+
+
+def run_attention(qkv, causal, scale=None):
+    d = qkv.to(DEV)
+    out = binding.attention(d[:, :, 0], d[:, :, 1], d[:, :, 2], causal, scale)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+def oracle_attention(qkv, causal, scale=None, first_query=0):
+    f = inputs.to_f64(qkv)
+    return oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, scale, first_query=first_query)
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("T", [1, 2, 31, 64, 65, 128, 129, 200, 257, 333])
+def test_attention_small(dtype, D, causal, T):
+    """One to three workgroups per head along the queries, ragged key blocks, several heads and batches."""
+    announce("attention small", dtype, D, causal, T)
+    qkv = inputs.make_qkv(100 + T, 2, T, 3, D, dtype)
+    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, "T=%d" % T)
+
+
+@pytest.mark.parametrize("dtype,D,causal,B,H,T", [
+    (BF16, 128, True, 8, 32, 300),    # 256 queries per workgroup (two query tiles per wave), ragged second workgroup
+    (BF16, 64, False, 4, 64, 520),
+    (F16, 128, False, 16, 16, 513),
+    (F16, 64, True, 2, 128, 777),
+])
+def test_attention_two_query_tiles_per_wave(dtype, D, causal, B, H, T):
+    announce("attention wide", dtype, D, causal, B, H, T)
+    qkv = inputs.make_qkv(7, B, T, H, D, dtype)
+    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype)
+
+
+def test_attention_peaked_and_flat_scores():
+    """Score spreads far from the N(0,1) of the workload: nearly one-hot rows (large scale) and nearly
+    uniform rows (tiny scale); the running maximum must keep both finite."""
+    for spread, scale in ((4.0, None), (1.0, 1e-3), (1.0, 2.0)):
+        announce("attention spread", spread, scale)
+        qkv = inputs.make_qkv(11, 2, 190, 2, 64, BF16, spread)
+        got = run_attention(qkv, True, scale)
+        assert torch.isfinite(got.float()).all()
+        assert_close(got, oracle_attention(qkv, True, scale), BF16)
+
+
+def test_attention_separate_tensors_and_out():
+    """q, k, v as three separate packed tensors, result written into a strided view."""
+    announce("attention separate operands")
+    B, T, H, D = 2, 150, 2, 128
+    qkv = inputs.make_qkv(3, B, T, H, D, BF16)
+    q, k, v = (qkv[:, :, i].contiguous().to(DEV) for i in range(3))
+    buf = torch.zeros(B, T, 2, H, D, device=DEV, dtype=BF16)
+    binding.attention(q, k, v, False, out=buf[:, :, 1])
+    torch.cuda.synchronize()
+    assert_close(buf[:, :, 1].cpu(), oracle_attention(qkv, False), BF16)
+    assert (buf[:, :, 0] == 0).all()
+
+
+def test_attention_rejects_what_it_cannot_run():
+    qkv = inputs.make_qkv(1, 1, 8, 1, 64, BF16).to(DEV)
+    q, k, v = qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2]
+    with pytest.raises(binding.FleError):
+        binding.attention(q.float(), k.float(), v.float(), False)          # fp32
+    bad = inputs.make_qkv(1, 1, 8, 1, 32, BF16).to(DEV)
+    with pytest.raises(binding.FleError):
+        binding.attention(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], False)  # head dimension 32
+    with pytest.raises(binding.FleError):
+        binding.attention(q, k, v, False, scale=-1.0)
+    with pytest.raises(binding.FleError):
+        binding.attention(q, k, v, False, out=q)                           # o overlaps q
+
+
+def run_block(ap):
+    d = lambda t: None if t is None else t.to(DEV)
+    x = d(ap.x)
+    out = binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal,
+                                  residual=x if ap.residual is not None else None)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+def oracle_block(ap):
+    f = inputs.to_f64
+    return oracle.attention_block(f(ap.x), f(ap.w_qkv), f(ap.b_qkv), f(ap.w_o), f(ap.b_o), ap.heads, ap.causal,
+                                  residual=f(ap.residual))
+
+
+@pytest.mark.parametrize("dtype,B,T,C,heads,causal,bias,residual", [
+    (BF16, 2, 200, 256, 2, True, True, True),
+    (BF16, 3, 77, 512, 8, False, True, False),
+    (F16, 2, 130, 384, 3, True, False, True),
+    (BF16, 1, 1, 128, 2, True, True, True),
+])
+def test_attention_block_small(dtype, B, T, C, heads, causal, bias, residual):
+    announce("attention block", dtype, B, T, C, heads, causal, bias, residual)
+    ap = inputs.make_attention("a1", 5, B=B, T=T, C=C, heads=heads, causal=causal, dtype=dtype, bias=bias, residual=residual)
+    assert_close(run_block(ap), oracle_block(ap), dtype)
