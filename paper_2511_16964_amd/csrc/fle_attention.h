@@ -10,9 +10,18 @@ struct AttnArgs {
     const void *q, *k, *v;
     void *o;
     int64_t ldq, ldk, ldv, ldo;  // elements between consecutive tokens
-    int32_t T, H;
+    int32_t T, H, B;
     int32_t causal;
     float scale_log2e;  // softmax scale times log2(e): the exponentials are taken in base 2
+};
+
+// The K and V of one sequence and head as buffer resources, and the copy of 1 KB of each into LDS.
+struct BufferPair {
+    __amdgpu_buffer_rsrc_t k, v;
+    __device__ __forceinline__ void copy_1k(char *dst_k, char *dst_v, uint32_t off_k, uint32_t off_v) const {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(k, (lds_void *)dst_k, 16, off_k, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(v, (lds_void *)dst_v, 16, off_v, 0, 0, 0);
+    }
 };
 
 // Everything is computed transposed, so that a lane owns one query:
@@ -33,8 +42,8 @@ struct AttnArgs {
 //
 // A workgroup is 4 waves; a wave owns QT tiles of 32 queries (QT = 2 halves the LDS reads per MFMA, which
 // is what bounds QT = 1) and walks the key blocks of 64 that all four waves share through LDS, double
-// buffered: the next block travels global -> registers while the current one is used, and is written to
-// the other stage before the one barrier of the iteration.  Rows of K / V are stored with their 16-byte
+// buffered: the next block is copied into the other stage (buffer loads that write LDS directly) while the
+// current one is used; one barrier per iteration.  Rows of K / V are stored with their 16-byte
 // chunks XOR-ed by (row & 7), which spreads both the row-wise reads of K and the transposing reads of V
 // over all banks.  With the causal mask a wave stops computing at its last visible block and only keeps
 // the barriers; the mask itself is applied on the diagonal and tail blocks only.
@@ -45,7 +54,6 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
     using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
     constexpr int BKV = 64, WQ = 32 * QT, BQ = 4 * WQ;
     constexpr int NC = D / 16, ND = D / 32, RB = D * 2, CPR = D / 8;
-    constexpr int NLD = BKV * CPR / 256;  // 16-byte chunks per thread and operand per block
     constexpr int STAGE = 2 * BKV * RB;
     __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
 
@@ -53,10 +61,19 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
     const int l31 = lane & 31, h2 = lane >> 5;
     const int T = a.T;
     const int n_qb = (T + BQ - 1) / BQ;
-    const int qb = a.causal ? n_qb - 1 - int(blockIdx.x) : int(blockIdx.x);  // longest rows first
+    // Workgroup -> (sequence and head, query block).  Consecutive workgroups go to the 8 XCDs in turn, so
+    // workgroup L is the (L / 8)-th one of XCD L % 8.  An XCD takes consecutive heads whole (every query block
+    // of a head reads the same K and V, which then stay in that XCD's L2) and, under the causal mask, each
+    // head's blocks from the longest to the shortest; handing out query blocks in plain order instead gives
+    // XCD j block j of every head, i.e. all the long blocks to one XCD and all the short ones to another.
+    const uint32_t n_items = uint32_t(a.H) * uint32_t(a.B) * uint32_t(n_qb);
+    const uint32_t per = n_items / 8, rem = n_items % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const uint32_t item = slot + xcd * per + (xcd < rem ? xcd : rem);  // XCD j owns a contiguous range of items
+    const int head = int(item / uint32_t(n_qb)), qi = int(item % uint32_t(n_qb));
+    const int qb = a.causal ? n_qb - 1 - qi : qi;
     const int q0 = qb * BQ, wq0 = q0 + wave * WQ;
-    const int64_t tok0 = int64_t(blockIdx.z) * T;
-    const int64_t col0 = int64_t(blockIdx.y) * D;
+    const int64_t tok0 = int64_t(head / a.H) * T;
+    const int64_t col0 = int64_t(head % a.H) * D;
     const char *qp = reinterpret_cast<const char *>(a.q) + (tok0 * a.ldq + col0) * 2;
     const char *kp = reinterpret_cast<const char *>(a.k) + (tok0 * a.ldk + col0) * 2;
     const char *vp = reinterpret_cast<const char *>(a.v) + (tok0 * a.ldv + col0) * 2;
@@ -73,14 +90,13 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
 
     // Q fragments stay in registers: B operand, lane = query, 8 consecutive d per 16-wide step
     frag_t qf[QT][NC];
+    {
+        const __amdgpu_buffer_rsrc_t rsrc_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(qp), 0, uint32_t(int64_t(T - 1) * a.ldq * 2 + RB), 0x00020000);
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-        const int row = wq0 + 32 * qt + l31;
+        for (int qt = 0; qt < QT; ++qt) {
+            const uint32_t off = uint32_t(wq0 + 32 * qt + l31) * uint32_t(a.ldq * 2) + uint32_t(16 * h2);  // rows at or beyond T read as zeros
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (row < T) raw = *reinterpret_cast<const u32x4 *>(qp + int64_t(row) * a.ldq * 2 + (16 * c + 8 * h2) * 2);
-            qf[qt][c] = __builtin_bit_cast(frag_t, raw);
+            for (int c = 0; c < NC; ++c) qf[qt][c] = __builtin_bit_cast(frag_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_q, off + 32 * c, 0, 0));
         }
     }
 
@@ -96,27 +112,28 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
             for (int r = 0; r < 16; ++r) oacc[dt][qt][r] = 0.0f;
     }
 
-    // global -> registers -> LDS copies of one K / V block
-    u32x4 kreg[NLD], vreg[NLD];
-    auto fetch = [&](int kb0) {
+    // Copies of one K / V block, global memory -> LDS without passing registers: one instruction moves
+    // 1 KB (RPI rows) to consecutive LDS addresses, so the XOR placement is applied on the source side: the
+    // lane that fills chunk position `pos` of a row fetches that row's chunk pos ^ (row & 7).  Rows at or
+    // beyond T lie outside the buffer range and arrive as zeros.
+    constexpr int RPI = 1024 / RB, NI = BKV / RPI / 4;  // rows per instruction; instructions per wave and operand
+    const uint32_t nrec_k = uint32_t(int64_t(T - 1) * a.ldk * 2 + RB), nrec_v = uint32_t(int64_t(T - 1) * a.ldv * 2 + RB);
+    BufferPair kv;
+    kv.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(kp), 0, nrec_k, 0x00020000);
+    kv.v = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(vp), 0, nrec_v, 0x00020000);
+    uint32_t cp_k[NI], cp_v[NI];  // this lane's source offsets inside a block
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int idx = i * 256 + tid, row = idx / CPR, ch = idx % CPR;
-            kreg[i] = u32x4{0u, 0u, 0u, 0u};
-            vreg[i] = u32x4{0u, 0u, 0u, 0u};
-            if (kb0 + row < T) {
-                kreg[i] = *reinterpret_cast<const u32x4 *>(kp + int64_t(kb0 + row) * a.ldk * 2 + ch * 16);
-                vreg[i] = *reinterpret_cast<const u32x4 *>(vp + int64_t(kb0 + row) * a.ldv * 2 + ch * 16);
-            }
-        }
-    };
-    auto stash = [&](char *stage) {
+    for (int i = 0; i < NI; ++i) {
+        const int row = (wave * NI + i) * RPI + lane / CPR, pos = lane % CPR;
+        cp_k[i] = uint32_t(row) * uint32_t(a.ldk * 2) + uint32_t((pos ^ (row & 7)) * 16);
+        cp_v[i] = uint32_t(row) * uint32_t(a.ldv * 2) + uint32_t((pos ^ (row & 7)) * 16);
+    }
+    auto copy_block = [&](char *stage, int kb0) {
+        const uint32_t k0 = uint32_t(kb0) * uint32_t(a.ldk * 2), v0 = uint32_t(kb0) * uint32_t(a.ldv * 2);
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int idx = i * 256 + tid, row = idx / CPR, ch = idx % CPR;
-            const int off = row * RB + ((ch ^ (row & 7)) * 16);
-            *reinterpret_cast<u32x4 *>(stage + off) = kreg[i];
-            *reinterpret_cast<u32x4 *>(stage + BKV * RB + off) = vreg[i];
+        for (int i = 0; i < NI; ++i) {
+            char *dst = stage + (wave * NI + i) * 1024;
+            kv.copy_1k(dst, dst + BKV * RB, cp_k[i] + k0, cp_v[i] + v0);
         }
     };
 
@@ -126,76 +143,74 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
     const int vj = lane & 15, vg = lane >> 4;
     const int v_key = (vj >> 2) + 4 * (vg >> 1), v_d = 16 * (vg & 1) + 4 * (vj & 3);
 
-    auto compute = [&](const char *stage, int kb0, auto mask_c) {
-        constexpr bool MASK = decltype(mask_c)::value;
+    // One block of 64 keys as two sub-blocks of 32: scores, running-softmax update, second product.
+    auto compute = [&](const char *stage, int kb0, bool mask) {
         const char *sK = stage, *sV = stage + BKV * RB;
-        f32x16 s[2][QT];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt) {
+            f32x16 s[QT];
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[kt][qt][r] = 0.0f;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+                for (int r = 0; r < 16; ++r) s[qt][r] = 0.0f;
             const int row = 32 * kt + l31;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 const frag_t kf = *reinterpret_cast<const frag_t *>(sK + row * RB + (((2 * c + h2) ^ (row & 7)) * 16));
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt) {
-                    if constexpr (DT == FLE_F16) s[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qt][c], s[kt][qt], 0, 0, 0);
-                    else s[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][c], s[kt][qt], 0, 0, 0);
+                    if constexpr (DT == FLE_F16) s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qt][c], s[qt], 0, 0, 0);
+                    else s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][c], s[qt], 0, 0, 0);
                 }
             }
-        }
-        frag_t pf[QT][2][2];
+            frag_t pf[QT][2];
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt) {
-            if constexpr (MASK) {
-                const int query = wq0 + 32 * qt + l31;
-#pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
+            for (int qt = 0; qt < QT; ++qt) {
+                if (mask) {  // diagonal and tail blocks only (uniform over the wave)
+                    const int query = wq0 + 32 * qt + l31;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = kb0 + 32 * kt + 8 * (r / 4) + 4 * h2 + (r % 4);
-                        if (key >= T || (a.causal && key > query)) s[kt][qt][r] = -INFINITY;
+                        if (key >= T || (a.causal && key > query)) s[qt][r] = -INFINITY;
                     }
-            }
-            float mx = s[0][qt][0];
+                }
+                float mx = s[qt][0];
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[qt][r]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // The reference point of the exponentials only moves when some row's maximum has grown by more
+                // than 2^8 past it (always in the first sub-block): the probabilities of a row then reach at most
+                // 256 instead of 1, a common factor that the final division by the row sum removes, and in most
+                // sub-blocks no lane of the wave has to rescale its accumulators.
+                const float cand = mx * a.scale_log2e;
+                const bool grow = cand > m_run[qt] + 8.0f;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                    const float m_new = grow ? cand : m_run[qt];
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+                    m_run[qt] = m_new;
+                    l_run[qt] *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][qt][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[qt], mx * a.scale_log2e);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-            m_run[qt] = m_new;
-            float ps = 0.0f;
+                    for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
+                        for (int r = 0; r < 16; ++r) oacc[dt][qt][r] *= alpha;
+                }
+                const float m_ref = m_run[qt];
+                float ps = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][qt][r], a.scale_log2e, -m_new));
-                    s[kt][qt][r] = p;
-                    ps += p;
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][r], a.scale_log2e, -m_ref));
+                    s[qt][r] = pr;
+                    ps += pr;
                 }
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2) {
-                    const u32x2 lo = pack4<DT>(f32x4{s[kt][qt][8 * c2 + 0], s[kt][qt][8 * c2 + 1], s[kt][qt][8 * c2 + 2], s[kt][qt][8 * c2 + 3]});
-                    const u32x2 hi = pack4<DT>(f32x4{s[kt][qt][8 * c2 + 4], s[kt][qt][8 * c2 + 5], s[kt][qt][8 * c2 + 6], s[kt][qt][8 * c2 + 7]});
-                    pf[qt][kt][c2] = __builtin_bit_cast(frag_t, u32x4{lo[0], lo[1], hi[0], hi[1]});
+                    const u32x2 lo = pack4<DT>(f32x4{s[qt][8 * c2 + 0], s[qt][8 * c2 + 1], s[qt][8 * c2 + 2], s[qt][8 * c2 + 3]});
+                    const u32x2 hi = pack4<DT>(f32x4{s[qt][8 * c2 + 4], s[qt][8 * c2 + 5], s[qt][8 * c2 + 6], s[qt][8 * c2 + 7]});
+                    pf[qt][c2] = __builtin_bit_cast(frag_t, u32x4{lo[0], lo[1], hi[0], hi[1]});
                 }
+                ps += __shfl_xor(ps, 32);
+                l_run[qt] += ps;
             }
-            ps += __shfl_xor(ps, 32);
-            l_run[qt] = l_run[qt] * alpha + ps;
-#pragma unroll
-            for (int dt = 0; dt < ND; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][qt][r] *= alpha;
-        }
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
@@ -210,25 +225,24 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
                     const frag_t vf = __builtin_bit_cast(frag_t, part);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
-                        if constexpr (DT == FLE_F16) oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[qt][kt][c2], oacc[dt][qt], 0, 0, 0);
-                        else oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][kt][c2], oacc[dt][qt], 0, 0, 0);
+                        if constexpr (DT == FLE_F16) oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[qt][c2], oacc[dt][qt], 0, 0, 0);
+                        else oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][c2], oacc[dt][qt], 0, 0, 0);
                     }
                 }
+        }
     };
 
-    fetch(0);
-    stash(smem);
+    copy_block(smem, 0);
+    wait_vmcnt<0>();
     __syncthreads();
     for (int j = 0; j < n_blocks; ++j) {
         const int kb0 = j * BKV;
-        const bool more = j + 1 < n_blocks;
-        if (more) fetch(kb0 + BKV);
+        // the other stage was last read before the barrier that ended the previous iteration
+        if (j + 1 < n_blocks) copy_block(smem + ((j + 1) & 1) * STAGE, kb0 + BKV);
         if (j <= wave_last) {
-            const bool mask = kb0 + BKV > T || (a.causal && kb0 + BKV - 1 > wq0);
-            if (mask) compute(smem + (j & 1) * STAGE, kb0, std::true_type{});
-            else compute(smem + (j & 1) * STAGE, kb0, std::false_type{});
+            compute(smem + (j & 1) * STAGE, kb0, kb0 + BKV > T || (a.causal && kb0 + BKV - 1 > wq0));
         }
-        if (more) stash(smem + ((j + 1) & 1) * STAGE);
+        wait_vmcnt<0>();
         __syncthreads();
     }
 

@@ -383,10 +383,17 @@ static fle_status check_attention(const fle_attention *p) {
     if (p->D != 64 && p->D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 64 or 128", (long long)p->D);
     if (p->B > 65535 || p->H > 65535) return fail(FLE_ERR_SHAPE, "B and H are limited to 65535");
     if (p->T > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T is limited to 2^24");
+    if ((p->T + 127) / 128 * p->H * p->B >= (int64_t(1) << 31)) return fail(FLE_ERR_SHAPE, "B * H * T / 128 is limited to 2^31 workgroups");
     const int64_t HD = p->H * p->D;
     const int64_t kLimit = int64_t(1) << 40;
     if (p->ldq < HD || p->ldk < HD || p->ldv < HD || p->ldo < HD) return fail(FLE_ERR_SHAPE, "a token stride is smaller than H*D = %lld", (long long)HD);
     if (p->ldq > kLimit || p->ldk > kLimit || p->ldv > kLimit || p->ldo > kLimit) return fail(FLE_ERR_SHAPE, "token stride too large");
+    // the kernel addresses the Q, K and V of one sequence with 32-bit byte offsets
+    {
+        int64_t ldmax = p->ldq > p->ldk ? p->ldq : p->ldk;
+        if (p->ldv > ldmax) ldmax = p->ldv;
+        if ((p->T + 256) * ldmax * 2 >= (int64_t(1) << 31)) return fail(FLE_ERR_SHAPE, "one sequence's Q, K or V spans 2 GiB or more");
+    }
     if (!(p->scale >= 0.0f) || std::isinf(p->scale)) return fail(FLE_ERR_OP, "scale must be finite and > 0 (or 0 for 1/sqrt(D))");
     if (p->B == 0) return FLE_OK;
     if (!p->q || !p->k || !p->v || !p->o) return fail(FLE_ERR_NULL, "q, k, v or o is NULL");

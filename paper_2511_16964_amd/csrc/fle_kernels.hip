@@ -191,9 +191,9 @@ static void launch_attention_dt(const fle_attention *p, const AttnArgs &a, hipSt
     // workgroups; short sequences and small batches take 128 queries per workgroup
     const int64_t wg2 = (p->T + 255) / 256 * p->H * p->B;
     if (p->T > 256 && wg2 >= 512) {
-        hipLaunchKernelGGL((flash_attention<DT, D, 2>), dim3(uint32_t((p->T + 255) / 256), uint32_t(p->H), uint32_t(p->B)), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((flash_attention<DT, D, 2>), dim3(uint32_t((p->T + 255) / 256 * p->H * p->B)), dim3(256), 0, stream, a);
     } else {
-        hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128), uint32_t(p->H), uint32_t(p->B)), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128 * p->H * p->B)), dim3(256), 0, stream, a);
     }
 }
 
@@ -202,7 +202,7 @@ fle_status launch_attention(const fle_attention *p) {
     AttnArgs a;
     a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o;
     a.ldq = p->ldq; a.ldk = p->ldk; a.ldv = p->ldv; a.ldo = p->ldo;
-    a.T = int32_t(p->T); a.H = int32_t(p->H); a.causal = p->causal != 0;
+    a.T = int32_t(p->T); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal != 0;
     const float scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(float(p->D));
     a.scale_log2e = scale * 1.44269504088896340736f;
     if (p->dtype == FLE_F16) {
