@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "a1": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -187,12 +187,35 @@ def cpu_baseline_chain(ch, inputs, budget_s=12.0):
             "sample": "the whole chain (%d layers, batch %d), %d passes, %.1f s" % (len(ch.ws), ch.x.shape[0], reps, t)}
 
 
+def cpu_baseline_attention(apb, inputs, budget_s=12.0):
+    """The oracle's attention block on the first tokens of the first sequence (a causal block needs nothing after them)."""
+    import oracle
+    f64 = inputs.to_f64
+    B, T, C = apb.x.shape
+    def run(n_seq, n_tok):
+        x = f64(apb.x[:n_seq, :n_tok])
+        t0 = time.perf_counter()
+        oracle.attention_block(x, f64(apb.w_qkv), f64(apb.b_qkv), f64(apb.w_o), f64(apb.b_o), apb.heads, apb.causal, residual=x)
+        return time.perf_counter() - t0
+    probe = min(T, 64)
+    t = run(1, probe)
+    n = int(max(probe, min(T, probe * budget_s / max(t, 1e-9))))
+    t = run(1, n)
+    seqs = int(max(1, min(B, budget_s / max(t, 1e-9)))) if n == T else 1
+    if seqs > 1:
+        t = run(seqs, n)
+    pairs = n * (n + 1) / 2 if apb.causal else n * n
+    flops = seqs * (2.0 * n * C * 3 * C + 4.0 * pairs * C + 2.0 * n * C * C)
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "the first %d of %d tokens of %d of %d sequences, whole block, %.1f s" % (n, T, seqs, B, t)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "a1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -261,6 +284,24 @@ def main():
                 h = F.relu(F.linear(h, w, b))
             return h
         alg_bytes = sum(4 * (w.numel() + b.numel()) for w, b in zip(ch.ws, ch.bs)) + 4 * 2 * len(ch.ws) * ch.x.numel()
+    elif args.workload == "a1":
+        # a causal self-attention block: QKV projection, attention, output projection + bias + residual (three launches)
+        apb = inputs.make_attention("a1")
+        B, T, C = apb.x.shape
+        H, D = apb.heads, C // apb.heads
+        xg, wqkv, bqkv, wo, bo = to(apb.x), to(apb.w_qkv), to(apb.b_qkv), to(apb.w_o), to(apb.b_o)
+        calls = [binding.AttentionBlockCall(xg, wqkv, bqkv, wo, bo, H, apb.causal, residual=xg)]
+        probs = [apb]
+        flops = apb.flops
+        desc = "a1: %s self-attention block (qkv projection + attention + output projection + bias + residual), bf16, B=%d T=%d C=%d heads=%d" % (
+            "causal" if apb.causal else "full", B, T, C, H)
+        def eager():
+            qkv = F.linear(xg, wqkv, bqkv)
+            q, k, v = (t.view(B, T, H, D).transpose(1, 2) for t in qkv.split(C, dim=2))
+            o = F.scaled_dot_product_attention(q, k, v, is_causal=apb.causal)
+            return F.linear(o.transpose(1, 2).reshape(B, T, C), wo, bo) + xg
+        # x, both weight matrices and biases, the residual, out; qkv and the attention output written and read once
+        alg_bytes = 2 * (3 * B * T * C + 4 * C * C + 4 * C + 2 * (3 * B * T * C + B * T * C))
     elif args.workload == "c5":
         blk = inputs.make_mlp()
         p1 = blk.call1()
@@ -301,15 +342,23 @@ def main():
     plans = [c.plan() for c in calls]
     import oracle
     prob0 = probs[0]
-    rows = sorted(set([0, prob0.M - 1] + [int(r) for r in np.random.default_rng(1).integers(0, prob0.M, 6)]))
-    if grouped:
-        owner = np.searchsorted(np.asarray(gp.offsets[1:]), np.asarray(rows), side="right")
-        ref = np.concatenate([oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(gp.b[g]),
-                                                           inputs.epilogue_f64(gp.epilogue, [m])) for m, g in zip(rows, owner)])
+    if args.workload == "a1":
+        # the first tokens of the first sequence: under the causal mask they depend on nothing after them
+        n_tok = 131
+        f64 = inputs.to_f64
+        ref = oracle.attention_block(f64(apb.x[:1, :n_tok]), f64(apb.w_qkv), f64(apb.b_qkv), f64(apb.w_o), f64(apb.b_o), apb.heads,
+                                     apb.causal, residual=f64(apb.x[:1, :n_tok]))[0]
+        got = calls[0].out[0, :n_tok].cpu().to(torch.float64).numpy()
     else:
-        ref = oracle.fused_linear_epilogue(inputs.to_f64(prob0.x[rows]), inputs.to_f64(prob0.w), inputs.to_f64(prob0.b),
-                                           inputs.epilogue_f64(prob0.epilogue, rows))
-    got = calls[0].out[rows].cpu().to(torch.float64).numpy()
+        rows = sorted(set([0, prob0.M - 1] + [int(r) for r in np.random.default_rng(1).integers(0, prob0.M, 6)]))
+        if grouped:
+            owner = np.searchsorted(np.asarray(gp.offsets[1:]), np.asarray(rows), side="right")
+            ref = np.concatenate([oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(gp.b[g]),
+                                                               inputs.epilogue_f64(gp.epilogue, [m])) for m, g in zip(rows, owner)])
+        else:
+            ref = oracle.fused_linear_epilogue(inputs.to_f64(prob0.x[rows]), inputs.to_f64(prob0.w), inputs.to_f64(prob0.b),
+                                               inputs.epilogue_f64(prob0.epilogue, rows))
+        got = calls[0].out[rows].cpu().to(torch.float64).numpy()
     tol = 2e-2 if prob0.dtype == torch.bfloat16 else 1e-4
     s = min(1.0, float(np.sqrt(np.mean(ref * ref))))
     if not np.all(np.abs(got - ref) <= tol * (s + np.abs(ref))):
@@ -355,7 +404,7 @@ def main():
                     c.run()
             lwall, _ = time_loop(torch, loop_step, max(10, args.steps // 4), 5)
             out["loop_of_plain_fused_calls"] = {"ms_per_step": lwall, "calls": len(loop_calls), "speedup_grouped_vs_loop": lwall / wall_ms}
-        else:
+        elif args.workload != "a1":
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
@@ -363,6 +412,8 @@ def main():
             out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs)
         elif args.workload == "m1":
             out["cpu_baseline"] = cpu_baseline_chain(ch, inputs)
+        elif args.workload == "a1":
+            out["cpu_baseline"] = cpu_baseline_attention(apb, inputs)
         else:
             out["cpu_baseline"] = cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
     if args.calibrate_copy:

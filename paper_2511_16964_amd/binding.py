@@ -369,6 +369,12 @@ class AttentionBlockCall:
             _check(status)
         return self.out
 
+    def plan(self) -> str:
+        """Plan text of the block's output projection (the last stage enqueued)."""
+        buf = ctypes.create_string_buffer(256)
+        lib().fle_last_plan(buf, 256)
+        return buf.value.decode()
+
 
 def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual=None, out=None, workspace=None):
     """out = (attention over `heads` heads of (x w_qkv^T + b_qkv)) w_o^T + b_o (+ residual), three fused launches.

@@ -6,6 +6,10 @@ namespace fle {
 
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 
+#ifndef FLE_ATTN_HEAD_GROUP
+#define FLE_ATTN_HEAD_GROUP 8u  // heads an XCD works on at a time (see the workgroup mapping)
+#endif
+
 struct AttnArgs {
     const void *q, *k, *v;
     void *o;
@@ -40,8 +44,8 @@ struct BufferPair {
 // receives d = i of those four keys.  A sum over keys does not care about their order, only that both
 // operands agree on it.
 //
-// A workgroup is 4 waves; a wave owns QT tiles of 32 queries (QT = 2 halves the LDS reads per MFMA, which
-// is what bounds QT = 1) and walks the key blocks of 64 that all four waves share through LDS, double
+// A workgroup is 4 waves; a wave owns QT tiles of 32 queries (the library launches QT = 1, which keeps two
+// or three waves on a SIMD) and walks the key blocks of 64 that all four waves share through LDS, double
 // buffered: the next block is copied into the other stage (buffer loads that write LDS directly) while the
 // current one is used; one barrier per iteration.  Rows of K / V are stored with their 16-byte
 // chunks XOR-ed by (row & 7), which spreads both the row-wise reads of K and the transposing reads of V
@@ -66,10 +70,22 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
     // of a head reads the same K and V, which then stay in that XCD's L2) and, under the causal mask, each
     // head's blocks from the longest to the shortest; handing out query blocks in plain order instead gives
     // XCD j block j of every head, i.e. all the long blocks to one XCD and all the short ones to another.
-    const uint32_t n_items = uint32_t(a.H) * uint32_t(a.B) * uint32_t(n_qb);
-    const uint32_t per = n_items / 8, rem = n_items % 8, xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const uint32_t item = slot + xcd * per + (xcd < rem ? xcd : rem);  // XCD j owns a contiguous range of items
-    const int head = int(item / uint32_t(n_qb)), qi = int(item % uint32_t(n_qb));
+    const uint32_t n_heads = uint32_t(a.H) * uint32_t(a.B), xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    int head, qi;
+    if (n_heads % 8 == 0) {
+        // heads xcd * hpx .. + hpx - 1, in groups of FLE_ATTN_HEAD_GROUP heads that are worked on together
+        // (their K and V share the L2), each group block-major: all its longest query blocks first
+        const uint32_t hpx = n_heads / 8, gsz = FLE_ATTN_HEAD_GROUP * uint32_t(n_qb);
+        const uint32_t g = slot / gsz, u = slot - g * gsz;
+        const uint32_t left = hpx - g * FLE_ATTN_HEAD_GROUP, gh = left < FLE_ATTN_HEAD_GROUP ? left : FLE_ATTN_HEAD_GROUP;
+        qi = int(u / gh);
+        head = int(xcd * hpx + g * FLE_ATTN_HEAD_GROUP + u % gh);
+    } else {
+        const uint32_t n_items = n_heads * uint32_t(n_qb), per = n_items / 8, rem = n_items % 8;
+        const uint32_t item = slot + xcd * per + (xcd < rem ? xcd : rem);  // XCD j owns a contiguous range of items
+        head = int(item / uint32_t(n_qb));
+        qi = int(item % uint32_t(n_qb));
+    }
     const int qb = a.causal ? n_qb - 1 - qi : qi;
     const int q0 = qb * BQ, wq0 = q0 + wave * WQ;
     const int64_t tok0 = int64_t(head / a.H) * T;

@@ -187,14 +187,10 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
 
 template <int DT, int D>
 static void launch_attention_dt(const fle_attention *p, const AttnArgs &a, hipStream_t stream) {
-    // two query tiles per wave (256 queries per workgroup) once that still gives every CU several
-    // workgroups; short sequences and small batches take 128 queries per workgroup
-    const int64_t wg2 = (p->T + 255) / 256 * p->H * p->B;
-    if (p->T > 256 && wg2 >= 512) {
-        hipLaunchKernelGGL((flash_attention<DT, D, 2>), dim3(uint32_t((p->T + 255) / 256 * p->H * p->B)), dim3(256), 0, stream, a);
-    } else {
-        hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128 * p->H * p->B)), dim3(256), 0, stream, a);
-    }
+    // One query tile per wave, 128 queries per workgroup: two (D = 128) or three (D = 64) waves per SIMD, so
+    // that one wave's softmax arithmetic runs under another's MFMAs.  Two tiles per wave halve the LDS reads
+    // per MFMA but leave one wave per SIMD at D = 128, and measured 10 - 35 % slower there (equal at D = 64).
+    hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128 * p->H * p->B)), dim3(256), 0, stream, a);
 }
 
 fle_status launch_attention(const fle_attention *p) {

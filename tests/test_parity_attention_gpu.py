@@ -44,12 +44,15 @@ def test_attention_small(dtype, D, causal, T):
 
 
 @pytest.mark.parametrize("dtype,D,causal,B,H,T", [
-    (BF16, 128, True, 8, 32, 300),    # 256 queries per workgroup (two query tiles per wave), ragged second workgroup
+    (BF16, 128, True, 8, 32, 300),    # hundreds of heads: several rounds of workgroups per XCD, ragged last query block
     (BF16, 64, False, 4, 64, 520),
     (F16, 128, False, 16, 16, 513),
     (F16, 64, True, 2, 128, 777),
+    (BF16, 64, True, 3, 7, 400),      # a head count that is not a multiple of 8 (plain work order)
+    (BF16, 128, True, 1, 24, 1100),   # 3 heads per XCD, fewer than a head group
+    (BF16, 64, False, 5, 16, 260),    # 10 heads per XCD: a full group of 8 and a rest of 2
 ])
-def test_attention_two_query_tiles_per_wave(dtype, D, causal, B, H, T):
+def test_attention_many_heads(dtype, D, causal, B, H, T):
     announce("attention wide", dtype, D, causal, B, H, T)
     qkv = inputs.make_qkv(7, B, T, H, D, dtype)
     assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype)

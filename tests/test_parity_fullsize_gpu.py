@@ -111,3 +111,36 @@ def test_m1_perceptron_chain_every_layer():
         h_gpu = out
     err = assert_close(h_gpu, h_ref, F32, "m1 end to end")
     print("m1 end-to-end max|err| %.3e" % err)
+
+
+def test_a1_attention_block_fullsize_sampled_tokens():
+    """The attention block at the benchmark's size (16 x 2048 tokens, 2048 wide, 16 heads, causal), as bench.py
+    launches it.  Checked: the first 200 tokens of two sequences in full (a causal block needs nothing after
+    them), and late tokens of one sequence and head through the attention kernel alone (the oracle evaluates
+    only the sampled queries, against all their keys)."""
+    import oracle
+    from paper_2511_16964_amd import binding
+    announce("a1 full size")
+    ap = inputs.make_attention("a1")
+    B, T, C = ap.x.shape
+    H, D = ap.heads, C // ap.heads
+    d = lambda t: t.to("cuda:0")
+    xg = d(ap.x)
+    call = binding.AttentionBlockCall(xg, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), H, ap.causal, residual=xg)
+    out = call.run()
+    torch.cuda.synchronize()
+    f64 = inputs.to_f64
+    n_tok = 200
+    for b in (0, B - 1):
+        x = f64(ap.x[b:b + 1, :n_tok])
+        ref = oracle.attention_block(x, f64(ap.w_qkv), f64(ap.b_qkv), f64(ap.w_o), f64(ap.b_o), H, ap.causal, residual=x)
+        assert_close(out[b:b + 1, :n_tok].cpu(), ref, ap.dtype, "a1 block, sequence %d" % b)
+    # the attention kernel on the block's own qkv (left in the workspace by the run above): last queries of a sequence
+    ws = call._keep[-1]
+    qkv = ws[:B * T * 3 * C * 2].view(ap.dtype).view(B, T, 3, H, D)
+    b, heads, first = 3, [0, H - 1], T - 40
+    got = binding.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], True)
+    torch.cuda.synchronize()
+    sub = f64(qkv[b:b + 1][:, :, :, heads].cpu())
+    ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], True, first_query=first)
+    assert_close(got[b:b + 1, first:][:, :, heads].cpu(), ref, ap.dtype, "a1 attention, last queries")
