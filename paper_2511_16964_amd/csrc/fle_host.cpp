@@ -458,6 +458,14 @@ static fle_status plan_block(const fle_attention_block *p, BlockParts *bp) {
 
     if (D != 64 && D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension C / H = %lld is not 64 or 128", (long long)D);
     if (rows > 0 && (!p->x || !p->w_qkv || !p->w_o || !p->out)) return fail(FLE_ERR_NULL, "x, w_qkv, w_o or out is NULL");
+    if (rows > 0) {
+        // the output projection checks out against its own operands; the first stage's are checked here
+        const size_t n_out = size_t(rows) * size_t(C) * 2;
+        if (overlaps(p->out, n_out, p->w_qkv, size_t(3 * C) * size_t(C) * 2) || overlaps(p->out, n_out, p->b_qkv, size_t(3 * C) * 2))
+            return fail(FLE_ERR_UNSUPPORTED, "out overlaps w_qkv or b_qkv");
+        if (overlaps(p->out, n_out, p->x, n_out) && !(p->out == p->x && p->residual == p->x))
+            return fail(FLE_ERR_UNSUPPORTED, "out overlaps x (allowed only when x is also the residual, exactly)");
+    }
     fle_status s;
     if (ws) {
         s = make_plan(&pj, V_AUTO, 0, &bp->proj_plan);

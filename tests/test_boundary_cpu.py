@@ -403,3 +403,72 @@ def test_every_variant_plans_every_kind_of_epilogue(L):
                     np_ = int(re.search(r"np=(\d+)", text).group(1))
                     has_row = any(o[0] >= 6 for o in ch)
                     assert (np_ > 0) == has_row and (need.value >= rows * np_ * 8) and ("row_op=-1" in text) == (not has_row), text
+
+
+# ------------------------------------------------------------------ attention (host-side validation only)
+def attention(B=2, H=4, T=100, D=64, dtype=binding.BF16, causal=1, base=G, ld=None, scale=0.0, o=None, ldo=None):
+    p = binding.FleAttention()
+    HD = H * D
+    ld = 3 * HD if ld is None else ld
+    p.dtype, p.causal, p.B, p.H, p.T, p.D = dtype, causal, B, H, T, D
+    p.q, p.k, p.v = base, base + 2 * HD, base + 4 * HD          # the three thirds of one [B*T, 3*H*D] matrix
+    p.ldq = p.ldk = p.ldv = ld
+    p.o = 64 * G if o is None else o
+    p.ldo = HD if ldo is None else ldo
+    p.scale = scale
+    return p
+
+
+def test_attention_validation(L):
+    v = lambda p: L.fle_attention_validate(ctypes.byref(p))
+    assert v(attention()) == OK
+    assert v(attention(D=128, dtype=binding.F16, causal=0, scale=0.25)) == OK
+    assert v(attention(B=0)) == OK                                   # empty batch: a no-op
+    assert v(attention(dtype=binding.F32)) == E_UNSUP
+    assert v(attention(D=32)) == E_UNSUP and v(attention(D=96)) == E_UNSUP
+    assert v(attention(T=0)) == E_SHAPE and v(attention(H=0)) == E_SHAPE and v(attention(B=-1)) == E_SHAPE
+    assert v(attention(ld=4 * 64 - 8)) == E_SHAPE                    # token stride below H*D
+    assert v(attention(ld=3 * 256 + 4)) == E_ALIGN                   # not a multiple of 8 elements
+    assert v(attention(base=G + 8)) == E_ALIGN
+    assert v(attention(ldo=4 * 64 + 2)) == E_ALIGN
+    assert v(attention(scale=-1.0)) == E_OP and v(attention(scale=float("inf"))) == E_OP and v(attention(scale=float("nan"))) == E_OP
+    assert v(attention(o=G + 64)) == E_UNSUP                         # o inside q
+    p = attention(); p.k = None
+    assert v(p) == E_NULL
+    assert v(attention(T=1 << 20, H=64, D=128)) == E_SHAPE           # a sequence's K spans more than 2 GiB
+    assert b"2 GiB" in L.fle_last_error()
+    assert L.fle_attention_validate(None) == E_NULL
+
+
+def attention_block(B=2, T=100, C=256, H=4, dtype=binding.BF16, residual=True, ws=None, ws_bytes=0):
+    p = binding.FleAttentionBlock()
+    p.dtype, p.causal, p.B, p.T, p.C, p.H = dtype, 1, B, T, C, H
+    p.x, p.w_qkv, p.b_qkv, p.w_o, p.b_o, p.out = G, 2 * G, 3 * G, 4 * G, 5 * G, 6 * G
+    p.residual = G if residual else None                             # the block's input
+    p.workspace, p.workspace_bytes = ws, ws_bytes
+    return p
+
+
+def test_attention_block_validation_and_workspace(L):
+    v = lambda p: L.fle_attention_block_validate(ctypes.byref(p))
+    assert v(attention_block()) == OK
+    assert v(attention_block(C=250)) == E_SHAPE                      # C not a multiple of H
+    assert v(attention_block(C=128, H=4)) == E_UNSUP                 # head dimension 32
+    assert v(attention_block(dtype=binding.F32)) == E_UNSUP
+    p = attention_block(); p.w_o = None
+    assert v(p) == E_NULL
+    p = attention_block(); p.out = 2 * G                             # out on top of w_qkv
+    assert v(p) == E_UNSUP
+    need = ctypes.c_size_t(0)
+    p = attention_block(B=2, T=100, C=256)
+    assert L.fle_attention_block_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    rows = 200
+    assert need.value >= rows * 3 * 256 * 2 + rows * 256 * 2 and need.value % 256 == 0
+    # run refuses a missing or short workspace before anything is enqueued (no HIP call is made)
+    assert L.fle_attention_block_run(ctypes.byref(p)) == E_WS
+    p = attention_block(ws=8 * G, ws_bytes=need.value - 256)
+    assert L.fle_attention_block_run(ctypes.byref(p)) == E_WS
+    p = attention_block(ws=8 * G + 16, ws_bytes=need.value)
+    assert L.fle_attention_block_run(ctypes.byref(p)) == E_ALIGN
+    p = attention_block(B=0)
+    assert L.fle_attention_block_run(ctypes.byref(p)) == OK          # empty batch

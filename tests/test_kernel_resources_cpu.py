@@ -56,6 +56,15 @@ def test_thin_kernels_do_not_spill(asm):
         assert p["scratch"] == 0 and p["vgpr"] <= 256, (name, p)   # at least two waves per SIMD
 
 
+def test_attention_kernels_keep_two_waves_per_simd(asm):
+    props = kernel_props(asm)
+    att = {k: v for k, v in props.items() if "flash_attention" in k}
+    assert len(att) == 4, sorted(att)   # bf16 / fp16 x head dimension 64 / 128
+    for name, p in att.items():
+        assert p["scratch"] == 0 and p["vgpr"] <= 256 and p["lds"] <= 64 * 1024, (name, p)
+    assert "ds_read_b64_tr_b16" in asm   # V is transposed by the LDS read itself
+
+
 def test_streaming_finalize_keeps_its_occupancy(asm):
     """The LayerNorm finalize pass is a bandwidth-bound streaming kernel: it needs many waves per SIMD, so
     its register count must stay low (a shared code path once pushed it to 149 and cost 40 % of its speed)."""

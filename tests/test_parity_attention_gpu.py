@@ -121,3 +121,18 @@ def test_attention_block_small(dtype, B, T, C, heads, causal, bias, residual):
     announce("attention block", dtype, B, T, C, heads, causal, bias, residual)
     ap = inputs.make_attention("a1", 5, B=B, T=T, C=C, heads=heads, causal=causal, dtype=dtype, bias=bias, residual=residual)
     assert_close(run_block(ap), oracle_block(ap), dtype)
+
+
+def test_attention_block_in_place():
+    """out == residual == x: the block overwrites its input (x is last read by the first stage)."""
+    announce("attention block in place")
+    ap = inputs.make_attention("a1", 9, B=2, T=140, C=256, heads=4, causal=True, dtype=BF16)
+    d = lambda t: t.to(DEV)
+    x = d(ap.x).clone()
+    out = binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=x, out=x)
+    torch.cuda.synchronize()
+    assert out.data_ptr() == x.data_ptr()
+    assert_close(x.cpu(), oracle_block(ap), BF16)
+    other = torch.empty_like(x)
+    with pytest.raises(binding.FleError):   # out on top of x without being the residual
+        binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=other, out=x)
