@@ -28,6 +28,20 @@ struct BufferPair {
     }
 };
 
+// Placement of the 16-byte chunks of a K / V row in LDS: chunk c of row r sits at position c ^ lds_swizzle(r).
+// Two access patterns must spread over all banks (256 bytes per cycle): the K fragment reads (16 consecutive
+// rows, the same chunk of each) and the transposing V reads (32 lanes = 4 consecutive rows x 64 contiguous
+// bytes).  The first needs 16 consecutive rows to land on 16 different 16-byte positions of a 256-byte bank
+// sweep, the second needs rows r .. r + 3 (r a multiple of 4) to move a 64-byte group to 4 different groups.
+// D = 128 (a row is one sweep, 16 chunks): the two low row bits go to the two high chunk bits, the next two
+// to the low ones.  D = 64 (two rows per sweep, 8 chunks; row parity picks the half sweep): row bit 1 goes
+// to the high chunk bit, bits 2 and 3 to the low ones.
+template <int D>
+__device__ __forceinline__ int lds_swizzle(int row) {
+    if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
 // Everything is computed transposed, so that a lane owns one query:
 //
 //     S^T[key, query] = K[key, :] . Q[query, :]          v_mfma_f32_32x32x16 (A = K rows, B = Q rows)
@@ -48,8 +62,8 @@ struct BufferPair {
 // or three waves on a SIMD) and walks the key blocks of 64 that all four waves share through LDS, double
 // buffered: the next block is copied into the other stage (buffer loads that write LDS directly) while the
 // current one is used; one barrier per iteration.  Rows of K / V are stored with their 16-byte
-// chunks XOR-ed by (row & 7), which spreads both the row-wise reads of K and the transposing reads of V
-// over all banks.  With the causal mask a wave stops computing at its last visible block and only keeps
+// chunks XOR-ed by lds_swizzle(row), which spreads both the row-wise reads of K and the transposing reads
+// of V over all banks.  With the causal mask a wave stops computing at its last visible block and only keeps
 // the barriers; the mask itself is applied on the diagonal and tail blocks only.
 template <int DT, int D, int QT>
 __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
@@ -130,7 +144,7 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
 
     // Copies of one K / V block, global memory -> LDS without passing registers: one instruction moves
     // 1 KB (RPI rows) to consecutive LDS addresses, so the XOR placement is applied on the source side: the
-    // lane that fills chunk position `pos` of a row fetches that row's chunk pos ^ (row & 7).  Rows at or
+    // lane that fills chunk position `pos` of a row fetches that row's chunk pos ^ lds_swizzle(row).  Rows at or
     // beyond T lie outside the buffer range and arrive as zeros.
     constexpr int RPI = 1024 / RB, NI = BKV / RPI / 4;  // rows per instruction; instructions per wave and operand
     const uint32_t nrec_k = uint32_t(int64_t(T - 1) * a.ldk * 2 + RB), nrec_v = uint32_t(int64_t(T - 1) * a.ldv * 2 + RB);
@@ -141,8 +155,8 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const int row = (wave * NI + i) * RPI + lane / CPR, pos = lane % CPR;
-        cp_k[i] = uint32_t(row) * uint32_t(a.ldk * 2) + uint32_t((pos ^ (row & 7)) * 16);
-        cp_v[i] = uint32_t(row) * uint32_t(a.ldv * 2) + uint32_t((pos ^ (row & 7)) * 16);
+        cp_k[i] = uint32_t(row) * uint32_t(a.ldk * 2) + uint32_t((pos ^ lds_swizzle<D>(row)) * 16);
+        cp_v[i] = uint32_t(row) * uint32_t(a.ldv * 2) + uint32_t((pos ^ lds_swizzle<D>(row)) * 16);
     }
     auto copy_block = [&](char *stage, int kb0) {
         const uint32_t k0 = uint32_t(kb0) * uint32_t(a.ldk * 2), v0 = uint32_t(kb0) * uint32_t(a.ldv * 2);
@@ -153,15 +167,29 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
         }
     };
 
-    // per-lane LDS offsets that do not change over the loop
-    // K fragment (A operand): row = 32 kt + l31, 16-byte chunk 2 c + h2
-    // V^T fragment: source lane j of a 16-lane group points at key (j >> 2) + 4 h2 (+ 16 c2 + 8 e + 32 kt), d = 16 (group & 1) + 4 (j & 3) (+ 32 dt)
+    // Per-lane LDS byte offsets that do not change over the loop.  The swizzle of a row only depends on the
+    // row's low four bits, so the constant parts of a row index (32 kt, 16 c2) are plain address immediates and
+    // only the parts that enter the XOR (the chunk, and the key bit 3 of the second half-fragment) need an
+    // offset register of their own.
+    // K fragment (A operand): row = 32 kt + l31, 16-byte chunk 2 c + h2.
+    int koff[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) koff[c] = l31 * RB + (((2 * c + h2) ^ lds_swizzle<D>(l31)) * 16);
+    // V^T fragment: source lane j of a 16-lane group points at key (j >> 2) + 4 h2 (+ 8 e + 16 c2 + 32 kt), d = 16 (group & 1) + 4 (j & 3) (+ 32 dt)
     const int vj = lane & 15, vg = lane >> 4;
     const int v_key = (vj >> 2) + 4 * (vg >> 1), v_d = 16 * (vg & 1) + 4 * (vj & 3);
+    int voff[ND][2];
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int key = 8 * e + v_key, d = 32 * dt + v_d;
+            voff[dt][e] = BKV * RB + key * RB + (((d >> 3) ^ lds_swizzle<D>(key)) * 16) + (d & 7) * 2;
+        }
 
     // One block of 64 keys as two sub-blocks of 32: scores, running-softmax update, second product.
-    auto compute = [&](const char *stage, int kb0, bool mask) {
-        const char *sK = stage, *sV = stage + BKV * RB;
+    auto compute = [&](auto stage_c, int kb0, bool mask) {
+        constexpr int SOFF = decltype(stage_c)::value * STAGE;  // compile-time, so that it folds into the address immediates
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             f32x16 s[QT];
@@ -169,10 +197,9 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
             for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[qt][r] = 0.0f;
-            const int row = 32 * kt + l31;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const frag_t kf = *reinterpret_cast<const frag_t *>(sK + row * RB + (((2 * c + h2) ^ (row & 7)) * 16));
+                const frag_t kf = *reinterpret_cast<const frag_t *>(smem + koff[c] + (SOFF + 32 * kt * RB));
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt) {
                     if constexpr (DT == FLE_F16) s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qt][c], s[qt], 0, 0, 0);
@@ -233,11 +260,9 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
                 for (int dt = 0; dt < ND; ++dt) {
                     struct { i16x4 e[2]; } part;
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int key = 32 * kt + 16 * c2 + 8 * e + v_key, d = 32 * dt + v_d;
-                        const int off = key * RB + (((d >> 3) ^ (key & 7)) * 16) + (d & 7) * 2;
-                        part.e[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(sV + off));
-                    }
+                    for (int e = 0; e < 2; ++e)
+                        part.e[e] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (__attribute__((address_space(3))) i16x4 *)(smem + voff[dt][e] + (SOFF + (32 * kt + 16 * c2) * RB)));
                     const frag_t vf = __builtin_bit_cast(frag_t, part);
 #pragma unroll
                     for (int qt = 0; qt < QT; ++qt) {
@@ -251,15 +276,19 @@ __global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
     copy_block(smem, 0);
     wait_vmcnt<0>();
     __syncthreads();
-    for (int j = 0; j < n_blocks; ++j) {
+    // two blocks per trip, so that the stage a block sits in is known at compile time
+    auto block_step = [&](int j, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
         const int kb0 = j * BKV;
-        // the other stage was last read before the barrier that ended the previous iteration
-        if (j + 1 < n_blocks) copy_block(smem + ((j + 1) & 1) * STAGE, kb0 + BKV);
-        if (j <= wave_last) {
-            compute(smem + (j & 1) * STAGE, kb0, kb0 + BKV > T || (a.causal && kb0 + BKV - 1 > wq0));
-        }
+        // the other stage was last read before the barrier that ended the previous block
+        if (j + 1 < n_blocks) copy_block(smem + (ST ^ 1) * STAGE, kb0 + BKV);
+        if (j <= wave_last) compute(stage_c, kb0, kb0 + BKV > T || (a.causal && kb0 + BKV - 1 > wq0));
         wait_vmcnt<0>();
         __syncthreads();
+    };
+    for (int j = 0; j < n_blocks; j += 2) {
+        block_step(j, std::integral_constant<int, 0>{});
+        if (j + 1 < n_blocks) block_step(j + 1, std::integral_constant<int, 1>{});
     }
 
     // O^T registers: lane = query, register r of tile dt is d = 32 dt + 8 (r / 4) + 4 h2 + r % 4
