@@ -65,8 +65,12 @@ __device__ __forceinline__ int lds_swizzle(int row) {
 // chunks XOR-ed by lds_swizzle(row), which spreads both the row-wise reads of K and the transposing reads
 // of V over all banks.  With the causal mask a wave stops computing at its last visible block and only keeps
 // the barriers; the mask itself is applied on the diagonal and tail blocks only.
+//
+// The kernel states the occupancy it is built for (two waves per SIMD at D = 128, three at D = 64): left to
+// itself the register allocator aims one step higher, caps the ordinary VGPRs accordingly and parks the
+// output accumulators in AGPRs, copying all of them in and out on every trip of the loop.
 template <int DT, int D, int QT>
-__global__ __launch_bounds__(256) void flash_attention(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 3, D == 128 ? 2 : 3))) void flash_attention(const AttnArgs a) {
     static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte dtypes only");
     static_assert(D == 64 || D == 128, "head dimension 64 or 128");
     using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
