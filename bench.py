@@ -360,6 +360,8 @@ def main():
                                                inputs.epilogue_f64(prob0.epilogue, rows))
         got = calls[0].out[rows].cpu().to(torch.float64).numpy()
     tol = 2e-2 if prob0.dtype == torch.bfloat16 else 1e-4
+    if args.workload == "a1":
+        tol *= 3.0 ** 0.5   # the block stores two intermediates in bf16: three roundings in sequence
     s = min(1.0, float(np.sqrt(np.mean(ref * ref))))
     if not np.all(np.abs(got - ref) <= tol * (s + np.abs(ref))):
         sys.exit("bench.py: GPU result fails parity against the oracle; no timing reported")

@@ -54,11 +54,17 @@ def excess(got: np.ndarray, ref: np.ndarray, tol: float):
     return float(np.max(err - tol * (s + np.abs(ref)))), float(err.max()), s
 
 
-def assert_close(got_t: torch.Tensor, ref: np.ndarray, dtype, what=""):
+# The attention block stores two intermediates (qkv and the attention output) in the storage dtype, as the
+# eager composition does, before the final rounding: three independent roundings of the same relative size in
+# sequence, so its allowance is sqrt(3) times that of a single fused call.
+BLOCK_FACTOR = 3.0 ** 0.5
+
+
+def assert_close(got_t: torch.Tensor, ref: np.ndarray, dtype, what="", factor=1.0):
     got = got_t.to(torch.float64).numpy()
     assert got.shape == ref.shape, (got.shape, ref.shape)
     assert np.isfinite(got).all(), "non-finite GPU output " + what
-    worst, maxerr, s = excess(got, ref, TOL[dtype])
+    worst, maxerr, s = excess(got, ref, TOL[dtype] * factor)
     assert worst <= 0, "%s: criterion exceeded by %.3e (max |err| %.3e, s %.3e)" % (what, worst, maxerr, s)
     return maxerr
 

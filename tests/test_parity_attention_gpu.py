@@ -1,6 +1,7 @@
 """GPU parity of the attention kernel and of the three-launch attention block against the CPU oracle
 (scaled dot-product attention written out in float64).  Floating point within 2e-2 (bf16) / 4e-3 (fp16)
-of the oracle, the same criterion as the fused linear operator."""
+of the oracle, the same criterion as the fused linear operator; the block, with its two stored intermediates,
+gets sqrt(3) times that allowance (three roundings in sequence)."""
 import numpy as np
 import pytest
 import torch
@@ -8,7 +9,7 @@ import torch
 import oracle
 from paper_2511_16964_amd import binding, inputs
 
-from parity import assert_close
+from parity import BLOCK_FACTOR, assert_close
 
 pytestmark = pytest.mark.gpu
 
@@ -120,7 +121,7 @@ def oracle_block(ap):
 def test_attention_block_small(dtype, B, T, C, heads, causal, bias, residual):
     announce("attention block", dtype, B, T, C, heads, causal, bias, residual)
     ap = inputs.make_attention("a1", 5, B=B, T=T, C=C, heads=heads, causal=causal, dtype=dtype, bias=bias, residual=residual)
-    assert_close(run_block(ap), oracle_block(ap), dtype)
+    assert_close(run_block(ap), oracle_block(ap), dtype, factor=BLOCK_FACTOR)
 
 
 def test_attention_block_in_place():
@@ -132,7 +133,7 @@ def test_attention_block_in_place():
     out = binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=x, out=x)
     torch.cuda.synchronize()
     assert out.data_ptr() == x.data_ptr()
-    assert_close(x.cpu(), oracle_block(ap), BF16)
+    assert_close(x.cpu(), oracle_block(ap), BF16, factor=BLOCK_FACTOR)
     other = torch.empty_like(x)
     with pytest.raises(binding.FleError):   # out on top of x without being the residual
         binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=other, out=x)

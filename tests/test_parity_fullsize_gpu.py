@@ -8,7 +8,7 @@ import torch
 
 from paper_2511_16964_amd import inputs
 
-from parity import assert_close, make_call, oracle_rows, run_gpu, sample_rows
+from parity import BLOCK_FACTOR, assert_close, make_call, oracle_rows, run_gpu, sample_rows
 
 pytestmark = pytest.mark.gpu
 BF16 = torch.bfloat16
@@ -134,7 +134,7 @@ def test_a1_attention_block_fullsize_sampled_tokens():
     for b in (0, B - 1):
         x = f64(ap.x[b:b + 1, :n_tok])
         ref = oracle.attention_block(x, f64(ap.w_qkv), f64(ap.b_qkv), f64(ap.w_o), f64(ap.b_o), H, ap.causal, residual=x)
-        assert_close(out[b:b + 1, :n_tok].cpu(), ref, ap.dtype, "a1 block, sequence %d" % b)
+        assert_close(out[b:b + 1, :n_tok].cpu(), ref, ap.dtype, "a1 block, sequence %d" % b, factor=BLOCK_FACTOR)
     # the attention kernel on the block's own qkv (left in the workspace by the run above): last queries of a sequence
     ws = call._keep[-1]
     qkv = ws[:B * T * 3 * C * 2].view(ap.dtype).view(B, T, 3, H, D)

@@ -7,7 +7,7 @@ import torch
 
 from paper_2511_16964_amd import binding, inputs
 
-from parity import assert_close, oracle_grouped, oracle_rows, run_grouped_gpu
+from parity import BLOCK_FACTOR, assert_close, oracle_grouped, oracle_rows, run_grouped_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -111,3 +111,55 @@ def test_random_grouped_problem_matches_oracle(seed):
     print("[case] grouped seed %d %s G=%d rows=%d N=%d K=%d %s %s" % (seed, str(dtype)[6:], G, total, N, K, variant, chain), flush=True)
     got, call = run_grouped_gpu(gp, variant)
     assert_close(got, oracle_grouped(gp), dtype, "%s %s" % (chain, call.plan()))
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_attention_matches_oracle(seed):
+    """Random sequence lengths (1 .. 700, mostly ragged against the 128-query and 64-key blocks), head counts,
+    batch sizes, both head dimensions and dtypes, with and without the causal mask, default and explicit
+    scales, q / k / v as views of one fused buffer or as separate tensors with padded token strides."""
+    import oracle
+    rng = np.random.default_rng(5000 + seed)
+    dtype = [torch.bfloat16, torch.float16][rng.integers(0, 2)]
+    D = [64, 128][rng.integers(0, 2)]
+    T = int(rng.integers(1, 700)) if rng.random() < 0.8 else int(rng.integers(1, 6)) * 128
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 12))
+    causal = bool(rng.integers(0, 2))
+    scale = None if rng.random() < 0.6 else float(rng.uniform(0.02, 0.5))
+    spread = float(rng.choice([0.3, 1.0, 2.5]))
+    print("[case] random attention", seed, dtype, D, T, B, H, causal, scale, spread, flush=True)
+    qkv = inputs.make_qkv(seed, B, T, H, D, dtype, spread)
+    dev = qkv.to("cuda:0")
+    if rng.random() < 0.5:
+        q, k, v = dev[:, :, 0], dev[:, :, 1], dev[:, :, 2]
+    else:   # separate buffers, token stride padded by 8 .. 64 elements
+        def padded(t):
+            pad = int(rng.integers(1, 9)) * 8
+            buf = torch.zeros(B * T, H * D + pad, device="cuda:0", dtype=dtype)
+            buf[:, :H * D] = t.reshape(B * T, H * D)
+            return buf[:, :H * D].view(B, T, H, D)
+        q, k, v = padded(dev[:, :, 0]), padded(dev[:, :, 1]), padded(dev[:, :, 2])
+    got = binding.attention(q, k, v, causal, scale)
+    torch.cuda.synchronize()
+    f = inputs.to_f64(qkv)
+    assert_close(got.cpu(), oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, scale), dtype, "seed %d" % seed)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_attention_block_matches_oracle(seed):
+    import oracle
+    rng = np.random.default_rng(7000 + seed)
+    dtype = [torch.bfloat16, torch.float16][rng.integers(0, 2)]
+    D = [64, 128][rng.integers(0, 2)]
+    heads = int(rng.integers(1, 7))
+    B, T = int(rng.integers(1, 4)), int(rng.integers(1, 400))
+    causal, bias, residual = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    print("[case] random attention block", seed, dtype, D, heads, B, T, causal, bias, residual, flush=True)
+    ap = inputs.make_attention("a1", seed, B=B, T=T, C=heads * D, heads=heads, causal=causal, dtype=dtype, bias=bias, residual=residual)
+    d = lambda t: None if t is None else t.to("cuda:0")
+    x = d(ap.x)
+    got = binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), heads, causal, residual=x if residual else None)
+    torch.cuda.synchronize()
+    f = inputs.to_f64
+    ref = oracle.attention_block(f(ap.x), f(ap.w_qkv), f(ap.b_qkv), f(ap.w_o), f(ap.b_o), heads, causal, residual=f(ap.residual))
+    assert_close(got.cpu(), ref, dtype, "seed %d" % seed, factor=BLOCK_FACTOR)
