@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "a1": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "a1": None, "a2": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -210,12 +210,31 @@ def cpu_baseline_attention(apb, inputs, budget_s=12.0):
             "sample": "the first %d of %d tokens of %d of %d sequences, whole block, %.1f s" % (n, T, seqs, B, t)}
 
 
+def cpu_baseline_attention_kernel(qkv, causal, inputs, budget_s=12.0):
+    """The oracle's attention on whole (sequence, head) problems of the same workload, as many as fill the budget."""
+    import oracle
+    B, T, _, H, D = qkv.shape
+    def run(n_seq, n_heads):
+        sub = inputs.to_f64(qkv[:n_seq, :, :, :n_heads])
+        t0 = time.perf_counter()
+        oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal)
+        return time.perf_counter() - t0
+    t = run(1, 1)
+    n = int(max(1, min(H, budget_s / max(t, 1e-9))))
+    seqs = int(max(1, min(B, budget_s / max(t * H, 1e-9)))) if n == H else 1
+    if n > 1 or seqs > 1:
+        t = run(seqs, n)
+    flops = 4.0 * seqs * n * (T * (T + 1) / 2 if causal else T * T) * D
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "%d of %d heads of %d of %d sequences, all %d tokens, %.1f s" % (n, H, seqs, B, T, t)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "a1"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "a1", "a2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -302,6 +321,20 @@ def main():
             return F.linear(o.transpose(1, 2).reshape(B, T, C), wo, bo) + xg
         # x, both weight matrices and biases, the residual, out; qkv and the attention output written and read once
         alg_bytes = 2 * (3 * B * T * C + 4 * C * C + 4 * C + 2 * (3 * B * T * C + B * T * C))
+    elif args.workload == "a2":
+        # the attention kernel alone, on q, k, v of a1's shape (views of one fused [B,T,3,H,D] buffer)
+        dt0, B, T, C, H, causal = inputs.ATTENTION_SHAPES["a1"]
+        D = C // H
+        qkv_cpu = inputs.make_qkv(0, B, T, H, D, dt0)
+        qkv = to(qkv_cpu)
+        calls = [binding.AttentionCall(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], causal)]
+        probs = [inputs.AttentionProblem("a2", dt0, H, causal, qkv_cpu, None, None, None, None, None)]
+        flops = 4.0 * B * H * (T * (T + 1) / 2 if causal else T * T) * D
+        desc = "a2: %s attention alone, bf16, B=%d T=%d heads=%d D=%d (q, k, v ~ N(0,1))" % ("causal" if causal else "full", B, T, H, D)
+        qe, ke, ve = (qkv[:, :, i].transpose(1, 2) for i in range(3))
+        def eager():
+            return F.scaled_dot_product_attention(qe, ke, ve, is_causal=causal)
+        alg_bytes = 2 * 4 * B * T * H * D   # q, k, v read once, o written once
     elif args.workload == "c5":
         blk = inputs.make_mlp()
         p1 = blk.call1()
@@ -339,10 +372,16 @@ def main():
     # ---- validity gate: a few rows against the oracle before any timing is reported
     step()
     torch.cuda.synchronize()
-    plans = [c.plan() for c in calls]
+    plans = [c.plan() if hasattr(c, "plan") else "attention kernel" for c in calls]
     import oracle
     prob0 = probs[0]
-    if args.workload == "a1":
+    if args.workload == "a2":
+        # the last queries of one sequence and two heads, against all their keys
+        b, heads, first = 1, [0, H - 1], T - 24
+        sub = inputs.to_f64(qkv_cpu[b:b + 1][:, :, :, heads])
+        ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal, first_query=first)
+        got = calls[0].out[b:b + 1, first:][:, :, heads].cpu().to(torch.float64).numpy()
+    elif args.workload == "a1":
         # the first tokens of the first sequence: under the causal mask they depend on nothing after them
         n_tok = 131
         f64 = inputs.to_f64
@@ -374,7 +413,7 @@ def main():
     cold_mean, cold_med, cold_min = time_cold(torch, step, 50, flush)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     out = {
-        "metric": "fused GEMM+epilogue TFLOP/s", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": {"a1": "fused attention block TFLOP/s", "a2": "attention TFLOP/s"}.get(args.workload, "fused GEMM+epilogue TFLOP/s"), "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if prob0.dtype == torch.bfloat16 else "f32", "data": "synthetic",
@@ -406,7 +445,7 @@ def main():
                     c.run()
             lwall, _ = time_loop(torch, loop_step, max(10, args.steps // 4), 5)
             out["loop_of_plain_fused_calls"] = {"ms_per_step": lwall, "calls": len(loop_calls), "speedup_grouped_vs_loop": lwall / wall_ms}
-        elif args.workload != "a1":
+        elif args.workload not in ("a1", "a2"):
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
@@ -416,6 +455,8 @@ def main():
             out["cpu_baseline"] = cpu_baseline_chain(ch, inputs)
         elif args.workload == "a1":
             out["cpu_baseline"] = cpu_baseline_attention(apb, inputs)
+        elif args.workload == "a2":
+            out["cpu_baseline"] = cpu_baseline_attention_kernel(qkv_cpu, causal, inputs)
         else:
             out["cpu_baseline"] = cpu_baseline(prob0, inputs, 2 * prob0.N * prob0.K)
     if args.calibrate_copy:

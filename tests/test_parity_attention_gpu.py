@@ -137,3 +137,30 @@ def test_attention_block_in_place():
     other = torch.empty_like(x)
     with pytest.raises(binding.FleError):   # out on top of x without being the residual
         binding.attention_block(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=other, out=x)
+
+
+def test_attention_block_in_a_hip_graph():
+    """The block only launches kernels (no allocation, synchronisation or memset), so its three stages can be
+    captured once and replayed; every replay reproduces the eager result bit for bit on changed inputs."""
+    announce("attention block in a graph")
+    ap = inputs.make_attention("a1", 21, B=2, T=300, C=256, heads=2, causal=True, dtype=BF16)
+    d = lambda t: t.to(DEV)
+    x = d(ap.x)
+    call = binding.AttentionBlockCall(x, d(ap.w_qkv), d(ap.b_qkv), d(ap.w_o), d(ap.b_o), ap.heads, ap.causal, residual=x)
+    call.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        call.run()
+    gen = torch.Generator().manual_seed(3)
+    for rep in range(3):
+        x.copy_(torch.randn(x.shape, generator=gen).to(x.dtype))
+        eager = call.run().clone()
+        torch.cuda.synchronize()
+        call.out.fill_(-5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(call.out, eager), "replay %d differs" % rep
+    cur = inputs.AttentionProblem("cur", BF16, ap.heads, ap.causal, x.cpu(), ap.w_qkv, ap.b_qkv, ap.w_o, ap.b_o, x.cpu())
+    assert_close(call.out.cpu(), oracle_block(cur), BF16, factor=BLOCK_FACTOR)
