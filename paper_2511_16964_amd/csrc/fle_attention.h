@@ -191,72 +191,85 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 
             voff[dt][e] = BKV * RB + key * RB + (((d >> 3) ^ lds_swizzle<D>(key)) * 16) + (d & 7) * 2;
         }
 
-    // One block of 64 keys as two sub-blocks of 32: scores, running-softmax update, second product.
+    // One block of 64 keys: the scores of its two 32-key tiles (two independent MFMA chains), one update of
+    // the running maximum, then exponentials and second product tile by tile in one straight-line stretch, so
+    // that the scheduler can run the exponentials of the second tile under the MFMAs of the first.
     auto compute = [&](auto stage_c, int kb0, bool mask) {
         constexpr int SOFF = decltype(stage_c)::value * STAGE;  // compile-time, so that it folds into the address immediates
+        f32x16 s[2][QT];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            f32x16 s[QT];
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[qt][r] = 0.0f;
+                for (int r = 0; r < 16; ++r) s[kt][qt][r] = 0.0f;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
                 const frag_t kf = *reinterpret_cast<const frag_t *>(smem + koff[c] + (SOFF + 32 * kt * RB));
 #pragma unroll
                 for (int qt = 0; qt < QT; ++qt) {
-                    if constexpr (DT == FLE_F16) s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qt][c], s[qt], 0, 0, 0);
-                    else s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][c], s[qt], 0, 0, 0);
+                    if constexpr (DT == FLE_F16) s[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qt][c], s[kt][qt], 0, 0, 0);
+                    else s[kt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qt][c], s[kt][qt], 0, 0, 0);
                 }
             }
-            frag_t pf[QT][2];
 #pragma unroll
-            for (int qt = 0; qt < QT; ++qt) {
-                if (mask) {  // diagonal and tail blocks only (uniform over the wave)
-                    const int query = wq0 + 32 * qt + l31;
+        for (int qt = 0; qt < QT; ++qt) {
+            if (mask) {  // diagonal and tail blocks only (uniform over the wave)
+                const int query = wq0 + 32 * qt + l31;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = kb0 + 32 * kt + 8 * (r / 4) + 4 * h2 + (r % 4);
-                        if (key >= T || (a.causal && key > query)) s[qt][r] = -INFINITY;
+                        if (key >= T || (a.causal && key > query)) s[kt][qt][r] = -INFINITY;
                     }
-                }
-                float mx = s[qt][0];
+            }
+            float mx = s[0][qt][0];
 #pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[qt][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // The reference point of the exponentials only moves when some row's maximum has grown by more
-                // than 2^8 past it (always in the first sub-block): the probabilities of a row then reach at most
-                // 256 instead of 1, a common factor that the final division by the row sum removes, and in most
-                // sub-blocks no lane of the wave has to rescale its accumulators.
-                const float cand = mx * a.scale_log2e;
-                const bool grow = cand > m_run[qt] + 8.0f;
-                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                    const float m_new = grow ? cand : m_run[qt];
-                    const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
-                    m_run[qt] = m_new;
-                    l_run[qt] *= alpha;
+            for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                    for (int dt = 0; dt < ND; ++dt)
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][qt][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // The reference point of the exponentials only moves when some row's maximum has grown by more
+            // than 2^8 past it (always in the first block): the probabilities of a row then reach at most 256
+            // instead of 1, a common factor that the final division by the row sum removes, and in most blocks
+            // no lane of the wave has to rescale its accumulators.
+            const float cand = mx * a.scale_log2e;
+            const bool grow = cand > m_run[qt] + 8.0f;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float m_new = grow ? cand : m_run[qt];
+                const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_new);
+                m_run[qt] = m_new;
+                l_run[qt] *= alpha;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[dt][qt][r] *= alpha;
-                }
+                for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][qt][r] *= alpha;
+            }
+        }
+        float ps[QT];
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) ps[qt] = 0.0f;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            frag_t pf[QT][2];
+#pragma unroll
+            for (int qt = 0; qt < QT; ++qt) {
                 const float m_ref = m_run[qt];
-                float ps = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][r], a.scale_log2e, -m_ref));
-                    s[qt][r] = pr;
-                    ps += pr;
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][qt][r], a.scale_log2e, -m_ref));
+                    s[kt][qt][r] = pr;
+                    ps[qt] += pr;
                 }
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2) {
-                    const u32x2 lo = pack4<DT>(f32x4{s[qt][8 * c2 + 0], s[qt][8 * c2 + 1], s[qt][8 * c2 + 2], s[qt][8 * c2 + 3]});
-                    const u32x2 hi = pack4<DT>(f32x4{s[qt][8 * c2 + 4], s[qt][8 * c2 + 5], s[qt][8 * c2 + 6], s[qt][8 * c2 + 7]});
+                    const u32x2 lo = pack4<DT>(f32x4{s[kt][qt][8 * c2 + 0], s[kt][qt][8 * c2 + 1], s[kt][qt][8 * c2 + 2], s[kt][qt][8 * c2 + 3]});
+                    const u32x2 hi = pack4<DT>(f32x4{s[kt][qt][8 * c2 + 4], s[kt][qt][8 * c2 + 5], s[kt][qt][8 * c2 + 6], s[kt][qt][8 * c2 + 7]});
                     pf[qt][c2] = __builtin_bit_cast(frag_t, u32x4{lo[0], lo[1], hi[0], hi[1]});
                 }
-                ps += __shfl_xor(ps, 32);
-                l_run[qt] += ps;
             }
 #pragma unroll
             for (int c2 = 0; c2 < 2; ++c2)
@@ -274,6 +287,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 
                         else oacc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][c2], oacc[dt][qt], 0, 0, 0);
                     }
                 }
+        }
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) {
+            ps[qt] += __shfl_xor(ps[qt], 32);
+            l_run[qt] += ps[qt];
         }
     };
 
