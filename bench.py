@@ -241,7 +241,7 @@ def main():
                     help="also run a plain 512 MiB device copy a few times (known traffic, to scale FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding): use --gpus 1")
+        sys.exit("bench.py: the library runs on ONE GPU (no collectives, no sharding): use --gpus 1")
 
     import numpy as np
     import torch

@@ -245,7 +245,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     plan->edge = 0;
     int auto_split = 0;  // chosen with the tile (tiled kernel); 0: decided below
     if (variant == V_SKINNY) {
-        // The widest K step that fits two stages wins on the box: 512-byte runs per W row stream at
+        // The widest K step that fits two stages wins on an MI355X: 512-byte runs per W row stream at
         // 6.0 TB/s where 128- and 256-byte runs reach 4.5 TB/s.  forced 64 keeps the narrow ring for comparison.
         int bk = forced_bk ? forced_bk : 256;  // in 2-byte elements; fp32 operands take half as many for the same bytes
         if (forced == V_SKINNY) bk = 64;

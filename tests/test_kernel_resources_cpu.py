@@ -1,6 +1,6 @@
 """Compile-time properties of the hot kernels, checked without a GPU: the gfx950 code object
 must keep the tiled and skinny GEMM kernels free of scratch spills (a spill in the K loop costs
-~30 % on the box) and inside the LDS and register budgets their launch configuration assumes."""
+~30 % on an MI355X) and inside the LDS and register budgets their launch configuration assumes."""
 import os
 import re
 import shutil
