@@ -168,14 +168,15 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0
     return out
 
 
-def attention(q, k, v, causal: bool, scale=None, n_threads: int = 0, first_query: int = 0) -> np.ndarray:
+def attention(q, k, v, causal, scale=None, n_threads: int = 0, first_query: int = 0) -> np.ndarray:
     """float64 gold result of scaled dot-product attention, token-major.
 
     q, k, v: [B, T, H, D] float64 (any strides whose last two axes are contiguous, so the three
     thirds of a fused QKV projection's output can be passed as views); scale defaults to
-    1/sqrt(D) and is rounded to fp32 as it is when it crosses the GPU boundary.  causal: query t
-    sees keys 0..t only (the mask the paper's attention solutions apply on the fly, appendix on
-    Level 5 outliers).  Returns [B, T, H, D]; with first_query = t0 only queries t0 .. T-1 are
+    1/sqrt(D) and is rounded to fp32 as it is when it crosses the GPU boundary.  causal: False / 0:
+    every key; True / 1: query t sees keys 0..t only; G > 1: the same over groups of G consecutive
+    tokens, query t sees keys 0 .. (t // G + 1) * G - 1 (the mask the paper's attention solutions
+    apply on the fly, appendix on Level 5 outliers).  Returns [B, T, H, D]; with first_query = t0 only queries t0 .. T-1 are
     evaluated (against all their keys) and [B, T - t0, H, D] is returned.
     """
     q, k, v = (np.asarray(a) for a in (q, k, v))
@@ -190,13 +191,13 @@ def attention(q, k, v, causal: bool, scale=None, n_threads: int = 0, first_query
     out = np.full((B * T, H * D), np.nan, dtype=np.float64)
     rc = _load().fle_oracle_attention(
         B, H, T, D, q2.ctypes.data, H * D, k2.ctypes.data, H * D, v2.ctypes.data, H * D,
-        1 if causal else 0, sc, out.ctypes.data, H * D, int(first_query), int(n_threads))
+        int(causal), sc, out.ctypes.data, H * D, int(first_query), int(n_threads))
     if rc != 0:
         raise ValueError("fle_oracle_attention rejected the arguments (code %d)" % rc)
     return out.reshape(B, T, H, D)[:, int(first_query):]
 
 
-def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads: int, causal: bool, residual=None, n_threads: int = 0) -> np.ndarray:
+def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads: int, causal, residual=None, n_threads: int = 0) -> np.ndarray:
     """float64 gold result of a self-attention block: the unfused composition.
 
     qkv = x w_qkv^T + b_qkv is cut into thirds q | k | v along its columns, each third into

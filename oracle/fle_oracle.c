@@ -195,7 +195,9 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
  *     p      = softmax over the allowed j
  *     o[b,t,h,:] = sum_j p[j] * v[b,j,h,:]
  *
- * causal != 0 allows keys j <= t only.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d],
+ * causal = 1 allows keys j <= t only; causal = G > 1 is the same mask over groups of G consecutive
+ * tokens (query t sees every key of its own and of earlier groups: j < (t / G + 1) * G), the form a
+ * causal mask takes when a sequence is made of frames or patches that are not ordered internally.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d],
  * likewise k, v and o.  Only queries t >= t_first are evaluated (the other rows of o are left
  * untouched), so that a few rows of a long sequence can be checked without computing all of them.
  * Returns 0, or a negative code for bad arguments / -5 out of memory.
@@ -203,7 +205,7 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
 int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const double *q, int64_t ldq,
                          const double *k, int64_t ldk, const double *v, int64_t ldv, int32_t causal,
                          double scale, double *o, int64_t ldo, int64_t t_first, int32_t threads) {
-    if (B < 0 || H < 1 || T < 1 || D < 1 || t_first < 0 || t_first > T) return -1;
+    if (B < 0 || H < 1 || T < 1 || D < 1 || t_first < 0 || t_first > T || causal < 0) return -1;
     if (!q || !k || !v || !o) return -2;
     if (ldq < H * D || ldk < H * D || ldv < H * D || ldo < H * D) return -3;
     int failed = 0;
@@ -223,7 +225,8 @@ int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const doubl
         for (int64_t b = 0; b < B; ++b)
             for (int64_t t = t_first; t < T; ++t) {
                 if (!s) continue;
-                const int64_t keys = causal ? t + 1 : T;
+                int64_t keys = T;
+                if (causal && (t / causal + 1) * (int64_t)causal < T) keys = (t / causal + 1) * (int64_t)causal;
                 for (int64_t h = 0; h < H; ++h) {
                     const double *qr = q + (b * T + t) * ldq + h * D;
                     for (int64_t j = 0; j < keys; ++j) {

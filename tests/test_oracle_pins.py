@@ -451,6 +451,29 @@ def test_attention_block_layout_and_composition():
     assert np.abs(oracle.attention_block(x, w_qkv, b_qkv, w_o, b_o, 1, False) - y).max() > 1e-3
 
 
+def test_attention_group_causal_mask():
+    B, T, H, D = 2, 23, 2, 8
+    q, k, v = _qkv(B, T, H, D)
+    # groups of one token are the plain causal mask; one group holding the whole sequence is no mask
+    np.testing.assert_allclose(oracle.attention(q, k, v, 1), oracle.attention(q, k, v, True), rtol=0, atol=0)
+    for G in (T, T + 5):
+        np.testing.assert_allclose(oracle.attention(q, k, v, G), oracle.attention(q, k, v, False), rtol=0, atol=0)
+    for G in (2, 5, 8):
+        limit = np.minimum(T, (np.arange(T) // G + 1) * G)             # keys visible to query t: 0 .. limit[t] - 1
+        # equal scores: the mean of the visible value rows
+        o = oracle.attention(np.zeros_like(q), k, v, G)
+        want = np.stack([v[:, :limit[t]].mean(axis=1) for t in range(T)], axis=1)
+        np.testing.assert_allclose(o, want, rtol=0, atol=1e-14)
+        # against torch CPU float64 with the mask spelt out
+        mask = torch.from_numpy(np.arange(T)[None, :] < limit[:, None])
+        tq, tk, tv = (torch.from_numpy(a).permute(0, 2, 1, 3) for a in (q, k, v))
+        ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=float(np.float32(1 / math.sqrt(D))))
+        np.testing.assert_allclose(oracle.attention(q, k, v, G), ref.permute(0, 2, 1, 3).numpy(), rtol=1e-12, atol=1e-13)
+        # all queries of a group see the same keys, so permuting the keys inside a group changes nothing
+        perm = np.arange(T); perm[:G] = perm[:G][::-1]
+        np.testing.assert_allclose(oracle.attention(q, k[:, perm], v[:, perm], G), oracle.attention(q, k, v, G), rtol=0, atol=1e-14)
+
+
 def test_attention_rejects_bad_arguments():
     q, k, v = _qkv(1, 3, 1, 4)
     with pytest.raises(ValueError):
