@@ -165,6 +165,10 @@ fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
  *
  *     o[b,t,h,:] = sum_j softmax_j( scale * q[b,t,h,:] . k[b,j,h,:] ) * v[b,j,h,:]      (j <= t when causal)
  *
+ * The mask can also be causal over groups of G consecutive tokens: query t then sees every key of its own
+ * and of earlier groups, j < (t / G + 1) * G -- the causal mask of a sequence made of frames or patches
+ * whose tokens are not ordered among themselves.
+ *
  * The paper's task-wise analysis (Section 5.3) and its appendix on Level 3-pike and Level 5 outliers
  * name a flash-attention kernel, fused with the input and output projections and masking causally
  * without a materialised mask, as the largest recurring speedup over eager PyTorch.  Operands are
@@ -177,7 +181,7 @@ fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
  */
 typedef struct {
     int32_t dtype;         /* FLE_BF16 or FLE_F16                                                  */
-    int32_t causal;        /* 0: every key; otherwise query t sees keys 0 .. t                      */
+    int32_t causal;        /* 0: every key; 1: query t sees keys 0 .. t; G > 1: keys below (t/G + 1)*G */
     int64_t B, H, T, D;    /* batch, heads, tokens per sequence (>= 1), head dimension (64 or 128)  */
     const void *q, *k, *v; /* DEVICE, 16-byte aligned                                               */
     int64_t ldq, ldk, ldv; /* elements between consecutive tokens, >= H*D, multiples of 8           */
@@ -205,7 +209,7 @@ fle_status fle_attention_run(const fle_attention *p);
  */
 typedef struct {
     int32_t dtype;        /* FLE_BF16 or FLE_F16                                          */
-    int32_t causal;
+    int32_t causal;       /* as fle_attention.causal                                      */
     int64_t B, T, C, H;   /* C = H * D with D = 64 or 128                                 */
     const void *x;        /* DEVICE [B*T, C]                                              */
     const void *w_qkv;    /* DEVICE [3C, C]                                               */

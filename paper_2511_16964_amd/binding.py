@@ -301,7 +301,7 @@ class AttentionCall:
         if out is None:
             out = torch.empty((B, T, H, D), device=q.device, dtype=q.dtype)
         p = FleAttention()
-        p.dtype, p.causal = _dtype_code(q.dtype), 1 if causal else 0
+        p.dtype, p.causal = _dtype_code(q.dtype), int(causal)
         p.B, p.H, p.T, p.D = B, H, T, D
         p.q, p.k, p.v, p.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
         p.ldq, p.ldk, p.ldv, p.ldo = (_token_stride(t) for t in (q, k, v, out))
@@ -322,7 +322,8 @@ def attention(q, k, v, causal, scale=None, out=None):
     """Scaled dot-product attention over token-major [B,T,H,D] tensors (bf16 or fp16, D = 64 or 128).
 
     q, k, v may be views into one fused projection output (``qkv.view(B,T,3,H,D)[:, :, i]``); nothing is
-    copied or transposed.  causal: query t sees keys 0..t.  scale defaults to 1/sqrt(D).
+    copied or transposed.  causal: False / 0 no mask, True / 1 query t sees keys 0..t, G > 1 the same over
+    groups of G tokens (keys below (t // G + 1) * G).  scale defaults to 1/sqrt(D).
     """
     return AttentionCall(q, k, v, causal, scale, out).run()
 
@@ -347,7 +348,7 @@ class AttentionBlockCall:
         if out is None:
             out = torch.empty_like(x)
         p = FleAttentionBlock()
-        p.dtype, p.causal = _dtype_code(x.dtype), 1 if causal else 0
+        p.dtype, p.causal = _dtype_code(x.dtype), int(causal)
         p.B, p.T, p.C, p.H = B, T, C, int(heads)
         p.x, p.w_qkv, p.w_o, p.out = x.data_ptr(), w_qkv.data_ptr(), w_o.data_ptr(), out.data_ptr()
         p.b_qkv = None if b_qkv is None else b_qkv.data_ptr()

@@ -15,7 +15,7 @@ struct AttnArgs {
     void *o;
     int64_t ldq, ldk, ldv, ldo;  // elements between consecutive tokens
     int32_t T, H, B;
-    int32_t causal;
+    int32_t causal;     // 0: no mask; G >= 1: query t sees the keys below (t / G + 1) * G (G = 1: the plain causal mask)
     float scale_log2e;  // softmax scale times log2(e): the exponentials are taken in base 2
 };
 
@@ -113,14 +113,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 
     const char *vp = reinterpret_cast<const char *>(a.v) + (tok0 * a.ldv + col0) * 2;
     char *op = reinterpret_cast<char *>(a.o) + (tok0 * a.ldo + col0) * 2;
 
-    const int n_blocks_all = (T + BKV - 1) / BKV;
-    int n_blocks = n_blocks_all, wave_last = n_blocks_all - 1;
-    if (a.causal) {
-        const int need = (q0 + BQ - 1) / BKV + 1;
-        n_blocks = need < n_blocks_all ? need : n_blocks_all;
-        wave_last = (wq0 + WQ - 1) / BKV;
-    }
-    if (wq0 >= T) wave_last = -1;  // a wave of padding rows only keeps the barriers
+    // Keys 0 .. limit - 1 are visible to a query; limits grow with the query index, so the last query of a
+    // workgroup (of a wave) decides how many key blocks it walks and the first one whether a block needs the mask.
+    const int G = a.causal;
+    auto limit_of = [&](int query) {
+        const int lim = G ? (query / G + 1) * G : T;
+        return lim < T ? lim : T;
+    };
+    const int q_last = (q0 + BQ < T ? q0 + BQ : T) - 1, w_last = (wq0 + WQ < T ? wq0 + WQ : T) - 1;
+    const int n_blocks = (limit_of(q_last) + BKV - 1) / BKV;
+    const int wave_last = wq0 < T ? (limit_of(w_last) + BKV - 1) / BKV - 1 : -1;  // a wave of padding rows only keeps the barriers
+    const int wave_first_limit = limit_of(wq0);
+    int key_limit[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) key_limit[qt] = limit_of(wq0 + 32 * qt + l31);
 
     // Q fragments stay in registers: B operand, lane = query, 8 consecutive d per 16-wide step
     frag_t qf[QT][NC];
@@ -217,13 +223,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt) {
             if (mask) {  // diagonal and tail blocks only (uniform over the wave)
-                const int query = wq0 + 32 * qt + l31;
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = kb0 + 32 * kt + 8 * (r / 4) + 4 * h2 + (r % 4);
-                        if (key >= T || (a.causal && key > query)) s[kt][qt][r] = -INFINITY;
+                        if (key >= key_limit[qt]) s[kt][qt][r] = -INFINITY;
                     }
             }
             float mx = s[0][qt][0];
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 
         const int kb0 = j * BKV;
         // the other stage was last read before the barrier that ended the previous block
         if (j + 1 < n_blocks) copy_block(smem + (ST ^ 1) * STAGE, kb0 + BKV);
-        if (j <= wave_last) compute(stage_c, kb0, kb0 + BKV > T || (a.causal && kb0 + BKV - 1 > wq0));
+        if (j <= wave_last) compute(stage_c, kb0, kb0 + BKV > wave_first_limit);
         wait_vmcnt<0>();
         __syncthreads();
     };

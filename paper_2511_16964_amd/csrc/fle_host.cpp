@@ -381,6 +381,7 @@ static fle_status check_attention(const fle_attention *p) {
     if (p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_UNSUPPORTED, "attention takes FLE_BF16 or FLE_F16 (got dtype %d)", p->dtype);
     if (p->B < 0 || p->H < 1 || p->T < 1) return fail(FLE_ERR_SHAPE, "need B >= 0, H >= 1, T >= 1 (got %lld, %lld, %lld)", (long long)p->B, (long long)p->H, (long long)p->T);
     if (p->D != 64 && p->D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 64 or 128", (long long)p->D);
+    if (p->causal < 0) return fail(FLE_ERR_OP, "causal must be 0, 1 or a group size (got %d)", p->causal);
     if (p->B > 65535 || p->H > 65535) return fail(FLE_ERR_SHAPE, "B and H are limited to 65535");
     if (p->T > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T is limited to 2^24");
     if ((p->T + 127) / 128 * p->H * p->B >= (int64_t(1) << 31)) return fail(FLE_ERR_SHAPE, "B * H * T / 128 is limited to 2^31 workgroups");

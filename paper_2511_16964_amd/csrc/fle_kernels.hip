@@ -198,7 +198,7 @@ fle_status launch_attention(const fle_attention *p) {
     AttnArgs a;
     a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o;
     a.ldq = p->ldq; a.ldk = p->ldk; a.ldv = p->ldv; a.ldo = p->ldo;
-    a.T = int32_t(p->T); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal != 0;
+    a.T = int32_t(p->T); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal;
     const float scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(float(p->D));
     a.scale_log2e = scale * 1.44269504088896340736f;
     if (p->dtype == FLE_F16) {

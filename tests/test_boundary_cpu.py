@@ -424,6 +424,7 @@ def test_attention_validation(L):
     assert v(attention()) == OK
     assert v(attention(D=128, dtype=binding.F16, causal=0, scale=0.25)) == OK
     assert v(attention(B=0)) == OK                                   # empty batch: a no-op
+    assert v(attention(causal=0)) == OK and v(attention(causal=37)) == OK and v(attention(causal=-1)) == E_OP
     assert v(attention(dtype=binding.F32)) == E_UNSUP
     assert v(attention(D=32)) == E_UNSUP and v(attention(D=96)) == E_UNSUP
     assert v(attention(T=0)) == E_SHAPE and v(attention(H=0)) == E_SHAPE and v(attention(B=-1)) == E_SHAPE

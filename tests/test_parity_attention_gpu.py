@@ -59,6 +59,17 @@ def test_attention_many_heads(dtype, D, causal, B, H, T):
     assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype)
 
 
+@pytest.mark.parametrize("dtype,D,T,G", [
+    (BF16, 128, 300, 7), (BF16, 64, 300, 64), (F16, 128, 513, 100), (BF16, 128, 257, 128), (F16, 64, 200, 2),
+    (BF16, 64, 130, 129), (BF16, 128, 130, 1000),       # a group that holds (nearly) the whole sequence
+])
+def test_attention_group_causal(dtype, D, T, G):
+    """Causal over groups of G tokens: group edges inside, at and across the 64-key blocks and 128-query blocks."""
+    announce("attention group causal", dtype, D, T, G)
+    qkv = inputs.make_qkv(300 + G, 2, T, 3, D, dtype)
+    assert_close(run_attention(qkv, G), oracle_attention(qkv, G), dtype, "G=%d" % G)
+
+
 def test_attention_peaked_and_flat_scores():
     """Score spreads far from the N(0,1) of the workload: nearly one-hot rows (large scale) and nearly
     uniform rows (tiny scale); the running maximum must keep both finite."""
@@ -93,6 +104,8 @@ def test_attention_rejects_what_it_cannot_run():
         binding.attention(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], False)  # head dimension 32
     with pytest.raises(binding.FleError):
         binding.attention(q, k, v, False, scale=-1.0)
+    with pytest.raises(binding.FleError):
+        binding.attention(q, k, v, -3)                                     # negative group size
     with pytest.raises(binding.FleError):
         binding.attention(q, k, v, False, out=q)                           # o overlaps q
 

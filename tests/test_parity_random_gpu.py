@@ -116,7 +116,7 @@ def test_random_grouped_problem_matches_oracle(seed):
 @pytest.mark.parametrize("seed", range(60))
 def test_random_attention_matches_oracle(seed):
     """Random sequence lengths (1 .. 700, mostly ragged against the 128-query and 64-key blocks), head counts,
-    batch sizes, both head dimensions and dtypes, with and without the causal mask, default and explicit
+    batch sizes, both head dimensions and dtypes, without mask, causal and causal over groups of tokens, default and explicit
     scales, q / k / v as views of one fused buffer or as separate tensors with padded token strides."""
     import oracle
     rng = np.random.default_rng(5000 + seed)
@@ -124,7 +124,7 @@ def test_random_attention_matches_oracle(seed):
     D = [64, 128][rng.integers(0, 2)]
     T = int(rng.integers(1, 700)) if rng.random() < 0.8 else int(rng.integers(1, 6)) * 128
     B, H = int(rng.integers(1, 4)), int(rng.integers(1, 12))
-    causal = bool(rng.integers(0, 2))
+    causal = [0, 1, int(rng.integers(2, 200))][rng.integers(0, 3)]   # none, per token, per group of tokens
     scale = None if rng.random() < 0.6 else float(rng.uniform(0.02, 0.5))
     spread = float(rng.choice([0.3, 1.0, 2.5]))
     print("[case] random attention", seed, dtype, D, T, B, H, causal, scale, spread, flush=True)
