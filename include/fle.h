@@ -182,7 +182,7 @@ fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
 typedef struct {
     int32_t dtype;         /* FLE_BF16 or FLE_F16                                                  */
     int32_t causal;        /* 0: every key; 1: query t sees keys 0 .. t; G > 1: keys below (t/G + 1)*G */
-    int64_t B, H, T, D;    /* batch, heads, tokens per sequence (>= 1), head dimension (64 or 128)  */
+    int64_t B, H, T, D;    /* batch, heads, tokens per sequence (>= 1), head dimension (32, 64, 128 or 256) */
     const void *q, *k, *v; /* DEVICE, 16-byte aligned                                               */
     int64_t ldq, ldk, ldv; /* elements between consecutive tokens, >= H*D, multiples of 8           */
     void *o;               /* DEVICE, 8-byte aligned; must not overlap q, k or v                    */
@@ -210,7 +210,7 @@ fle_status fle_attention_run(const fle_attention *p);
 typedef struct {
     int32_t dtype;        /* FLE_BF16 or FLE_F16                                          */
     int32_t causal;       /* as fle_attention.causal                                      */
-    int64_t B, T, C, H;   /* C = H * D with D = 64 or 128                                 */
+    int64_t B, T, C, H;   /* C = H * D with D = 32, 64, 128 or 256                        */
     const void *x;        /* DEVICE [B*T, C]                                              */
     const void *w_qkv;    /* DEVICE [3C, C]                                               */
     const void *b_qkv;    /* DEVICE [3C] or NULL                                          */

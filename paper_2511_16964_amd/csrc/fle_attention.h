@@ -33,13 +33,15 @@ struct BufferPair {
 // rows, the same chunk of each) and the transposing V reads (32 lanes = 4 consecutive rows x 64 contiguous
 // bytes).  The first needs 16 consecutive rows to land on 16 different 16-byte positions of a 256-byte bank
 // sweep, the second needs rows r .. r + 3 (r a multiple of 4) to move a 64-byte group to 4 different groups.
-// D = 128 (a row is one sweep, 16 chunks): the two low row bits go to the two high chunk bits, the next two
-// to the low ones.  D = 64 (two rows per sweep, 8 chunks; row parity picks the half sweep): row bit 1 goes
-// to the high chunk bit, bits 2 and 3 to the low ones.
+// D >= 128 (a row is one or two sweeps): the two low row bits go to chunk bits 3 and 2, the next two to the
+// low ones.  D = 64 (two rows per sweep, 8 chunks; row parity picks the half sweep): row bit 1 goes to the
+// high chunk bit, bits 2 and 3 to the low ones.  D = 32 (four rows per sweep, a row is one 64-byte group, so
+// the V reads need nothing): row bits 2 and 3 pick among the four chunks.
 template <int D>
 __device__ __forceinline__ int lds_swizzle(int row) {
-    if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-    else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    if constexpr (D >= 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    else if constexpr (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    else return (row >> 2) & 3;
 }
 
 // Everything is computed transposed, so that a lane owns one query:
@@ -66,13 +68,13 @@ __device__ __forceinline__ int lds_swizzle(int row) {
 // of V over all banks.  With the causal mask a wave stops computing at its last visible block and only keeps
 // the barriers; the mask itself is applied on the diagonal and tail blocks only.
 //
-// The kernel states the occupancy it is built for (two waves per SIMD at D = 128, three at D = 64): left to
+// The kernel states the occupancy it is built for (one wave per SIMD at D = 256, two at 128, three below): left to
 // itself the register allocator aims one step higher, caps the ordinary VGPRs accordingly and parks the
 // output accumulators in AGPRs, copying all of them in and out on every trip of the loop.
 template <int DT, int D, int QT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 3, D == 128 ? 2 : 3))) void flash_attention(const AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 256 ? 1 : D == 128 ? 2 : 3, D == 256 ? 1 : D == 128 ? 2 : 3))) void flash_attention(const AttnArgs a) {
     static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte dtypes only");
-    static_assert(D == 64 || D == 128, "head dimension 64 or 128");
+    static_assert(D == 32 || D == 64 || D == 128 || D == 256, "head dimension 32, 64, 128 or 256");
     using frag_t = typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type;
     constexpr int BKV = 64, WQ = 32 * QT, BQ = 4 * WQ;
     constexpr int NC = D / 16, ND = D / 32, RB = D * 2, CPR = D / 8;

@@ -380,7 +380,7 @@ static fle_status check_attention(const fle_attention *p) {
     if (!p) return fail(FLE_ERR_NULL, "attention problem is NULL");
     if (p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_UNSUPPORTED, "attention takes FLE_BF16 or FLE_F16 (got dtype %d)", p->dtype);
     if (p->B < 0 || p->H < 1 || p->T < 1) return fail(FLE_ERR_SHAPE, "need B >= 0, H >= 1, T >= 1 (got %lld, %lld, %lld)", (long long)p->B, (long long)p->H, (long long)p->T);
-    if (p->D != 64 && p->D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 64 or 128", (long long)p->D);
+    if (p->D != 32 && p->D != 64 && p->D != 128 && p->D != 256) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 32, 64, 128 or 256", (long long)p->D);
     if (p->causal < 0) return fail(FLE_ERR_OP, "causal must be 0, 1 or a group size (got %d)", p->causal);
     if (p->B > 65535 || p->H > 65535) return fail(FLE_ERR_SHAPE, "B and H are limited to 65535");
     if (p->T > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T is limited to 2^24");
@@ -457,7 +457,7 @@ static fle_status plan_block(const fle_attention_block *p, BlockParts *bp) {
     po.ops = bp->out_ops; po.n_ops = n;
     po.stream = p->stream;
 
-    if (D != 64 && D != 128) return fail(FLE_ERR_UNSUPPORTED, "head dimension C / H = %lld is not 64 or 128", (long long)D);
+    if (D != 32 && D != 64 && D != 128 && D != 256) return fail(FLE_ERR_UNSUPPORTED, "head dimension C / H = %lld is not 32, 64, 128 or 256", (long long)D);
     if (rows > 0 && (!p->x || !p->w_qkv || !p->w_o || !p->out)) return fail(FLE_ERR_NULL, "x, w_qkv, w_o or out is NULL");
     if (rows > 0) {
         // the output projection checks out against its own operands; the first stage's are checked here

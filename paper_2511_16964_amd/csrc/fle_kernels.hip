@@ -187,7 +187,7 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
 
 template <int DT, int D>
 static void launch_attention_dt(const fle_attention *p, const AttnArgs &a, hipStream_t stream) {
-    // One query tile per wave, 128 queries per workgroup: two (D = 128) or three (D = 64) waves per SIMD, so
+    // One query tile per wave, 128 queries per workgroup: two (D = 128) or three (D <= 64) waves per SIMD, so
     // that one wave's softmax arithmetic runs under another's MFMAs.  Two tiles per wave halve the LDS reads
     // per MFMA but leave one wave per SIMD at D = 128, and measured 10 - 35 % slower there (equal at D = 64).
     hipLaunchKernelGGL((flash_attention<DT, D, 1>), dim3(uint32_t((p->T + 127) / 128 * p->H * p->B)), dim3(256), 0, stream, a);
@@ -201,12 +201,12 @@ fle_status launch_attention(const fle_attention *p) {
     a.T = int32_t(p->T); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal;
     const float scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(float(p->D));
     a.scale_log2e = scale * 1.44269504088896340736f;
-    if (p->dtype == FLE_F16) {
-        if (p->D == 64) launch_attention_dt<FLE_F16, 64>(p, a, stream);
-        else launch_attention_dt<FLE_F16, 128>(p, a, stream);
-    } else {
-        if (p->D == 64) launch_attention_dt<FLE_BF16, 64>(p, a, stream);
-        else launch_attention_dt<FLE_BF16, 128>(p, a, stream);
+    const bool f16 = p->dtype == FLE_F16;
+    switch (p->D) {
+    case 32: f16 ? launch_attention_dt<FLE_F16, 32>(p, a, stream) : launch_attention_dt<FLE_BF16, 32>(p, a, stream); break;
+    case 64: f16 ? launch_attention_dt<FLE_F16, 64>(p, a, stream) : launch_attention_dt<FLE_BF16, 64>(p, a, stream); break;
+    case 128: f16 ? launch_attention_dt<FLE_F16, 128>(p, a, stream) : launch_attention_dt<FLE_BF16, 128>(p, a, stream); break;
+    default: f16 ? launch_attention_dt<FLE_F16, 256>(p, a, stream) : launch_attention_dt<FLE_BF16, 256>(p, a, stream); break;
     }
     return check_launch("flash_attention");
 }

@@ -426,7 +426,8 @@ def test_attention_validation(L):
     assert v(attention(B=0)) == OK                                   # empty batch: a no-op
     assert v(attention(causal=0)) == OK and v(attention(causal=37)) == OK and v(attention(causal=-1)) == E_OP
     assert v(attention(dtype=binding.F32)) == E_UNSUP
-    assert v(attention(D=32)) == E_UNSUP and v(attention(D=96)) == E_UNSUP
+    assert v(attention(D=16)) == E_UNSUP and v(attention(D=96)) == E_UNSUP and v(attention(D=512)) == E_UNSUP
+    assert v(attention(D=32)) == OK and v(attention(D=256, H=2)) == OK
     assert v(attention(T=0)) == E_SHAPE and v(attention(H=0)) == E_SHAPE and v(attention(B=-1)) == E_SHAPE
     assert v(attention(ld=4 * 64 - 8)) == E_SHAPE                    # token stride below H*D
     assert v(attention(ld=3 * 256 + 4)) == E_ALIGN                   # not a multiple of 8 elements
@@ -454,7 +455,7 @@ def test_attention_block_validation_and_workspace(L):
     v = lambda p: L.fle_attention_block_validate(ctypes.byref(p))
     assert v(attention_block()) == OK
     assert v(attention_block(C=250)) == E_SHAPE                      # C not a multiple of H
-    assert v(attention_block(C=128, H=4)) == E_UNSUP                 # head dimension 32
+    assert v(attention_block(C=64, H=4)) == E_UNSUP                  # head dimension 16
     assert v(attention_block(dtype=binding.F32)) == E_UNSUP
     p = attention_block(); p.w_o = None
     assert v(p) == E_NULL

@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2511_16964_amd import binding, inputs
 
-from parity import BLOCK_FACTOR, assert_close
+from parity import BLOCK_FACTOR, assert_close, value_scale
 
 pytestmark = pytest.mark.gpu
 
@@ -34,14 +34,14 @@ def oracle_attention(qkv, causal, scale=None, first_query=0):
 
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [32, 64, 128, 256])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("T", [1, 2, 31, 64, 65, 128, 129, 200, 257, 333])
 def test_attention_small(dtype, D, causal, T):
     """One to three workgroups per head along the queries, ragged key blocks, several heads and batches."""
     announce("attention small", dtype, D, causal, T)
     qkv = inputs.make_qkv(100 + T, 2, T, 3, D, dtype)
-    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, "T=%d" % T)
+    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, "T=%d" % T, s=value_scale(qkv[:, :, 2]))
 
 
 @pytest.mark.parametrize("dtype,D,causal,B,H,T", [
@@ -52,11 +52,13 @@ def test_attention_small(dtype, D, causal, T):
     (BF16, 64, True, 3, 7, 400),      # a head count that is not a multiple of 8 (plain work order)
     (BF16, 128, True, 1, 24, 1100),   # 3 heads per XCD, fewer than a head group
     (BF16, 64, False, 5, 16, 260),    # 10 heads per XCD: a full group of 8 and a rest of 2
+    (BF16, 32, True, 4, 24, 600),     # head dimension 32: a K / V row is a quarter of a bank sweep
+    (F16, 256, True, 2, 16, 700),     # head dimension 256: one workgroup per CU
 ])
 def test_attention_many_heads(dtype, D, causal, B, H, T):
     announce("attention wide", dtype, D, causal, B, H, T)
     qkv = inputs.make_qkv(7, B, T, H, D, dtype)
-    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype)
+    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, s=value_scale(qkv[:, :, 2]))
 
 
 @pytest.mark.parametrize("dtype,D,T,G", [
@@ -67,7 +69,7 @@ def test_attention_group_causal(dtype, D, T, G):
     """Causal over groups of G tokens: group edges inside, at and across the 64-key blocks and 128-query blocks."""
     announce("attention group causal", dtype, D, T, G)
     qkv = inputs.make_qkv(300 + G, 2, T, 3, D, dtype)
-    assert_close(run_attention(qkv, G), oracle_attention(qkv, G), dtype, "G=%d" % G)
+    assert_close(run_attention(qkv, G), oracle_attention(qkv, G), dtype, "G=%d" % G, s=value_scale(qkv[:, :, 2]))
 
 
 def test_attention_peaked_and_flat_scores():
@@ -78,7 +80,7 @@ def test_attention_peaked_and_flat_scores():
         qkv = inputs.make_qkv(11, 2, 190, 2, 64, BF16, spread)
         got = run_attention(qkv, True, scale)
         assert torch.isfinite(got.float()).all()
-        assert_close(got, oracle_attention(qkv, True, scale), BF16)
+        assert_close(got, oracle_attention(qkv, True, scale), BF16, s=value_scale(qkv[:, :, 2]))
 
 
 def test_attention_separate_tensors_and_out():
@@ -90,7 +92,7 @@ def test_attention_separate_tensors_and_out():
     buf = torch.zeros(B, T, 2, H, D, device=DEV, dtype=BF16)
     binding.attention(q, k, v, False, out=buf[:, :, 1])
     torch.cuda.synchronize()
-    assert_close(buf[:, :, 1].cpu(), oracle_attention(qkv, False), BF16)
+    assert_close(buf[:, :, 1].cpu(), oracle_attention(qkv, False), BF16, s=value_scale(qkv[:, :, 2]))
     assert (buf[:, :, 0] == 0).all()
 
 
@@ -99,9 +101,9 @@ def test_attention_rejects_what_it_cannot_run():
     q, k, v = qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2]
     with pytest.raises(binding.FleError):
         binding.attention(q.float(), k.float(), v.float(), False)          # fp32
-    bad = inputs.make_qkv(1, 1, 8, 1, 32, BF16).to(DEV)
+    bad = inputs.make_qkv(1, 1, 8, 1, 16, BF16).to(DEV)
     with pytest.raises(binding.FleError):
-        binding.attention(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], False)  # head dimension 32
+        binding.attention(bad[:, :, 0], bad[:, :, 1], bad[:, :, 2], False)  # head dimension 16
     with pytest.raises(binding.FleError):
         binding.attention(q, k, v, False, scale=-1.0)
     with pytest.raises(binding.FleError):
@@ -130,6 +132,8 @@ def oracle_block(ap):
     (BF16, 3, 77, 512, 8, False, True, False),
     (F16, 2, 130, 384, 3, True, False, True),
     (BF16, 1, 1, 128, 2, True, True, True),
+    (BF16, 2, 150, 256, 8, True, True, True),     # head dimension 32
+    (F16, 1, 260, 512, 2, False, True, False),    # head dimension 256
 ])
 def test_attention_block_small(dtype, B, T, C, heads, causal, bias, residual):
     announce("attention block", dtype, B, T, C, heads, causal, bias, residual)

@@ -8,7 +8,7 @@ import torch
 
 from paper_2511_16964_amd import inputs
 
-from parity import BLOCK_FACTOR, assert_close, make_call, oracle_rows, run_gpu, sample_rows
+from parity import BLOCK_FACTOR, assert_close, value_scale, make_call, oracle_rows, run_gpu, sample_rows
 
 pytestmark = pytest.mark.gpu
 BF16 = torch.bfloat16
@@ -143,4 +143,4 @@ def test_a1_attention_block_fullsize_sampled_tokens():
     torch.cuda.synchronize()
     sub = f64(qkv[b:b + 1][:, :, :, heads].cpu())
     ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], True, first_query=first)
-    assert_close(got[b:b + 1, first:][:, :, heads].cpu(), ref, ap.dtype, "a1 attention, last queries")
+    assert_close(got[b:b + 1, first:][:, :, heads].cpu(), ref, ap.dtype, "a1 attention, last queries", s=value_scale(qkv[:, :, 2]))
