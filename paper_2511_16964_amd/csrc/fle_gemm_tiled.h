@@ -48,17 +48,19 @@ struct TileLoader {
         chunk_even = lp ^ lr ^ p0;
         row_step = 8 * ldb;
     }
-    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at byte column k0.
+    // Copy instruction j (8 rows x 128 bytes) of this wave's quarter of the tile at byte column k0.  k0 travels
+    // as the instruction's scalar offset, so the per-lane offset does not change from one K step to the next
+    // and the main loop spends no vector ALU work on addresses.
     __device__ __forceinline__ void issue_one(char *lds, uint32_t k0, int j) const {
-        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, AUX);
+        const uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, k0, 0, AUX);
     }
     // Same for the last, partial K step: chunks at or beyond `valid` (= remaining row bytes / 16) get
     // an out-of-range offset, for which the buffer load delivers zeros.
     __device__ __forceinline__ void issue_one_tail(char *lds, uint32_t k0, int j, int valid) const {
-        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step + k0;
+        uint32_t voff = ((j & 1) ? off_odd : off_even) + uint32_t(j) * row_step;
         if ((chunk_even ^ (j & 1)) >= valid) voff = 0x80000000u;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, 0, 0, AUX);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(lds + (wave * (ROWS / 4) + j * 8) * 128), 16, voff, k0, 0, AUX);
     }
     __device__ __forceinline__ void issue(char *lds, uint32_t k0, int valid) const {
 #pragma unroll
@@ -280,9 +282,10 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     // next, slice (KK + 1) & 3 of the stage at (rW, rX), into the other buffer, and (HALF = 1 or 2) the first
     // or second half of the copy instructions of one K step into the stage at (iW, iX) (masked to the valid
     // chunks when that is the partial last step).
-    auto slice = [&](auto kk_c, auto read_c, auto half_c, const char *sW, const char *sX, const char *rW, const char *rX,
+    auto slice = [&](auto kk_c, auto read_c, auto half_c, auto full_c, const char *sW, const char *sX, const char *rW, const char *rX,
                      char *iW, char *iX, uint32_t ik0, int valid) {
         constexpr int KK = decltype(kk_c)::value, HALF = decltype(half_c)::value;
+        constexpr bool FULL = decltype(full_c)::value;  // the copied step is known to be a whole one: no masking of chunks
         constexpr bool READ = decltype(read_c)::value;
         constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
         constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
@@ -297,8 +300,13 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             }
             if (HALF != 0 && q % QV == (QV > 1 ? 1 : 0)) {
                 const int idx = (HALF - 1) * NVM + q / QV;
-                if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
-                else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                if constexpr (FULL) {
+                    if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                    else ldx_.issue_one(iX, ik0, idx - NIW);
+                } else {
+                    if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                    else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (F32) {
@@ -354,28 +362,33 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     // One K step: MORE: a next step exists (second half of its copies in slice 0, wait and barrier before
     // slice 3, its first fragments read in slice 3); MORE2: so does the one after it (first half of its copies
     // in slice 3).  The flags are compile-time so that the loop body is one straight-line sequence.
-    auto k_step = [&](int kt, auto more_c, auto more2_c) {
+    auto k_step = [&](int kt, auto more_c, auto more2_c, auto full_c) {
         constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
         char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;        // the stage being multiplied
         char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;  // the stage of the next step
-        slice(I0{}, std::true_type{}, std::integral_constant<int, MORE ? 2 : 0>{}, cW, cX, cW, cX, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
-        slice(I1{}, std::true_type{}, I0{}, cW, cX, cW, cX, nW, nX, 0u, 8);
-        slice(I2{}, std::true_type{}, I0{}, cW, cX, cW, cX, nW, nX, 0u, 8);
+        slice(I0{}, std::true_type{}, std::integral_constant<int, MORE ? 2 : 0>{}, full_c, cW, cX, cW, cX, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+        slice(I1{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
+        slice(I2{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
         if constexpr (MORE) {
             wait_vmcnt<0>();                          // this wave's copies of the next stage have landed ...
             __builtin_amdgcn_s_waitcnt(0xC07F);       // ... and its last fragment reads of this stage have returned
             __builtin_amdgcn_s_barrier();             // everyone's have: the next stage is complete, this one is free
         }
-        slice(I3{}, std::integral_constant<bool, MORE>{}, std::integral_constant<int, MORE2 ? 1 : 0>{}, cW, cX, nW, nX, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
+        slice(I3{}, std::integral_constant<bool, MORE>{}, std::integral_constant<int, MORE2 ? 1 : 0>{}, full_c, cW, cX, nW, nX, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
     };
     {
         int kt = kb;
-        for (; kt + 2 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{});
-        if (kt + 1 < ke) {
-            k_step(kt, std::true_type{}, std::false_type{});
+        // steps whose copies (for steps kt + 1 and kt + 2) cannot touch the last, possibly partial K step
+        for (; kt + 3 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{}, std::true_type{});
+        if (kt + 2 < ke) {
+            k_step(kt, std::true_type{}, std::true_type{}, std::false_type{});
             ++kt;
         }
-        k_step(kt, std::false_type{}, std::false_type{});
+        if (kt + 1 < ke) {
+            k_step(kt, std::true_type{}, std::false_type{}, std::false_type{});
+            ++kt;
+        }
+        k_step(kt, std::false_type{}, std::false_type{}, std::false_type{});
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;
