@@ -65,7 +65,7 @@ def _load():
             ctypes.POINTER(_Op), ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32]
         lib.fle_oracle_attention.restype = ctypes.c_int
         lib.fle_oracle_attention.argtypes = [
-            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_int32, ctypes.c_double, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]
         lib.fle_oracle_threads.restype = ctypes.c_int
@@ -171,8 +171,9 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0
 def attention(q, k, v, causal, scale=None, n_threads: int = 0, first_query: int = 0) -> np.ndarray:
     """float64 gold result of scaled dot-product attention, token-major.
 
-    q, k, v: [B, T, H, D] float64 (any strides whose last two axes are contiguous, so the three
-    thirds of a fused QKV projection's output can be passed as views); scale defaults to
+    q: [B, T, H, D], k and v: [B, Tk, H, D] float64 (views are accepted, e.g. the three thirds of a
+    fused QKV projection's output).  With Tk != T and a causal mask the queries are the last T of
+    the Tk positions (query t stands at position t + Tk - T; needs Tk >= T). scale defaults to
     1/sqrt(D) and is rounded to fp32 as it is when it crosses the GPU boundary.  causal: False / 0:
     every key; True / 1: query t sees keys 0..t only; G > 1: the same over groups of G consecutive
     tokens, query t sees keys 0 .. (t // G + 1) * G - 1 (the mask the paper's attention solutions
@@ -180,17 +181,19 @@ def attention(q, k, v, causal, scale=None, n_threads: int = 0, first_query: int 
     evaluated (against all their keys) and [B, T - t0, H, D] is returned.
     """
     q, k, v = (np.asarray(a) for a in (q, k, v))
-    if q.ndim != 4 or q.shape != k.shape or q.shape != v.shape:
-        raise ValueError("q, k, v must be [B,T,H,D] of one shape")
+    if q.ndim != 4 or k.ndim != 4 or k.shape != v.shape or q.shape[0] != k.shape[0] or q.shape[2:] != k.shape[2:]:
+        raise ValueError("q must be [B,T,H,D] and k, v [B,Tk,H,D]")
     for a in (q, k, v):
         if a.dtype != np.float64:
             raise TypeError("the oracle takes float64 arrays only")
     B, T, H, D = q.shape
-    q2, k2, v2 = (np.ascontiguousarray(a).reshape(B * T, H * D) for a in (q, k, v))
+    Tk = k.shape[1]
+    q2 = np.ascontiguousarray(q).reshape(B * T, H * D)
+    k2, v2 = (np.ascontiguousarray(a).reshape(B * Tk, H * D) for a in (k, v))
     sc = float(np.float32(1.0 / np.sqrt(D) if scale is None else scale))
     out = np.full((B * T, H * D), np.nan, dtype=np.float64)
     rc = _load().fle_oracle_attention(
-        B, H, T, D, q2.ctypes.data, H * D, k2.ctypes.data, H * D, v2.ctypes.data, H * D,
+        B, H, T, Tk, D, q2.ctypes.data, H * D, k2.ctypes.data, H * D, v2.ctypes.data, H * D,
         int(causal), sc, out.ctypes.data, H * D, int(first_query), int(n_threads))
     if rc != 0:
         raise ValueError("fle_oracle_attention rejected the arguments (code %d)" % rc)

@@ -197,15 +197,20 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
  *
  * causal = 1 allows keys j <= t only; causal = G > 1 is the same mask over groups of G consecutive
  * tokens (query t sees every key of its own and of earlier groups: j < (t / G + 1) * G), the form a
- * causal mask takes when a sequence is made of frames or patches that are not ordered internally.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d],
- * likewise k, v and o.  Only queries t >= t_first are evaluated (the other rows of o are left
+ * causal mask takes when a sequence is made of frames or patches that are not ordered internally.
+ * There are T queries and Tk keys per sequence; with a causal mask the queries are the last T of
+ * the Tk positions (query t stands at position t + Tk - T, as when earlier keys are kept from
+ * previous calls), which needs Tk >= T.  Element (b,t,h,d) of q lives at q[(b*T + t)*ldq + h*D + d]
+ * and likewise o; element (b,j,h,d) of k at k[(b*Tk + j)*ldk + h*D + d], likewise v.
+ * Only queries t >= t_first are evaluated (the other rows of o are left
  * untouched), so that a few rows of a long sequence can be checked without computing all of them.
  * Returns 0, or a negative code for bad arguments / -5 out of memory.
  */
-int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const double *q, int64_t ldq,
+int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t Tk, int64_t D, const double *q, int64_t ldq,
                          const double *k, int64_t ldk, const double *v, int64_t ldv, int32_t causal,
                          double scale, double *o, int64_t ldo, int64_t t_first, int32_t threads) {
-    if (B < 0 || H < 1 || T < 1 || D < 1 || t_first < 0 || t_first > T || causal < 0) return -1;
+    if (B < 0 || H < 1 || T < 1 || Tk < 1 || D < 1 || t_first < 0 || t_first > T || causal < 0) return -1;
+    if (causal && Tk < T) return -1;
     if (!q || !k || !v || !o) return -2;
     if (ldq < H * D || ldk < H * D || ldv < H * D || ldo < H * D) return -3;
     int failed = 0;
@@ -216,7 +221,7 @@ int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const doubl
 #endif
 #pragma omp parallel
     {
-        double *s = (double *)malloc(sizeof(double) * (size_t)T);
+        double *s = (double *)malloc(sizeof(double) * (size_t)Tk);
         if (!s) {
 #pragma omp atomic write
             failed = 1;
@@ -225,12 +230,13 @@ int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const doubl
         for (int64_t b = 0; b < B; ++b)
             for (int64_t t = t_first; t < T; ++t) {
                 if (!s) continue;
-                int64_t keys = T;
-                if (causal && (t / causal + 1) * (int64_t)causal < T) keys = (t / causal + 1) * (int64_t)causal;
+                int64_t keys = Tk;
+                const int64_t pos = t + Tk - T;
+                if (causal && (pos / causal + 1) * (int64_t)causal < Tk) keys = (pos / causal + 1) * (int64_t)causal;
                 for (int64_t h = 0; h < H; ++h) {
                     const double *qr = q + (b * T + t) * ldq + h * D;
                     for (int64_t j = 0; j < keys; ++j) {
-                        const double *kr = k + (b * T + j) * ldk + h * D;
+                        const double *kr = k + (b * Tk + j) * ldk + h * D;
                         double acc = 0.0;
                         for (int64_t d = 0; d < D; ++d) acc += qr[d] * kr[d];
                         s[j] = scale * acc;
@@ -245,7 +251,7 @@ int fle_oracle_attention(int64_t B, int64_t H, int64_t T, int64_t D, const doubl
                     for (int64_t d = 0; d < D; ++d) orow[d] = 0.0;
                     for (int64_t j = 0; j < keys; ++j) {
                         const double p = s[j] / sum;
-                        const double *vr = v + (b * T + j) * ldv + h * D;
+                        const double *vr = v + (b * Tk + j) * ldv + h * D;
                         for (int64_t d = 0; d < D; ++d) orow[d] += p * vr[d];
                     }
                 }

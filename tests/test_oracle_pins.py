@@ -474,10 +474,39 @@ def test_attention_group_causal_mask():
         np.testing.assert_allclose(oracle.attention(q, k[:, perm], v[:, perm], G), oracle.attention(q, k, v, G), rtol=0, atol=1e-14)
 
 
+def test_attention_with_more_keys_than_queries():
+    B, T, Tk, H, D = 2, 5, 12, 2, 8
+    q, _, _ = _qkv(B, T, H, D)
+    _, k, v = _qkv(B, Tk, H, D)
+    # no mask: each query is its own problem, so any subset of the queries of a square problem agrees with it
+    qq = RNG.standard_normal((B, Tk, H, D))
+    full = oracle.attention(qq, k, v, False)
+    np.testing.assert_allclose(oracle.attention(qq[:, 3:8], k, v, False), full[:, 3:8], rtol=0, atol=0)
+    # causal: the queries are the last T positions, so they equal the last T rows of the square causal problem
+    full = oracle.attention(qq, k, v, True)
+    np.testing.assert_allclose(oracle.attention(qq[:, Tk - T:], k, v, True), full[:, Tk - T:], rtol=0, atol=0)
+    for G in (3, 4):
+        full = oracle.attention(qq, k, v, G)
+        np.testing.assert_allclose(oracle.attention(qq[:, Tk - T:], k, v, G), full[:, Tk - T:], rtol=0, atol=0)
+    # equal scores: mean of the visible values; the first of the T queries stands at position Tk - T
+    o = oracle.attention(np.zeros((B, T, H, D)), k, v, True)
+    want = np.stack([v[:, :Tk - T + t + 1].mean(axis=1) for t in range(T)], axis=1)
+    np.testing.assert_allclose(o, want, rtol=0, atol=1e-14)
+    # against torch CPU float64 with the mask spelt out (one query, the decoding case, included)
+    for Tq in (1, T):
+        qs = q[:, :Tq]
+        mask = torch.from_numpy(np.arange(Tk)[None, :] <= (np.arange(Tq) + Tk - Tq)[:, None])
+        tq, tk, tv = (torch.from_numpy(a).permute(0, 2, 1, 3) for a in (qs, k, v))
+        ref = F.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=float(np.float32(1 / math.sqrt(D))))
+        np.testing.assert_allclose(oracle.attention(qs, k, v, True), ref.permute(0, 2, 1, 3).numpy(), rtol=1e-12, atol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.attention(qq, k[:, :4], v[:, :4], True)        # causal with fewer keys than queries
+
+
 def test_attention_rejects_bad_arguments():
     q, k, v = _qkv(1, 3, 1, 4)
     with pytest.raises(ValueError):
-        oracle.attention(q, k[:, :2], v, False)
+        oracle.attention(q, k[:, :2], v, False)                  # k and v differ in length
     with pytest.raises(TypeError):
         oracle.attention(q.astype(np.float32), k, v, False)
     with pytest.raises(ValueError):
