@@ -182,13 +182,21 @@ fle_status fle_run_grouped(const fle_problem *p, const fle_groups *g);
 typedef struct {
     int32_t dtype;         /* FLE_BF16 or FLE_F16                                                  */
     int32_t causal;        /* 0: every key; 1: query t sees keys 0 .. t; G > 1: keys below (t/G + 1)*G */
-    int64_t B, H, T, D;    /* batch, heads, tokens per sequence (>= 1), head dimension (32, 64, 128 or 256) */
+    int64_t B, H, T, D;    /* batch, heads, queries per sequence (>= 1), head dimension (32, 64, 128 or 256) */
     const void *q, *k, *v; /* DEVICE, 16-byte aligned                                               */
     int64_t ldq, ldk, ldv; /* elements between consecutive tokens, >= H*D, multiples of 8           */
     void *o;               /* DEVICE, 8-byte aligned; must not overlap q, k or v                    */
     int64_t ldo;           /* >= H*D, a multiple of 4                                               */
     float scale;           /* > 0, or 0 for 1/sqrt(D)                                               */
     void *stream;          /* hipStream_t (NULL = the default stream)                               */
+    int64_t Tk;            /* keys per sequence, or 0 for T.  Under a mask the queries are the last
+                              T of the Tk positions (query t stands at t + Tk - T; needs Tk >= T),
+                              the case of keys kept from earlier calls                               */
+    int64_t sbq, sbk, sbv, sbo; /* elements between consecutive sequences, or 0 for packed
+                              sequences (T*ldq, Tk*ldk, Tk*ldv, T*ldo).  Same multiples as the token
+                              strides.  Either the sequences follow each other (stride >= one
+                              sequence's extent) or the tokens of all sequences interleave
+                              (sequence-first layouts: token stride >= B sequence strides)           */
 } fle_attention;
 
 /* Host only (no HIP call): checks everything fle_attention_run checks. */

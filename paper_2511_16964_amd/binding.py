@@ -53,7 +53,8 @@ class FleAttention(ctypes.Structure):
                 ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("ldq", ctypes.c_int64), ("ldk", ctypes.c_int64), ("ldv", ctypes.c_int64),
                 ("o", ctypes.c_void_p), ("ldo", ctypes.c_int64), ("scale", ctypes.c_float),
-                ("stream", ctypes.c_void_p)]
+                ("stream", ctypes.c_void_p), ("Tk", ctypes.c_int64),
+                ("sbq", ctypes.c_int64), ("sbk", ctypes.c_int64), ("sbv", ctypes.c_int64), ("sbo", ctypes.c_int64)]
 
 
 class FleAttentionBlock(ctypes.Structure):
@@ -279,20 +280,20 @@ def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="
     return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, split=split).run()
 
 
-def _token_stride(t):
-    """[B,T,H,D] view whose (h, d) axes are packed and whose batch axis continues the token axis."""
+def _strides(t):
+    """(token stride, sequence stride) of a [B,T,H,D] view whose (h, d) axes are packed."""
     B, T, H, D = t.shape
-    if t.stride(3) != 1 or t.stride(2) != D or (B > 1 and t.stride(0) != T * t.stride(1)):
-        raise ValueError("q, k, v, o must be token-major [B,T,H,D] views: unit stride along D, D along H, one stride per token")
-    return t.stride(1)
+    if (D > 1 and t.stride(3) != 1) or (H > 1 and t.stride(2) != D):
+        raise ValueError("q, k, v, o must be [B,T,H,D] views with unit stride along D and stride D along H")
+    return t.stride(1) if T > 1 else H * D, t.stride(0) if B > 1 else 0
 
 
 class AttentionCall:
     """A marshalled fle_attention bound to its tensors; ``run()`` enqueues it on the current stream."""
 
     def __init__(self, q, k, v, causal, scale=None, out=None):
-        if q.dim() != 4 or q.shape != k.shape or q.shape != v.shape:
-            raise ValueError("q, k, v must be [B,T,H,D] of one shape")
+        if q.dim() != 4 or k.dim() != 4 or k.shape != v.shape or q.shape[0] != k.shape[0] or q.shape[2:] != k.shape[2:]:
+            raise ValueError("q must be [B,T,H,D] and k, v [B,Tk,H,D]")
         if not (q.is_cuda and k.is_cuda and v.is_cuda):
             raise RuntimeError("attention runs on the GPU only; there is no CPU path")
         if k.dtype != q.dtype or v.dtype != q.dtype:
@@ -302,9 +303,9 @@ class AttentionCall:
             out = torch.empty((B, T, H, D), device=q.device, dtype=q.dtype)
         p = FleAttention()
         p.dtype, p.causal = _dtype_code(q.dtype), int(causal)
-        p.B, p.H, p.T, p.D = B, H, T, D
+        p.B, p.H, p.T, p.D, p.Tk = B, H, T, D, k.shape[1]
         p.q, p.k, p.v, p.o = q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr()
-        p.ldq, p.ldk, p.ldv, p.ldo = (_token_stride(t) for t in (q, k, v, out))
+        (p.ldq, p.sbq), (p.ldk, p.sbk), (p.ldv, p.sbv), (p.ldo, p.sbo) = (_strides(t) for t in (q, k, v, out))
         p.scale = 0.0 if scale is None else float(scale)
         self._keep = (q, k, v)
         self.out, self._p, self._pref, self._dev = out, p, ctypes.byref(p), q.device.index
@@ -319,9 +320,10 @@ class AttentionCall:
 
 
 def attention(q, k, v, causal, scale=None, out=None):
-    """Scaled dot-product attention over token-major [B,T,H,D] tensors (bf16 or fp16, D = 64 or 128).
+    """Scaled dot-product attention over [B,T,H,D] queries and [B,Tk,H,D] keys / values (bf16 or fp16, D = 32 .. 256).
 
-    q, k, v may be views into one fused projection output (``qkv.view(B,T,3,H,D)[:, :, i]``); nothing is
+    q, k, v may be views into one fused projection output (``qkv.view(B,T,3,H,D)[:, :, i]``) or views of
+    sequence-first tensors (``x.view(T,B,H,D).transpose(0,1)``): any token and sequence strides; nothing is
     copied or transposed.  causal: False / 0 no mask, True / 1 query t sees keys 0..t, G > 1 the same over
     groups of G tokens (keys below (t // G + 1) * G).  scale defaults to 1/sqrt(D).
     """

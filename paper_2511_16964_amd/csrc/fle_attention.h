@@ -14,7 +14,8 @@ struct AttnArgs {
     const void *q, *k, *v;
     void *o;
     int64_t ldq, ldk, ldv, ldo;  // elements between consecutive tokens
-    int32_t T, H, B;
+    int64_t sbq, sbk, sbv, sbo;  // elements between consecutive sequences
+    int32_t T, Tk, H, B;         // queries and keys per sequence, heads, sequences
     int32_t causal;     // 0: no mask; G >= 1: query t sees the keys below (t / G + 1) * G (G = 1: the plain causal mask)
     float scale_log2e;  // softmax scale times log2(e): the exponentials are taken in base 2
 };
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 256 ? 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, h2 = lane >> 5;
-    const int T = a.T;
+    const int T = a.T, Tk = a.Tk;
     const int n_qb = (T + BQ - 1) / BQ;
     // Workgroup -> (sequence and head, query block).  Consecutive workgroups go to the 8 XCDs in turn, so
     // workgroup L is the (L / 8)-th one of XCD L % 8.  An XCD takes consecutive heads whole (every query block
@@ -108,19 +109,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 256 ? 
     }
     const int qb = a.causal ? n_qb - 1 - qi : qi;
     const int q0 = qb * BQ, wq0 = q0 + wave * WQ;
-    const int64_t tok0 = int64_t(head / a.H) * T;
+    const int64_t seq = head / a.H;
     const int64_t col0 = int64_t(head % a.H) * D;
-    const char *qp = reinterpret_cast<const char *>(a.q) + (tok0 * a.ldq + col0) * 2;
-    const char *kp = reinterpret_cast<const char *>(a.k) + (tok0 * a.ldk + col0) * 2;
-    const char *vp = reinterpret_cast<const char *>(a.v) + (tok0 * a.ldv + col0) * 2;
-    char *op = reinterpret_cast<char *>(a.o) + (tok0 * a.ldo + col0) * 2;
+    const char *qp = reinterpret_cast<const char *>(a.q) + (seq * a.sbq + col0) * 2;
+    const char *kp = reinterpret_cast<const char *>(a.k) + (seq * a.sbk + col0) * 2;
+    const char *vp = reinterpret_cast<const char *>(a.v) + (seq * a.sbv + col0) * 2;
+    char *op = reinterpret_cast<char *>(a.o) + (seq * a.sbo + col0) * 2;
 
     // Keys 0 .. limit - 1 are visible to a query; limits grow with the query index, so the last query of a
     // workgroup (of a wave) decides how many key blocks it walks and the first one whether a block needs the mask.
+    // Under a mask the T queries stand at the last T of the Tk key positions.
     const int G = a.causal;
     auto limit_of = [&](int query) {
-        const int lim = G ? (query / G + 1) * G : T;
-        return lim < T ? lim : T;
+        const int lim = G ? ((query + Tk - T) / G + 1) * G : Tk;
+        return lim < Tk ? lim : Tk;
     };
     const int q_last = (q0 + BQ < T ? q0 + BQ : T) - 1, w_last = (wq0 + WQ < T ? wq0 + WQ : T) - 1;
     const int n_blocks = (limit_of(q_last) + BKV - 1) / BKV;
@@ -157,9 +159,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 256 ? 
     // Copies of one K / V block, global memory -> LDS without passing registers: one instruction moves
     // 1 KB (RPI rows) to consecutive LDS addresses, so the XOR placement is applied on the source side: the
     // lane that fills chunk position `pos` of a row fetches that row's chunk pos ^ lds_swizzle(row).  Rows at or
-    // beyond T lie outside the buffer range and arrive as zeros.
+    // beyond Tk lie outside the buffer range and arrive as zeros.
     constexpr int RPI = 1024 / RB, NI = BKV / RPI / 4;  // rows per instruction; instructions per wave and operand
-    const uint32_t nrec_k = uint32_t(int64_t(T - 1) * a.ldk * 2 + RB), nrec_v = uint32_t(int64_t(T - 1) * a.ldv * 2 + RB);
+    const uint32_t nrec_k = uint32_t(int64_t(Tk - 1) * a.ldk * 2 + RB), nrec_v = uint32_t(int64_t(Tk - 1) * a.ldv * 2 + RB);
     BufferPair kv;
     kv.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(kp), 0, nrec_k, 0x00020000);
     kv.v = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(vp), 0, nrec_v, 0x00020000);

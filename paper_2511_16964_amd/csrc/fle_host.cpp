@@ -376,35 +376,47 @@ static fle_status check_workspace(const fle_problem *p, const Plan &plan) {
 }
 
 // ------------------------------------------------------------------ attention
+// Elements spanned by B sequences of T tokens of HD elements with token stride ld and sequence stride sb,
+// or 0 if the two strides make tokens of different sequences collide.
+static int64_t attention_extent(int64_t B, int64_t T, int64_t HD, int64_t ld, int64_t sb) {
+    const bool seq_major = sb >= (T - 1) * ld + HD, token_major = sb >= HD && ld >= (B - 1) * sb + HD;
+    if (B > 1 && !seq_major && !token_major) return 0;
+    return (B - 1) * sb + (T - 1) * ld + HD;
+}
+
 static fle_status check_attention(const fle_attention *p) {
     if (!p) return fail(FLE_ERR_NULL, "attention problem is NULL");
     if (p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_UNSUPPORTED, "attention takes FLE_BF16 or FLE_F16 (got dtype %d)", p->dtype);
-    if (p->B < 0 || p->H < 1 || p->T < 1) return fail(FLE_ERR_SHAPE, "need B >= 0, H >= 1, T >= 1 (got %lld, %lld, %lld)", (long long)p->B, (long long)p->H, (long long)p->T);
+    if (p->B < 0 || p->H < 1 || p->T < 1 || p->Tk < 0) return fail(FLE_ERR_SHAPE, "need B >= 0, H >= 1, T >= 1, Tk >= 0 (got %lld, %lld, %lld, %lld)", (long long)p->B, (long long)p->H, (long long)p->T, (long long)p->Tk);
     if (p->D != 32 && p->D != 64 && p->D != 128 && p->D != 256) return fail(FLE_ERR_UNSUPPORTED, "head dimension %lld is not 32, 64, 128 or 256", (long long)p->D);
     if (p->causal < 0) return fail(FLE_ERR_OP, "causal must be 0, 1 or a group size (got %d)", p->causal);
     if (p->B > 65535 || p->H > 65535) return fail(FLE_ERR_SHAPE, "B and H are limited to 65535");
-    if (p->T > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T is limited to 2^24");
+    const int64_t Tk = p->Tk > 0 ? p->Tk : p->T;
+    if (p->T > (int64_t(1) << 24) || Tk > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "T and Tk are limited to 2^24");
+    if (p->causal && Tk < p->T) return fail(FLE_ERR_SHAPE, "a causal mask needs Tk >= T (got Tk = %lld, T = %lld)", (long long)Tk, (long long)p->T);
     if ((p->T + 127) / 128 * p->H * p->B >= (int64_t(1) << 31)) return fail(FLE_ERR_SHAPE, "B * H * T / 128 is limited to 2^31 workgroups");
     const int64_t HD = p->H * p->D;
     const int64_t kLimit = int64_t(1) << 40;
     if (p->ldq < HD || p->ldk < HD || p->ldv < HD || p->ldo < HD) return fail(FLE_ERR_SHAPE, "a token stride is smaller than H*D = %lld", (long long)HD);
     if (p->ldq > kLimit || p->ldk > kLimit || p->ldv > kLimit || p->ldo > kLimit) return fail(FLE_ERR_SHAPE, "token stride too large");
+    if (p->sbq < 0 || p->sbk < 0 || p->sbv < 0 || p->sbo < 0 || p->sbq > kLimit || p->sbk > kLimit || p->sbv > kLimit || p->sbo > kLimit)
+        return fail(FLE_ERR_SHAPE, "sequence strides must be >= 0 (0 = packed)");
     // the kernel addresses the Q, K and V of one sequence with 32-bit byte offsets
-    {
-        int64_t ldmax = p->ldq > p->ldk ? p->ldq : p->ldk;
-        if (p->ldv > ldmax) ldmax = p->ldv;
-        if ((p->T + 256) * ldmax * 2 >= (int64_t(1) << 31)) return fail(FLE_ERR_SHAPE, "one sequence's Q, K or V spans 2 GiB or more");
-    }
+    if ((p->T + 256) * p->ldq * 2 >= (int64_t(1) << 31) || (Tk + 64) * (p->ldk > p->ldv ? p->ldk : p->ldv) * 2 >= (int64_t(1) << 31))
+        return fail(FLE_ERR_SHAPE, "one sequence's Q, K or V spans 2 GiB or more");
     if (!(p->scale >= 0.0f) || std::isinf(p->scale)) return fail(FLE_ERR_OP, "scale must be finite and > 0 (or 0 for 1/sqrt(D))");
     if (p->B == 0) return FLE_OK;
     if (!p->q || !p->k || !p->v || !p->o) return fail(FLE_ERR_NULL, "q, k, v or o is NULL");
     if (!aligned(p->q, 16) || !aligned(p->k, 16) || !aligned(p->v, 16)) return fail(FLE_ERR_ALIGN, "q, k and v must be 16-byte aligned");
-    if (p->ldq % 8 || p->ldk % 8 || p->ldv % 8) return fail(FLE_ERR_ALIGN, "ldq, ldk and ldv must be multiples of 8 elements");
-    if (!aligned(p->o, 8) || p->ldo % 4) return fail(FLE_ERR_ALIGN, "o must be 8-byte aligned and ldo a multiple of 4 elements");
-    const int64_t rows = p->B * p->T;
-    const size_t no = span_bytes(rows, HD, p->ldo, 2);
-    if (overlaps(p->o, no, p->q, span_bytes(rows, HD, p->ldq, 2)) || overlaps(p->o, no, p->k, span_bytes(rows, HD, p->ldk, 2)) ||
-        overlaps(p->o, no, p->v, span_bytes(rows, HD, p->ldv, 2)))
+    if (p->ldq % 8 || p->ldk % 8 || p->ldv % 8 || p->sbq % 8 || p->sbk % 8 || p->sbv % 8) return fail(FLE_ERR_ALIGN, "the strides of q, k and v must be multiples of 8 elements");
+    if (!aligned(p->o, 8) || p->ldo % 4 || p->sbo % 4) return fail(FLE_ERR_ALIGN, "o must be 8-byte aligned and its strides multiples of 4 elements");
+    const int64_t eq = attention_extent(p->B, p->T, HD, p->ldq, p->sbq > 0 ? p->sbq : p->T * p->ldq);
+    const int64_t ek = attention_extent(p->B, Tk, HD, p->ldk, p->sbk > 0 ? p->sbk : Tk * p->ldk);
+    const int64_t ev = attention_extent(p->B, Tk, HD, p->ldv, p->sbv > 0 ? p->sbv : Tk * p->ldv);
+    const int64_t eo = attention_extent(p->B, p->T, HD, p->ldo, p->sbo > 0 ? p->sbo : p->T * p->ldo);
+    if (!eq || !ek || !ev || !eo) return fail(FLE_ERR_SHAPE, "token and sequence strides make sequences collide");
+    const size_t no = size_t(eo) * 2;
+    if (overlaps(p->o, no, p->q, size_t(eq) * 2) || overlaps(p->o, no, p->k, size_t(ek) * 2) || overlaps(p->o, no, p->v, size_t(ev) * 2))
         return fail(FLE_ERR_UNSUPPORTED, "o overlaps q, k or v");
     return FLE_OK;
 }

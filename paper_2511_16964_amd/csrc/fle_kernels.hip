@@ -198,7 +198,10 @@ fle_status launch_attention(const fle_attention *p) {
     AttnArgs a;
     a.q = p->q; a.k = p->k; a.v = p->v; a.o = p->o;
     a.ldq = p->ldq; a.ldk = p->ldk; a.ldv = p->ldv; a.ldo = p->ldo;
-    a.T = int32_t(p->T); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal;
+    const int64_t Tk = p->Tk > 0 ? p->Tk : p->T;
+    a.sbq = p->sbq > 0 ? p->sbq : p->T * p->ldq; a.sbo = p->sbo > 0 ? p->sbo : p->T * p->ldo;
+    a.sbk = p->sbk > 0 ? p->sbk : Tk * p->ldk; a.sbv = p->sbv > 0 ? p->sbv : Tk * p->ldv;
+    a.T = int32_t(p->T); a.Tk = int32_t(Tk); a.H = int32_t(p->H); a.B = int32_t(p->B); a.causal = p->causal;
     const float scale = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(float(p->D));
     a.scale_log2e = scale * 1.44269504088896340736f;
     const bool f16 = p->dtype == FLE_F16;

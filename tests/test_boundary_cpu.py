@@ -440,6 +440,20 @@ def test_attention_validation(L):
     assert v(attention(T=1 << 20, H=64, D=128)) == E_SHAPE           # a sequence's K spans more than 2 GiB
     assert b"2 GiB" in L.fle_last_error()
     assert L.fle_attention_validate(None) == E_NULL
+    # different numbers of queries and keys; sequence strides
+    p = attention(T=10); p.Tk = 300
+    assert v(p) == OK
+    p = attention(T=300, causal=1); p.Tk = 10
+    assert v(p) == E_SHAPE                                           # causal needs Tk >= T
+    p = attention(T=300, causal=0); p.Tk = 10
+    assert v(p) == OK
+    p = attention(B=3, H=2, T=50, D=64, ld=3 * 3 * 128); p.sbq = p.sbk = p.sbv = 3 * 128   # sequence-first: tokens interleave
+    p.ldo, p.sbo = 3 * 128, 128
+    assert v(p) == OK
+    p.sbo = 64
+    assert v(p) == E_SHAPE                                           # output sequences would collide
+    p.sbo = 130
+    assert v(p) == E_ALIGN
 
 
 def attention_block(B=2, T=100, C=256, H=4, dtype=binding.BF16, residual=True, ws=None, ws_bytes=0):

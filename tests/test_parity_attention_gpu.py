@@ -72,6 +72,41 @@ def test_attention_group_causal(dtype, D, T, G):
     assert_close(run_attention(qkv, G), oracle_attention(qkv, G), dtype, "G=%d" % G, s=value_scale(qkv[:, :, 2]))
 
 
+@pytest.mark.parametrize("dtype,D,T,Tk,causal", [
+    (BF16, 64, 77, 300, 0),       # cross attention: fewer queries than keys, no mask
+    (BF16, 128, 300, 77, 0),      # more queries than keys
+    (F16, 64, 100, 356, 1),       # causal continuation: 100 new tokens after 256 kept keys
+    (BF16, 128, 1, 500, 1),       # one new token
+    (BF16, 32, 130, 400, 64),     # groups of 64 tokens, the queries start inside a group
+    (F16, 256, 200, 201, 1),
+])
+def test_attention_with_different_query_and_key_counts(dtype, D, T, Tk, causal):
+    announce("attention Tq != Tk", dtype, D, T, Tk, causal)
+    B, H = 2, 3
+    q = inputs.make_qkv(900 + T, B, T, H, D, dtype)[:, :, 0]
+    kv = inputs.make_qkv(901 + Tk, B, Tk, H, D, dtype)
+    d = lambda t: t.to(DEV)
+    got = binding.attention(d(q), d(kv)[:, :, 1], d(kv)[:, :, 2], causal)
+    torch.cuda.synchronize()
+    f = inputs.to_f64
+    ref = oracle.attention(f(q), f(kv[:, :, 1]), f(kv[:, :, 2]), causal)
+    assert_close(got.cpu(), ref, dtype, s=value_scale(kv[:, :, 2]))
+
+
+def test_attention_on_sequence_first_tensors():
+    """[T, B, ...] tensors (the layout of sequence-first modules) viewed as [B, T, H, D]: the token stride is
+    B rows, the sequence stride one row; input and output are used in place."""
+    announce("attention sequence-first")
+    T, B, H, D = 150, 3, 2, 64
+    qkv = inputs.make_qkv(33, B, T, H, D, BF16)                       # [B,T,3,H,D], the values to use
+    tb = qkv.transpose(0, 1).contiguous().to(DEV)                     # [T,B,3,H,D] in memory
+    q, k, v = (tb[:, :, i].transpose(0, 1) for i in range(3))         # [B,T,H,D] views
+    out_tb = torch.zeros(T, B, H, D, device=DEV, dtype=BF16)
+    binding.attention(q, k, v, True, out=out_tb.transpose(0, 1))
+    torch.cuda.synchronize()
+    assert_close(out_tb.transpose(0, 1).cpu(), oracle_attention(qkv, True), BF16, s=value_scale(qkv[:, :, 2]))
+
+
 def test_attention_peaked_and_flat_scores():
     """Score spreads far from the N(0,1) of the workload: nearly one-hot rows (large scale) and nearly
     uniform rows (tiny scale); the running maximum must keep both finite."""
@@ -108,6 +143,8 @@ def test_attention_rejects_what_it_cannot_run():
         binding.attention(q, k, v, False, scale=-1.0)
     with pytest.raises(binding.FleError):
         binding.attention(q, k, v, -3)                                     # negative group size
+    with pytest.raises(binding.FleError):
+        binding.attention(q, k[:, :4], v[:, :4], True)                     # causal with fewer keys than queries
     with pytest.raises(binding.FleError):
         binding.attention(q, k, v, False, out=q)                           # o overlaps q
 

@@ -130,8 +130,12 @@ def test_random_attention_matches_oracle(seed):
     print("[case] random attention", seed, dtype, D, T, B, H, causal, scale, spread, flush=True)
     qkv = inputs.make_qkv(seed, B, T, H, D, dtype, spread)
     dev = qkv.to("cuda:0")
-    if rng.random() < 0.5:
+    layout = rng.random()
+    if layout < 0.4:
         q, k, v = dev[:, :, 0], dev[:, :, 1], dev[:, :, 2]
+    elif layout < 0.6:   # sequence-first memory, viewed batch-first
+        tb = dev.transpose(0, 1).contiguous()
+        q, k, v = (tb[:, :, i].transpose(0, 1) for i in range(3))
     else:   # separate buffers, token stride padded by 8 .. 64 elements
         def padded(t):
             pad = int(rng.integers(1, 9)) * 8
