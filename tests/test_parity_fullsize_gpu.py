@@ -94,21 +94,22 @@ def test_c5b_per_call_on_oracle_rounded_h():
 
 
 def test_m1_perceptron_chain_every_layer():
-    """The batch-1 perceptron of bench.py's workload m1: every layer's GPU output against the oracle applied
-    to the same input (the GPU's own previous activation), and the chain end to end against the oracle's
-    float64 chain."""
+    """The batch-1 perceptron of bench.py's workload m1.  Layer by layer: the GPU and the oracle both start from
+    the oracle's own previous activation, rounded to the storage dtype (no oracle input comes from the GPU).
+    End to end: the GPU chain on its own activations against the oracle's float64 chain."""
     ch = inputs.make_chain()
     announce("m1", len(ch.ws), ch.x.shape)
     F32 = torch.float32
-    h_gpu, h_ref = ch.x, inputs.to_f64(ch.x)
     import oracle
+    h_gpu, h_ref = ch.x, inputs.to_f64(ch.x)
     for i in range(len(ch.ws)):
-        prob = ch.layer(i, h_gpu)
+        h_in = torch.from_numpy(h_ref).to(F32)                      # the oracle's activation as the layer's input
+        prob = ch.layer(i, h_in)
         out, call = run_gpu(prob)
         assert "thin_f32" in call.plan() and "tile=8x16" in call.plan(), call.plan()
         assert_close(out, oracle_rows(prob), F32, "m1 layer %d" % i)
+        h_gpu, _ = run_gpu(ch.layer(i, h_gpu))                      # the GPU's own chain
         h_ref = oracle.fused_linear_epilogue(h_ref, inputs.to_f64(ch.ws[i]), inputs.to_f64(ch.bs[i]), [("bias",), ("relu",)])
-        h_gpu = out
     err = assert_close(h_gpu, h_ref, F32, "m1 end to end")
     print("m1 end-to-end max|err| %.3e" % err)
 
@@ -116,8 +117,7 @@ def test_m1_perceptron_chain_every_layer():
 def test_a1_attention_block_fullsize_sampled_tokens():
     """The attention block at the benchmark's size (16 x 2048 tokens, 2048 wide, 16 heads, causal), as bench.py
     launches it.  Checked: the first 200 tokens of two sequences in full (a causal block needs nothing after
-    them), and late tokens of one sequence and head through the attention kernel alone (the oracle evaluates
-    only the sampled queries, against all their keys)."""
+    them)."""
     import oracle
     from paper_2511_16964_amd import binding
     announce("a1 full size")
@@ -135,12 +135,27 @@ def test_a1_attention_block_fullsize_sampled_tokens():
         x = f64(ap.x[b:b + 1, :n_tok])
         ref = oracle.attention_block(x, f64(ap.w_qkv), f64(ap.b_qkv), f64(ap.w_o), f64(ap.b_o), H, ap.causal, residual=x)
         assert_close(out[b:b + 1, :n_tok].cpu(), ref, ap.dtype, "a1 block, sequence %d" % b, factor=BLOCK_FACTOR)
-    # the attention kernel on the block's own qkv (left in the workspace by the run above): last queries of a sequence
-    ws = call._keep[-1]
-    qkv = ws[:B * T * 3 * C * 2].view(ap.dtype).view(B, T, 3, H, D)
-    b, heads, first = 3, [0, H - 1], T - 40
-    got = binding.attention(qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], True)
+
+
+def test_a2_attention_fullsize_sampled_queries():
+    """The attention kernel alone at the benchmark's size (workload a2: q, k, v of a1's shape from the seeded
+    generator), as bench.py launches it: the last queries of sampled sequences and heads against all their keys
+    (the oracle evaluates only those queries), and the first queries of another head."""
+    import oracle
+    from paper_2511_16964_amd import binding
+    dt, B, T, C, H, causal = inputs.ATTENTION_SHAPES["a1"]
+    D = C // H
+    announce("a2 full size", B, T, H, D)
+    qkv = inputs.make_qkv(0, B, T, H, D, dt)
+    dev = qkv.to("cuda:0")
+    got = binding.attention(dev[:, :, 0], dev[:, :, 1], dev[:, :, 2], causal)
     torch.cuda.synchronize()
-    sub = f64(qkv[b:b + 1][:, :, :, heads].cpu())
-    ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], True, first_query=first)
-    assert_close(got[b:b + 1, first:][:, :, heads].cpu(), ref, ap.dtype, "a1 attention, last queries", s=value_scale(qkv[:, :, 2]))
+    assert torch.isfinite(got.float()).all()
+    f64 = inputs.to_f64
+    for b, heads, first in ((3, [0, H - 1], T - 40), (B - 1, [5], T - 130)):
+        sub = f64(qkv[b:b + 1][:, :, :, heads])
+        ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal, first_query=first)
+        assert_close(got[b:b + 1, first:][:, :, heads].cpu(), ref, dt, "a2 last queries", s=value_scale(qkv[:, :, 2]))
+    sub = f64(qkv[0:1, :300][:, :, :, [7]])
+    ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal)
+    assert_close(got[0:1, :300][:, :, [7]].cpu(), ref, dt, "a2 first queries", s=value_scale(qkv[:, :, 2]))
