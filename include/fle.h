@@ -237,6 +237,52 @@ fle_status fle_attention_block_workspace_size(const fle_attention_block *p, size
  * already be enqueued (they only write the workspace). */
 fle_status fle_attention_block_run(const fle_attention_block *p);
 
+/*
+ * A whole perceptron at batch 1 in one persistent launch: a chain of layers
+ *
+ *     h_0 = x,   h_{l+1} = act_l( W_l h_l + b_l ),   out = h_L
+ *
+ * The paper's MLP tasks run at batch 1 on small layers, where launches and the refill of the memory
+ * pipeline between dependent launches dominate (appendix on task refinement: such tasks were noisy
+ * or dropped for being launch-bound), and its task-wise analysis names fusing a whole model into a
+ * single kernel as a recurring winner.  One launch keeps at most one workgroup resident per CU,
+ * separates the layers by a grid-wide barrier and requests the next layer's first weights before the
+ * barrier.  Intermediate activations are rounded to the storage dtype, as separate calls would.
+ * The barrier's waits are bounded: should the workgroups ever not be resident together (another
+ * kernel holding CUs that never finishes), the call ends with a wrong result and a non-zero error
+ * word (see workspace) instead of hanging.
+ */
+typedef struct {
+    const void *w;  /* DEVICE [n, k] row-major and packed (row stride k), 16-byte aligned            */
+    const void *b;  /* DEVICE [n] or NULL                                                            */
+    int64_t n, k;   /* k inputs -> n outputs; k must equal the previous layer's n; k a multiple of
+                       16 bytes (4 fp32 / 8 bf16 or fp16 elements)                                   */
+    int32_t act;    /* -1: none, or FLE_RELU, FLE_GELU_ERF, FLE_GELU_TANH                            */
+} fle_chain_layer;
+
+#define FLE_CHAIN_MAX_LAYERS 16
+
+typedef struct {
+    int32_t dtype;                 /* FLE_F32, FLE_BF16 or FLE_F16: x, every W and b, out            */
+    int32_t n_layers;              /* 1 .. FLE_CHAIN_MAX_LAYERS                                      */
+    const fle_chain_layer *layers; /* HOST array                                                     */
+    const void *x;                 /* DEVICE [layers[0].k], 16-byte aligned                          */
+    void *out;                     /* DEVICE [layers[n_layers-1].n]                                  */
+    void *workspace;               /* DEVICE, 256-byte aligned, fle_chain_workspace_size bytes: 2560
+                                      bytes of barrier state, then the activations between layers.
+                                      The barrier state must be ZERO before the first call; every
+                                      call leaves it zero, except the 32-bit error word at byte 256,
+                                      which becomes 1 if a barrier wait ran out.  Calls that share a
+                                      workspace must not overlap in time                             */
+    size_t workspace_bytes;
+    void *stream;
+} fle_chain;
+
+fle_status fle_chain_validate(const fle_chain *p);
+fle_status fle_chain_workspace_size(const fle_chain *p, size_t *bytes_out);
+/* Enqueues one kernel on p->stream.  Never allocates or synchronises. */
+fle_status fle_chain_run(const fle_chain *p);
+
 /* Static description of a status code. */
 const char *fle_status_string(fle_status s);
 

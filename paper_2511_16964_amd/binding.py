@@ -22,7 +22,8 @@ EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string",
            "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
            "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped",
            "fle_attention_validate", "fle_attention_run", "fle_attention_block_validate",
-           "fle_attention_block_workspace_size", "fle_attention_block_run"]
+           "fle_attention_block_workspace_size", "fle_attention_block_run",
+           "fle_chain_validate", "fle_chain_workspace_size", "fle_chain_run"]
 
 
 class FleOp(ctypes.Structure):
@@ -66,6 +67,17 @@ class FleAttentionBlock(ctypes.Structure):
                 ("stream", ctypes.c_void_p)]
 
 
+class FleChainLayer(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("b", ctypes.c_void_p), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+                ("act", ctypes.c_int32)]
+
+
+class FleChain(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("layers", ctypes.POINTER(FleChainLayer)),
+                ("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p)]
+
+
 class FleError(RuntimeError):
     def __init__(self, status: int, name: str, detail: str):
         super().__init__("libfle: %s (status %d): %s" % (name, status, detail))
@@ -101,6 +113,11 @@ def lib():
             getattr(L, name).argtypes = [ctypes.POINTER(FleAttentionBlock)]
         L.fle_attention_block_workspace_size.restype = ctypes.c_int
         L.fle_attention_block_workspace_size.argtypes = [ctypes.POINTER(FleAttentionBlock), ctypes.POINTER(ctypes.c_size_t)]
+        for name in ("fle_chain_validate", "fle_chain_run"):
+            getattr(L, name).restype = ctypes.c_int
+            getattr(L, name).argtypes = [ctypes.POINTER(FleChain)]
+        L.fle_chain_workspace_size.restype = ctypes.c_int
+        L.fle_chain_workspace_size.argtypes = [ctypes.POINTER(FleChain), ctypes.POINTER(ctypes.c_size_t)]
         L.fle_status_string.restype = ctypes.c_char_p
         L.fle_status_string.argtypes = [ctypes.c_int]
         L.fle_last_error.restype = ctypes.c_char_p
@@ -385,3 +402,65 @@ def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual=None, out
     x [B,T,C]; w_qkv [3C,C] with output columns q | k | v; C / heads must be 64 or 128; bf16 or fp16.
     """
     return AttentionBlockCall(x, w_qkv, b_qkv, w_o, b_o, heads, causal, residual, out, workspace).run()
+
+
+_ACTS = {None: -1, "none": -1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4}
+
+
+class ChainCall:
+    """A marshalled fle_chain (a perceptron at batch 1 in one persistent launch) bound to its tensors."""
+
+    def __init__(self, x, weights, biases, activations, out=None, workspace=None):
+        if not x.is_cuda:
+            raise RuntimeError("mlp_chain runs on the GPU only; there is no CPU path")
+        if x.numel() != weights[0].shape[1] or (x.dim() == 2 and x.shape[0] != 1) or x.dim() > 2:
+            raise ValueError("x must be one row of weights[0].shape[1] elements")
+        n = len(weights)
+        if len(biases) != n or len(activations) != n:
+            raise ValueError("one bias (or None) and one activation per layer")
+        arr = (FleChainLayer * n)()
+        for i, (w, b, act) in enumerate(zip(weights, biases, activations)):
+            for t in (w, b):
+                if t is not None and (t.dtype != x.dtype or t.device != x.device or not t.is_contiguous()):
+                    raise ValueError("weights and biases must be contiguous tensors of x's dtype and device")
+            if w.dim() != 2 or (b is not None and tuple(b.shape) != (w.shape[0],)):
+                raise ValueError("layer %d: w must be [n,k] and b [n]" % i)
+            arr[i].w, arr[i].b = w.data_ptr(), (None if b is None else b.data_ptr())
+            arr[i].n, arr[i].k, arr[i].act = w.shape[0], w.shape[1], _ACTS[act]
+        if out is None:
+            out = torch.empty((1, weights[-1].shape[0]) if x.dim() == 2 else (weights[-1].shape[0],), device=x.device, dtype=x.dtype)
+        p = FleChain()
+        p.dtype, p.n_layers, p.layers = _dtype_code(x.dtype), n, arr
+        p.x, p.out = x.data_ptr(), out.data_ptr()
+        need = ctypes.c_size_t(0)
+        _check(lib().fle_chain_workspace_size(ctypes.byref(p), ctypes.byref(need)))
+        if workspace is None:
+            workspace = torch.zeros(max(need.value, 256), device=x.device, dtype=torch.uint8)   # the barrier words start at zero
+        p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        self.workspace_needed = need.value
+        self.workspace = workspace
+        self._keep = (x, list(weights), list(biases), workspace, arr)
+        self.out, self._p, self._pref, self._dev = out, p, ctypes.byref(p), x.device.index
+
+    def run(self, stream=None):
+        self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
+        status = lib().fle_chain_run(self._pref)
+        if status != 0:
+            _check(status)
+        return self.out
+
+    def barrier_error(self) -> bool:
+        """True if a barrier wait ran out in some call since the workspace was zeroed (synchronises)."""
+        return bool(self.workspace[256:260].view(torch.int32).item())
+
+    def plan(self) -> str:
+        return "mlp_chain: %d layers in one launch" % self._p.n_layers
+
+
+def mlp_chain(x, weights, biases, activations, out=None, workspace=None):
+    """out = act_L(W_L ... act_1(W_1 x + b_1) ... + b_L) for one input row, every layer in one persistent launch.
+
+    x: [k] or [1,k]; weights[i]: [n_i, k_i] with k_{i+1} = n_i; biases[i]: [n_i] or None;
+    activations[i]: None, "relu", "gelu_erf" or "gelu_tanh".  float32, bfloat16 or float16.
+    """
+    return ChainCall(x, weights, biases, activations, out, workspace).run()

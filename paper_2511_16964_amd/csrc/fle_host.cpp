@@ -503,6 +503,33 @@ static fle_status plan_block(const fle_attention_block *p, BlockParts *bp) {
     return FLE_OK;
 }
 
+// ------------------------------------------------------------------ perceptron chain
+static const size_t kChainSyncBytes = 2560;  // the barrier state at the start of the workspace (rounded to 256-byte alignment below)
+static fle_status check_chain(const fle_chain *p, size_t *act_bytes) {
+    if (!p) return fail(FLE_ERR_NULL, "chain is NULL");
+    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
+    if (p->n_layers < 1 || p->n_layers > FLE_CHAIN_MAX_LAYERS) return fail(FLE_ERR_SHAPE, "n_layers %d outside 1..%d", p->n_layers, FLE_CHAIN_MAX_LAYERS);
+    if (!p->layers || !p->x || !p->out) return fail(FLE_ERR_NULL, "layers, x or out is NULL");
+    const size_t es = esize(p->dtype);
+    if (!aligned(p->x, 16)) return fail(FLE_ERR_ALIGN, "x must be 16-byte aligned");
+    int64_t widest = 0;
+    for (int l = 0; l < p->n_layers; ++l) {
+        const fle_chain_layer &L = p->layers[l];
+        if (L.n < 1 || L.k < 1 || L.n > (int64_t(1) << 24) || L.k > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "layer %d: n and k must be in 1 .. 2^24", l);
+        if (l > 0 && L.k != p->layers[l - 1].n) return fail(FLE_ERR_SHAPE, "layer %d takes %lld inputs but layer %d gives %lld", l, (long long)L.k, l - 1, (long long)p->layers[l - 1].n);
+        if ((size_t(L.k) * es) % 16) return fail(FLE_ERR_ALIGN, "layer %d: k must be a multiple of 16 bytes", l);
+        if (!L.w) return fail(FLE_ERR_NULL, "layer %d: w is NULL", l);
+        if (!aligned(L.w, 16)) return fail(FLE_ERR_ALIGN, "layer %d: w must be 16-byte aligned", l);
+        if (L.act != -1 && L.act != FLE_RELU && L.act != FLE_GELU_ERF && L.act != FLE_GELU_TANH) return fail(FLE_ERR_OP, "layer %d: activation %d is not -1, RELU, GELU_ERF or GELU_TANH", l, L.act);
+        if (overlaps(p->out, size_t(p->layers[p->n_layers - 1].n) * es, L.w, size_t(L.n) * size_t(L.k) * es)) return fail(FLE_ERR_UNSUPPORTED, "out overlaps the weights of layer %d", l);
+        if (l + 1 < p->n_layers && L.n > widest) widest = L.n;
+    }
+    if (overlaps(p->out, size_t(p->layers[p->n_layers - 1].n) * es, p->x, size_t(p->layers[0].k) * es) && p->n_layers > 1)
+        return fail(FLE_ERR_UNSUPPORTED, "out overlaps x");
+    *act_bytes = round_up(size_t(widest) * es, 256);
+    return FLE_OK;
+}
+
 extern "C" {
 
 fle_status fle_validate(const fle_problem *p) {
@@ -624,6 +651,34 @@ fle_status fle_attention_block_run(const fle_attention_block *p) {
     return s;
 }
 
+fle_status fle_chain_validate(const fle_chain *p) {
+    size_t act = 0;
+    return check_chain(p, &act);
+}
+
+fle_status fle_chain_workspace_size(const fle_chain *p, size_t *bytes_out) {
+    if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
+    size_t act = 0;
+    fle_status s = check_chain(p, &act);
+    if (s == FLE_OK) *bytes_out = kChainSyncBytes + 2 * act;
+    return s;
+}
+
+fle_status fle_chain_run(const fle_chain *p) {
+    size_t act = 0;
+    fle_status s = check_chain(p, &act);
+    if (s != FLE_OK) return s;
+    char *ws = reinterpret_cast<char *>(p->workspace);
+    const size_t need = kChainSyncBytes + 2 * act;
+    if (!ws) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (p->workspace_bytes < need) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
+    const size_t es = esize(p->dtype);
+    if (overlaps(ws, need, p->x, size_t(p->layers[0].k) * es) || overlaps(ws, need, p->out, size_t(p->layers[p->n_layers - 1].n) * es))
+        return fail(FLE_ERR_UNSUPPORTED, "the workspace overlaps x or out");
+    return launch_chain(p, ws, ws + kChainSyncBytes, ws + kChainSyncBytes + act);
+}
+
 const char *fle_status_string(fle_status s) {
     switch (s) {
     case FLE_OK: return "ok";
@@ -651,6 +706,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 500; }  // 0.5.0: attention (0.4.0: thin kernels; 0.3.0: grouped problems)
+int fle_version(void) { return 600; }  // 0.6.0: perceptron chain (0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
 
 }  // extern "C"

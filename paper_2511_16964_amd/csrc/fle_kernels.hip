@@ -20,6 +20,7 @@
 #include "fle_gemm_skinny.h"
 #include "fle_gemm_thin.h"
 #include "fle_attention.h"
+#include "fle_chain.h"
 #include "fle_gemm_tiled.h"
 #include "fle_rowops.h"
 
@@ -212,6 +213,35 @@ fle_status launch_attention(const fle_attention *p) {
     default: f16 ? launch_attention_dt<FLE_F16, 256>(p, a, stream) : launch_attention_dt<FLE_BF16, 256>(p, a, stream); break;
     }
     return check_launch("flash_attention");
+}
+
+fle_status launch_chain(const fle_chain *p, void *sync, void *act0, void *act1) {
+    hipStream_t stream = reinterpret_cast<hipStream_t>(p->stream);
+    ChainArgs a;
+    a.n_layers = p->n_layers;
+    a.x = p->x; a.out = p->out; a.act[0] = act0; a.act[1] = act1; a.sync = reinterpret_cast<uint32_t *>(sync);
+    int64_t widest = 0;
+    for (int l = 0; l < p->n_layers; ++l) {
+        a.layer[l].w = p->layers[l].w; a.layer[l].bias = p->layers[l].b;
+        a.layer[l].n = int32_t(p->layers[l].n); a.layer[l].k = int32_t(p->layers[l].k); a.layer[l].act = p->layers[l].act;
+        if (p->layers[l].n > widest) widest = p->layers[l].n;
+    }
+    // at most one workgroup of 16 waves per CU (a CU holds two), so that every workgroup is resident while the
+    // others wait at a barrier; fewer when no layer has 16 rows for each
+    static thread_local int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+            cus = 0;
+            return fail(FLE_ERR_HIP, "cannot query the device");
+        }
+    }
+    const int64_t want = (widest + 15) / 16;
+    const uint32_t grid = uint32_t(want < cus ? want : cus);
+    if (p->dtype == FLE_F32) hipLaunchKernelGGL(mlp_chain<FLE_F32>, dim3(grid), dim3(1024), 0, stream, a);
+    else if (p->dtype == FLE_F16) hipLaunchKernelGGL(mlp_chain<FLE_F16>, dim3(grid), dim3(1024), 0, stream, a);
+    else hipLaunchKernelGGL(mlp_chain<FLE_BF16>, dim3(grid), dim3(1024), 0, stream, a);
+    return check_launch("mlp_chain");
 }
 
 }  // namespace fle

@@ -69,6 +69,17 @@ def test_attention_kernels_keep_two_waves_per_simd(asm):
     assert "ds_read_b64_tr_b16" in asm   # V is transposed by the LDS read itself
 
 
+def test_chain_kernel_leaves_room_for_all_workgroups(asm):
+    """The persistent perceptron kernel waits at a grid barrier, so every workgroup must be resident: 16 waves of
+    at most 128 registers and no LDS let a CU hold two of them while the launch asks for one per CU."""
+    props = kernel_props(asm)
+    chain = {k: v for k, v in props.items() if "mlp_chain" in k}
+    assert len(chain) == 3, sorted(chain)
+    for name, p in chain.items():
+        assert p["scratch"] == 0 and p["vgpr"] <= 128 and p["lds"] == 0, (name, p)
+    assert "buffer_wbl2" not in asm and "buffer_inv" not in asm   # no kernel flushes or invalidates a cache
+
+
 def test_streaming_finalize_keeps_its_occupancy(asm):
     """The LayerNorm finalize pass is a bandwidth-bound streaming kernel: it needs many waves per SIMD, so
     its register count must stay low (a shared code path once pushed it to 149 and cost 40 % of its speed)."""

@@ -1,0 +1,110 @@
+"""GPU parity of the persistent perceptron chain (every layer of a batch-1 perceptron in one launch)
+against the CPU oracle's chain of fused linear calls in float64."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_16964_amd import binding, inputs
+
+from parity import assert_close
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16, F16 = torch.float32, torch.bfloat16, torch.float16
+DEV = "cuda:0"
+
+
+def announce(*a):
+    print("[case]", *a, flush=True)
+
+
+def random_chain(seed, widths, dtype, acts, bias=True):
+    rng = np.random.default_rng(seed)
+    x = torch.from_numpy(rng.standard_normal(widths[0]).astype(np.float32)).to(dtype)
+    ws, bs = [], []
+    for k, n in zip(widths, widths[1:]):
+        a = np.sqrt(6.0 / k)
+        ws.append(torch.from_numpy(rng.uniform(-a, a, (n, k)).astype(np.float32)).to(dtype))
+        bs.append(torch.from_numpy(rng.uniform(-0.1, 0.1, n).astype(np.float32)).to(dtype) if bias else None)
+    return x, ws, bs, list(acts)
+
+
+def oracle_chain(x, ws, bs, acts):
+    h = inputs.to_f64(x).reshape(1, -1)
+    for w, b, act in zip(ws, bs, acts):
+        ep = ([("bias",)] if b is not None else []) + ([(act,)] if act else [])
+        h = oracle.fused_linear_epilogue(h, inputs.to_f64(w), inputs.to_f64(b), ep)
+    return h.reshape(-1)
+
+
+def run_chain(x, ws, bs, acts):
+    d = lambda t: None if t is None else t.to(DEV)
+    out = binding.mlp_chain(d(x), [d(w) for w in ws], [d(b) for b in bs], acts)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+@pytest.mark.parametrize("dtype,widths,acts,bias", [
+    (F32, [64, 64], ["relu"], True),                                       # one layer: no barrier at all
+    (F32, [256, 512, 128, 16], ["relu", "relu", None], True),              # fewer rows than one per wave on the chip
+    (F32, [1024, 4096, 4096, 1000], ["relu", "gelu_tanh", None], True),    # ragged last layer
+    (BF16, [512, 2048, 2048, 512], ["gelu_erf", "relu", "relu"], False),
+    (F16, [2048, 8200, 264], ["relu", None], True),                        # more row blocks than workgroups
+    (F32, [4, 20, 4], ["relu", "relu"], True),                             # tiny: a K of one 16-byte chunk
+    (BF16, [4096] * 5, ["relu"] * 4, True),
+])
+def test_chain_matches_oracle(dtype, widths, acts, bias):
+    announce("chain", dtype, widths, acts, bias)
+    x, ws, bs, acts = random_chain(len(widths) * 7 + widths[0], widths, dtype, acts, bias)
+    got = run_chain(x, ws, bs, acts)
+    # intermediate activations are rounded to the storage dtype layer by layer: one rounding bound per layer
+    assert_close(got, oracle_chain(x, ws, bs, acts), dtype, factor=float(len(ws)) ** 0.5)
+
+
+def test_chain_equals_the_separate_calls_bit_for_bit_in_fp32():
+    """fp32: a layer in the chain and the same layer as its own fused call sum in different orders, so only the
+    oracle decides; but two runs of the chain must agree exactly (fixed summation order, no atomics)."""
+    announce("chain reproducible")
+    x, ws, bs, acts = random_chain(5, [4096, 4096, 4096], F32, ["relu", "relu"])
+    a = run_chain(x, ws, bs, acts)
+    b = run_chain(x, ws, bs, acts)
+    assert torch.equal(a, b)
+
+
+def test_chain_back_to_back_calls_leave_the_barrier_state_clean():
+    """200 calls queued without a host synchronisation in between, on one workspace: every call finds the barrier
+    words at zero (the last workgroup of a call resets them), no wait runs out, and the result never changes."""
+    announce("chain back to back")
+    x, ws, bs, acts = random_chain(9, [2048, 4096, 4096, 2048], BF16, ["relu", "gelu_tanh", None])
+    d = lambda t: t.to(DEV)
+    call = binding.ChainCall(d(x), [d(w) for w in ws], [d(b) for b in bs], acts)
+    first = call.run().clone()
+    for _ in range(200):
+        call.run()
+    torch.cuda.synchronize()
+    assert not call.barrier_error()
+    assert (call.workspace[:2560] == 0).all()
+    assert torch.equal(call.out, first)
+    assert_close(call.out.cpu(), oracle_chain(x, ws, bs, acts), BF16, factor=3.0 ** 0.5)
+
+
+def test_m1_chain_in_one_launch():
+    """bench.py's workload m2: the batch-1 perceptron of m1 (8 layers of 4096 x 4096, fp32) in one launch."""
+    ch = inputs.make_chain()
+    announce("m2", len(ch.ws))
+    acts = ["relu"] * len(ch.ws)
+    got = run_chain(ch.x, ch.ws, ch.bs, acts)
+    assert_close(got.reshape(-1), oracle_chain(ch.x, ch.ws, ch.bs, acts), F32, "m2 end to end")
+
+
+def test_chain_rejects_what_it_cannot_run():
+    d = lambda t: t.to(DEV)
+    x, ws, bs, acts = random_chain(1, [64, 32, 16], F32, ["relu", None])
+    with pytest.raises(binding.FleError):
+        binding.mlp_chain(d(x), [d(ws[0]), d(ws[0])], [None, None], acts)       # layer 1 takes 64 inputs, layer 0 gives 32
+    x, ws, bs, acts = random_chain(1, [6, 8], F32, ["relu"])
+    with pytest.raises(binding.FleError):
+        binding.mlp_chain(d(x), [d(w) for w in ws], [None], acts)                # k = 6 floats is not a multiple of 16 bytes
+    with pytest.raises(KeyError):
+        binding.mlp_chain(d(x), [d(w) for w in ws], [None], ["softmax"])
