@@ -107,6 +107,24 @@ def test_attention_on_sequence_first_tensors():
     assert_close(out_tb.transpose(0, 1).cpu(), oracle_attention(qkv, True), BF16, s=value_scale(qkv[:, :, 2]))
 
 
+@pytest.mark.parametrize("causal", [0, 1, 1000])
+def test_attention_long_sequence_sampled_queries(causal):
+    """40 000 tokens in one sequence (625 key blocks, 313 query blocks): the first and the last queries against the
+    oracle, which evaluates only those."""
+    announce("attention long sequence", causal)
+    B, T, H, D = 1, 40000, 2, 64
+    qkv = inputs.make_qkv(77, B, T, H, D, BF16)
+    got = run_attention(qkv, causal)
+    assert torch.isfinite(got.float()).all()
+    f = inputs.to_f64(qkv)
+    tail = oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, first_query=T - 6)
+    assert_close(got[:, T - 6:], tail, BF16, "last queries", s=value_scale(qkv[:, :, 2]))
+    if causal:   # the first queries only see the first keys: a short problem of its own
+        n = 2100 if causal == 1 else 2000     # with groups of 1000 tokens, queries 0 .. 1999 see exactly keys 0 .. 1999
+        head = oracle.attention(f[:, :n, 0], f[:, :n, 1], f[:, :n, 2], causal)
+        assert_close(got[:, :n], head, BF16, "first queries", s=value_scale(qkv[:, :, 2]))
+
+
 def test_attention_peaked_and_flat_scores():
     """Score spreads far from the N(0,1) of the workload: nearly one-hot rows (large scale) and nearly
     uniform rows (tiny scale); the running maximum must keep both finite."""
