@@ -108,3 +108,30 @@ def test_chain_rejects_what_it_cannot_run():
         binding.mlp_chain(d(x), [d(w) for w in ws], [None], acts)                # k = 6 floats is not a multiple of 16 bytes
     with pytest.raises(KeyError):
         binding.mlp_chain(d(x), [d(w) for w in ws], [None], ["softmax"])
+
+
+def test_chain_in_a_hip_graph():
+    """One ordinary kernel launch, no memset, no allocation: the chain can be captured and replayed; every replay
+    reproduces the eager result bit for bit on changed inputs and leaves the barrier state clean."""
+    announce("chain in a graph")
+    x, ws, bs, acts = random_chain(12, [1024, 2048, 2048, 512], F32, ["relu", "relu", None])
+    d = lambda t: t.to(DEV)
+    xg = d(x)
+    call = binding.ChainCall(xg, [d(w) for w in ws], [d(b) for b in bs], acts)
+    call.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        call.run()
+    gen = torch.Generator().manual_seed(8)
+    for rep in range(3):
+        xg.copy_(torch.randn(xg.shape, generator=gen))
+        eager = call.run().clone()
+        torch.cuda.synchronize()
+        call.out.fill_(-5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(call.out, eager), "replay %d differs" % rep
+    assert not call.barrier_error() and (call.workspace[:2560] == 0).all()
+    assert_close(call.out.cpu(), oracle_chain(xg.cpu(), ws, bs, acts), F32, factor=3.0 ** 0.5)
