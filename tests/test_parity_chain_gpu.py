@@ -53,6 +53,8 @@ def run_chain(x, ws, bs, acts):
     (F16, [2048, 8200, 264], ["relu", None], True),                        # more row blocks than workgroups
     (F32, [4, 20, 4], ["relu", "relu"], True),                             # tiny: a K of one 16-byte chunk
     (BF16, [4096] * 5, ["relu"] * 4, True),
+    (F32, [20000, 96, 20000, 8], ["relu", "relu", None], True),            # long input vectors, layers with few rows
+    (F16, [600, 16384, 600], ["gelu_tanh", None], True),
 ])
 def test_chain_matches_oracle(dtype, widths, acts, bias):
     announce("chain", dtype, widths, acts, bias)
