@@ -504,7 +504,7 @@ static fle_status plan_block(const fle_attention_block *p, BlockParts *bp) {
 }
 
 // ------------------------------------------------------------------ perceptron chain
-static const size_t kChainSyncBytes = 2560;  // the barrier state at the start of the workspace (rounded to 256-byte alignment below)
+static const size_t kChainSyncBytes = 2560;  // the barrier state at the start of the workspace: 20 lines of 128 bytes
 static fle_status check_chain(const fle_chain *p, size_t *act_bytes) {
     if (!p) return fail(FLE_ERR_NULL, "chain is NULL");
     if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
