@@ -228,14 +228,14 @@ fle_status launch_chain(const fle_chain *p, void *sync, void *act0, void *act1) 
     }
     // at most one workgroup of 16 waves per CU (a CU holds two), so that every workgroup is resident while the
     // others wait at a barrier; fewer when no layer has 16 rows for each
-    static thread_local int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
-            cus = 0;
-            return fail(FLE_ERR_HIP, "cannot query the device");
-        }
+    static thread_local int cu_count[64] = {0};  // per device: CUs (queried once per thread and device)
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(FLE_ERR_HIP, "cannot query the current device");
+    if (cu_count[dev] == 0 && (hipDeviceGetAttribute(&cu_count[dev], hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu_count[dev] < 1)) {
+        cu_count[dev] = 0;
+        return fail(FLE_ERR_HIP, "cannot query the device's CU count");
     }
+    const int cus = cu_count[dev];
     const int64_t want = (widest + 15) / 16;
     const uint32_t grid = uint32_t(want < cus ? want : cus);
     if (p->dtype == FLE_F32) hipLaunchKernelGGL(mlp_chain<FLE_F32>, dim3(grid), dim3(1024), 0, stream, a);
