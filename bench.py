@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "m2": None, "a1": None, "a2": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "m2": None, "m3": None, "a1": None, "a2": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -234,7 +234,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "a1", "a2"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -285,14 +285,18 @@ def main():
         # the same loop over groups with one plain fused call per group
         loop_out = torch.empty(gp.M, gp.N, dtype=xg.dtype, device=dev)
         loop_calls = [binding.Call(xg[lo:hi], wg[g], bg[g], ep, out=loop_out[lo:hi]) for g, lo, hi in spans]
-    elif args.workload in ("m1", "m2"):
+    elif args.workload in ("m1", "m2", "m3"):
         # a perceptron at batch 1 (the regime of the paper's MLP tasks), fp32: m1 = 8 dependent fused calls,
-        # m2 = the same chain in one persistent launch
+        # m2 = the same chain in one persistent launch, m3 = m2 with the weights stored in bf16 (activations,
+        # biases and output stay fp32; the eager comparator is the original fp32 chain)
         ch = inputs.make_chain()
         xg = to(ch.x)
         wsg, bsg = [to(w) for w in ch.ws], [to(b) for b in ch.bs]
         calls, cur = [], xg
-        if args.workload == "m2":
+        if args.workload == "m3":
+            ch.ws = [w.to(torch.bfloat16) for w in ch.ws]     # the stored weights, as the oracle sees them too
+            calls.append(binding.ChainCall(xg, [to(w) for w in ch.ws], bsg, ["relu"] * len(wsg)))
+        elif args.workload == "m2":
             calls.append(binding.ChainCall(xg, wsg, bsg, ["relu"] * len(wsg)))
         else:
             for w, b in zip(wsg, bsg):
@@ -301,13 +305,14 @@ def main():
         probs = [ch.layer(0, ch.x)]
         flops = sum(2 * ch.x.shape[0] * w.shape[0] * w.shape[1] for w in ch.ws)
         desc = "%s: perceptron, %d layers of linear+bias+relu, fp32, batch %d, width %d%s" % (
-            args.workload, len(ch.ws), ch.x.shape[0], ch.x.shape[1], " (one persistent launch)" if args.workload == "m2" else "")
+            args.workload, len(ch.ws), ch.x.shape[0], ch.x.shape[1],
+            {"m2": " (one persistent launch)", "m3": " (one persistent launch, weights stored in bf16)"}.get(args.workload, ""))
         def eager():
             h = xg
             for w, b in zip(wsg, bsg):
                 h = F.relu(F.linear(h, w, b))
             return h
-        alg_bytes = sum(4 * (w.numel() + b.numel()) for w, b in zip(ch.ws, ch.bs)) + 4 * 2 * len(ch.ws) * ch.x.numel()
+        alg_bytes = sum(w.element_size() * w.numel() + 4 * b.numel() for w, b in zip(ch.ws, ch.bs)) + 4 * 2 * len(ch.ws) * ch.x.numel()
     elif args.workload == "a1":
         # a causal self-attention block: QKV projection, attention, output projection + bias + residual (three launches)
         apb = inputs.make_attention("a1")
@@ -380,7 +385,7 @@ def main():
     plans = [c.plan() if hasattr(c, "plan") else "attention kernel" for c in calls]
     import oracle
     prob0 = probs[0]
-    if args.workload == "m2":
+    if args.workload in ("m2", "m3"):
         # the whole chain end to end (batch 1) against the oracle's float64 chain
         h = inputs.to_f64(ch.x)
         for w, b in zip(ch.ws, ch.bs):
@@ -437,7 +442,7 @@ def main():
         "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
                           "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
-    hbm_bound = args.workload in ("c4", "g2", "m1", "m2")
+    hbm_bound = args.workload in ("c4", "g2", "m1", "m2", "m3")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES[args.workload]}
@@ -457,13 +462,13 @@ def main():
                     c.run()
             lwall, _ = time_loop(torch, loop_step, max(10, args.steps // 4), 5)
             out["loop_of_plain_fused_calls"] = {"ms_per_step": lwall, "calls": len(loop_calls), "speedup_grouped_vs_loop": lwall / wall_ms}
-        elif args.workload not in ("a1", "a2", "m2"):
+        elif args.workload not in ("a1", "a2", "m2", "m3"):
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
         if grouped:
             out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs)
-        elif args.workload in ("m1", "m2"):
+        elif args.workload in ("m1", "m2", "m3"):
             out["cpu_baseline"] = cpu_baseline_chain(ch, inputs)
         elif args.workload == "a1":
             out["cpu_baseline"] = cpu_baseline_attention(apb, inputs)

@@ -75,7 +75,7 @@ class FleChainLayer(ctypes.Structure):
 class FleChain(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("layers", ctypes.POINTER(FleChainLayer)),
                 ("x", ctypes.c_void_p), ("out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
-                ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p)]
+                ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p), ("w_dtype", ctypes.c_int32)]
 
 
 class FleError(RuntimeError):
@@ -420,9 +420,11 @@ class ChainCall:
             raise ValueError("one bias (or None) and one activation per layer")
         arr = (FleChainLayer * n)()
         for i, (w, b, act) in enumerate(zip(weights, biases, activations)):
+            if w.dtype != weights[0].dtype or (b is not None and b.dtype != x.dtype):
+                raise ValueError("all weights share one dtype; biases have x's dtype")
             for t in (w, b):
-                if t is not None and (t.dtype != x.dtype or t.device != x.device or not t.is_contiguous()):
-                    raise ValueError("weights and biases must be contiguous tensors of x's dtype and device")
+                if t is not None and (t.device != x.device or not t.is_contiguous()):
+                    raise ValueError("weights and biases must be contiguous tensors on x's device")
             if w.dim() != 2 or (b is not None and tuple(b.shape) != (w.shape[0],)):
                 raise ValueError("layer %d: w must be [n,k] and b [n]" % i)
             arr[i].w, arr[i].b = w.data_ptr(), (None if b is None else b.data_ptr())
@@ -431,6 +433,7 @@ class ChainCall:
             out = torch.empty((1, weights[-1].shape[0]) if x.dim() == 2 else (weights[-1].shape[0],), device=x.device, dtype=x.dtype)
         p = FleChain()
         p.dtype, p.n_layers, p.layers = _dtype_code(x.dtype), n, arr
+        p.w_dtype = _dtype_code(weights[0].dtype)
         p.x, p.out = x.data_ptr(), out.data_ptr()
         need = ctypes.c_size_t(0)
         _check(lib().fle_chain_workspace_size(ctypes.byref(p), ctypes.byref(need)))
@@ -461,6 +464,7 @@ def mlp_chain(x, weights, biases, activations, out=None, workspace=None):
     """out = act_L(W_L ... act_1(W_1 x + b_1) ... + b_L) for one input row, every layer in one persistent launch.
 
     x: [k] or [1,k]; weights[i]: [n_i, k_i] with k_{i+1} = n_i; biases[i]: [n_i] or None;
-    activations[i]: None, "relu", "gelu_erf" or "gelu_tanh".  float32, bfloat16 or float16.
+    activations[i]: None, "relu", "gelu_erf" or "gelu_tanh".  float32, bfloat16 or float16; with a float32 x the
+    weights may be bfloat16 or float16 (biases, activations and the result stay float32).
     """
     return ChainCall(x, weights, biases, activations, out, workspace).run()

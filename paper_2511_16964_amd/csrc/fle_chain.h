@@ -17,7 +17,7 @@ struct ChainArgs {
     int32_t n_layers;
     const void *x;     // [k of layer 0]
     void *out;         // [n of the last layer]
-    void *act[2];      // activations of the layers in between, alternating (storage dtype)
+    void *act[kChainMaxLayers];  // act[l]: output of layer l < n_layers - 1 (storage dtype), every one a buffer of its own
     uint32_t *sync;    // grid barrier state (20 lines of 128 bytes, see chain_barrier); all zero between calls
     ChainLayer layer[kChainMaxLayers];
 };
@@ -96,15 +96,20 @@ __device__ __forceinline__ void store_activation(void *dst, int64_t i, float v) 
     }
 }
 
-template <int DT>
+// DT: dtype of the activations, biases and the output; DW: dtype of the weights (DT, or a 2-byte dtype under
+// fp32 activations: reduced-precision weights halve the bytes that bound this kernel).
+template <int DT, int DW>
 __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
-    constexpr int ES = DT == FLE_F32 ? 4 : 2;
+    static_assert(DW == DT || (DT == FLE_F32 && DW != FLE_F32), "weights in the activations' dtype, or 2-byte weights under fp32");
+    constexpr int ES = DW == FLE_F32 ? 4 : 2;   // bytes per weight
+    constexpr int EX = DT == FLE_F32 ? 4 : 2;   // bytes per activation
+    constexpr int XW = EX / ES;                 // 16-byte pieces of x that go with 16 bytes of W
     constexpr int D = 2;  // 1 KB blocks of a row per register batch
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     struct Batch {
-        u32x4 w[D], x[D];
+        u32x4 w[D], x[D][XW];
     };
     // the first row of this wave in a layer, its buffer resource, and the loads of K blocks j D .. j D + D - 1
     auto w_rsrc = [&](const ChainLayer &L, int row) {
@@ -120,11 +125,14 @@ __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
             b.w[d] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, col < kbytes ? col : 0x80000000u, 0, 2));
         }
     };
+    // the x elements that go with W bytes col .. col + 15 start at byte col * XW
     auto load_x = [&](Batch &b, const __amdgpu_buffer_rsrc_t &rx, uint32_t kbytes, uint32_t j) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             const uint32_t col = (j * D + d) * 1024 + uint32_t(lane) * 16;
-            b.x[d] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, col < kbytes ? col : 0x80000000u, 0, 16));  // sc1: device scope
+#pragma unroll
+            for (int h = 0; h < XW; ++h)
+                b.x[d][h] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, col < kbytes ? col * XW + 16 * h : 0x80000000u, 0, 0));
         }
     };
 
@@ -132,10 +140,10 @@ __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
     bool have_w0 = false;  // b0.w and b1.w already hold the first two weight batches of this wave's first row of the layer
     for (int l = 0; l < a.n_layers; ++l) {
         const ChainLayer &L = a.layer[l];
-        const void *src = l == 0 ? a.x : a.act[(l - 1) & 1];
-        void *dst = l + 1 == a.n_layers ? a.out : a.act[l & 1];
-        const uint32_t kbytes = uint32_t(L.k) * ES;
-        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(src), 0, kbytes, 0x00020000);
+        const void *src = l == 0 ? a.x : a.act[l - 1];
+        void *dst = l + 1 == a.n_layers ? a.out : a.act[l];
+        const uint32_t kbytes = uint32_t(L.k) * ES;  // of a W row
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(src), 0, uint32_t(L.k) * EX, 0x00020000);
         const uint32_t blocks = (kbytes + 1023) / 1024, batches = (blocks + D - 1) / D;
         for (int row = int(blockIdx.x) * 16 + wave; row < L.n; row += int(gridDim.x) * 16) {
             const __amdgpu_buffer_rsrc_t rw = w_rsrc(L, row);
@@ -147,9 +155,15 @@ __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
             auto multiply = [&](const Batch &b) {
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
-                    const Unpacked<DT> w = unpack16<DT>(b.w[d]), x = unpack16<DT>(b.x[d]);
+                    const Unpacked<DW> w = unpack16<DW>(b.w[d]);
+                    if constexpr (XW == 1) {
+                        const Unpacked<DT> x = unpack16<DT>(b.x[d][0]);
 #pragma unroll
-                    for (int e = 0; e < (DT == FLE_F32 ? 4 : 8); ++e) acc = fmaf(w.v[e], x.v[e], acc);
+                        for (int e = 0; e < (DW == FLE_F32 ? 4 : 8); ++e) acc = fmaf(w.v[e], x.v[e], acc);
+                    } else {  // 8 two-byte weights against 8 fp32 activations
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc = fmaf(w.v[e], __uint_as_float(b.x[d][e / 4][e % 4]), acc);
+                    }
                 }
             };
             for (uint32_t j = 0; j < batches; j += 2) {

@@ -510,18 +510,20 @@ static fle_status check_chain(const fle_chain *p, size_t *act_bytes) {
     if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
     if (p->n_layers < 1 || p->n_layers > FLE_CHAIN_MAX_LAYERS) return fail(FLE_ERR_SHAPE, "n_layers %d outside 1..%d", p->n_layers, FLE_CHAIN_MAX_LAYERS);
     if (!p->layers || !p->x || !p->out) return fail(FLE_ERR_NULL, "layers, x or out is NULL");
-    const size_t es = esize(p->dtype);
+    if (p->w_dtype != p->dtype && !(p->dtype == FLE_F32 && (p->w_dtype == FLE_BF16 || p->w_dtype == FLE_F16)))
+        return fail(FLE_ERR_UNSUPPORTED, "w_dtype %d must equal dtype %d, or be a 2-byte dtype under FLE_F32", p->w_dtype, p->dtype);
+    const size_t es = esize(p->dtype), ws_ = esize(p->w_dtype);
     if (!aligned(p->x, 16)) return fail(FLE_ERR_ALIGN, "x must be 16-byte aligned");
     int64_t widest = 0;
     for (int l = 0; l < p->n_layers; ++l) {
         const fle_chain_layer &L = p->layers[l];
         if (L.n < 1 || L.k < 1 || L.n > (int64_t(1) << 24) || L.k > (int64_t(1) << 24)) return fail(FLE_ERR_SHAPE, "layer %d: n and k must be in 1 .. 2^24", l);
         if (l > 0 && L.k != p->layers[l - 1].n) return fail(FLE_ERR_SHAPE, "layer %d takes %lld inputs but layer %d gives %lld", l, (long long)L.k, l - 1, (long long)p->layers[l - 1].n);
-        if ((size_t(L.k) * es) % 16) return fail(FLE_ERR_ALIGN, "layer %d: k must be a multiple of 16 bytes", l);
+        if ((size_t(L.k) * ws_) % 16) return fail(FLE_ERR_ALIGN, "layer %d: a row of W must be a multiple of 16 bytes", l);
         if (!L.w) return fail(FLE_ERR_NULL, "layer %d: w is NULL", l);
         if (!aligned(L.w, 16)) return fail(FLE_ERR_ALIGN, "layer %d: w must be 16-byte aligned", l);
         if (L.act != -1 && L.act != FLE_RELU && L.act != FLE_GELU_ERF && L.act != FLE_GELU_TANH) return fail(FLE_ERR_OP, "layer %d: activation %d is not -1, RELU, GELU_ERF or GELU_TANH", l, L.act);
-        if (overlaps(p->out, size_t(p->layers[p->n_layers - 1].n) * es, L.w, size_t(L.n) * size_t(L.k) * es)) return fail(FLE_ERR_UNSUPPORTED, "out overlaps the weights of layer %d", l);
+        if (overlaps(p->out, size_t(p->layers[p->n_layers - 1].n) * es, L.w, size_t(L.n) * size_t(L.k) * ws_)) return fail(FLE_ERR_UNSUPPORTED, "out overlaps the weights of layer %d", l);
         if (l + 1 < p->n_layers && L.n > widest) widest = L.n;
     }
     if (overlaps(p->out, size_t(p->layers[p->n_layers - 1].n) * es, p->x, size_t(p->layers[0].k) * es) && p->n_layers > 1)
@@ -660,7 +662,7 @@ fle_status fle_chain_workspace_size(const fle_chain *p, size_t *bytes_out) {
     if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
     size_t act = 0;
     fle_status s = check_chain(p, &act);
-    if (s == FLE_OK) *bytes_out = kChainSyncBytes + 2 * act;
+    if (s == FLE_OK) *bytes_out = kChainSyncBytes + size_t(p->n_layers - 1) * act;
     return s;
 }
 
@@ -669,14 +671,14 @@ fle_status fle_chain_run(const fle_chain *p) {
     fle_status s = check_chain(p, &act);
     if (s != FLE_OK) return s;
     char *ws = reinterpret_cast<char *>(p->workspace);
-    const size_t need = kChainSyncBytes + 2 * act;
+    const size_t need = kChainSyncBytes + size_t(p->n_layers - 1) * act;
     if (!ws) return fail(FLE_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
     if (p->workspace_bytes < need) return fail(FLE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, need);
     if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(FLE_ERR_ALIGN, "workspace must be 256-byte aligned");
     const size_t es = esize(p->dtype);
     if (overlaps(ws, need, p->x, size_t(p->layers[0].k) * es) || overlaps(ws, need, p->out, size_t(p->layers[p->n_layers - 1].n) * es))
         return fail(FLE_ERR_UNSUPPORTED, "the workspace overlaps x or out");
-    return launch_chain(p, ws, ws + kChainSyncBytes, ws + kChainSyncBytes + act);
+    return launch_chain(p, ws, ws + kChainSyncBytes, act);
 }
 
 const char *fle_status_string(fle_status s) {

@@ -215,11 +215,12 @@ fle_status launch_attention(const fle_attention *p) {
     return check_launch("flash_attention");
 }
 
-fle_status launch_chain(const fle_chain *p, void *sync, void *act0, void *act1) {
+fle_status launch_chain(const fle_chain *p, void *sync, void *acts, size_t act_stride) {
     hipStream_t stream = reinterpret_cast<hipStream_t>(p->stream);
     ChainArgs a;
     a.n_layers = p->n_layers;
-    a.x = p->x; a.out = p->out; a.act[0] = act0; a.act[1] = act1; a.sync = reinterpret_cast<uint32_t *>(sync);
+    a.x = p->x; a.out = p->out; a.sync = reinterpret_cast<uint32_t *>(sync);
+    for (int l = 0; l < kChainMaxLayers; ++l) a.act[l] = acts ? reinterpret_cast<char *>(acts) + size_t(l) * act_stride : nullptr;
     int64_t widest = 0;
     for (int l = 0; l < p->n_layers; ++l) {
         a.layer[l].w = p->layers[l].w; a.layer[l].bias = p->layers[l].b;
@@ -238,9 +239,15 @@ fle_status launch_chain(const fle_chain *p, void *sync, void *act0, void *act1) 
     const int cus = cu_count[dev];
     const int64_t want = (widest + 15) / 16;
     const uint32_t grid = uint32_t(want < cus ? want : cus);
-    if (p->dtype == FLE_F32) hipLaunchKernelGGL(mlp_chain<FLE_F32>, dim3(grid), dim3(1024), 0, stream, a);
-    else if (p->dtype == FLE_F16) hipLaunchKernelGGL(mlp_chain<FLE_F16>, dim3(grid), dim3(1024), 0, stream, a);
-    else hipLaunchKernelGGL(mlp_chain<FLE_BF16>, dim3(grid), dim3(1024), 0, stream, a);
+    if (p->dtype == FLE_F32) {
+        if (p->w_dtype == FLE_BF16) hipLaunchKernelGGL((mlp_chain<FLE_F32, FLE_BF16>), dim3(grid), dim3(1024), 0, stream, a);
+        else if (p->w_dtype == FLE_F16) hipLaunchKernelGGL((mlp_chain<FLE_F32, FLE_F16>), dim3(grid), dim3(1024), 0, stream, a);
+        else hipLaunchKernelGGL((mlp_chain<FLE_F32, FLE_F32>), dim3(grid), dim3(1024), 0, stream, a);
+    } else if (p->dtype == FLE_F16) {
+        hipLaunchKernelGGL((mlp_chain<FLE_F16, FLE_F16>), dim3(grid), dim3(1024), 0, stream, a);
+    } else {
+        hipLaunchKernelGGL((mlp_chain<FLE_BF16, FLE_BF16>), dim3(grid), dim3(1024), 0, stream, a);
+    }
     return check_launch("mlp_chain");
 }
 

@@ -65,8 +65,8 @@ fle_status fail(fle_status s, const char *fmt, ...);
 fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *groups = nullptr);
 
 // Implemented in the kernel translation unit: enqueue the persistent perceptron kernel for an already validated
-// chain (sync: the barrier words, act0 / act1: the two activation buffers, all in the workspace).
-fle_status launch_chain(const fle_chain *p, void *sync, void *act0, void *act1);
+// chain (sync: the barrier words; acts: one activation buffer per layer boundary, act_stride bytes apart; all in the workspace).
+fle_status launch_chain(const fle_chain *p, void *sync, void *acts, size_t act_stride);
 
 // Implemented in the kernel translation unit: enqueue the attention kernel for an already validated problem.
 fle_status launch_attention(const fle_attention *p);

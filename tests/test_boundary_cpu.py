@@ -491,13 +491,14 @@ def test_attention_block_validation_and_workspace(L):
 
 
 # ------------------------------------------------------------------ perceptron chain (host-side validation only)
-def chain(widths=(256, 512, 128), dtype=binding.F32, act=2, ws=7 * G, ws_bytes=1 << 20):
+def chain(widths=(256, 512, 128), dtype=binding.F32, act=2, ws=7 * G, ws_bytes=1 << 20, w_dtype=None):
     n = len(widths) - 1
     arr = (binding.FleChainLayer * n)()
     for i in range(n):
         arr[i].w, arr[i].b, arr[i].n, arr[i].k, arr[i].act = (10 + i) * G, (30 + i) * G, widths[i + 1], widths[i], act
     p = binding.FleChain()
     p.dtype, p.n_layers, p.layers, p.x, p.out = dtype, n, arr, G, 2 * G
+    p.w_dtype = dtype if w_dtype is None else w_dtype
     p.workspace, p.workspace_bytes = ws, ws_bytes
     p._keep = arr
     return p
@@ -508,6 +509,9 @@ def test_chain_validation_and_workspace(L):
     assert v(chain()) == OK
     assert v(chain(dtype=binding.BF16, act=-1)) == OK and v(chain(act=4)) == OK
     assert v(chain(act=7)) == E_OP                                   # softmax is not an activation of the chain
+    assert v(chain(w_dtype=binding.BF16)) == OK and v(chain(w_dtype=binding.F16)) == OK   # 2-byte weights under fp32
+    assert v(chain(dtype=binding.BF16, w_dtype=binding.F32)) == E_UNSUP and v(chain(dtype=binding.BF16, w_dtype=binding.F16)) == E_UNSUP
+    assert v(chain(widths=(260, 512, 128), w_dtype=binding.BF16)) == E_ALIGN   # 260 bf16 weights: 520 bytes per row
     assert v(chain(widths=(250, 512, 128))) == E_ALIGN               # 250 floats: not a multiple of 16 bytes
     assert v(chain(widths=(256,))) == E_SHAPE                        # no layer
     p = chain(); p.layers[1].k = 640
@@ -518,7 +522,7 @@ def test_chain_validation_and_workspace(L):
     assert v(p) == E_UNSUP                                           # out on top of the first weight matrix
     need = ctypes.c_size_t(0)
     assert L.fle_chain_workspace_size(ctypes.byref(chain()), ctypes.byref(need)) == OK
-    assert need.value == 2560 + 2 * 512 * 4                          # barrier state + two buffers of the widest hidden layer
+    assert need.value == 2560 + 1 * 512 * 4                          # barrier state + one buffer (of the widest hidden layer) per layer boundary
     assert L.fle_chain_run(ctypes.byref(chain(ws=None))) == E_WS
     assert L.fle_chain_run(ctypes.byref(chain(ws_bytes=1000))) == E_WS
     assert L.fle_chain_run(ctypes.byref(chain(ws=7 * G + 64))) == E_ALIGN

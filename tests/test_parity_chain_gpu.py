@@ -64,6 +64,24 @@ def test_chain_matches_oracle(dtype, widths, acts, bias):
     assert_close(got, oracle_chain(x, ws, bs, acts), dtype, factor=float(len(ws)) ** 0.5)
 
 
+@pytest.mark.parametrize("wdtype,widths,acts", [
+    (BF16, [4096, 4096, 4096, 4096], ["relu", "relu", "relu"]),
+    (F16, [1024, 2048, 1000], ["gelu_tanh", None]),
+    (BF16, [8, 24, 8], ["relu", None]),                                    # a W row of one 16-byte chunk
+    (BF16, [20000, 96, 4104], ["relu", "relu"]),
+])
+def test_chain_with_reduced_precision_weights(wdtype, widths, acts):
+    """fp32 input, biases, activations and output; weights stored in bf16 / fp16.  The oracle gets the same stored
+    weights (upcast exactly), so the comparison is at the fp32 tolerance: the precision was reduced when the
+    weights were prepared, not by the kernel."""
+    announce("chain mixed", wdtype, widths, acts)
+    x, ws, bs, acts = random_chain(31 + len(widths), widths, F32, acts)
+    ws = [w.to(wdtype) for w in ws]
+    got = run_chain(x, ws, bs, acts)
+    assert got.dtype == F32
+    assert_close(got, oracle_chain(x, ws, bs, acts), F32, factor=float(len(ws)) ** 0.5)
+
+
 def test_chain_equals_the_separate_calls_bit_for_bit_in_fp32():
     """fp32: a layer in the chain and the same layer as its own fused call sum in different orders, so only the
     oracle decides; but two runs of the chain must agree exactly (fixed summation order, no atomics)."""
