@@ -23,10 +23,10 @@ _SRC = os.path.join(_HERE, "fle_oracle.c")
 _LIB = os.path.join(_HERE, "libfle_oracle.so")
 
 # op kinds, in the numbering of fle_oracle.c
-BIAS, SCALE, RELU, GELU_ERF, GELU_TANH, RESIDUAL, LAYERNORM, SOFTMAX, LOGSUMEXP = range(9)
+BIAS, SCALE, RELU, GELU_ERF, GELU_TANH, RESIDUAL, LAYERNORM, SOFTMAX, LOGSUMEXP, STORE = range(10)
 _KINDS = {
     "bias": BIAS, "scale": SCALE, "relu": RELU, "gelu_erf": GELU_ERF, "gelu_tanh": GELU_TANH,
-    "residual": RESIDUAL, "layernorm": LAYERNORM, "softmax": SOFTMAX, "logsumexp": LOGSUMEXP,
+    "residual": RESIDUAL, "layernorm": LAYERNORM, "softmax": SOFTMAX, "logsumexp": LOGSUMEXP, "store": STORE,
 }
 
 
@@ -96,6 +96,10 @@ def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
         ("bias",) ("scale", alpha) ("relu",) ("gelu_erf",) ("gelu_tanh",)
         ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps)
         ("softmax",) ("logsumexp",)       -- logsumexp only as the last entry.
+        ("store", t[M,N])                 -- t (a float64 array, written in place) receives a copy of the
+                                             values as they stand at this point of the chain; the chain
+                                             goes on unchanged.  This is how a producer hands over both a
+                                             value and its normalisation (x + f(x) and LayerNorm of it).
     alpha and eps cross the GPU boundary as fp32, so they are rounded to fp32
     here too (Appendix A compares like with like).
     Returns [M,N] float64, or [M] when the list ends in logsumexp.
@@ -118,6 +122,13 @@ def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
                 raise ValueError("residual must be [M,N]")
             keep.append(r)
             ops[i].p0 = r.ctypes.data
+            ops[i].ld = N
+        elif kind == STORE:
+            t = e[1]
+            if not isinstance(t, np.ndarray) or t.dtype != np.float64 or t.shape != (M, N) or not t.flags.c_contiguous:
+                raise ValueError("store needs a C-contiguous float64 array [M,N]")
+            keep.append(t)
+            ops[i].p0 = t.ctypes.data
             ops[i].ld = N
         elif kind == LAYERNORM:
             g, be = _f64(e[1]), _f64(e[2])

@@ -33,13 +33,14 @@ enum {
     ORC_RESIDUAL = 5,  /* z[n] += r[m, n]                                     */
     ORC_LAYERNORM = 6, /* over the row, biased variance, eps inside the sqrt  */
     ORC_SOFTMAX = 7,   /* over the row, max-shifted                           */
-    ORC_LOGSUMEXP = 8  /* over the row, max-shifted; output becomes one value */
+    ORC_LOGSUMEXP = 8, /* over the row, max-shifted; output becomes one value */
+    ORC_STORE = 9      /* t[m, n] = z[n]: a copy of the row as it stands; z unchanged */
 };
 
 typedef struct {
     int32_t kind;
     double alpha;     /* SCALE: factor.  LAYERNORM: eps.                       */
-    const double *p0; /* RESIDUAL: r[M, ld].  LAYERNORM: gamma[N] or NULL (=1) */
+    const double *p0; /* RESIDUAL: r[M, ld].  LAYERNORM: gamma[N] or NULL (=1).  STORE: t[M, ld] (written) */
     const double *p1; /* LAYERNORM: beta[N] or NULL (=0)                       */
     int64_t ld;       /* RESIDUAL: row stride of r in elements                 */
 } orc_op;
@@ -94,6 +95,9 @@ static int64_t row_apply(const orc_op *op, int64_t m, int64_t N, const double *b
         for (int64_t n = 0; n < N; ++n) z[n] += r[n];
         return N;
     }
+    case ORC_STORE:
+        memcpy((double *)op->p0 + m * op->ld, z, sizeof(double) * (size_t)N);
+        return N;
     case ORC_LAYERNORM: {
         double mu = 0.0, var = 0.0;
         for (int64_t n = 0; n < N; ++n) mu += z[n];
@@ -148,7 +152,8 @@ int fle_oracle_run(int64_t M, int64_t N, int64_t K, const double *x, int64_t ldx
     int ends_in_lse = 0;
     for (int32_t i = 0; i < n_ops; ++i) {
         int32_t kd = ops[i].kind;
-        if (kd < ORC_BIAS || kd > ORC_LOGSUMEXP) return -3;
+        if (kd < ORC_BIAS || kd > ORC_STORE) return -3;
+        if (kd == ORC_STORE && (!ops[i].p0 || ops[i].ld < N)) return -2;
         if (kd == ORC_BIAS && !b) return -2;
         if (kd == ORC_RESIDUAL && !ops[i].p0) return -2;
         if (kd == ORC_LOGSUMEXP) {

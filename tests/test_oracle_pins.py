@@ -268,6 +268,23 @@ def test_structural_invariants():
     assert np.array_equal(np.vstack([top, bot]), base)                                            # split M
 
 
+def test_store_copies_the_values_at_its_place_in_the_chain():
+    M, N, K = 5, 7, 3
+    x, w, b, r = RNG.standard_normal((M, K)), RNG.standard_normal((N, K)), RNG.standard_normal(N), RNG.standard_normal((M, N))
+    g, be = RNG.standard_normal(N), RNG.standard_normal(N)
+    t1, t2, t3 = (np.full((M, N), np.nan) for _ in range(3))
+    out = run(x, w, b, [("store", t1), ("bias",), ("residual", r), ("store", t2), ("layernorm", g, be, 1e-5), ("store", t3), ("relu",)])
+    # each copy equals the chain cut off at that point, and the chain's own result is what it is without the stores
+    np.testing.assert_array_equal(t1, run(x, w, b, []))
+    np.testing.assert_array_equal(t2, run(x, w, b, [("bias",), ("residual", r)]))
+    np.testing.assert_array_equal(t3, run(x, w, b, [("bias",), ("residual", r), ("layernorm", g, be, 1e-5)]))
+    np.testing.assert_array_equal(out, run(x, w, b, [("bias",), ("residual", r), ("layernorm", g, be, 1e-5), ("relu",)]))
+    # independent values: t2 is x w^T + b + r by numpy
+    np.testing.assert_allclose(t2, x @ w.T + b + r, rtol=1e-13, atol=1e-13)
+    with pytest.raises(ValueError):
+        run(x, w, b, [("store", np.zeros((M, N + 1)))])
+
+
 def test_rejects_bad_arguments():
     x = np.zeros((2, 3)); w = np.zeros((4, 3))
     with pytest.raises(ValueError):
