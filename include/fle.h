@@ -64,7 +64,12 @@ typedef enum {
     FLE_LAYERNORM = 6, /* over n: (v - mean) / sqrt(biased var + alpha) * gamma[n] + beta[n];
                           p0 = gamma or NULL (1), p1 = beta or NULL (0), alpha = eps        */
     FLE_SOFTMAX = 7,   /* over n: exp(v - max) / sum exp(v - max)                           */
-    FLE_LOGSUMEXP = 8  /* over n: max + log sum exp(v - max); out becomes [M]; last op only */
+    FLE_LOGSUMEXP = 8, /* over n: max + log sum exp(v - max); out becomes [M]; last op only */
+    FLE_STORE = 9      /* t[m,n] = v, rounded to the dtype; v itself goes on unchanged (p0 = t, ld).
+                          Allowed before the row op (or anywhere in a list without one).  It is how
+                          one call hands over both a value and its normalisation, e.g. bias, residual,
+                          STORE, LAYERNORM gives x + f(x) in t and its LayerNorm in out: what a
+                          pre-norm transformer layer needs from the call that ends the previous block */
 } fle_op_kind;
 
 #define FLE_MAX_OPS 8
@@ -72,9 +77,10 @@ typedef enum {
 typedef struct {
     int32_t kind;   /* fle_op_kind */
     float alpha;    /* SCALE: factor.  LAYERNORM: eps.  Otherwise ignored.                 */
-    const void *p0; /* RESIDUAL: r[M,N] (device).  LAYERNORM: gamma[N] (device) or NULL.   */
+    const void *p0; /* RESIDUAL: r[M,N] (device).  LAYERNORM: gamma[N] (device) or NULL.
+                       STORE: t[M,N] (device, written; must not overlap any other operand) */
     const void *p1; /* LAYERNORM: beta[N] (device) or NULL.                                */
-    int64_t ld;     /* RESIDUAL: row stride of r in elements (>= N).                       */
+    int64_t ld;     /* RESIDUAL / STORE: row stride of r / t in elements (>= N).           */
 } fle_op;
 
 typedef struct {
@@ -99,8 +105,9 @@ typedef struct {
 
 /*
  * Accepted epilogue grammar:   elementwise*  [ LAYERNORM | SOFTMAX | LOGSUMEXP ]  elementwise*
- * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL, at most one row
- * op, and nothing after LOGSUMEXP.  A second row op gives FLE_ERR_UNSUPPORTED.
+ * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL | STORE (STORE only before
+ * the row op), at most one row op, and nothing after LOGSUMEXP.  A second row op gives
+ * FLE_ERR_UNSUPPORTED.
  *
  * Alignment rule: no alignment is required for correctness.  The fast kernels (tiled MFMA
  * kernels for every dtype; the skinny and thin kernels that stream W for up to 256, 32 or 8

@@ -173,7 +173,8 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0
         lo, hi = offsets[g], offsets[g + 1]
         if hi == lo:
             continue
-        ep = [("residual", np.asarray(e[1])[lo:hi]) if e[0] == "residual" else e for e in epilogue]
+        # [M,N] operands are cut to the group's rows (a store target as a view, written in place)
+        ep = [(e[0], np.asarray(e[1])[lo:hi]) if e[0] in ("residual", "store") else e for e in epilogue]
         bg = None if b is None else (b[g] if b.ndim == 2 else b)
         out[lo:hi] = fused_linear_epilogue(x[lo:hi], w[g], bg, ep, n_threads)
     return out

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libfle.so")
 
 F32, BF16, F16 = 0, 1, 2
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
-            "layernorm": 6, "softmax": 7, "logsumexp": 8}
+            "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9}
 MAX_OPS = 8
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
 EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
@@ -204,6 +204,13 @@ class Call:
                 tensors.append(r)
                 ops[i].p0 = r.data_ptr()
                 ops[i].ld = r.stride(0) if M > 1 else max(N, r.stride(0))
+            elif e[0] == "store":
+                t = e[1]
+                if t.shape != (M, N) or (t.stride(1) != 1 and N > 1):
+                    raise ValueError("store target must be [M,N] with unit column stride")
+                tensors.append(t)
+                ops[i].p0 = t.data_ptr()
+                ops[i].ld = t.stride(0) if M > 1 else max(N, t.stride(0))
             elif e[0] == "layernorm":
                 g, be, eps = e[1], e[2], e[3]
                 tensors += [g, be]
@@ -289,7 +296,8 @@ def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="
 
     x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32, bfloat16 or float16).
     epilogue: ordered list of ("bias",) ("scale", a) ("relu",) ("gelu_erf",) ("gelu_tanh",)
-    ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",).
+    ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",)
+    ("store", t[M,N]): t receives a copy of the values at that point of the list (before the row op only).
     Returns a tensor of x's dtype: [M,N], or [M] when the list ends in logsumexp.
     """
     if not x.is_cuda:

@@ -152,6 +152,7 @@ __device__ __forceinline__ float apply_op(const DevOp &op, float v, int64_t m, i
     case FLE_GELU_ERF: return gelu_erf_f(v);
     case FLE_GELU_TANH: return gelu_tanh_f(v);
     case FLE_RESIDUAL: return v + ld_elem(op.p0, m * op.ld + n, dtype);
+    case FLE_STORE: st_elem(const_cast<void *>(op.p0), m * op.ld + n, dtype, v); return v;
     default: return v;
     }
 }

@@ -253,6 +253,25 @@ __device__ __forceinline__ void gemm_bf16_skinny_body(const GemmArgs &a) {
                 }
             }
             break;
+        case FLE_STORE:  // a copy of the values as they stand, rounded to the dtype
+#pragma unroll
+            for (int t = 0; t < TMB; ++t) {
+                const int64_t m = m0 + 32 * t + (lane & 31);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t n = n_lane + 8 * q;
+                    if (m < M && n < N) {
+                        const f32x4 v = f32x4{acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+                        if constexpr (F32) {
+                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(const_cast<void *>(op.p0)) + m * op.ld + n) = v;
+                        } else {
+                            constexpr int DT2 = F32 ? FLE_BF16 : DT;
+                            *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(const_cast<void *>(op.p0)) + m * op.ld + n) = pack4<DT2>(v);
+                        }
+                    }
+                }
+            }
+            break;
         default: break;
         }
     }

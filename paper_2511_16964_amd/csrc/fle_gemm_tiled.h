@@ -525,6 +525,26 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                     }
                 }
                 break;
+            case FLE_STORE:  // a copy of the values as they stand, rounded to the dtype; rows and columns inside the matrix only
+#pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int64_t m = m_blk + 4 * it + rsub;
+#pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (m < M && n_ok[hc]) {
+                            if constexpr (EDGE) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) st_elem(const_cast<void *>(op.p0), m * op.ld + n_col[hc] + e, DT, v[it][hc][e]);
+                            } else if constexpr (F32) {
+                                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = v[it][hc];
+                            } else {
+                                constexpr int DT2 = F32 ? FLE_BF16 : DT;
+                                *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = pack4<DT2>(v[it][hc]);
+                            }
+                        }
+                }
+                break;
             default: break;
             }
         }

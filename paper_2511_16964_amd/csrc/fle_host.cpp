@@ -73,7 +73,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     const size_t es = esize(p->dtype);
     for (int i = 0; i < p->n_ops; ++i) {
         const fle_op &op = p->ops[i];
-        if (op.kind < FLE_BIAS || op.kind > FLE_LOGSUMEXP) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (op.kind < FLE_BIAS || op.kind > FLE_STORE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
         if (e.row_kind == FLE_LOGSUMEXP) return fail(FLE_ERR_UNSUPPORTED, "op %d follows logsumexp, which must be last", i);
         DevOp d{op.kind, op.alpha, op.p0, op.p1, op.ld};
         if (is_row_op(op.kind)) {
@@ -85,10 +85,12 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         }
         if (op.kind == FLE_BIAS && !p->b && M > 0) return fail(FLE_ERR_NULL, "op %d: bias listed but b is NULL", i);
         if (op.kind == FLE_SCALE && !std::isfinite(op.alpha)) return fail(FLE_ERR_OP, "op %d: scale factor is not finite", i);
-        if (op.kind == FLE_RESIDUAL) {
-            if (!op.p0 && M > 0) return fail(FLE_ERR_NULL, "op %d: residual pointer is NULL", i);
-            if (op.ld < N) return fail(FLE_ERR_SHAPE, "op %d: residual ld %lld < N %lld", i, (long long)op.ld, (long long)N);
-            if (op.ld > kLimit) return fail(FLE_ERR_SHAPE, "op %d: residual ld too large", i);
+        if (op.kind == FLE_RESIDUAL || op.kind == FLE_STORE) {
+            const char *what = op.kind == FLE_STORE ? "store" : "residual";
+            if (!op.p0 && M > 0) return fail(FLE_ERR_NULL, "op %d: %s pointer is NULL", i, what);
+            if (op.ld < N) return fail(FLE_ERR_SHAPE, "op %d: %s ld %lld < N %lld", i, what, (long long)op.ld, (long long)N);
+            if (op.ld > kLimit) return fail(FLE_ERR_SHAPE, "op %d: %s ld too large", i, what);
+            if (op.kind == FLE_STORE && e.row_kind >= 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: a store after the row op is not supported", i);
         }
         if (e.row_kind < 0) e.pre[e.n_pre++] = d; else e.post[e.n_post++] = d;
     }
@@ -114,6 +116,19 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
                 if (!aligned(op.p0, es)) return fail(FLE_ERR_ALIGN, "op %d: residual pointer not aligned to its element size", i);
                 const bool same = op.p0 == p->out && op.ld == p->ldo && !lse;
                 if (!same && overlaps(p->out, out_bytes, op.p0, span_bytes(M, N, op.ld, es))) return fail(FLE_ERR_UNSUPPORTED, "op %d: out overlaps the residual without being identical to it", i);
+            } else if (op.kind == FLE_STORE) {
+                if (!aligned(op.p0, es)) return fail(FLE_ERR_ALIGN, "op %d: store pointer not aligned to its element size", i);
+                const size_t t_bytes = span_bytes(M, N, op.ld, es);
+                bool clash = overlaps(op.p0, t_bytes, p->out, out_bytes) || overlaps(op.p0, t_bytes, p->x, span_bytes(M, K, p->ldx, es)) ||
+                             overlaps(op.p0, t_bytes, p->w, w_bytes) || overlaps(op.p0, t_bytes, p->b, b_bytes) ||
+                             overlaps(op.p0, t_bytes, p->workspace, p->workspace_bytes) || (grp && overlaps(op.p0, t_bytes, grp->row_offsets, size_t(G + 1) * 8));
+                for (int j = 0; j < p->n_ops && !clash; ++j) {
+                    const fle_op &o2 = p->ops[j];
+                    if (j == i) continue;
+                    if (o2.kind == FLE_RESIDUAL || o2.kind == FLE_STORE) clash = overlaps(op.p0, t_bytes, o2.p0, span_bytes(M, N, o2.ld, es));
+                    else if (o2.kind == FLE_LAYERNORM) clash = overlaps(op.p0, t_bytes, o2.p0, size_t(N) * es) || overlaps(op.p0, t_bytes, o2.p1, size_t(N) * es);
+                }
+                if (clash) return fail(FLE_ERR_UNSUPPORTED, "op %d: the store target overlaps another operand, out or the workspace", i);
             } else if (op.kind == FLE_LAYERNORM) {
                 if (!aligned(op.p0, es) || !aligned(op.p1, es)) return fail(FLE_ERR_ALIGN, "op %d: gamma/beta not aligned to the element size", i);
                 if (overlaps(p->out, out_bytes, op.p0, size_t(N) * es) || overlaps(p->out, out_bytes, op.p1, size_t(N) * es)) return fail(FLE_ERR_UNSUPPORTED, "op %d: out overlaps gamma or beta", i);
@@ -129,8 +144,9 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     const size_t vec4 = 4 * es;                              // alignment of a 4-column group
     const int64_t ld_max = int64_t(1) << (f32 ? 20 : 21);    // 32-bit byte offsets inside a 256-row tile
     bool res_ok = true, post_res_alias_out = false;
-    for (int i = 0; i < e.n_pre; ++i)
-        if (e.pre[i].kind == FLE_RESIDUAL && !(aligned(e.pre[i].p0, vec4) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < ld_max)) res_ok = false;
+    for (int i = 0; i < e.n_pre; ++i) {
+        if ((e.pre[i].kind == FLE_RESIDUAL || e.pre[i].kind == FLE_STORE) && !(aligned(e.pre[i].p0, vec4) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < ld_max)) res_ok = false;
+    }
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
     // x and W rows must be whole, aligned 16-byte chunks; everything the epilogue touches may be ragged
@@ -708,6 +724,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 600; }  // 0.6.0: perceptron chain (0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
+int fle_version(void) { return 700; }  // 0.7.0: store op (0.6.0: perceptron chain; 0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
 
 }  // extern "C"

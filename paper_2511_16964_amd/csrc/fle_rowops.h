@@ -262,6 +262,19 @@ __global__ __launch_bounds__(256) void reduce_slabs(const RedArgs a) {
                     for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
                     break;
                 case FLE_RESIDUAL: add4(op.p0, row * op.ld + n); break;
+                case FLE_STORE: {  // a copy of the values as they stand, rounded to the dtype
+                    void *tp = const_cast<void *>(op.p0);
+                    if (!vec) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (okc[e]) st_elem(tp, row * op.ld + n + e, dtype, v[e]);
+                    } else if (f32) {
+                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(tp) + row * op.ld + n) = v;
+                    } else {
+                        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(tp) + row * op.ld + n) = pack4_rt(v, dtype);
+                    }
+                    break;
+                }
                 default: break;
                 }
             }

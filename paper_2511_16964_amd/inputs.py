@@ -155,6 +155,8 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
         elif kd == "layernorm":
             g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
             ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+        elif kd == "store":   # the target: an output, pre-filled so that an unwritten element shows
+            ep.append(("store", torch.full((M, N), -7.0, dtype=dtype)))
         else:
             ep.append((kd,))
     return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), ep)
@@ -222,6 +224,8 @@ def random_grouped(seed: int, counts, N: int, K: int, dtype: torch.dtype, kinds:
         elif kd == "layernorm":
             g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
             ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+        elif kd == "store":   # the target: an output, pre-filled so that an unwritten element shows
+            ep.append(("store", torch.full((M, N), -7.0, dtype=dtype)))
         else:
             ep.append((kd,))
     return GroupedProblem(dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), offsets_of(counts), ep)
@@ -338,6 +342,9 @@ def epilogue_f64(epilogue, rows=None):
             out.append(("residual", to_f64(r)))
         elif e[0] == "layernorm":
             out.append(("layernorm", to_f64(e[1]), to_f64(e[2]), e[3]))
+        elif e[0] == "store":   # a fresh float64 target of the selected rows; the caller reads it back from the list
+            t = e[1] if rows is None else e[1][rows]
+            out.append(("store", np.full(tuple(t.shape), np.nan, dtype=np.float64)))
         else:
             out.append(tuple(e))
     return out

@@ -296,6 +296,52 @@ def test_split_k_planning(L):
     assert split(text) == 1, text
 
 
+def test_store_validation_and_planning(L):
+    """The store op: a second output [M,N] that takes a copy of the values at its place in the list."""
+    t = 6 * G
+    pre_norm = [op("bias"), op("residual", p0=G, ld=64), op("store", p0=t, ld=64), op("layernorm", 1e-5, 7 * G, 8 * G)]
+    p = problem(ops=pre_norm); p.x = 3 * G + G // 2                     # the residual is not x here
+    assert validate(L, p) == OK
+    assert validate(L, problem(ops=[op("store", p0=t, ld=64), op("store", p0=t + G // 2, ld=80)])) == OK
+    assert validate(L, problem(ops=[op("store", p0=None, ld=64)])) == E_NULL
+    assert validate(L, problem(ops=[op("store", p0=t, ld=63)])) == E_SHAPE
+    assert validate(L, problem(ops=[op("store", p0=t + 1, ld=64)])) == E_ALIGN
+    # only before the row op
+    assert validate(L, problem(ops=[op("softmax"), op("store", p0=t, ld=64)])) == E_UNSUP
+    assert b"store" in L.fle_last_error()
+    assert validate(L, problem(ops=[op("store", p0=t, ld=64), op("logsumexp")])) == OK
+    # the target overlaps nothing else the call reads or writes
+    q = problem()
+    for other in (q.x, q.w, q.b, q.out, q.out + 2):
+        assert validate(L, problem(ops=[op("store", p0=other, ld=64)])) == E_UNSUP, hex(other)
+    assert validate(L, problem(ops=[op("residual", p0=t, ld=64), op("store", p0=t, ld=64)])) == E_UNSUP
+    assert validate(L, problem(ops=[op("store", p0=t, ld=64), op("relu"), op("store", p0=t + 64, ld=64)])) == E_UNSUP
+    assert validate(L, problem(ops=[op("store", p0=7 * G, ld=64), op("layernorm", 1e-5, 7 * G, 8 * G)])) == E_UNSUP
+    p = problem(M=128, N=4096, K=4096, ops=[op("softmax")]); p.workspace, p.workspace_bytes = t, 1 << 26
+    assert validate(L, p) == OK
+    p = problem(M=128, N=4096, K=4096, ops=[op("store", p0=t + 4096, ld=4096), op("softmax")]); p.workspace, p.workspace_bytes = t, 1 << 26
+    assert validate(L, p) == E_UNSUP
+    # a split along K keeps the op: the reduction pass writes the copy
+    need = ctypes.c_size_t(0)
+    buf = ctypes.create_string_buffer(256)
+    p = problem(M=128, N=4096, K=4096, ops=[op("store", p0=t, ld=4096)])
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    L.fle_last_plan(buf, 256)
+    sp = int(re.search(r"split_k=(\d+)", buf.value.decode()).group(1))
+    assert sp > 1 and need.value == sp * 128 * 4096 * 4, buf.value
+    # every kernel family takes the op; an unaligned target or leading dimension falls back to element stores
+    for shape, name in (((4096, 4096, 4096), "tiled"), ((16, 2048, 2048), "thin"), ((64, 4096, 4096), "skinny"), ((64, 63, 64), "general")):
+        M, N, K = shape
+        p = problem(M=M, N=N, K=K, ops=[op("bias"), op("store", p0=t, ld=N)])
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        L.fle_last_plan(buf, 256)
+        assert name in buf.value.decode(), (shape, buf.value)
+    p = problem(M=4096, N=4096, K=4096, ops=[op("store", p0=t + 2, ld=4098)])
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    L.fle_last_plan(buf, 256)
+    assert "edge" in buf.value.decode() or "general" in buf.value.decode(), buf.value
+
+
 # ---------------------------------------------------------------- grouped problems
 def groups(n=8, offs=9 * G, w_stride=None, b_stride=None, N=1024, K=512):
     g = binding.FleGroups()
