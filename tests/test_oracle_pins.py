@@ -319,6 +319,22 @@ def test_grouped_equals_one_hot_masked_sum():
     np.testing.assert_allclose(grouped(x, w, b[0], off, [("bias",)]), np.einsum("mg,mgn->mn", onehot, np.einsum("mk,gnk->mgn", x, w)) + b[0], atol=1e-13)
 
 
+def test_grouped_store_targets_follow_the_groups():
+    """Independent formulation (numpy only): a store after bias and residual holds, in row m, x[m] W_g^T + b_g + r[m]
+    of the group g that owns the row; rows of no group do not exist, so every element is written."""
+    counts = [2, 0, 4, 3]
+    off = np.concatenate([[0], np.cumsum(counts)])
+    M, N, K = int(off[-1]), 6, 5
+    x = RNG.standard_normal((M, K)); w = RNG.standard_normal((4, N, K)); b = RNG.standard_normal((4, N)); r = RNG.standard_normal((M, N))
+    t = np.full((M, N), np.nan)
+    out = grouped(x, w, b, off, [("bias",), ("residual", r), ("store", t), ("relu",)])
+    owner = np.repeat(np.arange(4), counts)
+    want = np.einsum("mk,mnk->mn", x, w[owner]) + b[owner] + r
+    np.testing.assert_allclose(t, want, atol=1e-13)
+    np.testing.assert_allclose(out, np.maximum(want, 0.0), atol=1e-13)
+    assert np.abs(want - (np.einsum("mk,mnk->mn", x, w[np.roll(owner, 1)]) + b[owner] + r)).max() > 0.1   # a shifted owner differs
+
+
 def test_grouped_reductions_and_plain_form():
     counts = [4, 2, 6]
     off = [0, 4, 6, 12]
