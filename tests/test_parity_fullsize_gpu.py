@@ -159,3 +159,28 @@ def test_a2_attention_fullsize_sampled_queries():
     sub = f64(qkv[0:1, :300][:, :, :, [7]])
     ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal)
     assert_close(got[0:1, :300][:, :, [7]].cpu(), ref, dt, "a2 first queries", s=value_scale(qkv[:, :, 2]))
+
+
+@pytest.mark.parametrize("name,at", [("c2", 2), ("c3", 2)])
+def test_full_size_with_a_store(name, at):
+    """The benchmark shapes with a store put into their lists (c2: after the ReLU; c3: in front of the
+    LayerNorm): out and the copy on sampled rows, and a property that holds at any size: no element of
+    the copy keeps the fill, i.e. every tile wrote its part."""
+    import oracle
+    from parity import to_dev
+    from paper_2511_16964_amd import binding
+    prob = inputs.make(name)
+    announce(name, "with a store at", at, prob.M, prob.N, prob.K)
+    t = torch.full((prob.M, prob.N), float("nan"), dtype=prob.dtype, device="cuda:0")
+    ep_cpu = list(prob.epilogue[:at]) + [("store", torch.empty(prob.M, prob.N, dtype=prob.dtype))] + list(prob.epilogue[at:])
+    ep_dev = [("store", t) if e[0] == "store" else tuple(to_dev(a) if isinstance(a, torch.Tensor) else a for a in e) for e in ep_cpu]
+    call = binding.Call(to_dev(prob.x), to_dev(prob.w), to_dev(prob.b), ep_dev)
+    out = call.run()
+    torch.cuda.synchronize()
+    assert "tile=256x256" in call.plan(), call.plan()
+    rows = sample_rows(prob.M, 48)
+    ep64 = inputs.epilogue_f64(ep_cpu, rows)
+    ref = oracle.fused_linear_epilogue(inputs.to_f64(prob.x[rows]), inputs.to_f64(prob.w), inputs.to_f64(prob.b), ep64)
+    assert_close(out[rows].cpu(), ref, prob.dtype, name + " out")
+    assert_close(t[rows].cpu(), ep64[at][1], prob.dtype, name + " store")
+    assert not bool(torch.isnan(t).any())
