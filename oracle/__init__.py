@@ -233,3 +233,26 @@ def attention_block(x, w_qkv, b_qkv, w_o, b_o, heads: int, causal, residual=None
     ep = ([("bias",)] if b_o is not None else []) + ([("residual", _f64(residual).reshape(B * T, C))] if residual is not None else [])
     y = fused_linear_epilogue(o.reshape(B * T, C), w_o, b_o, ep, n_threads)
     return y.reshape(B, T, C)
+
+
+def transformer_layer(x, n, w_qkv, b_qkv, w_o, b_o, heads: int, causal, ln_mid, w1, b1, w2, b2, ln_out, n_threads: int = 0):
+    """float64 gold result of one pre-norm transformer layer, from its normalised input on: the unfused composition.
+
+    The paper's Level-3 style tasks are whole architectures made of such layers (attention block, then a
+    perceptron block, each added to the residual stream, each fed by a LayerNorm of it).  With x the residual
+    stream [B,T,C] and n [B,T,C] its normalised form (what the previous layer hands over):
+        h  = x + attention_block(n)                      (projections, attention, output projection + bias)
+        m  = LayerNorm_mid(h)
+        x' = h + gelu_erf(m w1^T + b1) w2^T + b2
+        n' = LayerNorm_out(x')                           (the next layer's normalised input)
+    ln_mid and ln_out are (gamma, beta, eps).  Returns (x', n'), both [B,T,C].
+    """
+    x = _f64(x)
+    B, T, C = x.shape
+    h = attention_block(n, w_qkv, b_qkv, w_o, b_o, heads, causal, residual=x, n_threads=n_threads).reshape(B * T, C)
+    eye = np.eye(C, dtype=np.float64)   # a LayerNorm alone, written as the epilogue of a product with the identity
+    m = fused_linear_epilogue(h, eye, None, [("layernorm", ln_mid[0], ln_mid[1], ln_mid[2])], n_threads)
+    u = fused_linear_epilogue(m, w1, b1, [("bias",), ("gelu_erf",)], n_threads)
+    x2 = fused_linear_epilogue(u, w2, b2, [("bias",), ("residual", h)], n_threads)
+    n2 = fused_linear_epilogue(x2, eye, None, [("layernorm", ln_out[0], ln_out[1], ln_out[2])], n_threads)
+    return x2.reshape(B, T, C), n2.reshape(B, T, C)

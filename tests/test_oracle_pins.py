@@ -544,3 +544,45 @@ def test_attention_rejects_bad_arguments():
         oracle.attention(q.astype(np.float32), k, v, False)
     with pytest.raises(ValueError):
         oracle.attention_block(np.zeros((1, 2, 6)), np.zeros((18, 6)), None, np.eye(6), None, 4, False)
+
+
+def test_transformer_layer_against_a_numpy_formulation():
+    """The pre-norm layer from its normalised input on, written independently: per sequence and head an
+    explicit masked softmax in numpy, LayerNorm from numpy's mean and variance, GELU from scipy's erf."""
+    B, T, C, heads, Fh = 2, 7, 12, 3, 20
+    D = C // heads
+    x = RNG.standard_normal((B, T, C)); n = RNG.standard_normal((B, T, C))
+    w_qkv = RNG.standard_normal((3 * C, C)) * 0.4; b_qkv = RNG.standard_normal(3 * C) * 0.1
+    w_o = RNG.standard_normal((C, C)) * 0.4; b_o = RNG.standard_normal(C) * 0.1
+    w1 = RNG.standard_normal((Fh, C)) * 0.4; b1 = RNG.standard_normal(Fh) * 0.1
+    w2 = RNG.standard_normal((C, Fh)) * 0.4; b2 = RNG.standard_normal(C) * 0.1
+    g1, be1, g2, be2 = (RNG.standard_normal(C) for _ in range(4))
+    eps = 1e-5
+
+    def ln(a, g, be):
+        mu = a.mean(axis=-1, keepdims=True); var = ((a - mu) ** 2).mean(axis=-1, keepdims=True)
+        return (a - mu) / np.sqrt(var + np.float64(np.float32(eps))) * g + be
+
+    for causal in (True, False):
+        got_x, got_n = oracle.transformer_layer(x, n, w_qkv, b_qkv, w_o, b_o, heads, causal, (g1, be1, eps), w1, b1, w2, b2, (g2, be2, eps))
+        qkv = n @ w_qkv.T + b_qkv
+        att = np.zeros((B, T, C))
+        scale = np.float64(np.float32(1 / math.sqrt(D)))
+        for b in range(B):
+            for hd in range(heads):
+                q = qkv[b, :, hd * D:(hd + 1) * D]; k = qkv[b, :, C + hd * D:C + (hd + 1) * D]; v = qkv[b, :, 2 * C + hd * D:2 * C + (hd + 1) * D]
+                s = q @ k.T * scale
+                if causal:
+                    s = np.where(np.arange(T)[None, :] <= np.arange(T)[:, None], s, -np.inf)
+                p = np.exp(s - s.max(axis=1, keepdims=True)); p /= p.sum(axis=1, keepdims=True)
+                att[b, :, hd * D:(hd + 1) * D] = p @ v
+        h = x + att @ w_o.T + b_o
+        m = ln(h, g1, be1)
+        pre = m @ w1.T + b1
+        want_x = h + (0.5 * pre * (1 + scipy.special.erf(pre / math.sqrt(2)))) @ w2.T + b2
+        want_n = ln(want_x, g2, be2)
+        np.testing.assert_allclose(got_x, want_x, rtol=1e-11, atol=1e-11)
+        np.testing.assert_allclose(got_n, want_n, rtol=1e-10, atol=1e-10)
+        # plausible mistakes differ: the perceptron added to x instead of h, or the middle LayerNorm taken of x
+        assert np.abs(want_x - (x + (want_x - h))).max() > 1e-2
+        assert np.abs(got_n - ln(h, g2, be2)).max() > 1e-2
