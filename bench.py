@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused linear + epilogue hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5|c1|g1|g2|m1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5|g1|g2|m1|m2|m3|a1|a2|l1]
 
 A step is one pass of the whole path (every kernel the call enqueues) over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s
@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
 # measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "m2": None, "m3": None, "a1": None, "a2": None}
+TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "m2": None, "m3": None, "a1": None, "a2": None, "l1": None}
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -210,6 +210,29 @@ def cpu_baseline_attention(apb, inputs, budget_s=12.0):
             "sample": "the first %d of %d tokens of %d of %d sequences, whole block, %.1f s" % (n, T, seqs, B, t)}
 
 
+def cpu_baseline_layer(lp, inputs, budget_s=12.0):
+    """The oracle's transformer layer on the first tokens of the first sequence (causal: they need nothing after them)."""
+    import oracle
+    f64 = inputs.to_f64
+    a = lp.attn
+    B, T, C = a.x.shape
+    Fh = lp.w1.shape[0]
+    def run(n_tok):
+        t0 = time.perf_counter()
+        oracle.transformer_layer(f64(a.x[:1, :n_tok]), f64(lp.n[:1, :n_tok]), f64(a.w_qkv), f64(a.b_qkv), f64(a.w_o), f64(a.b_o), a.heads, a.causal,
+                                 (f64(lp.g_mid), f64(lp.be_mid), lp.eps), f64(lp.w1), f64(lp.b1), f64(lp.w2), f64(lp.b2), (f64(lp.g_out), f64(lp.be_out), lp.eps))
+        return time.perf_counter() - t0
+    probe = min(T, 32)
+    t = run(probe)
+    n = int(max(probe, min(T, probe * budget_s / max(t, 1e-9))))
+    if n > probe:
+        t = run(n)
+    pairs = n * (n + 1) / 2 if a.causal else n * n
+    flops = 2.0 * n * C * 3 * C + 4.0 * pairs * C + 2.0 * n * C * C + 4.0 * n * C * Fh   # the layer's own work; the oracle's two identity products are not counted
+    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": "the first %d of %d tokens of one of %d sequences, whole layer, %.1f s" % (n, T, B, t)}
+
+
 def cpu_baseline_attention_kernel(qkv, causal, inputs, budget_s=12.0):
     """The oracle's attention on whole (sequence, head) problems of the same workload, as many as fill the budget."""
     import oracle
@@ -234,7 +257,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -331,6 +354,30 @@ def main():
             return F.linear(o.transpose(1, 2).reshape(B, T, C), wo, bo) + xg
         # x, both weight matrices and biases, the residual, out; qkv and the attention output written and read once
         alg_bytes = 2 * (3 * B * T * C + 4 * C * C + 4 * C + 2 * (3 * B * T * C + B * T * C))
+    elif args.workload == "l1":
+        # one pre-norm transformer layer from its normalised input on: five fused calls (plus the LayerNorm finalize passes)
+        lp = inputs.make_layer("a1")
+        apb = lp.attn
+        B, T, C = apb.x.shape
+        H, D, Fh = apb.heads, C // apb.heads, lp.w1.shape[0]
+        xg, ng, wqkv, bqkv, wo, bo = to(apb.x), to(lp.n), to(apb.w_qkv), to(apb.b_qkv), to(apb.w_o), to(apb.b_o)
+        w1g, b1g, w2g, b2g = to(lp.w1), to(lp.b1), to(lp.w2), to(lp.b2)
+        gm, bm, go, bo2 = to(lp.g_mid), to(lp.be_mid), to(lp.g_out), to(lp.be_out)
+        calls = [binding.TransformerLayerCall(xg, ng, wqkv, bqkv, wo, bo, H, apb.causal, (gm, bm, lp.eps), w1g, b1g, w2g, b2g, (go, bo2, lp.eps))]
+        probs = [apb]
+        flops = lp.flops
+        desc = "l1: pre-norm transformer layer from its normalised input on (%s attention block + LayerNorm + perceptron block + LayerNorm), bf16, B=%d T=%d C=%d heads=%d F=%d" % (
+            "causal" if apb.causal else "full", B, T, C, H, Fh)
+        def eager():
+            qkv = F.linear(ng, wqkv, bqkv)
+            q, k, v = (t.view(B, T, H, D).transpose(1, 2) for t in qkv.split(C, dim=2))
+            o = F.scaled_dot_product_attention(q, k, v, is_causal=apb.causal)
+            h = F.linear(o.transpose(1, 2).reshape(B, T, C), wo, bo) + xg
+            m = F.layer_norm(h, (C,), gm, bm, lp.eps)
+            x2 = F.linear(F.gelu(F.linear(m, w1g, b1g)), w2g, b2g) + h
+            return x2, F.layer_norm(x2, (C,), go, bo2, lp.eps)
+        # every activation written once and read once by its consumer (h and x read twice: residual), weights once
+        alg_bytes = 2 * (B * T * (2 * C + 2 * 3 * C + 2 * C + 3 * C + 2 * C + 2 * Fh + 2 * C) + 4 * C * C + 2 * C * Fh)
     elif args.workload == "a2":
         # the attention kernel alone, on q, k, v of a1's shape (views of one fused [B,T,3,H,D] buffer)
         dt0, B, T, C, H, causal = inputs.ATTENTION_SHAPES["a1"]
@@ -398,6 +445,14 @@ def main():
         sub = inputs.to_f64(qkv_cpu[b:b + 1][:, :, :, heads])
         ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal, first_query=first)
         got = calls[0].out[b:b + 1, first:][:, :, heads].cpu().to(torch.float64).numpy()
+    elif args.workload == "l1":
+        # the first tokens of the first sequence (causal mask: they depend on nothing after them); x' and n' side by side
+        n_tok = 131
+        f64 = inputs.to_f64
+        rx, rn = oracle.transformer_layer(f64(apb.x[:1, :n_tok]), f64(lp.n[:1, :n_tok]), f64(apb.w_qkv), f64(apb.b_qkv), f64(apb.w_o), f64(apb.b_o), apb.heads, apb.causal,
+                                          (f64(lp.g_mid), f64(lp.be_mid), lp.eps), f64(lp.w1), f64(lp.b1), f64(lp.w2), f64(lp.b2), (f64(lp.g_out), f64(lp.be_out), lp.eps))
+        ref = np.concatenate([rx[0], rn[0]], axis=1)
+        got = torch.cat([calls[0].x_out[0, :n_tok], calls[0].n_out[0, :n_tok]], dim=1).cpu().to(torch.float64).numpy()
     elif args.workload == "a1":
         # the first tokens of the first sequence: under the causal mask they depend on nothing after them
         n_tok = 131
@@ -418,6 +473,8 @@ def main():
     tol = 2e-2 if prob0.dtype == torch.bfloat16 else 1e-4
     if args.workload == "a1":
         tol *= 3.0 ** 0.5   # the block stores two intermediates in bf16: three roundings in sequence
+    if args.workload == "l1":
+        tol *= 6.0 ** 0.5   # qkv, o, h, m, u and the result: six storage roundings in sequence
     s = min(1.0, float(np.sqrt(np.mean(ref * ref))))
     if not np.all(np.abs(got - ref) <= tol * (s + np.abs(ref))):
         sys.exit("bench.py: GPU result fails parity against the oracle; no timing reported")
@@ -430,7 +487,7 @@ def main():
     cold_mean, cold_med, cold_min = time_cold(torch, step, 50, flush)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     out = {
-        "metric": {"a1": "fused attention block TFLOP/s", "a2": "attention TFLOP/s"}.get(args.workload, "fused GEMM+epilogue TFLOP/s"), "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": {"a1": "fused attention block TFLOP/s", "a2": "attention TFLOP/s", "l1": "transformer layer TFLOP/s"}.get(args.workload, "fused GEMM+epilogue TFLOP/s"), "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if prob0.dtype == torch.bfloat16 else "f32", "data": "synthetic",
@@ -462,7 +519,7 @@ def main():
                     c.run()
             lwall, _ = time_loop(torch, loop_step, max(10, args.steps // 4), 5)
             out["loop_of_plain_fused_calls"] = {"ms_per_step": lwall, "calls": len(loop_calls), "speedup_grouped_vs_loop": lwall / wall_ms}
-        elif args.workload not in ("a1", "a2", "m2", "m3"):
+        elif args.workload not in ("a1", "a2", "m2", "m3", "l1"):
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(calls[0]._tensors[0], calls[0]._tensors[1]), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
     if not args.no_cpu_baseline:
@@ -472,6 +529,8 @@ def main():
             out["cpu_baseline"] = cpu_baseline_chain(ch, inputs)
         elif args.workload == "a1":
             out["cpu_baseline"] = cpu_baseline_attention(apb, inputs)
+        elif args.workload == "l1":
+            out["cpu_baseline"] = cpu_baseline_layer(lp, inputs)
         elif args.workload == "a2":
             out["cpu_baseline"] = cpu_baseline_attention_kernel(qkv_cpu, causal, inputs)
         else:

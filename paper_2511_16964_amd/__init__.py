@@ -7,7 +7,7 @@ implementation: if the library is missing, calls raise.
 """
 import importlib
 
-__all__ = ["fused_linear_epilogue", "grouped_fused_linear_epilogue", "attention", "attention_block", "mlp_chain"]
+__all__ = ["fused_linear_epilogue", "grouped_fused_linear_epilogue", "attention", "attention_block", "mlp_chain", "transformer_layer"]
 
 
 def __getattr__(name):

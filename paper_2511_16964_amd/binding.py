@@ -355,6 +355,52 @@ def attention(q, k, v, causal, scale=None, out=None):
     return AttentionCall(q, k, v, causal, scale, out).run()
 
 
+class TransformerLayerCall:
+    """One pre-norm transformer layer as five fused calls bound to their tensors (no arithmetic here: every
+    step is a library call; the store op hands each residual sum over together with its LayerNorm):
+        qkv = n W_qkv^T + b_qkv;  o = attention(qkv, in place);
+        h, m = store / LayerNorm_mid of (o W_o^T + b_o + x);  u = gelu_erf(m W1^T + b1);
+        x', n' = store / LayerNorm_out of (u W2^T + b2 + h).
+    ``run()`` returns (x', n'), the residual stream and its normalised form for the next layer."""
+
+    def __init__(self, x, n, w_qkv, b_qkv, w_o, b_o, heads, causal, ln_mid, w1, b1, w2, b2, ln_out):
+        if x.dim() != 3 or n.shape != x.shape:
+            raise ValueError("x and n must be [B,T,C]")
+        if not x.is_cuda:
+            raise RuntimeError("transformer_layer runs on the GPU only; there is no CPU path")
+        B, T, C = x.shape
+        if C % heads:
+            raise ValueError("C must be a multiple of heads")
+        D, M, Fh = C // heads, B * T, w1.shape[0]
+        new = lambda *shape: torch.empty(shape, device=x.device, dtype=x.dtype)
+        x2, n2 = x.reshape(M, C), n.reshape(M, C)
+        self.qkv, self.o, self.h, self.m, self.u = new(M, 3 * C), new(M, C), new(M, C), new(M, C), new(M, Fh)
+        self.x_out, self.n_out = new(B, T, C), new(B, T, C)
+        q5 = self.qkv.view(B, T, 3, heads, D)
+        self.calls = [
+            Call(n2, w_qkv, b_qkv, [("bias",)] if b_qkv is not None else [], out=self.qkv),
+            AttentionCall(q5[:, :, 0], q5[:, :, 1], q5[:, :, 2], causal, out=self.o.view(B, T, heads, D)),
+            Call(self.o, w_o, b_o, ([("bias",)] if b_o is not None else []) + [("residual", x2), ("store", self.h), ("layernorm", ln_mid[0], ln_mid[1], ln_mid[2])], out=self.m),
+            Call(self.m, w1, b1, [("bias",), ("gelu_erf",)], out=self.u),
+            Call(self.u, w2, b2, [("bias",), ("residual", self.h), ("store", self.x_out.view(M, C)), ("layernorm", ln_out[0], ln_out[1], ln_out[2])], out=self.n_out.view(M, C)),
+        ]
+        self.out = self.x_out
+
+    def run(self, stream=None):
+        for c in self.calls:
+            c.run(stream)
+        return self.x_out, self.n_out
+
+    def plan(self) -> str:
+        return "transformer layer: five fused calls (qkv projection, attention, output projection + residual + store + LayerNorm, perceptron up + GELU, perceptron down + residual + store + LayerNorm)"
+
+
+def transformer_layer(x, n, w_qkv, b_qkv, w_o, b_o, heads, causal, ln_mid, w1, b1, w2, b2, ln_out):
+    """One pre-norm transformer layer from its normalised input on; see ``TransformerLayerCall``.
+    x, n [B,T,C]; ln_mid, ln_out = (gamma, beta, eps).  Returns (x', n')."""
+    return TransformerLayerCall(x, n, w_qkv, b_qkv, w_o, b_o, heads, causal, ln_mid, w1, b1, w2, b2, ln_out).run()
+
+
 class AttentionBlockCall:
     """A marshalled fle_attention_block (QKV projection, attention, output projection) bound to its tensors."""
 

@@ -320,6 +320,48 @@ def make_attention(name: str = "a1", seed: int = 0, B: int | None = None, T: int
                             x if residual else None)
 
 
+@dataclass
+class LayerProblem:
+    """One pre-norm transformer layer from its normalised input on: the attention block of ``attn`` applied
+    to n and added to x, LayerNorm (g_mid, be_mid), the perceptron block (w1, b1, GELU-erf, w2, b2) added to
+    that, LayerNorm (g_out, be_out) for the next layer."""
+    attn: AttentionProblem      # x = the residual stream [B,T,C]; its weights are the block's
+    n: torch.Tensor             # [B,T,C]: the normalised stream the previous layer hands over
+    g_mid: torch.Tensor
+    be_mid: torch.Tensor
+    w1: torch.Tensor            # [F,C]
+    b1: torch.Tensor
+    w2: torch.Tensor            # [C,F]
+    b2: torch.Tensor
+    g_out: torch.Tensor
+    be_out: torch.Tensor
+    eps: float = 1e-5
+
+    @property
+    def flops(self) -> float:
+        B, T, C = self.n.shape
+        return self.attn.flops + 4.0 * B * T * C * self.w1.shape[0]
+
+
+def make_layer(name: str = "a1", seed: int = 0, F: int | None = None, **kw) -> LayerProblem:
+    """The attention block of ``make_attention`` (same draws, so x and the block's weights are a1's) and then,
+    in this order: n ~ N(0,1) (what a LayerNorm of a random stream looks like; drawn, not computed: the
+    generator holds no arithmetic of the method), gamma ~ N(1, 0.02) and beta ~ N(0, 0.02) of the middle
+    LayerNorm, W1 ~ U(+-1/sqrt(C)), b1 likewise, W2 ~ U(+-1/sqrt(F)), b2 likewise, gamma and beta of the
+    last LayerNorm.  F defaults to 4 C."""
+    apb = make_attention(name, seed, **kw)
+    B, T, C = apb.x.shape
+    F = 4 * C if F is None else F
+    rng = np.random.default_rng(seed + 1000)
+    s = lambda a: _store(a, apb.dtype)
+    n = s(_normal(rng, (B, T, C)))
+    g_mid = s(_normal(rng, (C,), 1.0, 0.02)); be_mid = s(_normal(rng, (C,), 0.0, 0.02))
+    w1 = s(_uniform(rng, (F, C), 1 / math.sqrt(C))); b1 = s(_uniform(rng, (F,), 1 / math.sqrt(C)))
+    w2 = s(_uniform(rng, (C, F), 1 / math.sqrt(F))); b2 = s(_uniform(rng, (C,), 1 / math.sqrt(F)))
+    g_out = s(_normal(rng, (C,), 1.0, 0.02)); be_out = s(_normal(rng, (C,), 0.0, 0.02))
+    return LayerProblem(apb, n, g_mid, be_mid, w1, b1, w2, b2, g_out, be_out)
+
+
 def make_qkv(seed: int, B: int, T: int, H: int, D: int, dtype: torch.dtype, spread: float = 1.0):
     """q, k, v for the attention kernel alone: one [B, T, 3, H, D] tensor ~ N(0, spread) (the layout a
     fused QKV projection writes); q, k, v are its views [:, :, i]."""

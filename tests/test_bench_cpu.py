@@ -15,5 +15,5 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_traffic_table_names_every_workload():
     sys.path.insert(0, ROOT)
     import bench
-    assert set(bench.TRAFFIC_BYTES) == {"c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2"}
+    assert set(bench.TRAFFIC_BYTES) == {"c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"}
     assert bench.PEAK_BF16_TFLOPS == 2516.6 and bench.PEAK_HBM_GBS == 8000.0
