@@ -426,7 +426,9 @@ def test_every_variant_plans_every_kind_of_epilogue(L):
     """Planning is pure host arithmetic: every kernel variant must produce a complete plan (partials per
     row, staging, workspace) for every kind of epilogue, for each dtype it supports."""
     chains = [[], [op("bias")], [op("softmax")], [op("scale", 2.0), op("logsumexp")],
-              [op("bias"), op("residual", p0=6 * G, ld=2048), op("layernorm", 1e-5, 7 * G, 8 * G)]]
+              [op("bias"), op("residual", p0=6 * G, ld=2048), op("layernorm", 1e-5, 7 * G, 8 * G)],
+              [op("bias"), op("store", p0=10 * G, ld=2048), op("gelu_erf")],
+              [op("bias"), op("residual", p0=6 * G, ld=2048), op("store", p0=10 * G, ld=2048), op("layernorm", 1e-5, 7 * G, 8 * G)]]
     shapes = {"general": (70, 2048, 83), "tiled": (200, 2048, 128), "tiled256": (300, 2048, 256), "tiled128": (64, 2048, 64),
               "skinny": (32, 2048, 256), "skinny128": (40, 2048, 640), "skinny256": (32, 2048, 1024), "skinnyseq": (100, 2048, 512),
               "thin": (1, 2048, 1024), "auto": (1, 2048, 2048)}
@@ -447,7 +449,7 @@ def test_every_variant_plans_every_kind_of_epilogue(L):
                     L.fle_last_plan(buf, 256)
                     text = buf.value.decode()
                     np_ = int(re.search(r"np=(\d+)", text).group(1))
-                    has_row = any(o[0] >= 6 for o in ch)
+                    has_row = any(6 <= o[0] <= 8 for o in ch)
                     assert (np_ > 0) == has_row and (need.value >= rows * np_ * 8) and ("row_op=-1" in text) == (not has_row), text
 
 
