@@ -133,6 +133,24 @@ fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out);
 fle_status fle_run(const fle_problem *p);
 
 /*
+ * fle_run for callers that cannot allocate device memory or cannot bring a workspace: code inside a HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  p->workspace and
+ * p->workspace_bytes are ignored; the scratch that fle_run takes from the workspace (row-reduction
+ * partials, fp32 staging, split-K slabs) lives instead in a static device array of
+ * FLE_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing and never
+ * synchronises; its first call on a device looks the array's address up once
+ * (hipGetSymbolAddress), so make that first call outside a graph capture.
+ * A problem whose fle_workspace_size exceeds FLE_STATIC_SCRATCH_BYTES is refused with
+ * FLE_ERR_WORKSPACE and nothing is enqueued.  Results are bit-identical to fle_run's.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ * streams, different threads) race on it and must be serialised by the caller.  Nothing in the array has
+ * to start at zero, and a call leaves its contents undefined.
+ */
+#define FLE_STATIC_SCRATCH_BYTES (16u << 20)
+fle_status fle_run_static(const fle_problem *p);
+
+/*
  * Grouped form: the rows of x are cut into G consecutive groups and group g is multiplied by its
  * own weight matrix W_g (and gets its own bias b_g), all in one launch.  This is the layout of a
  * mixture-of-experts layer after the tokens have been sorted by expert; the paper's appendix on

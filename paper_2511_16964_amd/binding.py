@@ -17,8 +17,9 @@ F32, BF16, F16 = 0, 1, 2
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
             "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9}
 MAX_OPS = 8
+STATIC_SCRATCH_BYTES = 16 << 20
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
-EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_status_string", "fle_last_error",
+EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_run_static", "fle_status_string", "fle_last_error",
            "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
            "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped",
            "fle_attention_validate", "fle_attention_run", "fle_attention_block_validate",
@@ -95,7 +96,7 @@ def lib():
             raise FileNotFoundError(
                 LIB_PATH + " is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
         L = ctypes.CDLL(LIB_PATH)
-        for name in ("fle_validate", "fle_run"):
+        for name in ("fle_validate", "fle_run", "fle_run_static"):
             getattr(L, name).restype = ctypes.c_int
             getattr(L, name).argtypes = [ctypes.POINTER(FleProblem)]
         L.fle_workspace_size.restype = ctypes.c_int
@@ -269,6 +270,24 @@ class Call:
             finally:
                 L.fle_force_variant(0)
                 L.fle_force_split(0)
+        if status != 0:
+            _check(status)
+        return self.out
+
+    def run_static(self, stream=None):
+        """As ``run`` through ``fle_run_static``: the library's static scratch array stands in for the
+        workspace (plain problems up to FLE_STATIC_SCRATCH_BYTES of scratch; calls must not overlap on one GPU)."""
+        if self._groups is not None:
+            raise ValueError("fle_run_static takes plain problems only")
+        L = lib()
+        self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
+        L.fle_force_variant(self.variant)
+        L.fle_force_split(self.split)
+        try:
+            status = L.fle_run_static(self._pref)
+        finally:
+            L.fle_force_variant(0)
+            L.fle_force_split(0)
         if status != 0:
             _check(status)
         return self.out

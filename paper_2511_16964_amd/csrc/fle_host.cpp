@@ -580,6 +580,36 @@ fle_status fle_run(const fle_problem *p) {
     return s;
 }
 
+fle_status fle_run_static(const fle_problem *p) {
+    if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
+    fle_problem q = *p;
+    q.workspace = nullptr;  // the caller's workspace fields are ignored
+    q.workspace_bytes = 0;
+    Plan plan;
+    fle_status s = make_plan(&q, g_forced, g_split, &plan);
+    if (s != FLE_OK) return s;
+    if (q.M == 0) return FLE_OK;
+    if (plan.ws_total > size_t(FLE_STATIC_SCRATCH_BYTES))
+        return fail(FLE_ERR_WORKSPACE, "this problem needs %zu bytes of scratch, the static array holds %zu: use fle_run with a workspace", plan.ws_total,
+                    size_t(FLE_STATIC_SCRATCH_BYTES));
+    if (plan.ws_total > 0) {
+        void *ptr = nullptr;
+        s = static_scratch(&ptr);
+        if (s != FLE_OK) return s;
+        q.workspace = ptr;
+        q.workspace_bytes = size_t(FLE_STATIC_SCRATCH_BYTES);
+        s = make_plan(&q, g_forced, g_split, &plan);  // again with the scratch in place: no operand may reach into it
+        if (s == FLE_OK) s = check_workspace(&q, plan);
+        if (s != FLE_OK) return s;
+    }
+    s = launch(&q, plan);
+    if (s == FLE_OK) {
+        g_plan = plan;
+        g_have_plan = true;
+    }
+    return s;
+}
+
 static fle_status check_groups(const fle_groups *g) { return g ? FLE_OK : fail(FLE_ERR_NULL, "groups is NULL"); }
 
 fle_status fle_validate_grouped(const fle_problem *p, const fle_groups *g) {
@@ -724,6 +754,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 700; }  // 0.7.0: store op (0.6.0: perceptron chain; 0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
+int fle_version(void) { return 800; }  // 0.8.0: fle_run_static (0.7.0: store op; 0.6.0: perceptron chain; 0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
 
 }  // extern "C"

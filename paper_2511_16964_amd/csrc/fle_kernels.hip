@@ -24,7 +24,29 @@
 #include "fle_gemm_tiled.h"
 #include "fle_rowops.h"
 
+#include <atomic>
+
 namespace fle {
+
+// ------------------------------------------------------------------ static scratch (fle_run_static)
+// Device memory for callers that cannot allocate: part of the code object, one copy per GPU.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels and copies get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[FLE_STATIC_SCRATCH_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+fle_status static_scratch(void **ptr) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(FLE_ERR_HIP, "cannot query the current device");
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {  // once per device, with that device current (two threads racing here look up the same address)
+        const hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) return fail(FLE_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(err));
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return FLE_OK;
+}
 
 // ------------------------------------------------------------------ launcher
 static fle_status check_launch(const char *what) {

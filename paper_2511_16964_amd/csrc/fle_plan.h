@@ -64,6 +64,10 @@ fle_status fail(fle_status s, const char *fmt, ...);
 // Implemented in the kernel translation unit: enqueue the planned kernels.
 fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *groups = nullptr);
 
+// Implemented in the kernel translation unit: the address, on the current device, of the library's static
+// scratch array of FLE_STATIC_SCRATCH_BYTES (looked up once per device; no allocation).
+fle_status static_scratch(void **ptr);
+
 // Implemented in the kernel translation unit: enqueue the persistent perceptron kernel for an already validated
 // chain (sync: the barrier words; acts: one activation buffer per layer boundary, act_stride bytes apart; all in the workspace).
 fle_status launch_chain(const fle_chain *p, void *sync, void *acts, size_t act_stride);

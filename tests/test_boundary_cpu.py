@@ -574,3 +574,20 @@ def test_chain_validation_and_workspace(L):
     assert L.fle_chain_run(ctypes.byref(chain(ws=None))) == E_WS
     assert L.fle_chain_run(ctypes.byref(chain(ws_bytes=1000))) == E_WS
     assert L.fle_chain_run(ctypes.byref(chain(ws=7 * G + 64))) == E_ALIGN
+
+
+def test_run_static_refuses_on_the_host_what_it_cannot_take(L):
+    """fle_run_static decides everything except the launch on the host: an invalid problem and a problem whose
+    scratch exceeds the static array come back as errors before any HIP call."""
+    assert L.fle_run_static(None) == E_NULL
+    p = problem(ops=[op("softmax"), op("softmax")])
+    assert L.fle_run_static(ctypes.byref(p)) == E_UNSUP
+    out = 2 * G
+    p = problem(M=4096, N=8192, K=64, ops=[op("layernorm", 1e-5), op("residual", p0=G + out, ld=8192)])
+    p.workspace, p.workspace_bytes = 9 * G, 1 << 30     # ignored: the static array is what counts
+    need = ctypes.c_size_t(0)
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK and need.value > binding.STATIC_SCRATCH_BYTES
+    assert L.fle_run_static(ctypes.byref(p)) == E_WS
+    assert b"static array" in L.fle_last_error()
+    text = open(os.path.join(ROOT, "include", "fle.h")).read()
+    assert "#define FLE_STATIC_SCRATCH_BYTES (16u << 20)" in text and binding.STATIC_SCRATCH_BYTES == 16 << 20
