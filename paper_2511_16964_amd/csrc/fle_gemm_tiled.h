@@ -84,6 +84,16 @@ __device__ __forceinline__ float row16_allreduce(float v) {
     return v;
 }
 
+// acc += A B on v_mfma_f32_16x16x32_bf16 / _f16 with the accumulator tied to one place in the accumulation
+// registers.  (Through the compiler's builtin the 64 four-register accumulators of a 128 x 128 wave tile are
+// shuffled between register files on every trip of the K loop: the instruction's result need not overwrite its
+// addend, and the allocator uses that freedom.)  a, b: 16 bytes of one row each, 8 consecutive k.
+template <int DT>
+__device__ __forceinline__ void mfma_16x16x32(f32x4 &acc, const u32x4 &a, const u32x4 &b) {
+    if constexpr (DT == FLE_F16) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 // The output tile a workgroup computes: its origin, the first row past the rows it may touch (the
 // end of the matrix, or of the row group that owns the tile), and the W and bias of that owner.
 struct TileRef {
@@ -195,9 +205,15 @@ __device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs 
 // accesses; the epilogue then touches memory one element at a time, masked per column.
 // W_NT: the W panel is read by this workgroup only (grouped problems with about one tile row per group), so
 // its copies carry the non-temporal hint and do not displace other data from L2 and the Infinity Cache.
-template <int BM, int BN, int DT, bool EDGE, bool W_NT = false>
+// MF: shape of the MFMA tiles of the main loop, 32 (v_mfma_f32_32x32x16, k slices of 16, four per K step) or, for
+// the 2-byte dtypes, 16 (v_mfma_f32_16x16x32, k slices of 32, two per K step: twice as many issue slots between
+// matrix instructions for the same fragment reads and copies, and half the accumulator traffic per flop).
+// C1: (MF = 16) how many of a K step's copy instructions go out in the slice right behind the barrier; the
+// rest follow in the next slice.
+template <int BM, int BN, int DT, bool EDGE, bool W_NT = false, int MF = 32, int C1 = -1>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef &t) {
     constexpr bool F32 = DT == FLE_F32;
+    static_assert(MF == 32 || (MF == 16 && !F32), "the 16x16x32 loop exists for the 2-byte dtypes");
     constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
@@ -256,129 +272,116 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     ldw_.init(reinterpret_cast<const char *>(t.w) + n0 * a.ldw * ES, a.ldw * ES, N - n0, a.K * ES, wave, lane);
     constexpr int NIW = TileLoader<BN>::NI, NIX = TileLoader<BM>::NI;
 
-    // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
-    uint32_t rd_off[4];
-    {
-        const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
-    }
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
     // 16 bytes of one row: 4 fp32, 8 bf16 or 8 fp16 along K
     using frag_t = typename std::conditional<F32, f32x4, typename std::conditional<DT == FLE_F16, f16x8, bf16x8>::type>::type;
-    frag_t fw[2][TN], fx[2][TM];
     const int KT = int((a.K * ES + 127) / 128);
     const int tail_valid = int((a.K * ES - int64_t(KT - 1) * 128) / 16);  // 16-byte chunks of the last K step (8 = full)
-    // One 16-wide k slice KK of the stage at (sW, sX): NMF MFMAs on the fragments in buffer KK & 1.  In the
-    // issue slots between them go, one at a time, (READ) the fragment reads of the slice that is multiplied
-    // next, slice (KK + 1) & 3 of the stage at (rW, rX), into the other buffer, and (HALF = 1 or 2) the first
-    // or second half of the copy instructions of one K step into the stage at (iW, iX) (masked to the valid
-    // chunks when that is the partial last step).
-    auto slice = [&](auto kk_c, auto read_c, auto half_c, auto full_c, const char *sW, const char *sX, const char *rW, const char *rX,
-                     char *iW, char *iX, uint32_t ik0, int valid) {
-        constexpr int KK = decltype(kk_c)::value, HALF = decltype(half_c)::value;
-        constexpr bool FULL = decltype(full_c)::value;  // the copied step is known to be a whole one: no masking of chunks
-        constexpr bool READ = decltype(read_c)::value;
-        constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
-        constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
-        constexpr int cur = KK & 1;
-        (void)sW; (void)sX;
-#pragma unroll
-        for (int q = 0; q < NMF; ++q) {
-            if (READ && q % QD == 0) {
-                const int g = q / QD;
-                if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(rW + (wn * WN + g * 32) * 128 + rd_off[(KK + 1) & 3]);
-                else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(rX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(KK + 1) & 3]);
-            }
-            if (HALF != 0 && q % QV == (QV > 1 ? 1 : 0)) {
-                const int idx = (HALF - 1) * NVM + q / QV;
-                if constexpr (FULL) {
-                    if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
-                    else ldx_.issue_one(iX, ik0, idx - NIW);
-                } else {
-                    if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
-                    else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (F32) {
-                // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
-                // same K permutation for both operands
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
-            } else if constexpr (DT == FLE_F16) {
-                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
-            } else {
-                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
+    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y).
+    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
+    auto valid_of = [&](int step) { return step + 1 == KT ? tail_valid : 8; };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>;
     using I3 = std::integral_constant<int, 3>;
-
-    // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y).
-    //
-    // The loop is rotated by one slice against the K steps.  The wait for the next stage and the workgroup
-    // barrier sit between slices 2 and 3 of a step, not at its end: by then every fragment of the current
-    // stage is in registers (so the stage may be overwritten) and the copies of the next stage have had two
-    // slices to land.  Slice 3 then runs on registers alone and covers the first fragment reads of the next
-    // stage and the first half of the copies of the step after it; the other half goes out during slice 0.
-    // No MFMA ever waits right behind the barrier for an LDS read.
-    const int kb = int(int64_t(blockIdx.y) * KT / gridDim.y), ke = int(int64_t(blockIdx.y + 1) * KT / gridDim.y);
-    auto valid_of = [&](int step) { return step + 1 == KT ? tail_valid : 8; };
-    ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
-    ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    {
-        const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
+    constexpr int TM16 = WM / 16, TN16 = WN / 16;
+    f32x16 acc[MF == 32 ? TM : 1][MF == 32 ? TN : 1];
+    f32x4 acc16[MF == 16 ? TM16 : 1][MF == 16 ? TN16 : 1];
+    if constexpr (MF == 16) {
+        // ---- main loop on 16x16x32 tiles.  A K step is two k slices of 32; a fragment (16 rows x 32 k) is one
+        // 16-byte read per lane: row (lane & 15) and one of the four chunks of slice s.  The instruction takes the k
+        // values of lanes 16 h .. 16 h + 15 as one group of 8, and a sum over k does not care which group holds
+        // which chunk as long as both operands agree, so group h reads chunk kq(h) = 0, 2, 1, 3: the LDS serves a
+        // 16-byte read of lanes l and l + 32 in the same cycle, and with chunks two apart in those two lane
+        // groups the row swizzle sent them to the same banks (measured: 8.7e6 conflict cycles per 4096^3 call, the
+        // LDS twice as long busy; chunks one apart: none).
+        uint32_t rd_off[2];
+        {
+            const int r = lane & 15, g = (r & 7) ^ ((r >> 3) & 1);
+            const int h = lane >> 4, kq = ((h & 1) << 1) | (h >> 1);
 #pragma unroll
-        for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
+            for (int sl = 0; sl < 2; ++sl) rd_off[sl] = uint32_t(r * 128 + (((4 * sl + kq) ^ g) << 4));
+        }
 #pragma unroll
-        for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
-        if (kb + 1 < ke) {  // first half of the copies of the second step (later steps: during slice 3 of the step before)
-            char *iW = smem + ((kb + 1) & 1) * STAGE, *iX = iW + SW;
-            constexpr int NVM = (NIW + NIX) / 2;
+        for (int i = 0; i < TM16; ++i)
 #pragma unroll
-            for (int idx = 0; idx < NVM; ++idx) {
-                if (idx < NIW) ldw_.issue_one_tail(iW, uint32_t(kb + 1) * 128, idx, valid_of(kb + 1));
-                else ldx_.issue_one_tail(iX, uint32_t(kb + 1) * 128, idx - NIW, valid_of(kb + 1));
+            for (int j = 0; j < TN16; ++j) acc16[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        asm volatile("s_nop 7");
+        u32x4 fw[2][TN16], fx[2][TM16];
+        constexpr int NMF = TM16 * TN16, NDS = TM16 + TN16, QD = NMF / NDS;  // MFMAs per slice, fragment reads per slice, MFMAs per read
+        constexpr int NCP = NIW + NIX;                                        // copy instructions per K step
+        constexpr int NC1 = C1 < 0 ? (NCP * 7) / 8 : C1;                      // ... of which in the slice behind the barrier
+        static_assert(NC1 >= 0 && NC1 <= NCP && NC1 <= NMF && NCP - NC1 <= NMF, "copy placement");
+        // Slice SL of the stage being multiplied: NMF MFMAs on the fragments in buffer SL.  In the issue slots
+        // between them go, one at a time, (READ) the fragment reads of the slice that is multiplied next (slice rs
+        // of the stage at (rW, rX)) into the other buffer, and copy instructions FIRST .. FIRST + COUNT - 1 of one
+        // K step into the stage at (iW, iX), evenly spaced.
+        auto slice = [&](auto sl_c, auto read_c, auto first_c, auto count_c, auto full_c, const char *rW, const char *rX, int rs,
+                         char *iW, char *iX, uint32_t ik0, int valid) {
+            constexpr int SL = decltype(sl_c)::value, FIRST = decltype(first_c)::value, COUNT = decltype(count_c)::value;
+            constexpr bool READ = decltype(read_c)::value, FULL = decltype(full_c)::value;
+#pragma unroll
+            for (int q = 0; q < NMF; ++q) {
+                if (READ && q % QD == 0) {
+                    const int g = q / QD;
+                    if (g < TN16) fw[SL ^ 1][g] = *reinterpret_cast<const u32x4 *>(rW + (wn * WN + g * 16) * 128 + rd_off[rs]);
+                    else fx[SL ^ 1][g - TN16] = *reinterpret_cast<const u32x4 *>(rX + (wm * WM + (g - TN16) * 16) * 128 + rd_off[rs]);
+                }
+#pragma unroll
+                for (int c = 0; c < COUNT; ++c) {  // copy c of this slice goes out before MFMA (2 c + 1) NMF / (2 COUNT): evenly spread
+                    if (((2 * c + 1) * NMF) / (2 * (COUNT > 0 ? COUNT : 1)) != q) continue;
+                    const int idx = FIRST + c;
+                    if constexpr (FULL) {
+                        if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                        else ldx_.issue_one(iX, ik0, idx - NIW);
+                    } else {
+                        if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                        else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_16x16x32<DT>(acc16[q / TN16][q % TN16], fw[SL][q % TN16], fx[SL][q / TN16]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        };
+        using CNT1 = std::integral_constant<int, NC1>;
+        // The loop is rotated by one slice against the K steps: the wait for the next stage and the workgroup
+        // barrier sit between the two slices of a step.  By then every fragment of the current stage is in
+        // registers (its second slice was read during the first), so the stage may be overwritten; the second
+        // slice runs on registers alone and covers the first fragment reads of the next stage and the first NC1
+        // copies of the step after it, the other copies go out during the next step's first slice.
+        ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
+        ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        {
+            const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
+#pragma unroll
+            for (int g = 0; g < TN16; ++g) fw[0][g] = *reinterpret_cast<const u32x4 *>(sW + (wn * WN + g * 16) * 128 + rd_off[0]);
+#pragma unroll
+            for (int g = 0; g < TM16; ++g) fx[0][g] = *reinterpret_cast<const u32x4 *>(sX + (wm * WM + g * 16) * 128 + rd_off[0]);
+            if (kb + 1 < ke) {  // first copies of the second step (later steps: during the second slice of the step before)
+                char *iW = smem + ((kb + 1) & 1) * STAGE, *iX = iW + SW;
+#pragma unroll
+                for (int idx = 0; idx < NC1; ++idx) {
+                    if (idx < NIW) ldw_.issue_one_tail(iW, uint32_t(kb + 1) * 128, idx, valid_of(kb + 1));
+                    else ldx_.issue_one_tail(iX, uint32_t(kb + 1) * 128, idx - NIW, valid_of(kb + 1));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // One K step: MORE: a next step exists (second half of its copies in slice 0, wait and barrier before
-    // slice 3, its first fragments read in slice 3); MORE2: so does the one after it (first half of its copies
-    // in slice 3).  The flags are compile-time so that the loop body is one straight-line sequence.
-    auto k_step = [&](int kt, auto more_c, auto more2_c, auto full_c) {
-        constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
-        char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;        // the stage being multiplied
-        char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;  // the stage of the next step
-        slice(I0{}, std::true_type{}, std::integral_constant<int, MORE ? 2 : 0>{}, full_c, cW, cX, cW, cX, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
-        slice(I1{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
-        slice(I2{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
-        if constexpr (MORE) {
-            wait_vmcnt<0>();                          // this wave's copies of the next stage have landed ...
-            __builtin_amdgcn_s_waitcnt(0xC07F);       // ... and its last fragment reads of this stage have returned
-            __builtin_amdgcn_s_barrier();             // everyone's have: the next stage is complete, this one is free
-        }
-        slice(I3{}, std::integral_constant<bool, MORE>{}, std::integral_constant<int, MORE2 ? 1 : 0>{}, full_c, cW, cX, nW, nX, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
-    };
-    {
+        auto k_step = [&](int kt, auto more_c, auto more2_c, auto full_c) {
+            constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+            char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;        // the stage being multiplied
+            char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;  // the stage of the next step
+            slice(I0{}, std::true_type{}, CNT1{}, std::integral_constant<int, MORE ? NCP - NC1 : 0>{}, full_c, cW, cX, 1, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+            if constexpr (MORE) {
+                wait_vmcnt<0>();                          // this wave's copies of the next stage have landed ...
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // ... and its last fragment reads of this stage have returned
+                __builtin_amdgcn_s_barrier();             // everyone's have: the next stage is complete, this one is free
+            }
+            slice(I1{}, std::integral_constant<bool, MORE>{}, I0{}, std::integral_constant<int, MORE2 ? NC1 : 0>{}, full_c, nW, nX, 0, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
+        };
         int kt = kb;
-        // steps whose copies (for steps kt + 1 and kt + 2) cannot touch the last, possibly partial K step
         for (; kt + 3 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{}, std::true_type{});
         if (kt + 2 < ke) {
             k_step(kt, std::true_type{}, std::true_type{}, std::false_type{});
@@ -389,6 +392,135 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             ++kt;
         }
         k_step(kt, std::false_type{}, std::false_type{}, std::false_type{});
+        // (the matrix instructions above are opaque to the compiler's hazard recognizer: keep the wait states
+        // that an accumulator read behind the last of them needs)
+        asm volatile("s_nop 7");
+        asm volatile("s_nop 7");
+        asm volatile("s_nop 7");
+    } else {
+        // Fragment read offsets: lane reads row (lane & 31) of a 32-row block, logical chunk 2*kk + (lane >> 5).
+        uint32_t rd_off[4];
+        {
+            const int g = (lane & 7) ^ ((lane >> 3) & 1), hh = lane >> 5;
+    #pragma unroll
+            for (int kk = 0; kk < 4; ++kk) rd_off[kk] = uint32_t((lane & 31) * 128 + (((2 * kk + hh) ^ g) << 4));
+        }
+
+    #pragma unroll
+        for (int i = 0; i < TM; ++i)
+    #pragma unroll
+            for (int j = 0; j < TN; ++j)
+    #pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        frag_t fw[2][TN], fx[2][TM];
+        // One 16-wide k slice KK of the stage at (sW, sX): NMF MFMAs on the fragments in buffer KK & 1.  In the
+        // issue slots between them go, one at a time, (READ) the fragment reads of the slice that is multiplied
+        // next, slice (KK + 1) & 3 of the stage at (rW, rX), into the other buffer, and (HALF = 1 or 2) the first
+        // or second half of the copy instructions of one K step into the stage at (iW, iX) (masked to the valid
+        // chunks when that is the partial last step).
+        auto slice = [&](auto kk_c, auto read_c, auto half_c, auto full_c, const char *sW, const char *sX, const char *rW, const char *rX,
+                         char *iW, char *iX, uint32_t ik0, int valid) {
+            constexpr int KK = decltype(kk_c)::value, HALF = decltype(half_c)::value;
+            constexpr bool FULL = decltype(full_c)::value;  // the copied step is known to be a whole one: no masking of chunks
+            constexpr bool READ = decltype(read_c)::value;
+            constexpr int NMF = TM * TN, NDS = TM + TN, NVM = (NIW + NIX) / 2;
+            constexpr int QD = NMF / NDS, QV = NMF / NVM;  // MFMAs per fragment read / per copy instruction
+            constexpr int cur = KK & 1;
+            (void)sW; (void)sX;
+    #pragma unroll
+            for (int q = 0; q < NMF; ++q) {
+                if (READ && q % QD == 0) {
+                    const int g = q / QD;
+                    if (g < TN) fw[cur ^ 1][g] = *reinterpret_cast<const frag_t *>(rW + (wn * WN + g * 32) * 128 + rd_off[(KK + 1) & 3]);
+                    else fx[cur ^ 1][g - TN] = *reinterpret_cast<const frag_t *>(rX + (wm * WM + (g - TN) * 32) * 128 + rd_off[(KK + 1) & 3]);
+                }
+                if (HALF != 0 && q % QV == (QV > 1 ? 1 : 0)) {
+                    const int idx = (HALF - 1) * NVM + q / QV;
+                    if constexpr (FULL) {
+                        if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                        else ldx_.issue_one(iX, ik0, idx - NIW);
+                    } else {
+                        if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                        else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (F32) {
+                    // four 32x32x2 steps; step e pairs element e of the two 16-byte groups of every row, the
+                    // same K permutation for both operands
+    #pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[cur][q % TN][e], fx[cur][q / TN][e], acc[q / TN][q % TN], 0, 0, 0);
+                } else if constexpr (DT == FLE_F16) {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                } else {
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q % TN], fx[cur][q / TN], acc[q / TN][q % TN], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
+        // K steps kb .. ke-1 of this workgroup (all of them unless K is split over gridDim.y).
+        //
+        // The loop is rotated by one slice against the K steps.  The wait for the next stage and the workgroup
+        // barrier sit between slices 2 and 3 of a step, not at its end: by then every fragment of the current
+        // stage is in registers (so the stage may be overwritten) and the copies of the next stage have had two
+        // slices to land.  Slice 3 then runs on registers alone and covers the first fragment reads of the next
+        // stage and the first half of the copies of the step after it; the other half goes out during slice 0.
+        // No MFMA ever waits right behind the barrier for an LDS read.
+        ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
+        ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        {
+            const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
+    #pragma unroll
+            for (int t = 0; t < TN; ++t) fw[0][t] = *reinterpret_cast<const frag_t *>(sW + (wn * WN + t * 32) * 128 + rd_off[0]);
+    #pragma unroll
+            for (int t = 0; t < TM; ++t) fx[0][t] = *reinterpret_cast<const frag_t *>(sX + (wm * WM + t * 32) * 128 + rd_off[0]);
+            if (kb + 1 < ke) {  // first half of the copies of the second step (later steps: during slice 3 of the step before)
+                char *iW = smem + ((kb + 1) & 1) * STAGE, *iX = iW + SW;
+                constexpr int NVM = (NIW + NIX) / 2;
+    #pragma unroll
+                for (int idx = 0; idx < NVM; ++idx) {
+                    if (idx < NIW) ldw_.issue_one_tail(iW, uint32_t(kb + 1) * 128, idx, valid_of(kb + 1));
+                    else ldx_.issue_one_tail(iX, uint32_t(kb + 1) * 128, idx - NIW, valid_of(kb + 1));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // One K step: MORE: a next step exists (second half of its copies in slice 0, wait and barrier before
+        // slice 3, its first fragments read in slice 3); MORE2: so does the one after it (first half of its copies
+        // in slice 3).  The flags are compile-time so that the loop body is one straight-line sequence.
+        auto k_step = [&](int kt, auto more_c, auto more2_c, auto full_c) {
+            constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+            char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;        // the stage being multiplied
+            char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;  // the stage of the next step
+            slice(I0{}, std::true_type{}, std::integral_constant<int, MORE ? 2 : 0>{}, full_c, cW, cX, cW, cX, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+            slice(I1{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
+            slice(I2{}, std::true_type{}, I0{}, full_c, cW, cX, cW, cX, nW, nX, 0u, 8);
+            if constexpr (MORE) {
+                wait_vmcnt<0>();                          // this wave's copies of the next stage have landed ...
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // ... and its last fragment reads of this stage have returned
+                __builtin_amdgcn_s_barrier();             // everyone's have: the next stage is complete, this one is free
+            }
+            slice(I3{}, std::integral_constant<bool, MORE>{}, std::integral_constant<int, MORE2 ? 1 : 0>{}, full_c, cW, cX, nW, nX, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
+        };
+        {
+            int kt = kb;
+            // steps whose copies (for steps kt + 1 and kt + 2) cannot touch the last, possibly partial K step
+            for (; kt + 3 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{}, std::true_type{});
+            if (kt + 2 < ke) {
+                k_step(kt, std::true_type{}, std::true_type{}, std::false_type{});
+                ++kt;
+            }
+            if (kt + 1 < ke) {
+                k_step(kt, std::true_type{}, std::false_type{}, std::false_type{});
+                ++kt;
+            }
+            k_step(kt, std::false_type{}, std::false_type{}, std::false_type{});
+        }
     }
     __syncthreads();  // the stage area becomes epilogue scratch
     if (!wave_live) return;
@@ -434,17 +566,25 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             wait_vmcnt<0>();  // residual block i is in LDS (and this wave's earlier stores are done)
             if (i + 1 < TM && m_blk + 32 < M) issue_residual(i + 1, (i + 1) & 1);
         }
-        // accumulators of row block i -> LDS, row (lane & 31), columns 32 j + 8 q + 4 h .. + 3
+        // accumulators of row block i -> LDS.  32x32 tiles: row (lane & 31), columns 32 j + 8 q + 4 h .. + 3;
+        // 16x16 tiles (two tile rows per block): row 16 t + (lane & 15), columns 16 j + 4 (lane >> 4) .. + 3
         {
-            char *wr = ep + (lane & 31) * EP_STRIDE + (lane >> 5) * 16;
+            char *wr = MF == 16 ? ep + (lane & 15) * EP_STRIDE + (lane >> 4) * 16 : ep + (lane & 31) * EP_STRIDE + (lane >> 5) * 16;
             auto put = [&](auto ic) {
                 constexpr int I = decltype(ic)::value;
                 if constexpr (I < TM) {
+                    if constexpr (MF == 16) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
+                        for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
-                            *reinterpret_cast<f32x4 *>(wr + (32 * j + 8 * q) * 4) = f32x4{acc[I][j][4 * q], acc[I][j][4 * q + 1], acc[I][j][4 * q + 2], acc[I][j][4 * q + 3]};
+                            for (int j = 0; j < TN16; ++j) *reinterpret_cast<f32x4 *>(wr + tt * 16 * EP_STRIDE + 16 * j * 4) = acc16[2 * I + tt][j];
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                *reinterpret_cast<f32x4 *>(wr + (32 * j + 8 * q) * 4) = f32x4{acc[I][j][4 * q], acc[I][j][4 * q + 1], acc[I][j][4 * q + 2], acc[I][j][4 * q + 3]};
+                    }
                 }
             };
             switch (i) {
@@ -649,24 +789,24 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 // 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).  DT: fle_dtype of the operands.
 // fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
-template <int DT, bool EDGE>
-__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE>(a, whole_matrix_tile<256>(a)); }
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 ? 32 : 16), int C1 = -1>
+__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<256>(a)); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-template <int DT, bool EDGE>
-__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE>(a, whole_matrix_tile<128>(a)); }
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 ? 32 : 16), int C1 = -1>
+__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<128>(a)); }
 
 // Grouped forms: the same tiles, with the tile -> rows mapping taken from the group offsets.
 template <int DT, bool EDGE>
 __global__ __launch_bounds__(256) void gemm_tiled_grouped_256(const GemmArgs a, const GroupArgs ga) {
     TileRef t;
     if (!grouped_tile<256>(a, ga, t)) return;
-    gemm_tiled_body<256, 256, DT, EDGE>(a, t);
+    gemm_tiled_body<256, 256, DT, EDGE, false, (DT == FLE_F32 ? 32 : 16)>(a, t);
 }
 template <int DT, bool EDGE, bool W_NT>
 __global__ __launch_bounds__(256, 2) void gemm_tiled_grouped_128(const GemmArgs a, const GroupArgs ga) {
     TileRef t;
     if (!grouped_tile<128>(a, ga, t)) return;
-    gemm_tiled_body<128, 128, DT, EDGE, W_NT>(a, t);
+    gemm_tiled_body<128, 128, DT, EDGE, W_NT, (DT == FLE_F32 ? 32 : 16)>(a, t);
 }
 
 }  // namespace fle

@@ -90,10 +90,21 @@ def test_streaming_finalize_keeps_its_occupancy(asm):
 
 def test_main_loop_uses_the_intended_instructions(asm):
     body = asm
-    assert "v_mfma_f32_32x32x16_bf16" in body and "v_mfma_f32_32x32x16_f16" in body
     assert re.search(r"buffer_load_dwordx4 .* lds", body)          # direct-to-LDS copies
     assert "v_mfma_f32_16x16x4_f32" in asm                         # fp32 path stays on fp32 MFMA
-    m = re.search(r"^_ZN3fle14gemm_tiled_256ILi0ELb0EEEvNS_8GemmArgsE:(.*?)s_endpgm", asm, flags=re.S | re.M)   # fp32 operands
-    assert m and "v_mfma_f32_32x32x2_f32" in m.group(1) and "_bf16" not in m.group(1) and "x16_f16" not in m.group(1)
+    m = re.search(r"^_ZN3fle14gemm_tiled_256ILi0ELb0ELi32ELin1EEEvNS_8GemmArgsE:(.*?)s_endpgm", asm, flags=re.S | re.M)   # fp32 operands
+    assert m and "v_mfma_f32_32x32x2_f32" in m.group(1) and "_bf16" not in m.group(1) and "x16_f16" not in m.group(1) and "x32_f16" not in m.group(1)
+    # 2-byte operands: the tiled loop runs on the 16x16x32 shape, whose accumulators stay where they are (no
+    # accumulator moves between register files inside the K loop) and nothing spills
+    for dt, mn in ((1, "v_mfma_f32_16x16x32_bf16"), (2, "v_mfma_f32_16x16x32_f16")):
+        for kern in ("gemm_tiled_256", "gemm_tiled_128"):
+            m = re.search(r"^_ZN3fle14%sILi%dELb0ELi16ELin1EEEvNS_8GemmArgsE:(.*?)s_endpgm" % (kern, dt), asm, flags=re.S | re.M)
+            assert m, (kern, dt)
+            text = m.group(1)
+            first, last = text.index(mn), text.rindex(mn)
+            assert text.count(mn) >= 128 and "32x32x16" not in text
+            # (the only accumulator moves allowed between the matrix instructions are the one-time zero fill,
+            # which the compiler places between its copies of the K step)
+            assert text[first:last].count("v_accvgpr") <= 256 and "v_accvgpr_read" not in text[first:last] and "scratch_" not in text
     assert "v_mfma_f32_16x16x16_bf16" in asm and "v_mfma_f32_16x16x16_f16" in asm   # general kernel on 2-byte operands
     assert "v_pk_fma_f32" not in asm and "v_pk_mul_f32" not in asm and "v_pk_add_f32" not in asm
