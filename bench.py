@@ -23,10 +23,67 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/CU/clk
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-# Bytes per launch of the dominant kernel at the L2 <-> fabric boundary, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs scaled by a plain copy of known size (profiles/traffic_pmc_c2_c3_c4.md).  None = not
-# measured for the kernel as it stands.
-TRAFFIC_BYTES = {"c2": 235.3e6 + 33.6e6, "c3": 403.3e6 + 69.2e6, "c4": 541.2e6 + 2.4e6, "c1": None, "c5": None, "g1": None, "g2": None, "m1": None, "m2": None, "m3": None, "a1": None, "a2": None, "l1": None}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+KERNEL_SOURCES = os.path.join(ROOT, "paper_2511_16964_amd", "csrc")
+
+
+def kernel_source_hash():
+    """One hash over the library's sources: the counters in profiles/traffic.json only describe the kernels
+    they were taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCES)):
+        if name.endswith((".h", ".hip", ".cpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(KERNEL_SOURCES, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload):
+    """Bytes per step at the L2 <-> fabric boundary (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by what
+    the same counter reads for a plain copy of known size), from the file that `--summarize-traffic` wrote; None
+    when there is no measurement for this workload or the kernels have changed since it was taken."""
+    try:
+        d = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None
+    e = d.get("workloads", {}).get(workload)
+    if not e or d.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return e["read_bytes"] + e["write_bytes"]
+
+
+def summarize_traffic(dirs):
+    """Reads the counter_collection CSVs that the two rocprofv3 --pmc runs of `bench.py --workload W --calibrate-copy`
+    left under each given directory (named traffic_<workload>), and writes profiles/traffic.json.  Per dispatch the
+    counters are in KiB; the plain-copy dispatches of the same run (512 MiB read and written each) give the scale."""
+    import csv
+    import glob
+    out = {"kernel_source_hash": kernel_source_hash(), "unit": "bytes per step (all kernels of one call)", "workloads": {}}
+    for d in dirs:
+        wl = os.path.basename(os.path.normpath(d)).split("_")[-1]
+        per = {}
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            rows = []
+            for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+                rows += [r for r in csv.DictReader(open(f)) if r["Counter_Name"] == counter]
+            copies = [float(r["Counter_Value"]) for r in rows if "copyBuffer" in r["Kernel_Name"] and r["Grid_Size"] == "131072"]
+            if not rows or not copies:
+                sys.exit("summarize-traffic: no %s rows with calibration copies under %s" % (counter, d))
+            scale = (512 << 20) / (sorted(copies)[len(copies) // 2] * 1024.0)
+            kernels = {}
+            for r in rows:
+                if "fle::" in r["Kernel_Name"]:
+                    kernels.setdefault(r["Kernel_Name"].split("(")[0], []).append(float(r["Counter_Value"]))
+            per[counter] = {"scale": scale, "kernels": {k: sorted(v)[len(v) // 2] * 1024.0 * scale for k, v in kernels.items()}}
+        out["workloads"][wl] = {
+            "read_bytes": sum(per["FETCH_SIZE"]["kernels"].values()), "write_bytes": sum(per["WRITE_SIZE"]["kernels"].values()),
+            "fetch_scale": per["FETCH_SIZE"]["scale"], "write_scale": per["WRITE_SIZE"]["scale"],
+            "per_kernel_read_bytes": per["FETCH_SIZE"]["kernels"], "per_kernel_write_bytes": per["WRITE_SIZE"]["kernels"]}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+        f.write("\n")
+    print(json.dumps(out["workloads"], indent=1))
 
 
 def eager_fn(torch, F, x, w, b, ep):
@@ -112,9 +169,13 @@ class ClockSampler:
         return out
 
 
-def time_cold(torch, fn, iters, flush):
-    """Mean per-call event time with L2 and the Infinity Cache evicted before every call."""
+def time_cold(torch, fn, iters, flush, warmups=0):
+    """Mean per-call event time with L2 and the Infinity Cache evicted before every call: every iteration has
+    its own event pair and ends with a synchronisation (the paper times a call that way, Section 4.6)."""
     ts = []
+    for _ in range(warmups):
+        fn()
+    torch.cuda.synchronize()
     for _ in range(iters):
         flush.zero_()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -262,7 +323,12 @@ def main():
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, to scale FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--summarize-traffic", nargs="+", metavar="DIR",
+                    help="no benchmark: read the FETCH_SIZE / WRITE_SIZE counter CSVs under the given traffic_<workload> directories and write profiles/traffic.json")
     args = ap.parse_args()
+    if args.summarize_traffic:
+        summarize_traffic(args.summarize_traffic)
+        return
     if args.gpus != 1:
         sys.exit("bench.py: the library runs on ONE GPU (no collectives, no sharding): use --gpus 1")
 
@@ -444,6 +510,8 @@ def main():
         b, heads, first = 1, [0, H - 1], T - 24
         sub = inputs.to_f64(qkv_cpu[b:b + 1][:, :, :, heads])
         ref = oracle.attention(sub[:, :, 0], sub[:, :, 1], sub[:, :, 2], causal, first_query=first)
+        # probabilities rounded to bf16 for the second product, the row sum unrounded: 2 * 2^-9 of sum_j p_j |v_j|
+        extra = 2.0 ** -8 * oracle.attention(sub[:, :, 0], sub[:, :, 1], np.abs(sub[:, :, 2]), causal, first_query=first)
         got = calls[0].out[b:b + 1, first:][:, :, heads].cpu().to(torch.float64).numpy()
     elif args.workload == "l1":
         # the first tokens of the first sequence (causal mask: they depend on nothing after them); x' and n' side by side
@@ -476,7 +544,7 @@ def main():
     if args.workload == "l1":
         tol *= 6.0 ** 0.5   # qkv, o, h, m, u and the result: six storage roundings in sequence
     s = min(1.0, float(np.sqrt(np.mean(ref * ref))))
-    if not np.all(np.abs(got - ref) <= tol * (s + np.abs(ref))):
+    if not np.all(np.abs(got - ref) <= tol * (s + np.abs(ref)) + (extra if args.workload == "a2" else 0.0)):
         sys.exit("bench.py: GPU result fails parity against the oracle; no timing reported")
 
     # ---- timing
@@ -484,7 +552,11 @@ def main():
         wall_ms, ev_ms = time_loop(torch, step, args.steps, args.warmup)
         repeats = [ev_ms] + [time_loop(torch, step, args.steps, 0)[1] for _ in range(2)]  # spread only; `value` uses the first
     flush = torch.empty(768 << 20, dtype=torch.uint8, device=dev)
-    cold_mean, cold_med, cold_min = time_cold(torch, step, 50, flush)
+    # The protocol the paper's evaluator uses (Section 4.6 and the appendix on MLP task noise): warm-ups, then many
+    # iterations, each timed on its own with a synchronisation inside the timed region; here with the caches
+    # evicted before every call, three times over for the spread.
+    pp = [time_cold(torch, step, 100, flush, warmups=10) for _ in range(3)]
+    cold_mean, cold_med, cold_min = pp[0]
     tflops = flops / (wall_ms * 1e-3) / 1e12
     out = {
         "metric": {"a1": "fused attention block TFLOP/s", "a2": "attention TFLOP/s", "l1": "transformer layer TFLOP/s"}.get(args.workload, "fused GEMM+epilogue TFLOP/s"), "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
@@ -496,17 +568,19 @@ def main():
         "event_ms_per_step": ev_ms,
         "event_ms_per_step_repeats": repeats,
         "clocks_during_timed_loops": clocks.summary(),
-        "cold_cache_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
-                          "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
+        "per_call_protocol_ms": {"mean": cold_mean, "median": cold_med, "min": cold_min,
+                                 "means_of_3_repeats": [p_[0] for p_ in pp], "warmups": 10, "iterations": 100,
+                                 "how": "one event pair and one synchronisation per call, L2 and Infinity Cache evicted (768 MB overwritten) before each",
+                                 "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
     hbm_bound = args.workload in ("c4", "g2", "m1", "m2", "m3")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES[args.workload]}
+        out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": measured_traffic(args.workload)}
     else:
         peak = PEAK_BF16_TFLOPS if prob0.dtype == torch.bfloat16 else PEAK_F32_TFLOPS
         a = flops / (ev_ms * 1e-3) / 1e12
-        out["roofline"] = {"bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak, "traffic": TRAFFIC_BYTES[args.workload]}
+        out["roofline"] = {"bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak, "traffic": measured_traffic(args.workload)}
     out["roofline"]["kernel"] = "all kernels of one step (event time over the timed region / steps)"
     out["algorithmic_bytes"] = alg_bytes
 

@@ -274,8 +274,9 @@ fle_status fle_attention_block_run(const fle_attention_block *p);
  * separates the layers by a grid-wide barrier and requests the next layer's first weights before the
  * barrier.  Intermediate activations are rounded to the storage dtype, as separate calls would.
  * The barrier's waits are bounded: should the workgroups ever not be resident together (another
- * kernel holding CUs that never finishes), the call ends with a wrong result and a non-zero error
- * word (see workspace) instead of hanging.
+ * kernel holding CUs that never finishes), the call ends instead of hanging: the error word (see
+ * workspace) becomes non-zero and every workgroup that gave up fills its share of out with NaN, so
+ * such a call cannot be mistaken for a result.
  */
 typedef struct {
     const void *w;  /* DEVICE [n, k] row-major and packed (row stride k), 16-byte aligned            */
@@ -297,8 +298,10 @@ typedef struct {
                                       bytes of barrier state, then one activation buffer per layer boundary.
                                       The barrier state must be ZERO before the first call; every
                                       call leaves it zero, except the 32-bit error word at byte 256,
-                                      which becomes 1 if a barrier wait ran out.  Calls that share a
-                                      workspace must not overlap in time                             */
+                                      which becomes 1 if a barrier wait ran out.  While that word is
+                                      non-zero every call on this workspace gives up at its first wait
+                                      (out becomes NaN): zero all 2560 bytes again before the next
+                                      call.  Calls that share a workspace must not overlap in time   */
     size_t workspace_bytes;
     void *stream;
     int32_t w_dtype;               /* dtype of every W: equal to dtype, or FLE_BF16 / FLE_F16 under

@@ -176,6 +176,10 @@ class Call:
         N = w.shape[-2]
         dt = x.dtype
         tensors = [x, w, b]
+        if b is not None and not grouped and (b.dim() != 1 or b.shape[0] != N or (N > 1 and b.stride(0) != 1)):
+            raise ValueError("b must be a contiguous vector of N = %d elements" % N)
+        if b is not None and grouped and b.dim() == 1 and (b.shape[0] != N or (N > 1 and b.stride(0) != 1)):
+            raise ValueError("a shared b must be a contiguous vector of N = %d elements" % N)
         self._groups = None
         if grouped:
             G = w.shape[0]
@@ -214,6 +218,9 @@ class Call:
                 ops[i].ld = t.stride(0) if M > 1 else max(N, t.stride(0))
             elif e[0] == "layernorm":
                 g, be, eps = e[1], e[2], e[3]
+                for name, t in (("gamma", g), ("beta", be)):
+                    if t is not None and (t.dim() != 1 or t.shape[0] != N or (N > 1 and t.stride(0) != 1)):
+                        raise ValueError("layernorm %s must be a contiguous vector of N = %d elements" % (name, N))
                 tensors += [g, be]
                 ops[i].p0 = None if g is None else g.data_ptr()
                 ops[i].p1 = None if be is None else be.data_ptr()
@@ -224,6 +231,14 @@ class Call:
         lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
         if out is None:
             out = torch.empty((M,) if lse else (M, N), dtype=dt, device=x.device)
+        else:   # the kernels write through a raw pointer and a row stride: everything they assume is checked here
+            if out.dtype != dt or out.device != x.device:
+                raise TypeError("out must have x's dtype and device")
+            if lse:
+                if tuple(out.shape) != (M,) or (M > 1 and out.stride(0) != 1):
+                    raise ValueError("out must be a contiguous vector of M = %d elements (the list ends in logsumexp)" % M)
+            elif tuple(out.shape) != (M, N) or (N > 1 and out.stride(1) != 1) or (M > 1 and out.stride(0) < N):
+                raise ValueError("out must be [M,N] = [%d,%d] with unit column stride and a row stride of at least N" % (M, N))
         self.out = out
         p = FleProblem()
         p.M, p.N, p.K, p.dtype = M, N, K, _dtype_code(dt)
@@ -234,7 +249,7 @@ class Call:
         p.ldo = 0 if lse else (out.stride(0) if M > 1 else max(N, out.stride(0)))
         p.ops, p.n_ops = ops, len(epilogue)
         self._p, self._ops, self._tensors = p, ops, tensors
-        self._dev = x.device.index if x.device.index is not None else torch.cuda.current_device()
+        self._dev = x.device.index   # (None: resolved when the call is enqueued)
         L = lib()
         L.fle_force_variant(self.variant)
         L.fle_force_split(self.split)
@@ -258,6 +273,8 @@ class Call:
     def run(self, stream=None):
         """Enqueue on ``stream`` (default: torch's current stream) and return ``out`` without synchronising."""
         L = lib()
+        if self._dev is None:
+            self._dev = torch.cuda.current_device()
         # the HIP stream handle: torch's current stream on the operands' device unless one is given
         self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
         if self.variant == 0 and self.split == 0:
@@ -280,6 +297,8 @@ class Call:
         if self._groups is not None:
             raise ValueError("fle_run_static takes plain problems only")
         L = lib()
+        if self._dev is None:
+            self._dev = torch.cuda.current_device()
         self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
         L.fle_force_variant(self.variant)
         L.fle_force_split(self.split)
@@ -529,6 +548,17 @@ class ChainCall:
         """True if a barrier wait ran out in some call since the workspace was zeroed (synchronises)."""
         return bool(self.workspace[256:260].view(torch.int32).item())
 
+    def run_checked(self, stream=None):
+        """``run``, then wait for the result and raise if a barrier wait was given up (the workgroups were not all
+        resident: out holds NaN in the shares of those that gave up).  The barrier state is zeroed again so that
+        the workspace can be reused."""
+        out = self.run(stream)
+        torch.cuda.synchronize(self._dev)
+        if self.barrier_error():
+            self.workspace[:2560].zero_()
+            raise RuntimeError("mlp_chain: a grid barrier wait was given up; the result is not valid")
+        return out
+
     def plan(self) -> str:
         return "mlp_chain: %d layers in one launch" % self._p.n_layers
 
@@ -541,3 +571,8 @@ def mlp_chain(x, weights, biases, activations, out=None, workspace=None):
     weights may be bfloat16 or float16 (biases, activations and the result stay float32).
     """
     return ChainCall(x, weights, biases, activations, out, workspace).run()
+
+
+def mlp_chain_checked(x, weights, biases, activations, out=None, workspace=None):
+    """As ``mlp_chain``, synchronising and raising if a grid barrier wait was given up."""
+    return ChainCall(x, weights, biases, activations, out, workspace).run_checked()

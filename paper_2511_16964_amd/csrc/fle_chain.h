@@ -33,14 +33,17 @@ struct ChainArgs {
 // launches is what bounds a 64 MB layer.
 //
 // The barrier: thread 0 of a workgroup counts itself in; the last arrival resets the counts and publishes the
-// new generation, the others wait for it.  Nothing here flushes or invalidates a cache: the
-// activations are the only data that cross it, and they are stored and loaded with device-scope coherence
-// (write-through stores, loads that do not trust the XCD's L2), so relaxed device-scope atomics after the
-// workgroup's own barrier are enough; a version with release / acquire fences (an L2 write-back and
-// invalidation per workgroup and barrier) cost 30 us per layer.  Every wait is bounded: a workgroup that gives
-// up raises the error word, which ends all later waits at once, so the kernel always terminates (with a wrong
-// result that the host can detect) even if the workgroups were not all resident.  The last workgroup to finish
-// the kernel puts the state back to zero.
+// new generation, the others wait for it.  Nothing here flushes or invalidates a cache.  The activations are the
+// only data that cross the barrier.  They are stored with device scope (written through to memory), and every
+// storing wave waits for its own stores to be acknowledged (vmcnt(0)) before its workgroup arrives, so the order
+// store -> arrive is explicit; relaxed device-scope atomics are then enough (a version with release / acquire
+// fences, an L2 write-back and invalidation per workgroup and barrier, cost 30 us per layer).  They are loaded
+// with ordinary cached loads: every layer writes a buffer of its own that no workgroup has read earlier in the
+// launch, so no XCD's L2 can hold an older copy of a line; across launches the same holds because a kernel
+// starts with clean (invalidated) L2s.  Every wait is bounded: a workgroup that gives up raises the error word,
+// which ends all later waits at once, fills its share of the output with NaN and leaves, so the kernel always
+// terminates, and a call whose workgroups were not all resident cannot be mistaken for a result.  The last
+// workgroup to finish the kernel puts the counters and generations back to zero (the error word stays).
 constexpr uint32_t kChainSpinLimit = 1u << 21;
 
 // st: 32-bit words, one 128-byte line each: line 0 = arrivals of the group leaders, line 1 = finished workgroups,
@@ -51,8 +54,10 @@ constexpr uint32_t kChainSpinLimit = 1u << 21;
 constexpr int kChainGroups = 8;
 __device__ __forceinline__ uint32_t *chain_word(uint32_t *st, int line) { return st + line * 32; }
 
-__device__ __forceinline__ void chain_barrier(uint32_t *st, uint32_t n_wg, uint32_t target_gen) {
-    __syncthreads();  // every wave's activation stores of this layer have been acknowledged
+// Returns false (to every thread of the workgroup) if the wait was given up.
+__device__ __forceinline__ bool chain_barrier(uint32_t *st, uint32_t n_wg, uint32_t target_gen) {
+    int gave_up = 0;
+    __syncthreads();  // every wave of the workgroup has waited for its activation stores (see the caller)
     if (threadIdx.x == 0) {
         const int g = int(blockIdx.x) % kChainGroups;
         const uint32_t n_groups = n_wg < uint32_t(kChainGroups) ? n_wg : uint32_t(kChainGroups);
@@ -74,13 +79,14 @@ __device__ __forceinline__ void chain_barrier(uint32_t *st, uint32_t n_wg, uint3
             while (__hip_atomic_load(chain_word(st, 12 + g), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target_gen) {
                 if (++spins > kChainSpinLimit || __hip_atomic_load(chain_word(st, 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
                     __hip_atomic_store(chain_word(st, 2), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    gave_up = 1;
                     break;
                 }
                 __builtin_amdgcn_s_sleep(1);
             }
         }
     }
-    __syncthreads();
+    return __syncthreads_or(gave_up) == 0;
 }
 
 // One element of an activation vector, stored with device scope (written through, visible to every XCD).
@@ -191,6 +197,9 @@ __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
             }
         }
         if (l + 1 < a.n_layers) {
+            // this wave's activation stores have reached memory before its workgroup arrives at the barrier
+            // (and before the loads below, which stay in flight across it, join the same counter)
+            wait_vmcnt<0>();
             // request the first two weight batches of the next layer's first row before waiting for the other workgroups
             const ChainLayer &Ln = a.layer[l + 1];
             const int row = int(blockIdx.x) * 16 + wave;
@@ -200,15 +209,24 @@ __global__ __launch_bounds__(1024) void mlp_chain(const ChainArgs a) {
                 load_w(b1, rn, uint32_t(Ln.k) * ES, 1);
                 have_w0 = true;
             }
-            chain_barrier(a.sync, gridDim.x, uint32_t(l + 1));  // layer l is complete and visible everywhere
+            if (!chain_barrier(a.sync, gridDim.x, uint32_t(l + 1))) {  // layer l is complete and visible everywhere, or:
+                // the wait was given up: this workgroup's share of the result becomes NaN and it computes no further
+                const ChainLayer &Le = a.layer[a.n_layers - 1];
+                if (lane == 0)
+                    for (int row = int(blockIdx.x) * 16 + wave; row < Le.n; row += int(gridDim.x) * 16) st_elem(a.out, row, DT, __builtin_nanf(""));
+                break;
+            }
         }
     }
-    // the last workgroup to get here leaves the barrier state as it found it (the error word stays if raised)
+    // the last workgroup to get here puts the barrier state back to zero (the error word stays if raised)
     if (threadIdx.x == 0 && a.n_layers > 1) {
         if (__hip_atomic_fetch_add(chain_word(a.sync, 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1) {
             __hip_atomic_store(chain_word(a.sync, 1), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            for (int q = 0; q < kChainGroups; ++q)
+            __hip_atomic_store(chain_word(a.sync, 0), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int q = 0; q < kChainGroups; ++q) {
+                __hip_atomic_store(chain_word(a.sync, 4 + q), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(chain_word(a.sync, 12 + q), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }

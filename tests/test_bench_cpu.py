@@ -12,8 +12,36 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
 
 
-def test_traffic_table_names_every_workload():
+def test_traffic_comes_from_a_measurement_of_the_current_kernels(tmp_path, monkeypatch):
+    """roofline.traffic is read from the file the profile step writes, and only while the kernels are the ones
+    the counters were taken from."""
     sys.path.insert(0, ROOT)
+    import json
     import bench
-    assert set(bench.TRAFFIC_BYTES) == {"c1", "c2", "c3", "c4", "c5", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"}
     assert bench.PEAK_BF16_TFLOPS == 2516.6 and bench.PEAK_HBM_GBS == 8000.0
+    f = tmp_path / "traffic.json"
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(f))
+    assert bench.measured_traffic("c2") is None                       # no file
+    f.write_text(json.dumps({"kernel_source_hash": bench.kernel_source_hash(), "workloads": {"c2": {"read_bytes": 3.0, "write_bytes": 4.0}}}))
+    assert bench.measured_traffic("c2") == 7.0 and bench.measured_traffic("c3") is None
+    f.write_text(json.dumps({"kernel_source_hash": "stale", "workloads": {"c2": {"read_bytes": 3.0, "write_bytes": 4.0}}}))
+    assert bench.measured_traffic("c2") is None                       # the kernels have changed since
+
+
+def test_summarize_traffic_scales_by_the_calibration_copy(tmp_path, monkeypatch):
+    sys.path.insert(0, ROOT)
+    import json
+    import bench
+    d = tmp_path / "traffic_c2"
+    d.mkdir()
+    head = "Kernel_Name,Grid_Size,Counter_Name,Counter_Value\n"
+    rows = ""
+    for counter, copy_kib, kern_kib in (("FETCH_SIZE", 262144.0, 1000.0), ("WRITE_SIZE", 524288.0, 500.0)):
+        rows += '"__amd_rocclr_copyBuffer",131072,%s,%f\n' % (counter, copy_kib)
+        rows += '"void fle::gemm_tiled_256<1, false>(fle::GemmArgs)",65536,%s,%f\n' % (counter, kern_kib)
+    (d / "x_counter_collection.csv").write_text(head + rows)
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "traffic.json"))
+    bench.summarize_traffic([str(d)])
+    w = json.load(open(tmp_path / "traffic.json"))["workloads"]["c2"]
+    assert abs(w["fetch_scale"] - 2.0) < 1e-9 and abs(w["write_scale"] - 1.0) < 1e-9
+    assert abs(w["read_bytes"] - 1000 * 1024 * 2.0) < 1e-3 and abs(w["write_bytes"] - 500 * 1024) < 1e-3

@@ -591,3 +591,35 @@ def test_run_static_refuses_on_the_host_what_it_cannot_take(L):
     assert b"static array" in L.fle_last_error()
     text = open(os.path.join(ROOT, "include", "fle.h")).read()
     assert "#define FLE_STATIC_SCRATCH_BYTES (16u << 20)" in text and binding.STATIC_SCRATCH_BYTES == 16 << 20
+
+
+def test_binding_checks_every_tensor_a_kernel_would_touch(L):
+    """The kernels get raw pointers and strides: the binding refuses, before the call, an out / b / gamma / beta
+    whose shape, dtype, device or stride is not what the kernels assume (host tensors suffice: nothing runs)."""
+    import torch
+    M, N, K = 8, 16, 32
+    bf = torch.bfloat16
+    x, w, b = torch.zeros(M, K, dtype=bf), torch.zeros(N, K, dtype=bf), torch.zeros(N, dtype=bf)
+    g = torch.ones(N, dtype=bf)
+    ok = binding.Call(x, w, b, [("bias",), ("layernorm", g, g, 1e-5)], out=torch.zeros(M, N, dtype=bf))
+    assert ok.out.shape == (M, N)
+    view = torch.zeros(M, 2 * N, dtype=bf)[:, :N]                     # a row stride larger than N is fine
+    assert binding.Call(x, w, b, [("bias",)], out=view).out is view
+    bad_outs = [torch.zeros(M, N - 1, dtype=bf), torch.zeros(M - 1, N, dtype=bf), torch.zeros(M, N, dtype=torch.float32),
+                torch.zeros(N, M, dtype=bf).t(), torch.zeros(M * N, dtype=bf)]
+    for out in bad_outs:
+        with pytest.raises((ValueError, TypeError)):
+            binding.Call(x, w, b, [("bias",)], out=out)
+    with pytest.raises(ValueError):
+        binding.Call(x, w, None, [("logsumexp",)], out=torch.zeros(M, 1, dtype=bf))
+    assert binding.Call(x, w, None, [("logsumexp",)], out=torch.zeros(M, dtype=bf)).out.shape == (M,)
+    for bad_b in (torch.zeros(N - 1, dtype=bf), torch.zeros(2 * N, dtype=bf)[::2], torch.zeros(1, N, dtype=bf)):
+        with pytest.raises(ValueError):
+            binding.Call(x, w, bad_b, [("bias",)])
+    for bad in (torch.ones(N + 1, dtype=bf), torch.ones(2 * N, dtype=bf)[::2]):
+        with pytest.raises(ValueError):
+            binding.Call(x, w, b, [("layernorm", bad, g, 1e-5)])
+        with pytest.raises(ValueError):
+            binding.Call(x, w, b, [("layernorm", g, bad, 1e-5)])
+    with pytest.raises(TypeError):
+        binding.Call(x, w, b, [("layernorm", g.float(), g, 1e-5)])

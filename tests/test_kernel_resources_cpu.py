@@ -71,12 +71,13 @@ def test_attention_kernels_keep_two_waves_per_simd(asm):
 
 def test_chain_kernel_leaves_room_for_all_workgroups(asm):
     """The persistent perceptron kernel waits at a grid barrier, so every workgroup must be resident: 16 waves of
-    at most 128 registers and no LDS let a CU hold two of them while the launch asks for one per CU."""
+    at most 128 registers and next to no LDS let a CU hold two of them while the launch asks for one per CU."""
     props = kernel_props(asm)
     chain = {k: v for k, v in props.items() if "mlp_chain" in k}
     assert len(chain) == 5, sorted(chain)   # three dtypes, and bf16 / fp16 weights under fp32 activations
     for name, p in chain.items():
-        assert p["scratch"] == 0 and p["vgpr"] <= 128 and p["lds"] == 0, (name, p)
+        # (the only LDS is the few words through which a workgroup agrees on whether its barrier wait was given up)
+        assert p["scratch"] == 0 and p["vgpr"] <= 128 and p["lds"] <= 1024, (name, p)
     assert "buffer_wbl2" not in asm and "buffer_inv" not in asm   # no kernel flushes or invalidates a cache
 
 

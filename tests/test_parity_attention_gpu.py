@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2511_16964_amd import binding, inputs
 
-from parity import BLOCK_FACTOR, assert_close, value_scale
+from parity import BLOCK_FACTOR, assert_close, attention_reference
 
 pytestmark = pytest.mark.gpu
 
@@ -28,9 +28,11 @@ def run_attention(qkv, causal, scale=None):
     return out.cpu()
 
 
-def oracle_attention(qkv, causal, scale=None, first_query=0):
+def check_attention(got, qkv, causal, dtype, what="", scale=None):
+    """got against the oracle on the packed [B,T,3,H,D] operands, under the attention kernel's criterion."""
     f = inputs.to_f64(qkv)
-    return oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, scale, first_query=first_query)
+    ref, extra = attention_reference(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, dtype, scale)
+    assert_close(got, ref, dtype, what, extra=extra)
 
 
 @pytest.mark.parametrize("dtype", [BF16, F16])
@@ -41,7 +43,7 @@ def test_attention_small(dtype, D, causal, T):
     """One to three workgroups per head along the queries, ragged key blocks, several heads and batches."""
     announce("attention small", dtype, D, causal, T)
     qkv = inputs.make_qkv(100 + T, 2, T, 3, D, dtype)
-    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, "T=%d" % T, s=value_scale(qkv[:, :, 2]))
+    check_attention(run_attention(qkv, causal), qkv, causal, dtype, "T=%d" % T)
 
 
 @pytest.mark.parametrize("dtype,D,causal,B,H,T", [
@@ -58,7 +60,7 @@ def test_attention_small(dtype, D, causal, T):
 def test_attention_many_heads(dtype, D, causal, B, H, T):
     announce("attention wide", dtype, D, causal, B, H, T)
     qkv = inputs.make_qkv(7, B, T, H, D, dtype)
-    assert_close(run_attention(qkv, causal), oracle_attention(qkv, causal), dtype, s=value_scale(qkv[:, :, 2]))
+    check_attention(run_attention(qkv, causal), qkv, causal, dtype)
 
 
 @pytest.mark.parametrize("dtype,D,T,G", [
@@ -69,7 +71,7 @@ def test_attention_group_causal(dtype, D, T, G):
     """Causal over groups of G tokens: group edges inside, at and across the 64-key blocks and 128-query blocks."""
     announce("attention group causal", dtype, D, T, G)
     qkv = inputs.make_qkv(300 + G, 2, T, 3, D, dtype)
-    assert_close(run_attention(qkv, G), oracle_attention(qkv, G), dtype, "G=%d" % G, s=value_scale(qkv[:, :, 2]))
+    check_attention(run_attention(qkv, G), qkv, G, dtype, "G=%d" % G)
 
 
 @pytest.mark.parametrize("dtype,D,T,Tk,causal", [
@@ -89,8 +91,8 @@ def test_attention_with_different_query_and_key_counts(dtype, D, T, Tk, causal):
     got = binding.attention(d(q), d(kv)[:, :, 1], d(kv)[:, :, 2], causal)
     torch.cuda.synchronize()
     f = inputs.to_f64
-    ref = oracle.attention(f(q), f(kv[:, :, 1]), f(kv[:, :, 2]), causal)
-    assert_close(got.cpu(), ref, dtype, s=value_scale(kv[:, :, 2]))
+    ref, extra = attention_reference(f(q), f(kv[:, :, 1]), f(kv[:, :, 2]), causal, dtype)
+    assert_close(got.cpu(), ref, dtype, extra=extra)
 
 
 def test_attention_on_sequence_first_tensors():
@@ -104,7 +106,7 @@ def test_attention_on_sequence_first_tensors():
     out_tb = torch.zeros(T, B, H, D, device=DEV, dtype=BF16)
     binding.attention(q, k, v, True, out=out_tb.transpose(0, 1))
     torch.cuda.synchronize()
-    assert_close(out_tb.transpose(0, 1).cpu(), oracle_attention(qkv, True), BF16, s=value_scale(qkv[:, :, 2]))
+    check_attention(out_tb.transpose(0, 1).cpu(), qkv, True, BF16)
 
 
 @pytest.mark.parametrize("causal", [0, 1, 1000])
@@ -117,12 +119,12 @@ def test_attention_long_sequence_sampled_queries(causal):
     got = run_attention(qkv, causal)
     assert torch.isfinite(got.float()).all()
     f = inputs.to_f64(qkv)
-    tail = oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, first_query=T - 6)
-    assert_close(got[:, T - 6:], tail, BF16, "last queries", s=value_scale(qkv[:, :, 2]))
+    tail, extra = attention_reference(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, BF16, first_query=T - 6)
+    assert_close(got[:, T - 6:], tail, BF16, "last queries", extra=extra)
     if causal:   # the first queries only see the first keys: a short problem of its own
         n = 2100 if causal == 1 else 2000     # with groups of 1000 tokens, queries 0 .. 1999 see exactly keys 0 .. 1999
-        head = oracle.attention(f[:, :n, 0], f[:, :n, 1], f[:, :n, 2], causal)
-        assert_close(got[:, :n], head, BF16, "first queries", s=value_scale(qkv[:, :, 2]))
+        head, extra = attention_reference(f[:, :n, 0], f[:, :n, 1], f[:, :n, 2], causal, BF16)
+        assert_close(got[:, :n], head, BF16, "first queries", extra=extra)
 
 
 def test_attention_peaked_and_flat_scores():
@@ -133,7 +135,7 @@ def test_attention_peaked_and_flat_scores():
         qkv = inputs.make_qkv(11, 2, 190, 2, 64, BF16, spread)
         got = run_attention(qkv, True, scale)
         assert torch.isfinite(got.float()).all()
-        assert_close(got, oracle_attention(qkv, True, scale), BF16, s=value_scale(qkv[:, :, 2]))
+        check_attention(got, qkv, True, BF16, scale=scale)
 
 
 def test_attention_separate_tensors_and_out():
@@ -145,7 +147,7 @@ def test_attention_separate_tensors_and_out():
     buf = torch.zeros(B, T, 2, H, D, device=DEV, dtype=BF16)
     binding.attention(q, k, v, False, out=buf[:, :, 1])
     torch.cuda.synchronize()
-    assert_close(buf[:, :, 1].cpu(), oracle_attention(qkv, False), BF16, s=value_scale(qkv[:, :, 2]))
+    check_attention(buf[:, :, 1].cpu(), qkv, False, BF16)
     assert (buf[:, :, 0] == 0).all()
 
 

@@ -7,7 +7,7 @@ import torch
 
 from paper_2511_16964_amd import binding, inputs
 
-from parity import BLOCK_FACTOR, assert_close, value_scale, oracle_grouped, oracle_rows, run_grouped_gpu
+from parity import BLOCK_FACTOR, assert_close, attention_reference, oracle_grouped, oracle_rows, run_grouped_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -146,7 +146,8 @@ def test_random_attention_matches_oracle(seed):
     got = binding.attention(q, k, v, causal, scale)
     torch.cuda.synchronize()
     f = inputs.to_f64(qkv)
-    assert_close(got.cpu(), oracle.attention(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, scale), dtype, "seed %d" % seed, s=value_scale(qkv[:, :, 2]))
+    ref, extra = attention_reference(f[:, :, 0], f[:, :, 1], f[:, :, 2], causal, dtype, scale)
+    assert_close(got.cpu(), ref, dtype, "seed %d" % seed, extra=extra)
 
 
 @pytest.mark.parametrize("seed", range(12))
