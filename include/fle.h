@@ -16,9 +16,9 @@
  * Conventions
  *   - All tensors are row-major.  W is [N,K] (the nn.Linear weight layout).
  *   - One dtype per problem for x, W, b, residual, gamma, beta and out:
- *     FLE_F32, FLE_BF16 or FLE_F16.  Products are accumulated in fp32, the whole
- *     epilogue runs in fp32, and the result is rounded once
- *     (round-to-nearest-even) to the output dtype.
+ *     FLE_F32, FLE_BF16 or FLE_F16 (FLE_F8E4M3: x and W in fp8, the rest in bf16).
+ *     Products are accumulated in fp32, the whole epilogue runs in fp32, and the
+ *     result is rounded once (round-to-nearest-even) to the output dtype.
  *   - Pointers inside fle_problem and fle_op are DEVICE pointers unless
  *     stated otherwise; the structs themselves and the ops array live on the
  *     HOST and are only read during the call.
@@ -52,7 +52,20 @@ typedef enum {
     FLE_ERR_HIP = 7          /* the HIP runtime refused a launch                         */
 } fle_status;
 
-typedef enum { FLE_F32 = 0, FLE_BF16 = 1, FLE_F16 = 2 } fle_dtype;
+typedef enum {
+    FLE_F32 = 0,
+    FLE_BF16 = 1,
+    FLE_F16 = 2,
+    FLE_F8E4M3 = 3 /* x and W in OCP 8-bit floating point (e4m3: 4 exponent bits, 3 mantissa bits, no infinities, the
+                      torch.float8_e4m3fn encoding); b, residual and store operands, gamma, beta and out in bf16.
+                      Products of the stored values are accumulated in fp32 exactly as for the wider dtypes, on
+                      the fp8 matrix instructions (twice the bf16 rate, half the bytes per operand element): the
+                      precision reduction that the paper's analysis names as its most effective single pattern
+                      (Section 5.3) and that its tolerance admits (Appendix A).  Per-tensor scale factors of x
+                      and W are applied by listing FLE_SCALE with their product as the first op.  fp8 problems
+                      run on the tiled kernels only: x and W 16-byte aligned, K and the row strides multiples of
+                      16 elements; otherwise FLE_ERR_UNSUPPORTED.                                             */
+} fle_dtype;
 
 typedef enum {
     FLE_BIAS = 0,      /* v += b[n]                                  (needs problem.b)     */
@@ -328,7 +341,11 @@ const char *fle_last_error(void);
  * dot-product thin kernel ("thin_*_dot") C is the number of W rows per wave instead. */
 fle_status fle_last_plan(char *buf, size_t n);
 
-/* Force a kernel variant for the calling thread's next calls, for tests and tuning:
+/* The two calls below are knobs for tests and tuning, not part of the operator: they keep a setting per
+ * calling thread (the only mutable state of the library besides the error text and the last plan) that
+ * stays in force until it is set back to 0, so a product call path should never touch them.
+ *
+ * Force a kernel variant for the calling thread's next calls:
  * 0 = automatic, 1 = general kernel, 2 = tiled MFMA kernel (automatic tile), 3 = skinny kernel
  * (bf16 / fp16, M <= 256) with a K step of 64, 4 = tiled with the 256x256 tile, 5 = tiled with
  * the 128x128 tile, 6 / 7 = skinny kernel with a K step of 128 / 256, 8 = skinny kernel with one
@@ -338,8 +355,8 @@ fle_status fle_last_plan(char *buf, size_t n);
  * problems accept 0, 2, 4 and 5. */
 void fle_force_variant(int variant);
 
-/* Force the split of K for the calling thread's next calls on the tiled and skinny kernels, for
- * tests and tuning: 0 = automatic, 1 = no split, S > 1 = S workgroups per output tile, each
+/* Force the split of K for the calling thread's next calls on the tiled and skinny kernels (a test
+ * and tuning knob like fle_force_variant): 0 = automatic, 1 = no split, S > 1 = S workgroups per output tile, each
  * over its own K range, summed in a fixed order by a reduction pass (capped at the number of
  * K steps and at 64).  A split needs S * M * N * 4 more workspace bytes; fle_workspace_size
  * reports them. */

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfle.so")
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
             "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9}
 MAX_OPS = 8
@@ -146,7 +146,9 @@ def _dtype_code(dt: torch.dtype) -> int:
         return BF16
     if dt == torch.float16:
         return F16
-    raise TypeError("fused_linear_epilogue supports float32, bfloat16 and float16, got %s" % dt)
+    if dt == torch.float8_e4m3fn:
+        return F8E4M3
+    raise TypeError("fused_linear_epilogue supports float32, bfloat16, float16 and float8_e4m3fn (x and W only), got %s" % dt)
 
 
 def _ptr(t):
@@ -175,6 +177,9 @@ class Call:
         M, K = x.shape
         N = w.shape[-2]
         dt = x.dtype
+        io = torch.bfloat16 if dt == torch.float8_e4m3fn else dt   # dtype of everything but x and W
+        if w.dtype != dt:
+            raise TypeError("x and w must share one dtype")
         tensors = [x, w, b]
         if b is not None and not grouped and (b.dim() != 1 or b.shape[0] != N or (N > 1 and b.stride(0) != 1)):
             raise ValueError("b must be a contiguous vector of N = %d elements" % N)
@@ -225,15 +230,15 @@ class Call:
                 ops[i].p0 = None if g is None else g.data_ptr()
                 ops[i].p1 = None if be is None else be.data_ptr()
                 ops[i].alpha = float(eps)
-        for t in tensors:
-            if t is not None and t.dtype != torch.int64 and (t.dtype != dt or t.device != x.device):
-                raise TypeError("all operands must share x's dtype and device")
+        for i, t in enumerate(tensors):
+            if t is not None and t.dtype != torch.int64 and (t.dtype != (dt if i < 2 else io) or t.device != x.device):
+                raise TypeError("all operands must be on x's device; b, residual and store operands, gamma and beta must have x's dtype (bfloat16 for fp8 problems)")
         lse = bool(epilogue) and epilogue[-1][0] == "logsumexp"
         if out is None:
-            out = torch.empty((M,) if lse else (M, N), dtype=dt, device=x.device)
+            out = torch.empty((M,) if lse else (M, N), dtype=io, device=x.device)
         else:   # the kernels write through a raw pointer and a row stride: everything they assume is checked here
-            if out.dtype != dt or out.device != x.device:
-                raise TypeError("out must have x's dtype and device")
+            if out.dtype != io or out.device != x.device:
+                raise TypeError("out must have x's dtype (bfloat16 for fp8 problems) and device")
             if lse:
                 if tuple(out.shape) != (M,) or (M > 1 and out.stride(0) != 1):
                     raise ValueError("out must be a contiguous vector of M = %d elements (the list ends in logsumexp)" % M)

@@ -212,9 +212,10 @@ __device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs 
 // rest follow in the next slice.
 template <int BM, int BN, int DT, bool EDGE, bool W_NT = false, int MF = 32, int C1 = -1>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef &t) {
-    constexpr bool F32 = DT == FLE_F32;
-    static_assert(MF == 32 || (MF == 16 && !F32), "the 16x16x32 loop exists for the 2-byte dtypes");
-    constexpr int ES = F32 ? 4 : 2;  // bytes per operand element; a staged row is 128 bytes = 64 bf16 or 32 fp32
+    constexpr bool F32 = DT == FLE_F32, F8 = DT == FLE_F8E4M3;
+    static_assert(MF == 32 || (MF == 16 && !F32 && !F8), "16x16 tiles exist for the 2-byte dtypes");
+    constexpr int DTE = F8 ? FLE_BF16 : DT;     // dtype of b, the residual and store operands and out (fp8 problems: bf16)
+    constexpr int ES = F32 ? 4 : F8 ? 1 : 2;    // bytes per operand element; a staged row is 128 bytes = 128 fp8, 64 bf16 or 32 fp32
     constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
     constexpr int SW = BN * 128, SX = BM * 128, STAGE = SW + SX;  // bytes per stage
     constexpr int NH = WN / 64;                                    // 64-column runs per wave tile
@@ -286,7 +287,124 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     constexpr int TM16 = WM / 16, TN16 = WN / 16;
     f32x16 acc[MF == 32 ? TM : 1][MF == 32 ? TN : 1];
     f32x4 acc16[MF == 16 ? TM16 : 1][MF == 16 ? TN16 : 1];
-    if constexpr (MF == 16) {
+    if constexpr (F8) {
+        // ---- main loop on 32x32x64 tiles (fp8 operands).  A K step (128 bytes of every row) is two k slices of 64;
+        // a fragment (32 rows x 64 k) is 32 bytes per lane, read as two 16-byte pieces: row (lane & 31), chunks
+        // 4 s + hh and 4 s + 2 + hh of slice s, hh = lane >> 5 (the instruction takes the 32 bytes of a lane as 32
+        // consecutive k values of its half of the slice; which chunks those are is free as long as both operands
+        // agree, and with this choice lanes l and l + 32, which the LDS serves in the same cycle, read chunks one
+        // apart: no bank conflicts under the row swizzle).  16 matrix instructions of 64 cycles per slice move the
+        // same bytes through LDS as the 2-byte loop's 64 of 16 cycles, for twice the products.  The schedule is
+        // that loop's: fragments one slice ahead, wait and barrier between the two slices of a step, the copies
+        // of the step after next right behind the barrier.
+        // (The 16x16x128 shape needs its fragments a whole K step ahead, 192 registers of them next to 256
+        // accumulators: it spilled.)
+        uint32_t rd_off[2][2];  // [slice][piece]
+        {
+            const int r = lane & 31, g = (r & 7) ^ ((r >> 3) & 1), hh = lane >> 5;
+#pragma unroll
+            for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) rd_off[sl][e] = uint32_t(r * 128 + (((4 * sl + 2 * e + hh) ^ g) << 4));
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        typedef __attribute__((ext_vector_type(8))) int i32x8;
+        struct Frag { u32x4 lo, hi; };
+        Frag fw[2][TN], fx[2][TM];
+        constexpr int NMF = TM * TN, NRD = 2 * (TM + TN);  // MFMAs per slice, 16-byte reads per slice
+        constexpr int NCP = NIW + NIX;
+        constexpr int NC1 = C1 < 0 ? (NCP * 3) / 4 : C1;
+        auto slice = [&](auto sl_c, auto read_c, auto first_c, auto count_c, auto full_c, const char *rW, const char *rX, int rs,
+                         char *iW, char *iX, uint32_t ik0, int valid) {
+            constexpr int SL = decltype(sl_c)::value, FIRST = decltype(first_c)::value, COUNT = decltype(count_c)::value;
+            constexpr bool READ = decltype(read_c)::value, FULL = decltype(full_c)::value;
+#pragma unroll
+            for (int q = 0; q < NMF; ++q) {
+#pragma unroll
+                for (int r = 0; r < NRD; ++r) {  // read r (piece e of fragment g of the next slice) goes out before MFMA r NMF / NRD
+                    if (!READ || (r * NMF) / NRD != q) continue;
+                    const int g = r / 2, e = r % 2;
+                    const u32x4 v = g < TN ? *reinterpret_cast<const u32x4 *>(rW + (wn * WN + (g % TN) * 32) * 128 + rd_off[rs][e])
+                                           : *reinterpret_cast<const u32x4 *>(rX + (wm * WM + ((g - TN) % TM) * 32) * 128 + rd_off[rs][e]);
+                    Frag &f = g < TN ? fw[SL ^ 1][g % TN] : fx[SL ^ 1][(g - TN) % TM];
+                    if (e == 0) f.lo = v; else f.hi = v;
+                }
+#pragma unroll
+                for (int c = 0; c < COUNT; ++c) {  // copy c goes out before MFMA c (as many per slot as it takes when there are fewer slots):
+                    if ((c < NMF ? c : c % NMF) != q) continue;  // a matrix instruction lasts as long as the texture path needs for one copy of each wave
+                    const int idx = FIRST + c;
+                    if constexpr (FULL) {
+                        if (idx < NIW) ldw_.issue_one(iW, ik0, idx);
+                        else ldx_.issue_one(iX, ik0, idx - NIW);
+                    } else {
+                        if (idx < NIW) ldw_.issue_one_tail(iW, ik0, idx, valid);
+                        else ldx_.issue_one_tail(iX, ik0, idx - NIW, valid);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const Frag &fa = fw[SL][q % TN], &fb = fx[SL][q / TN];
+                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    __builtin_bit_cast(i32x8, __builtin_shufflevector(fa.lo, fa.hi, 0, 1, 2, 3, 4, 5, 6, 7)),
+                    __builtin_bit_cast(i32x8, __builtin_shufflevector(fb.lo, fb.hi, 0, 1, 2, 3, 4, 5, 6, 7)), acc[q / TN][q % TN], 0, 0, 0, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using CNT1 = std::integral_constant<int, NC1>;
+        ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
+        ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        {
+            const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
+#pragma unroll
+            for (int g = 0; g < TN; ++g) {
+                fw[0][g].lo = *reinterpret_cast<const u32x4 *>(sW + (wn * WN + g * 32) * 128 + rd_off[0][0]);
+                fw[0][g].hi = *reinterpret_cast<const u32x4 *>(sW + (wn * WN + g * 32) * 128 + rd_off[0][1]);
+            }
+#pragma unroll
+            for (int g = 0; g < TM; ++g) {
+                fx[0][g].lo = *reinterpret_cast<const u32x4 *>(sX + (wm * WM + g * 32) * 128 + rd_off[0][0]);
+                fx[0][g].hi = *reinterpret_cast<const u32x4 *>(sX + (wm * WM + g * 32) * 128 + rd_off[0][1]);
+            }
+            if (kb + 1 < ke) {
+                char *iW = smem + ((kb + 1) & 1) * STAGE, *iX = iW + SW;
+#pragma unroll
+                for (int idx = 0; idx < NC1; ++idx) {
+                    if (idx < NIW) ldw_.issue_one_tail(iW, uint32_t(kb + 1) * 128, idx, valid_of(kb + 1));
+                    else ldx_.issue_one_tail(iX, uint32_t(kb + 1) * 128, idx - NIW, valid_of(kb + 1));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        auto k_step = [&](int kt, auto more_c, auto more2_c, auto full_c) {
+            constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+            char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;
+            char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;
+            slice(I0{}, std::true_type{}, CNT1{}, std::integral_constant<int, MORE ? NCP - NC1 : 0>{}, full_c, cW, cX, 1, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+            if constexpr (MORE) {
+                wait_vmcnt<0>();
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+            }
+            slice(I1{}, std::integral_constant<bool, MORE>{}, I0{}, std::integral_constant<int, MORE2 ? NC1 : 0>{}, full_c, nW, nX, 0, cW, cX, uint32_t(kt + 2) * 128, valid_of(kt + 2));
+        };
+        int kt = kb;
+        for (; kt + 3 < ke; ++kt) k_step(kt, std::true_type{}, std::true_type{}, std::true_type{});
+        if (kt + 2 < ke) {
+            k_step(kt, std::true_type{}, std::true_type{}, std::false_type{});
+            ++kt;
+        }
+        if (kt + 1 < ke) {
+            k_step(kt, std::true_type{}, std::false_type{}, std::false_type{});
+            ++kt;
+        }
+        k_step(kt, std::false_type{}, std::false_type{}, std::false_type{});
+    } else if constexpr (MF == 16) {
         // ---- main loop on 16x16x32 tiles.  A K step is two k slices of 32; a fragment (16 rows x 32 k) is one
         // 16-byte read per lane: row (lane & 15) and one of the four chunks of slice s.  The instruction takes the k
         // values of lanes 16 h .. 16 h + 15 as one group of 8, and a sum over k does not care which group holds
@@ -550,9 +668,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             if constexpr (EDGE) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(t.bias, n_col[hc] + e, DT);
+                    if (n_col[hc] + e < N) bias_v[hc][e] = ld_elem(t.bias, n_col[hc] + e, DTE);
             } else {
-                bias_v[hc] = ld4<DT>(t.bias, n_ok[hc] ? n_col[hc] : N - 4);
+                bias_v[hc] = ld4<DTE>(t.bias, n_ok[hc] ? n_col[hc] : N - 4);
             }
         }
     }
@@ -649,7 +767,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 #pragma unroll
                     for (int it = 0; it < NIT; ++it)
 #pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<DT>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8, 0);
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<DTE>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8, 0);
                 } else {  // a further residual operand: straight from memory, clamped to stay in bounds
 #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
@@ -660,9 +778,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                             if constexpr (EDGE) {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DT);
+                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DTE);
                             } else {
-                                v[it][hc] += ld4<DT>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                                v[it][hc] += ld4<DTE>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
                             }
                         }
                     }
@@ -678,11 +796,11 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                             if constexpr (EDGE) {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) st_elem(const_cast<void *>(op.p0), m * op.ld + n_col[hc] + e, DT, v[it][hc][e]);
+                                    if (n_col[hc] + e < N) st_elem(const_cast<void *>(op.p0), m * op.ld + n_col[hc] + e, DTE, v[it][hc][e]);
                             } else if constexpr (F32) {
                                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = v[it][hc];
                             } else {
-                                constexpr int DT2 = F32 ? FLE_BF16 : DT;
+                                constexpr int DT2 = F32 ? FLE_BF16 : DTE;
                                 *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = pack4<DT2>(v[it][hc]);
                             }
                         }
@@ -772,14 +890,14 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                         if constexpr (EDGE) {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DT, v[it][hc][e]);
+                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DTE, v[it][hc][e]);
                         } else if (F32 || a.dst_f32) {
                             f32x4 *q = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]);
                             if (stream_out) __builtin_nontemporal_store(v[it][hc], q);
                             else *q = v[it][hc];
                         } else {
                             u32x2 *q = reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n_col[hc]);
-                            constexpr int DT2 = F32 ? FLE_BF16 : DT;  // (this branch is never taken for fp32 problems)
+                            constexpr int DT2 = F32 ? FLE_BF16 : DTE;  // (this branch is never taken for fp32 problems)
                             if (stream_out) __builtin_nontemporal_store(pack4<DT2>(v[it][hc]), q);
                             else *q = pack4<DT2>(v[it][hc]);
                         }
@@ -792,10 +910,10 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 // 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).  DT: fle_dtype of the operands.
 // fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
-template <int DT, bool EDGE, int MF = (DT == FLE_F32 ? 32 : 16), int C1 = -1>
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1>
 __global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<256>(a)); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-template <int DT, bool EDGE, int MF = (DT == FLE_F32 ? 32 : 16), int C1 = -1>
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1>
 __global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<128>(a)); }
 
 // Grouped forms: the same tiles, with the tile -> rows mapping taken from the group offsets.
@@ -803,13 +921,13 @@ template <int DT, bool EDGE>
 __global__ __launch_bounds__(256) void gemm_tiled_grouped_256(const GemmArgs a, const GroupArgs ga) {
     TileRef t;
     if (!grouped_tile<256>(a, ga, t)) return;
-    gemm_tiled_body<256, 256, DT, EDGE, false, (DT == FLE_F32 ? 32 : 16)>(a, t);
+    gemm_tiled_body<256, 256, DT, EDGE, false, (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16)>(a, t);
 }
 template <int DT, bool EDGE, bool W_NT>
 __global__ __launch_bounds__(256, 2) void gemm_tiled_grouped_128(const GemmArgs a, const GroupArgs ga) {
     TileRef t;
     if (!grouped_tile<128>(a, ga, t)) return;
-    gemm_tiled_body<128, 128, DT, EDGE, W_NT, (DT == FLE_F32 ? 32 : 16)>(a, t);
+    gemm_tiled_body<128, 128, DT, EDGE, W_NT, (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16)>(a, t);
 }
 
 }  // namespace fle

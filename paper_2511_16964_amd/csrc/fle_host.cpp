@@ -49,7 +49,9 @@ static const int64_t kGroupedStreamRows = 64;
 fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
-    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16) return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16 or FLE_F16", p->dtype);
+    if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16 && p->dtype != FLE_F8E4M3)
+        return fail(FLE_ERR_OP, "dtype %d is not FLE_F32, FLE_BF16, FLE_F16 or FLE_F8E4M3", p->dtype);
+    const bool f8 = p->dtype == FLE_F8E4M3;
     const int64_t M = p->M, N = p->N, K = p->K;
     const int64_t kLimit = int64_t(1) << 40;
     if (M < 0 || N < 1 || K < 0) return fail(FLE_ERR_SHAPE, "need M >= 0, N >= 1, K >= 0 (got %lld, %lld, %lld)", (long long)M, (long long)N, (long long)K);
@@ -68,9 +70,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
 
     DevEpilogue &e = plan->epi;
     e.row_kind = -1;
-    e.dtype = p->dtype;
+    e.dtype = f8 ? int32_t(FLE_BF16) : p->dtype;  // fp8 problems: everything but x and W is bf16
     e.bias = p->b;
-    const size_t es = esize(p->dtype);
+    plan->op_dtype = p->dtype;
+    const size_t es = esize(e.dtype);      // bytes per element of b, residual / store operands, gamma, beta, out
+    const size_t xs = f8 ? 1 : es;         // bytes per element of x and W
     for (int i = 0; i < p->n_ops; ++i) {
         const fle_op &op = p->ops[i];
         if (op.kind < FLE_BIAS || op.kind > FLE_STORE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
@@ -102,11 +106,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         if (!p->out) return fail(FLE_ERR_NULL, "out is NULL");
         if (K > 0 && (!p->x || !p->w)) return fail(FLE_ERR_NULL, "x or w is NULL");
         // element alignment is the only hard requirement
-        if (!aligned(p->x, es) || !aligned(p->w, es) || !aligned(p->out, es) || !aligned(p->b, es)) return fail(FLE_ERR_ALIGN, "a pointer is not aligned to its element size");
+        if (!aligned(p->x, xs) || !aligned(p->w, xs) || !aligned(p->out, es) || !aligned(p->b, es)) return fail(FLE_ERR_ALIGN, "a pointer is not aligned to its element size");
         const size_t out_bytes = lse ? size_t(M) * es : span_bytes(M, N, p->ldo, es);
-        const size_t w_bytes = span_bytes(N, K, p->ldw, es) + (grp ? size_t(G - 1) * size_t(grp->w_group_stride) * es : 0);
+        const size_t w_bytes = span_bytes(N, K, p->ldw, xs) + (grp ? size_t(G - 1) * size_t(grp->w_group_stride) * xs : 0);
         const size_t b_bytes = size_t(N) * es + (grp ? size_t(G - 1) * size_t(grp->b_group_stride) * es : 0);
-        if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, es)) || overlaps(p->out, out_bytes, p->w, w_bytes) || overlaps(p->out, out_bytes, p->b, b_bytes))
+        if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, xs)) || overlaps(p->out, out_bytes, p->w, w_bytes) || overlaps(p->out, out_bytes, p->b, b_bytes))
             return fail(FLE_ERR_UNSUPPORTED, "out overlaps x, w or b");
         if (grp && (overlaps(p->out, out_bytes, grp->row_offsets, size_t(G + 1) * 8) || overlaps(p->workspace, p->workspace_bytes, grp->row_offsets, size_t(G + 1) * 8)))
             return fail(FLE_ERR_UNSUPPORTED, "out or the workspace overlaps row_offsets");
@@ -119,7 +123,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
             } else if (op.kind == FLE_STORE) {
                 if (!aligned(op.p0, es)) return fail(FLE_ERR_ALIGN, "op %d: store pointer not aligned to its element size", i);
                 const size_t t_bytes = span_bytes(M, N, op.ld, es);
-                bool clash = overlaps(op.p0, t_bytes, p->out, out_bytes) || overlaps(op.p0, t_bytes, p->x, span_bytes(M, K, p->ldx, es)) ||
+                bool clash = overlaps(op.p0, t_bytes, p->out, out_bytes) || overlaps(op.p0, t_bytes, p->x, span_bytes(M, K, p->ldx, xs)) ||
                              overlaps(op.p0, t_bytes, p->w, w_bytes) || overlaps(op.p0, t_bytes, p->b, b_bytes) ||
                              overlaps(op.p0, t_bytes, p->workspace, p->workspace_bytes) || (grp && overlaps(op.p0, t_bytes, grp->row_offsets, size_t(G + 1) * 8));
                 for (int j = 0; j < p->n_ops && !clash; ++j) {
@@ -140,9 +144,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // ---- kernel variant
     const bool f32 = p->dtype == FLE_F32;
     // The tiled kernels copy 16-byte chunks and read / write groups of 4 consecutive columns.
-    const int64_t chunk = 16 / int64_t(es);                  // elements per 16-byte chunk: 8 bf16, 4 fp32
+    const int64_t chunk = 16 / int64_t(xs);                  // x / W elements per 16-byte chunk: 16 fp8, 8 bf16, 4 fp32
     const size_t vec4 = 4 * es;                              // alignment of a 4-column group
-    const int64_t ld_max = int64_t(1) << (f32 ? 20 : 21);    // 32-bit byte offsets inside a 256-row tile
+    const int64_t ld_max = (int64_t(1) << 22) / int64_t(es); // 32-bit byte offsets inside a 256-row tile (epilogue operands)
+    const int64_t ldx_max = (int64_t(1) << 22) / int64_t(xs);  // (x and W)
     bool res_ok = true, post_res_alias_out = false;
     for (int i = 0; i < e.n_pre; ++i) {
         if ((e.pre[i].kind == FLE_RESIDUAL || e.pre[i].kind == FLE_STORE) && !(aligned(e.pre[i].p0, vec4) && e.pre[i].ld % 4 == 0 && e.pre[i].ld < ld_max)) res_ok = false;
@@ -152,7 +157,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // x and W rows must be whole, aligned 16-byte chunks; everything the epilogue touches may be ragged
     // (the kernel then has an element-wise epilogue)
     const bool tiled_ok = K >= chunk && K % chunk == 0 && aligned(p->x, 16) && aligned(p->w, 16) && p->ldx % chunk == 0 && p->ldw % chunk == 0 &&
-                          p->ldx < ld_max && p->ldw < ld_max && (!grp || grp->w_group_stride % chunk == 0);
+                          p->ldx < ldx_max && p->ldw < ldx_max && (!grp || grp->w_group_stride % chunk == 0);
     const bool vec_epi = N % 4 == 0 && (lse || (aligned(p->out, vec4) && p->ldo % 4 == 0)) && aligned(p->b, vec4) && res_ok && (!grp || grp->b_group_stride % 4 == 0);
     if (grp) {
         // Grouped problems run on the tiled kernels only, one workgroup per tile over the whole K.  A group's
@@ -173,6 +178,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         }
         forced_split = 1;
     }
+    if (f8) {  // fp8 operands exist on the tiled kernels only
+        if (forced != V_AUTO && forced != V_TILED && forced != V_TILED_256 && forced != V_TILED_128) return fail(FLE_ERR_UNSUPPORTED, "fp8 problems run on the tiled kernels only");
+        if (!tiled_ok) return fail(FLE_ERR_UNSUPPORTED, "an fp8 problem needs x and W rows made of whole, 16-byte aligned chunks (K and the leading dimensions multiples of 16 elements, K >= 16)");
+        if (forced == V_AUTO) forced = V_TILED;
+    }
     int variant = forced, forced_tile = 0;
     if (variant == V_TILED_256 || variant == V_TILED_128) {
         forced_tile = variant == V_TILED_256 ? 256 : 128;
@@ -185,8 +195,8 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         forced_seq = variant == V_SKINNY_SEQ;
         variant = V_SKINNY;
     }
-    const bool skinny_ok = tiled_ok && vec_epi && M <= 256 && K % (f32 ? 32 : 64) == 0;  // a K step is at least 128 bytes of every row
-    const bool thin_ok = tiled_ok && M >= 1 && M <= 32;  // element-wise epilogue: nothing else needs alignment
+    const bool skinny_ok = !f8 && tiled_ok && vec_epi && M <= 256 && K % (f32 ? 32 : 64) == 0;  // a K step is at least 128 bytes of every row
+    const bool thin_ok = !f8 && tiled_ok && M >= 1 && M <= 32;  // element-wise epilogue: nothing else needs alignment
 
     // Tile and split of K of the tiled kernel together, by a coarse time model (microseconds) fitted
     // to measured runs.  bf16: a K step (128 bytes of every row) costs a 256 tile 1.45, a 128 tile 0.85
@@ -195,7 +205,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     // workgroups beyond the 256 (512) that are resident at once wait for a second round; a split adds
     // a launch and 8 S M N bytes of slab traffic at about 6 TB/s (the slabs mostly stay in the
     // last-level cache).
-    const int64_t tiled_steps = (K * int64_t(es) + 127) / 128;
+    const int64_t tiled_steps = (K * int64_t(xs) + 127) / 128;
     auto tiled_cost = [&](int tile, int64_t sp) -> double {
         const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
         const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
@@ -293,7 +303,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->part_cols = 16;
     } else if (variant == V_TILED) {
         plan->bm = plan->bn = best_tile;
-        plan->bk = f32 ? 32 : 64;
+        plan->bk = f32 ? 32 : f8 ? 128 : 64;
         plan->part_cols = plan->bn / 2;  // one partial per wave column
         plan->edge = vec_epi ? 0 : 1;
         auto_split = best_split;
@@ -374,8 +384,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
 using namespace fle;
 
 static void format_plan(const Plan &plan, char *buf, size_t n) {
-    const bool f32 = plan.epi.dtype == FLE_F32;
-    const char *dt = f32 ? "f32" : plan.epi.dtype == FLE_F16 ? "f16" : "bf16";
+    const char *dt = plan.op_dtype == FLE_F32 ? "f32" : plan.op_dtype == FLE_F16 ? "f16" : plan.op_dtype == FLE_F8E4M3 ? "f8" : "bf16";
     snprintf(buf, n, "variant=%s_%s_%s%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
              plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : plan.variant == V_THIN ? "thin" : "general", dt,
              plan.variant == V_THIN && plan.bm == 8 ? "dot" : "mfma",

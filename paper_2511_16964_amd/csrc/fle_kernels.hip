@@ -127,7 +127,8 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         hipLaunchKernelGGL(kern, dim3(uint32_t(plan.tiles_n)), dim3(threads), 0, stream, g);
     } else if (plan.variant == V_TILED && grp) {
         const bool edge = plan.edge != 0;
-        GroupArgs ga{grp->row_offsets, grp->n_groups, grp->w_group_stride * int64_t(es), grp->b_group_stride * int64_t(es)};
+        const int64_t xs = plan.op_dtype == FLE_F8E4M3 ? 1 : int64_t(es);  // bytes per element of W
+        GroupArgs ga{grp->row_offsets, grp->n_groups, grp->w_group_stride * xs, grp->b_group_stride * int64_t(es)};
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs, GroupArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm == 256) return edge ? gemm_tiled_grouped_256<DT, true> : gemm_tiled_grouped_256<DT, false>;
@@ -135,7 +136,8 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
             return edge ? gemm_tiled_grouped_128<DT, true, false> : gemm_tiled_grouped_128<DT, false, false>;
         };
         void (*kern)(GemmArgs, GroupArgs) = p->dtype == FLE_F32 ? pick(std::integral_constant<int, FLE_F32>{})
-                                            : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{}) : pick(std::integral_constant<int, FLE_BF16>{});
+                                            : p->dtype == FLE_F16 ? pick(std::integral_constant<int, FLE_F16>{})
+                                            : p->dtype == FLE_F8E4M3 ? pick(std::integral_constant<int, FLE_F8E4M3>{}) : pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g, ga);
     } else if (plan.variant == V_TILED) {
         // split K writes fp32 slabs with a padded leading dimension: vector stores whatever out looks like
@@ -148,6 +150,7 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         };
         if (p->dtype == FLE_F32) kern = pick(std::integral_constant<int, FLE_F32>{});
         else if (p->dtype == FLE_F16) kern = pick(std::integral_constant<int, FLE_F16>{});
+        else if (p->dtype == FLE_F8E4M3) kern = pick(std::integral_constant<int, FLE_F8E4M3>{});
         else kern = pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);
     } else {

@@ -22,7 +22,7 @@ struct DevEpilogue {
     int32_t n_pre;     // elementwise ops applied in the GEMM kernel's registers
     int32_t n_post;    // elementwise ops applied by the finalize pass, after the row op
     int32_t row_kind;  // FLE_LAYERNORM / FLE_SOFTMAX / FLE_LOGSUMEXP, or -1
-    int32_t dtype;     // fle_dtype of every operand
+    int32_t dtype;     // fle_dtype of b, residual / store operands, gamma, beta and out (fp8 problems: FLE_BF16)
     const void *bias;  // b[N] or nullptr
     DevOp row;         // valid when row_kind >= 0
     DevOp pre[FLE_MAX_OPS];
@@ -49,6 +49,7 @@ struct Plan {
     int32_t split_k;         // workgroups along K per tile (1: none); > 1 adds fp32 slabs and a reduction pass
     int32_t groups;          // grouped problem: number of row groups (tiles_m is then an upper bound); 0 otherwise
     int32_t w_stream;        // grouped problem with about one tile row per group: W panels are read once (non-temporal copies)
+    int32_t op_dtype;        // fle_dtype of x and W (differs from epi.dtype for fp8 problems only)
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
     DevEpilogue epi;

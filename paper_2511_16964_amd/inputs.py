@@ -60,6 +60,15 @@ def _store(a: np.ndarray, dtype: torch.dtype) -> torch.Tensor:
     return torch.from_numpy(a).to(dtype)
 
 
+F8 = torch.float8_e4m3fn
+
+
+def io_dtype(dtype: torch.dtype) -> torch.dtype:
+    """Dtype of b, residual / store operands, gamma, beta and out of a problem whose x and W have ``dtype``
+    (fp8 problems keep everything but x and W in bf16)."""
+    return torch.bfloat16 if dtype == F8 else dtype
+
+
 # name -> (dtype, M, N, K)
 SHAPES = {
     "c1": (torch.float32, 64, 256, 256),
@@ -68,12 +77,13 @@ SHAPES = {
     "c4": (torch.bfloat16, 32, 32768, 8192),
     "c5a": (torch.bfloat16, 16384, 16384, 4096),
     "c5b": (torch.bfloat16, 16384, 4096, 16384),
+    "f2": (torch.float8_e4m3fn, 4096, 4096, 4096),   # c2 with x and W stored in fp8 (one scale per tensor)
 }
 
 
 def make(name: str, seed: int = 0, M: int | None = None, N: int | None = None,
          K: int | None = None) -> Problem:
-    """Build configuration ``name`` ("c1".."c4"); M, N, K override the shape
+    """Build configuration ``name`` ("c1".."c4", "f2"); M, N, K override the shape
     (same distributions, for reduced-size parity cases)."""
     dtype, M0, N0, K0 = SHAPES[name]
     M, N, K = M or M0, N or N0, K or K0
@@ -87,6 +97,12 @@ def make(name: str, seed: int = 0, M: int | None = None, N: int | None = None,
         r = _normal(rng, (M, N))
         return Problem(name, dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype),
                        [("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, dtype))])
+    if name == "f2":    # c2's layer with fp8 storage: x / sx and W / sw in e4m3 (the largest magnitude maps to 448), scale sx sw first
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
+        r = _normal(rng, (M, N))
+        sx, sw = float(np.abs(x).max()) / 448.0, float(np.abs(w).max()) / 448.0
+        return Problem(name, dtype, _store(x / np.float32(sx), dtype), _store(w / np.float32(sw), dtype), _store(b, torch.bfloat16),
+                       [("scale", float(np.float32(sx * sw))), ("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, torch.bfloat16))])
     if name == "c3":    # Linear + bias + GELU-tanh + LayerNorm, bf16
         x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
         g = _normal(rng, (N,), 1.0, 0.02); be = _normal(rng, (N,), 0.0, 0.02)
@@ -146,20 +162,21 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
         x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / math.sqrt(max(K, 1)))
         b = _uniform(rng, (N,), 0.5)
     ep = []
+    io = io_dtype(dtype)
     for kd in kinds:
         if kd == "scale":
             ep.append(("scale", 0.5 if integer else float(np.float32(rng.uniform(0.25, 2.0)))))
         elif kd == "residual":
             r = ri((M, N), 8) if integer else _normal(rng, (M, N))
-            ep.append(("residual", _store(r, dtype)))
+            ep.append(("residual", _store(r, io)))
         elif kd == "layernorm":
             g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
-            ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+            ep.append(("layernorm", _store(g, io), _store(be, io), 1e-5))
         elif kd == "store":   # the target: an output, pre-filled so that an unwritten element shows
-            ep.append(("store", torch.full((M, N), -7.0, dtype=dtype)))
+            ep.append(("store", torch.full((M, N), -7.0, dtype=io)))
         else:
             ep.append((kd,))
-    return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), ep)
+    return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, io), ep)
 
 
 @dataclass
@@ -220,15 +237,15 @@ def random_grouped(seed: int, counts, N: int, K: int, dtype: torch.dtype, kinds:
             ep.append(("scale", 0.5 if integer else float(np.float32(rng.uniform(0.25, 2.0)))))
         elif kd == "residual":
             r = ri((M, N), 8) if integer else _normal(rng, (M, N))
-            ep.append(("residual", _store(r, dtype)))
+            ep.append(("residual", _store(r, io_dtype(dtype))))
         elif kd == "layernorm":
             g = _normal(rng, (N,), 1.0, 0.1); be = _normal(rng, (N,), 0.0, 0.1)
-            ep.append(("layernorm", _store(g, dtype), _store(be, dtype), 1e-5))
+            ep.append(("layernorm", _store(g, io_dtype(dtype)), _store(be, io_dtype(dtype)), 1e-5))
         elif kd == "store":   # the target: an output, pre-filled so that an unwritten element shows
-            ep.append(("store", torch.full((M, N), -7.0, dtype=dtype)))
+            ep.append(("store", torch.full((M, N), -7.0, dtype=io_dtype(dtype))))
         else:
             ep.append((kd,))
-    return GroupedProblem(dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype), offsets_of(counts), ep)
+    return GroupedProblem(dtype, _store(x, dtype), _store(w, dtype), _store(b, io_dtype(dtype)), offsets_of(counts), ep)
 
 
 # name -> (dtype, rows M, groups G, N, K, Dirichlet skew of the routing)

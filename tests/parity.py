@@ -20,7 +20,7 @@ import torch
 import oracle
 from paper_2511_16964_amd import binding, inputs
 
-TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2, torch.float16: 4e-3}
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2, torch.float16: 4e-3, torch.float8_e4m3fn: 2e-2}   # (fp8 problems: bf16 out, exact products)
 
 
 def to_dev(t, dev="cuda:0"):
@@ -41,7 +41,7 @@ def run_gpu(prob: inputs.Problem, variant="auto", poison=False, **kw):
     in the result (a fresh torch.empty may hold anything, including plausible numbers)."""
     if poison:
         lse = bool(prob.epilogue) and prob.epilogue[-1][0] == "logsumexp"
-        kw["out"] = torch.full((prob.M,) if lse else (prob.M, prob.N), float("nan"), dtype=prob.x.dtype, device="cuda:0")
+        kw["out"] = torch.full((prob.M,) if lse else (prob.M, prob.N), float("nan"), dtype=inputs.io_dtype(prob.x.dtype), device="cuda:0")
     call = make_call(prob, variant, **kw)
     out = call.run()
     torch.cuda.synchronize()

@@ -623,3 +623,42 @@ def test_binding_checks_every_tensor_a_kernel_would_touch(L):
             binding.Call(x, w, b, [("layernorm", g, bad, 1e-5)])
     with pytest.raises(TypeError):
         binding.Call(x, w, b, [("layernorm", g.float(), g, 1e-5)])
+
+
+def test_fp8_problems_validate_and_plan_on_the_tiled_kernels_only(L):
+    F8 = binding.F8E4M3
+    res = 6 * G
+    p = problem(M=4096, N=4096, K=4096, dtype=F8, ops=[op("scale", 0.01), op("bias"), op("relu"), op("residual", p0=res, ld=4096)])
+    assert validate(L, p) == OK
+    need = ctypes.c_size_t(0)
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK and need.value == 0
+    buf = ctypes.create_string_buffer(256)
+    L.fle_last_plan(buf, 256)
+    assert b"tiled_f8_mfma" in buf.value and b"tile=256x256x128" in buf.value, buf.value
+    # a K step is 128 fp8 values; rows must be whole 16-byte chunks: K and the strides multiples of 16 elements
+    assert validate(L, problem(M=64, N=64, K=48, dtype=F8)) == OK
+    assert validate(L, problem(M=64, N=64, K=40, dtype=F8)) == E_UNSUP
+    assert validate(L, problem(M=64, N=64, K=8, dtype=F8)) == E_UNSUP
+    q = problem(M=64, N=64, K=64, dtype=F8)
+    q.x = G + 8
+    assert validate(L, q) == E_UNSUP
+    # out / b / residual are bf16: 2-byte alignment and spans
+    q = problem(M=64, N=64, K=64, dtype=F8)
+    q.out = 3 * G + 1
+    assert validate(L, q) == E_ALIGN
+    # row ops and the split of K work as for the other dtypes; every other kernel family refuses fp8
+    p = problem(M=8192, N=4096, K=4096, dtype=F8, ops=[op("bias"), op("gelu_tanh"), op("layernorm", 1e-5, 7 * G, 8 * G)])
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK and need.value == 8192 * 32 * 2 * 4   # one partial per row and 128 columns
+    for forced in (1, 3, 6, 7, 8, 9):
+        L.fle_force_variant(forced)
+        try:
+            assert validate(L, problem(M=32, N=256, K=256, dtype=F8)) == E_UNSUP, forced
+        finally:
+            L.fle_force_variant(0)
+    L.fle_force_split(4)
+    try:
+        p = problem(M=64, N=128, K=4096, dtype=F8, ops=[op("bias")])
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK and need.value == 4 * 64 * 128 * 4
+    finally:
+        L.fle_force_split(0)
+    assert validate(L, problem(dtype=4)) == E_OP
