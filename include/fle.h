@@ -117,10 +117,13 @@ typedef struct {
 } fle_problem;
 
 /*
- * Accepted epilogue grammar:   elementwise*  [ LAYERNORM | SOFTMAX | LOGSUMEXP ]  elementwise*
- * with elementwise = BIAS | SCALE | RELU | GELU_ERF | GELU_TANH | RESIDUAL | STORE (STORE only before
- * the row op), at most one row op, and nothing after LOGSUMEXP.  A second row op gives
- * FLE_ERR_UNSUPPORTED.
+ * Accepted epilogue grammar:   elementwise*  [ rowop  elementwise*  [ rowop  elementwise* ] ]
+ * with rowop = LAYERNORM | SOFTMAX | LOGSUMEXP and elementwise = BIAS | SCALE | RELU | GELU_ERF |
+ * GELU_TANH | RESIDUAL | STORE (STORE only before the first row op); nothing follows LOGSUMEXP.  A
+ * list with two row ops (e.g. LAYERNORM, SOFTMAX: a normalised layer's class probabilities) costs
+ * M * N * 4 more workspace bytes and a third pass over the rows; the values between the two
+ * reductions stay in fp32.  A third row op gives FLE_ERR_UNSUPPORTED, as does a second one in a
+ * grouped problem.
  *
  * Alignment rule: no alignment is required for correctness.  The fast kernels (tiled MFMA
  * kernels for every dtype; the skinny and thin kernels that stream W for up to 256, 32 or 8

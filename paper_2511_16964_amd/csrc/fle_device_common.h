@@ -64,11 +64,21 @@ struct FinArgs {
     const float *partials;
     void *out;
     int64_t ldo;
+    int32_t out_f32;  // out holds fp32 regardless of the storage dtype (the values handed to a second row reduction)
     // grouped problems whose list has a bias op after the row op: the row's group selects the bias
     const int64_t *row_offsets;  // [n_groups + 1] (device), or nullptr
     int32_t n_groups;
     int64_t b_stride_bytes;
     DevEpilogue epi;
+};
+
+// Second row reduction of a list (second_row_op): v[M,N] fp32 in, out in the storage dtype.
+struct Row2Args {
+    int64_t M, N;
+    const float *v;  // [M][N] fp32, packed rows
+    void *out;       // [M][ldo], or [M] for logsumexp
+    int64_t ldo;
+    DevEpilogue epi; // row2_kind, row2, post2 (and bias, dtype)
 };
 
 // ------------------------------------------------------------------ scalar helpers

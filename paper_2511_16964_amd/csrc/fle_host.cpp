@@ -70,6 +70,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
 
     DevEpilogue &e = plan->epi;
     e.row_kind = -1;
+    e.row2_kind = -1;
     e.dtype = f8 ? int32_t(FLE_BF16) : p->dtype;  // fp8 problems: everything but x and W is bf16
     e.bias = p->b;
     plan->op_dtype = p->dtype;
@@ -78,13 +79,14 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     for (int i = 0; i < p->n_ops; ++i) {
         const fle_op &op = p->ops[i];
         if (op.kind < FLE_BIAS || op.kind > FLE_STORE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
-        if (e.row_kind == FLE_LOGSUMEXP) return fail(FLE_ERR_UNSUPPORTED, "op %d follows logsumexp, which must be last", i);
+        if (e.row_kind == FLE_LOGSUMEXP || e.row2_kind == FLE_LOGSUMEXP) return fail(FLE_ERR_UNSUPPORTED, "op %d follows logsumexp, which must be last", i);
         DevOp d{op.kind, op.alpha, op.p0, op.p1, op.ld};
         if (is_row_op(op.kind)) {
-            if (e.row_kind >= 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: a second row reduction in one list is not supported", i);
+            if (e.row2_kind >= 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: a third row reduction in one list is not supported", i);
+            if (e.row_kind >= 0 && grp) return fail(FLE_ERR_UNSUPPORTED, "op %d: grouped problems take one row reduction", i);
             if (op.kind == FLE_LAYERNORM && !(op.alpha >= 0.0f && std::isfinite(op.alpha))) return fail(FLE_ERR_OP, "op %d: layernorm eps must be finite and >= 0", i);
-            e.row_kind = op.kind;
-            e.row = d;
+            if (e.row_kind >= 0) { e.row2_kind = op.kind; e.row2 = d; }
+            else { e.row_kind = op.kind; e.row = d; }
             continue;
         }
         if (op.kind == FLE_BIAS && !p->b && M > 0) return fail(FLE_ERR_NULL, "op %d: bias listed but b is NULL", i);
@@ -96,9 +98,11 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
             if (op.ld > kLimit) return fail(FLE_ERR_SHAPE, "op %d: %s ld too large", i, what);
             if (op.kind == FLE_STORE && e.row_kind >= 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: a store after the row op is not supported", i);
         }
-        if (e.row_kind < 0) e.pre[e.n_pre++] = d; else e.post[e.n_post++] = d;
+        if (e.row_kind < 0) e.pre[e.n_pre++] = d;
+        else if (e.row2_kind < 0) e.post[e.n_post++] = d;
+        else e.post2[e.n_post2++] = d;
     }
-    const bool lse = e.row_kind == FLE_LOGSUMEXP;
+    const bool lse = e.row_kind == FLE_LOGSUMEXP || e.row2_kind == FLE_LOGSUMEXP;  // out is [M]
     if (p->ldx < K || p->ldw < K) return fail(FLE_ERR_SHAPE, "ldx %lld / ldw %lld smaller than K %lld", (long long)p->ldx, (long long)p->ldw, (long long)K);
     if (!lse && p->ldo < N) return fail(FLE_ERR_SHAPE, "ldo %lld < N %lld", (long long)p->ldo, (long long)N);
     if (p->ldx > kLimit || p->ldw > kLimit || p->ldo > kLimit) return fail(FLE_ERR_SHAPE, "leading dimension too large");
@@ -154,6 +158,8 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     }
     for (int i = 0; i < e.n_post; ++i)
         if (e.post[i].kind == FLE_RESIDUAL && e.post[i].p0 == p->out) post_res_alias_out = true;
+    for (int i = 0; i < e.n_post2; ++i)
+        if (e.post2[i].kind == FLE_RESIDUAL && e.post2[i].p0 == p->out) post_res_alias_out = true;
     // x and W rows must be whole, aligned 16-byte chunks; everything the epilogue touches may be ragged
     // (the kernel then has an element-wise epilogue)
     const bool tiled_ok = K >= chunk && K % chunk == 0 && aligned(p->x, 16) && aligned(p->w, 16) && p->ldx % chunk == 0 && p->ldw % chunk == 0 &&
@@ -356,13 +362,14 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         plan->np = int32_t((N + plan->part_cols - 1) / plan->part_cols);
         plan->ws_part_off = off;
         off = round_up(off + size_t(M) * size_t(plan->np) * 2 * sizeof(float), 256);
-        if (!lse) {
-            // Staged in out itself unless a trailing residual aliases out.  A 2-byte dtype stages v minus the
+        if (e.row_kind != FLE_LOGSUMEXP) {
+            // Staged in out itself unless a trailing residual aliases out (or out is the [M] vector of a logsumexp
+            // that comes second).  A 2-byte dtype stages v minus the
             // statistic of v's partial (its mean for LayerNorm, its maximum for softmax), which the finalize pass
             // adds back in fp32: the rounding error of the staged value is then relative to the distance from that
             // statistic, not to v itself (a row of mean 100 and deviation 0.01 keeps its deviations; exp() of a
             // distance d <= 0 is off by at most |d| 2^-9, negligible where the probability is not).
-            const bool in_out = !post_res_alias_out;
+            const bool in_out = !post_res_alias_out && !lse;
             plan->staging = in_out ? ST_OUT : ST_WS;
             plan->stage_rel = (in_out && p->dtype != FLE_F32) ? 1 : 0;
             if (!in_out) {
@@ -370,6 +377,10 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
                 off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);
             }
         }
+    }
+    if (e.row2_kind >= 0) {  // the values between the two row reductions, fp32 [M,N]
+        plan->ws_mid_off = off;
+        off = round_up(off + size_t(M) * size_t(N) * sizeof(float), 256);
     }
     if (plan->split_k > 1) {
         plan->ws_slab_off = off;

@@ -193,12 +193,14 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         hipLaunchKernelGGL(finalize_lse, dim3(uint32_t((p->M + 3) / 4)), dim3(256), 0, stream, f);
         return check_launch("logsumexp finalize launch");
     }
+    const bool two = e.row2_kind >= 0;  // a second row reduction: this pass hands its values over in fp32
+    if (two) { f.out = ws + plan.ws_mid_off; f.ldo = p->N; f.out_f32 = 1; }
     if (split) { f.y = r.dst; f.ldy = r.ldd; f.y_f32 = r.dst_f32; }
     else { f.y = g.dst; f.ldy = g.ldd; f.y_f32 = g.dst_f32; }
     f.y_rel = plan.stage_rel;
     const size_t ysz = f.y_f32 ? 4 : es;
-    const bool vec = p->N % 8 == 0 && f.ldy % 8 == 0 && p->ldo % 8 == 0 && reinterpret_cast<uintptr_t>(f.y) % (8 * ysz) == 0 &&
-                     reinterpret_cast<uintptr_t>(p->out) % (8 * es) == 0;
+    const bool vec = p->N % 8 == 0 && f.ldy % 8 == 0 && f.ldo % 8 == 0 && reinterpret_cast<uintptr_t>(f.y) % (8 * ysz) == 0 &&
+                     reinterpret_cast<uintptr_t>(f.out) % (8 * (two ? 4 : es)) == 0;
     // vector path also needs 16-byte aligned gamma / beta
     const bool gb_ok = reinterpret_cast<uintptr_t>(e.row.p0) % (8 * es) == 0 && reinterpret_cast<uintptr_t>(e.row.p1) % (8 * es) == 0;
     const int64_t items = p->M * ((p->N + 2047) / 2048);
@@ -208,7 +210,15 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     if (e.row_kind == FLE_LAYERNORM) fin = (vec && gb_ok) ? finalize_rows<true, true> : finalize_rows<false, true>;
     else fin = (vec && gb_ok) ? finalize_rows<true, false> : finalize_rows<false, false>;
     hipLaunchKernelGGL(fin, fgrid, dim3(256), 0, stream, f);
-    return check_launch("row finalize launch");
+    s = check_launch("row finalize launch");
+    if (s != FLE_OK || !two) return s;
+    Row2Args r2{};
+    r2.M = p->M; r2.N = p->N;
+    r2.v = reinterpret_cast<const float *>(ws + plan.ws_mid_off);
+    r2.out = p->out; r2.ldo = p->ldo;
+    r2.epi = e;
+    hipLaunchKernelGGL(second_row_op, dim3(uint32_t(p->M < (int64_t(1) << 16) ? p->M : (int64_t(1) << 16))), dim3(256), 0, stream, r2);
+    return check_launch("second row reduction launch");
 }
 
 template <int DT, int D>

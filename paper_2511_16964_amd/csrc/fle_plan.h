@@ -27,6 +27,12 @@ struct DevEpilogue {
     DevOp row;         // valid when row_kind >= 0
     DevOp pre[FLE_MAX_OPS];
     DevOp post[FLE_MAX_OPS];
+    // a second row reduction later in the list: the finalize pass hands its values over in fp32, a third pass
+    // (second_row_op) reduces, normalises and applies the ops behind it
+    int32_t row2_kind;  // FLE_LAYERNORM / FLE_SOFTMAX / FLE_LOGSUMEXP, or -1
+    int32_t n_post2;
+    DevOp row2;
+    DevOp post2[FLE_MAX_OPS];
 };
 
 enum Variant { V_AUTO = 0, V_GENERAL = 1, V_TILED = 2, V_SKINNY = 3, V_TILED_256 = 4, V_TILED_128 = 5, V_SKINNY_128 = 6, V_SKINNY_256 = 7, V_SKINNY_SEQ = 8, V_THIN = 9 };
@@ -51,7 +57,7 @@ struct Plan {
     int32_t w_stream;        // grouped problem with about one tile row per group: W panels are read once (non-temporal copies)
     int32_t op_dtype;        // fle_dtype of x and W (differs from epi.dtype for fp8 problems only)
     int64_t tiles_m, tiles_n;
-    size_t ws_part_off, ws_y_off, ws_slab_off, ws_total;
+    size_t ws_part_off, ws_y_off, ws_slab_off, ws_mid_off, ws_total;  // (ws_mid: fp32 [M,N] between two row ops)
     DevEpilogue epi;
 };
 

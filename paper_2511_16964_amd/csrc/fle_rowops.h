@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = post(v[e], n + e);
                     }
-                    if (f32) {
+                    if (f32 || a.out_f32) {
                         f32x4 *dstp = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.out) + row * a.ldo + n);
                         dstp[0] = f32x4{v[0], v[1], v[2], v[3]};
                         dstp[1] = f32x4{v[4], v[5], v[6], v[7]};
@@ -136,14 +136,14 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                 } else {
                     v = __expf(yv - shift) * mul;
                 }
-                st_elem(a.out, row * a.ldo + n, dtype, post(v, n));
+                st_elem(a.out, row * a.ldo + n, a.out_f32 ? FLE_F32 : dtype, post(v, n));
             };
             // bf16 rows whose staged values and outputs share their offset within a 16-byte line (always so
             // when staged in out itself): skip h elements to the next line boundary, then whole lines as
             // 16-byte vectors.  Chunk k takes elements h + 2048 k ... of the row, chunk 0 also the first h.
             const uintptr_t ya = reinterpret_cast<uintptr_t>(a.y) + uintptr_t(row * a.ldy) * 2;
             const uintptr_t oa = reinterpret_cast<uintptr_t>(a.out) + uintptr_t(row * a.ldo) * 2;
-            if (!f32 && !a.y_f32 && ((ya ^ oa) & 15) == 0 && (ya & 1) == 0) {
+            if (!f32 && !a.y_f32 && !a.out_f32 && ((ya ^ oa) & 15) == 0 && (ya & 1) == 0) {
                 const int h = int(((16 - (ya & 15)) & 15) >> 1);
                 if (c0 == 0 && lane < h && lane < N) one(lane);
 #pragma unroll
@@ -192,6 +192,72 @@ __global__ __launch_bounds__(256) void finalize_lse(const FinArgs a) {
     if (row >= a.M) return;
     const Stat s = reduce_partials<false>(a.partials, row, a.np, a.part_cols, a.N, lane);
     if (lane == 0) st_elem(a.out, row, a.epi.dtype, s.a + __logf(s.b));
+}
+
+// ------------------------------------------------------------------ a second row reduction in the list
+// One workgroup per row: the values behind the first row reduction (and the ops that follow it) arrive in fp32;
+// three sweeps over the row (it stays in the L2): mean or maximum, then sum of squared deviations or of
+// exponentials, then normalise, apply the ops behind the reduction, round and store.  Sums are formed per thread
+// in index order, across the wave by a fixed butterfly and across the four waves in wave order: reproducible.
+__device__ __forceinline__ float block_allreduce(float v, bool max, float *lds) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const float o = __shfl_xor(v, d);
+        v = max ? fmaxf(v, o) : v + o;
+    }
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();  // (the previous use of lds is over)
+    if ((threadIdx.x & 63) == 0) lds[wave] = v;
+    __syncthreads();
+    float r = lds[0];
+    for (int w = 1; w < 4; ++w) r = max ? fmaxf(r, lds[w]) : r + lds[w];
+    return r;
+}
+
+__global__ __launch_bounds__(256) void second_row_op(const Row2Args a) {
+    __shared__ float lds[4];
+    const int64_t N = a.N;
+    const int dtype = a.epi.dtype;
+    const int kind = a.epi.row2_kind;
+    for (int64_t row = blockIdx.x; row < a.M; row += gridDim.x) {
+        const float *v = a.v + row * N;
+        float sub, mul;
+        if (kind == FLE_LAYERNORM) {
+            float s = 0.0f;
+            for (int64_t n = threadIdx.x; n < N; n += 256) s += v[n];
+            const float mean = block_allreduce(s, false, lds) / float(N);
+            float m2 = 0.0f;
+            for (int64_t n = threadIdx.x; n < N; n += 256) m2 += (v[n] - mean) * (v[n] - mean);
+            m2 = block_allreduce(m2, false, lds);
+            sub = mean;
+            mul = rsqrtf(m2 / float(N) + a.epi.row2.alpha);
+        } else {
+            float mx = -INFINITY;
+            for (int64_t n = threadIdx.x; n < N; n += 256) mx = fmaxf(mx, v[n]);
+            mx = block_allreduce(mx, true, lds);
+            float se = 0.0f;
+            for (int64_t n = threadIdx.x; n < N; n += 256) se += __expf(v[n] - mx);
+            se = block_allreduce(se, false, lds);
+            sub = mx;
+            mul = 1.0f / se;
+            if (kind == FLE_LOGSUMEXP) {
+                if (threadIdx.x == 0) st_elem(a.out, row, dtype, mx + __logf(se));
+                continue;
+            }
+        }
+        for (int64_t n = threadIdx.x; n < N; n += 256) {
+            float o;
+            if (kind == FLE_LAYERNORM) {
+                o = (v[n] - sub) * mul;
+                if (a.epi.row2.p0) o *= ld_elem(a.epi.row2.p0, n, dtype);
+                if (a.epi.row2.p1) o += ld_elem(a.epi.row2.p1, n, dtype);
+            } else {
+                o = __expf(v[n] - sub) * mul;
+            }
+            for (int q = 0; q < a.epi.n_post2; ++q) o = apply_op(a.epi.post2[q], o, row, n, a.epi.bias, dtype);
+            st_elem(a.out, row * a.ldo + n, dtype, o);
+        }
+    }
 }
 
 // ------------------------------------------------------------------ split-K reduction

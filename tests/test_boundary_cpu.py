@@ -123,7 +123,16 @@ def test_ops_and_grammar(L):
     assert validate(L, p) == E_OP
     p = problem(); p.dtype = 7
     assert validate(L, p) == E_OP
-    assert validate(L, problem(ops=[op("softmax"), op("layernorm", 1e-5)])) == E_UNSUP
+    # two row reductions in one list are accepted (a third one is not): fp32 [M,N] more workspace for the values between them
+    need = ctypes.c_size_t(0)
+    one = problem(M=64, N=64, K=64, ops=[op("softmax")])
+    assert L.fle_workspace_size(ctypes.byref(one), ctypes.byref(need)) == OK
+    base = need.value
+    two = problem(M=64, N=64, K=64, ops=[op("softmax"), op("relu"), op("layernorm", 1e-5), op("scale", 2.0)])
+    assert L.fle_workspace_size(ctypes.byref(two), ctypes.byref(need)) == OK and need.value == base + 64 * 64 * 4
+    assert validate(L, problem(ops=[op("layernorm", 1e-5), op("bias"), op("logsumexp")])) == OK
+    assert validate(L, problem(ops=[op("softmax"), op("layernorm", 1e-5), op("softmax")])) == E_UNSUP
+    assert validate(L, problem(ops=[op("layernorm", 1e-5), op("logsumexp"), op("relu")])) == E_UNSUP
     assert validate(L, problem(ops=[op("logsumexp"), op("relu")])) == E_UNSUP
     assert b"logsumexp" in L.fle_last_error()
 
@@ -580,7 +589,7 @@ def test_run_static_refuses_on_the_host_what_it_cannot_take(L):
     """fle_run_static decides everything except the launch on the host: an invalid problem and a problem whose
     scratch exceeds the static array come back as errors before any HIP call."""
     assert L.fle_run_static(None) == E_NULL
-    p = problem(ops=[op("softmax"), op("softmax")])
+    p = problem(ops=[op("softmax"), op("softmax"), op("softmax")])
     assert L.fle_run_static(ctypes.byref(p)) == E_UNSUP
     out = 2 * G
     p = problem(M=4096, N=8192, K=64, ops=[op("layernorm", 1e-5), op("residual", p0=G + out, ld=8192)])
