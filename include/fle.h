@@ -149,6 +149,23 @@ fle_status fle_workspace_size(const fle_problem *p, size_t *bytes_out);
 fle_status fle_run(const fle_problem *p);
 
 /*
+ * The plan (kernel family, tile, split of K) that fle_run derives from a cost model can also be given by the
+ * caller, per call and without any state in the library: this is how a table made by an offline tuning run is
+ * applied (the paper credits autotuned tile choices for many of its best solutions, Section 5.2 and the appendix
+ * on outlier tasks; the package's autotune module measures every candidate plan of a list of shapes on the GPU at
+ * hand and writes such a table).  variant and split mean what fle_force_variant and fle_force_split document
+ * (0 = the library's own choice for that part).  c NULL gives FLE_ERR_NULL, values outside the ranges below
+ * FLE_ERR_OP, a choice that cannot run the problem FLE_ERR_UNSUPPORTED; nothing is enqueued then.  The thread's
+ * fle_force_* knobs are not read.  Results do not depend on the plan beyond floating-point summation order.
+ */
+typedef struct {
+    int32_t variant; /* 0 .. 9 as for fle_force_variant */
+    int32_t split;   /* 0 = automatic, 1 = none, S > 1 = S workgroups per output tile (at most 64) */
+} fle_plan_choice;
+fle_status fle_workspace_size_with(const fle_problem *p, const fle_plan_choice *c, size_t *bytes_out);
+fle_status fle_run_with(const fle_problem *p, const fle_plan_choice *c);
+
+/*
  * fle_run for callers that cannot allocate device memory or cannot bring a workspace: code inside a HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  p->workspace and
  * p->workspace_bytes are ignored; the scratch that fle_run takes from the workspace (row-reduction

@@ -19,7 +19,7 @@ OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "re
 MAX_OPS = 8
 STATIC_SCRATCH_BYTES = 16 << 20
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
-EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_run_static", "fle_status_string", "fle_last_error",
+EXPORTS = ["fle_validate", "fle_workspace_size", "fle_run", "fle_run_static", "fle_run_with", "fle_workspace_size_with", "fle_status_string", "fle_last_error",
            "fle_last_plan", "fle_force_variant", "fle_force_split", "fle_version",
            "fle_validate_grouped", "fle_workspace_size_grouped", "fle_run_grouped",
            "fle_attention_validate", "fle_attention_run", "fle_attention_block_validate",
@@ -42,6 +42,10 @@ class FleProblem(ctypes.Structure):
                 ("ops", ctypes.POINTER(FleOp)), ("n_ops", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p)]
+
+
+class FlePlanChoice(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("split", ctypes.c_int32)]
 
 
 class FleGroups(ctypes.Structure):
@@ -101,6 +105,10 @@ def lib():
             getattr(L, name).argtypes = [ctypes.POINTER(FleProblem)]
         L.fle_workspace_size.restype = ctypes.c_int
         L.fle_workspace_size.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(ctypes.c_size_t)]
+        L.fle_run_with.restype = ctypes.c_int
+        L.fle_run_with.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FlePlanChoice)]
+        L.fle_workspace_size_with.restype = ctypes.c_int
+        L.fle_workspace_size_with.argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FlePlanChoice), ctypes.POINTER(ctypes.c_size_t)]
         for name in ("fle_validate_grouped", "fle_run_grouped"):
             getattr(L, name).restype = ctypes.c_int
             getattr(L, name).argtypes = [ctypes.POINTER(FleProblem), ctypes.POINTER(FleGroups)]
@@ -166,7 +174,7 @@ class Call:
     """A marshalled fle_problem bound to its tensors: ``run()`` enqueues it on the
     current stream.  Keeps every tensor alive; reusable (the benchmark times ``run``)."""
 
-    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0, offsets=None):
+    def __init__(self, x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0, offsets=None, table=None):
         grouped = offsets is not None
         if x.dim() != 2 or w.dim() != (3 if grouped else 2) or x.shape[1] != w.shape[-1]:
             raise ValueError("x must be [M,K] and w [N,K] (grouped: [G,N,K])")
@@ -256,17 +264,22 @@ class Call:
         self._p, self._ops, self._tensors = p, ops, tensors
         self._dev = x.device.index   # (None: resolved when the call is enqueued)
         L = lib()
-        L.fle_force_variant(self.variant)
-        L.fle_force_split(self.split)
-        try:
-            need = ctypes.c_size_t(0)
-            if self._groups is None:
-                _check(L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)))
-            else:
+        if table is not None and not grouped and self.variant == 0 and self.split == 0:   # a tuned plan, where the table has one
+            hit = table.lookup(p.dtype, M, N, K, epilogue)
+            if hit is not None:
+                self.variant, self.split = VARIANTS[hit[0]], int(hit[1])
+        need = ctypes.c_size_t(0)
+        if self._groups is None:   # plain problems: the plan choice travels with the call, the library keeps no state
+            self._choice = FlePlanChoice(self.variant, self.split)
+            _check(L.fle_workspace_size_with(ctypes.byref(p), ctypes.byref(self._choice), ctypes.byref(need)))
+        else:
+            L.fle_force_variant(self.variant)
+            L.fle_force_split(self.split)
+            try:
                 _check(L.fle_workspace_size_grouped(ctypes.byref(p), self._gref, ctypes.byref(need)))
-        finally:
-            L.fle_force_variant(0)
-            L.fle_force_split(0)
+            finally:
+                L.fle_force_variant(0)
+                L.fle_force_split(0)
         if workspace is None and need.value:
             workspace = torch.empty(need.value, dtype=torch.uint8, device=x.device)
         self.workspace = workspace
@@ -284,11 +297,13 @@ class Call:
         self._p.stream = _raw_stream(self._dev) if stream is None else stream.cuda_stream
         if self.variant == 0 and self.split == 0:
             status = L.fle_run(self._pref) if self._groups is None else L.fle_run_grouped(self._pref, self._gref)
-        else:
+        elif self._groups is None:
+            status = L.fle_run_with(self._pref, ctypes.byref(self._choice))
+        else:   # (grouped problems have no per-call form: the thread's test knobs, set back at once)
             L.fle_force_variant(self.variant)
             L.fle_force_split(self.split)
             try:
-                status = L.fle_run(self._pref) if self._groups is None else L.fle_run_grouped(self._pref, self._gref)
+                status = L.fle_run_grouped(self._pref, self._gref)
             finally:
                 L.fle_force_variant(0)
                 L.fle_force_split(0)
@@ -322,6 +337,45 @@ class Call:
         return buf.value.decode()
 
 
+class TileTable:
+    """Plans found by an offline tuning run (``python -m paper_2511_16964_amd.autotune``): for a class of problems
+    (dtype, whether the list holds a row reduction, M, N, K each rounded to the nearest power of two) the kernel
+    variant and split of K that measured fastest on the GPU the table was made on.  ``Call(..., table=t)`` uses
+    the entry of its problem's class if there is one and the library's own cost model otherwise."""
+
+    DEFAULT_PATH = os.path.join(_HERE, "tile_table.json")
+
+    def __init__(self, entries=None, meta=None):
+        self.entries, self.meta = dict(entries or {}), dict(meta or {})
+
+    @staticmethod
+    def bucket(v: int) -> int:
+        v = max(1, int(v))
+        b = v.bit_length() - 1
+        return b + 1 if v * v > (1 << (2 * b + 1)) else b      # round log2(v) to the nearest integer
+
+    @classmethod
+    def key(cls, dtype_code, M, N, K, epilogue) -> str:
+        row = int(any(e[0] in ("layernorm", "softmax", "logsumexp") for e in epilogue))
+        return "%d:%d:%d:%d:%d" % (dtype_code, row, cls.bucket(M), cls.bucket(N), cls.bucket(K))
+
+    def lookup(self, dtype_code, M, N, K, epilogue):
+        e = self.entries.get(self.key(dtype_code, M, N, K, epilogue))
+        return None if e is None else (e["variant"], e["split"])
+
+    @classmethod
+    def load(cls, path=None):
+        import json
+        d = json.load(open(path or cls.DEFAULT_PATH))
+        return cls(d.get("entries"), {k: v for k, v in d.items() if k != "entries"})
+
+    def save(self, path):
+        import json
+        with open(path, "w") as f:
+            json.dump(dict(self.meta, entries=self.entries), f, indent=1, sort_keys=True)
+            f.write("\n")
+
+
 def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, out=None, workspace=None, variant="auto"):
     """Grouped form: rows offsets[g] .. offsets[g+1]-1 of x go through w[g] (and b[g]), one launch.
 
@@ -334,18 +388,19 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, out=None, workspac
     return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, offsets=offsets).run()
 
 
-def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0):
+def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0, table=None):
     """out = epilogue(x @ w.T) in one fused library call.
 
     x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32, bfloat16 or float16).
     epilogue: ordered list of ("bias",) ("scale", a) ("relu",) ("gelu_erf",) ("gelu_tanh",)
     ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",)
     ("store", t[M,N]): t receives a copy of the values at that point of the list (before the row op only).
+    table: a ``TileTable`` of tuned plans (default: the library's cost model decides).
     Returns a tensor of x's dtype: [M,N], or [M] when the list ends in logsumexp.
     """
     if not x.is_cuda:
         raise RuntimeError("fused_linear_epilogue runs on the GPU only; there is no CPU path")
-    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, split=split).run()
+    return Call(x, w, b, epilogue, out=out, workspace=workspace, variant=variant, split=split, table=table).run()
 
 
 def _strides(t):

@@ -600,6 +600,43 @@ fle_status fle_run(const fle_problem *p) {
     return s;
 }
 
+// A plan choice is valid when it names a variant the force knob knows and a split in 0 .. 64.
+static fle_status check_choice(const fle_plan_choice *c) {
+    if (!c) return fail(FLE_ERR_NULL, "plan choice is NULL");
+    if (c->variant < V_AUTO || c->variant > V_THIN) return fail(FLE_ERR_OP, "plan choice: unknown variant %d", c->variant);
+    if (c->split < 0 || c->split > 64) return fail(FLE_ERR_OP, "plan choice: split %d outside 0..64", c->split);
+    return FLE_OK;
+}
+
+fle_status fle_workspace_size_with(const fle_problem *p, const fle_plan_choice *c, size_t *bytes_out) {
+    if (!bytes_out) return fail(FLE_ERR_NULL, "bytes_out is NULL");
+    fle_status s = check_choice(c);
+    if (s != FLE_OK) return s;
+    Plan plan;
+    s = make_plan(p, c->variant, c->split, &plan);
+    if (s != FLE_OK) return s;
+    *bytes_out = plan.ws_total;
+    g_plan = plan;
+    g_have_plan = true;
+    return FLE_OK;
+}
+
+fle_status fle_run_with(const fle_problem *p, const fle_plan_choice *c) {
+    fle_status s = check_choice(c);
+    if (s != FLE_OK) return s;
+    Plan plan;
+    s = make_plan(p, c->variant, c->split, &plan);
+    if (s != FLE_OK) return s;
+    if (p->M == 0) return FLE_OK;
+    s = check_workspace(p, plan);
+    if (s == FLE_OK) s = launch(p, plan);
+    if (s == FLE_OK) {
+        g_plan = plan;
+        g_have_plan = true;
+    }
+    return s;
+}
+
 fle_status fle_run_static(const fle_problem *p) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     fle_problem q = *p;
@@ -774,6 +811,6 @@ void fle_force_variant(int variant) { g_forced = variant; }
 
 void fle_force_split(int split) { g_split = split < 0 ? 0 : split; }
 
-int fle_version(void) { return 800; }  // 0.8.0: fle_run_static (0.7.0: store op; 0.6.0: perceptron chain; 0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
+int fle_version(void) { return 900; }  // 0.9.0: fp8 operands, two row reductions, per-call plan choice (0.8.0: fle_run_static; 0.7.0: store op; 0.6.0: perceptron chain; 0.5.0: attention; 0.4.0: thin kernels; 0.3.0: grouped problems)
 
 }  // extern "C"

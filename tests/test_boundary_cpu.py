@@ -671,3 +671,62 @@ def test_fp8_problems_validate_and_plan_on_the_tiled_kernels_only(L):
     finally:
         L.fle_force_split(0)
     assert validate(L, problem(dtype=4)) == E_OP
+
+
+def test_per_call_plan_choice_is_stateless_and_validated(L):
+    """fle_workspace_size_with / fle_run_with take the plan choice as an argument: the same plans as the thread's
+    knobs give, nothing left set afterwards, bad choices refused on the host."""
+    from paper_2511_16964_amd.binding import FlePlanChoice
+
+    def plan_with(p, variant, split):
+        need = ctypes.c_size_t(0)
+        c = FlePlanChoice(variant, split)
+        st = L.fle_workspace_size_with(ctypes.byref(p), ctypes.byref(c), ctypes.byref(need))
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return st, need.value, buf.value.decode()
+
+    def plan_auto(p):
+        need = ctypes.c_size_t(0)
+        assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return need.value, buf.value.decode()
+
+    p = problem(M=4096, N=4096, K=4096)
+    auto = plan_auto(p)
+    st, need, text = plan_with(p, binding.VARIANTS["tiled128"], 4)
+    assert st == OK and "tile=128x128" in text and "split_k=4" in text and need > 0
+    assert plan_auto(p) == auto                                   # nothing stays set
+    L.fle_force_variant(binding.VARIANTS["tiled128"]); L.fle_force_split(4)
+    try:
+        assert plan_auto(p) == (need, text)                       # the knobs reach the same plan
+        st2, need2, text2 = plan_with(p, binding.VARIANTS["tiled256"], 1)   # the argument wins over the knobs
+        assert st2 == OK and "tile=256x256" in text2 and "split_k=1 " in text2
+    finally:
+        L.fle_force_variant(0); L.fle_force_split(0)
+    assert plan_with(p, 0, 0)[1:] == auto                          # {0, 0} is the library's own choice
+    assert L.fle_workspace_size_with(ctypes.byref(p), None, ctypes.byref(ctypes.c_size_t(0))) == E_NULL
+    assert plan_with(p, 10, 0)[0] == E_OP and plan_with(p, -1, 0)[0] == E_OP
+    assert plan_with(p, 0, 65)[0] == E_OP and plan_with(p, 0, -2)[0] == E_OP
+    assert plan_with(problem(M=512, N=512, K=500), binding.VARIANTS["tiled256"], 1)[0] == E_UNSUP    # a plan the problem cannot take
+    assert L.fle_run_with(None, None) == E_NULL and L.fle_run_with(ctypes.byref(p), None) == E_NULL
+    p = problem(M=512, N=1024, K=256, ops=[op("layernorm", 1e-5)])                                  # needs a workspace: refused on the host
+    assert L.fle_run_with(ctypes.byref(p), ctypes.byref(FlePlanChoice(binding.VARIANTS["tiled128"], 1))) == E_WS
+
+
+def test_tile_table_lookup_and_round_trip(tmp_path):
+    T = binding.TileTable
+    assert [T.bucket(v) for v in (0, 1, 2, 3, 4, 5, 6, 11, 12, 4096, 5792, 5793, 8192)] == [0, 0, 1, 2, 2, 2, 3, 3, 4, 12, 12, 13, 13]
+    plain, row = [("bias",), ("relu",)], [("bias",), ("softmax",)]
+    t = T(meta={"device": "x"})
+    t.entries[T.key(binding.BF16, 4096, 4096, 4096, plain)] = {"variant": "tiled128", "split": 2, "us": 1.0, "auto_us": 2.0}
+    assert t.lookup(binding.BF16, 4000, 4500, 3000, plain) == ("tiled128", 2)
+    assert t.lookup(binding.BF16, 4096, 4096, 4096, row) is None           # row reductions are a class of their own
+    assert t.lookup(binding.F16, 4096, 4096, 4096, plain) is None and t.lookup(binding.BF16, 2048, 4096, 4096, plain) is None
+    t.save(tmp_path / "t.json")
+    u = T.load(tmp_path / "t.json")
+    assert u.entries == t.entries and u.meta["device"] == "x"
+    shipped = T.load()                                                       # the table in the package parses and names real plans
+    assert shipped.entries and all(e["variant"] in binding.VARIANTS and 0 <= e["split"] <= 64 for e in shipped.entries.values())
+    assert all(re.fullmatch(r"\d:[01]:\d+:\d+:\d+", k) for k in shipped.entries)
