@@ -22,8 +22,11 @@ namespace fle {
 // Epilogue.  One 32-row block of the wave's accumulators at a time is staged through LDS as
 // fp32 and read back row-contiguous: a lane then owns 4 (or 2 x 4) consecutive columns of one
 // row, 16 lanes cover a whole 64-column run, so bias / residual / output accesses are full
-// cache lines and a row reduction is a 16-lane DPP reduction.  The residual tile is copied
-// into LDS by the same direct loads, the first block before the main loop starts.
+// cache lines and a row reduction is a 16-lane DPP reduction.  (Stores straight from the
+// accumulators' layout, 16 rows x 32 bytes per instruction, skip the 3.3 us that the LDS trip
+// costs a 256 x 256 tile and were still slower: 97.7 against 96.3 us on 4096^3.)  The residual
+// tile is copied into LDS by the same direct loads, block by block, the first one behind the
+// first barrier of the main loop.
 // AUX: cache policy bits of the copy instructions (2 = non-temporal, for a panel that is read once).
 template <int ROWS, int AUX = 0>
 struct TileLoader {
@@ -82,6 +85,22 @@ __device__ __forceinline__ float row16_allreduce(float v) {
     FLE_ROR(8) FLE_ROR(4) FLE_ROR(2) FLE_ROR(1)
 #undef FLE_ROR
     return v;
+}
+
+// 4 packed 2-byte values as fp32.
+template <int DT>
+__device__ __forceinline__ f32x4 unpack4(u32x2 u) {
+    static_assert(DT == FLE_BF16 || DT == FLE_F16, "2-byte dtypes only");
+    if constexpr (DT == FLE_F16) {
+        return __builtin_convertvector(__builtin_bit_cast(f16x4, u), f32x4);
+    } else {
+        f32x4 r;
+        r[0] = __uint_as_float(u[0] << 16);
+        r[1] = __uint_as_float(u[0] & 0xffff0000u);
+        r[2] = __uint_as_float(u[1] << 16);
+        r[3] = __uint_as_float(u[1] & 0xffff0000u);
+        return r;
+    }
 }
 
 // acc += A B on v_mfma_f32_16x16x32_bf16 / _f16 with the accumulator tied to one place in the accumulation
@@ -265,7 +284,6 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
         for (int t = 0; t < NI; ++t)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(res_rsrc, (lds_void *)(dst + t * 1024), 16, base + uint32_t(t) * res_block_step, 0, 0, 2);  // read once: non-temporal
     };
-    if (res_idx >= 0 && wave_live) issue_residual(0, 0);
 
     TileLoader<BM> ldx_;
     TileLoader<BN, W_NT ? 2 : 0> ldw_;
@@ -359,6 +377,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
         ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+        if (res_idx >= 0 && wave_live) issue_residual(0, 0);  // (behind the first stage: the wait above does not include it)
         {
             const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
 #pragma unroll
@@ -474,6 +493,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
         ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+        if (res_idx >= 0 && wave_live) issue_residual(0, 0);  // (behind the first stage: the wait above does not include it)
         {
             const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
 #pragma unroll
@@ -594,6 +614,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
         ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+        if (res_idx >= 0 && wave_live) issue_residual(0, 0);  // (behind the first stage: the wait above does not include it)
         {
             const char *sW = smem + (kb & 1) * STAGE, *sX = sW + SW;
     #pragma unroll
@@ -677,21 +698,17 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     const int p_idx = int(n_wave / WN);
     const int64_t cols_left = N - n_wave;
     const float cnt = float(cols_left < WN ? cols_left : WN);
-    constexpr int NIT = 8;  // 4 rows per iteration
 
-#pragma unroll 1
-    for (int i = 0; i < TM; ++i) {
+    // One 32-row block.  FULL: all of this wave's rows and columns lie inside the matrix, and nothing in the block
+    // is masked: every store is issued, unconditionally, so their number is known (see the residual below).
+    auto block = [&](const int i, auto full_c) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_c)::value;
         const int64_t m_blk = m_wave + 32 * i;
-        if (m_blk >= M) break;
-        if (res_idx >= 0) {
-            wait_vmcnt<0>();  // residual block i is in LDS (and this wave's earlier stores are done)
-            if (i + 1 < TM && m_blk + 32 < M) issue_residual(i + 1, (i + 1) & 1);
-        }
         // accumulators of row block i -> LDS.  32x32 tiles: row (lane & 31), columns 32 j + 8 q + 4 h .. + 3;
         // 16x16 tiles (two tile rows per block): row 16 t + (lane & 15), columns 16 j + 4 (lane >> 4) .. + 3
         {
             char *wr = MF == 16 ? ep + (lane & 15) * EP_STRIDE + (lane >> 4) * 16 : ep + (lane & 31) * EP_STRIDE + (lane >> 5) * 16;
-            auto put = [&](auto ic) {
+            auto put = [&](auto ic) __attribute__((always_inline)) {
                 constexpr int I = decltype(ic)::value;
                 if constexpr (I < TM) {
                     if constexpr (MF == 16) {
@@ -706,6 +723,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                             for (int q = 0; q < 4; ++q)
                                 *reinterpret_cast<f32x4 *>(wr + (32 * j + 8 * q) * 4) = f32x4{acc[I][j][4 * q], acc[I][j][4 * q + 1], acc[I][j][4 * q + 2], acc[I][j][4 * q + 3]};
                     }
+                    asm volatile("; accumulator block %0" ::"n"(I));  // (keeps the four cases of the switch below apart: merged, they would index the accumulators at run time, which sends them to scratch memory)
                 }
             };
             switch (i) {
@@ -715,195 +733,228 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             default: put(std::integral_constant<int, 3>{}); break;
             }
         }
-        // read back row-contiguous: v[it][hc] = row 4 it + rsub, columns of run hc
-        f32x4 v[NIT][NH];
+        // The residual of this block, out of LDS into registers, then the copy of the next block's.  The copy of
+        // this block went out a block ago, in front of that block's stores; vector memory instructions complete in
+        // the order of issue, so waiting until no more than those stores are outstanding (8 NH of them, when
+        // nothing was masked) is waiting for the copy, and the stores stay in flight.  (Waiting for everything
+        // cost 7.8 of the epilogue's 16.6 us on the 4096^3 chain: a round trip to memory in every block.)
+        u32x2 rv[F32 ? 1 : 8][F32 ? 1 : NH];
+        if constexpr (!F32) {
+            if (res_idx >= 0) {
+                if (FULL && a.dst) wait_vmcnt<8 * NH>();
+                else wait_vmcnt<0>();
+                const char *rb = smem + ((i & 1) ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
 #pragma unroll
-        for (int it = 0; it < NIT; ++it)
+                for (int it = 0; it < 8; ++it)
 #pragma unroll
-            for (int hc = 0; hc < NH; ++hc) v[it][hc] = *reinterpret_cast<const f32x4 *>(ep + (4 * it + rsub) * EP_STRIDE + hc * 256 + cl * 16);
+                    for (int hc = 0; hc < NH; ++hc) rv[it][hc] = *reinterpret_cast<const u32x2 *>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8);
+                if (i + 1 < TM && (FULL || m_blk + 32 < M)) issue_residual(i + 1, (i + 1) & 1);
+            }
+        }
 
-        for (int o = 0; o < a.epi.n_pre; ++o) {
-            const DevOp op = a.epi.pre[o];
-            switch (op.kind) {
-            case FLE_BIAS:
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc) v[it][hc] += bias_v[hc];
-                break;
-            case FLE_SCALE:
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc) v[it][hc] *= op.alpha;
-                break;
-            case FLE_RELU:
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[it][hc][e] = relu_f(v[it][hc][e]);
-                break;
-            case FLE_GELU_ERF:
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_erf_f(v[it][hc][e]);
-                break;
-            case FLE_GELU_TANH:
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_tanh_f(v[it][hc][e]);
-                break;
-            case FLE_RESIDUAL:
-                if (o == res_idx) {  // staged in LDS: [32 rows][WN] bf16
-                    const char *rb = smem + ((i & 1) ? RES1_OFF : RES0_OFF) + wave * RES_WAVE;
-#pragma unroll
+        // The two 16-row halves of the block one after the other (half the values in registers at a time).
+        auto half_pass = [&](auto hf_c) __attribute__((always_inline)) {
+            constexpr int HF = decltype(hf_c)::value;
+            constexpr int NIT = 4;  // 4 rows per iteration
+            // read back row-contiguous: v[it][hc] = row 16 HF + 4 it + rsub, columns of run hc
+            f32x4 v[NIT][NH];
+    #pragma unroll
+            for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                for (int hc = 0; hc < NH; ++hc) v[it][hc] = *reinterpret_cast<const f32x4 *>(ep + (16 * HF + 4 * it + rsub) * EP_STRIDE + hc * 256 + cl * 16);
+            for (int o = 0; o < a.epi.n_pre; ++o) {
+                const DevOp op = a.epi.pre[o];
+                switch (op.kind) {
+                case FLE_BIAS:
+    #pragma unroll
                     for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += ld4<DTE>(rb + (4 * it + rsub) * (WN * 2) + hc * 128 + cl * 8, 0);
-                } else {  // a further residual operand: straight from memory, clamped to stay in bounds
-#pragma unroll
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] += bias_v[hc];
+                    break;
+                case FLE_SCALE:
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] *= op.alpha;
+                    break;
+                case FLE_RELU:
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+    #pragma unroll
+                            for (int e = 0; e < 4; ++e) v[it][hc][e] = relu_f(v[it][hc][e]);
+                    break;
+                case FLE_GELU_ERF:
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+    #pragma unroll
+                            for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_erf_f(v[it][hc][e]);
+                    break;
+                case FLE_GELU_TANH:
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+    #pragma unroll
+                            for (int e = 0; e < 4; ++e) v[it][hc][e] = gelu_tanh_f(v[it][hc][e]);
+                    break;
+                case FLE_RESIDUAL:
+                    if (o == res_idx) {  // staged through LDS
+                        if constexpr (!F32) {
+    #pragma unroll
+                            for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                                for (int hc = 0; hc < NH; ++hc) v[it][hc] += unpack4<DTE>(rv[4 * HF + it][hc]);
+                        }
+                    } else {  // a further residual operand: straight from memory, clamped to stay in bounds
+    #pragma unroll
+                        for (int it = 0; it < NIT; ++it) {
+                            const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
+                            const int64_t mc = m < M ? m : M - 1;
+    #pragma unroll
+                            for (int hc = 0; hc < NH; ++hc) {
+                                if constexpr (EDGE) {
+    #pragma unroll
+                                    for (int e = 0; e < 4; ++e)
+                                        if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DTE);
+                                } else {
+                                    v[it][hc] += ld4<DTE>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                                }
+                            }
+                        }
+                    }
+                    break;
+                case FLE_STORE:  // a copy of the values as they stand, rounded to the dtype; rows and columns inside the matrix only
+    #pragma unroll
                     for (int it = 0; it < NIT; ++it) {
-                        const int64_t m = m_blk + 4 * it + rsub;
-                        const int64_t mc = m < M ? m : M - 1;
-#pragma unroll
-                        for (int hc = 0; hc < NH; ++hc) {
-                            if constexpr (EDGE) {
-#pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) v[it][hc][e] += ld_elem(op.p0, mc * op.ld + n_col[hc] + e, DTE);
-                            } else {
-                                v[it][hc] += ld4<DTE>(op.p0, mc * op.ld + (n_ok[hc] ? n_col[hc] : N - 4));
+                        const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+                            if (FULL || (m < M && n_ok[hc])) {
+                                if constexpr (EDGE) {
+    #pragma unroll
+                                    for (int e = 0; e < 4; ++e)
+                                        if (n_col[hc] + e < N) st_elem(const_cast<void *>(op.p0), m * op.ld + n_col[hc] + e, DTE, v[it][hc][e]);
+                                } else if constexpr (F32) {
+                                    *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = v[it][hc];
+                                } else {
+                                    constexpr int DT2 = F32 ? FLE_BF16 : DTE;
+                                    *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = pack4<DT2>(v[it][hc]);
+                                }
                             }
-                        }
                     }
+                    break;
+                default: break;
                 }
-                break;
-            case FLE_STORE:  // a copy of the values as they stand, rounded to the dtype; rows and columns inside the matrix only
-#pragma unroll
+            }
+
+            // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
+            float part_max[NIT];  // softmax: the partial's maximum per row of this block
+            if (a.epi.row_kind >= 0) {
+                const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+    #pragma unroll
                 for (int it = 0; it < NIT; ++it) {
-                    const int64_t m = m_blk + 4 * it + rsub;
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-                        if (m < M && n_ok[hc]) {
-                            if constexpr (EDGE) {
-#pragma unroll
-                                for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) st_elem(const_cast<void *>(op.p0), m * op.ld + n_col[hc] + e, DTE, v[it][hc][e]);
-                            } else if constexpr (F32) {
-                                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = v[it][hc];
-                            } else {
-                                constexpr int DT2 = F32 ? FLE_BF16 : DTE;
-                                *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(const_cast<void *>(op.p0)) + m * op.ld + n_col[hc]) = pack4<DT2>(v[it][hc]);
+                    const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
+                    float s0, s1;
+                    if (ln) {
+                        float sum = 0.0f;
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+                            if (n_ok[hc]) {
+                                if constexpr (EDGE) {
+    #pragma unroll
+                                    for (int e = 0; e < 4; ++e)
+                                        if (n_col[hc] + e < N) sum += v[it][hc][e];
+                                } else {
+                                    sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                                }
                             }
-                        }
-                }
-                break;
-            default: break;
-            }
-        }
-
-        // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
-        float part_max[NIT];  // softmax: the partial's maximum per row of this block
-        if (a.epi.row_kind >= 0) {
-            const bool ln = a.epi.row_kind == FLE_LAYERNORM;
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int64_t m = m_blk + 4 * it + rsub;
-                float s0, s1;
-                if (ln) {
-                    float sum = 0.0f;
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc]) {
-                            if constexpr (EDGE) {
-#pragma unroll
+                        sum = row16_allreduce<false>(sum);
+                        const float mean = sum / cnt;
+                        float m2 = 0.0f;
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+                            if (n_ok[hc])
+    #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) sum += v[it][hc][e];
-                            } else {
-                                sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                                    if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
+                        m2 = row16_allreduce<false>(m2);
+                        s0 = mean;
+                        s1 = m2;
+                    } else {
+                        float mx = -INFINITY;
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+                            if (n_ok[hc]) {
+                                if constexpr (EDGE) {
+    #pragma unroll
+                                    for (int e = 0; e < 4; ++e)
+                                        if (n_col[hc] + e < N) mx = fmaxf(mx, v[it][hc][e]);
+                                } else {
+                                    mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
+                                }
                             }
-                        }
-                    sum = row16_allreduce<false>(sum);
-                    const float mean = sum / cnt;
-                    float m2 = 0.0f;
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc])
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
-                    m2 = row16_allreduce<false>(m2);
-                    s0 = mean;
-                    s1 = m2;
-                } else {
-                    float mx = -INFINITY;
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc]) {
-                            if constexpr (EDGE) {
-#pragma unroll
+                        mx = row16_allreduce<true>(mx);
+                        float se = 0.0f;
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc)
+                            if (n_ok[hc])
+    #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (n_col[hc] + e < N) mx = fmaxf(mx, v[it][hc][e]);
-                            } else {
-                                mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
-                            }
-                        }
-                    mx = row16_allreduce<true>(mx);
-                    float se = 0.0f;
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc)
-                        if (n_ok[hc])
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - mx);
-                    se = row16_allreduce<false>(se);
-                    s0 = mx;
-                    s1 = se;
-                }
-                part_max[it] = s0;
-                if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
-            }
-            if (a.dst_rel) {
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-#pragma unroll
-                    for (int hc = 0; hc < NH; ++hc) v[it][hc] -= part_max[it];
-            }
-        }
-
-        // store: final values (no row op) or staged values for the finalize pass
-        if (a.dst) {
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int64_t m = m_blk + 4 * it + rsub;
-#pragma unroll
-                for (int hc = 0; hc < NH; ++hc)
-                    if (m < M && n_ok[hc]) {
-                        if constexpr (EDGE) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DTE, v[it][hc][e]);
-                        } else if (F32 || a.dst_f32) {
-                            f32x4 *q = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]);
-                            if (stream_out) __builtin_nontemporal_store(v[it][hc], q);
-                            else *q = v[it][hc];
-                        } else {
-                            u32x2 *q = reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n_col[hc]);
-                            constexpr int DT2 = F32 ? FLE_BF16 : DTE;  // (this branch is never taken for fp32 problems)
-                            if (stream_out) __builtin_nontemporal_store(pack4<DT2>(v[it][hc]), q);
-                            else *q = pack4<DT2>(v[it][hc]);
-                        }
+                                    if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - mx);
+                        se = row16_allreduce<false>(se);
+                        s0 = mx;
+                        s1 = se;
                     }
+                    part_max[it] = s0;
+                    if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
+                }
+                if (a.dst_rel) {
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it)
+    #pragma unroll
+                        for (int hc = 0; hc < NH; ++hc) v[it][hc] -= part_max[it];
+                }
             }
-        }
+
+            // store: final values (no row op) or staged values for the finalize pass
+            if (a.dst) {
+    #pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
+    #pragma unroll
+                    for (int hc = 0; hc < NH; ++hc)
+                        if (FULL || (m < M && n_ok[hc])) {
+                            if constexpr (EDGE) {
+    #pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (n_col[hc] + e < N) st_elem(dst, m * a.ldd + n_col[hc] + e, a.dst_f32 ? FLE_F32 : DTE, v[it][hc][e]);
+                            } else if (F32 || a.dst_f32) {
+                                f32x4 *q = reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(dst) + m * a.ldd + n_col[hc]);
+                                if (stream_out) __builtin_nontemporal_store(v[it][hc], q);
+                                else *q = v[it][hc];
+                            } else {
+                                u32x2 *q = reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(dst) + m * a.ldd + n_col[hc]);
+                                constexpr int DT2 = F32 ? FLE_BF16 : DTE;  // (this branch is never taken for fp32 problems)
+                                if (stream_out) __builtin_nontemporal_store(pack4<DT2>(v[it][hc]), q);
+                                else *q = pack4<DT2>(v[it][hc]);
+                            }
+                        }
+                }
+            }
+        };
+        half_pass(I0{});
+        half_pass(I1{});
+    };
+    if (!EDGE && m_wave + WM <= M && n_wave + WN <= N) {
+#pragma unroll 1
+        for (int i = 0; i < TM; ++i) block(i, std::true_type{});
+    } else {
+#pragma unroll 1
+        for (int i = 0; i < TM && m_wave + 32 * i < M; ++i) block(i, std::false_type{});
     }
 }
 
