@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused linear + epilogue hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5|f2|g1|g2|m1|m2|m3|a1|a2|l1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5|f2|f3|g1|g2|m1|m2|m3|a1|a2|l1]
 
 A step is one pass of the whole path (every kernel the call enqueues) over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s
@@ -187,13 +187,26 @@ def time_cold(torch, fn, iters, flush, warmups=0):
     return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
 
 
+def oracle_operands(prob, inputs, rows=None):
+    """(x of the listed rows, W, epilogue) as the oracle takes them: stored values upcast exactly; block-scaled
+    operands as the values they stand for, with the scale entry taken off the list."""
+    import oracle
+    x64, w64, ep = inputs.to_f64(prob.x if rows is None else prob.x[rows]), inputs.to_f64(prob.w), prob.epilogue
+    if ep and ep[0][0] == "mxscale":
+        sx = ep[0][1] if rows is None else ep[0][1][rows]
+        x64, w64, ep = oracle.mx_dequantize(x64, sx.numpy()), oracle.mx_dequantize(w64, ep[0][2].numpy()), ep[1:]
+    return x64, w64, ep
+
+
 def cpu_baseline(prob, inputs, flops_per_row, budget_s=12.0):
     """Time the oracle, as it stands, on a bounded sample of rows of the same workload."""
     import oracle
-    w64, b64 = inputs.to_f64(prob.w), inputs.to_f64(prob.b)
+    _, w64, ep = oracle_operands(prob, inputs, [0])
+    b64 = inputs.to_f64(prob.b)
     def run(rows):
+        x64 = oracle_operands(prob, inputs, rows)[0]
         t0 = time.perf_counter()
-        oracle.fused_linear_epilogue(inputs.to_f64(prob.x[rows]), w64, b64, inputs.epilogue_f64(prob.epilogue, rows))
+        oracle.fused_linear_epilogue(x64, w64, b64, inputs.epilogue_f64(ep, rows))
         return time.perf_counter() - t0
     probe = list(range(min(prob.M, 16)))
     t = run(probe)
@@ -319,7 +332,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "f2", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "f2", "f3", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -483,14 +496,21 @@ def main():
         probs = [prob]
         flops = prob.flops
         f8 = prob.dtype == torch.float8_e4m3fn
-        desc = "%s: %s, %s, M=%d N=%d K=%d" % (args.workload, "+".join(["linear"] + [e[0] for e in prob.epilogue]),
+        mxs = bool(ep) and ep[0][0] == "mxscale"
+        desc = "%s: %s, %s, M=%d N=%d K=%d" % (args.workload, "+".join(["linear"] + [e[0] for e in prob.epilogue if e[0] != "mxscale"]),
+                                              "block-scaled fp8 (MXFP8: e4m3, one E8M0 scale per 32 k) x and W, bf16 elsewhere" if mxs else
                                               "fp8 (e4m3) x and W, bf16 elsewhere" if f8 else "bf16" if prob.dtype == torch.bfloat16 else "fp32", prob.M, prob.N, prob.K)
         # (fp8: the comparator is the bf16 composition of the same layer on the upcast operands, converted outside the timed region)
-        eager = eager_fn(torch, F, xg.to(torch.bfloat16), wg.to(torch.bfloat16), bg, ep) if f8 else eager_fn(torch, F, xg, wg, bg, ep)
+        if mxs:
+            deq = lambda t, sc: (t.float() * torch.exp2(sc.float() - 127.0).repeat_interleave(32, dim=1)).to(torch.bfloat16)
+            eager = eager_fn(torch, F, deq(xg, ep[0][1]), deq(wg, ep[0][2]), bg, ep[1:])
+        else:
+            eager = eager_fn(torch, F, xg.to(torch.bfloat16), wg.to(torch.bfloat16), bg, ep) if f8 else eager_fn(torch, F, xg, wg, bg, ep)
         es = 2 if prob.dtype in (torch.bfloat16, torch.float8_e4m3fn) else 4     # b, residual, gamma, beta, out
         xs = 1 if f8 else es                                                       # x, W
         alg_bytes = xs * (prob.M * prob.K + prob.N * prob.K) + es * (prob.M * prob.N + (prob.N if bg is not None else 0)
-                          + sum(prob.M * prob.N for e in ep if e[0] == "residual") + sum(2 * prob.N for e in ep if e[0] == "layernorm"))
+                          + sum(prob.M * prob.N for e in ep if e[0] == "residual") + sum(2 * prob.N for e in ep if e[0] == "layernorm")) \
+                    + ((prob.M + prob.N) * (prob.K // 32) if mxs else 0)
 
     def step():
         for c in calls:
@@ -539,8 +559,8 @@ def main():
             ref = np.concatenate([oracle.fused_linear_epilogue(inputs.to_f64(gp.x[m:m + 1]), inputs.to_f64(gp.w[g]), inputs.to_f64(gp.b[g]),
                                                                inputs.epilogue_f64(gp.epilogue, [m])) for m, g in zip(rows, owner)])
         else:
-            ref = oracle.fused_linear_epilogue(inputs.to_f64(prob0.x[rows]), inputs.to_f64(prob0.w), inputs.to_f64(prob0.b),
-                                               inputs.epilogue_f64(prob0.epilogue, rows))
+            x64, w64, ep64 = oracle_operands(prob0, inputs, rows)
+            ref = oracle.fused_linear_epilogue(x64, w64, inputs.to_f64(prob0.b), inputs.epilogue_f64(ep64, rows))
         got = calls[0].out[rows].cpu().to(torch.float64).numpy()
     tol = 2e-2 if prob0.dtype in (torch.bfloat16, torch.float8_e4m3fn) else 1e-4
     if args.workload == "a1":

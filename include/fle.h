@@ -78,6 +78,15 @@ typedef enum {
                           p0 = gamma or NULL (1), p1 = beta or NULL (0), alpha = eps        */
     FLE_SOFTMAX = 7,   /* over n: exp(v - max) / sum exp(v - max)                           */
     FLE_LOGSUMEXP = 8, /* over n: max + log sum exp(v - max); out becomes [M]; last op only */
+    FLE_MXSCALE = 10,  /* not an epilogue step: says that the FLE_F8E4M3 operands are block-scaled (OCP microscaling,
+                          MXFP8): every 32 consecutive k of a row of x and of W share a power-of-two scale, stored
+                          as one byte e (E8M0: the scale is 2^(e - 127); e = 255 marks NaN).  p0 = scales of x,
+                          device [M][K/32] bytes, p1 = scales of W, device [N][K/32] bytes, rows contiguous, both
+                          4-byte aligned.  out = epilogue( (x * scale_x) (W * scale_W)^T ), with the products formed
+                          and summed on the matrix instruction's block-scaled form.  First entry of the list only;
+                          K a multiple of 128; plain problems only (fle_run*, not the grouped form).  This is the
+                          finer-grained of the reduced-precision formats the paper's tolerance admits (Section 5.3,
+                          Appendix A); per-tensor scales need no such entry (FLE_SCALE).                       */
     FLE_STORE = 9      /* t[m,n] = v, rounded to the dtype; v itself goes on unchanged (p0 = t, ld).
                           Allowed before the row op (or anywhere in a list without one).  It is how
                           one call hands over both a value and its normalisation, e.g. bias, residual,
@@ -91,8 +100,9 @@ typedef struct {
     int32_t kind;   /* fle_op_kind */
     float alpha;    /* SCALE: factor.  LAYERNORM: eps.  Otherwise ignored.                 */
     const void *p0; /* RESIDUAL: r[M,N] (device).  LAYERNORM: gamma[N] (device) or NULL.
-                       STORE: t[M,N] (device, written; must not overlap any other operand) */
-    const void *p1; /* LAYERNORM: beta[N] (device) or NULL.                                */
+                       STORE: t[M,N] (device, written; must not overlap any other operand).
+                       MXSCALE: block scales of x (device)                                  */
+    const void *p1; /* LAYERNORM: beta[N] (device) or NULL.  MXSCALE: block scales of W     */
     int64_t ld;     /* RESIDUAL / STORE: row stride of r / t in elements (>= N).           */
 } fle_op;
 
@@ -117,7 +127,7 @@ typedef struct {
 } fle_problem;
 
 /*
- * Accepted epilogue grammar:   elementwise*  [ rowop  elementwise*  [ rowop  elementwise* ] ]
+ * Accepted epilogue grammar:   [ MXSCALE ]  elementwise*  [ rowop  elementwise*  [ rowop  elementwise* ] ]
  * with rowop = LAYERNORM | SOFTMAX | LOGSUMEXP and elementwise = BIAS | SCALE | RELU | GELU_ERF |
  * GELU_TANH | RESIDUAL | STORE (STORE only before the first row op); nothing follows LOGSUMEXP.  A
  * list with two row ops (e.g. LAYERNORM, SOFTMAX: a normalised layer's class probabilities) costs

@@ -146,6 +146,20 @@ def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
     return out
 
 
+def mx_dequantize(elems, scales) -> np.ndarray:
+    """The values a block-scaled operand stands for (OCP Microscaling Formats specification, MXFP8): elems [R, K]
+    are the stored elements (already upcast exactly), scales [R, K/32] one byte per block of 32 consecutive
+    elements of a row, E8M0: the block's values are multiplied by 2^(byte - 127); byte 255 makes them NaN.
+    The product is exact in float64 (an 8-bit element times a power of two within double's exponent range)."""
+    elems = _f64(elems)
+    sc = np.asarray(scales)
+    if sc.dtype != np.uint8 or elems.ndim != 2 or sc.shape != (elems.shape[0], elems.shape[1] // 32) or elems.shape[1] % 32:
+        raise ValueError("need elems [R, K], K a multiple of 32, and uint8 scales [R, K/32]")
+    factor = np.ldexp(1.0, sc.astype(np.int64) - 127)
+    factor[sc == 255] = np.nan
+    return elems * np.repeat(factor, 32, axis=1)
+
+
 def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, n_threads: int = 0) -> np.ndarray:
     """float64 gold result of the grouped form: the loop over groups written out.
 

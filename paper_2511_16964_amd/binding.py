@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libfle.so")
 
 F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
-            "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9}
+            "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9, "mxscale": 10}
 MAX_OPS = 8
 STATIC_SCRATCH_BYTES = 16 << 20
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
@@ -229,6 +229,13 @@ class Call:
                 tensors.append(t)
                 ops[i].p0 = t.data_ptr()
                 ops[i].ld = t.stride(0) if M > 1 else max(N, t.stride(0))
+            elif e[0] == "mxscale":   # block scales of fp8 operands: uint8 [M, K/32] and [N, K/32]
+                sx, sw = e[1], e[2]
+                for name, t, rows in (("x", sx, M), ("w", sw, N)):
+                    if t.dtype != torch.uint8 or tuple(t.shape) != (rows, K // 32) or not t.is_contiguous() or t.device != x.device:
+                        raise ValueError("block scales of %s must be a contiguous uint8 tensor [%d, K/32 = %d] on x's device" % (name, rows, K // 32))
+                self._scales = (sx, sw)   # (kept alive; uint8, so outside the dtype check below)
+                ops[i].p0, ops[i].p1 = sx.data_ptr(), sw.data_ptr()
             elif e[0] == "layernorm":
                 g, be, eps = e[1], e[2], e[3]
                 for name, t in (("gamma", g), ("beta", be)):

@@ -34,6 +34,7 @@ struct GemmArgs {
     float *partials;  // [M][np][2], or nullptr without a row op
     int32_t tiles_m, tiles_n;
     int64_t split_stride;  // split K (gridDim.y > 1): workgroup row y owns a K range and writes dst + y * split_stride bytes
+    const void *x_scale, *w_scale;  // block-scaled fp8 operands: one E8M0 byte per 32 consecutive k, [M][K/32] and [N][K/32]
     DevEpilogue epi;
 };
 

@@ -229,9 +229,12 @@ __device__ __forceinline__ bool grouped_tile(const GemmArgs &a, const GroupArgs 
 // matrix instructions for the same fragment reads and copies, and half the accumulator traffic per flop).
 // C1: (MF = 16) how many of a K step's copy instructions go out in the slice right behind the barrier; the
 // rest follow in the next slice.
-template <int BM, int BN, int DT, bool EDGE, bool W_NT = false, int MF = 32, int C1 = -1>
+// MX: (fp8 operands) every 32 consecutive k of a row of x and of W share a power-of-two scale, one E8M0 byte each:
+// the OCP microscaling format, multiplied on the matrix instruction's scaled form.
+template <int BM, int BN, int DT, bool EDGE, bool W_NT = false, int MF = 32, int C1 = -1, bool MX = false>
 __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef &t) {
     constexpr bool F32 = DT == FLE_F32, F8 = DT == FLE_F8E4M3;
+    static_assert(!MX || F8, "block scales exist for fp8 operands");
     static_assert(MF == 32 || (MF == 16 && !F32 && !F8), "16x16 tiles exist for the 2-byte dtypes");
     constexpr int DTE = F8 ? FLE_BF16 : DT;     // dtype of b, the residual and store operands and out (fp8 problems: bf16)
     constexpr int ES = F32 ? 4 : F8 ? 1 : 2;    // bytes per operand element; a staged row is 128 bytes = 128 fp8, 64 bf16 or 32 fp32
@@ -308,10 +311,9 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     if constexpr (F8) {
         // ---- main loop on 32x32x64 tiles (fp8 operands).  A K step (128 bytes of every row) is two k slices of 64;
         // a fragment (32 rows x 64 k) is 32 bytes per lane, read as two 16-byte pieces: row (lane & 31), chunks
-        // 4 s + hh and 4 s + 2 + hh of slice s, hh = lane >> 5 (the instruction takes the 32 bytes of a lane as 32
-        // consecutive k values of its half of the slice; which chunks those are is free as long as both operands
-        // agree, and with this choice lanes l and l + 32, which the LDS serves in the same cycle, read chunks one
-        // apart: no bank conflicts under the row swizzle).  16 matrix instructions of 64 cycles per slice move the
+        // 4 s + hh and 4 s + 2 + hh of slice s, hh = lane >> 5, which is where the instruction expects them (16 k
+        // values of the slice's first half, then 16 of its second); lanes l and l + 32, which the LDS serves in
+        // the same cycle, then read chunks one apart: no bank conflicts under the row swizzle.  16 matrix instructions of 64 cycles per slice move the
         // same bytes through LDS as the 2-byte loop's 64 of 16 cycles, for twice the products.  The schedule is
         // that loop's: fragments one slice ahead, wait and barrier between the two slices of a step, the copies
         // of the step after next right behind the barrier.
@@ -325,6 +327,50 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 #pragma unroll
                 for (int e = 0; e < 2; ++e) rd_off[sl][e] = uint32_t(r * 128 + (((4 * sl + 2 * e + hh) ^ g) << 4));
         }
+        // Block scales.  With the pieces as above, the first 16 bytes of a lane lie in the slice's first block of 32
+        // k values and the second 16 bytes in its second block, for both lane halves, and the instruction takes the
+        // scale of a row's first block from that row's lane in the lower half and the scale of its second block
+        // from its lane in the upper half (established with single non-unit scales and single non-zero k
+        // positions).  The scale bytes of a K step (4 blocks) are one dword per row, read from memory a K step
+        // ahead; lanes of the upper half shift theirs down a byte, and the instruction picks byte 2 s: block
+        // 2 s + hh.  Rows beyond the tile's valid rows read zero: 2^-127 times operand bytes that are zero as well.
+        [[maybe_unused]] uint32_t sw_cur[TN], sx_cur[TM], sw_nxt[TN], sx_nxt[TM], sw_nx2[TN], sx_nx2[TM];
+        [[maybe_unused]] __amdgpu_buffer_rsrc_t sw_rsrc = __builtin_amdgcn_make_buffer_rsrc(nullptr, 0, 0, 0x00020000), sx_rsrc = sw_rsrc;
+        [[maybe_unused]] uint32_t sc_row = 0, sc_shift = 0;
+        if constexpr (MX) {
+            const int64_t ks = a.K / 32;  // bytes per row of scales
+            const int64_t rows_w = (N - n0) < BN ? (N - n0) : BN, rows_x = (M - m0) < BM ? (M - m0) : BM;
+            sw_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.w_scale) + n0 * ks), 0, uint32_t((rows_w > 0 ? rows_w : 0) * ks), 0x00020000);
+            sx_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(reinterpret_cast<const char *>(a.x_scale) + m0 * ks), 0, uint32_t((rows_x > 0 ? rows_x : 0) * ks), 0x00020000);
+            sc_row = uint32_t(lane & 31) * uint32_t(ks);
+            sc_shift = uint32_t(lane >> 5) * 8;
+        }
+        // The scales of step kt + 2 are requested in the middle of step kt, behind the copies of its first slice, and
+        // the wait in front of the barrier leaves exactly these TN + TM loads in flight (loads complete in order):
+        // they have a step and a half to arrive, and no wait ever includes a request that has only just gone out.
+        auto load_scales = [&](int kt, uint32_t (&dw)[TN], uint32_t (&dx)[TM]) {
+            if constexpr (MX) {
+                const uint32_t ks = uint32_t(a.K / 32);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) dw[j] = __builtin_amdgcn_raw_buffer_load_b32(sw_rsrc, int(sc_row + uint32_t(wn * WN + j * 32) * ks), kt * 4, 0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) dx[i] = __builtin_amdgcn_raw_buffer_load_b32(sx_rsrc, int(sc_row + uint32_t(wm * WM + i * 32) * ks), kt * 4, 0);
+            }
+        };
+        auto take_scales = [&]() {  // this step's scales, and the next step's move up
+            if constexpr (MX) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    sw_cur[j] = sw_nxt[j] >> sc_shift;
+                    sw_nxt[j] = sw_nx2[j];
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    sx_cur[i] = sx_nxt[i] >> sc_shift;
+                    sx_nxt[i] = sx_nx2[i];
+                }
+            }
+        };
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -366,13 +412,27 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 const Frag &fa = fw[SL][q % TN], &fb = fx[SL][q / TN];
-                acc[q / TN][q % TN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                    __builtin_bit_cast(i32x8, __builtin_shufflevector(fa.lo, fa.hi, 0, 1, 2, 3, 4, 5, 6, 7)),
-                    __builtin_bit_cast(i32x8, __builtin_shufflevector(fb.lo, fb.hi, 0, 1, 2, 3, 4, 5, 6, 7)), acc[q / TN][q % TN], 0, 0, 0, 0, 0, 0);
+                if constexpr (MX)
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        __builtin_bit_cast(i32x8, __builtin_shufflevector(fa.lo, fa.hi, 0, 1, 2, 3, 4, 5, 6, 7)),
+                        __builtin_bit_cast(i32x8, __builtin_shufflevector(fb.lo, fb.hi, 0, 1, 2, 3, 4, 5, 6, 7)), acc[q / TN][q % TN], 0, 0,
+                        2 * SL, int(sw_cur[q % TN]), 2 * SL, int(sx_cur[q / TN]));
+                else
+                    acc[q / TN][q % TN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        __builtin_bit_cast(i32x8, __builtin_shufflevector(fa.lo, fa.hi, 0, 1, 2, 3, 4, 5, 6, 7)),
+                        __builtin_bit_cast(i32x8, __builtin_shufflevector(fb.lo, fb.hi, 0, 1, 2, 3, 4, 5, 6, 7)), acc[q / TN][q % TN], 0, 0, 0, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         using CNT1 = std::integral_constant<int, NC1>;
+        if constexpr (MX) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) sw_nx2[j] = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) sx_nx2[i] = 0;
+        }
+        load_scales(kb, sw_nxt, sx_nxt);
+        if (kb + 1 < ke) load_scales(kb + 1, sw_nx2, sx_nx2);
         ldw_.issue(smem + (kb & 1) * STAGE, uint32_t(kb) * 128, valid_of(kb));
         ldx_.issue(smem + (kb & 1) * STAGE + SW, uint32_t(kb) * 128, valid_of(kb));
         wait_vmcnt<0>();
@@ -404,9 +464,11 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
             constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
             char *cW = smem + (kt & 1) * STAGE, *cX = cW + SW;
             char *nW = smem + ((kt + 1) & 1) * STAGE, *nX = nW + SW;
+            take_scales();
             slice(I0{}, std::true_type{}, CNT1{}, std::integral_constant<int, MORE ? NCP - NC1 : 0>{}, full_c, cW, cX, 1, nW, nX, uint32_t(kt + 1) * 128, valid_of(kt + 1));
+            if constexpr (MX && MORE2) load_scales(kt + 2, sw_nx2, sx_nx2);
             if constexpr (MORE) {
-                wait_vmcnt<0>();
+                wait_vmcnt<(MX && MORE2) ? TN + TM : 0>();
                 __builtin_amdgcn_s_waitcnt(0xC07F);
                 __builtin_amdgcn_s_barrier();
             }
@@ -961,11 +1023,11 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 // 256 x 256: one workgroup per CU (160 KB of LDS, 512 registers per lane).  DT: fle_dtype of the operands.
 // fp32 operands run on the same tiles: a K step is 32 elements and each fragment pair feeds four
 // v_mfma_f32_32x32x2_f32 (64 cycles each), so the loop is bound by the matrix pipe with room to spare.
-template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1>
-__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<256>(a)); }
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1, bool MX = false>
+__global__ __launch_bounds__(256) void gemm_tiled_256(const GemmArgs a) { gemm_tiled_body<256, 256, DT, EDGE, false, MF, C1, MX>(a, whole_matrix_tile<256>(a)); }
 // 128 x 128: two workgroups per CU (80 KB of LDS each), so at most 256 registers per lane.
-template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1>
-__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE, false, MF, C1>(a, whole_matrix_tile<128>(a)); }
+template <int DT, bool EDGE, int MF = (DT == FLE_F32 || DT == FLE_F8E4M3 ? 32 : 16), int C1 = -1, bool MX = false>
+__global__ __launch_bounds__(256, 2) void gemm_tiled_128(const GemmArgs a) { gemm_tiled_body<128, 128, DT, EDGE, false, MF, C1, MX>(a, whole_matrix_tile<128>(a)); }
 
 // Grouped forms: the same tiles, with the tile -> rows mapping taken from the group offsets.
 template <int DT, bool EDGE>

@@ -78,7 +78,19 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     const size_t xs = f8 ? 1 : es;         // bytes per element of x and W
     for (int i = 0; i < p->n_ops; ++i) {
         const fle_op &op = p->ops[i];
-        if (op.kind < FLE_BIAS || op.kind > FLE_STORE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (op.kind < FLE_BIAS || op.kind > FLE_MXSCALE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (op.kind == FLE_MXSCALE) {  // not an epilogue op: says how x and W are to be read
+            if (i != 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: the block scales of x and W must be the first entry of the list", i);
+            if (!f8) return fail(FLE_ERR_UNSUPPORTED, "op %d: block scales need FLE_F8E4M3 operands", i);
+            if (grp) return fail(FLE_ERR_UNSUPPORTED, "op %d: grouped problems take no block scales", i);
+            if (K % 128 != 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: block scales need K to be a multiple of 128 (got %lld)", i, (long long)K);
+            if ((!op.p0 || !op.p1) && M > 0 && K > 0) return fail(FLE_ERR_NULL, "op %d: a block-scale pointer is NULL", i);
+            if (!aligned(op.p0, 4) || !aligned(op.p1, 4)) return fail(FLE_ERR_ALIGN, "op %d: block scales must be 4-byte aligned", i);
+            plan->mx = 1;
+            plan->x_scale = op.p0;
+            plan->w_scale = op.p1;
+            continue;
+        }
         if (e.row_kind == FLE_LOGSUMEXP || e.row2_kind == FLE_LOGSUMEXP) return fail(FLE_ERR_UNSUPPORTED, "op %d follows logsumexp, which must be last", i);
         DevOp d{op.kind, op.alpha, op.p0, op.p1, op.ld};
         if (is_row_op(op.kind)) {
@@ -116,6 +128,9 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
         const size_t b_bytes = size_t(N) * es + (grp ? size_t(G - 1) * size_t(grp->b_group_stride) * es : 0);
         if (overlaps(p->out, out_bytes, p->x, span_bytes(M, K, p->ldx, xs)) || overlaps(p->out, out_bytes, p->w, w_bytes) || overlaps(p->out, out_bytes, p->b, b_bytes))
             return fail(FLE_ERR_UNSUPPORTED, "out overlaps x, w or b");
+        if (plan->mx && (overlaps(p->out, out_bytes, plan->x_scale, size_t(M) * size_t(K / 32)) || overlaps(p->out, out_bytes, plan->w_scale, size_t(N) * size_t(K / 32)) ||
+                         overlaps(p->workspace, p->workspace_bytes, plan->x_scale, size_t(M) * size_t(K / 32)) || overlaps(p->workspace, p->workspace_bytes, plan->w_scale, size_t(N) * size_t(K / 32))))
+            return fail(FLE_ERR_UNSUPPORTED, "out or the workspace overlaps the block scales");
         if (grp && (overlaps(p->out, out_bytes, grp->row_offsets, size_t(G + 1) * 8) || overlaps(p->workspace, p->workspace_bytes, grp->row_offsets, size_t(G + 1) * 8)))
             return fail(FLE_ERR_UNSUPPORTED, "out or the workspace overlaps row_offsets");
         for (int i = 0; i < p->n_ops; ++i) {
@@ -395,7 +410,7 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
 using namespace fle;
 
 static void format_plan(const Plan &plan, char *buf, size_t n) {
-    const char *dt = plan.op_dtype == FLE_F32 ? "f32" : plan.op_dtype == FLE_F16 ? "f16" : plan.op_dtype == FLE_F8E4M3 ? "f8" : "bf16";
+    const char *dt = plan.op_dtype == FLE_F32 ? "f32" : plan.op_dtype == FLE_F16 ? "f16" : plan.op_dtype == FLE_F8E4M3 ? (plan.mx ? "f8mx" : "f8") : "bf16";
     snprintf(buf, n, "variant=%s_%s_%s%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
              plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : plan.variant == V_THIN ? "thin" : "general", dt,
              plan.variant == V_THIN && plan.bm == 8 ? "dot" : "mfma",

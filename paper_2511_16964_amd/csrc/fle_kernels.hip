@@ -69,6 +69,8 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     g.partials = e.row_kind >= 0 ? reinterpret_cast<float *>(ws + plan.ws_part_off) : nullptr;
     g.tiles_m = int32_t(plan.tiles_m); g.tiles_n = int32_t(plan.tiles_n);
     g.epi = e;
+    g.x_scale = plan.x_scale;
+    g.w_scale = plan.w_scale;
     if (e.row_kind < 0 || plan.staging == ST_OUT) { g.dst = p->out; g.ldd = p->ldo; g.dst_f32 = 0; g.dst_rel = plan.stage_rel; }
     else if (plan.staging == ST_WS) { g.dst = ws + plan.ws_y_off; g.ldd = p->N; g.dst_f32 = 1; }
     else { g.dst = nullptr; g.ldd = 0; g.dst_f32 = 0; }
@@ -150,6 +152,9 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         };
         if (p->dtype == FLE_F32) kern = pick(std::integral_constant<int, FLE_F32>{});
         else if (p->dtype == FLE_F16) kern = pick(std::integral_constant<int, FLE_F16>{});
+        else if (p->dtype == FLE_F8E4M3 && plan.mx)
+            kern = plan.bm == 256 ? (edge ? gemm_tiled_256<FLE_F8E4M3, true, 32, -1, true> : gemm_tiled_256<FLE_F8E4M3, false, 32, -1, true>)
+                                  : (edge ? gemm_tiled_128<FLE_F8E4M3, true, 32, -1, true> : gemm_tiled_128<FLE_F8E4M3, false, 32, -1, true>);
         else if (p->dtype == FLE_F8E4M3) kern = pick(std::integral_constant<int, FLE_F8E4M3>{});
         else kern = pick(std::integral_constant<int, FLE_BF16>{});
         hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, g);

@@ -56,6 +56,8 @@ struct Plan {
     int32_t groups;          // grouped problem: number of row groups (tiles_m is then an upper bound); 0 otherwise
     int32_t w_stream;        // grouped problem with about one tile row per group: W panels are read once (non-temporal copies)
     int32_t op_dtype;        // fle_dtype of x and W (differs from epi.dtype for fp8 problems only)
+    int32_t mx;              // fp8 problem whose operands carry block scales (FLE_MXSCALE)
+    const void *x_scale, *w_scale;
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_mid_off, ws_total;  // (ws_mid: fp32 [M,N] between two row ops)
     DevEpilogue epi;

@@ -78,6 +78,7 @@ SHAPES = {
     "c5a": (torch.bfloat16, 16384, 16384, 4096),
     "c5b": (torch.bfloat16, 16384, 4096, 16384),
     "f2": (torch.float8_e4m3fn, 4096, 4096, 4096),   # c2 with x and W stored in fp8 (one scale per tensor)
+    "f3": (torch.float8_e4m3fn, 4096, 4096, 4096),   # ... in block-scaled fp8 (MXFP8: one power-of-two scale per 32 k)
 }
 
 
@@ -103,6 +104,12 @@ def make(name: str, seed: int = 0, M: int | None = None, N: int | None = None,
         sx, sw = float(np.abs(x).max()) / 448.0, float(np.abs(w).max()) / 448.0
         return Problem(name, dtype, _store(x / np.float32(sx), dtype), _store(w / np.float32(sw), dtype), _store(b, torch.bfloat16),
                        [("scale", float(np.float32(sx * sw))), ("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, torch.bfloat16))])
+    if name == "f3":    # c2's layer with block-scaled fp8 storage (the same values as c2 and f2, quantised block by block)
+        x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
+        r = _normal(rng, (M, N))
+        (xq, sx), (wq, sw) = mx_quantize(x), mx_quantize(w)
+        return Problem(name, dtype, xq, wq, _store(b, torch.bfloat16),
+                       [("mxscale", sx, sw), ("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, torch.bfloat16))])
     if name == "c3":    # Linear + bias + GELU-tanh + LayerNorm, bf16
         x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
         g = _normal(rng, (N,), 1.0, 0.02); be = _normal(rng, (N,), 0.0, 0.02)
@@ -149,11 +156,29 @@ def make_mlp(seed: int = 0, T: int = 16384, D: int = 4096, F: int = 16384,
     return MlpBlock(s(x), s(w1), s(b1), s(w2), s(b2), s(g), s(be))
 
 
+def mx_quantize(a: np.ndarray):
+    """Stores a float matrix [R, K] (K a multiple of 32) in the OCP microscaling format with e4m3 elements (MXFP8):
+    every block of 32 consecutive values of a row gets the power of two 2^e with e = floor(log2(max |v|)) - 8 (8 is
+    the exponent of e4m3's largest value, 448 = 1.75 * 2^8; a block of zeros gets the smallest scale), stored as
+    the byte e + 127, and its values divided by that scale are rounded to e4m3, saturating at +-448.
+    Returns (elements as a float8_e4m3fn tensor [R, K], scales as a uint8 tensor [R, K/32])."""
+    R, K = a.shape
+    blocks = a.astype(np.float64).reshape(R, K // 32, 32)
+    amax = np.abs(blocks).max(axis=2)
+    e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 8, -127).clip(-127, 127).astype(np.int64)
+    elems = np.clip(blocks / np.ldexp(1.0, e)[:, :, None], -448.0, 448.0).reshape(R, K)
+    return torch.from_numpy(elems.astype(np.float32)).to(F8), torch.from_numpy((e + 127).astype(np.uint8))
+
+
 def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds: list[str],
-                   integer: bool = False) -> Problem:
+                   integer: bool = False, mx: bool = False) -> Problem:
     """A problem with an arbitrary epilogue list, for parity sweeps.  With
     ``integer`` every tensor holds small integers (exactly representable in
-    bf16), which makes the elementwise chain bias/relu/scale(0.5)/residual exact."""
+    bf16), which makes the elementwise chain bias/relu/scale(0.5)/residual exact.
+    ``mx`` (fp8 problems, K a multiple of 128): x and W are block-scaled; their magnitudes then vary from one
+    block of 32 to the next by up to 2^12 (integer: the scales are random powers of two from 1/4 to 4 and the
+    elements small integers, so every product and partial sum is still exact in fp32); the list starts with the
+    ("mxscale", scales of x, scales of W) entry."""
     rng = np.random.default_rng(seed)
     if integer:
         ri = lambda shape, a: rng.integers(-a, a + 1, size=shape).astype(np.float32)
@@ -163,6 +188,17 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
         b = _uniform(rng, (N,), 0.5)
     ep = []
     io = io_dtype(dtype)
+    if mx:
+        assert dtype == F8 and K % 128 == 0
+        if integer:
+            sx = rng.integers(125, 130, size=(M, K // 32)).astype(np.uint8); sw = rng.integers(125, 130, size=(N, K // 32)).astype(np.uint8)
+            xq, wq = _store(x, F8), _store(w, F8)
+            sx, sw = torch.from_numpy(sx), torch.from_numpy(sw)
+        else:
+            x = x * np.ldexp(1.0, rng.integers(-6, 7, size=(M, K // 32))).repeat(32, axis=1).astype(np.float32)
+            w = w * np.ldexp(1.0, rng.integers(-6, 7, size=(N, K // 32))).repeat(32, axis=1).astype(np.float32)
+            (xq, sx), (wq, sw) = mx_quantize(x), mx_quantize(w)
+        ep.append(("mxscale", sx, sw))
     for kd in kinds:
         if kd == "scale":
             ep.append(("scale", 0.5 if integer else float(np.float32(rng.uniform(0.25, 2.0)))))
@@ -176,6 +212,8 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
             ep.append(("store", torch.full((M, N), -7.0, dtype=io)))
         else:
             ep.append((kd,))
+    if mx:
+        return Problem("random", dtype, xq, wq, _store(b, io), ep)
     return Problem("random", dtype, _store(x, dtype), _store(w, dtype), _store(b, io), ep)
 
 

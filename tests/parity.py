@@ -51,8 +51,11 @@ def run_gpu(prob: inputs.Problem, variant="auto", poison=False, **kw):
 def oracle_rows(prob: inputs.Problem, rows=None) -> np.ndarray:
     """Oracle result for all rows, or for the listed rows only (every op is row-local)."""
     x = prob.x if rows is None else prob.x[rows]
-    return oracle.fused_linear_epilogue(inputs.to_f64(x), inputs.to_f64(prob.w), inputs.to_f64(prob.b),
-                                        inputs.epilogue_f64(prob.epilogue, rows))
+    x64, w64, ep = inputs.to_f64(x), inputs.to_f64(prob.w), prob.epilogue
+    if ep and ep[0][0] == "mxscale":   # block-scaled operands: the oracle multiplies the values they stand for
+        sx = ep[0][1] if rows is None else ep[0][1][rows]
+        x64, w64, ep = oracle.mx_dequantize(x64, sx.numpy()), oracle.mx_dequantize(w64, ep[0][2].numpy()), ep[1:]
+    return oracle.fused_linear_epilogue(x64, w64, inputs.to_f64(prob.b), inputs.epilogue_f64(ep, rows))
 
 
 def excess(got: np.ndarray, ref: np.ndarray, tol: float, s=None, extra=None):

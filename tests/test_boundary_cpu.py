@@ -730,3 +730,29 @@ def test_tile_table_lookup_and_round_trip(tmp_path):
     shipped = T.load()                                                       # the table in the package parses and names real plans
     assert shipped.entries and all(e["variant"] in binding.VARIANTS and 0 <= e["split"] <= 64 for e in shipped.entries.values())
     assert all(re.fullmatch(r"\d:[01]:\d+:\d+:\d+", k) for k in shipped.entries)
+
+
+def test_block_scaled_fp8_problems_validate_and_plan(L):
+    """FLE_MXSCALE: first entry only, fp8 operands only, K a multiple of 128, both scale pointers, no grouped form;
+    the plan names the block-scaled kernel."""
+    def mx(**kw):
+        return op("mxscale", p0=kw.pop("p0", 20 * G), p1=kw.pop("p1", 21 * G))
+    p = problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[mx(), op("bias"), op("relu")])
+    need = ctypes.c_size_t(0)
+    assert L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need)) == OK
+    buf = ctypes.create_string_buffer(256)
+    L.fle_last_plan(buf, 256)
+    assert "tiled_f8mx_mfma" in buf.value.decode(), buf.value
+    assert validate(L, problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[op("bias"), mx()])) == E_UNSUP        # not first
+    assert validate(L, problem(M=512, N=512, K=512, dtype=binding.BF16, ops=[mx()])) == E_UNSUP                      # bf16 operands
+    assert validate(L, problem(M=512, N=512, K=448, dtype=binding.F8E4M3, ops=[mx()])) == E_UNSUP                    # K not a multiple of 128
+    assert validate(L, problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[op("mxscale", p0=20 * G, p1=0)])) == E_NULL
+    assert validate(L, problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[op("mxscale", p0=20 * G + 2, p1=21 * G)])) == E_ALIGN
+    p = problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[mx()])
+    assert validate(L, p) == OK
+    p = problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[op("mxscale", p0=3 * G + 64, p1=21 * G)])             # scales inside out
+    assert validate(L, p) == E_UNSUP
+    p = problem(M=512, N=512, K=1024, dtype=binding.F8E4M3, ops=[mx(), op("layernorm", 1e-5)])
+    from paper_2511_16964_amd.binding import FlePlanChoice
+    c = FlePlanChoice(binding.VARIANTS["tiled128"], 2)
+    assert L.fle_workspace_size_with(ctypes.byref(p), ctypes.byref(c), ctypes.byref(need)) == OK and need.value > 0  # split K keeps the scales

@@ -37,7 +37,7 @@ def kernel_props(asm):
 def test_hot_kernels_do_not_spill_and_fit_their_budgets(asm):
     props = kernel_props(asm)
     names = {k: v for k, v in props.items() if "gemm_bf16_skinny" in k or "gemm_tiled_" in k}
-    assert len(names) == 17 + 16 + 24, sorted(props)   # skinny: 7 shapes x 2 dtypes and 3 K steps in fp32; tiled: 2 tiles x 4 dtypes (fp8 among them) x 2 epilogues; grouped: the same plus the 128 tile with streamed W
+    assert len(names) == 17 + 20 + 24, sorted(props)   # skinny: 7 shapes x 2 dtypes and 3 K steps in fp32; tiled: 2 tiles x 4 dtypes (fp8 among them) x 2 epilogues, and the block-scaled fp8 form of each tile and epilogue; grouped: the same 4 dtypes plus the 128 tile with streamed W
     for name, p in names.items():
         assert p["scratch"] == 0, "%s spills %d bytes of scratch" % (name, p["scratch"])
         assert p["lds"] <= 160 * 1024, name
@@ -93,13 +93,13 @@ def test_main_loop_uses_the_intended_instructions(asm):
     body = asm
     assert re.search(r"buffer_load_dwordx4 .* lds", body)          # direct-to-LDS copies
     assert "v_mfma_f32_16x16x4_f32" in asm                         # fp32 path stays on fp32 MFMA
-    m = re.search(r"^_ZN3fle14gemm_tiled_256ILi0ELb0ELi32ELin1EEEvNS_8GemmArgsE:(.*?)s_endpgm", asm, flags=re.S | re.M)   # fp32 operands
+    m = re.search(r"^_ZN3fle14gemm_tiled_256ILi0ELb0ELi32ELin1ELb0EEEvNS_8GemmArgsE:(.*?)s_endpgm", asm, flags=re.S | re.M)   # fp32 operands
     assert m and "v_mfma_f32_32x32x2_f32" in m.group(1) and "_bf16" not in m.group(1) and "x16_f16" not in m.group(1) and "x32_f16" not in m.group(1)
     # 2-byte operands: the tiled loop runs on the 16x16x32 shape, whose accumulators stay where they are (no
     # accumulator moves between register files inside the K loop) and nothing spills
     for dt, mn in ((1, "v_mfma_f32_16x16x32_bf16"), (2, "v_mfma_f32_16x16x32_f16")):
         for kern in ("gemm_tiled_256", "gemm_tiled_128"):
-            m = re.search(r"^_ZN3fle14%sILi%dELb0ELi16ELin1EEEvNS_8GemmArgsE:(.*?)s_endpgm" % (kern, dt), asm, flags=re.S | re.M)
+            m = re.search(r"^_ZN3fle14%sILi%dELb0ELi16ELin1ELb0EEEvNS_8GemmArgsE:(.*?)s_endpgm" % (kern, dt), asm, flags=re.S | re.M)
             assert m, (kern, dt)
             text = m.group(1)
             first, last = text.index(mn), text.rindex(mn)

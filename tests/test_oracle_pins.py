@@ -586,3 +586,48 @@ def test_transformer_layer_against_a_numpy_formulation():
         # plausible mistakes differ: the perceptron added to x instead of h, or the middle LayerNorm taken of x
         assert np.abs(want_x - (x + (want_x - h))).max() > 1e-2
         assert np.abs(got_n - ln(h, g2, be2)).max() > 1e-2
+
+
+def test_mx_dequantize_follows_the_e8m0_definition():
+    """OCP Microscaling Formats specification: a scale byte e stands for 2^(e - 127), 255 for NaN, and it covers 32
+    consecutive elements of its row.  The expected values are that definition evaluated by hand."""
+    elems = np.ones((2, 96))
+    elems[0, 31], elems[0, 32], elems[1, 95] = -3.0, 5.0, 0.5
+    scales = np.array([[127, 128, 120], [0, 254, 255]], dtype=np.uint8)
+    got = oracle.mx_dequantize(elems, scales)
+    assert got.shape == (2, 96) and got.dtype == np.float64
+    assert got[0, 0] == 1.0 and got[0, 31] == -3.0            # byte 127: the values themselves
+    assert got[0, 32] == 10.0 and got[0, 63] == 2.0           # byte 128 starts exactly at element 32
+    assert got[0, 64] == 0.0078125                            # byte 120: 2^-7
+    assert got[1, 0] == 5.877471754111438e-39                 # byte 0: 2^-127
+    assert got[1, 32] == 1.7014118346046923e38                # byte 254: 2^127
+    assert np.isnan(got[1, 64:]).all() and not np.isnan(got[1, :64]).any()
+    # a dot product of block-scaled rows is the plain one of the dequantised values
+    w = oracle.mx_dequantize(np.full((1, 96), 2.0), np.array([[126, 127, 130]], dtype=np.uint8))
+    y = oracle.fused_linear_epilogue(got[:1], w, None, [])
+    assert y[0, 0] == (31 * 1.0 - 3.0) * 1.0 + (5.0 + 31) * 2.0 * 2.0 + 32 * 0.0078125 * 16.0 == 176.0   # w: 2 * 2^-1, 2 * 1, 2 * 2^3 per block
+    with pytest.raises(ValueError):
+        oracle.mx_dequantize(np.ones((2, 96)), np.zeros((2, 2), dtype=np.uint8))
+    with pytest.raises(ValueError):
+        oracle.mx_dequantize(np.ones((2, 96)), np.zeros((2, 3), dtype=np.int32))
+
+
+def test_mx_quantize_round_trips_within_an_e4m3_rounding():
+    """The input generator's quantiser against the oracle's decoder: every value comes back within one e4m3 rounding
+    (2^-4 relative, or the subnormal step of the block's scale), powers of two are exact, and the scale is the one
+    the specification's recipe gives."""
+    from paper_2511_16964_amd import inputs
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((8, 256)) * np.ldexp(1.0, rng.integers(-10, 10, size=(8, 8))).repeat(32, axis=1)
+    a[0, :32] = 0.0
+    a[1, 32:64] = np.ldexp(1.0, np.arange(32) % 7)
+    q, s = inputs.mx_quantize(a)
+    back = oracle.mx_dequantize(q.to(torch.float64).numpy(), s.numpy())
+    amax = np.abs(a).reshape(8, 8, 32).max(axis=2).repeat(32, axis=1)
+    scale = np.ldexp(1.0, s.numpy().astype(np.int64) - 127).repeat(32, axis=1)
+    near = np.abs(back - a) <= np.maximum(np.abs(a) * 2.0 ** -4, amax * 2.0 ** -10)
+    saturated = (np.abs(a) > 448 * scale) & (back == np.sign(a) * 448 * scale)   # (the format's largest value is 1.75 * 2^8: a block maximum above 1.75 times its power of two is cut there)
+    assert (near | saturated).all() and saturated.sum() < near.size // 20
+    assert (amax[:, ::32][amax[:, ::32] > 0] >= 256 * scale[:, ::32][amax[:, ::32] > 0]).all() and (amax < 512 * scale)[amax > 0].all()   # e = floor(log2(max)) - 8
+    assert (back[0, :32] == 0).all() and (back[1, 32:64] == a[1, 32:64]).all()
+    assert s.dtype == torch.uint8 and s.shape == (8, 8) and s[0, 0] == 0
