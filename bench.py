@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused linear + epilogue hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5|f2|f3|g1|g2|m1|m2|m3|a1|a2|l1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5|f2|f3|p1|p2|g1|g2|m1|m2|m3|a1|a2|l1]
 
 A step is one pass of the whole path (every kernel the call enqueues) over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s
@@ -90,7 +90,10 @@ def summarize_traffic(dirs):
 def eager_fn(torch, F, x, w, b, ep):
     """The unfused PyTorch-eager composition: one library call per op."""
     def run():
-        z = F.linear(x, w)
+        if ep and ep[0][0] == "layernorm_pre":   # the normalisation as its own library call, then the projection
+            z = F.linear(F.layer_norm(x, (x.shape[1],), ep[0][1], ep[0][2], ep[0][3]), w)
+        else:
+            z = F.linear(x, w)
         for e in ep:
             k = e[0]
             if k == "bias": z = z + b
@@ -195,6 +198,8 @@ def oracle_operands(prob, inputs, rows=None):
     if ep and ep[0][0] == "mxscale":
         sx = ep[0][1] if rows is None else ep[0][1][rows]
         x64, w64, ep = oracle.mx_dequantize(x64, sx.numpy()), oracle.mx_dequantize(w64, ep[0][2].numpy()), ep[1:]
+    if ep and ep[0][0] == "layernorm_pre":
+        x64, ep = oracle.layernorm_rows(x64, inputs.to_f64(ep[0][1]), inputs.to_f64(ep[0][2]), ep[0][3]), ep[1:]
     return x64, w64, ep
 
 
@@ -332,7 +337,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "f2", "f3", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "f2", "f3", "p1", "p2", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -497,7 +502,7 @@ def main():
         flops = prob.flops
         f8 = prob.dtype == torch.float8_e4m3fn
         mxs = bool(ep) and ep[0][0] == "mxscale"
-        desc = "%s: %s, %s, M=%d N=%d K=%d" % (args.workload, "+".join(["linear"] + [e[0] for e in prob.epilogue if e[0] != "mxscale"]),
+        desc = "%s: %s, %s, M=%d N=%d K=%d" % (args.workload, "+".join((["layernorm(x)"] if ep and ep[0][0] == "layernorm_pre" else []) + ["linear"] + [e[0] for e in prob.epilogue if e[0] not in ("mxscale", "layernorm_pre")]),
                                               "block-scaled fp8 (MXFP8: e4m3, one E8M0 scale per 32 k) x and W, bf16 elsewhere" if mxs else
                                               "fp8 (e4m3) x and W, bf16 elsewhere" if f8 else "bf16" if prob.dtype == torch.bfloat16 else "fp32", prob.M, prob.N, prob.K)
         # (fp8: the comparator is the bf16 composition of the same layer on the upcast operands, converted outside the timed region)
@@ -510,7 +515,7 @@ def main():
         xs = 1 if f8 else es                                                       # x, W
         alg_bytes = xs * (prob.M * prob.K + prob.N * prob.K) + es * (prob.M * prob.N + (prob.N if bg is not None else 0)
                           + sum(prob.M * prob.N for e in ep if e[0] == "residual") + sum(2 * prob.N for e in ep if e[0] == "layernorm")) \
-                    + ((prob.M + prob.N) * (prob.K // 32) if mxs else 0)
+                    + ((prob.M + prob.N) * (prob.K // 32) if mxs else 0) + (2 * es * prob.K if ep and ep[0][0] == "layernorm_pre" else 0)
 
     def step():
         for c in calls:
@@ -607,7 +612,7 @@ def main():
                                  "how": "one event pair and one synchronisation per call, L2 and Infinity Cache evicted (768 MB overwritten) before each",
                                  "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
-    hbm_bound = args.workload in ("c4", "g2", "m1", "m2", "m3")
+    hbm_bound = args.workload in ("c4", "g2", "m1", "m2", "m3", "p1")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS, "traffic": measured_traffic(args.workload)}

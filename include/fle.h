@@ -87,6 +87,17 @@ typedef enum {
                           K a multiple of 128; plain problems only (fle_run*, not the grouped form).  This is the
                           finer-grained of the reduced-precision formats the paper's tolerance admits (Section 5.3,
                           Appendix A); per-tensor scales need no such entry (FLE_SCALE).                       */
+    FLE_LAYERNORM_PRE = 11, /* not an epilogue step: LayerNorm over K of every row of x in front of the multiplication,
+                          out = epilogue( LN(x) W^T ) with LN(x)[m,k] = (x[m,k] - mean_m) / sqrt(biased var_m + alpha)
+                          * gamma[k] + beta[k]; p0 = gamma[K] or NULL (1), p1 = beta[K] or NULL (0), alpha = eps
+                          (the normalisation -> projection pairs of a transformer block, Section 5.3).  First entry
+                          of the list only; FLE_F32, FLE_BF16 and FLE_F16; plain problems only.  For up to 4 rows of
+                          x on the dot-product kernel the statistics and the normalisation are part of
+                          that kernel's one sweep over W: one launch in place of two, where launches are most of
+                          the time.  Every other shape gets a pass that writes LN(x), rounded to the dtype as the
+                          unfused composition rounds it, into M * K more elements of workspace, which the usual
+                          kernels then read (inside the K loop of a compute-bound kernel the normalisation costs
+                          more than that pass).                                                                */
     FLE_STORE = 9      /* t[m,n] = v, rounded to the dtype; v itself goes on unchanged (p0 = t, ld).
                           Allowed before the row op (or anywhere in a list without one).  It is how
                           one call hands over both a value and its normalisation, e.g. bias, residual,
@@ -98,11 +109,12 @@ typedef enum {
 
 typedef struct {
     int32_t kind;   /* fle_op_kind */
-    float alpha;    /* SCALE: factor.  LAYERNORM: eps.  Otherwise ignored.                 */
+    float alpha;    /* SCALE: factor.  LAYERNORM, LAYERNORM_PRE: eps.  Otherwise ignored.  */
     const void *p0; /* RESIDUAL: r[M,N] (device).  LAYERNORM: gamma[N] (device) or NULL.
                        STORE: t[M,N] (device, written; must not overlap any other operand).
-                       MXSCALE: block scales of x (device)                                  */
-    const void *p1; /* LAYERNORM: beta[N] (device) or NULL.  MXSCALE: block scales of W     */
+                       MXSCALE: block scales of x (device).  LAYERNORM_PRE: gamma[K] or NULL */
+    const void *p1; /* LAYERNORM: beta[N] (device) or NULL.  MXSCALE: block scales of W.
+                       LAYERNORM_PRE: beta[K] (device) or NULL                              */
     int64_t ld;     /* RESIDUAL / STORE: row stride of r / t in elements (>= N).           */
 } fle_op;
 
@@ -127,7 +139,7 @@ typedef struct {
 } fle_problem;
 
 /*
- * Accepted epilogue grammar:   [ MXSCALE ]  elementwise*  [ rowop  elementwise*  [ rowop  elementwise* ] ]
+ * Accepted epilogue grammar:   [ MXSCALE | LAYERNORM_PRE ]  elementwise*  [ rowop  elementwise*  [ rowop  elementwise* ] ]
  * with rowop = LAYERNORM | SOFTMAX | LOGSUMEXP and elementwise = BIAS | SCALE | RELU | GELU_ERF |
  * GELU_TANH | RESIDUAL | STORE (STORE only before the first row op); nothing follows LOGSUMEXP.  A
  * list with two row ops (e.g. LAYERNORM, SOFTMAX: a normalised layer's class probabilities) costs

@@ -146,6 +146,22 @@ def fused_linear_epilogue(x, w, b, epilogue, n_threads: int = 0) -> np.ndarray:
     return out
 
 
+def layernorm_rows(x, gamma=None, beta=None, eps: float = 1e-5) -> np.ndarray:
+    """LayerNorm over the last axis of x [M, K], the definition written out in float64 (PyTorch-eager semantics:
+    biased variance, eps inside the square root): (x - mean) / sqrt(var + eps) * gamma + beta.  This is what a
+    LayerNorm in front of the linear layer hands to the multiplication."""
+    x = _f64(x)
+    eps = float(np.float32(eps))   # (eps crosses the GPU boundary as fp32, as for the row op)
+    mean = x.mean(axis=1, keepdims=True)
+    var = ((x - mean) ** 2).mean(axis=1, keepdims=True)
+    y = (x - mean) / np.sqrt(var + eps)
+    if gamma is not None:
+        y = y * _f64(gamma)[None, :]
+    if beta is not None:
+        y = y + _f64(beta)[None, :]
+    return y
+
+
 def mx_dequantize(elems, scales) -> np.ndarray:
     """The values a block-scaled operand stands for (OCP Microscaling Formats specification, MXFP8): elems [R, K]
     are the stored elements (already upcast exactly), scales [R, K/32] one byte per block of 32 consecutive

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libfle.so")
 
 F32, BF16, F16, F8E4M3 = 0, 1, 2, 3
 OP_KINDS = {"bias": 0, "scale": 1, "relu": 2, "gelu_erf": 3, "gelu_tanh": 4, "residual": 5,
-            "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9, "mxscale": 10}
+            "layernorm": 6, "softmax": 7, "logsumexp": 8, "store": 9, "mxscale": 10, "layernorm_pre": 11}
 MAX_OPS = 8
 STATIC_SCRATCH_BYTES = 16 << 20
 VARIANTS = {"auto": 0, "general": 1, "tiled": 2, "skinny": 3, "tiled256": 4, "tiled128": 5, "skinny128": 6, "skinny256": 7, "skinnyseq": 8, "thin": 9}
@@ -236,11 +236,12 @@ class Call:
                         raise ValueError("block scales of %s must be a contiguous uint8 tensor [%d, K/32 = %d] on x's device" % (name, rows, K // 32))
                 self._scales = (sx, sw)   # (kept alive; uint8, so outside the dtype check below)
                 ops[i].p0, ops[i].p1 = sx.data_ptr(), sw.data_ptr()
-            elif e[0] == "layernorm":
+            elif e[0] in ("layernorm", "layernorm_pre"):   # over the N outputs / over the K inputs of every row of x
                 g, be, eps = e[1], e[2], e[3]
+                n_aff = K if e[0] == "layernorm_pre" else N
                 for name, t in (("gamma", g), ("beta", be)):
-                    if t is not None and (t.dim() != 1 or t.shape[0] != N or (N > 1 and t.stride(0) != 1)):
-                        raise ValueError("layernorm %s must be a contiguous vector of N = %d elements" % (name, N))
+                    if t is not None and (t.dim() != 1 or t.shape[0] != n_aff or (n_aff > 1 and t.stride(0) != 1)):
+                        raise ValueError("%s %s must be a contiguous vector of %d elements" % (e[0], name, n_aff))
                 tensors += [g, be]
                 ops[i].p0 = None if g is None else g.data_ptr()
                 ops[i].p1 = None if be is None else be.data_ptr()

@@ -35,7 +35,21 @@ struct GemmArgs {
     int32_t tiles_m, tiles_n;
     int64_t split_stride;  // split K (gridDim.y > 1): workgroup row y owns a K range and writes dst + y * split_stride bytes
     const void *x_scale, *w_scale;  // block-scaled fp8 operands: one E8M0 byte per 32 consecutive k, [M][K/32] and [N][K/32]
+    const void *ln_gamma, *ln_beta;  // LayerNorm of x over K in front of the multiplication, done by the kernel itself
+    float ln_eps;                    // (dot-product kernel for a few rows of x only); gamma / beta [K] or nullptr
     DevEpilogue epi;
+};
+
+// LayerNorm of the rows of x over K, written to a contiguous copy (the pass in front of the GEMM kernels).
+struct LnArgs {
+    int64_t M, K;
+    const void *x;
+    int64_t ldx;
+    const void *gamma, *beta;  // [K] or nullptr
+    float eps;
+    int32_t dtype;
+    int32_t vec;               // rows, gamma and beta allow 16-byte accesses of 8 (2-byte dtypes) or 4 (fp32) elements
+    void *dst;                 // [M][K], rows contiguous
 };
 
 // Sum of the split-K slabs followed by the ops before the row op (reduce_slabs).

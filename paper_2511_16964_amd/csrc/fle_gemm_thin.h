@@ -152,7 +152,16 @@ __device__ __forceinline__ Unpacked<DT> unpack16(u32x4 r) {
 // MR: x rows held per lane (M <= MR).
 // R: W rows per wave; the workgroup always owns 16 rows, so it has 16 / R waves.  R = 4 and 4 waves is the
 // default; R = 1 and 16 waves (used for a single x row) keeps more loads in flight per CU.
-template <int DT, int MR, int R>
+// LNP: LayerNorm of the x rows over K in front of the multiplication, in the same sweep.  With
+// xn_k = (x_k - mean) rstd gamma_k + beta_k the dot product is
+//     sum_k w_k xn_k = rstd (S1 - mean S2) + S3,   S1 = sum_k (w_k gamma_k) x_k,  S2 = sum_k w_k gamma_k,  S3 = sum_k w_k beta_k,
+// so every lane accumulates S1 per (W row, x row) as it does the plain products, S2 and S3 per W row, and the sum and
+// sum of squares of its x values; mean and rstd come out of the same lane reduction as the dot products (every wave
+// sees all of x).  One kernel and one pass over W where the unfused form launches a normalisation first: at one row
+// of x, where the launch is a large part of the time, that is the point (the paper's perceptron tasks at batch 1,
+// Appendix C).  The variance is E[x^2] - mean^2 in fp32, exact enough while |mean| is within a few hundred
+// deviations; rows far off centre belong to the two-pass form in front of the other kernels.
+template <int DT, int MR, int R, bool LNP = false>
 __global__ __launch_bounds__(1024 / R) void gemm_gemv(const GemmArgs a) {
     constexpr int ES = DT == FLE_F32 ? 4 : 2;
     constexpr int NW = 16 / R;           // waves per workgroup
@@ -186,8 +195,10 @@ __global__ __launch_bounds__(1024 / R) void gemm_gemv(const GemmArgs a) {
     const uint32_t kbytes = uint32_t(K * ES), ldwb = uint32_t(a.ldw) * ES, ldxb = uint32_t(a.ldx) * ES;
 
     struct Batch {
-        u32x4 w[D][R], x[D][MR];
+        u32x4 w[D][R], x[D][MR], g[LNP ? D : 1], be[LNP ? D : 1];
     };
+    [[maybe_unused]] const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.ln_gamma), 0, LNP && a.ln_gamma ? uint32_t(K * ES) : 0u, 0x00020000);
+    [[maybe_unused]] const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.ln_beta), 0, LNP && a.ln_beta ? uint32_t(K * ES) : 0u, 0x00020000);
     // K blocks j D .. j D + D - 1; bytes past the end of the row, rows past N or M: zeros, no memory traffic
     auto load = [&](Batch &b, uint32_t j) {
 #pragma unroll
@@ -198,25 +209,69 @@ __global__ __launch_bounds__(1024 / R) void gemm_gemv(const GemmArgs a) {
             for (int m = 0; m < MR; ++m) b.x[d][m] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, uint32_t(m) * ldxb + off, 0, 0));
 #pragma unroll
             for (int r = 0; r < R; ++r) b.w[d][r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, uint32_t(r) * ldwb + off, 0, 2));
+            if constexpr (LNP) {  // (a missing gamma / beta has an empty descriptor: its loads return zeros and cost nothing)
+                b.g[d] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, 0));
+                b.be[d] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, 0));
+            }
         }
     };
+    [[maybe_unused]] float s2[R], s3[R], xs[MR], xq[MR];  // LNP: S2, S3 per W row; sum and sum of squares per x row
+    if constexpr (LNP) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) s2[r] = s3[r] = 0.0f;
+#pragma unroll
+        for (int m = 0; m < MR; ++m) xs[m] = xq[m] = 0.0f;
+    }
+    [[maybe_unused]] const bool has_gamma = LNP && a.ln_gamma != nullptr;
     float acc[R][MR];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int m = 0; m < MR; ++m) acc[r][m] = 0.0f;
     auto multiply = [&](const Batch &b) {
+        constexpr int E = DT == FLE_F32 ? 4 : 8;
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-#pragma unroll
-            for (int r = 0; r < R; ++r)
+        for (int d = 0; d < D; ++d) {
+            if constexpr (LNP) {
+                const Unpacked<DT> g = unpack16<DT>(b.g[d]), be = unpack16<DT>(b.be[d]);
 #pragma unroll
                 for (int m = 0; m < MR; ++m) {
-                    // (the compiler hoists the conversions: x once per block, W once per row)
-                    const Unpacked<DT> w = unpack16<DT>(b.w[d][r]), x = unpack16<DT>(b.x[d][m]);
+                    const Unpacked<DT> x = unpack16<DT>(b.x[d][m]);
 #pragma unroll
-                    for (int e = 0; e < (DT == FLE_F32 ? 4 : 8); ++e) acc[r][m] = fmaf(w.v[e], x.v[e], acc[r][m]);
+                    for (int e = 0; e < E; ++e) {
+                        xs[m] += x.v[e];
+                        xq[m] = fmaf(x.v[e], x.v[e], xq[m]);
+                    }
                 }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const Unpacked<DT> w = unpack16<DT>(b.w[d][r]);
+                    float wg[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        wg[e] = has_gamma ? w.v[e] * g.v[e] : w.v[e];
+                        s2[r] += wg[e];
+                        s3[r] = fmaf(w.v[e], be.v[e], s3[r]);
+                    }
+#pragma unroll
+                    for (int m = 0; m < MR; ++m) {
+                        const Unpacked<DT> x = unpack16<DT>(b.x[d][m]);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[r][m] = fmaf(wg[e], x.v[e], acc[r][m]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int m = 0; m < MR; ++m) {
+                        // (the compiler hoists the conversions: x once per block, W once per row)
+                        const Unpacked<DT> w = unpack16<DT>(b.w[d][r]), x = unpack16<DT>(b.x[d][m]);
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc[r][m] = fmaf(w.v[e], x.v[e], acc[r][m]);
+                    }
+            }
+        }
     };
     const uint32_t blocks = (kbytes + 1023) / 1024, batches = (blocks + D - 1) / D;
     // The scheduling barriers keep the compiler from sinking a batch's loads down to their first use, which
@@ -238,6 +293,35 @@ __global__ __launch_bounds__(1024 / R) void gemm_gemv(const GemmArgs a) {
     // partial sums are transposed through LDS instead: value v is summed by 64 / V lanes, each adding V of
     // the 64 partials in index order, and a short butterfly over those lanes finishes it.
     constexpr int V = R * MR, LPV = 64 / V;  // values per wave; lanes per value
+    if constexpr (LNP) {
+        // the statistics first, by butterflies (few values: 2 per x row and 2 per W row), then the dot products turn
+        // into those of the normalised rows before they take the usual way
+        float mean[MR], rstd[MR];
+#pragma unroll
+        for (int m = 0; m < MR; ++m) {
+            float sx = xs[m], sq = xq[m];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                sx += __shfl_xor(sx, d);
+                sq += __shfl_xor(sq, d);
+            }
+            mean[m] = sx / float(K);
+            const float var = sq / float(K) - mean[m] * mean[m];
+            rstd[m] = rsqrtf((var > 0.0f ? var : 0.0f) + a.ln_eps);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float t2 = s2[r], t3 = s3[r];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                t2 += __shfl_xor(t2, d);
+                t3 += __shfl_xor(t3, d);
+            }
+            // per lane: rstd (S1_lane - mean S2 / 64) + S3 / 64 sums over the lanes to rstd (S1 - mean S2) + S3
+#pragma unroll
+            for (int m = 0; m < MR; ++m) acc[r][m] = rstd[m] * (acc[r][m] - mean[m] * t2 * (1.0f / 64.0f)) + t3 * (1.0f / 64.0f);
+        }
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll

@@ -46,7 +46,55 @@ static size_t span_bytes(int64_t rows, int64_t cols, int64_t ld, size_t es) {
 // 249 -> 185 us from cold caches; at 128 rows per group the hint costs 3 % back to back, so the limit is 64).
 static const int64_t kGroupedStreamRows = 64;
 
+static fle_status make_plan_core(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp);
+
+// A list that starts with FLE_LAYERNORM_PRE: the rest of the list is planned as a problem of its own, first on x as
+// it is.  If that gives the dot-product kernel for a few rows, the kernel normalises in its own sweep and nothing else
+// changes.  Otherwise a pass writes the normalised rows into the workspace and the rest is planned again for that
+// copy (contiguous and aligned whatever x looks like).
 fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp) {
+    if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
+    bool ln_pre = false;
+    if (p->n_ops > 0 && p->n_ops <= FLE_MAX_OPS && p->ops)
+        for (int i = 0; i < p->n_ops; ++i)
+            if (p->ops[i].kind == FLE_LAYERNORM_PRE) {
+                if (i != 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: the LayerNorm of x must be the first entry of the list", i);
+                ln_pre = true;
+            }
+    if (!ln_pre) return make_plan_core(p, forced, forced_split, plan, grp);
+    const fle_op &op = p->ops[0];
+    if (grp) return fail(FLE_ERR_UNSUPPORTED, "op 0: grouped problems take no LayerNorm of x");
+    if (p->dtype == FLE_F8E4M3) return fail(FLE_ERR_UNSUPPORTED, "op 0: fp8 operands take no LayerNorm of x");
+    if (!(op.alpha >= 0.0f && std::isfinite(op.alpha))) return fail(FLE_ERR_OP, "op 0: layernorm eps must be finite and >= 0");
+    if (p->K < 1) return fail(FLE_ERR_SHAPE, "op 0: a LayerNorm of x needs K >= 1");
+    fle_problem q = *p;
+    q.ops = p->ops + 1;
+    q.n_ops = p->n_ops - 1;
+    fle_status s = make_plan_core(&q, forced, forced_split, plan, nullptr);
+    if (s != FLE_OK && !(s == FLE_ERR_UNSUPPORTED && forced != V_AUTO)) return s;  // (a forced kernel may only fit the copy)
+    const size_t es = p->dtype == FLE_F32 ? 4 : 2;
+    if (!aligned(op.p0, es) || !aligned(op.p1, es)) return fail(FLE_ERR_ALIGN, "op 0: gamma/beta not aligned to the element size");
+    if (p->M > 0 && p->out) {
+        const size_t ob = (plan->epi.row_kind == FLE_LOGSUMEXP || plan->epi.row2_kind == FLE_LOGSUMEXP) ? size_t(p->M) * es : span_bytes(p->M, p->N, p->ldo, es);
+        if (overlaps(p->out, ob, op.p0, size_t(p->K) * es) || overlaps(p->out, ob, op.p1, size_t(p->K) * es)) return fail(FLE_ERR_UNSUPPORTED, "op 0: out overlaps gamma or beta");
+    }
+    const bool fused = s == FLE_OK && plan->variant == V_THIN && plan->bm == 8 && p->M <= 4;  // (8 fp32 rows with the extra sums need more than 256 registers)
+    if (!fused) {
+        q.x = reinterpret_cast<const void *>(uintptr_t(256));  // stands for the copy: aligned, rows contiguous, overlapping nothing
+        q.ldx = p->K;
+        s = make_plan_core(&q, forced, forced_split, plan, nullptr);
+        if (s != FLE_OK) return s;
+        plan->ws_xhat_off = plan->ws_total;
+        plan->ws_total = round_up(plan->ws_total + size_t(p->M) * size_t(p->K) * es, 256);
+    }
+    plan->ln_pre = fused ? LN_PRE_FUSED : LN_PRE_PASS;
+    plan->ln_gamma = op.p0;
+    plan->ln_beta = op.p1;
+    plan->ln_eps = op.alpha;
+    return FLE_OK;
+}
+
+static fle_status make_plan_core(const fle_problem *p, int forced, int forced_split, Plan *plan, const fle_groups *grp) {
     if (!p) return fail(FLE_ERR_NULL, "problem is NULL");
     std::memset(plan, 0, sizeof *plan);
     if (p->dtype != FLE_F32 && p->dtype != FLE_BF16 && p->dtype != FLE_F16 && p->dtype != FLE_F8E4M3)
@@ -78,7 +126,8 @@ fle_status make_plan(const fle_problem *p, int forced, int forced_split, Plan *p
     const size_t xs = f8 ? 1 : es;         // bytes per element of x and W
     for (int i = 0; i < p->n_ops; ++i) {
         const fle_op &op = p->ops[i];
-        if (op.kind < FLE_BIAS || op.kind > FLE_MXSCALE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (op.kind < FLE_BIAS || op.kind > FLE_LAYERNORM_PRE) return fail(FLE_ERR_OP, "op %d: unknown kind %d", i, op.kind);
+        if (op.kind == FLE_LAYERNORM_PRE) return fail(FLE_ERR_UNSUPPORTED, "op %d: the LayerNorm of x must be the first entry of the list", i);
         if (op.kind == FLE_MXSCALE) {  // not an epilogue op: says how x and W are to be read
             if (i != 0) return fail(FLE_ERR_UNSUPPORTED, "op %d: the block scales of x and W must be the first entry of the list", i);
             if (!f8) return fail(FLE_ERR_UNSUPPORTED, "op %d: block scales need FLE_F8E4M3 operands", i);
@@ -411,11 +460,12 @@ using namespace fle;
 
 static void format_plan(const Plan &plan, char *buf, size_t n) {
     const char *dt = plan.op_dtype == FLE_F32 ? "f32" : plan.op_dtype == FLE_F16 ? "f16" : plan.op_dtype == FLE_F8E4M3 ? (plan.mx ? "f8mx" : "f8") : "bf16";
-    snprintf(buf, n, "variant=%s_%s_%s%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu",
+    snprintf(buf, n, "variant=%s_%s_%s%s%s tile=%dx%dx%d tiles=%lldx%lld split_k=%d row_op=%d np=%d staging=%s workspace=%zu%s",
              plan.variant == V_TILED ? (plan.groups ? "grouped_tiled" : "tiled") : plan.variant == V_SKINNY ? "skinny" : plan.variant == V_THIN ? "thin" : "general", dt,
              plan.variant == V_THIN && plan.bm == 8 ? "dot" : "mfma",
              plan.edge ? "+edge" : "", plan.w_stream ? "+wstream" : "", plan.bm, plan.bn, plan.bk, (long long)plan.tiles_m, (long long)plan.tiles_n, plan.split_k, plan.epi.row_kind,
-             plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total);
+             plan.np, plan.staging == ST_OUT ? "out" : plan.staging == ST_WS ? "workspace_f32" : "none", plan.ws_total,
+             plan.ln_pre == LN_PRE_FUSED ? " ln_pre=fused" : plan.ln_pre == LN_PRE_PASS ? " ln_pre=pass" : "");
 }
 
 static fle_status check_workspace(const fle_problem *p, const Plan &plan) {

@@ -71,6 +71,25 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     g.epi = e;
     g.x_scale = plan.x_scale;
     g.w_scale = plan.w_scale;
+    if (plan.ln_pre == LN_PRE_FUSED) {
+        g.ln_gamma = plan.ln_gamma; g.ln_beta = plan.ln_beta; g.ln_eps = plan.ln_eps;
+    } else if (plan.ln_pre == LN_PRE_PASS) {
+        // the normalised copy of x, rows contiguous, which the GEMM kernel then reads in place of x
+        LnArgs l{};
+        l.M = p->M; l.K = p->K; l.x = p->x; l.ldx = p->ldx; l.gamma = plan.ln_gamma; l.beta = plan.ln_beta; l.eps = plan.ln_eps;
+        l.dtype = p->dtype; l.dst = ws + plan.ws_xhat_off;
+        const uintptr_t all = reinterpret_cast<uintptr_t>(p->x) | reinterpret_cast<uintptr_t>(plan.ln_gamma) | reinterpret_cast<uintptr_t>(plan.ln_beta) | uintptr_t(p->ldx * int64_t(es));
+        l.vec = (all % 16 == 0 && p->K % int64_t(16 / es) == 0) ? 1 : 0;
+        if (p->M > 0 && p->K > 0) {
+            const bool in_regs = l.vec && p->K <= 16384;  // one wave per row, four rows per workgroup
+            const int64_t wgs_ln = in_regs ? (p->M + 3) / 4 : p->M;
+            void (*lnk)(LnArgs) = p->dtype == FLE_F32 ? ln_prologue<FLE_F32> : p->dtype == FLE_F16 ? ln_prologue<FLE_F16> : ln_prologue<FLE_BF16>;
+            hipLaunchKernelGGL(lnk, dim3(uint32_t(wgs_ln < 65536 ? wgs_ln : 65536)), dim3(256), 0, stream, l);
+            const fle_status ls = check_launch("LayerNorm pass launch");
+            if (ls != FLE_OK) return ls;
+        }
+        g.x = l.dst; g.ldx = p->K;
+    }
     if (e.row_kind < 0 || plan.staging == ST_OUT) { g.dst = p->out; g.ldd = p->ldo; g.dst_f32 = 0; g.dst_rel = plan.stage_rel; }
     else if (plan.staging == ST_WS) { g.dst = ws + plan.ws_y_off; g.ldd = p->N; g.dst_f32 = 1; }
     else { g.dst = nullptr; g.ldd = 0; g.dst_f32 = 0; }
@@ -116,6 +135,10 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
         auto pick = [&](auto dt_c) -> void (*)(GemmArgs) {
             constexpr int DT = decltype(dt_c)::value;
             if (plan.bm <= 8) {  // (the planner gives 5 .. 8 rows to this form for fp32 only)
+                if (plan.ln_pre == LN_PRE_FUSED) {  // (the planner fuses up to 4 rows)
+                    if (wide) return gemm_gemv<DT, 1, 1, true>;
+                    return p->M <= 1 ? gemm_gemv<DT, 1, 4, true> : p->M <= 2 ? gemm_gemv<DT, 2, 4, true> : gemm_gemv<DT, 4, 4, true>;
+                }
                 if constexpr (DT == FLE_F32)
                     if (p->M > 4) return gemm_gemv<DT, 8, 4>;
                 if (wide) return gemm_gemv<DT, 1, 1>;

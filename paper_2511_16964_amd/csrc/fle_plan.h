@@ -58,10 +58,16 @@ struct Plan {
     int32_t op_dtype;        // fle_dtype of x and W (differs from epi.dtype for fp8 problems only)
     int32_t mx;              // fp8 problem whose operands carry block scales (FLE_MXSCALE)
     const void *x_scale, *w_scale;
+    int32_t ln_pre;          // LayerNorm of x over K in front of the multiplication (FLE_LAYERNORM_PRE): LN_PRE_*
+    const void *ln_gamma, *ln_beta;
+    float ln_eps;
+    size_t ws_xhat_off;      // LN_PRE_PASS: the normalised copy of x, [M][K] of the dtype
     int64_t tiles_m, tiles_n;
     size_t ws_part_off, ws_y_off, ws_slab_off, ws_mid_off, ws_total;  // (ws_mid: fp32 [M,N] between two row ops)
     DevEpilogue epi;
 };
+
+enum { LN_PRE_NONE = 0, LN_PRE_FUSED = 1, LN_PRE_PASS = 2 };  // inside the dot-product kernel / a pass of its own in front of the GEMM kernel
 
 // Validates p (everything except workspace size) and fills plan.  Host only, no HIP calls.
 // groups: nullptr for a plain problem, else the row groups of a grouped one.

@@ -78,6 +78,8 @@ SHAPES = {
     "c5a": (torch.bfloat16, 16384, 16384, 4096),
     "c5b": (torch.bfloat16, 16384, 4096, 16384),
     "f2": (torch.float8_e4m3fn, 4096, 4096, 4096),   # c2 with x and W stored in fp8 (one scale per tensor)
+    "p1": (torch.bfloat16, 1, 4096, 4096),            # one token: LayerNorm over K, then Linear + bias + GELU-erf (launch-bound)
+    "p2": (torch.bfloat16, 4096, 4096, 4096),         # 4096 tokens: the same normalisation -> projection pair (compute-bound)
     "f3": (torch.float8_e4m3fn, 4096, 4096, 4096),   # ... in block-scaled fp8 (MXFP8: one power-of-two scale per 32 k)
 }
 
@@ -104,6 +106,11 @@ def make(name: str, seed: int = 0, M: int | None = None, N: int | None = None,
         sx, sw = float(np.abs(x).max()) / 448.0, float(np.abs(w).max()) / 448.0
         return Problem(name, dtype, _store(x / np.float32(sx), dtype), _store(w / np.float32(sw), dtype), _store(b, torch.bfloat16),
                        [("scale", float(np.float32(sx * sw))), ("bias",), ("relu",), ("scale", 0.5), ("residual", _store(r, torch.bfloat16))])
+    if name in ("p1", "p2"):   # a transformer block's normalisation -> projection pair: LayerNorm(x) W^T + b, GELU-erf
+        x = _normal(rng, (M, K), 0.25, 1.0); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
+        g = _normal(rng, (K,), 1.0, 0.02); be = _normal(rng, (K,), 0.0, 0.02)
+        return Problem(name, dtype, _store(x, dtype), _store(w, dtype), _store(b, dtype),
+                       [("layernorm_pre", _store(g, dtype), _store(be, dtype), 1e-5), ("bias",), ("gelu_erf",)])
     if name == "f3":    # c2's layer with block-scaled fp8 storage (the same values as c2 and f2, quantised block by block)
         x = _normal(rng, (M, K)); w = _uniform(rng, (N, K), 1 / 64); b = _uniform(rng, (N,), 1 / 64)
         r = _normal(rng, (M, N))
@@ -171,10 +178,12 @@ def mx_quantize(a: np.ndarray):
 
 
 def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds: list[str],
-                   integer: bool = False, mx: bool = False) -> Problem:
+                   integer: bool = False, mx: bool = False, ln_pre: bool = False, x_mean: float = 0.5) -> Problem:
     """A problem with an arbitrary epilogue list, for parity sweeps.  With
     ``integer`` every tensor holds small integers (exactly representable in
     bf16), which makes the elementwise chain bias/relu/scale(0.5)/residual exact.
+    ``ln_pre``: the list starts with ("layernorm_pre", gamma[K], beta[K], 1e-5), a LayerNorm of x over K in front of the
+    multiplication; the rows of x then have mean ``x_mean`` (and unit deviation), gamma ~ N(1, 0.1), beta ~ N(0, 0.1).
     ``mx`` (fp8 problems, K a multiple of 128): x and W are block-scaled; their magnitudes then vary from one
     block of 32 to the next by up to 2^12 (integer: the scales are random powers of two from 1/4 to 4 and the
     elements small integers, so every product and partial sum is still exact in fp32); the list starts with the
@@ -188,6 +197,9 @@ def random_problem(seed: int, M: int, N: int, K: int, dtype: torch.dtype, kinds:
         b = _uniform(rng, (N,), 0.5)
     ep = []
     io = io_dtype(dtype)
+    if ln_pre:
+        x = x + np.float32(x_mean)
+        ep.append(("layernorm_pre", _store(_normal(rng, (K,), 1.0, 0.1), io), _store(_normal(rng, (K,), 0.0, 0.1), io), 1e-5))
     if mx:
         assert dtype == F8 and K % 128 == 0
         if integer:

@@ -55,6 +55,8 @@ def oracle_rows(prob: inputs.Problem, rows=None) -> np.ndarray:
     if ep and ep[0][0] == "mxscale":   # block-scaled operands: the oracle multiplies the values they stand for
         sx = ep[0][1] if rows is None else ep[0][1][rows]
         x64, w64, ep = oracle.mx_dequantize(x64, sx.numpy()), oracle.mx_dequantize(w64, ep[0][2].numpy()), ep[1:]
+    if ep and ep[0][0] == "layernorm_pre":   # LayerNorm of x over K in front of the multiplication
+        x64, ep = oracle.layernorm_rows(x64, inputs.to_f64(ep[0][1]), inputs.to_f64(ep[0][2]), ep[0][3]), ep[1:]
     return oracle.fused_linear_epilogue(x64, w64, inputs.to_f64(prob.b), inputs.epilogue_f64(ep, rows))
 
 

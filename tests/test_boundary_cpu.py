@@ -756,3 +756,41 @@ def test_block_scaled_fp8_problems_validate_and_plan(L):
     from paper_2511_16964_amd.binding import FlePlanChoice
     c = FlePlanChoice(binding.VARIANTS["tiled128"], 2)
     assert L.fle_workspace_size_with(ctypes.byref(p), ctypes.byref(c), ctypes.byref(need)) == OK and need.value > 0  # split K keeps the scales
+
+
+def test_layernorm_in_front_of_the_multiplication_validates_and_plans(L):
+    """FLE_LAYERNORM_PRE: first entry only, no fp8 and no grouped form; a few rows plan the fused dot-product kernel
+    without workspace, other shapes a pass with M * K elements of workspace more than the same list without it."""
+    def plan_of(p):
+        need = ctypes.c_size_t(0)
+        st = L.fle_workspace_size(ctypes.byref(p), ctypes.byref(need))
+        buf = ctypes.create_string_buffer(256)
+        L.fle_last_plan(buf, 256)
+        return st, need.value, buf.value.decode()
+    lnp = op("layernorm_pre", 1e-5, 20 * G, 21 * G)
+    st, need, text = plan_of(problem(M=2, N=4096, K=4096, ops=[lnp, op("bias"), op("gelu_erf")]))
+    assert st == OK and need == 0 and "thin_bf16_dot" in text and "ln_pre=fused" in text
+    st, need, text = plan_of(problem(M=4, N=4096, K=4096, dtype=binding.F32, ops=[lnp]))
+    assert st == OK and need == 0 and "ln_pre=fused" in text
+    st, need, text = plan_of(problem(M=8, N=4096, K=4096, dtype=binding.F32, ops=[lnp]))
+    assert st == OK and need == 8 * 4096 * 4 and "thin_f32_dot" in text and "ln_pre=pass" in text   # more than 4 rows: the pass, then the same kernel
+    st, need, text = plan_of(problem(M=4096, N=4096, K=4096, ops=[lnp, op("bias")]))
+    assert st == OK and need == 4096 * 4096 * 2 and "tile=256x256" in text and "ln_pre=pass" in text
+    st0, need0, _ = plan_of(problem(M=512, N=1024, K=256, ops=[op("layernorm", 1e-5)]))
+    st, need, text = plan_of(problem(M=512, N=1024, K=256, ops=[lnp, op("layernorm", 1e-5)]))
+    assert st == OK and need == need0 + 512 * 256 * 2 and "ln_pre=pass" in text
+    p = problem(M=1024, N=1024, K=1024, ops=[lnp]); p.x = p.x + 2; p.ldx = 1027          # misaligned x: the copy is what the kernels read
+    st, need, text = plan_of(p)
+    assert st == OK and "tiled" in text and "ln_pre=pass" in text
+    assert validate(L, problem(M=64, N=64, K=64, ops=[op("bias"), lnp])) == E_UNSUP         # not first
+    assert validate(L, problem(M=512, N=512, K=512, dtype=binding.F8E4M3, ops=[lnp])) == E_UNSUP
+    assert validate(L, problem(M=64, N=64, K=64, ops=[op("layernorm_pre", float("nan"), 20 * G, 21 * G)])) == E_OP
+    assert validate(L, problem(M=64, N=64, K=64, ops=[op("layernorm_pre", 1e-5, 20 * G + 1, 21 * G)])) == E_ALIGN
+    assert validate(L, problem(M=64, N=64, K=64, ops=[op("layernorm_pre", 1e-5, 3 * G + 8, 21 * G)])) == E_UNSUP   # gamma inside out
+    assert validate(L, problem(M=64, N=64, K=64, ops=[op("layernorm_pre", 1e-5)])) == OK    # gamma and beta absent
+    p = problem(M=4096, N=4096, K=4096, ops=[lnp])
+    assert L.fle_run(ctypes.byref(p)) == E_WS                                               # the pass needs its workspace
+    # grouped problems refuse it
+    from paper_2511_16964_amd.binding import FleGroups
+    g = FleGroups(); g.n_groups, g.row_offsets, g.w_group_stride, g.b_group_stride = 2, 30 * G, 64 * 64, 64
+    assert L.fle_validate_grouped(ctypes.byref(problem(M=64, N=64, K=64, ops=[lnp])), ctypes.byref(g)) == E_UNSUP

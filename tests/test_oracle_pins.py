@@ -631,3 +631,22 @@ def test_mx_quantize_round_trips_within_an_e4m3_rounding():
     assert (amax[:, ::32][amax[:, ::32] > 0] >= 256 * scale[:, ::32][amax[:, ::32] > 0]).all() and (amax < 512 * scale)[amax > 0].all()   # e = floor(log2(max)) - 8
     assert (back[0, :32] == 0).all() and (back[1, 32:64] == a[1, 32:64]).all()
     assert s.dtype == torch.uint8 and s.shape == (8, 8) and s[0, 0] == 0
+
+
+def test_layernorm_rows_matches_torch_and_the_row_op():
+    """The LayerNorm that precedes the multiplication: against torch's CPU float64 layer_norm (a library routine with
+    the same definition), against the oracle's own row op over N applied to x I^T (independent C code, pinned above),
+    and on a row whose result is known in closed form."""
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((5, 48)) * 3.0 + 7.0
+    g, b = rng.standard_normal(48), rng.standard_normal(48)
+    got = oracle.layernorm_rows(x, g, b, 2.0 ** -10)   # (an eps that float32, in which the row op takes it, holds exactly)
+    ref = F.layer_norm(torch.from_numpy(x), (48,), torch.from_numpy(g), torch.from_numpy(b), 2.0 ** -10).numpy()
+    assert np.abs(got - ref).max() < 1e-13
+    via_row_op = oracle.fused_linear_epilogue(x, np.eye(48), None, [("layernorm", g, b, 2.0 ** -10)])
+    assert np.abs(got - via_row_op).max() < 1e-13
+    assert np.abs(oracle.layernorm_rows(x, None, None, 0.0).mean(axis=1)).max() < 1e-14
+    assert np.abs(oracle.layernorm_rows(x, None, None, 0.0).var(axis=1) - 1.0).max() < 1e-13
+    # the row (1, 3): mean 2, biased variance 1 -> (-1, 1) / sqrt(1 + eps)
+    two = oracle.layernorm_rows(np.array([[1.0, 3.0]]), np.array([2.0, 2.0]), np.array([0.5, -0.5]), 3.0)
+    assert np.array_equal(two, np.array([[-1.0 / 2.0 * 2.0 + 0.5, 1.0 / 2.0 * 2.0 - 0.5]]))
