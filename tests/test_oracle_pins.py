@@ -650,3 +650,31 @@ def test_layernorm_rows_matches_torch_and_the_row_op():
     # the row (1, 3): mean 2, biased variance 1 -> (-1, 1) / sqrt(1 + eps)
     two = oracle.layernorm_rows(np.array([[1.0, 3.0]]), np.array([2.0, 2.0]), np.array([0.5, -0.5]), 3.0)
     assert np.array_equal(two, np.array([[-1.0 / 2.0 * 2.0 + 0.5, 1.0 / 2.0 * 2.0 - 0.5]]))
+
+
+def test_non_finite_rows_follow_torch_float64():
+    """Rows holding +inf, -inf or NaN are outside the GPU's tested contract, but the oracle's branches for them (the
+    NaN-propagating row maximum, logsumexp of an infinite maximum) are code like any other: pinned against torch's
+    CPU float64 softmax and logsumexp, which take the same limits."""
+    inf, nan = float("inf"), float("nan")
+    rows = np.array([
+        [1.0, 2.0, -inf, 0.5],       # a -inf entry: probability 0
+        [-inf, -inf, -inf, -inf],    # all -inf: softmax NaN (0/0), logsumexp -inf
+        [1.0, inf, 3.0, 2.0],        # a +inf entry: logsumexp +inf, softmax NaN at the inf (inf - inf)
+        [1.0, nan, 3.0, 2.0],        # NaN anywhere poisons the row
+        [nan, 1.0, 2.0, 3.0],        # ... also in the first place
+        [0.0, 1.0, 2.0, 3.0],
+    ])
+    t = torch.from_numpy(rows)
+    # (each row enters as the bias of a zero product: through a matrix product an infinity times zero would be NaN already)
+    x0, w0 = np.zeros((1, 1)), np.zeros((4, 1))
+    sm = np.concatenate([oracle.fused_linear_epilogue(x0, w0, r.copy(), [("bias",), ("softmax",)]) for r in rows])
+    ref = torch.softmax(t, dim=-1).numpy()
+    assert np.array_equal(np.isnan(sm), np.isnan(ref))
+    assert np.allclose(sm[~np.isnan(ref)], ref[~np.isnan(ref)], rtol=1e-15, atol=0)
+    lse = np.concatenate([oracle.fused_linear_epilogue(x0, w0, r.copy(), [("bias",), ("logsumexp",)]).reshape(-1) for r in rows])
+    ref = torch.logsumexp(t, dim=-1).numpy()
+    assert np.array_equal(np.isnan(lse), np.isnan(ref)), (lse, ref)
+    fin = ~np.isnan(ref)
+    assert np.array_equal(np.isinf(lse[fin]), np.isinf(ref[fin])) and np.array_equal(np.sign(lse[fin & np.isinf(ref)]), np.sign(ref[fin & np.isinf(ref)]))
+    assert np.allclose(lse[fin & np.isfinite(ref)], ref[fin & np.isfinite(ref)], rtol=1e-15, atol=0)
