@@ -206,6 +206,9 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     FinArgs f{};
     f.M = p->M; f.N = p->N;
     f.np = plan.np; f.part_cols = plan.part_cols;
+    f.part_shift = 0;
+    while ((1 << f.part_shift) < plan.part_cols) ++f.part_shift;
+    if ((1 << f.part_shift) != plan.part_cols) return fail(FLE_ERR_UNSUPPORTED, "internal: partial width %d is not a power of two", plan.part_cols);
     f.partials = split ? r.partials : g.partials;
     f.out = p->out; f.ldo = p->ldo;
     f.epi = e;
@@ -235,8 +238,13 @@ fle_status launch(const fle_problem *p, const Plan &plan, const fle_groups *grp)
     const int64_t want = (items + 3) / 4;
     const dim3 fgrid(uint32_t(want < (int64_t(1) << 20) ? want : (int64_t(1) << 20)));
     void (*fin)(FinArgs);
-    if (e.row_kind == FLE_LAYERNORM) fin = (vec && gb_ok) ? finalize_rows<true, true> : finalize_rows<false, true>;
-    else fin = (vec && gb_ok) ? finalize_rows<true, false> : finalize_rows<false, false>;
+    const int fdt = e.dtype;
+    if (e.row_kind == FLE_LAYERNORM)
+        fin = !(vec && gb_ok) ? finalize_rows<false, true>
+              : fdt == FLE_BF16 ? finalize_rows<true, true, FLE_BF16> : fdt == FLE_F16 ? finalize_rows<true, true, FLE_F16> : finalize_rows<true, true, FLE_F32>;
+    else
+        fin = !(vec && gb_ok) ? finalize_rows<false, false>
+              : fdt == FLE_BF16 ? finalize_rows<true, false, FLE_BF16> : fdt == FLE_F16 ? finalize_rows<true, false, FLE_F16> : finalize_rows<true, false, FLE_F32>;
     hipLaunchKernelGGL(fin, fgrid, dim3(256), 0, stream, f);
     s = check_launch("row finalize launch");
     if (s != FLE_OK || !two) return s;

@@ -44,18 +44,35 @@ __device__ __forceinline__ void st8_2byte(void *p, int64_t i, int dtype, const f
 }
 
 // LNK: LayerNorm (true) or softmax (false); separate kernels so that each gets its own register budget.
-template <bool VEC, bool LNK>
+// DT: the storage dtype when known at compile time (the vector forms: the conversions then carry no run-time
+// choice), -1: read from the arguments.
+template <bool VEC, bool LNK, int DT = -1>
 __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
     constexpr int CH = 2048, IT = CH / 512;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int dtype = a.epi.dtype;
+    const int dtype = DT >= 0 ? DT : a.epi.dtype;
     const bool f32 = dtype == FLE_F32;
     constexpr bool ln = LNK;
     const int64_t N = a.N;
     const int64_t chunks = (N + CH - 1) / CH, items = a.M * chunks;
+    // item -> (row, first column).  (64-bit divisions cost over a hundred vector instructions each; so does the
+    // run-time choice of conversions that a dtype known at compile time avoids: c3's pass 34.4 -> 31.5 us with the
+    // cheaper combine of the partials.  Walking several items per wave with the next item's loads ahead: 34.1 us.)
+    auto place = [&](int64_t item, int64_t &row, int64_t &c0) {
+        if (items <= 0x7fffffff) {
+            const uint32_t r32 = uint32_t(item) / uint32_t(chunks);
+            row = r32;
+            c0 = int64_t(uint32_t(item) - r32 * uint32_t(chunks)) * CH;
+        } else {
+            row = item / chunks;
+            c0 = (item % chunks) * CH;
+        }
+    };
     for (int64_t item = int64_t(blockIdx.x) * 4 + wave; item < items; item += int64_t(gridDim.x) * 4) {
-        const int64_t row = item / chunks, c0 = (item % chunks) * CH;
+        int64_t row;
+        int64_t c0;
+        place(item, row, c0);
         const int64_t c1 = c0 + CH < N ? c0 + CH : N;
         float y[IT][8];
         if (VEC) {  // issue the loads before the partials are combined
@@ -98,7 +115,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                 if (n < c1) {
                     float *v = y[it];
                     // staged relative to the statistic (mean / maximum) of the partial the 8 columns lie in (part_cols is a multiple of 8)
-                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
+                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + (n >> a.part_shift)) * 2] : sub;
                     if (ln) {
                         float g[8], be[8];
 #pragma unroll
@@ -128,7 +145,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
             auto one = [&](int64_t n) {  // one element
                 const float yv = ld_elem(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype);
                 float v;
-                const float shift = a.y_rel ? sub - a.partials[(row * a.np + n / a.part_cols) * 2] : sub;
+                const float shift = a.y_rel ? sub - a.partials[(row * a.np + (n >> a.part_shift)) * 2] : sub;
                 if (ln) {
                     v = (yv - shift) * mul;
                     if (a.epi.row.p0) v *= ld_elem(a.epi.row.p0, n, dtype);
@@ -153,7 +170,7 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                         float v[8];
                         ld8(a.y, row * a.ldy + n, dtype, v);
                         float s0 = sub, s1 = sub;
-                        const int64_t p0 = n / a.part_cols, p1 = (n + 7) / a.part_cols;  // the 8 columns may straddle two partials
+                        const int64_t p0 = (n >> a.part_shift), p1 = ((n + 7) >> a.part_shift);  // the 8 columns may straddle two partials
                         if (a.y_rel) {
                             s0 = sub - a.partials[(row * a.np + p0) * 2];
                             s1 = sub - a.partials[(row * a.np + p1) * 2];
@@ -161,13 +178,13 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                         if (ln) {
 #pragma unroll
                             for (int e = 0; e < 8; ++e) {
-                                v[e] = (v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
+                                v[e] = (v[e] - (((n + e) >> a.part_shift) == p0 ? s0 : s1)) * mul;
                                 if (a.epi.row.p0) v[e] *= ld_elem(a.epi.row.p0, n + e, dtype);
                                 if (a.epi.row.p1) v[e] += ld_elem(a.epi.row.p1, n + e, dtype);
                             }
                         } else {
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - ((n + e) / a.part_cols == p0 ? s0 : s1)) * mul;
+                            for (int e = 0; e < 8; ++e) v[e] = __expf(v[e] - (((n + e) >> a.part_shift) == p0 ? s0 : s1)) * mul;
                         }
                         if (a.epi.n_post > 0) {
 #pragma unroll
