@@ -399,12 +399,17 @@ def grouped_fused_linear_epilogue(x, w, b, offsets, epilogue, out=None, workspac
 def fused_linear_epilogue(x, w, b, epilogue, out=None, workspace=None, variant="auto", split=0, table=None):
     """out = epilogue(x @ w.T) in one fused library call.
 
-    x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32, bfloat16 or float16).
+    x [M,K], w [N,K], b [N] or None: CUDA(HIP) tensors of one dtype (float32, bfloat16 or float16), or x and w in
+    float8_e4m3fn with b and everything else in bfloat16.
     epilogue: ordered list of ("bias",) ("scale", a) ("relu",) ("gelu_erf",) ("gelu_tanh",)
-    ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",)
-    ("store", t[M,N]): t receives a copy of the values at that point of the list (before the row op only).
+    ("residual", r[M,N]) ("layernorm", gamma|None, beta|None, eps) ("softmax",) ("logsumexp",), at most two of the
+    last three;
+    ("store", t[M,N]): t receives a copy of the values at that point of the list (before the first row op only);
+    as the first entry only: ("mxscale", sx[M,K/32], sw[N,K/32]): the fp8 operands are block-scaled, one uint8 E8M0
+    scale per 32 consecutive k (K a multiple of 128); ("layernorm_pre", gamma[K]|None, beta[K]|None, eps): LayerNorm
+    over K of every row of x in front of the multiplication.
     table: a ``TileTable`` of tuned plans (default: the library's cost model decides).
-    Returns a tensor of x's dtype: [M,N], or [M] when the list ends in logsumexp.
+    Returns a tensor of x's dtype (bfloat16 for fp8 operands): [M,N], or [M] when the list ends in logsumexp.
     """
     if not x.is_cuda:
         raise RuntimeError("fused_linear_epilogue runs on the GPU only; there is no CPU path")
