@@ -223,8 +223,9 @@ __device__ __forceinline__ Stat combine_sm(const Stat &p, const Stat &q) {
 // LayerNorm: Chan's update, lane-serial then a butterfly.  Softmax / logsumexp: the row maximum first
 // (exact in any order), then every partial sum rescaled to it once and added lane-serially and by
 // butterfly: one exp per partial instead of two per pairwise combine.
+// first: (LayerNorm) partial `lane` of the row if the caller has already loaded it (with the rest of what it reads), else nullptr.
 template <bool LN>
-__device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t row, int np, int part_cols, int64_t N, int lane) {
+__device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t row, int np, int part_cols, int64_t N, int lane, const float2 *first = nullptr) {
     Stat s;
     s.n = 0.0f;
     s.a = LN ? 0.0f : -INFINITY;
@@ -235,8 +236,13 @@ __device__ __forceinline__ Stat reduce_partials(const float *partials, int64_t r
             Stat q;
             const int64_t left = N - int64_t(p) * part_cols;
             q.n = float(left < part_cols ? left : part_cols);
-            q.a = pr[2 * p];
-            q.b = pr[2 * p + 1];
+            if (first && p == lane) {
+                q.a = first->x;
+                q.b = first->y;
+            } else {
+                q.a = pr[2 * p];
+                q.b = pr[2 * p + 1];
+            }
             s = combine_ln(s, q);
         }
 #pragma unroll

@@ -43,6 +43,18 @@ __device__ __forceinline__ void st8_2byte(void *p, int64_t i, int dtype, const f
     *reinterpret_cast<u32x4 *>(reinterpret_cast<uint16_t *>(p) + i) = o;
 }
 
+// 16 bytes of a 2-byte dtype (known at run time) as 8 fp32 values.
+__device__ __forceinline__ void unpack8_2byte(const u32x4 r, int dtype, float (&v)[8]) {
+    if (dtype == FLE_F16) {
+        const f16x8 h = __builtin_bit_cast(f16x8, r);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = float(h[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[2 * e] = __uint_as_float(r[e] << 16); v[2 * e + 1] = __uint_as_float(r[e] & 0xffff0000u); }
+    }
+}
+
 // LNK: LayerNorm (true) or softmax (false); separate kernels so that each gets its own register budget.
 // DT: the storage dtype when known at compile time (the vector forms: the conversions then carry no run-time
 // choice), -1: read from the arguments.
@@ -74,17 +86,55 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
         int64_t c0;
         place(item, row, c0);
         const int64_t c1 = c0 + CH < N ? c0 + CH : N;
+        // Everything the item reads goes out in one batch in front of the combine of the partials, as loaded
+        // (conversions later) and without a branch around any of it: a vector past the end of the row re-reads
+        // the row's last one.  (Loads inside per-vector conditions, each converted where it stood, came out as
+        // load, wait, convert, load, wait, convert: four round trips to memory per wave instead of one.)
         float y[IT][8];
-        if (VEC) {  // issue the loads before the partials are combined
+        [[maybe_unused]] u32x4 yr[VEC ? IT : 1][2], gr[VEC && LNK ? IT : 1], br[VEC && LNK ? IT : 1];
+        [[maybe_unused]] float pmean[IT];
+        const bool yf = f32 || a.y_f32;                       // staged values are fp32
+        constexpr bool early_gb = VEC && LNK && DT >= 0 && DT != FLE_F32;   // gamma / beta of a 2-byte dtype: 4 registers per vector
+        [[maybe_unused]] float2 part_first = make_float2(0.0f, 0.0f);
+        if (VEC) {
+            if constexpr (LNK) {  // this lane's partial of the row, in the same batch
+                if (lane < a.np) part_first = *reinterpret_cast<const float2 *>(a.partials + (row * a.np + lane) * 2);
+            }
+            int64_t nc[IT];
 #pragma unroll
             for (int it = 0; it < IT; ++it) {
                 const int64_t n = c0 + it * 512 + lane * 8;
-                if (n < c1) ld8(a.y, row * a.ldy + n, a.y_f32 ? FLE_F32 : dtype, y[it]);
+                nc[it] = n < c1 ? n : c1 - 8;
+            }
+            if (yf) {
+#pragma unroll
+                for (int it = 0; it < IT; ++it) {
+                    const u32x4 *q = reinterpret_cast<const u32x4 *>(reinterpret_cast<const float *>(a.y) + row * a.ldy + nc[it]);
+                    yr[it][0] = q[0];
+                    yr[it][1] = q[1];
+                }
+            } else {
+#pragma unroll
+                for (int it = 0; it < IT; ++it) yr[it][0] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.y) + row * a.ldy + nc[it]);
+            }
+            if (a.y_rel) {
+#pragma unroll
+                for (int it = 0; it < IT; ++it) pmean[it] = a.partials[(row * a.np + (nc[it] >> a.part_shift)) * 2];
+            }
+            if constexpr (early_gb) {
+                if (a.epi.row.p0) {
+#pragma unroll
+                    for (int it = 0; it < IT; ++it) gr[it] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.epi.row.p0) + nc[it]);
+                }
+                if (a.epi.row.p1) {
+#pragma unroll
+                    for (int it = 0; it < IT; ++it) br[it] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.epi.row.p1) + nc[it]);
+                }
             }
         }
         float sub, mul;  // out = (y - sub) * mul  (LayerNorm),  exp(y - sub) * mul  (softmax)
         if (ln) {
-            const Stat s = reduce_partials<true>(a.partials, row, a.np, a.part_cols, N, lane);
+            const Stat s = reduce_partials<true>(a.partials, row, a.np, a.part_cols, N, lane, VEC ? &part_first : nullptr);
             sub = s.a;
             mul = rsqrtf(s.b / float(N) + a.epi.row.alpha);
         } else {
@@ -114,14 +164,25 @@ __global__ __launch_bounds__(256) void finalize_rows(const FinArgs a) {
                 const int64_t n = c0 + it * 512 + lane * 8;
                 if (n < c1) {
                     float *v = y[it];
+                    if (yf) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { v[e] = __uint_as_float(yr[it][0][e]); v[4 + e] = __uint_as_float(yr[it][1][e]); }
+                    } else {
+                        unpack8_2byte(yr[it][0], dtype, y[it]);
+                    }
                     // staged relative to the statistic (mean / maximum) of the partial the 8 columns lie in (part_cols is a multiple of 8)
-                    const float shift = a.y_rel ? sub - a.partials[(row * a.np + (n >> a.part_shift)) * 2] : sub;
+                    const float shift = a.y_rel ? sub - pmean[it] : sub;
                     if (ln) {
                         float g[8], be[8];
 #pragma unroll
                         for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; }
-                        if (a.epi.row.p0) ld8(a.epi.row.p0, n, dtype, g);
-                        if (a.epi.row.p1) ld8(a.epi.row.p1, n, dtype, be);
+                        if constexpr (early_gb) {
+                            if (a.epi.row.p0) unpack8_2byte(gr[it], dtype, g);
+                            if (a.epi.row.p1) unpack8_2byte(br[it], dtype, be);
+                        } else {
+                            if (a.epi.row.p0) ld8(a.epi.row.p0, n, dtype, g);
+                            if (a.epi.row.p1) ld8(a.epi.row.p1, n, dtype, be);
+                        }
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = (v[e] - shift) * mul * g[e] + be[e];
                     } else {

@@ -82,11 +82,12 @@ def test_chain_kernel_leaves_room_for_all_workgroups(asm):
 
 
 def test_streaming_finalize_keeps_its_occupancy(asm):
-    """The LayerNorm finalize pass is a bandwidth-bound streaming kernel: it needs many waves per SIMD, so
-    its register count must stay low (a shared code path once pushed it to 149 and cost 40 % of its speed)."""
+    """The LayerNorm finalize pass is a streaming kernel: it needs several waves per SIMD, so its register count
+    must stay bounded (a shared code path once pushed it to 149 and cost 40 % of its speed; holding a whole item's
+    loads as one batch takes 116, four waves per SIMD, and measured faster than 79 with the loads one by one)."""
     props = kernel_props(asm)
     ln = [v for k, v in props.items() if "finalize_rowsILb1ELb1" in k]
-    assert len(ln) == 3 and all(v["vgpr"] <= 96 and v["scratch"] == 0 for v in ln), ln   # one per storage dtype
+    assert len(ln) == 3 and all(v["vgpr"] <= 128 and v["scratch"] == 0 for v in ln), ln   # one per storage dtype
 
 
 def test_main_loop_uses_the_intended_instructions(asm):
