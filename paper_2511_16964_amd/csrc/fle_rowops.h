@@ -373,8 +373,76 @@ __global__ __launch_bounds__(256) void ln_prologue(const LnArgs a) {
     constexpr int dtype = DT;
     constexpr int W = DT == FLE_F32 ? 4 : 8;  // elements per 16 bytes
     constexpr int ES = DT == FLE_F32 ? 4 : 2;
+    constexpr int NVR = 8;  // vectors of 16 bytes per lane that the register form holds: rows of up to 4096 (fp32: 2048) elements
+    if (a.vec && K <= int64_t(64) * W * NVR) {
+        // One wave per row, the row read once: all of a lane's vectors requested in one batch, without a branch (a
+        // vector past the end of the row re-reads the row's last one and is left out of the sums), and kept as
+        // loaded, 4 registers each; each of the three phases converts them anew.  gamma and beta come in two batches
+        // of four vectors each.
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        for (int64_t row = int64_t(blockIdx.x) * 4 + wave; row < a.M; row += int64_t(gridDim.x) * 4) {
+            const char *src = reinterpret_cast<const char *>(a.x) + row * a.ldx * ES;
+            u32x4 raw[NVR];
+            int64_t kc[NVR];
+#pragma unroll
+            for (int i = 0; i < NVR; ++i) {
+                const int64_t k = (int64_t(i) * 64 + lane) * W;
+                kc[i] = k < K ? k : K - W;
+                raw[i] = *reinterpret_cast<const u32x4 *>(src + kc[i] * ES);
+            }
+            float s = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NVR; ++i) {
+                float v[8];
+                unpack_vec<DT>(raw[i], v);
+                float part = 0.0f;
+#pragma unroll
+                for (int e = 0; e < W; ++e) part += v[e];
+                s += (int64_t(i) * 64 + lane) * W < K ? part : 0.0f;
+            }
+            const float mean = wave_allreduce_sum(s) / float(K);
+            float m2 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NVR; ++i) {
+                float v[8];
+                unpack_vec<DT>(raw[i], v);
+                float part = 0.0f;
+#pragma unroll
+                for (int e = 0; e < W; ++e) part += (v[e] - mean) * (v[e] - mean);
+                m2 += (int64_t(i) * 64 + lane) * W < K ? part : 0.0f;
+            }
+            const float rstd = rsqrtf(wave_allreduce_sum(m2) / float(K) + a.eps);
+#pragma unroll
+            for (int h = 0; h < NVR; h += 4) {
+                u32x4 gr[4], br[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    gr[j] = br[j] = u32x4{0u, 0u, 0u, 0u};
+                    if (a.gamma) gr[j] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(a.gamma) + kc[h + j] * ES);
+                    if (a.beta) br[j] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(a.beta) + kc[h + j] * ES);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t k = (int64_t(h + j) * 64 + lane) * W;
+                    float v[8], g[8], be[8], o[8];
+                    unpack_vec<DT>(raw[h + j], v);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { g[e] = 1.0f; be[e] = 0.0f; }
+                    if (a.gamma) unpack_vec<DT>(gr[j], g);
+                    if (a.beta) unpack_vec<DT>(br[j], be);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = (v[e] - mean) * rstd * g[e] + be[e];
+                    if (k < K) {
+                        if constexpr (DT == FLE_F32) *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.dst) + row * K + k) = f32x4{o[0], o[1], o[2], o[3]};
+                        else st8_2byte(a.dst, row * K + k, dtype, o);
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (a.vec && K <= 16384) {
-        // one wave per row, three sweeps of 16-byte loads; the second and third find the row in the CU's own cache
+        // (longer rows) one wave per row, three sweeps of 16-byte loads; the second and third find the row in the CU's own cache
         // (holding it in registers instead, 128 of them at 8192 elements, left one or two waves per SIMD and
         // nothing to cover the loads: 42 us against torch's 23 on 4096 x 4096)
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
