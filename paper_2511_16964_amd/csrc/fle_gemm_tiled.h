@@ -760,6 +760,7 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
     const int p_idx = int(n_wave / WN);
     const int64_t cols_left = N - n_wave;
     const float cnt = float(cols_left < WN ? cols_left : WN);
+    const float inv_cnt = 1.0f / cnt;  // (exact for a full wave tile; the partial's M2 is taken about the mean as computed, so an ulp in it costs nothing)
 
     // One 32-row block.  FULL: all of this wave's rows and columns lie inside the matrix, and nothing in the block
     // is masked: every store is issued, unconditionally, so their number is known (see the residual below).
@@ -913,44 +914,52 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                 }
             }
 
-            // row-reduction partials over this wave's WN columns, from the unrounded fp32 values
+            // row-reduction partials over this wave's WN columns, from the unrounded fp32 values.  (The choice between the
+            // two kinds of partial is made once, around the four row groups, not inside each: the compiler then interleaves
+            // the four chains of cross-lane steps, each of which waits two cycles on the one before.)
             float part_max[NIT];  // softmax: the partial's maximum per row of this block
             if (a.epi.row_kind >= 0) {
                 const bool ln = a.epi.row_kind == FLE_LAYERNORM;
+                float s0[NIT], s1[NIT];
+                if (ln) {
+                    float sum[NIT];
     #pragma unroll
-                for (int it = 0; it < NIT; ++it) {
-                    const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
-                    float s0, s1;
-                    if (ln) {
-                        float sum = 0.0f;
+                    for (int it = 0; it < NIT; ++it) {
+                        sum[it] = 0.0f;
     #pragma unroll
                         for (int hc = 0; hc < NH; ++hc)
-                            if (n_ok[hc]) {
+                            if (FULL || n_ok[hc]) {
                                 if constexpr (EDGE) {
     #pragma unroll
                                     for (int e = 0; e < 4; ++e)
-                                        if (n_col[hc] + e < N) sum += v[it][hc][e];
+                                        if (n_col[hc] + e < N) sum[it] += v[it][hc][e];
                                 } else {
-                                    sum += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
+                                    sum[it] += (v[it][hc][0] + v[it][hc][1]) + (v[it][hc][2] + v[it][hc][3]);
                                 }
                             }
-                        sum = row16_allreduce<false>(sum);
-                        const float mean = sum / cnt;
+                    }
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) s0[it] = row16_allreduce<false>(sum[it]) * inv_cnt;
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
                         float m2 = 0.0f;
     #pragma unroll
                         for (int hc = 0; hc < NH; ++hc)
-                            if (n_ok[hc])
+                            if (FULL || n_ok[hc])
     #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - mean) * (v[it][hc][e] - mean);
-                        m2 = row16_allreduce<false>(m2);
-                        s0 = mean;
-                        s1 = m2;
-                    } else {
+                                    if (!EDGE || n_col[hc] + e < N) m2 += (v[it][hc][e] - s0[it]) * (v[it][hc][e] - s0[it]);
+                        s1[it] = m2;
+                    }
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) s1[it] = row16_allreduce<false>(s1[it]);
+                } else {
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
                         float mx = -INFINITY;
     #pragma unroll
                         for (int hc = 0; hc < NH; ++hc)
-                            if (n_ok[hc]) {
+                            if (FULL || n_ok[hc]) {
                                 if constexpr (EDGE) {
     #pragma unroll
                                     for (int e = 0; e < 4; ++e)
@@ -959,20 +968,29 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
                                     mx = fmaxf(fmaxf(mx, fmaxf(v[it][hc][0], v[it][hc][1])), fmaxf(v[it][hc][2], v[it][hc][3]));
                                 }
                             }
-                        mx = row16_allreduce<true>(mx);
+                        s0[it] = mx;
+                    }
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) s0[it] = row16_allreduce<true>(s0[it]);
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
                         float se = 0.0f;
     #pragma unroll
                         for (int hc = 0; hc < NH; ++hc)
-                            if (n_ok[hc])
+                            if (FULL || n_ok[hc])
     #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - mx);
-                        se = row16_allreduce<false>(se);
-                        s0 = mx;
-                        s1 = se;
+                                    if (!EDGE || n_col[hc] + e < N) se += __expf(v[it][hc][e] - s0[it]);
+                        s1[it] = se;
                     }
-                    part_max[it] = s0;
-                    if (cl == 0 && m < M) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0, s1);
+    #pragma unroll
+                    for (int it = 0; it < NIT; ++it) s1[it] = row16_allreduce<false>(s1[it]);
+                }
+    #pragma unroll
+                for (int it = 0; it < NIT; ++it) {
+                    const int64_t m = m_blk + 16 * HF + 4 * it + rsub;
+                    part_max[it] = s0[it];
+                    if (cl == 0 && (FULL || m < M)) *reinterpret_cast<float2 *>(a.partials + (m * a.np + p_idx) * 2) = make_float2(s0[it], s1[it]);
                 }
                 if (a.dst_rel) {
     #pragma unroll
