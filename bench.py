@@ -29,14 +29,19 @@ KERNEL_SOURCES = os.path.join(ROOT, "paper_2511_16964_amd", "csrc")
 
 
 def kernel_source_hash():
-    """One hash over the library's sources: the counters in profiles/traffic.json only describe the kernels
-    they were taken from."""
+    """One hash over the library's sources, comments and white space left out: the counters in
+    profiles/traffic.json only describe the kernels they were taken from."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in sorted(os.listdir(KERNEL_SOURCES)):
         if name.endswith((".h", ".hip", ".cpp")):
+            text = open(os.path.join(KERNEL_SOURCES, name), "r", encoding="utf-8", errors="replace").read()
+            # (string literals in these sources hold neither comment markers nor significant runs of blanks)
+            text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+            text = re.sub(r"//[^\n]*", " ", text)
             h.update(name.encode())
-            h.update(open(os.path.join(KERNEL_SOURCES, name), "rb").read())
+            h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

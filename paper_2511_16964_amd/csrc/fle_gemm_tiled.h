@@ -1,23 +1,24 @@
-// The tiled MFMA GEMM (bf16, fp16 and fp32 operands) with the fused epilogue.
+// The tiled MFMA GEMM (bf16, fp16, fp32, fp8 and block-scaled fp8 operands) with the fused epilogue.
 #pragma once
 #include "fle_device_common.h"
 
 namespace fle {
 
 // ------------------------------------------------------------------ tiled MFMA GEMM
-// Block tile BM x BN (rows of x, rows of W), K step 128 bytes (64 bf16 / fp16 or 32 fp32), 4 waves
-// as 2 x 2, each wave owning (BM/2) x (BN/2) outputs as 32x32 accumulator tiles of
-// v_mfma_f32_32x32x16_bf16 / _f16 (fp32 operands: four v_mfma_f32_32x32x2_f32 per fragment pair).
+// Block tile BM x BN (rows of x, rows of W), K step 128 bytes of every row (64 bf16 / fp16, 32 fp32, 128 fp8),
+// 4 waves as 2 x 2, each wave owning (BM/2) x (BN/2) outputs: as 16x16 accumulator tiles of
+// v_mfma_f32_16x16x32_bf16 / _f16 for the 2-byte dtypes, as 32x32 tiles of v_mfma_f32_32x32x2_f32 (four per
+// fragment pair) for fp32 and of v_mfma_f32_32x32x64_f8f6f4 (plain or block-scaled) for fp8.
 //
 // Main loop.  Operand tiles go HBM -> LDS by buffer loads that write LDS directly (no
 // registers), two stages deep.  A stage row is 128 bytes = 8 chunks of 16 bytes, stored at chunk
 // position c ^ g(row), g(row) = (row & 7) ^ ((row >> 3) & 1): the 16-byte reads of an MFMA
-// fragment (32 consecutive rows, one logical chunk) then hit every LDS bank once.  Within a
-// K step the copy instructions for the next stage and the fragment reads for the next
-// 16-wide k slice are issued one at a time in the gaps between MFMAs (pinned with
+// fragment (consecutive rows, one logical chunk) then hit every LDS bank once.  Within a
+// K step the copy instructions for a later stage and the fragment reads for the next
+// k slice are issued one at a time in the gaps between MFMAs (pinned with
 // sched_barrier): a wave issues in order, so a burst of memory instructions would otherwise
-// leave the matrix pipe idle while the LDS and texture paths accept them.  The copies all go
-// out in the first half of the K step, which gives them most of a K step to land.
+// leave the matrix pipe idle while the LDS and texture paths accept them.  Each of the three
+// loops below says where its copies and reads go and why.
 //
 // Epilogue.  One 32-row block of the wave's accumulators at a time is staged through LDS as
 // fp32 and read back row-contiguous: a lane then owns 4 (or 2 x 4) consecutive columns of one

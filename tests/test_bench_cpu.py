@@ -45,3 +45,18 @@ def test_summarize_traffic_scales_by_the_calibration_copy(tmp_path, monkeypatch)
     w = json.load(open(tmp_path / "traffic.json"))["workloads"]["c2"]
     assert abs(w["fetch_scale"] - 2.0) < 1e-9 and abs(w["write_scale"] - 1.0) < 1e-9
     assert abs(w["read_bytes"] - 1000 * 1024 * 2.0) < 1e-3 and abs(w["write_bytes"] - 500 * 1024) < 1e-3
+
+
+def test_kernel_hash_ignores_comments_and_white_space(tmp_path, monkeypatch):
+    """A comment edit does not change what the counters describe; a code edit does."""
+    sys.path.insert(0, ROOT)
+    import bench
+    d = tmp_path / "csrc"
+    d.mkdir()
+    monkeypatch.setattr(bench, "KERNEL_SOURCES", str(d))
+    (d / "k.h").write_text("// one\nint f(int a) { return a + 1; }  /* two */\n")
+    h0 = bench.kernel_source_hash()
+    (d / "k.h").write_text("// another comment\n\nint f(int a)   {\n    return a + 1;\n}\n")
+    assert bench.kernel_source_hash() == h0
+    (d / "k.h").write_text("int f(int a) { return a + 2; }\n")
+    assert bench.kernel_source_hash() != h0
