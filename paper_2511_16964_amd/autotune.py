@@ -20,28 +20,34 @@ CANDIDATES = [("auto", 0)] + [(v, s) for v in ("tiled256", "tiled128") for s in 
     [("skinny", 0), ("skinny128", 0), ("skinny256", 0), ("skinnyseq", 0), ("thin", 0), ("general", 0)]
 
 
-def time_call(call, budget_ms=6.0):
+_flush = None
+
+
+def time_call(call, iters=12):
+    """Median time of one call in microseconds, each call timed on its own behind an overwrite of 768 MB that
+    evicts L2 and the Infinity Cache: in a network a layer's weights are read once per pass, and a candidate that
+    only wins because the same 100 - 250 MB of weights stay in the 256 MB cache from one timed call to the next (the
+    tiled kernels against the streaming ones, up to 20 % in a back-to-back loop) would be the wrong choice there."""
+    global _flush
+    if _flush is None:
+        _flush = torch.empty(768 << 20, dtype=torch.uint8, device="cuda:0")
     call.run()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(); call.run(); e1.record(); torch.cuda.synchronize()
-    one = max(e0.elapsed_time(e1), 1e-3)
-    iters = int(max(3, min(200, budget_ms / one)))
-    best = float("inf")
-    for _ in range(2):
-        e0.record()
-        for _ in range(iters):
-            call.run()
-        e1.record()
+    times = []
+    for _ in range(iters):
+        _flush.fill_(1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); call.run(); e1.record()
         torch.cuda.synchronize()
-        best = min(best, e0.elapsed_time(e1) / iters)
-    return best * 1e3   # microseconds
+        times.append(e0.elapsed_time(e1))
+    times.sort()
+    return times[len(times) // 2] * 1e3
 
 
 def tune(shapes, dtypes, log=print):
     dev = torch.device("cuda:0")
     table = binding.TileTable(meta={"device": torch.cuda.get_device_name(0), "made": time.strftime("%Y-%m-%d"),
-                                    "unit": "microseconds per call", "library_version": binding.lib().fle_version()})
+                                    "unit": "microseconds per call, caches evicted before each", "library_version": binding.lib().fle_version()})
     for dt in dtypes:
         for (M, N, K) in shapes:
             x = torch.randn(M, K, device=dev).to(dt)
