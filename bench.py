@@ -136,8 +136,10 @@ class ClockSampler:
     roofline is priced against should be read with the clock it was measured at.  Best effort: any failure
     (library missing, no permission) just leaves the fields out."""
 
-    def __init__(self):
+    def __init__(self, enabled=True):
         self.samples, self._stop, self._thread, self._h = [], False, None, None
+        if not enabled:
+            return
         try:
             import amdsmi
             amdsmi.amdsmi_init()
@@ -344,6 +346,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "f2", "f3", "p1", "p2", "g1", "g2", "m1", "m2", "m3", "a1", "a2", "l1"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clocks", action="store_true", help="do not sample clock and power from a host thread during the timed loops")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, to scale FETCH_SIZE / WRITE_SIZE)")
@@ -591,7 +594,7 @@ def main():
         for _ in range(10):
             step()
         torch.cuda.synchronize()
-    with ClockSampler() as clocks:
+    with ClockSampler(not args.no_clocks) as clocks:
         wall_ms, ev_ms = time_loop(torch, step, args.steps, args.warmup)
         repeats = [ev_ms] + [time_loop(torch, step, args.steps, 0)[1] for _ in range(2)]  # spread only; `value` uses the first
     flush = torch.empty(768 << 20, dtype=torch.uint8, device=dev)
