@@ -318,6 +318,16 @@ static fle_status make_plan_core(const fle_problem *p, int forced, int forced_sp
         if ((gemv_auto || thin_auto) && forced_split <= 1) variant = V_THIN;
         // (fp32 operands keep the matrix pipe about as busy as the memory system: worth it from 2^24 weights on,
         // 2^25 up to 16 rows where the general kernel's 16 x 16 tiles are as fast; 8192^2 at 16 rows 83 -> 60 us)
+        // 65 .. 128 rows of a 2-byte dtype: the skinny kernel with 64 rows at once on a 128-wide K step.  Measured with
+        // the weights coming from memory, as they do when a layer is used once per pass: 128 x 16384 x 4096 42.5 us
+        // against 77.0 us for the 128 tile with K split, 128 x 4096 x 16384 50.4 against 74.4, 128 x 4096 x 4096 20.7
+        // against 28.2; in a back-to-back loop, where up to 256 MB of weights stay in the Infinity Cache for the
+        // tiled kernel's cacheable copies, within 12 % either way.  (192 .. 256 rows: 20 - 35 % faster from memory
+        // but 35 - 50 % slower back to back; left to the tuned table.)
+        else if (skinny_ok && !f32 && M > 64 && M <= 128 && K % 128 == 0 && N >= 2048 && N * K >= (int64_t(1) << 22) && forced_split <= 1) {
+            variant = V_SKINNY;
+            forced_bk = 128;
+        }
         else if (skinny_ok && ((M <= 64 && N >= 2048 && N * K >= (int64_t(1) << (f32 ? (M <= 16 ? 25 : 24) : 22))) || (!f32 && M <= 128 && K % 256 == 0 && N >= 8192 && N * K >= (int64_t(1) << 27)))) variant = V_SKINNY;
         else {
             // The general kernel: about 4 us of launch and latency, then either its throughput (55 TFLOP/s on

@@ -279,9 +279,15 @@ def test_split_k_planning(L):
         text, need = plan_of(problem(M=M, N=N, K=K))
         assert "tile=256x256" in text and split(text) == 1 and need == 0, text
     # one tile row and a long K: split, and the slabs are counted in the workspace
+    text, need = plan_of(problem(M=192, N=4096, K=4096))
+    s = split(text)
+    assert "tiled" in text and s > 1 and need == s * 192 * 4096 * 4, text
+    # 65 .. 128 rows of a 2-byte dtype: the streaming kernel, 64 rows at once on a 128-wide K step (fp32: still tiled)
     text, need = plan_of(problem(M=128, N=4096, K=4096))
     s = split(text)
-    assert "tiled" in text and s > 1 and need == s * 128 * 4096 * 4, text
+    assert "skinny" in text and "tile=64x128x128" in text and s > 1 and need == s * 128 * 4096 * 4, text
+    text, need = plan_of(problem(M=128, N=4096, K=4096, dtype=binding.F32))
+    assert "tiled" in text, text
     text, need = plan_of(problem(M=16, N=4096, K=4096))
     assert "skinny" in text and split(text) > 1 and need == split(text) * 16 * 4096 * 4, text
     # many small tiles and a short K: the 128 tile without a split
