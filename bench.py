@@ -348,6 +348,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-clocks", action="store_true", help="do not sample clock and power from a host thread during the timed loops")
     ap.add_argument("--no-eager", action="store_true")
+    ap.add_argument("--no-constant-run", action="store_true",
+                    help="(c2, c3) skip the extra loop on constant operands that reads the chip's power limit; profile runs use this so that every dispatch of a trace is a call on the workload's own data")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy a few times (known traffic, to scale FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--summarize-traffic", nargs="+", metavar="DIR",
@@ -370,6 +372,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
+    const_calls = []   # (c2, c3) the same calls on constant operands, timed after the real ones
     to = lambda t: None if t is None else t.to(dev)
     dev_ep = lambda ep: [tuple(to(a) if isinstance(a, torch.Tensor) else a for a in e) for e in ep]
 
@@ -519,6 +522,9 @@ def main():
             eager = eager_fn(torch, F, deq(xg, ep[0][1]), deq(wg, ep[0][2]), bg, ep[1:])
         else:
             eager = eager_fn(torch, F, xg.to(torch.bfloat16), wg.to(torch.bfloat16), bg, ep) if f8 else eager_fn(torch, F, xg, wg, bg, ep)
+        if prob.dtype == torch.bfloat16 and args.workload in ("c2", "c3") and not args.no_constant_run:
+            # the same call on constant x and W: identical instruction stream, no switching activity in the multipliers
+            const_calls = [binding.Call(torch.ones_like(xg), torch.full_like(wg, 1.0 / 64), bg, ep)]
         es = 2 if prob.dtype in (torch.bfloat16, torch.float8_e4m3fn) else 4     # b, residual, gamma, beta, out
         xs = 1 if f8 else es                                                       # x, W
         alg_bytes = xs * (prob.M * prob.K + prob.N * prob.K) + es * (prob.M * prob.N + (prob.N if bg is not None else 0)
@@ -527,6 +533,10 @@ def main():
 
     def step():
         for c in calls:
+            c.run()
+
+    def const_step():
+        for c in const_calls:
             c.run()
 
     # ---- validity gate: a few rows against the oracle before any timing is reported
@@ -620,6 +630,14 @@ def main():
                                  "how": "one event pair and one synchronisation per call, L2 and Infinity Cache evicted (768 MB overwritten) before each",
                                  "tflops_at_mean": flops / (cold_mean * 1e-3) / 1e12},
     }
+    if const_calls:
+        # How much of the distance to the nominal peak is the chip's power limit and not the kernel: with random
+        # operands the sustained clock sits well under 2.4 GHz at the socket's power limit; with constant operands
+        # the same launches run at the full clock.  Context only; `value` is the figure on the workload's own data.
+        with ClockSampler(not args.no_clocks) as cclocks:
+            _, cev = time_loop(torch, const_step, args.steps, min(args.warmup, 100))
+        out["constant_operands"] = {"ms_per_step": cev, "tflops": flops / (cev * 1e-3) / 1e12, "frac_of_peak": flops / (cev * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                    "clocks": cclocks.summary(), "what": "the same calls on x = 1, W = 1/64 (every product identical): not a result, a reading of the power limit"}
     hbm_bound = args.workload in ("c4", "g2", "m1", "m2", "m3", "p1")
     if hbm_bound:
         a = alg_bytes / (ev_ms * 1e-3) / 1e9

@@ -504,7 +504,14 @@ __device__ __forceinline__ void gemm_tiled_body(const GemmArgs &a, const TileRef
 #pragma unroll
         for (int i = 0; i < TM16; ++i)
 #pragma unroll
-            for (int j = 0; j < TN16; ++j) acc16[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int j = 0; j < TN16; ++j) {
+                acc16[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                // The zeros are written here, in front of the wait states below.  Left free, the compiler may sink
+                // each write to just before the first matrix instruction that reads it (seen when the first K steps
+                // were peeled out of the loop); that instruction is inline asm, so the hazard recognizer puts no wait
+                // states between the two and the instruction reads a stale accumulator.
+                asm volatile("" : "+a"(acc16[i][j]));
+            }
         asm volatile("s_nop 7");
         u32x4 fw[2][TN16], fx[2][TM16];
         constexpr int NMF = TM16 * TN16, NDS = TM16 + TN16, QD = NMF / NDS;  // MFMAs per slice, fragment reads per slice, MFMAs per read
