@@ -279,7 +279,9 @@ static fle_status make_plan_core(const fle_problem *p, int forced, int forced_sp
     auto tiled_cost = [&](int tile, int64_t sp) -> double {
         const int64_t tiles = ((M + tile - 1) / tile) * ((N + tile - 1) / tile), wgs = tiles * sp;
         const int64_t slots = tile == 128 ? 512 : 256, rounds = (wgs + slots - 1) / slots;
-        const double per_step = f32 ? (tile == 256 ? 7.8 : wgs > 256 ? 3.9 : 1.95) : (tile == 256 ? 1.45 : wgs > 256 ? 0.85 : 0.6);
+        // (a 256 tile whose K is split over no more workgroups than there are CUs measured 1.3 per step: 768 .. 2048 x
+        // 4096 x 16384 with K split in 2 or 4 came out 10 - 26 % ahead of the 128 tile where 1.45 said the opposite)
+        const double per_step = f32 ? (tile == 256 ? 7.8 : wgs > 256 ? 3.9 : 1.95) : (tile == 256 ? (sp > 1 && wgs <= 256 ? 1.3 : 1.45) : wgs > 256 ? 0.85 : 0.6);
         // in K steps; two co-resident 128 tiles hide part of each other's epilogue
         const double fixed = f32 ? (tile == 256 ? 1.5 : 3.5) : (tile == 256 ? 10.5 : wgs > 256 ? 7.0 : 8.0);
         double t = double(rounds) * (double((tiled_steps + sp - 1) / sp) + fixed) * per_step;

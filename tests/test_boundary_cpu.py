@@ -290,6 +290,10 @@ def test_split_k_planning(L):
     assert "tiled" in text, text
     text, need = plan_of(problem(M=16, N=4096, K=4096))
     assert "skinny" in text and split(text) > 1 and need == split(text) * 16 * 4096 * 4, text
+    # a long K and too few 256 tiles for the chip: the 256 tile with K split until the workgroups fill it (measured ahead of the 128 tile)
+    for M, sp in ((768, 4), (1024, 4), (1536, 2), (2048, 2)):
+        text, need = plan_of(problem(M=M, N=4096, K=16384))
+        assert "tile=256x256" in text and split(text) == sp and need == sp * M * 4096 * 4, text
     # many small tiles and a short K: the 128 tile without a split
     text, need = plan_of(problem(M=512, N=16384, K=1024))
     assert "tile=128x128" in text and split(text) == 1 and need == 0, text
