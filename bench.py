@@ -634,6 +634,11 @@ def main():
         # How much of the distance to the nominal peak is the chip's power limit and not the kernel: with random
         # operands the sustained clock sits well under 2.4 GHz at the socket's power limit; with constant operands
         # the same launches run at the full clock.  Context only; `value` is the figure on the workload's own data.
+        settle_end = time.perf_counter() + 1.5   # (the driver refreshes its clock and power readings about once a second)
+        while time.perf_counter() < settle_end:
+            for _ in range(10):
+                const_step()
+            torch.cuda.synchronize()
         with ClockSampler(not args.no_clocks) as cclocks:
             _, cev = time_loop(torch, const_step, args.steps, min(args.warmup, 100))
         out["constant_operands"] = {"ms_per_step": cev, "tflops": flops / (cev * 1e-3) / 1e12, "frac_of_peak": flops / (cev * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -664,6 +669,11 @@ def main():
                 mx, mw = mx.to(torch.bfloat16), mw.to(torch.bfloat16)
             mm_wall, mm_ev = time_loop(torch, lambda: F.linear(mx, mw), max(10, args.steps // 4), 5)
             out["eager"]["bare_matmul_first_call_tflops"] = probs[0].flops / (mm_wall * 1e-3) / 1e12
+            if const_calls:   # the vendor GEMM alone on the same constant operands, for the same reading of the power limit
+                cx, cw = const_calls[0]._tensors[0], const_calls[0]._tensors[1]
+                _, cmm_ev = time_loop(torch, lambda: F.linear(cx, cw), max(10, args.steps // 4), 50)
+                out["constant_operands"]["bare_matmul_ms"] = cmm_ev
+                out["constant_operands"]["bare_matmul_tflops"] = probs[0].flops / (cmm_ev * 1e-3) / 1e12
     if not args.no_cpu_baseline:
         if grouped:
             out["cpu_baseline"] = cpu_baseline_grouped(gp, inputs)
