@@ -652,6 +652,11 @@ def main():
         a = flops / (ev_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak, "traffic": measured_traffic(args.workload)}
     out["roofline"]["kernel"] = "all kernels of one step (event time over the timed region / steps)"
+    cs = clocks.summary()
+    if not hbm_bound and cs and cs["gfx_clock_mhz"]["last"]:
+        # context: the same achieved rate against the matrix peak at the clock the chip actually held (it is power-limited
+        # on this data); `frac` above stays the fraction of the nominal 2.4 GHz peak
+        out["roofline"]["frac_at_sampled_clock"] = out["roofline"]["frac"] * 2400.0 / float(cs["gfx_clock_mhz"]["last"])
     out["algorithmic_bytes"] = alg_bytes
 
     if not args.no_eager:
